@@ -1,0 +1,216 @@
+"""ctypes front end of the CPU oracle (test infrastructure, see lpmm_oracle.cpp).
+
+Only tests, the smoke check and the benchmark's cpu_baseline leg may import this package.
+It never imports the GPU package and the GPU package never imports it.
+Arrays are numpy, C-contiguous; state buffers are modified in place.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "lpmm_oracle.cpp")
+_LIB = os.path.join(_HERE, "liblpmm_oracle.so")
+
+BLOCK = 128
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with g++ (no contraction, no fast-math)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["g++", "-O2", "-std=c++17", "-ffp-contract=off", "-fno-fast-math", "-fPIC",
+               "-shared", _SRC, "-o", _LIB]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        build()
+        L = ctypes.CDLL(_LIB)
+        f32p = ctypes.POINTER(ctypes.c_float)
+        f64p = ctypes.POINTER(ctypes.c_double)
+        u8p = ctypes.POINTER(ctypes.c_uint8)
+        i64 = ctypes.c_int64
+        cf = ctypes.c_float
+        L.oracle_table_linear.argtypes = [ctypes.c_int, f32p]
+        L.oracle_table_de.argtypes = [ctypes.c_int, ctypes.c_int, f32p]
+        L.oracle_table_de_f64.argtypes = [ctypes.c_int, ctypes.c_int, f64p]
+        L.oracle_step_table.argtypes = [ctypes.c_int, f32p]
+        L.oracle_nearest_code.argtypes = [f32p, ctypes.c_int, cf]
+        L.oracle_nearest_code.restype = ctypes.c_int
+        L.oracle_nearest_codes.argtypes = [f32p, ctypes.c_int, f32p, i64, u8p]
+        L.oracle_quant_m.argtypes = [f32p, i64, u8p, f32p]
+        L.oracle_dequant_m.argtypes = [u8p, f32p, i64, f32p]
+        L.oracle_quant_v.argtypes = [f32p, i64, i64, u8p, f32p, f32p]
+        L.oracle_dequant_v.argtypes = [u8p, f32p, f32p, i64, i64, f32p]
+        L.oracle_adamw32_step.argtypes = [f32p, f32p, f32p, f32p, i64, cf, cf, cf, cf, cf, i64]
+        L.oracle_adamw4_step.argtypes = [f32p, f32p, u8p, f32p, u8p, f32p, f32p, i64, i64,
+                                         cf, cf, cf, cf, cf, i64, f32p, f32p]
+        L.oracle_state_zero.argtypes = [u8p, f32p, u8p, f32p, f32p, i64, i64]
+        for name in ("oracle_table_linear", "oracle_table_de", "oracle_table_de_f64",
+                     "oracle_step_table", "oracle_nearest_codes", "oracle_quant_m",
+                     "oracle_dequant_m", "oracle_quant_v", "oracle_dequant_v",
+                     "oracle_adamw32_step", "oracle_adamw4_step", "oracle_state_zero"):
+            getattr(L, name).restype = None
+        _lib = L
+    return _lib
+
+
+def _f32(a: np.ndarray):
+    assert a.dtype == np.float32 and a.flags["C_CONTIGUOUS"]
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_float))
+
+
+def _u8(a: np.ndarray):
+    assert a.dtype == np.uint8 and a.flags["C_CONTIGUOUS"]
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8))
+
+
+# ---- tables and mapping ----------------------------------------------------------------------
+
+def table_linear(bits: int = 4) -> np.ndarray:
+    out = np.empty(1 << bits, np.float32)
+    lib().oracle_table_linear(bits, _f32(out))
+    return out
+
+
+def table_de(bits: int = 4, signed: bool = True) -> np.ndarray:
+    out = np.empty(1 << bits, np.float32)
+    lib().oracle_table_de(bits, int(signed), _f32(out))
+    return out
+
+
+def table_de_f64(bits: int = 4, signed: bool = True) -> np.ndarray:
+    out = np.empty(1 << bits, np.float64)
+    lib().oracle_table_de_f64(bits, int(signed), out.ctypes.data_as(ctypes.POINTER(ctypes.c_double)))
+    return out
+
+
+def step_table(what: str) -> np.ndarray:
+    out = np.empty(16, np.float32)
+    lib().oracle_step_table({"de": 0, "linear": 1}[what], _f32(out))
+    return out
+
+
+def nearest_codes(table: np.ndarray, n: np.ndarray) -> np.ndarray:
+    table = np.ascontiguousarray(table, np.float32)
+    n = np.ascontiguousarray(n, np.float32)
+    out = np.empty(n.size, np.uint8)
+    lib().oracle_nearest_codes(_f32(table), table.size, _f32(n), n.size, _u8(out))
+    return out.reshape(n.shape)
+
+
+# ---- quantizers ------------------------------------------------------------------------------
+
+def codes_bytes(P: int) -> int:
+    return (P + 1) // 2
+
+
+def n_blocks(P: int) -> int:
+    return (P + BLOCK - 1) // BLOCK
+
+
+def quant_m(x: np.ndarray):
+    x = np.ascontiguousarray(x, np.float32).reshape(-1)
+    codes = np.zeros(codes_bytes(x.size), np.uint8)
+    scales = np.zeros(n_blocks(x.size), np.float32)
+    lib().oracle_quant_m(_f32(x), x.size, _u8(codes), _f32(scales))
+    return codes, scales
+
+
+def dequant_m(codes: np.ndarray, scales: np.ndarray, P: int) -> np.ndarray:
+    out = np.empty(P, np.float32)
+    lib().oracle_dequant_m(_u8(codes), _f32(scales), P, _f32(out))
+    return out
+
+
+def quant_v(x: np.ndarray):
+    x = np.ascontiguousarray(x, np.float32)
+    rows, cols = x.shape
+    codes = np.zeros(codes_bytes(x.size), np.uint8)
+    r = np.zeros(rows, np.float32)
+    c = np.zeros(cols, np.float32)
+    lib().oracle_quant_v(_f32(x), rows, cols, _u8(codes), _f32(r), _f32(c))
+    return codes, r, c
+
+
+def dequant_v(codes: np.ndarray, r: np.ndarray, c: np.ndarray) -> np.ndarray:
+    rows, cols = r.size, c.size
+    out = np.empty((rows, cols), np.float32)
+    lib().oracle_dequant_v(_u8(codes), _f32(r), _f32(c), rows, cols, _f32(out))
+    return out
+
+
+def unpack_codes(codes: np.ndarray, P: int) -> np.ndarray:
+    """Byte k holds element 2k in its low nibble and element 2k+1 in its high nibble."""
+    out = np.empty(codes.size * 2, np.uint8)
+    out[0::2] = codes & 0x0F
+    out[1::2] = codes >> 4
+    return out[:P]
+
+
+# ---- optimizer -------------------------------------------------------------------------------
+
+@dataclass
+class Hyper:
+    lr: float = 1e-3
+    beta1: float = 0.9
+    beta2: float = 0.999
+    eps: float = 1e-8
+    weight_decay: float = 0.01
+
+
+@dataclass
+class State4:
+    """Compressed state of one rows x cols tensor."""
+    rows: int
+    cols: int
+    m_codes: np.ndarray
+    m_scales: np.ndarray
+    v_codes: np.ndarray
+    v_r: np.ndarray
+    v_c: np.ndarray
+
+    def copy(self) -> "State4":
+        return State4(self.rows, self.cols, self.m_codes.copy(), self.m_scales.copy(),
+                      self.v_codes.copy(), self.v_r.copy(), self.v_c.copy())
+
+
+def state_zero(rows: int, cols: int) -> State4:
+    P = rows * cols
+    st = State4(rows, cols, np.zeros(codes_bytes(P), np.uint8), np.zeros(n_blocks(P), np.float32),
+                np.zeros(codes_bytes(P), np.uint8), np.zeros(rows, np.float32),
+                np.zeros(cols, np.float32))
+    lib().oracle_state_zero(_u8(st.m_codes), _f32(st.m_scales), _u8(st.v_codes), _f32(st.v_r),
+                            _f32(st.v_c), rows, cols)
+    return st
+
+
+def adamw4_step(w: np.ndarray, g: np.ndarray, st: State4, hp: Hyper, t: int, want_moments=False):
+    """In place on w (float32, rows*cols) and st.  g is float32 (a bf16 gradient is passed upcast)."""
+    assert w.size == st.rows * st.cols == g.size
+    mt = vt = None
+    null = ctypes.POINTER(ctypes.c_float)()
+    if want_moments:
+        mt = np.empty(w.size, np.float32)
+        vt = np.empty(w.size, np.float32)
+    lib().oracle_adamw4_step(_f32(w), _f32(g), _u8(st.m_codes), _f32(st.m_scales), _u8(st.v_codes),
+                             _f32(st.v_r), _f32(st.v_c), st.rows, st.cols, hp.lr, hp.beta1,
+                             hp.beta2, hp.eps, hp.weight_decay, t,
+                             _f32(mt) if want_moments else null, _f32(vt) if want_moments else null)
+    return mt, vt
+
+
+def adamw32_step(w: np.ndarray, g: np.ndarray, m: np.ndarray, v: np.ndarray, hp: Hyper, t: int):
+    lib().oracle_adamw32_step(_f32(w), _f32(g), _f32(m), _f32(v), w.size, hp.lr, hp.beta1, hp.beta2,
+                              hp.eps, hp.weight_decay, t)

@@ -1,0 +1,307 @@
+// lpmm_oracle.cpp -- plain, slow, single-threaded CPU oracle for the 4-bit AdamW step of
+// "Memory Efficient Optimizers with 4-bit States" (arXiv 2309.01507).
+//
+// THIS IS TEST INFRASTRUCTURE.  It exists so that the GPU library can be checked against
+// something written straight from the paper.  It shares no code, header, table or constant
+// with the GPU path, and nothing in the product may call it.  Only the test-suite, the smoke
+// check and the benchmark's "cpu_baseline" leg load it.
+//
+// What it follows (section / equation / algorithm of the paper):
+//   * Sec. 2.1, Alg. 1 and App. E Alg. 3: decompress -> Adam update -> compress, per tensor.
+//   * Eq. 1: the Adam moment, bias-correction and parameter formulas.
+//   * Sec. 2.2: quantizer = mapping o normalization, mapping = argmin_i |n - T(i)|,
+//     dequantizer = N^-1 o T; block-wise normalization over the row-major flattening.
+//   * Sec. 3: block size 128 for the first moment.
+//   * Sec. 4.1 and App. D.2: the zero-excluding Linear map T(i) = (i+1)/2^b.
+//   * Sec. 4.2: rank-1 normalization, r_i = max_j x_ij, c_j = max_i x_ij, n_ij = x_ij / min(r_i, c_j).
+//   * App. D.1: signed normalization n = sign(x) N(|x|).
+//   * App. D.2: the dynamic-exponent (DE) map: sign bit, E leading zeros, indicator bit,
+//     F fraction bits; value 10^-E * fraction[k]; two special bit patterns; sorted list.
+//
+// Precision.  The moments m_t, v_t and the two normalizing divisions are evaluated in IEEE fp32
+// (round-to-nearest-even, no contraction except the two explicit fmaf calls, denormals kept),
+// because they decide integer codes and both sides must take that decision in the same precision.
+// The nearest-entry search takes its differences in double, which is exact for fp32 operands.
+// The parameter update, which decides no integer, is evaluated in double from the fp32 moments
+// and rounded once to fp32 for storage.
+//
+// Readings where the paper is silent or inconsistent (each also listed in the design notes):
+//   * Alg. 3 prints (1-beta1) in the second-moment line; Eq. 1 has (1-beta2).  Eq. 1 is used.
+//   * AdamW = Adam plus decoupled decay: w <- w - lr*( m^/(sqrt(v^)+eps) + wd*w ).
+//   * The parameter update uses the precise m_t, v_t (compress is the last line of Alg. 3).
+//   * A stored code is the rank of the value in the sorted table (App. D.2, last sentence).
+//   * argmin ties go to the lowest index.
+//   * A zero scale (all-zero block, untouched row/column, the zero initial state) gives n := 0.
+//   * Scales are fp32.  Two codes per byte: element 2k in bits 0..3, element 2k+1 in bits 4..7.
+//   * Blocks are [128k, 128k+127] of the row-major flattening; the last one may be short.
+//
+// Parity status: every function below is pinned by the CPU tests against values the paper prints,
+// closed forms, brute force, invariants or an fp64 library AdamW, EXCEPT the multi-step trajectory
+// of the full quantized step, for which the paper prints nothing: "parity unpinned" beyond its parts.
+//
+// Build: g++ -O2 -std=c++17 -ffp-contract=off -fPIC -shared lpmm_oracle.cpp -o liblpmm_oracle.so
+
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <algorithm>
+#include <vector>
+
+namespace {
+
+constexpr int kBits = 4;
+constexpr int kCodes = 1 << kBits;   // 16 quantization points (Sec. 4.1)
+constexpr int64_t kBlock = 128;      // B128 (Sec. 3)
+
+// ---------------------------------------------------------------------------------------------
+// Quantization mappings (App. D.2)
+// ---------------------------------------------------------------------------------------------
+
+// Linear map: T(i) = (i+1)/2^b, i.e. linspace(0,1,2^b+1) without its first point.
+void table_linear(int bits, std::vector<double>& out) {
+    const int n = 1 << bits;
+    out.resize(n);
+    for (int i = 0; i < n; ++i) out[i] = double(i + 1) / double(n);
+}
+
+// fraction[k] for F fraction bits: p_j = 0.9/2^F * j + 0.1, fraction[k] = (p_k + p_{k+1})/2.
+double de_fraction(int F, int k) {
+    const double step = (1.0 - 0.1) / double(1 << F);
+    const double pk = step * k + 0.1;
+    const double pk1 = step * (k + 1) + 0.1;
+    return (pk + pk1) / 2.0;
+}
+
+// Dynamic-exponent map with `bits` total bits.  Every bit pattern is decoded by the rule of
+// App. D.2; the two special patterns are overridden; the values are then sorted increasingly.
+void table_de(int bits, bool is_signed, std::vector<double>& out) {
+    const int n = 1 << bits;
+    const int mag_bits = is_signed ? bits - 1 : bits;   // bits after the sign bit
+    out.clear();
+    for (int pat = 0; pat < n; ++pat) {
+        const int sign = is_signed ? (pat >> mag_bits) & 1 : 0;
+        const int mag = pat & ((1 << mag_bits) - 1);
+        double val;
+        if (mag == 0) {
+            // All-zero magnitude field: no indicator bit.  0...0 -> 0; in the signed case the
+            // pattern 10...0 is assigned +1 (so -1 does not exist and the map is not symmetric).
+            val = (sign == 0) ? 0.0 : 1.0;
+        } else if (!is_signed && mag == 1) {
+            // Unsigned special pattern 0...01 -> 1.
+            val = 1.0;
+        } else {
+            int E = 0;   // leading zeros of the magnitude field
+            while (((mag >> (mag_bits - 1 - E)) & 1) == 0) ++E;
+            const int F = mag_bits - E - 1;             // bits after the indicator
+            const int k = mag & ((1 << F) - 1);
+            val = std::pow(10.0, -double(E)) * de_fraction(F, k);
+            if (sign) val = -val;
+        }
+        out.push_back(val);
+    }
+    std::sort(out.begin(), out.end());
+}
+
+struct Tables {
+    float lin[kCodes];
+    float de[kCodes];
+    Tables() {
+        std::vector<double> t;
+        table_linear(kBits, t);
+        for (int i = 0; i < kCodes; ++i) lin[i] = float(t[i]);
+        table_de(kBits, true, t);
+        for (int i = 0; i < kCodes; ++i) de[i] = float(t[i]);
+    }
+};
+const Tables& tables() { static const Tables t; return t; }
+
+// Mapping M(n) = argmin_i |n - T(i)| (Sec. 2.2); brute force over all entries, differences in
+// double (exact for fp32 inputs), first minimum wins.
+int nearest_code(const float* T, int n_entries, float n) {
+    int best = 0;
+    double best_d = std::fabs(double(n) - double(T[0]));
+    for (int i = 1; i < n_entries; ++i) {
+        const double d = std::fabs(double(n) - double(T[i]));
+        if (d < best_d) { best_d = d; best = i; }
+    }
+    return best;
+}
+
+inline int get_code(const uint8_t* codes, int64_t idx) {
+    const uint8_t b = codes[idx >> 1];
+    return (idx & 1) ? (b >> 4) : (b & 0x0F);
+}
+inline void put_code(uint8_t* codes, int64_t idx, int q) {
+    uint8_t& b = codes[idx >> 1];
+    if (idx & 1) b = uint8_t((b & 0x0F) | (q << 4));
+    else         b = uint8_t((b & 0xF0) | q);
+}
+
+// ---------------------------------------------------------------------------------------------
+// First moment: B128 normalization (Sec. 2.2, 3; signed form App. D.1) + signed DE map
+// ---------------------------------------------------------------------------------------------
+
+void quant_m(const float* x, int64_t P, uint8_t* codes, float* scales) {
+    const float* T = tables().de;
+    std::memset(codes, 0, size_t((P + 1) / 2));
+    const int64_t nblk = (P + kBlock - 1) / kBlock;
+    for (int64_t k = 0; k < nblk; ++k) {
+        const int64_t lo = k * kBlock, hi = std::min(P, lo + kBlock);
+        float s = 0.0f;
+        for (int64_t i = lo; i < hi; ++i) s = std::max(s, std::fabs(x[i]));
+        scales[k] = s;
+        for (int64_t i = lo; i < hi; ++i) {
+            const float n = (s == 0.0f) ? 0.0f : x[i] / s;   // sign(x) * |x| / s == x / s
+            put_code(codes, i, nearest_code(T, kCodes, n));
+        }
+    }
+}
+
+void dequant_m(const uint8_t* codes, const float* scales, int64_t P, float* out) {
+    const float* T = tables().de;
+    for (int64_t i = 0; i < P; ++i) out[i] = T[get_code(codes, i)] * scales[i / kBlock];
+}
+
+// ---------------------------------------------------------------------------------------------
+// Second moment: rank-1 normalization (Sec. 4.2) + Linear map (Sec. 4.1)
+// ---------------------------------------------------------------------------------------------
+
+void quant_v(const float* x, int64_t rows, int64_t cols, uint8_t* codes, float* r, float* c) {
+    const float* T = tables().lin;
+    const int64_t P = rows * cols;
+    std::memset(codes, 0, size_t((P + 1) / 2));
+    for (int64_t i = 0; i < rows; ++i) r[i] = 0.0f;
+    for (int64_t j = 0; j < cols; ++j) c[j] = 0.0f;
+    for (int64_t i = 0; i < rows; ++i)
+        for (int64_t j = 0; j < cols; ++j) {
+            const float v = x[i * cols + j];
+            r[i] = std::max(r[i], v);
+            c[j] = std::max(c[j], v);
+        }
+    for (int64_t i = 0; i < rows; ++i)
+        for (int64_t j = 0; j < cols; ++j) {
+            const float sc = std::min(r[i], c[j]);
+            const float n = (sc == 0.0f) ? 0.0f : x[i * cols + j] / sc;
+            put_code(codes, i * cols + j, nearest_code(T, kCodes, n));
+        }
+}
+
+void dequant_v(const uint8_t* codes, const float* r, const float* c, int64_t rows, int64_t cols,
+               float* out) {
+    const float* T = tables().lin;
+    for (int64_t i = 0; i < rows; ++i)
+        for (int64_t j = 0; j < cols; ++j)
+            out[i * cols + j] = T[get_code(codes, i * cols + j)] * std::min(r[i], c[j]);
+}
+
+// ---------------------------------------------------------------------------------------------
+// The optimizer rule A of Alg. 1: Adam (Eq. 1) with decoupled weight decay, on precise states.
+// m and v are updated in place (m_{t-1} -> m_t); w is updated in place.
+// ---------------------------------------------------------------------------------------------
+
+void adamw_rule(float* w, float* m, float* v, const float* g, int64_t P, float lr, float beta1,
+                float beta2, float eps, float wd, int64_t t) {
+    const float omb1 = 1.0f - beta1;
+    const float omb2 = 1.0f - beta2;
+    const double bc1 = 1.0 - std::pow(double(beta1), double(t));
+    const double bc2 = 1.0 - std::pow(double(beta2), double(t));
+    for (int64_t i = 0; i < P; ++i) {
+        // fp32 moments; the operation order is part of the definition both sides implement
+        const float mt = std::fmaf(beta1, m[i], omb1 * g[i]);
+        const float vt = std::fmaf(beta2, v[i], (omb2 * g[i]) * g[i]);
+        m[i] = mt;
+        v[i] = vt;
+        const double mhat = double(mt) / bc1;
+        const double vhat = double(vt) / bc2;
+        const double wi = double(w[i]);
+        w[i] = float(wi - double(lr) * (mhat / (std::sqrt(vhat) + double(eps)) + double(wd) * wi));
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+// ---- tables --------------------------------------------------------------------------------
+// out must hold 2^bits floats (table_de) / doubles (table_de_f64).
+void oracle_table_linear(int bits, float* out) {
+    std::vector<double> t; table_linear(bits, t);
+    for (size_t i = 0; i < t.size(); ++i) out[i] = float(t[i]);
+}
+void oracle_table_de(int bits, int is_signed, float* out) {
+    std::vector<double> t; table_de(bits, is_signed != 0, t);
+    for (size_t i = 0; i < t.size(); ++i) out[i] = float(t[i]);
+}
+void oracle_table_de_f64(int bits, int is_signed, double* out) {
+    std::vector<double> t; table_de(bits, is_signed != 0, t);
+    for (size_t i = 0; i < t.size(); ++i) out[i] = t[i];
+}
+// The two 16-entry tables the step actually uses (what=0: signed DE, what=1: Linear).
+void oracle_step_table(int what, float* out) {
+    const float* T = what == 0 ? tables().de : tables().lin;
+    for (int i = 0; i < kCodes; ++i) out[i] = T[i];
+}
+
+// ---- mapping -------------------------------------------------------------------------------
+int oracle_nearest_code(const float* table, int n_entries, float n) {
+    return nearest_code(table, n_entries, n);
+}
+void oracle_nearest_codes(const float* table, int n_entries, const float* n, int64_t count,
+                          uint8_t* out) {
+    for (int64_t i = 0; i < count; ++i) out[i] = uint8_t(nearest_code(table, n_entries, n[i]));
+}
+
+// ---- quantizers (compress / decompress of Alg. 1) --------------------------------------------
+// codes: (P+1)/2 bytes; scales: ceil(P/128) floats; r: rows floats; c: cols floats.
+void oracle_quant_m(const float* x, int64_t P, uint8_t* codes, float* scales) {
+    quant_m(x, P, codes, scales);
+}
+void oracle_dequant_m(const uint8_t* codes, const float* scales, int64_t P, float* out) {
+    dequant_m(codes, scales, P, out);
+}
+void oracle_quant_v(const float* x, int64_t rows, int64_t cols, uint8_t* codes, float* r, float* c) {
+    quant_v(x, rows, cols, codes, r, c);
+}
+void oracle_dequant_v(const uint8_t* codes, const float* r, const float* c, int64_t rows,
+                      int64_t cols, float* out) {
+    dequant_v(codes, r, c, rows, cols, out);
+}
+
+// ---- optimizer steps -------------------------------------------------------------------------
+// Adam/AdamW on uncompressed fp32 states: Alg. 3 with compress = decompress = identity.  Also the
+// path for tensors that are not quantized (App. C.1: size <= 4096).
+void oracle_adamw32_step(float* w, const float* g, float* m, float* v, int64_t P, float lr,
+                         float beta1, float beta2, float eps, float wd, int64_t t) {
+    adamw_rule(w, m, v, g, P, lr, beta1, beta2, eps, wd, t);
+}
+
+// One step of 4-bit AdamW on one rows x cols tensor (Alg. 3): decompress both moments, apply the
+// rule on the precise states, compress both.  All state buffers are updated in place.
+// m_t_out / v_t_out (each rows*cols floats, may be null) receive the precise moments before
+// compression, so that a test can tell how close a value was to a decision boundary.
+void oracle_adamw4_step(float* w, const float* g, uint8_t* m_codes, float* m_scales,
+                        uint8_t* v_codes, float* v_r, float* v_c, int64_t rows, int64_t cols,
+                        float lr, float beta1, float beta2, float eps, float wd, int64_t t,
+                        float* m_t_out, float* v_t_out) {
+    const int64_t P = rows * cols;
+    std::vector<float> m(static_cast<size_t>(P)), v(static_cast<size_t>(P));
+    dequant_m(m_codes, m_scales, P, m.data());                    // Alg. 3: decompress
+    dequant_v(v_codes, v_r, v_c, rows, cols, v.data());
+    adamw_rule(w, m.data(), v.data(), g, P, lr, beta1, beta2, eps, wd, t);   // Eq. 1
+    if (m_t_out) std::memcpy(m_t_out, m.data(), sizeof(float) * size_t(P));
+    if (v_t_out) std::memcpy(v_t_out, v.data(), sizeof(float) * size_t(P));
+    quant_m(m.data(), P, m_codes, m_scales);                      // Alg. 3: compress
+    quant_v(v.data(), rows, cols, v_codes, v_r, v_c);
+}
+
+// The zero initial state of Alg. 3 (m_0 = v_0 = 0): m codes all point at the table's 0 entry with
+// zero scales; the Linear map has no zero, so v = 0 is carried by r = c = 0.
+void oracle_state_zero(uint8_t* m_codes, float* m_scales, uint8_t* v_codes, float* v_r, float* v_c,
+                       int64_t rows, int64_t cols) {
+    const int64_t P = rows * cols;
+    std::vector<float> z(static_cast<size_t>(P), 0.0f);
+    quant_m(z.data(), P, m_codes, m_scales);
+    quant_v(z.data(), rows, cols, v_codes, v_r, v_c);
+}
+
+}  // extern "C"
