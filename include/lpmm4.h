@@ -1,0 +1,136 @@
+/*
+ * lpmm4.h -- C ABI of lpmm4.so: the fused 4-bit AdamW optimizer step for AMD MI355X (gfx950).
+ *
+ * Method: "Memory Efficient Optimizers with 4-bit States" (arXiv 2309.01507).  One step is
+ * Alg. 1 lines 3-5 / App. E Alg. 3 for one parameter tensor: decompress the 4-bit first and
+ * second moment, apply the Adam rule of Eq. 1 (with AdamW's decoupled weight decay) on the precise
+ * moments, compress both moments again.
+ *   first moment : block-wise normalization, block 128 over the row-major flattening (Sec. 2.2,
+ *                  Sec. 3), signed form n = sign(x) N(|x|) (App. D.1), signed 4-bit
+ *                  dynamic-exponent map (App. D.2).
+ *   second moment: rank-1 normalization n_ij = x_ij / min(r_i, c_j) with r_i = max_j x_ij,
+ *                  c_j = max_i x_ij (Sec. 4.2), Linear map T(i) = (i+1)/16 without zero (Sec. 4.1).
+ *
+ * Conventions for every call
+ *   - All data pointers are DEVICE pointers unless the comment says "host".  The caller owns every
+ *     buffer; the library allocates no device memory and never frees anything.
+ *   - `shape` is a HOST pointer to {rows, cols}; tensors are row-major, P = rows*cols elements.
+ *     A 1-D tensor is passed as {1, P}.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue work
+ *     and return; they never synchronize.  Work of one call is ordered on `stream`.
+ *   - Return value: LPMM_OK or a negative error code; nothing is printed, nothing aborts.
+ *     On error nothing has been enqueued, except LPMM_EHIP from a launch in the middle of a call.
+ *   - NaN/Inf in gradients or states are not detected; the result is then unspecified.
+ *
+ * State layout of one quantized tensor (all caller-owned, sizes from lpmm_adamw4_state_sizes)
+ *   m_codes      uint8[(P+1)/2]   two codes per byte: element 2k in bits 0..3, element 2k+1 in
+ *                                 bits 4..7; a code is the rank of the value in the increasing
+ *                                 DE table (code 7 = 0.0, code 15 = +1.0)
+ *   m_blockscale float[ceil(P/128)]  absmax of block k = elements [128k, 128k+127]
+ *   v_codes      uint8[(P+1)/2]   same packing; code q stands for (q+1)/16
+ *   v_rowmax     float[rows]      r_i
+ *   v_colmax     float[cols]      c_j
+ *   The zero state of Alg. 3 (m_0 = v_0 = 0) is: m codes 7, block scales 0, v codes 0, r = c = 0.
+ */
+#ifndef LPMM4_H
+#define LPMM4_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define LPMM_OK          0
+#define LPMM_EINVAL     (-1)  /* null / misaligned pointer, bad shape, step < 1, bad hyper-parameter */
+#define LPMM_ENOTINIT   (-2)  /* lpmm_adamw4_init has not been called for the current device */
+#define LPMM_EHIP       (-3)  /* a HIP call failed; see lpmm_last_hip_error() */
+#define LPMM_EWORKSPACE (-4)  /* the workspace given to init is too small for this tensor */
+
+#define LPMM_BLOCK 128        /* B128, Sec. 3 */
+
+/* Gradient element types. */
+#define LPMM_GRAD_F32  0
+#define LPMM_GRAD_BF16 1
+
+/* Human-readable text for an error code (host, static storage). */
+const char* lpmm_strerror(int code);
+/* hipError_t (as int) of the most recent LPMM_EHIP in the calling host thread, else 0. */
+int lpmm_last_hip_error(void);
+
+/* The two 16-entry quantization maps the kernels use (host call, no GPU needed):
+ * which = 0: signed dynamic-exponent map of App. D.2; which = 1: Linear map of Sec. 4.1.
+ * out: host float[16].  Returns LPMM_EINVAL for another `which` or a null pointer. */
+int lpmm_table(int which, float* out);
+
+/* Host model of the kernels' nearest-entry search M(n) = argmin_i |n - T(i)| (Sec. 2.2), ties to
+ * the lower index: the same bucket table the kernels read, evaluated on the CPU.  For tests of
+ * the host-built table; which as in lpmm_table.  n, out: host arrays of `count` elements. */
+int lpmm_host_nearest_codes(int which, const float* n, int64_t count, uint8_t* out);
+
+/* Bytes of workspace lpmm_adamw4_init needs so that steps on tensors with rows + cols <=
+ * max_rows_plus_cols can run.  The workspace holds the row/column maxima of the updated second
+ * moment (Sec. 4.2) while the old ones are still being read, plus completion counters. */
+size_t lpmm_adamw4_workspace_bytes(int64_t max_rows_plus_cols);
+
+/* Registers `workspace` (device memory, 256-byte aligned, workspace_bytes long, owned by the caller
+ * and kept alive until the process ends or init is called again) for device `device`, clears it
+ * on `stream`, and uploads the quantization tables.  May be called again to replace the
+ * workspace.  Steps on one device share this workspace: calls that may overlap in time on one
+ * device (different streams) race; calls on one stream are safe. */
+int lpmm_adamw4_init(int device, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Sizes in bytes of the five state buffers of a rows x cols tensor, in the order
+ * {m_codes, m_blockscale, v_codes, v_rowmax, v_colmax}.  shape, sizes: host. */
+int lpmm_adamw4_state_sizes(const int64_t shape[2], size_t sizes[5]);
+
+/* Writes the zero state (m_0 = v_0 = 0 of Alg. 3) into the five buffers. */
+int lpmm_adamw4_state_zero(uint8_t* m_codes, float* m_blockscale, uint8_t* v_codes,
+                           float* v_rowmax, float* v_colmax, const int64_t shape[2], void* stream);
+
+/* One 4-bit AdamW step on one tensor (Alg. 3 with Eq. 1 and decoupled decay):
+ *   m~ = T_DE[m_code] * blockscale,  v~ = T_LIN[v_code] * min(r_i, c_j)          (decompress)
+ *   m_t = beta1*m~ + (1-beta1)*g,    v_t = beta2*v~ + (1-beta2)*g^2              (Eq. 1)
+ *   w  <- w - lr*( (m_t/(1-beta1^t)) / (sqrt(v_t/(1-beta2^t)) + eps) + weight_decay*w )
+ *   m codes/scales <- B128/DE(m_t),  v codes, r, c <- rank-1/Linear(v_t)           (compress)
+ * param: float[P], updated in place.  grad: float[P], read only.  The five state buffers are
+ * updated in place.  param and grad must be 16-byte aligned, the others 4-byte aligned.
+ * step is t >= 1.  Hyper-parameters: lr >= 0, 0 <= beta < 1, eps >= 0, weight_decay >= 0.
+ * Two kernels are enqueued (the column maxima of v_t must be complete before any v code can be
+ * written).  Needs lpmm_adamw4_init on the current device with rows + cols within the workspace. */
+int lpmm_adamw4_step(void* param, const void* grad, uint8_t* m_codes, float* m_blockscale,
+                     uint8_t* v_codes, float* v_rowmax, float* v_colmax, const int64_t shape[2],
+                     float lr, float beta1, float beta2, float eps, float weight_decay,
+                     int64_t step, void* stream);
+
+/* Same step with a bf16 gradient buffer (uint16 bit patterns, upcast exactly in the kernel). */
+int lpmm_adamw4_step_bf16g(void* param, const void* grad, uint8_t* m_codes, float* m_blockscale,
+                           uint8_t* v_codes, float* v_rowmax, float* v_colmax,
+                           const int64_t shape[2], float lr, float beta1, float beta2, float eps,
+                           float weight_decay, int64_t step, void* stream);
+
+/* AdamW step with uncompressed fp32 states, for tensors that are not quantized (App. C.1: size
+ * <= 4096, biases and normalization vectors): Alg. 3 with compress = decompress = identity.
+ * param, m, v: float[numel] in place; grad: float or bf16 [numel] per grad_dtype. */
+int lpmm_adamw32_step(void* param, const void* grad, float* m, float* v, int64_t numel,
+                      int grad_dtype, float lr, float beta1, float beta2, float eps,
+                      float weight_decay, int64_t step, void* stream);
+
+/* Decompress one moment to fp32 (the dequantizer N^-1 o T of Sec. 2.2).
+ * which = 0: first moment, scale_a = m_blockscale, scale_b ignored (may be NULL).
+ * which = 1: second moment, scale_a = v_rowmax, scale_b = v_colmax.
+ * out: float[P]. */
+int lpmm_dequant_state(int which, const uint8_t* codes, const float* scale_a, const float* scale_b,
+                       const int64_t shape[2], float* out, void* stream);
+
+/* Compress an fp32 moment into 4-bit state (the quantizer M o N of Sec. 2.2), same `which` and
+ * scale arguments as lpmm_dequant_state, all outputs.  in: float[P]; for which = 1 the values
+ * must be >= 0.  For which = 1 needs lpmm_adamw4_init (it uses no workspace but the tables). */
+int lpmm_quant_state(int which, const float* in, const int64_t shape[2], uint8_t* codes,
+                     float* scale_a, float* scale_b, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LPMM4_H */

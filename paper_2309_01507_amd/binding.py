@@ -1,0 +1,239 @@
+"""ctypes binding of lpmm4.so (see include/lpmm4.h for the contract of every call).
+
+Argument marshalling only: tensors are torch CUDA tensors used as device memory, the stream is
+torch's current stream.  If the shared library is missing the import of a symbol fails loudly;
+there is no fallback of any kind.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_ROOT = os.path.dirname(_HERE)
+_SRC_DIR = os.path.join(_HERE, "csrc")
+_LIB = os.path.join(_HERE, "lpmm4.so")
+
+HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",
+               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+
+GRAD_F32, GRAD_BF16 = 0, 1
+
+
+class LpmmError(RuntimeError):
+    pass
+
+
+def lib_path() -> str:
+    return _LIB
+
+
+def build_library(verbose: bool = False) -> str:
+    """Cross-compile lpmm4.so for gfx950 with hipcc (works without a GPU)."""
+    cmd = ["hipcc", *HIPCC_FLAGS, os.path.join(_SRC_DIR, "lpmm4.hip"), "-o", _LIB]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise LpmmError("hipcc failed:\n" + res.stdout + res.stderr)
+    if verbose:
+        print(" ".join(cmd))
+    return _LIB
+
+
+_lib = None
+
+_F = ctypes.c_float
+_I64 = ctypes.c_int64
+_VP = ctypes.c_void_p
+_SHAPE = ctypes.c_int64 * 2
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library.  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB):
+            raise LpmmError(f"{_LIB} is missing: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                            "(there is no CPU fallback)")
+        L = ctypes.CDLL(_LIB)
+        L.lpmm_strerror.argtypes = [ctypes.c_int]
+        L.lpmm_strerror.restype = ctypes.c_char_p
+        L.lpmm_last_hip_error.restype = ctypes.c_int
+        L.lpmm_table.argtypes = [ctypes.c_int, _VP]
+        L.lpmm_host_nearest_codes.argtypes = [ctypes.c_int, _VP, _I64, _VP]
+        L.lpmm_adamw4_workspace_bytes.argtypes = [_I64]
+        L.lpmm_adamw4_workspace_bytes.restype = ctypes.c_size_t
+        L.lpmm_adamw4_init.argtypes = [ctypes.c_int, _VP, ctypes.c_size_t, _VP]
+        L.lpmm_adamw4_state_sizes.argtypes = [_VP, _VP]
+        L.lpmm_adamw4_state_zero.argtypes = [_VP] * 5 + [_VP, _VP]
+        step_args = [_VP] * 7 + [_VP] + [_F] * 5 + [_I64, _VP]
+        L.lpmm_adamw4_step.argtypes = step_args
+        L.lpmm_adamw4_step_bf16g.argtypes = step_args
+        L.lpmm_adamw32_step.argtypes = [_VP] * 4 + [_I64, ctypes.c_int] + [_F] * 5 + [_I64, _VP]
+        L.lpmm_dequant_state.argtypes = [ctypes.c_int, _VP, _VP, _VP, _VP, _VP, _VP]
+        L.lpmm_quant_state.argtypes = [ctypes.c_int, _VP, _VP, _VP, _VP, _VP, _VP]
+        _lib = L
+    return _lib
+
+
+def _check(rc: int, what: str) -> None:
+    if rc != 0:
+        L = lib()
+        msg = L.lpmm_strerror(rc).decode()
+        if rc == -3:
+            msg += f" [hipError {L.lpmm_last_hip_error()}]"
+        raise LpmmError(f"{what}: {msg} (code {rc})")
+
+
+def _ptr(t) -> Optional[int]:
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+def _shape(rows: int, cols: int):
+    return _SHAPE(int(rows), int(cols))
+
+
+# ---- host-only calls ---------------------------------------------------------------------------------
+
+def lpmm_table(which: int):
+    import numpy as np
+    out = np.empty(16, np.float32)
+    _check(lib().lpmm_table(which, out.ctypes.data), "lpmm_table")
+    return out
+
+
+def lpmm_host_nearest_codes(which: int, n):
+    import numpy as np
+    n = np.ascontiguousarray(n, np.float32)
+    out = np.empty(n.size, np.uint8)
+    _check(lib().lpmm_host_nearest_codes(which, n.ctypes.data, n.size, out.ctypes.data),
+           "lpmm_host_nearest_codes")
+    return out.reshape(n.shape)
+
+
+def lpmm_adamw4_workspace_bytes(max_rows_plus_cols: int) -> int:
+    return int(lib().lpmm_adamw4_workspace_bytes(int(max_rows_plus_cols)))
+
+
+def lpmm_adamw4_state_sizes(rows: int, cols: int):
+    sizes = (ctypes.c_size_t * 5)()
+    shape = _shape(rows, cols)
+    _check(lib().lpmm_adamw4_state_sizes(ctypes.addressof(shape), ctypes.addressof(sizes)),
+           "lpmm_adamw4_state_sizes")
+    return [int(s) for s in sizes]
+
+
+# ---- device calls ------------------------------------------------------------------------------------
+
+_workspaces = {}   # device index -> (tensor kept alive, capacity in rows+cols)
+
+
+def lpmm_adamw4_init(device: int, workspace, stream=None) -> None:
+    nbytes = workspace.numel() * workspace.element_size()
+    _check(lib().lpmm_adamw4_init(int(device), _ptr(workspace), nbytes, _stream(stream)),
+           "lpmm_adamw4_init")
+
+
+def ensure_init(max_rows_plus_cols: int, device=None) -> None:
+    """Allocate (with torch) and register a workspace large enough for rows + cols, once per device."""
+    import torch
+    dev = torch.cuda.current_device() if device is None else int(device)
+    have = _workspaces.get(dev)
+    if have is not None and have[1] >= max_rows_plus_cols:
+        return
+    torch.cuda.synchronize(dev)   # steps that use the old workspace must have finished
+    cap = max(int(max_rows_plus_cols), 1 << 16)
+    nbytes = lpmm_adamw4_workspace_bytes(cap)
+    ws = torch.zeros((nbytes + 255) // 256 * 256, dtype=torch.uint8, device=f"cuda:{dev}")
+    with torch.cuda.device(dev):
+        lpmm_adamw4_init(dev, ws)
+        torch.cuda.synchronize(dev)
+    _workspaces[dev] = (ws, cap)
+
+
+@dataclass
+class State4:
+    """The five device buffers of one quantized tensor's optimizer state."""
+    rows: int
+    cols: int
+    m_codes: "object"
+    m_blockscale: "object"
+    v_codes: "object"
+    v_rowmax: "object"
+    v_colmax: "object"
+
+
+def new_state(rows: int, cols: int, device="cuda") -> State4:
+    """Allocate (torch) and zero (library) the state of a rows x cols tensor."""
+    import torch
+    sz = lpmm_adamw4_state_sizes(rows, cols)
+    pad4 = lambda n: (n + 3) // 4 * 4
+    st = State4(rows, cols,
+                torch.empty(pad4(sz[0]), dtype=torch.uint8, device=device)[:sz[0]],
+                torch.empty(sz[1] // 4, dtype=torch.float32, device=device),
+                torch.empty(pad4(sz[2]), dtype=torch.uint8, device=device)[:sz[2]],
+                torch.empty(sz[3] // 4, dtype=torch.float32, device=device),
+                torch.empty(sz[4] // 4, dtype=torch.float32, device=device))
+    lpmm_adamw4_state_zero(st)
+    return st
+
+
+def lpmm_adamw4_state_zero(st: State4, stream=None) -> None:
+    shape = _shape(st.rows, st.cols)
+    _check(lib().lpmm_adamw4_state_zero(_ptr(st.m_codes), _ptr(st.m_blockscale), _ptr(st.v_codes),
+                                        _ptr(st.v_rowmax), _ptr(st.v_colmax),
+                                        ctypes.addressof(shape), _stream(stream)),
+           "lpmm_adamw4_state_zero")
+
+
+def _step(fn_name, param, grad, st: State4, lr, beta1, beta2, eps, weight_decay, step, stream):
+    shape = _shape(st.rows, st.cols)
+    fn = getattr(lib(), fn_name)
+    _check(fn(_ptr(param), _ptr(grad), _ptr(st.m_codes), _ptr(st.m_blockscale), _ptr(st.v_codes),
+              _ptr(st.v_rowmax), _ptr(st.v_colmax), ctypes.addressof(shape), lr, beta1, beta2, eps,
+              weight_decay, int(step), _stream(stream)), fn_name)
+
+
+def lpmm_adamw4_step(param, grad, st: State4, lr, beta1, beta2, eps, weight_decay, step, stream=None):
+    _step("lpmm_adamw4_step", param, grad, st, lr, beta1, beta2, eps, weight_decay, step, stream)
+
+
+def lpmm_adamw4_step_bf16g(param, grad, st: State4, lr, beta1, beta2, eps, weight_decay, step,
+                           stream=None):
+    _step("lpmm_adamw4_step_bf16g", param, grad, st, lr, beta1, beta2, eps, weight_decay, step, stream)
+
+
+def lpmm_adamw32_step(param, grad, m, v, numel, grad_dtype, lr, beta1, beta2, eps, weight_decay, step,
+                      stream=None):
+    _check(lib().lpmm_adamw32_step(_ptr(param), _ptr(grad), _ptr(m), _ptr(v), int(numel),
+                                   int(grad_dtype), lr, beta1, beta2, eps, weight_decay, int(step),
+                                   _stream(stream)), "lpmm_adamw32_step")
+
+
+def lpmm_dequant_state(which: int, codes, scale_a, scale_b, rows, cols, out, stream=None):
+    shape = _shape(rows, cols)
+    _check(lib().lpmm_dequant_state(int(which), _ptr(codes), _ptr(scale_a), _ptr(scale_b),
+                                    ctypes.addressof(shape), _ptr(out), _stream(stream)),
+           "lpmm_dequant_state")
+
+
+def lpmm_quant_state(which: int, x, rows, cols, codes, scale_a, scale_b, stream=None):
+    shape = _shape(rows, cols)
+    _check(lib().lpmm_quant_state(int(which), _ptr(x), ctypes.addressof(shape), _ptr(codes),
+                                  _ptr(scale_a), _ptr(scale_b), _stream(stream)),
+           "lpmm_quant_state")

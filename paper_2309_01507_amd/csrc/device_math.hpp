@@ -1,0 +1,119 @@
+// Device-side building blocks of the 4-bit AdamW step for gfx950 (wave64).
+//
+// Everything that decides a 4-bit code (the moments, the two normalizing divisions) is evaluated
+// in IEEE fp32 with a fixed operation order: one rounding per written operation, fused
+// multiply-add only where __builtin_fmaf is written (the translation unit is compiled with
+// -ffp-contract=off), denormals kept, correctly rounded division.  The parameter update decides no
+// integer and uses the hardware's approximate sqrt / reciprocal.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tables.hpp"
+
+namespace lpmm {
+
+struct Hyper {
+    float beta1, beta2;
+    float omb1, omb2;     // 1 - beta, rounded once in fp32
+    float eps;
+    float step_size;      // lr / (1 - beta1^t)
+    float inv_sqrt_bc2;   // 1 / sqrt(1 - beta2^t)
+    float lr_wd;          // lr * weight_decay
+};
+
+// ---- cross-lane reductions inside one DPP row (16 lanes = one 128-element block) ----------------
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float x) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL,
+                                                                 0xF, 0xF, false));
+}
+
+// Maximum over the 16 lanes of a row, result in every lane of the row.  Inputs must be >= 0 or all
+// lanes of the row must be active (both hold where this is used).
+__device__ __forceinline__ float row16_allmax(float x) {
+    x = fmaxf(x, dpp_f32<0xB1>(x));    // quad_perm [1,0,3,2]: lane ^ 1
+    x = fmaxf(x, dpp_f32<0x4E>(x));    // quad_perm [2,3,0,1]: lane ^ 2
+    x = fmaxf(x, dpp_f32<0x141>(x));   // row_half_mirror: other quad of the half row
+    x = fmaxf(x, dpp_f32<0x140>(x));   // row_mirror: other half of the row
+    return x;
+}
+
+// ---- gradient element access ---------------------------------------------------------------------
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+template <bool BF16>
+__device__ __forceinline__ void load_grad8(const void* g, int64_t idx, float out[8]) {
+    if constexpr (BF16) {
+        const uint4 w = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(g) + idx);
+        out[0] = bf16_lo(w.x); out[1] = bf16_hi(w.x);
+        out[2] = bf16_lo(w.y); out[3] = bf16_hi(w.y);
+        out[4] = bf16_lo(w.z); out[5] = bf16_hi(w.z);
+        out[6] = bf16_lo(w.w); out[7] = bf16_hi(w.w);
+    } else {
+        const float4* p = reinterpret_cast<const float4*>(reinterpret_cast<const float*>(g) + idx);
+        const float4 a = p[0], b = p[1];
+        out[0] = a.x; out[1] = a.y; out[2] = a.z; out[3] = a.w;
+        out[4] = b.x; out[5] = b.y; out[6] = b.z; out[7] = b.w;
+    }
+}
+
+template <bool BF16>
+__device__ __forceinline__ float load_grad1(const void* g, int64_t idx) {
+    if constexpr (BF16)
+        return __uint_as_float(uint32_t(reinterpret_cast<const uint16_t*>(g)[idx]) << 16);
+    else
+        return reinterpret_cast<const float*>(g)[idx];
+}
+
+// ---- decompress ----------------------------------------------------------------------------------
+
+// second moment: T_LIN[q] * min(r_i, c_j), T_LIN[q] = (q+1)/16 exactly
+__device__ __forceinline__ float dequant_v(uint32_t q, float sc) {
+    return (float(q + 1u) * 0.0625f) * sc;
+}
+
+// ---- the Adam rule of Eq. 1 on one element -------------------------------------------------------
+
+__device__ __forceinline__ float moment_m(const Hyper& h, float m_prev, float g) {
+    return __builtin_fmaf(h.beta1, m_prev, h.omb1 * g);
+}
+__device__ __forceinline__ float moment_v(const Hyper& h, float v_prev, float g) {
+    return __builtin_fmaf(h.beta2, v_prev, (h.omb2 * g) * g);
+}
+// w - lr*( m^/(sqrt(v^)+eps) + wd*w ), to a few ulp (no integer depends on it)
+__device__ __forceinline__ float param_update(const Hyper& h, float w, float mt, float vt) {
+    const float denom = __builtin_fmaf(__builtin_amdgcn_sqrtf(vt), h.inv_sqrt_bc2, h.eps);
+    const float x = mt * __builtin_amdgcn_rcpf(denom);
+    const float wdec = __builtin_fmaf(-h.lr_wd, w, w);
+    return __builtin_fmaf(-h.step_size, x, wdec);
+}
+
+// ---- compress ------------------------------------------------------------------------------------
+
+// first moment: n = m_t / s (0 when the block is all zero), code from the bucket table in LDS
+__device__ __forceinline__ uint32_t quant_m_code(const SearchEntry* s_search, float mt, float s) {
+    const float n = (s == 0.0f) ? 0.0f : mt / s;
+    const SearchEntry e = s_search[__float_as_uint(n) >> kBucketShift];
+    return e.base + (n > e.thr ? 1u : 0u);
+}
+
+// second moment: n = v_t / min(r_i, c_j) (0 when the scale is zero); nearest (k+1)/16 with ties
+// down is ceil(16 n - 1.5) clamped to 0..15 (16 n and the subtraction are exact where it matters)
+__device__ __forceinline__ uint32_t quant_v_code(float vt, float sc) {
+    const float n = (sc == 0.0f) ? 0.0f : vt / sc;
+    const float f = ceilf(__builtin_fmaf(16.0f, n, -1.5f));
+    return uint32_t(fminf(fmaxf(f, 0.0f), 15.0f));
+}
+
+// ---- float maximum through an integer atomic (values >= +0 only: bit order == value order) --------
+
+__device__ __forceinline__ void atomic_max_nonneg(float* addr, float v) {
+    atomicMax(reinterpret_cast<unsigned int*>(addr), __float_as_uint(v));
+}
+
+}  // namespace lpmm

@@ -1,0 +1,403 @@
+// lpmm4.so -- C ABI and launch logic of the 4-bit AdamW step (declared in include/lpmm4.h).
+// Host side only: argument checks, launch geometry, bias corrections.  All arithmetic of the
+// method runs in the kernels of kernels.hpp.
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdlib>
+#include <mutex>
+
+#include "../../include/lpmm4.h"
+#include "kernels.hpp"
+
+namespace {
+
+using namespace lpmm;
+
+constexpr int kMaxDevices = 16;
+constexpr size_t kCounterBytes = 256;   // tail of the workspace: counters, one cache line apart
+
+struct DeviceCtx {
+    bool ready = false;
+    float* ws = nullptr;        // workspace: floats [0, cap) for r', c'; then counters
+    int64_t cap_floats = 0;
+    unsigned int* counter = nullptr;
+    int n_cu = 256;
+};
+
+DeviceCtx g_ctx[kMaxDevices];
+std::mutex g_mu;
+thread_local int g_last_hip = 0;
+
+// host copies of the tables (also serve the host-only entry points)
+struct HostTables {
+    float de[kCodes], lin[kCodes], thr[kCodes - 1];
+    float byte_decode[512];
+    SearchEntry search[kBuckets];
+    bool ok;
+    HostTables() {
+        build_de_signed(de);
+        build_linear(lin);
+        build_thresholds(de, thr);
+        ok = build_search(thr, search);
+        build_byte_decode(de, byte_decode);
+    }
+};
+const HostTables& host_tables() { static const HostTables t; return t; }
+
+int hip_fail(hipError_t e) { g_last_hip = int(e); return LPMM_EHIP; }
+#define LPMM_HIP(call) do { hipError_t e_ = (call); if (e_ != hipSuccess) return hip_fail(e_); } while (0)
+
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+bool finite_nonneg(float x) { return std::isfinite(x) && x >= 0.0f; }
+
+int env_int(const char* name, int dflt) {
+    const char* s = std::getenv(name);
+    return (s && *s) ? std::atoi(s) : dflt;
+}
+
+int check_shape(const int64_t* shape, int64_t* rows, int64_t* cols) {
+    if (!shape) return LPMM_EINVAL;
+    if (shape[0] < 1 || shape[1] < 1) return LPMM_EINVAL;
+    if (shape[0] > (int64_t(1) << 31) || shape[1] > (int64_t(1) << 31)) return LPMM_EINVAL;
+    if (shape[0] * shape[1] > (int64_t(1) << 40)) return LPMM_EINVAL;
+    *rows = shape[0];
+    *cols = shape[1];
+    return LPMM_OK;
+}
+
+int make_hyper(float lr, float beta1, float beta2, float eps, float wd, int64_t step, Hyper* h) {
+    if (step < 1) return LPMM_EINVAL;
+    if (!finite_nonneg(lr) || !finite_nonneg(eps) || !finite_nonneg(wd)) return LPMM_EINVAL;
+    if (!(beta1 >= 0.0f && beta1 < 1.0f) || !(beta2 >= 0.0f && beta2 < 1.0f)) return LPMM_EINVAL;
+    h->beta1 = beta1;
+    h->beta2 = beta2;
+    h->omb1 = 1.0f - beta1;
+    h->omb2 = 1.0f - beta2;
+    h->eps = eps;
+    const double bc1 = 1.0 - std::pow(double(beta1), double(step));
+    const double bc2 = 1.0 - std::pow(double(beta2), double(step));
+    h->step_size = float(double(lr) / bc1);
+    h->inv_sqrt_bc2 = float(1.0 / std::sqrt(bc2));
+    h->lr_wd = float(double(lr) * double(wd));
+    return LPMM_OK;
+}
+
+int current_ctx(DeviceCtx** out) {
+    int dev = 0;
+    LPMM_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices || !g_ctx[dev].ready) return LPMM_ENOTINIT;
+    *out = &g_ctx[dev];
+    return LPMM_OK;
+}
+
+int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
+int pad8(int64_t n) { return int(round_up(n, kXcds)); }
+
+// Geometry of the fast path.  gx column blocks share a workgroup (so that one workgroup touches
+// whole 128-byte lines of codes and runs of block scales), gy = 16/gx groups walk interleaved
+// rows of the same column blocks and combine their column maxima in LDS.
+void fast_geometry(Tensor4* a, int n_cu) {
+    a->nb = int(a->cols / LPMM_BLOCK);
+    int gx = env_int("LPMM_GX", 4);
+    while (gx > 1 && (a->nb % gx) != 0) gx >>= 1;
+    if (gx < 1 || gx > 16 || (gx & (gx - 1))) gx = 1;
+    a->gx = gx;
+    a->gy = 16 / gx;
+    a->strips = a->nb / gx;
+    // rows per workgroup: enough workgroups to fill the chip several times, and each group walks
+    // at least a few rows so that the column atomics are amortized
+    const int64_t target_wg = int64_t(n_cu) * env_int("LPMM_WG_PER_CU", 8);
+    int64_t rw = env_int("LPMM_RW", 0);
+    if (rw <= 0) {
+        rw = (a->rows * a->strips + target_wg - 1) / target_wg;
+        const int64_t min_rw = int64_t(a->gy) * 4;
+        if (rw < min_rw) rw = min_rw;
+    }
+    rw = round_up(rw, a->gy);
+    if (rw > a->rows) rw = round_up(a->rows, a->gy);
+    a->rw = int(rw);
+    a->n_wg = int(a->strips * ((a->rows + rw - 1) / rw));
+}
+
+template <bool BF16>
+int launch_step(const Tensor4& t, const Hyper& h, bool fast, hipStream_t s) {
+    if (fast) {
+        const int grid = pad8(t.n_wg);
+        hipLaunchKernelGGL(pass1_fast<BF16>, dim3(grid), dim3(kThreads), 0, s, t, h);
+        LPMM_HIP(hipGetLastError());
+        hipLaunchKernelGGL(pass2_fast<BF16>, dim3(grid), dim3(kThreads), 0, s, t, h);
+        LPMM_HIP(hipGetLastError());
+    } else {
+        const int64_t lanes = (t.P + 7) / 8;
+        const int grid = int((lanes + kThreads - 1) / kThreads);
+        hipLaunchKernelGGL(pass1_general<BF16>, dim3(grid), dim3(kThreads), 0, s, t, h);
+        LPMM_HIP(hipGetLastError());
+        hipLaunchKernelGGL(pass2_general<BF16>, dim3(grid), dim3(kThreads), 0, s, t, h);
+        LPMM_HIP(hipGetLastError());
+    }
+    return LPMM_OK;
+}
+
+int step_impl(bool bf16, void* param, const void* grad, uint8_t* m_codes, float* m_blockscale,
+              uint8_t* v_codes, float* v_rowmax, float* v_colmax, const int64_t* shape, float lr,
+              float beta1, float beta2, float eps, float wd, int64_t step, void* stream) {
+    int64_t rows, cols;
+    int rc = check_shape(shape, &rows, &cols);
+    if (rc) return rc;
+    if (!param || !grad || !m_codes || !m_blockscale || !v_codes || !v_rowmax || !v_colmax)
+        return LPMM_EINVAL;
+    if (!aligned(param, 16) || !aligned(grad, 16) || !aligned(m_codes, 4) || !aligned(v_codes, 4) ||
+        !aligned(m_blockscale, 4) || !aligned(v_rowmax, 4) || !aligned(v_colmax, 4))
+        return LPMM_EINVAL;
+    Hyper h;
+    rc = make_hyper(lr, beta1, beta2, eps, wd, step, &h);
+    if (rc) return rc;
+    DeviceCtx* ctx;
+    rc = current_ctx(&ctx);
+    if (rc) return rc;
+    const int64_t rows_pad = round_up(rows, 64), cols_pad = round_up(cols, 64);
+    if (rows_pad + cols_pad > ctx->cap_floats) return LPMM_EWORKSPACE;
+
+    Tensor4 t{};
+    t.p = static_cast<float*>(param);
+    t.g = grad;
+    t.mq = reinterpret_cast<uint32_t*>(m_codes);
+    t.ms = m_blockscale;
+    t.vq = reinterpret_cast<uint32_t*>(v_codes);
+    t.r = v_rowmax;
+    t.c = v_colmax;
+    t.r_new = ctx->ws;
+    t.c_new = ctx->ws + rows_pad;
+    t.counter = ctx->counter;
+    t.rows = rows;
+    t.cols = cols;
+    t.P = rows * cols;
+    const bool fast = (cols % LPMM_BLOCK) == 0 && aligned(v_colmax, 16) && !env_int("LPMM_FORCE_GENERAL", 0);
+    if (fast) fast_geometry(&t, ctx->n_cu);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    return bf16 ? launch_step<true>(t, h, fast, s) : launch_step<false>(t, h, fast, s);
+}
+
+int grid_for(int64_t items, int64_t per_thread, int max_blocks = 1 << 20) {
+    const int64_t threads = (items + per_thread - 1) / per_thread;
+    int64_t blocks = (threads + kThreads - 1) / kThreads;
+    if (blocks < 1) blocks = 1;
+    if (blocks > max_blocks) blocks = max_blocks;
+    return int(blocks);
+}
+
+int fill(void* dst, int64_t n, uint8_t value, int64_t last_index, uint8_t last, hipStream_t s) {
+    if (n <= 0) return LPMM_OK;
+    hipLaunchKernelGGL(fill_bytes_kernel, dim3(grid_for(n, 16, 4096)), dim3(kThreads), 0, s,
+                       static_cast<uint8_t*>(dst), n, value, last_index, last);
+    LPMM_HIP(hipGetLastError());
+    return LPMM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* lpmm_strerror(int code) {
+    switch (code) {
+        case LPMM_OK: return "ok";
+        case LPMM_EINVAL: return "invalid argument (null or misaligned pointer, bad shape, step < 1, or bad hyper-parameter)";
+        case LPMM_ENOTINIT: return "lpmm_adamw4_init has not been called for the current device";
+        case LPMM_EHIP: return "a HIP call failed (see lpmm_last_hip_error)";
+        case LPMM_EWORKSPACE: return "workspace too small for this tensor (rows + cols)";
+        default: return "unknown lpmm error code";
+    }
+}
+
+int lpmm_last_hip_error(void) { return g_last_hip; }
+
+int lpmm_table(int which, float* out) {
+    if (!out || (which != 0 && which != 1)) return LPMM_EINVAL;
+    const HostTables& t = host_tables();
+    for (int i = 0; i < kCodes; ++i) out[i] = which == 0 ? t.de[i] : t.lin[i];
+    return LPMM_OK;
+}
+
+int lpmm_host_nearest_codes(int which, const float* n, int64_t count, uint8_t* out) {
+    if (!n || !out || count < 0 || (which != 0 && which != 1)) return LPMM_EINVAL;
+    const HostTables& t = host_tables();
+    if (!t.ok) return LPMM_EINVAL;
+    for (int64_t i = 0; i < count; ++i) {
+        if (which == 0) {
+            out[i] = uint8_t(search_code(t.search, n[i]));
+        } else {
+            const float f = std::ceil(std::fmaf(16.0f, n[i], -1.5f));
+            out[i] = uint8_t(std::fmin(std::fmax(f, 0.0f), 15.0f));
+        }
+    }
+    return LPMM_OK;
+}
+
+size_t lpmm_adamw4_workspace_bytes(int64_t max_rows_plus_cols) {
+    if (max_rows_plus_cols < 2) max_rows_plus_cols = 2;
+    // rows and cols are each rounded up to 64 floats inside the workspace
+    return size_t(round_up(max_rows_plus_cols, 64) + 128) * sizeof(float) + kCounterBytes;
+}
+
+int lpmm_adamw4_init(int device, void* workspace, size_t workspace_bytes, void* stream) {
+    if (device < 0 || device >= kMaxDevices) return LPMM_EINVAL;
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < kCounterBytes + 256 * sizeof(float))
+        return LPMM_EINVAL;
+    const HostTables& t = host_tables();
+    if (!t.ok) return LPMM_EINVAL;
+    std::lock_guard<std::mutex> lock(g_mu);
+    int prev = 0;
+    LPMM_HIP(hipGetDevice(&prev));
+    LPMM_HIP(hipSetDevice(device));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = hipMemcpyToSymbolAsync(HIP_SYMBOL(d_byte_decode), t.byte_decode, sizeof(t.byte_decode), 0,
+                                          hipMemcpyHostToDevice, s);
+    if (e == hipSuccess)
+        e = hipMemcpyToSymbolAsync(HIP_SYMBOL(d_search), t.search, sizeof(t.search), 0,
+                                   hipMemcpyHostToDevice, s);
+    if (e == hipSuccess) e = hipMemsetAsync(workspace, 0, workspace_bytes, s);
+    int n_cu = 256;
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, device);
+    (void)hipSetDevice(prev);
+    if (e != hipSuccess) return hip_fail(e);
+    DeviceCtx& c = g_ctx[device];
+    c.ws = static_cast<float*>(workspace);
+    c.cap_floats = int64_t((workspace_bytes - kCounterBytes) / sizeof(float)) / 64 * 64;
+    c.counter = reinterpret_cast<unsigned int*>(static_cast<char*>(workspace) + size_t(c.cap_floats) * sizeof(float));
+    c.n_cu = n_cu > 0 ? n_cu : 256;
+    c.ready = true;
+    return LPMM_OK;
+}
+
+int lpmm_adamw4_state_sizes(const int64_t shape[2], size_t sizes[5]) {
+    int64_t rows, cols;
+    const int rc = check_shape(shape, &rows, &cols);
+    if (rc) return rc;
+    if (!sizes) return LPMM_EINVAL;
+    const int64_t P = rows * cols;
+    sizes[0] = size_t((P + 1) / 2);
+    sizes[1] = size_t((P + LPMM_BLOCK - 1) / LPMM_BLOCK) * sizeof(float);
+    sizes[2] = size_t((P + 1) / 2);
+    sizes[3] = size_t(rows) * sizeof(float);
+    sizes[4] = size_t(cols) * sizeof(float);
+    return LPMM_OK;
+}
+
+int lpmm_adamw4_state_zero(uint8_t* m_codes, float* m_blockscale, uint8_t* v_codes, float* v_rowmax,
+                           float* v_colmax, const int64_t shape[2], void* stream) {
+    size_t sz[5];
+    const int rc = lpmm_adamw4_state_sizes(shape, sz);
+    if (rc) return rc;
+    if (!m_codes || !m_blockscale || !v_codes || !v_rowmax || !v_colmax) return LPMM_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t P = shape[0] * shape[1];
+    // code 7 is the rank of 0.0 in the DE map; an odd tail leaves its unused high nibble 0
+    int r = fill(m_codes, int64_t(sz[0]), 0x77, (P & 1) ? int64_t(sz[0]) - 1 : -1, 0x07, s);
+    if (!r) r = fill(m_blockscale, int64_t(sz[1]), 0, -1, 0, s);
+    if (!r) r = fill(v_codes, int64_t(sz[2]), 0, -1, 0, s);
+    if (!r) r = fill(v_rowmax, int64_t(sz[3]), 0, -1, 0, s);
+    if (!r) r = fill(v_colmax, int64_t(sz[4]), 0, -1, 0, s);
+    return r;
+}
+
+int lpmm_adamw4_step(void* param, const void* grad, uint8_t* m_codes, float* m_blockscale,
+                     uint8_t* v_codes, float* v_rowmax, float* v_colmax, const int64_t shape[2],
+                     float lr, float beta1, float beta2, float eps, float weight_decay, int64_t step,
+                     void* stream) {
+    return step_impl(false, param, grad, m_codes, m_blockscale, v_codes, v_rowmax, v_colmax, shape, lr,
+                     beta1, beta2, eps, weight_decay, step, stream);
+}
+
+int lpmm_adamw4_step_bf16g(void* param, const void* grad, uint8_t* m_codes, float* m_blockscale,
+                           uint8_t* v_codes, float* v_rowmax, float* v_colmax, const int64_t shape[2],
+                           float lr, float beta1, float beta2, float eps, float weight_decay,
+                           int64_t step, void* stream) {
+    return step_impl(true, param, grad, m_codes, m_blockscale, v_codes, v_rowmax, v_colmax, shape, lr,
+                     beta1, beta2, eps, weight_decay, step, stream);
+}
+
+int lpmm_adamw32_step(void* param, const void* grad, float* m, float* v, int64_t numel, int grad_dtype,
+                      float lr, float beta1, float beta2, float eps, float weight_decay, int64_t step,
+                      void* stream) {
+    if (!param || !grad || !m || !v || numel < 1) return LPMM_EINVAL;
+    if (grad_dtype != LPMM_GRAD_F32 && grad_dtype != LPMM_GRAD_BF16) return LPMM_EINVAL;
+    if (!aligned(param, 4) || !aligned(m, 4) || !aligned(v, 4) ||
+        !aligned(grad, grad_dtype == LPMM_GRAD_F32 ? 4 : 2))
+        return LPMM_EINVAL;
+    Hyper h;
+    const int rc = make_hyper(lr, beta1, beta2, eps, weight_decay, step, &h);
+    if (rc) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int grid = grid_for(numel, 1, 8192);
+    if (grad_dtype == LPMM_GRAD_BF16)
+        hipLaunchKernelGGL(adamw32_kernel<true>, dim3(grid), dim3(kThreads), 0, s,
+                           static_cast<float*>(param), grad, m, v, numel, h);
+    else
+        hipLaunchKernelGGL(adamw32_kernel<false>, dim3(grid), dim3(kThreads), 0, s,
+                           static_cast<float*>(param), grad, m, v, numel, h);
+    LPMM_HIP(hipGetLastError());
+    return LPMM_OK;
+}
+
+int lpmm_dequant_state(int which, const uint8_t* codes, const float* scale_a, const float* scale_b,
+                       const int64_t shape[2], float* out, void* stream) {
+    int64_t rows, cols;
+    const int rc = check_shape(shape, &rows, &cols);
+    if (rc) return rc;
+    if ((which != 0 && which != 1) || !codes || !scale_a || !out || (which == 1 && !scale_b))
+        return LPMM_EINVAL;
+    if (!aligned(codes, 4) || !aligned(out, 4)) return LPMM_EINVAL;
+    DeviceCtx* ctx;
+    const int rc2 = current_ctx(&ctx);   // the DE table lives in device memory filled by init
+    if (rc2) return rc2;
+    QuantArgs q{};
+    q.q_in = reinterpret_cast<const uint32_t*>(codes);
+    q.x_out = out;
+    q.sa = const_cast<float*>(scale_a);
+    q.sb = const_cast<float*>(scale_b);
+    q.rows = rows; q.cols = cols; q.P = rows * cols;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int grid = grid_for(q.P, 8);
+    if (which == 0) hipLaunchKernelGGL(dequant_m_kernel, dim3(grid), dim3(kThreads), 0, s, q);
+    else hipLaunchKernelGGL(dequant_v_kernel, dim3(grid), dim3(kThreads), 0, s, q);
+    LPMM_HIP(hipGetLastError());
+    return LPMM_OK;
+}
+
+int lpmm_quant_state(int which, const float* in, const int64_t shape[2], uint8_t* codes, float* scale_a,
+                     float* scale_b, void* stream) {
+    int64_t rows, cols;
+    const int rc = check_shape(shape, &rows, &cols);
+    if (rc) return rc;
+    if ((which != 0 && which != 1) || !codes || !scale_a || !in || (which == 1 && !scale_b))
+        return LPMM_EINVAL;
+    if (!aligned(codes, 4) || !aligned(in, 4)) return LPMM_EINVAL;
+    DeviceCtx* ctx;
+    const int rc2 = current_ctx(&ctx);
+    if (rc2) return rc2;
+    QuantArgs q{};
+    q.x_in = in;
+    q.q_out = reinterpret_cast<uint32_t*>(codes);
+    q.sa = scale_a;
+    q.sb = scale_b;
+    q.rows = rows; q.cols = cols; q.P = rows * cols;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int grid = grid_for(q.P, 8);
+    if (which == 0) {
+        hipLaunchKernelGGL(quant_m_kernel, dim3(grid), dim3(kThreads), 0, s, q);
+        LPMM_HIP(hipGetLastError());
+    } else {
+        int r = fill(scale_a, rows * int64_t(sizeof(float)), 0, -1, 0, s);
+        if (!r) r = fill(scale_b, cols * int64_t(sizeof(float)), 0, -1, 0, s);
+        if (r) return r;
+        hipLaunchKernelGGL(quant_v_max_kernel, dim3(grid), dim3(kThreads), 0, s, q);
+        LPMM_HIP(hipGetLastError());
+        hipLaunchKernelGGL(quant_v_code_kernel, dim3(grid), dim3(kThreads), 0, s, q);
+        LPMM_HIP(hipGetLastError());
+    }
+    return LPMM_OK;
+}
+
+}  // extern "C"

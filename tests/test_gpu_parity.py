@@ -1,0 +1,226 @@
+"""GPU parity tests: the HIP path through the C ABI against the CPU oracle, element by element, on
+the same seeded inputs.  Codes, scales and row/column maxima must be bit-exact; parameters within
+1e-5 relative / 1e-7 absolute."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2309_01507_amd as lpmm
+import workloads
+from gpu_util import (DEV, PARAM_ATOL, PARAM_RTOL, compare_step, download_state, gpu_step, run_parity,
+                      to_dev, upload_state)
+
+pytestmark = pytest.mark.gpu
+
+HP = oracle.Hyper()
+
+
+@pytest.fixture(autouse=True)
+def _announce(request):
+    print(f"\n[gpu-test] {request.node.name}", flush=True)   # names the case should the box die
+    yield
+    torch.cuda.synchronize()
+
+
+# ---- stand-alone decompress / compress -------------------------------------------------------------
+
+def _random_state(rows, cols, seed):
+    rng = np.random.default_rng(seed)
+    m = (rng.standard_normal((rows, cols)) * np.exp(rng.standard_normal((rows, cols)))).astype(np.float32) * 1e-3
+    v = (rng.standard_normal((rows, cols)) ** 2 * np.exp(2 * rng.standard_normal(cols))[None, :] * 1e-8).astype(np.float32)
+    return m, v
+
+
+@pytest.mark.parametrize("rows,cols", [(64, 256), (37, 200), (13, 77), (1, 5000), (300, 1), (1, 1), (3, 43)])
+def test_dequant_matches_oracle(rows, cols):
+    lpmm.ensure_init(rows + cols)
+    m, v = _random_state(rows, cols, 1)
+    P = rows * cols
+    mc, ms = oracle.quant_m(m)
+    vc, vr, vcm = oracle.quant_v(v)
+    out = torch.empty(P, dtype=torch.float32, device=DEV)
+    lpmm.lpmm_dequant_state(0, to_dev(mc), to_dev(ms), None, rows, cols, out)
+    np.testing.assert_array_equal(out.cpu().numpy(), oracle.dequant_m(mc, ms, P))
+    lpmm.lpmm_dequant_state(1, to_dev(vc), to_dev(vr), to_dev(vcm), rows, cols, out)
+    np.testing.assert_array_equal(out.cpu().numpy().reshape(rows, cols), oracle.dequant_v(vc, vr, vcm))
+
+
+@pytest.mark.parametrize("rows,cols", [(64, 256), (37, 200), (13, 77), (1, 5000), (300, 1), (1, 1), (3, 43)])
+def test_quant_matches_oracle(rows, cols):
+    lpmm.ensure_init(rows + cols)
+    m, v = _random_state(rows, cols, 2)
+    m[0, :min(cols, 128)] = 0.0                                  # an all-zero block (when cols >= 128)
+    v[rows // 2, :] = 0.0                                        # an all-zero row
+    P = rows * cols
+    nbytes = (P + 1) // 2
+    codes = torch.zeros((nbytes + 3) // 4 * 4, dtype=torch.uint8, device=DEV)
+    sa = torch.empty((P + 127) // 128, dtype=torch.float32, device=DEV)
+    lpmm.lpmm_quant_state(0, to_dev(m), rows, cols, codes, sa, None)
+    mc, ms = oracle.quant_m(m)
+    np.testing.assert_array_equal(sa.cpu().numpy(), ms)
+    np.testing.assert_array_equal(codes.cpu().numpy()[:nbytes], mc)
+    r = torch.empty(rows, dtype=torch.float32, device=DEV)
+    c = torch.empty(cols, dtype=torch.float32, device=DEV)
+    codes.zero_()
+    lpmm.lpmm_quant_state(1, to_dev(v), rows, cols, codes, r, c)
+    vc, vr, vcm = oracle.quant_v(v)
+    np.testing.assert_array_equal(r.cpu().numpy(), vr)
+    np.testing.assert_array_equal(c.cpu().numpy(), vcm)
+    np.testing.assert_array_equal(codes.cpu().numpy()[:nbytes], vc)
+
+
+def test_quant_at_decision_boundaries():
+    """Blocks whose normalized values sit exactly on, one ulp above and one ulp below every decision
+    boundary of both maps (block scale 1, and a scale that is not a power of two)."""
+    lpmm.ensure_init(4096)
+    for which, T in ((0, oracle.step_table("de")), (1, oracle.step_table("linear"))):
+        mids = ((T[:-1].astype(np.float64) + T[1:].astype(np.float64)) / 2).astype(np.float32)
+        pts = np.concatenate([mids, np.nextafter(mids, np.float32(4)), np.nextafter(mids, np.float32(-4)), T])
+        for scale in (np.float32(1.0), np.float32(0.37), np.float32(3.1e-7)):
+            x = np.zeros((9, 128), np.float32)
+            x.reshape(-1)[:pts.size] = pts * scale
+            x[:, 127] = scale                                    # every block / row has its maximum here
+            x[8, :] = scale                                      # ... and every column, so min(r, c) = scale
+            if which == 1:
+                x = np.abs(x)
+            P = x.size
+            codes = torch.zeros(P // 2, dtype=torch.uint8, device=DEV)
+            sa = torch.empty(9, dtype=torch.float32, device=DEV)
+            sb = torch.empty(128, dtype=torch.float32, device=DEV)
+            lpmm.lpmm_quant_state(which, to_dev(x), 9, 128, codes, sa, sb)
+            want = oracle.quant_m(x)[0] if which == 0 else oracle.quant_v(x)[0]
+            np.testing.assert_array_equal(codes.cpu().numpy(), want)
+
+
+def test_zero_state_matches_oracle():
+    for rows, cols in ((5, 130), (3, 43), (16, 128)):
+        st = download_state(lpmm.new_state(rows, cols, DEV))
+        ref = oracle.state_zero(rows, cols)
+        for a, b in ((st.m_codes, ref.m_codes), (st.m_scales, ref.m_scales), (st.v_codes, ref.v_codes),
+                     (st.v_r, ref.v_r), (st.v_c, ref.v_c)):
+            np.testing.assert_array_equal(a, b)
+
+
+# ---- the step --------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("rows,cols,recipe", [
+    (256, 512, "iid"),                 # fast path, several tiles
+    (203, 384, "col_lognormal"),       # fast path, ragged last row tile, 3 column blocks
+    (64, 128, "iid"),                  # fast path, one column block
+    (37, 200, "col_lognormal"),        # general path: blocks straddle rows
+    (13, 77, "iid"),                   # general path, odd element count, short last block
+    (1, 5000, "iid"),                  # one row
+    (300, 1, "iid"),                   # one column
+    (1, 1, "iid"), (1, 2, "iid"),      # degenerate
+])
+def test_step_parity_small(rows, cols, recipe):
+    assert run_parity(rows, cols, steps=6, recipe=recipe, seed=3) == 0
+
+
+def test_step_parity_bf16_gradients():
+    assert run_parity(256, 384, steps=6, recipe="col_lognormal", bf16=True, seed=4) == 0
+    assert run_parity(37, 200, steps=4, recipe="col_lognormal", bf16=True, seed=4) == 0
+
+
+def test_config1_full():
+    """BASELINE config 1: one 1024 x 1024 fp32 matrix, 10 steps, fresh gradients each step."""
+    assert run_parity(1024, 1024, steps=10, recipe="iid", seed=1) == 0
+
+
+def test_outlier_sparse_rows():
+    """Config 3's structure at reduced size: x1e3 rows/columns, 90 % zero rows per step, rows that
+    never receive a gradient (zero scale -> n := 0)."""
+    assert run_parity(2000, 512, steps=8, recipe="outlier_sparse", seed=5) == 0
+
+
+@pytest.mark.parametrize("hp", [oracle.Hyper(3e-4, 0.8, 0.95, 1e-6, 0.1), oracle.Hyper(1e-2, 0.0, 0.5, 1e-3, 0.0)])
+def test_other_hyperparameters(hp):
+    assert run_parity(128, 256, steps=5, recipe="col_lognormal", seed=6, hp=hp) == 0
+
+
+def test_launch_geometry_does_not_change_results():
+    """Maxima are order-independent, so every tiling of the fast path and the general path must give
+    identical bits; a difference would be a race or an indexing error."""
+    rows, cols = 300, 1024
+    lpmm.ensure_init(rows + cols)
+    w0 = workloads.weights(7, 0, rows, cols).reshape(-1)
+    grads = [workloads.grads(7, 0, t, rows, cols, "col_lognormal").reshape(-1) for t in (1, 2, 3)]
+    results = []
+    knobs = [{}, {"LPMM_GX": "1"}, {"LPMM_GX": "8", "LPMM_RW": "16"}, {"LPMM_GX": "2", "LPMM_RW": "300"},
+             {"LPMM_FORCE_GENERAL": "1"}]
+    try:
+        for env in knobs:
+            for k in ("LPMM_GX", "LPMM_RW", "LPMM_FORCE_GENERAL"):
+                os.environ.pop(k, None)
+            os.environ.update(env)
+            w = to_dev(w0.copy())
+            st = lpmm.new_state(rows, cols, DEV)
+            for t, g in enumerate(grads, 1):
+                gpu_step(w, to_dev(g), st, HP, t)
+            torch.cuda.synchronize()
+            results.append((download_state(st), w.cpu().numpy()))
+    finally:
+        for k in ("LPMM_GX", "LPMM_RW", "LPMM_FORCE_GENERAL"):
+            os.environ.pop(k, None)
+    ref_st, ref_w = results[0]
+    for st, w in results[1:]:
+        np.testing.assert_array_equal(st.m_codes, ref_st.m_codes)
+        np.testing.assert_array_equal(st.v_codes, ref_st.v_codes)
+        np.testing.assert_array_equal(st.m_scales, ref_st.m_scales)
+        np.testing.assert_array_equal(st.v_r, ref_st.v_r)
+        np.testing.assert_array_equal(st.v_c, ref_st.v_c)
+        np.testing.assert_array_equal(w, ref_w)
+
+
+def test_resume_from_copied_state():
+    """The five buffers are the whole optimizer state: 6 steps == 3 steps + copy out/in + 3 steps."""
+    rows, cols = 128, 256
+    lpmm.ensure_init(rows + cols)
+    w0 = workloads.weights(8, 0, rows, cols).reshape(-1)
+    grads = [workloads.grads(8, 0, t, rows, cols).reshape(-1) for t in range(1, 7)]
+    wa, sta = to_dev(w0.copy()), lpmm.new_state(rows, cols, DEV)
+    for t, g in enumerate(grads, 1):
+        gpu_step(wa, to_dev(g), sta, HP, t)
+    wb, stb = to_dev(w0.copy()), lpmm.new_state(rows, cols, DEV)
+    for t, g in enumerate(grads[:3], 1):
+        gpu_step(wb, to_dev(g), stb, HP, t)
+    torch.cuda.synchronize()
+    saved, wsaved = download_state(stb), wb.cpu().numpy()
+    stc, wc = upload_state(saved), to_dev(wsaved)
+    for t, g in enumerate(grads[3:], 4):
+        gpu_step(wc, to_dev(g), stc, HP, t)
+    torch.cuda.synchronize()
+    a, c = download_state(sta), download_state(stc)
+    for x, y in ((a.m_codes, c.m_codes), (a.v_codes, c.v_codes), (a.m_scales, c.m_scales), (a.v_r, c.v_r),
+                 (a.v_c, c.v_c), (wa.cpu().numpy(), wc.cpu().numpy())):
+        np.testing.assert_array_equal(x, y)
+
+
+def test_adamw32_matches_oracle():
+    """The uncompressed-state path used for tensors that are not quantized."""
+    for n, bf16 in ((768, False), (4096, True), (5, False)):
+        w_ref = workloads.weights(9, 1, 1, n).reshape(-1)
+        m_ref, v_ref = np.zeros(n, np.float32), np.zeros(n, np.float32)
+        w, m, v = to_dev(w_ref.copy()), to_dev(m_ref.copy()), to_dev(v_ref.copy())
+        for t in range(1, 6):
+            g = workloads.grads(9, 1, t, 1, n, "iid", bf16).reshape(-1)
+            oracle.adamw32_step(w_ref, g, m_ref, v_ref, HP, t)
+            lpmm.lpmm_adamw32_step(w, to_dev(g, bf16), m, v, n, 1 if bf16 else 0, HP.lr, HP.beta1, HP.beta2,
+                                   HP.eps, HP.weight_decay, t)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(m.cpu().numpy(), m_ref)
+        np.testing.assert_array_equal(v.cpu().numpy(), v_ref)
+        np.testing.assert_allclose(w.cpu().numpy(), w_ref, rtol=PARAM_RTOL, atol=PARAM_ATOL)
+
+
+def test_workspace_too_small_is_an_error():
+    lpmm.ensure_init(1024)
+    cap = lpmm.binding._workspaces[torch.cuda.current_device()][1]
+    rows, cols = cap + 4096, 128
+    st = lpmm.State4(rows, cols, *[torch.zeros(16, dtype=torch.uint8, device=DEV)] * 5)
+    with pytest.raises(lpmm.LpmmError, match="workspace"):
+        lpmm.lpmm_adamw4_step(torch.zeros(16, device=DEV), torch.zeros(16, device=DEV), st, 1e-3, 0.9, 0.999,
+                              1e-8, 0.0, 1)

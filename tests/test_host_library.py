@@ -1,0 +1,100 @@
+"""CPU-only checks of lpmm4.so: it loads, exports what include/lpmm4.h declares, and its host-built
+tables and search structure agree with the oracle's definitions.  No GPU call is made here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2309_01507_amd as lpmm
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "lpmm4.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(lpmm_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_symbols()
+    assert len(names) >= 12
+    L = lpmm.lib()
+    for n in names:
+        assert hasattr(L, n), f"{n} is declared in include/lpmm4.h but not exported"
+
+
+def test_tables_equal_the_oracles():
+    np.testing.assert_array_equal(lpmm.lpmm_table(0), oracle.step_table("de"))
+    np.testing.assert_array_equal(lpmm.lpmm_table(1), oracle.step_table("linear"))
+
+
+def _probe_values(T):
+    rng = np.random.default_rng(0)
+    mids = ((T[:-1].astype(np.float64) + T[1:].astype(np.float64)) / 2).astype(np.float32)
+    near = [mids]
+    for k in range(1, 4):
+        up, dn = mids.copy(), mids.copy()
+        for _ in range(k):
+            up, dn = np.nextafter(up, np.float32(4)), np.nextafter(dn, np.float32(-4))
+        near += [up, dn]
+    # bucket edges of the search table: every multiple of 2^e/4 in the binades that matter
+    edges = np.array([s * (1 + q / 4) * 2.0 ** e for s in (-1, 1) for e in range(-12, 1) for q in range(4)],
+                     np.float32)
+    edges = np.concatenate([edges, np.nextafter(edges, np.float32(4)), np.nextafter(edges, np.float32(-4))])
+    rnd = rng.uniform(-1.2, 1.2, 400000).astype(np.float32)
+    small = (rng.uniform(-1, 1, 200000) * 10.0 ** rng.uniform(-8, 0, 200000)).astype(np.float32)
+    bits = rng.integers(0, 2 ** 32, 400000, dtype=np.uint64).astype(np.uint32).view(np.float32)
+    bits = bits[np.isfinite(bits) & (np.abs(bits) <= 4)]   # normalized values lie in [-1, 1]
+    special = np.array([0.0, -0.0, 1.0, -1.0, 1e-45, -1e-45, 1e-38, 3.0, -3.0], np.float32)
+    return np.concatenate([T, *near, edges, rnd, small, bits, special]).astype(np.float32)
+
+
+def test_host_search_matches_bruteforce_de():
+    T = oracle.step_table("de")
+    n = _probe_values(T)
+    np.testing.assert_array_equal(lpmm.lpmm_host_nearest_codes(0, n), oracle.nearest_codes(T, n))
+
+
+def test_host_search_matches_bruteforce_linear():
+    T = oracle.step_table("linear")
+    n = _probe_values(T)
+    np.testing.assert_array_equal(lpmm.lpmm_host_nearest_codes(1, n), oracle.nearest_codes(T, n))
+
+
+def test_state_sizes():
+    assert lpmm.lpmm_adamw4_state_sizes(1024, 1024) == [524288, 32768, 524288, 4096, 4096]
+    assert lpmm.lpmm_adamw4_state_sizes(3, 43) == [65, 8, 65, 12, 172]       # P = 129: odd, 2 blocks
+    assert lpmm.lpmm_adamw4_workspace_bytes(8192) >= 4 * 8192
+
+
+def test_argument_errors_are_reported_before_any_gpu_work():
+    L = lpmm.lib()
+    shape = (ctypes.c_int64 * 2)(16, 128)
+    bad_shape = (ctypes.c_int64 * 2)(0, 128)
+    sizes = (ctypes.c_size_t * 5)()
+    assert L.lpmm_adamw4_state_sizes(ctypes.addressof(bad_shape), ctypes.addressof(sizes)) == -1
+    assert L.lpmm_adamw4_state_sizes(None, ctypes.addressof(sizes)) == -1
+    buf = ctypes.create_string_buffer(4096 + 256)
+    p = (ctypes.addressof(buf) + 255) // 256 * 256             # an aligned, non-null fake pointer
+    args = [p] * 7 + [ctypes.addressof(shape)]
+    ok_h = [1e-3, 0.9, 0.999, 1e-8, 0.01]
+
+    def call(ptrs=args, h=ok_h, step=1):
+        return L.lpmm_adamw4_step(*ptrs, *[ctypes.c_float(x) for x in h], step, None)
+
+    assert call(step=0) == -1                                   # t starts at 1
+    assert call(h=[1e-3, 1.0, 0.999, 1e-8, 0.01]) == -1          # beta1 must be < 1
+    assert call(h=[1e-3, 0.9, -0.1, 1e-8, 0.01]) == -1
+    assert call(h=[float("nan"), 0.9, 0.999, 1e-8, 0.01]) == -1
+    assert call(h=[1e-3, 0.9, 0.999, -1.0, 0.01]) == -1
+    assert call(ptrs=[None] + args[1:]) == -1                   # null parameter pointer
+    assert call(ptrs=[p + 4] + args[1:]) == -1                  # misaligned parameter pointer
+    assert call(ptrs=args[:7] + [ctypes.addressof(bad_shape)]) == -1
+    assert L.lpmm_table(2, p) == -1
+    assert b"invalid" in L.lpmm_strerror(-1) and b"workspace" in L.lpmm_strerror(-4)
+    # a well-formed call before init (or without a GPU) is refused, not executed
+    assert call() in (-2, -3)
