@@ -1,0 +1,186 @@
+#!/usr/bin/env python3
+"""Benchmark of the 4-bit AdamW step on one MI355X.
+
+A "step" is one pass of the whole hot path over every tensor of the workload: for each quantized
+tensor the two-kernel 4-bit step (decompress, Adam rule, parameter update, compress), for each small
+tensor the fp32-state AdamW kernel.  All inputs are synthetic, seeded and resident in HBM before the
+timed region starts.  Prints ONE JSON line (see the keys at the bottom).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c5_llama_7b] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
+# Algorithmic bytes per quantized parameter (every stream touched once per kernel):
+#   pass 1: param read+write 8, grad 4 or 2, m codes read+write 1, v codes read 0.5, block scales
+#           read+write 8/128
+#   pass 2: grad 4 or 2 again, v codes read+write 1
+def bytes_per_param(bf16: bool):
+    g = 2.0 if bf16 else 4.0
+    p1 = 8.0 + g + 1.0 + 0.5 + 8.0 / 128.0
+    p2 = g + 1.0
+    return p1, p2
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="c5_llama_7b")
+    ap.add_argument("--seed", type=int, default=1)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2309_01507_amd as lpmm
+    import workloads
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    lpmm.lib()                                   # fail loudly if lpmm4.so is missing
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    specs = workloads.param_set(args.config)
+    bf16 = workloads.GRAD_BF16[args.config]
+    recipe = workloads.GRAD_RECIPE[args.config]
+    lr, b1, b2, eps, wd = 1e-3, 0.9, 0.999, 1e-8, 0.01
+
+    # ---- synthetic workload, generated on the device ------------------------------------------------
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(args.seed)
+    n_grad_sets = 2                              # the timed steps alternate between two gradient sets
+    tensors = []
+    max_rc = 2
+    for tid, sp in enumerate(specs):
+        p = torch.randn(sp.numel, generator=gen, device=dev, dtype=torch.float32) * 0.02
+        if recipe == "col_lognormal":
+            sigma = 1e-3 * torch.exp(torch.randn(sp.cols, generator=gen, device=dev))
+        gs = []
+        for k in range(n_grad_sets):
+            z = torch.randn(sp.rows, sp.cols, generator=gen, device=dev, dtype=torch.float32)
+            if recipe == "col_lognormal":
+                z *= sigma[None, :]
+            elif recipe == "iid":
+                z *= 1e-3
+            else:                                # outlier_sparse (config 3)
+                z *= 1e-4
+                hot_r = torch.randperm(sp.rows, generator=gen, device=dev)[:max(1, sp.rows // 100)]
+                hot_c = torch.randperm(sp.cols, generator=gen, device=dev)[:max(1, sp.cols // 200)]
+                z[hot_r, :] *= 1e3
+                z[:, hot_c] *= 1e3
+                zero = torch.rand(sp.rows, generator=gen, device=dev) < 0.9
+                z[zero, :] = 0.0
+            gs.append(z.reshape(-1).to(torch.bfloat16) if bf16 else z.reshape(-1).contiguous())
+            del z
+        if sp.quantized:
+            st = lpmm.new_state(sp.rows, sp.cols, dev)
+            max_rc = max(max_rc, sp.rows + sp.cols)
+            tensors.append(("q", sp, p, gs, st))
+        else:
+            m = torch.zeros(sp.numel, device=dev)
+            v = torch.zeros(sp.numel, device=dev)
+            tensors.append(("f", sp, p, gs, (m, v)))
+    lpmm.ensure_init(max_rc)
+    torch.cuda.synchronize()
+
+    n_params = sum(sp.numel for sp in specs)
+    n_quant = sum(sp.numel for sp in specs if sp.quantized)
+    step4 = lpmm.lpmm_adamw4_step_bf16g if bf16 else lpmm.lpmm_adamw4_step
+
+    def one_step(t):
+        k = t % n_grad_sets
+        for kind, sp, p, gs, st in tensors:
+            if kind == "q":
+                step4(p, gs[k], st, lr, b1, b2, eps, wd, t)
+            else:
+                lpmm.lpmm_adamw32_step(p, gs[k], st[0], st[1], sp.numel, 1 if bf16 else 0, lr, b1, b2, eps,
+                                       wd, t)
+
+    # ---- warm-up, then the timed region ---------------------------------------------------------------
+    t = 0
+    for _ in range(args.warmup):
+        t += 1
+        one_step(t)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        t += 1
+        one_step(t)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+    value = n_params / (elapsed / args.steps)
+
+    # ---- the same K steps again with HIP events around every kernel of the 4-bit step ------------------
+    n_q_tensors = sum(1 for x in tensors if x[0] == "q")
+    lpmm.lpmm_profile_begin(n_q_tensors * args.steps)
+    for _ in range(args.steps):
+        t += 1
+        one_step(t)
+    torch.cuda.synchronize()
+    p1_ms, p2_ms, n_calls = lpmm.lpmm_profile_end()
+    bp1, bp2 = bytes_per_param(bf16)
+    launches = max(n_calls, 1)
+    p1_avg_ms = p1_ms / launches
+    p1_bytes_per_launch = bp1 * n_quant * args.steps / launches
+    achieved = p1_bytes_per_launch / (p1_avg_ms * 1e-3) / 1e9
+    roofline = {
+        "bound": "hbm", "kernel": "pass1_fast", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+        "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+        "bytes_per_param": bp1, "launches": n_calls, "avg_launch_ms": round(p1_avg_ms, 5),
+        "params_per_launch": round(n_quant * args.steps / launches),
+        "pass2": {"bytes_per_param": bp2, "avg_launch_ms": round(p2_ms / launches, 5),
+                  "achieved": round(bp2 * n_quant * args.steps / max(p2_ms, 1e-9) / 1e6, 1)},
+    }
+
+    # ---- CPU baseline: the oracle as it stands, one thread, on a bounded sample of the workload -----------
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        big = max((sp for sp in specs if sp.quantized), key=lambda s: s.numel)
+        rows = min(big.rows, max(1, (24 << 20) // big.cols))        # about 25 M parameters of that tensor
+        cols = big.cols
+        w = workloads.weights(args.seed, 0, rows, cols).reshape(-1)
+        st = oracle.state_zero(rows, cols)
+        hp = oracle.Hyper(lr, b1, b2, eps, wd)
+        n_cpu_steps = 4
+        gs = [workloads.grads(args.seed, 0, s, rows, cols, recipe, bf16).reshape(-1) for s in (1, 2)]
+        c0 = time.perf_counter()
+        for s in range(1, n_cpu_steps + 1):
+            oracle.adamw4_step(w, gs[s % 2], st, hp, s)
+        cdt = time.perf_counter() - c0
+        cpu = {"value": round(rows * cols * n_cpu_steps / cdt, 1), "unit": "params/s", "cores": 1,
+               "kind": "oracle",
+               "sample": f"{n_cpu_steps} steps on the first {rows} rows of '{big.name}' ({rows}x{cols}, "
+                         f"{rows * cols} params), {cdt:.1f} s; host has {os.cpu_count()} logical cpus"}
+
+    total_gbps = (bp1 + bp2) * n_quant / (elapsed / args.steps) / 1e9
+    out = {
+        "metric": "params updated/sec per 4-bit AdamW step", "value": round(value, 1), "unit": "params/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": args.config, "tensors": len(specs), "params": n_params,
+                   "quantized_params": n_quant, "grad_dtype": "bf16" if bf16 else "f32",
+                   "grad_recipe": recipe, "launch": "per-tensor, 2 kernels per quantized tensor",
+                   "hbm_gbps_two_pass_model": round(total_gbps, 1),
+                   "hbm_frac_two_pass_model": round(total_gbps / HBM_PEAK_GBPS, 4)},
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -130,6 +130,16 @@ int lpmm_dequant_state(int which, const uint8_t* codes, const float* scale_a, co
 int lpmm_quant_state(int which, const float* in, const int64_t shape[2], uint8_t* codes,
                      float* scale_a, float* scale_b, void* stream);
 
+/* Per-kernel timing for benchmarks, with HIP events recorded on each call's own stream.
+ * lpmm_profile_begin(max_calls): from now on every lpmm_adamw4_step / _step_bf16g call in this process
+ * records an event before pass 1, between the two passes and after pass 2, for at most max_calls
+ * calls (later calls run unrecorded).  Creates host-side event objects only.
+ * lpmm_profile_end: waits for the recorded events, stores the summed durations in milliseconds of
+ * all recorded pass-1 launches in ms[0] and of all pass-2 launches in ms[1], the number of recorded
+ * calls in *n_calls, and stops recording.  ms, n_calls: host.  Not thread-safe. */
+int lpmm_profile_begin(int64_t max_calls);
+int lpmm_profile_end(double ms[2], int64_t* n_calls);
+
 #ifdef __cplusplus
 }
 #endif

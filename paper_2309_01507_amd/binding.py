@@ -74,6 +74,8 @@ def lib() -> ctypes.CDLL:
         L.lpmm_adamw32_step.argtypes = [_VP] * 4 + [_I64, ctypes.c_int] + [_F] * 5 + [_I64, _VP]
         L.lpmm_dequant_state.argtypes = [ctypes.c_int, _VP, _VP, _VP, _VP, _VP, _VP]
         L.lpmm_quant_state.argtypes = [ctypes.c_int, _VP, _VP, _VP, _VP, _VP, _VP]
+        L.lpmm_profile_begin.argtypes = [_I64]
+        L.lpmm_profile_end.argtypes = [_VP, _VP]
         _lib = L
     return _lib
 
@@ -237,3 +239,15 @@ def lpmm_quant_state(which: int, x, rows, cols, codes, scale_a, scale_b, stream=
     _check(lib().lpmm_quant_state(int(which), _ptr(x), ctypes.addressof(shape), _ptr(codes),
                                   _ptr(scale_a), _ptr(scale_b), _stream(stream)),
            "lpmm_quant_state")
+
+
+def lpmm_profile_begin(max_calls: int) -> None:
+    _check(lib().lpmm_profile_begin(int(max_calls)), "lpmm_profile_begin")
+
+
+def lpmm_profile_end():
+    """Returns (sum of pass-1 ms, sum of pass-2 ms, recorded calls)."""
+    ms = (ctypes.c_double * 2)()
+    n = ctypes.c_int64()
+    _check(lib().lpmm_profile_end(ctypes.addressof(ms), ctypes.addressof(n)), "lpmm_profile_end")
+    return float(ms[0]), float(ms[1]), int(n.value)

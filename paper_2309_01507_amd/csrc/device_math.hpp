@@ -110,6 +110,55 @@ __device__ __forceinline__ uint32_t quant_v_code(float vt, float sc) {
     return uint32_t(fminf(fmaxf(f, 0.0f), 15.0f));
 }
 
+// ---- approximate compress with a guard ---------------------------------------------------------------
+//
+// The exact functions above cost one IEEE division per element.  The fast variants multiply by an
+// approximate reciprocal (v_rcp_f32, 1 ulp) instead and keep track of how close the approximate
+// normalized value came to a decision boundary.  The approximate n' and the exact n = RN(x/s)
+// differ by at most 2^-22 |n| (1 ulp of the reciprocal, half an ulp each for the product and for
+// the exact quotient), so whenever n' stays further than twice that from every boundary both give
+// the same code.  `slack` accumulates the margin over a lane's elements; if it ends up negative in
+// any lane, the wave recomputes that row's codes with the exact functions.  Scales outside
+// [2^-100, 2^100] (where the reciprocal or scale/16 may lose bits) always take the exact path.
+
+constexpr float kScaleLo = 0x1p-100f;
+constexpr float kScaleHi = 0x1p100f;
+
+__device__ __forceinline__ bool scale_is_tame(float s) {
+    return s == 0.0f || (s >= kScaleLo && s <= kScaleHi);
+}
+__device__ __forceinline__ float approx_inv(float s) {
+    return s == 0.0f ? 0.0f : __builtin_amdgcn_rcpf(s);
+}
+
+// first moment: `slack` = |n' - thr| * 2^21 - |thr| for the one threshold of the bucket; negative
+// means the approximate n' is within 2^-21 |thr| of it and may sit on the wrong side
+__device__ __forceinline__ uint32_t quant_m_code_fast(const SearchEntry* s_search, float mt, float inv_s,
+                                                      float& slack) {
+    const float n = mt * inv_s;
+    const SearchEntry e = s_search[__float_as_uint(n) >> kBucketShift];
+    slack = __builtin_fmaf(fabsf(n - e.thr), 0x1p21f, -fabsf(e.thr));
+    return e.base + (n > e.thr ? 1u : 0u);
+}
+
+// second moment: boundaries of the Linear map are the integers of f = 16 n - 1.5 and the code is
+// ceil(f).  The approximate f' is within 2^-17 of the exact one; away from integers
+// round-to-nearest(f' + 0.5) equals ceil(f), and the saturating byte convert both rounds that way and
+// clamps below at 0 (above, n <= 1 keeps the code at 15).  `fr` returns fract(f'): a value within
+// 2^-16 of 0 or 1 sends the row to the exact path.
+constexpr float kMarginV = 0x1p-16f;
+
+template <int BYTE>
+__device__ __forceinline__ uint32_t quant_v_code_fast(float vt, float inv_sc, uint32_t packed, float& fr) {
+    const float n = vt * inv_sc;
+    fr = __builtin_amdgcn_fractf(__builtin_fmaf(16.0f, n, -1.5f));
+    return __builtin_amdgcn_cvt_pk_u8_f32(__builtin_fmaf(16.0f, n, -1.0f), BYTE, packed);
+}
+
+// second-moment decompress with the scale already divided by 16 (exact for tame scales):
+// (q+1) * s16 in one rounding == T_LIN[q] * scale
+__device__ __forceinline__ float dequant_v16(float qf, float s16) { return __builtin_fmaf(qf, s16, s16); }
+
 // ---- float maximum through an integer atomic (values >= +0 only: bit order == value order) --------
 
 __device__ __forceinline__ void atomic_max_nonneg(float* addr, float v) {

@@ -60,17 +60,102 @@ __device__ __forceinline__ void load_tables(float2* s_deq, SearchEntry* s_search
     for (int i = threadIdx.x; i < kBuckets; i += kThreads) ss[i] = gs[i];
 }
 
-// One lane's share of pass 1 on 8 elements held in registers.  Returns the new code words.
-struct Lane8 {
-    float w[8];
-    float g[8];
-    uint32_t mq, vq;
-};
-
 // =====================================================================================================
 // Fast path: cols % 128 == 0, so a block never straddles a row and a group can walk down the rows
 // of one column block with the 8 old and 8 running new column maxima of its lane in registers.
+// The loads of the next row are issued before the current row is computed.
 // =====================================================================================================
+
+struct Geo {            // where this group works
+    int strip, tile, grp, l, gxi, gyi, cb;
+    int64_t row0, row1, col0;
+    bool active;
+};
+
+__device__ __forceinline__ Geo geometry(const Tensor4& a, int wg) {
+    Geo g;
+    g.strip = wg % a.strips;
+    g.tile = wg / a.strips;
+    g.grp = threadIdx.x >> 4;
+    g.l = threadIdx.x & 15;
+    g.gxi = g.grp % a.gx;
+    g.gyi = g.grp / a.gx;
+    g.cb = g.strip * a.gx + g.gxi;
+    g.row0 = int64_t(g.tile) * a.rw;
+    g.row1 = (g.row0 + a.rw < a.rows) ? g.row0 + a.rw : a.rows;
+    g.col0 = int64_t(g.cb) * 128 + g.l * 8;
+    g.active = g.cb < a.nb;
+    return g;
+}
+
+__device__ __forceinline__ void load8(const float* p, float out[8]) {
+    const float4 a = *reinterpret_cast<const float4*>(p);
+    const float4 b = *reinterpret_cast<const float4*>(p + 4);
+    out[0] = a.x; out[1] = a.y; out[2] = a.z; out[3] = a.w;
+    out[4] = b.x; out[5] = b.y; out[6] = b.z; out[7] = b.w;
+}
+
+template <bool BF16> struct GradRegs;
+template <> struct GradRegs<true> { uint4 w; };
+template <> struct GradRegs<false> { float4 a, b; };
+
+template <bool BF16>
+__device__ __forceinline__ GradRegs<BF16> load_grad_regs(const void* g, int64_t idx) {
+    GradRegs<BF16> r;
+    if constexpr (BF16) {
+        r.w = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(g) + idx);
+    } else {
+        const float4* p = reinterpret_cast<const float4*>(reinterpret_cast<const float*>(g) + idx);
+        r.a = p[0];
+        r.b = p[1];
+    }
+    return r;
+}
+template <bool BF16>
+__device__ __forceinline__ void unpack_grad(const GradRegs<BF16>& r, float out[8]) {
+    if constexpr (BF16) {
+        out[0] = bf16_lo(r.w.x); out[1] = bf16_hi(r.w.x);
+        out[2] = bf16_lo(r.w.y); out[3] = bf16_hi(r.w.y);
+        out[4] = bf16_lo(r.w.z); out[5] = bf16_hi(r.w.z);
+        out[6] = bf16_lo(r.w.w); out[7] = bf16_hi(r.w.w);
+    } else {
+        out[0] = r.a.x; out[1] = r.a.y; out[2] = r.a.z; out[3] = r.a.w;
+        out[4] = r.b.x; out[5] = r.b.y; out[6] = r.b.z; out[7] = r.b.w;
+    }
+}
+
+// float(code) of a lane's 8 codes: split the word into low and high nibbles, then byte converts
+__device__ __forceinline__ void codes_to_float(uint32_t w, float qf[8]) {
+    const uint32_t lo = w & 0x0F0F0F0Fu, hi = (w >> 4) & 0x0F0F0F0Fu;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        qf[2 * k] = float((lo >> (8 * k)) & 255u);
+        qf[2 * k + 1] = float((hi >> (8 * k)) & 255u);
+    }
+}
+
+template <bool BF16>
+struct Row1 {                      // everything pass 1 reads for one row of one lane
+    float4 p0, p1;
+    GradRegs<BF16> g;
+    uint32_t mq, vq;
+    float s_old, r_old;
+};
+
+template <bool BF16>
+__device__ __forceinline__ Row1<BF16> load_row1(const Tensor4& a, const Geo& g, int64_t i) {
+    Row1<BF16> r;
+    const int64_t e0 = i * a.cols + g.col0;
+    const float4* pp = reinterpret_cast<const float4*>(a.p + e0);
+    r.p0 = pp[0];
+    r.p1 = pp[1];
+    r.g = load_grad_regs<BF16>(a.g, e0);
+    r.mq = a.mq[e0 >> 3];
+    r.vq = a.vq[e0 >> 3];
+    r.s_old = a.ms[i * a.nb + g.cb];
+    r.r_old = a.r[i];
+    return r;
+}
 
 template <bool BF16>
 __global__ __launch_bounds__(kThreads) void pass1_fast(const Tensor4 a, const Hyper h) {
@@ -83,93 +168,134 @@ __global__ __launch_bounds__(kThreads) void pass1_fast(const Tensor4 a, const Hy
     load_tables(s_deq, s_search);
     __syncthreads();
 
-    const int strip = wg % a.strips, tile = wg / a.strips;
-    const int grp = threadIdx.x >> 4, l = threadIdx.x & 15;
-    const int gxi = grp % a.gx, gyi = grp / a.gx;
-    const int cb = strip * a.gx + gxi;
-    const int64_t row0 = int64_t(tile) * a.rw;
-    const int64_t row1 = (row0 + a.rw < a.rows) ? row0 + a.rw : a.rows;
-
+    const Geo geo = geometry(a, wg);
     float cmax[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) cmax[e] = 0.0f;
 
-    if (cb < a.nb) {
-        const int64_t col0 = int64_t(cb) * 128 + l * 8;
-        float cold[8];
-        {
-            const float4 c0 = *reinterpret_cast<const float4*>(a.c + col0);
-            const float4 c1 = *reinterpret_cast<const float4*>(a.c + col0 + 4);
-            cold[0] = c0.x; cold[1] = c0.y; cold[2] = c0.z; cold[3] = c0.w;
-            cold[4] = c1.x; cold[5] = c1.y; cold[6] = c1.z; cold[7] = c1.w;
+    if (geo.active) {
+        float cold[8], cold16[8];
+        load8(a.c + geo.col0, cold);
+        bool cols_tame = true;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            cols_tame = cols_tame && scale_is_tame(cold[e]);
+            cold16[e] = cold[e] * 0.0625f;
         }
-        for (int64_t i = row0 + gyi; i < row1; i += a.gy) {
-            const int64_t e0 = i * a.cols + col0;
-            float4* pp = reinterpret_cast<float4*>(a.p + e0);
-            const float4 p0 = pp[0], p1 = pp[1];
-            float g[8];
-            load_grad8<BF16>(a.g, e0, g);
-            const uint32_t mq = a.mq[e0 >> 3];
-            const uint32_t vq = a.vq[e0 >> 3];
-            const float s_old = a.ms[i * a.nb + cb];
-            const float r_old = a.r[i];
-            float w[8] = {p0.x, p0.y, p0.z, p0.w, p1.x, p1.y, p1.z, p1.w};
+        const int64_t stride = a.gy;
+        int64_t i = geo.row0 + geo.gyi;
+        Row1<BF16> cur;
+        if (i < geo.row1) cur = load_row1<BF16>(a, geo, i);
+        while (i < geo.row1) {
+            const int64_t inext = i + stride;
+            Row1<BF16> nxt;
+            if (inext < geo.row1) nxt = load_row1<BF16>(a, geo, inext);
 
-            float mt[8], amax = 0.0f, rmax = 0.0f;
+            const int64_t e0 = i * a.cols + geo.col0;
+            float w[8] = {cur.p0.x, cur.p0.y, cur.p0.z, cur.p0.w, cur.p1.x, cur.p1.y, cur.p1.z, cur.p1.w};
+            float g[8];
+            unpack_grad<BF16>(cur.g, g);
+            float mt[8], vt[8], amax = 0.0f, rmax = 0.0f;
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                const float2 t = s_deq[(mq >> (8 * k)) & 255u];
-                mt[2 * k] = t.x * s_old;          // decompress: T_DE[code] * block scale
-                mt[2 * k + 1] = t.y * s_old;
+                const float2 t = s_deq[(cur.mq >> (8 * k)) & 255u];
+                mt[2 * k] = t.x * cur.s_old;          // decompress: T_DE[code] * block scale
+                mt[2 * k + 1] = t.y * cur.s_old;
+            }
+            // the wave takes the exact route for this row if any of its scales is extreme
+            const bool tame_in = cols_tame && scale_is_tame(cur.r_old);
+            if (__builtin_expect(__ballot(!tame_in) == 0, 1)) {
+                float qf[8];
+                codes_to_float(cur.vq, qf);
+                const float r16 = cur.r_old * 0.0625f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) vt[e] = dequant_v16(qf[e], fminf(r16, cold16[e]));
+            } else {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) vt[e] = dequant_v((cur.vq >> (4 * e)) & 15u, fminf(cur.r_old, cold[e]));
             }
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const float v_prev = dequant_v((vq >> (4 * e)) & 15u, fminf(r_old, cold[e]));
                 mt[e] = moment_m(h, mt[e], g[e]);
-                const float vt = moment_v(h, v_prev, g[e]);
-                w[e] = param_update(h, w[e], mt[e], vt);
+                vt[e] = moment_v(h, vt[e], g[e]);
+                w[e] = param_update(h, w[e], mt[e], vt[e]);
                 amax = fmaxf(amax, fabsf(mt[e]));
-                rmax = fmaxf(rmax, vt);
-                cmax[e] = fmaxf(cmax[e], vt);
+                rmax = fmaxf(rmax, vt[e]);
+                cmax[e] = fmaxf(cmax[e], vt[e]);
             }
             const float s_new = row16_allmax(amax);     // block absmax of m_t
             rmax = row16_allmax(rmax);
-            uint32_t mq_new = 0;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) mq_new |= quant_m_code(s_search, mt[e], s_new) << (4 * e);
 
+            uint32_t mq_new = 0;
+            float slack = 1.0f;
+            if (scale_is_tame(s_new)) {
+                const float inv_s = approx_inv(s_new);
+#pragma unroll
+                for (int e = 0; e < 8; e += 2) {
+                    float sa, sb;
+                    mq_new |= quant_m_code_fast(s_search, mt[e], inv_s, sa) << (4 * e);
+                    mq_new |= quant_m_code_fast(s_search, mt[e + 1], inv_s, sb) << (4 * e + 4);
+                    slack = fminf(fminf(slack, sa), sb);
+                }
+            } else {
+                slack = -1.0f;
+            }
+            if (__builtin_expect(__ballot(slack < 0.0f) != 0, 0)) {
+                mq_new = 0;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) mq_new |= quant_m_code(s_search, mt[e], s_new) << (4 * e);
+            }
+
+            float4* pp = reinterpret_cast<float4*>(a.p + e0);
             pp[0] = make_float4(w[0], w[1], w[2], w[3]);
             pp[1] = make_float4(w[4], w[5], w[6], w[7]);
             a.mq[e0 >> 3] = mq_new;
-            if (l == 0) {
-                a.ms[i * a.nb + cb] = s_new;
+            if (geo.l == 0) {
+                a.ms[i * a.nb + geo.cb] = s_new;
                 if (rmax > 0.0f) atomic_max_nonneg(a.r_new + i, rmax);
             }
+            cur = nxt;
+            i = inext;
         }
     }
 
     // column maxima: combine the gy groups that share a column block, then one atomic per column
 #pragma unroll
-    for (int e = 0; e < 8; ++e) s_col[grp * 128 + l * 8 + e] = cmax[e];
+    for (int e = 0; e < 8; ++e) s_col[geo.grp * 128 + geo.l * 8 + e] = cmax[e];
     __syncthreads();
     for (int t = threadIdx.x; t < a.gx * 128; t += kThreads) {
         const int gi = t >> 7;
         float m = 0.0f;
         for (int y = 0; y < a.gy; ++y) m = fmaxf(m, s_col[((y * a.gx + gi) << 7) + (t & 127)]);
-        const int cbi = strip * a.gx + gi;
+        const int cbi = geo.strip * a.gx + gi;
         if (cbi < a.nb && m > 0.0f) atomic_max_nonneg(a.c_new + int64_t(cbi) * 128 + (t & 127), m);
     }
 }
 
 // The last workgroup of pass 2 to finish makes r', c' the state and clears the workspace.  Every
 // other workgroup has read the old r, c before it took its ticket, so overwriting them is safe.
+// Tickets are taken in two levels (kTicketLanes first-level counters, one cache line apart, then
+// one top counter) so that thousands of workgroups do not queue up on a single address.
+constexpr int kTicketLanes = 32;
+constexpr int kTicketStride = 32;   // in 32-bit words: 128 bytes
+
 __device__ __forceinline__ void publish_if_last(const Tensor4& a) {
     __shared__ int s_last;
     __syncthreads();
     if (threadIdx.x == 0) {
-        __threadfence();
-        const unsigned int ticket = atomicAdd(a.counter, 1u);
-        s_last = (ticket == gridDim.x - 1) ? 1 : 0;
+        // No fence: the ticket orders nothing but "this workgroup's loads of r, c have returned",
+        // which holds once its waves have computed their codes and reached the barrier above.  (An
+        // agent-scope release here would write back the XCD's whole L2 once per workgroup.)
+        const unsigned int n_wg = gridDim.x;
+        const unsigned int lane = blockIdx.x % kTicketLanes;
+        const unsigned int in_lane = n_wg / kTicketLanes + (lane < n_wg % kTicketLanes ? 1u : 0u);
+        int last = 0;
+        if (atomicAdd(a.counter + (1 + lane) * kTicketStride, 1u) == in_lane - 1) {
+            a.counter[(1 + lane) * kTicketStride] = 0u;      // this lane is complete: reset it
+            const unsigned int lanes_used = n_wg < kTicketLanes ? n_wg : kTicketLanes;
+            last = atomicAdd(a.counter, 1u) == lanes_used - 1;
+        }
+        s_last = last;
     }
     __syncthreads();
     if (!s_last) return;
@@ -179,43 +305,95 @@ __device__ __forceinline__ void publish_if_last(const Tensor4& a) {
 }
 
 template <bool BF16>
+struct Row2 {                      // everything pass 2 reads for one row of one lane
+    GradRegs<BF16> g;
+    uint32_t vq;
+    float r_old, r_new;
+};
+
+template <bool BF16>
+__device__ __forceinline__ Row2<BF16> load_row2(const Tensor4& a, const Geo& g, int64_t i) {
+    Row2<BF16> r;
+    const int64_t e0 = i * a.cols + g.col0;
+    r.g = load_grad_regs<BF16>(a.g, e0);
+    r.vq = a.vq[e0 >> 3];
+    r.r_old = a.r[i];
+    r.r_new = a.r_new[i];
+    return r;
+}
+
+template <bool BF16>
+__device__ __forceinline__ uint32_t pass2_row(const Hyper& h, const Row2<BF16>& row, const float cold[8],
+                                              const float cold16[8], const float cnew[8],
+                                              const float inv_cnew[8], bool cols_tame) {
+    float g[8], vt[8];
+    unpack_grad<BF16>(row.g, g);
+    const bool tame = cols_tame && scale_is_tame(row.r_old) && scale_is_tame(row.r_new);
+    const bool fast = __ballot(!tame) == 0;
+    if (__builtin_expect(fast, 1)) {
+        float qf[8];
+        codes_to_float(row.vq, qf);
+        const float r16 = row.r_old * 0.0625f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) vt[e] = moment_v(h, dequant_v16(qf[e], fminf(r16, cold16[e])), g[e]);
+        const float inv_r = approx_inv(row.r_new);
+        // even elements collect in the bytes of `lo`, odd ones in `hi`; word = lo | hi << 4
+        uint32_t lo = 0, hi = 0;
+        float fmin_ = 0.5f, fmax_ = 0.5f, fa, fb;
+#define LPMM_V2(K)                                                                                        \
+        lo = quant_v_code_fast<K>(vt[2 * K], fmaxf(inv_r, inv_cnew[2 * K]), lo, fa);                      \
+        hi = quant_v_code_fast<K>(vt[2 * K + 1], fmaxf(inv_r, inv_cnew[2 * K + 1]), hi, fb);              \
+        fmin_ = fminf(fminf(fmin_, fa), fb);                                                              \
+        fmax_ = fmaxf(fmaxf(fmax_, fa), fb);
+        LPMM_V2(0) LPMM_V2(1) LPMM_V2(2) LPMM_V2(3)
+#undef LPMM_V2
+        const bool near = fmin_ < kMarginV || fmax_ > 1.0f - kMarginV;
+        if (__builtin_expect(__ballot(near) == 0, 1)) return lo | (hi << 4);
+    } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            vt[e] = moment_v(h, dequant_v((row.vq >> (4 * e)) & 15u, fminf(row.r_old, cold[e])), g[e]);
+    }
+    uint32_t out = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) out |= quant_v_code(vt[e], fminf(row.r_new, cnew[e])) << (4 * e);
+    return out;
+}
+
+template <bool BF16>
 __global__ __launch_bounds__(kThreads) void pass2_fast(const Tensor4 a, const Hyper h) {
     const int wg = logical_wg();
     if (wg < a.n_wg) {
-        const int strip = wg % a.strips, tile = wg / a.strips;
-        const int grp = threadIdx.x >> 4, l = threadIdx.x & 15;
-        const int gxi = grp % a.gx, gyi = grp / a.gx;
-        const int cb = strip * a.gx + gxi;
-        const int64_t row0 = int64_t(tile) * a.rw;
-        const int64_t row1 = (row0 + a.rw < a.rows) ? row0 + a.rw : a.rows;
-        if (cb < a.nb) {
-            const int64_t col0 = int64_t(cb) * 128 + l * 8;
-            float cold[8], cnew[8];
-            {
-                const float4 c0 = *reinterpret_cast<const float4*>(a.c + col0);
-                const float4 c1 = *reinterpret_cast<const float4*>(a.c + col0 + 4);
-                cold[0] = c0.x; cold[1] = c0.y; cold[2] = c0.z; cold[3] = c0.w;
-                cold[4] = c1.x; cold[5] = c1.y; cold[6] = c1.z; cold[7] = c1.w;
-                const float4 n0 = *reinterpret_cast<const float4*>(a.c_new + col0);
-                const float4 n1 = *reinterpret_cast<const float4*>(a.c_new + col0 + 4);
-                cnew[0] = n0.x; cnew[1] = n0.y; cnew[2] = n0.z; cnew[3] = n0.w;
-                cnew[4] = n1.x; cnew[5] = n1.y; cnew[6] = n1.z; cnew[7] = n1.w;
-            }
-            for (int64_t i = row0 + gyi; i < row1; i += a.gy) {
-                const int64_t e0 = i * a.cols + col0;
-                float g[8];
-                load_grad8<BF16>(a.g, e0, g);
-                const uint32_t vq = a.vq[e0 >> 3];
-                const float r_old = a.r[i];
-                const float r_new = a.r_new[i];
-                uint32_t vq_new = 0;
+        const Geo geo = geometry(a, wg);
+        if (geo.active) {
+            float cold[8], cold16[8], cnew[8], inv_cnew[8];
+            load8(a.c + geo.col0, cold);
+            load8(a.c_new + geo.col0, cnew);
+            bool cols_tame = true;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float v_prev = dequant_v((vq >> (4 * e)) & 15u, fminf(r_old, cold[e]));
-                    const float vt = moment_v(h, v_prev, g[e]);
-                    vq_new |= quant_v_code(vt, fminf(r_new, cnew[e])) << (4 * e);
-                }
-                a.vq[e0 >> 3] = vq_new;
+            for (int e = 0; e < 8; ++e) {
+                cols_tame = cols_tame && scale_is_tame(cold[e]) && scale_is_tame(cnew[e]);
+                cold16[e] = cold[e] * 0.0625f;
+                inv_cnew[e] = approx_inv(cnew[e]);
+            }
+            // two rows per stage, the next stage's loads in flight while this one is computed
+            const int64_t stride = a.gy;
+            int64_t i = geo.row0 + geo.gyi;
+            Row2<BF16> c0, c1;
+            if (i < geo.row1) c0 = load_row2<BF16>(a, geo, i);
+            if (i + stride < geo.row1) c1 = load_row2<BF16>(a, geo, i + stride);
+            while (i < geo.row1) {
+                const int64_t j0 = i + 2 * stride, j1 = i + 3 * stride;
+                Row2<BF16> n0, n1;
+                if (j0 < geo.row1) n0 = load_row2<BF16>(a, geo, j0);
+                if (j1 < geo.row1) n1 = load_row2<BF16>(a, geo, j1);
+                a.vq[(i * a.cols + geo.col0) >> 3] = pass2_row<BF16>(h, c0, cold, cold16, cnew, inv_cnew, cols_tame);
+                if (i + stride < geo.row1)
+                    a.vq[((i + stride) * a.cols + geo.col0) >> 3] =
+                        pass2_row<BF16>(h, c1, cold, cold16, cnew, inv_cnew, cols_tame);
+                c0 = n0;
+                c1 = n1;
+                i = j0;
             }
         }
     }

@@ -7,6 +7,7 @@
 #include <cmath>
 #include <cstdlib>
 #include <mutex>
+#include <vector>
 
 #include "../../include/lpmm4.h"
 #include "kernels.hpp"
@@ -16,7 +17,7 @@ namespace {
 using namespace lpmm;
 
 constexpr int kMaxDevices = 16;
-constexpr size_t kCounterBytes = 256;   // tail of the workspace: counters, one cache line apart
+constexpr size_t kCounterBytes = 8192;  // tail of the workspace: ticket counters of pass 2, one cache line apart
 
 struct DeviceCtx {
     bool ready = false;
@@ -29,6 +30,18 @@ struct DeviceCtx {
 DeviceCtx g_ctx[kMaxDevices];
 std::mutex g_mu;
 thread_local int g_last_hip = 0;
+
+// per-kernel timing (lpmm_profile_begin / _end)
+struct Profile {
+    bool on = false;
+    int64_t max_calls = 0, calls = 0;
+    std::vector<hipEvent_t> ev;    // 3 per recorded call
+};
+Profile g_prof;
+
+hipEvent_t prof_event(int64_t call, int which) {
+    return g_prof.ev[size_t(call) * 3 + which];
+}
 
 // host copies of the tables (also serve the host-only entry points)
 struct HostTables {
@@ -123,19 +136,21 @@ void fast_geometry(Tensor4* a, int n_cu) {
 
 template <bool BF16>
 int launch_step(const Tensor4& t, const Hyper& h, bool fast, hipStream_t s) {
-    if (fast) {
-        const int grid = pad8(t.n_wg);
-        hipLaunchKernelGGL(pass1_fast<BF16>, dim3(grid), dim3(kThreads), 0, s, t, h);
-        LPMM_HIP(hipGetLastError());
-        hipLaunchKernelGGL(pass2_fast<BF16>, dim3(grid), dim3(kThreads), 0, s, t, h);
-        LPMM_HIP(hipGetLastError());
-    } else {
-        const int64_t lanes = (t.P + 7) / 8;
-        const int grid = int((lanes + kThreads - 1) / kThreads);
-        hipLaunchKernelGGL(pass1_general<BF16>, dim3(grid), dim3(kThreads), 0, s, t, h);
-        LPMM_HIP(hipGetLastError());
-        hipLaunchKernelGGL(pass2_general<BF16>, dim3(grid), dim3(kThreads), 0, s, t, h);
-        LPMM_HIP(hipGetLastError());
+    const bool rec = g_prof.on && g_prof.calls < g_prof.max_calls;
+    const int64_t call = g_prof.calls;
+    if (rec) LPMM_HIP(hipEventRecord(prof_event(call, 0), s));
+    const int64_t lanes = (t.P + 7) / 8;
+    const int grid = fast ? pad8(t.n_wg) : int((lanes + kThreads - 1) / kThreads);
+    if (fast) hipLaunchKernelGGL(pass1_fast<BF16>, dim3(grid), dim3(kThreads), 0, s, t, h);
+    else hipLaunchKernelGGL(pass1_general<BF16>, dim3(grid), dim3(kThreads), 0, s, t, h);
+    LPMM_HIP(hipGetLastError());
+    if (rec) LPMM_HIP(hipEventRecord(prof_event(call, 1), s));
+    if (fast) hipLaunchKernelGGL(pass2_fast<BF16>, dim3(grid), dim3(kThreads), 0, s, t, h);
+    else hipLaunchKernelGGL(pass2_general<BF16>, dim3(grid), dim3(kThreads), 0, s, t, h);
+    LPMM_HIP(hipGetLastError());
+    if (rec) {
+        LPMM_HIP(hipEventRecord(prof_event(call, 2), s));
+        g_prof.calls = call + 1;
     }
     return LPMM_OK;
 }
@@ -397,6 +412,36 @@ int lpmm_quant_state(int which, const float* in, const int64_t shape[2], uint8_t
         hipLaunchKernelGGL(quant_v_code_kernel, dim3(grid), dim3(kThreads), 0, s, q);
         LPMM_HIP(hipGetLastError());
     }
+    return LPMM_OK;
+}
+
+int lpmm_profile_begin(int64_t max_calls) {
+    if (max_calls < 1 || max_calls > (int64_t(1) << 20)) return LPMM_EINVAL;
+    while (int64_t(g_prof.ev.size()) < 3 * max_calls) {
+        hipEvent_t e;
+        LPMM_HIP(hipEventCreate(&e));
+        g_prof.ev.push_back(e);
+    }
+    g_prof.max_calls = max_calls;
+    g_prof.calls = 0;
+    g_prof.on = true;
+    return LPMM_OK;
+}
+
+int lpmm_profile_end(double ms[2], int64_t* n_calls) {
+    if (!ms || !n_calls) return LPMM_EINVAL;
+    g_prof.on = false;
+    ms[0] = ms[1] = 0.0;
+    *n_calls = g_prof.calls;
+    for (int64_t c = 0; c < g_prof.calls; ++c) {
+        LPMM_HIP(hipEventSynchronize(prof_event(c, 2)));
+        float a = 0.0f, b = 0.0f;
+        LPMM_HIP(hipEventElapsedTime(&a, prof_event(c, 0), prof_event(c, 1)));
+        LPMM_HIP(hipEventElapsedTime(&b, prof_event(c, 1), prof_event(c, 2)));
+        ms[0] += a;
+        ms[1] += b;
+    }
+    g_prof.calls = 0;
     return LPMM_OK;
 }
 

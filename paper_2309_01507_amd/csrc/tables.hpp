@@ -25,8 +25,12 @@ constexpr int kBucketBits = 11;
 constexpr int kBuckets = 1 << kBucketBits;   // 2048
 constexpr int kBucketShift = 32 - kBucketBits;
 
+// Buckets without a threshold compare against a value no normalized input reaches (|n| <= 1 up to
+// rounding); it is finite so that distance arithmetic on it stays finite.
+constexpr float kNoThreshold = 8.0f;
+
 struct SearchEntry {
-    float thr;       // the one decision threshold inside this bucket, +inf if none
+    float thr;       // the one decision threshold inside this bucket, kNoThreshold if none
     uint32_t base;   // number of thresholds below the bucket
 };
 
@@ -80,8 +84,9 @@ inline bool build_search(const float thr[kCodes - 1], SearchEntry tab[kBuckets])
         const uint32_t hi_bits = lo_bits | ((1u << kBucketShift) - 1u);
         const bool neg = (b >> (kBucketBits - 1)) != 0;
         const int expo = (b >> 2) & 0xFF;
-        SearchEntry e{inf, 0};
+        SearchEntry e{kNoThreshold, 0};
         if (expo == 0xFF) {           // inf / NaN patterns: behave like the brute-force argmin -> code 0
+            e.thr = inf;
             tab[b] = e;
             continue;
         }
