@@ -38,6 +38,9 @@ def main():
     ap.add_argument("--config", default="c5_llama_7b")
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--launch", choices=["multi", "per-tensor"], default="multi",
+                    help="multi: one plan, pass 1 / pass 2 of neighbouring tensor groups share launches; "
+                         "per-tensor: two launches per quantized tensor")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
@@ -99,8 +102,18 @@ def main():
     n_quant = sum(sp.numel for sp in specs if sp.quantized)
     step4 = lpmm.lpmm_adamw4_step_bf16g if bf16 else lpmm.lpmm_adamw4_step
 
+    # one plan per gradient set (a plan refers to its buffers by address)
+    plans = []
+    if args.launch == "multi":
+        for k in range(n_grad_sets):
+            descs = [lpmm.make_desc(p, gs[k], st, sp.rows, sp.cols) for kind, sp, p, gs, st in tensors]
+            plans.append(lpmm.new_plan(descs, 1 if bf16 else 0, dev))
+
     def one_step(t):
         k = t % n_grad_sets
+        if plans:
+            lpmm.lpmm_adamw4_step_multi(plans[k], lr, b1, b2, eps, wd, t)
+            return
         for kind, sp, p, gs, st in tensors:
             if kind == "q":
                 step4(p, gs[k], st, lr, b1, b2, eps, wd, t)
@@ -123,27 +136,41 @@ def main():
     ms_per_step = elapsed * 1e3 / args.steps
     value = n_params / (elapsed / args.steps)
 
-    # ---- the same K steps again with HIP events around every kernel of the 4-bit step ------------------
+    # ---- the same K steps again with HIP events around every launch of the step -------------------------
+    bp1, bp2 = bytes_per_param(bf16)
+    n_small = n_params - n_quant
+    small_bytes = (24.0 + (2.0 if bf16 else 4.0)) * n_small      # fp32-state AdamW: p, m, v read+write, g read
     n_q_tensors = sum(1 for x in tensors if x[0] == "q")
-    lpmm.lpmm_profile_begin(n_q_tensors * args.steps)
+    lpmm.lpmm_profile_begin(max(n_q_tensors, 64) * args.steps)
     for _ in range(args.steps):
         t += 1
         one_step(t)
     torch.cuda.synchronize()
     p1_ms, p2_ms, n_calls = lpmm.lpmm_profile_end()
-    bp1, bp2 = bytes_per_param(bf16)
     launches = max(n_calls, 1)
-    p1_avg_ms = p1_ms / launches
-    p1_bytes_per_launch = bp1 * n_quant * args.steps / launches
-    achieved = p1_bytes_per_launch / (p1_avg_ms * 1e-3) / 1e9
-    roofline = {
-        "bound": "hbm", "kernel": "pass1_fast", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
-        "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
-        "bytes_per_param": bp1, "launches": n_calls, "avg_launch_ms": round(p1_avg_ms, 5),
-        "params_per_launch": round(n_quant * args.steps / launches),
-        "pass2": {"bytes_per_param": bp2, "avg_launch_ms": round(p2_ms / launches, 5),
-                  "achieved": round(bp2 * n_quant * args.steps / max(p2_ms, 1e-9) / 1e6, 1)},
-    }
+    if plans:
+        # every launch is the phase kernel: pass 1 of one tensor group + pass 2 of the previous group
+        bytes_per_launch = ((bp1 + bp2) * n_quant + small_bytes) * args.steps / launches
+        avg_ms = p1_ms / launches
+        achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9
+        roofline = {
+            "bound": "hbm", "kernel": "phase_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+            "bytes_per_param": bp1 + bp2, "launches": n_calls, "avg_launch_ms": round(avg_ms, 5),
+            "bytes_per_launch": round(bytes_per_launch),
+        }
+    else:
+        p1_avg_ms = p1_ms / launches
+        p1_bytes_per_launch = bp1 * n_quant * args.steps / launches
+        achieved = p1_bytes_per_launch / (p1_avg_ms * 1e-3) / 1e9
+        roofline = {
+            "bound": "hbm", "kernel": "pass1_fast", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+            "bytes_per_param": bp1, "launches": n_calls, "avg_launch_ms": round(p1_avg_ms, 5),
+            "bytes_per_launch": round(p1_bytes_per_launch),
+            "pass2": {"bytes_per_param": bp2, "avg_launch_ms": round(p2_ms / launches, 5),
+                      "achieved": round(bp2 * n_quant * args.steps / max(p2_ms, 1e-9) / 1e6, 1)},
+        }
 
     # ---- CPU baseline: the oracle as it stands, one thread, on a bounded sample of the workload -----------
     cpu = None
@@ -166,7 +193,7 @@ def main():
                "sample": f"{n_cpu_steps} steps on the first {rows} rows of '{big.name}' ({rows}x{cols}, "
                          f"{rows * cols} params), {cdt:.1f} s; host has {os.cpu_count()} logical cpus"}
 
-    total_gbps = (bp1 + bp2) * n_quant / (elapsed / args.steps) / 1e9
+    total_gbps = ((bp1 + bp2) * n_quant + small_bytes) / (elapsed / args.steps) / 1e9
     out = {
         "metric": "params updated/sec per 4-bit AdamW step", "value": round(value, 1), "unit": "params/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
@@ -174,7 +201,9 @@ def main():
         "data": "synthetic",
         "config": {"workload": args.config, "tensors": len(specs), "params": n_params,
                    "quantized_params": n_quant, "grad_dtype": "bf16" if bf16 else "f32",
-                   "grad_recipe": recipe, "launch": "per-tensor, 2 kernels per quantized tensor",
+                   "grad_recipe": recipe,
+                   "launch": ("multi-tensor plan, %d launches per step" % (n_calls // max(args.steps, 1)))
+                   if plans else "per-tensor, 2 kernels per quantized tensor",
                    "hbm_gbps_two_pass_model": round(total_gbps, 1),
                    "hbm_frac_two_pass_model": round(total_gbps / HBM_PEAK_GBPS, 4)},
         "roofline": roofline, "cpu_baseline": cpu,

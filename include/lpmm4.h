@@ -130,13 +130,61 @@ int lpmm_dequant_state(int which, const uint8_t* codes, const float* scale_a, co
 int lpmm_quant_state(int which, const float* in, const int64_t shape[2], uint8_t* codes,
                      float* scale_a, float* scale_b, void* stream);
 
+/* ---- many tensors in one call ---------------------------------------------------------------------
+ * The same step for a whole parameter set (Alg. 1: "perform the optimizer steps separately for each
+ * layer" -- here all layers are enqueued by one call).  A plan is built once for a list of tensors;
+ * lpmm_adamw4_step_multi then enqueues a short sequence of launches, each of which runs pass 1 of one
+ * group of tensors next to pass 2 of the previous group.  Results are identical to calling the
+ * single-tensor entry points one tensor at a time. */
+
+#define LPMM_KIND_4BIT 0   /* quantized states as in lpmm_adamw4_step */
+#define LPMM_KIND_FP32 1   /* uncompressed fp32 states as in lpmm_adamw32_step */
+
+typedef struct lpmm_tensor_desc {
+    void* param;            /* float[rows*cols], in place */
+    const void* grad;       /* float or bf16 [rows*cols] (one type for the whole plan) */
+    void* m_state;          /* 4BIT: uint8 m_codes;  FP32: float m[rows*cols] */
+    float* m_blockscale;    /* 4BIT only */
+    void* v_state;          /* 4BIT: uint8 v_codes;  FP32: float v[rows*cols] */
+    float* v_rowmax;        /* 4BIT only */
+    float* v_colmax;        /* 4BIT only */
+    int64_t rows, cols;
+    int32_t kind;           /* LPMM_KIND_* */
+    int32_t reserved;       /* 0 */
+} lpmm_tensor_desc;
+
+/* Bytes of device memory a plan for these tensors needs (descriptor tables, per-tensor row/column
+ * maxima of the updated second moment, ticket counters).  descs: host array of n entries; only
+ * rows, cols and kind are read.  Returns 0 for invalid input. */
+size_t lpmm_adamw4_plan_bytes(const lpmm_tensor_desc* descs, int64_t n);
+
+/* Builds the plan into `plan` (device memory, 256-byte aligned, plan_bytes long, owned by the caller
+ * and kept alive and unmodified while the plan is in use) on `stream`; the copy is complete when
+ * work enqueued on `stream` before this call's return has finished.  Pointer alignment rules are
+ * those of the single-tensor calls.  The plan refers to the tensors' buffers by address: rebuild it
+ * if any of them moves.  A small host-side record is kept until lpmm_adamw4_plan_release(plan). */
+int lpmm_adamw4_plan_build(const lpmm_tensor_desc* descs, int64_t n, int grad_dtype, void* plan,
+                           size_t plan_bytes, void* stream);
+
+/* One step (same t, same hyper-parameters) for every tensor of the plan.  A plan holds its own
+ * workspace, so plans (and single-tensor steps) may run concurrently on different streams as long
+ * as they share no tensor; two steps of the same plan must not overlap. */
+int lpmm_adamw4_step_multi(void* plan, float lr, float beta1, float beta2, float eps,
+                           float weight_decay, int64_t step, void* stream);
+
+/* Forgets the host-side record of a plan (the device memory stays the caller's). */
+int lpmm_adamw4_plan_release(void* plan);
+
 /* Per-kernel timing for benchmarks, with HIP events recorded on each call's own stream.
  * lpmm_profile_begin(max_calls): from now on every lpmm_adamw4_step / _step_bf16g call in this process
- * records an event before pass 1, between the two passes and after pass 2, for at most max_calls
- * calls (later calls run unrecorded).  Creates host-side event objects only.
- * lpmm_profile_end: waits for the recorded events, stores the summed durations in milliseconds of
- * all recorded pass-1 launches in ms[0] and of all pass-2 launches in ms[1], the number of recorded
- * calls in *n_calls, and stops recording.  ms, n_calls: host.  Not thread-safe. */
+ * records an event before pass 1, between the two passes and after pass 2, and every
+ * lpmm_adamw4_step_multi call an event before and after each of its launches, for at most max_calls
+ * recorded launches pairs / launches (later ones run unrecorded).  Creates host-side event objects only.
+ * lpmm_profile_end: waits for the recorded events and stops recording.  Single-tensor steps: ms[0]
+ * = summed duration in milliseconds of the recorded pass-1 launches, ms[1] = of the pass-2 launches,
+ * *n_calls = recorded calls.  Multi-tensor steps: ms[0] = summed duration of the recorded phase
+ * launches, ms[1] = 0, *n_calls = recorded launches.  (Do not mix the two kinds between one begin
+ * and end.)  ms, n_calls: host.  Not thread-safe. */
 int lpmm_profile_begin(int64_t max_calls);
 int lpmm_profile_end(double ms[2], int64_t* n_calls);
 

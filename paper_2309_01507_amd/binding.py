@@ -74,6 +74,11 @@ def lib() -> ctypes.CDLL:
         L.lpmm_adamw32_step.argtypes = [_VP] * 4 + [_I64, ctypes.c_int] + [_F] * 5 + [_I64, _VP]
         L.lpmm_dequant_state.argtypes = [ctypes.c_int, _VP, _VP, _VP, _VP, _VP, _VP]
         L.lpmm_quant_state.argtypes = [ctypes.c_int, _VP, _VP, _VP, _VP, _VP, _VP]
+        L.lpmm_adamw4_plan_bytes.argtypes = [_VP, _I64]
+        L.lpmm_adamw4_plan_bytes.restype = ctypes.c_size_t
+        L.lpmm_adamw4_plan_build.argtypes = [_VP, _I64, ctypes.c_int, _VP, ctypes.c_size_t, _VP]
+        L.lpmm_adamw4_step_multi.argtypes = [_VP] + [_F] * 5 + [_I64, _VP]
+        L.lpmm_adamw4_plan_release.argtypes = [_VP]
         L.lpmm_profile_begin.argtypes = [_I64]
         L.lpmm_profile_end.argtypes = [_VP, _VP]
         _lib = L
@@ -239,6 +244,62 @@ def lpmm_quant_state(which: int, x, rows, cols, codes, scale_a, scale_b, stream=
     _check(lib().lpmm_quant_state(int(which), _ptr(x), ctypes.addressof(shape), _ptr(codes),
                                   _ptr(scale_a), _ptr(scale_b), _stream(stream)),
            "lpmm_quant_state")
+
+
+# ---- many tensors in one call ------------------------------------------------------------------------
+
+KIND_4BIT, KIND_FP32 = 0, 1
+
+
+class TensorDesc(ctypes.Structure):
+    """Mirror of lpmm_tensor_desc."""
+    _fields_ = [("param", _VP), ("grad", _VP), ("m_state", _VP), ("m_blockscale", _VP), ("v_state", _VP),
+                ("v_rowmax", _VP), ("v_colmax", _VP), ("rows", _I64), ("cols", _I64),
+                ("kind", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+
+
+def make_desc(param, grad, state, rows=None, cols=None) -> TensorDesc:
+    """state: a State4 (4-bit) or a (m, v) pair of fp32 tensors (then rows, cols must be given)."""
+    if isinstance(state, State4):
+        return TensorDesc(_ptr(param), _ptr(grad), _ptr(state.m_codes), _ptr(state.m_blockscale),
+                          _ptr(state.v_codes), _ptr(state.v_rowmax), _ptr(state.v_colmax), state.rows,
+                          state.cols, KIND_4BIT, 0)
+    m, v = state
+    return TensorDesc(_ptr(param), _ptr(grad), _ptr(m), None, _ptr(v), None, None, int(rows), int(cols),
+                      KIND_FP32, 0)
+
+
+def lpmm_adamw4_plan_bytes(descs) -> int:
+    arr = (TensorDesc * len(descs))(*descs)
+    return int(lib().lpmm_adamw4_plan_bytes(ctypes.addressof(arr), len(descs)))
+
+
+def lpmm_adamw4_plan_build(descs, grad_dtype: int, plan, stream=None) -> None:
+    arr = (TensorDesc * len(descs))(*descs)
+    nbytes = plan.numel() * plan.element_size()
+    _check(lib().lpmm_adamw4_plan_build(ctypes.addressof(arr), len(descs), int(grad_dtype), _ptr(plan), nbytes,
+                                        _stream(stream)), "lpmm_adamw4_plan_build")
+
+
+def lpmm_adamw4_step_multi(plan, lr, beta1, beta2, eps, weight_decay, step, stream=None) -> None:
+    _check(lib().lpmm_adamw4_step_multi(_ptr(plan), lr, beta1, beta2, eps, weight_decay, int(step),
+                                        _stream(stream)), "lpmm_adamw4_step_multi")
+
+
+def lpmm_adamw4_plan_release(plan) -> None:
+    _check(lib().lpmm_adamw4_plan_release(_ptr(plan)), "lpmm_adamw4_plan_release")
+
+
+def new_plan(descs, grad_dtype: int, device="cuda"):
+    """Allocate (torch) and build a plan; returns the device buffer that is the plan."""
+    import torch
+    nbytes = lpmm_adamw4_plan_bytes(descs)
+    if nbytes == 0:
+        raise LpmmError("lpmm_adamw4_plan_bytes: invalid tensor list")
+    plan = torch.zeros(nbytes, dtype=torch.uint8, device=device)
+    lpmm_adamw4_plan_build(descs, grad_dtype, plan)
+    torch.cuda.synchronize()
+    return plan
 
 
 def lpmm_profile_begin(max_calls: int) -> None:

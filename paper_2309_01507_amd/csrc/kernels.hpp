@@ -4,7 +4,7 @@
 // row-major flattening; each lane owns 8 consecutive elements, i.e. one 32-bit word of 4-bit codes
 // of each moment, one 128-bit word of bf16 gradient and two 128-bit words of fp32 parameter.
 //
-// One step is two launches, because every v code needs the complete row and column maxima of the
+// One step is two passes, because every v code needs the complete row and column maxima of the
 // updated second moment (rank-1 normalization, paper Sec. 4.2):
 //   pass 1: decompress m, v -> Adam moments (Eq. 1) -> parameter update -> block absmax of m_t,
 //           compress m_t (B128 + signed dynamic-exponent map) -> row/column maxima of v_t into
@@ -12,6 +12,9 @@
 //   pass 2: recompute v_t with the identical operation sequence, compress it against
 //           min(r'_i, c'_j) (Linear map), and let the last workgroup publish r', c' as the new
 //           state and clear the workspace.
+// The bodies are "tile" functions; thin __global__ wrappers run them for one tensor (two launches
+// per step), and the phase kernel runs pass 1 of one set of tensors next to pass 2 of the previous
+// set, so that the arithmetic-heavy pass 2 hides under the memory-bound pass 1.
 #pragma once
 
 #include "device_math.hpp"
@@ -22,28 +25,33 @@ namespace lpmm {
 __device__ float d_byte_decode[512];          // entry b: {T_DE[b & 15], T_DE[b >> 4]}
 __device__ SearchEntry d_search[kBuckets];    // nearest-entry search for the DE map
 
+enum TensorKind : int { kQuantFast = 0, kQuantGeneral = 1, kFp32State = 2 };
+
 struct Tensor4 {
     float* p;               // parameters, fp32 [P]
     const void* g;          // gradient, fp32 or bf16 [P]
-    uint32_t* mq;           // first-moment codes, 8 per word
+    uint32_t* mq;           // first-moment codes, 8 per word   (kFp32State: float* m)
     float* ms;              // first-moment block scales
-    uint32_t* vq;           // second-moment codes
+    uint32_t* vq;           // second-moment codes              (kFp32State: float* v)
     float* r;               // row maxima (state)
     float* c;               // column maxima (state)
     float* r_new;           // workspace: row maxima of v_t (zero between steps)
     float* c_new;           // workspace: column maxima of v_t (zero between steps)
-    unsigned int* counter;  // workspace: finished-workgroup counter of pass 2 (zero between steps)
+    unsigned int* counter;  // workspace: ticket counters of pass 2 (zero between steps)
     int64_t rows, cols, P;
     // geometry of the fast path (cols % 128 == 0)
     int nb;                 // column blocks per row = cols / 128
     int gx, gy;             // a workgroup's 16 groups: gx column blocks x gy row phases
-    int rw;                 // rows per workgroup tile
-    int strips;             // ceil(nb / gx)
-    int n_wg;               // strips * ceil(rows / rw)
+    int rw;                 // rows per workgroup tile; rw * cols < 2^29
+    int strips;             // nb / gx
+    int n_wg;               // workgroups per pass
+    int kind;
+    int pad_;
 };
 
 constexpr int kThreads = 256;
 constexpr int kXcds = 8;
+constexpr int kElemsPerWg32 = kThreads * 16;   // fp32-state path: elements per workgroup
 
 // Workgroups are dealt to the 8 XCDs round-robin by their id.  Remap so that consecutive logical
 // ids -- which touch neighbouring memory -- run on the same XCD and share its L2.
@@ -52,40 +60,41 @@ __device__ __forceinline__ int logical_wg() {
     return (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
 }
 
-__device__ __forceinline__ void load_tables(float2* s_deq, SearchEntry* s_search) {
-    const float2* gd = reinterpret_cast<const float2*>(d_byte_decode);
-    for (int i = threadIdx.x; i < 256; i += kThreads) s_deq[i] = gd[i];
-    const uint2* gs = reinterpret_cast<const uint2*>(d_search);
-    uint2* ss = reinterpret_cast<uint2*>(s_search);
-    for (int i = threadIdx.x; i < kBuckets; i += kThreads) ss[i] = gs[i];
-}
-
-// =====================================================================================================
-// Fast path: cols % 128 == 0, so a block never straddles a row and a group can walk down the rows
-// of one column block with the 8 old and 8 running new column maxima of its lane in registers.
-// The loads of the next row are issued before the current row is computed.
-// =====================================================================================================
-
-struct Geo {            // where this group works
-    int strip, tile, grp, l, gxi, gyi, cb;
-    int64_t row0, row1, col0;
-    bool active;
+struct Lds {
+    float2 deq[256];
+    SearchEntry search[kBuckets];
+    float col[16 * 128];
+    int last;
 };
 
-__device__ __forceinline__ Geo geometry(const Tensor4& a, int wg) {
-    Geo g;
-    g.strip = wg % a.strips;
-    g.tile = wg / a.strips;
-    g.grp = threadIdx.x >> 4;
-    g.l = threadIdx.x & 15;
-    g.gxi = g.grp % a.gx;
-    g.gyi = g.grp / a.gx;
-    g.cb = g.strip * a.gx + g.gxi;
-    g.row0 = int64_t(g.tile) * a.rw;
-    g.row1 = (g.row0 + a.rw < a.rows) ? g.row0 + a.rw : a.rows;
-    g.col0 = int64_t(g.cb) * 128 + g.l * 8;
-    g.active = g.cb < a.nb;
-    return g;
+__device__ __forceinline__ void load_tables(Lds& s) {
+    const float2* gd = reinterpret_cast<const float2*>(d_byte_decode);
+    for (int i = threadIdx.x; i < 256; i += kThreads) s.deq[i] = gd[i];
+    const uint2* gs = reinterpret_cast<const uint2*>(d_search);
+    uint2* ss = reinterpret_cast<uint2*>(s.search);
+    for (int i = threadIdx.x; i < kBuckets; i += kThreads) ss[i] = gs[i];
+    __syncthreads();
+}
+
+// ---- small helpers -----------------------------------------------------------------------------------
+
+// min / max of two floats that are both >= +0, through the integer units (no NaN canonicalization)
+__device__ __forceinline__ float min_nonneg(float a, float b) {
+    const uint32_t x = __float_as_uint(a), y = __float_as_uint(b);
+    return __uint_as_float(x < y ? x : y);
+}
+__device__ __forceinline__ float max_nonneg(float a, float b) {
+    const uint32_t x = __float_as_uint(a), y = __float_as_uint(b);
+    return __uint_as_float(x > y ? x : y);
+}
+
+template <typename T>
+__device__ __forceinline__ T ld(const void* base, uint32_t byte_off) {
+    return *reinterpret_cast<const T*>(reinterpret_cast<const char*>(base) + byte_off);
+}
+template <typename T>
+__device__ __forceinline__ void st(void* base, uint32_t byte_off, T v) {
+    *reinterpret_cast<T*>(reinterpret_cast<char*>(base) + byte_off) = v;
 }
 
 __device__ __forceinline__ void load8(const float* p, float out[8]) {
@@ -99,15 +108,15 @@ template <bool BF16> struct GradRegs;
 template <> struct GradRegs<true> { uint4 w; };
 template <> struct GradRegs<false> { float4 a, b; };
 
+// gradient of a lane's 8 elements; off4 is the byte offset the elements have in an fp32 array
 template <bool BF16>
-__device__ __forceinline__ GradRegs<BF16> load_grad_regs(const void* g, int64_t idx) {
+__device__ __forceinline__ GradRegs<BF16> load_grad_regs(const void* g_tile, uint32_t off4) {
     GradRegs<BF16> r;
     if constexpr (BF16) {
-        r.w = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(g) + idx);
+        r.w = ld<uint4>(g_tile, off4 >> 1);
     } else {
-        const float4* p = reinterpret_cast<const float4*>(reinterpret_cast<const float*>(g) + idx);
-        r.a = p[0];
-        r.b = p[1];
+        r.a = ld<float4>(g_tile, off4);
+        r.b = ld<float4>(g_tile, off4 + 16);
     }
     return r;
 }
@@ -124,14 +133,74 @@ __device__ __forceinline__ void unpack_grad(const GradRegs<BF16>& r, float out[8
     }
 }
 
-// float(code) of a lane's 8 codes: split the word into low and high nibbles, then byte converts
+// float(code) of a lane's 8 codes: split the word into low and high nibbles (kept opaque so that
+// the byte-to-float converts are used), then one convert per element
 __device__ __forceinline__ void codes_to_float(uint32_t w, float qf[8]) {
-    const uint32_t lo = w & 0x0F0F0F0Fu, hi = (w >> 4) & 0x0F0F0F0Fu;
+    uint32_t lo = w & 0x0F0F0F0Fu, hi = (w >> 4) & 0x0F0F0F0Fu;
+    asm("" : "+v"(lo));
+    asm("" : "+v"(hi));
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         qf[2 * k] = float((lo >> (8 * k)) & 255u);
         qf[2 * k + 1] = float((hi >> (8 * k)) & 255u);
     }
+}
+
+// =====================================================================================================
+// Fast path: cols % 128 == 0, so a block never straddles a row and a group can walk down the rows
+// of one column block with the 8 old and 8 running new column maxima of its lane in registers.
+// Addresses are a uniform tile base plus a 32-bit lane offset; the loads of the next row are
+// issued before the current row is computed.
+// =====================================================================================================
+
+struct Geo {            // where this group works
+    int strip, grp, l, gxi, gyi, cb;
+    int64_t row0;
+    int n_rows;         // rows of this tile
+    uint32_t col0;
+    bool active;
+};
+
+__device__ __forceinline__ Geo geometry(const Tensor4& a, int wg) {
+    Geo g;
+    g.strip = wg % a.strips;
+    const int tile = wg / a.strips;
+    g.grp = threadIdx.x >> 4;
+    g.l = threadIdx.x & 15;
+    g.gxi = g.grp % a.gx;
+    g.gyi = g.grp / a.gx;
+    g.cb = g.strip * a.gx + g.gxi;
+    g.row0 = int64_t(tile) * a.rw;
+    const int64_t left = a.rows - g.row0;
+    g.n_rows = left < a.rw ? int(left) : a.rw;
+    g.col0 = uint32_t(g.cb) * 128u + uint32_t(g.l) * 8u;
+    g.active = g.cb < a.nb;
+    return g;
+}
+
+// uniform base pointers of a tile (row0 folded in), so that lane offsets fit 32 bits
+struct TileBase {
+    float* p;
+    const char* g;
+    uint32_t* mq;
+    uint32_t* vq;
+    float* ms;
+    const float* r;
+    float* r_new;
+};
+
+template <bool BF16>
+__device__ __forceinline__ TileBase tile_base(const Tensor4& a, int64_t row0) {
+    TileBase b;
+    const int64_t e = row0 * a.cols;
+    b.p = a.p + e;
+    b.g = reinterpret_cast<const char*>(a.g) + e * (BF16 ? 2 : 4);
+    b.mq = a.mq + (e >> 3);
+    b.vq = a.vq + (e >> 3);
+    b.ms = a.ms + row0 * a.nb;
+    b.r = a.r + row0;
+    b.r_new = a.r_new + row0;
+    return b;
 }
 
 template <bool BF16>
@@ -142,33 +211,25 @@ struct Row1 {                      // everything pass 1 reads for one row of one
     float s_old, r_old;
 };
 
+// il = row index inside the tile
 template <bool BF16>
-__device__ __forceinline__ Row1<BF16> load_row1(const Tensor4& a, const Geo& g, int64_t i) {
+__device__ __forceinline__ Row1<BF16> load_row1(const TileBase& b, const Tensor4& a, const Geo& g, int il) {
     Row1<BF16> r;
-    const int64_t e0 = i * a.cols + g.col0;
-    const float4* pp = reinterpret_cast<const float4*>(a.p + e0);
-    r.p0 = pp[0];
-    r.p1 = pp[1];
-    r.g = load_grad_regs<BF16>(a.g, e0);
-    r.mq = a.mq[e0 >> 3];
-    r.vq = a.vq[e0 >> 3];
-    r.s_old = a.ms[i * a.nb + g.cb];
-    r.r_old = a.r[i];
+    const uint32_t off4 = (uint32_t(il) * uint32_t(a.cols) + g.col0) * 4u;   // byte offset, fp32 array
+    r.p0 = ld<float4>(b.p, off4);
+    r.p1 = ld<float4>(b.p, off4 + 16);
+    r.g = load_grad_regs<BF16>(b.g, off4);
+    r.mq = ld<uint32_t>(b.mq, off4 >> 3);
+    r.vq = ld<uint32_t>(b.vq, off4 >> 3);
+    r.s_old = ld<float>(b.ms, (uint32_t(il) * uint32_t(a.nb) + uint32_t(g.cb)) * 4u);
+    r.r_old = ld<float>(b.r, uint32_t(il) * 4u);
     return r;
 }
 
 template <bool BF16>
-__global__ __launch_bounds__(kThreads) void pass1_fast(const Tensor4 a, const Hyper h) {
-    __shared__ float2 s_deq[256];
-    __shared__ SearchEntry s_search[kBuckets];
-    __shared__ float s_col[16 * 128];
-
-    const int wg = logical_wg();
-    if (wg >= a.n_wg) return;
-    load_tables(s_deq, s_search);
-    __syncthreads();
-
+__device__ __forceinline__ void pass1_fast_tile(const Tensor4& a, const Hyper& h, int wg, Lds& s) {
     const Geo geo = geometry(a, wg);
+    const TileBase tb = tile_base<BF16>(a, geo.row0);
     float cmax[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) cmax[e] = 0.0f;
@@ -182,23 +243,21 @@ __global__ __launch_bounds__(kThreads) void pass1_fast(const Tensor4 a, const Hy
             cols_tame = cols_tame && scale_is_tame(cold[e]);
             cold16[e] = cold[e] * 0.0625f;
         }
-        const int64_t stride = a.gy;
-        int64_t i = geo.row0 + geo.gyi;
+        int il = geo.gyi;
         Row1<BF16> cur;
-        if (i < geo.row1) cur = load_row1<BF16>(a, geo, i);
-        while (i < geo.row1) {
-            const int64_t inext = i + stride;
+        if (il < geo.n_rows) cur = load_row1<BF16>(tb, a, geo, il);
+        while (il < geo.n_rows) {
+            const int inext = il + a.gy;
             Row1<BF16> nxt;
-            if (inext < geo.row1) nxt = load_row1<BF16>(a, geo, inext);
+            if (inext < geo.n_rows) nxt = load_row1<BF16>(tb, a, geo, inext);
 
-            const int64_t e0 = i * a.cols + geo.col0;
             float w[8] = {cur.p0.x, cur.p0.y, cur.p0.z, cur.p0.w, cur.p1.x, cur.p1.y, cur.p1.z, cur.p1.w};
             float g[8];
             unpack_grad<BF16>(cur.g, g);
             float mt[8], vt[8], amax = 0.0f, rmax = 0.0f;
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                const float2 t = s_deq[(cur.mq >> (8 * k)) & 255u];
+                const float2 t = s.deq[(cur.mq >> (8 * k)) & 255u];
                 mt[2 * k] = t.x * cur.s_old;          // decompress: T_DE[code] * block scale
                 mt[2 * k + 1] = t.y * cur.s_old;
             }
@@ -209,7 +268,7 @@ __global__ __launch_bounds__(kThreads) void pass1_fast(const Tensor4 a, const Hy
                 codes_to_float(cur.vq, qf);
                 const float r16 = cur.r_old * 0.0625f;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) vt[e] = dequant_v16(qf[e], fminf(r16, cold16[e]));
+                for (int e = 0; e < 8; ++e) vt[e] = dequant_v16(qf[e], min_nonneg(r16, cold16[e]));
             } else {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) vt[e] = dequant_v((cur.vq >> (4 * e)) & 15u, fminf(cur.r_old, cold[e]));
@@ -233,8 +292,8 @@ __global__ __launch_bounds__(kThreads) void pass1_fast(const Tensor4 a, const Hy
 #pragma unroll
                 for (int e = 0; e < 8; e += 2) {
                     float sa, sb;
-                    mq_new |= quant_m_code_fast(s_search, mt[e], inv_s, sa) << (4 * e);
-                    mq_new |= quant_m_code_fast(s_search, mt[e + 1], inv_s, sb) << (4 * e + 4);
+                    mq_new |= quant_m_code_fast(s.search, mt[e], inv_s, sa) << (4 * e);
+                    mq_new |= quant_m_code_fast(s.search, mt[e + 1], inv_s, sb) << (4 * e + 4);
                     slack = fminf(fminf(slack, sa), sb);
                 }
             } else {
@@ -243,56 +302,58 @@ __global__ __launch_bounds__(kThreads) void pass1_fast(const Tensor4 a, const Hy
             if (__builtin_expect(__ballot(slack < 0.0f) != 0, 0)) {
                 mq_new = 0;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) mq_new |= quant_m_code(s_search, mt[e], s_new) << (4 * e);
+                for (int e = 0; e < 8; ++e) mq_new |= quant_m_code(s.search, mt[e], s_new) << (4 * e);
             }
 
-            float4* pp = reinterpret_cast<float4*>(a.p + e0);
-            pp[0] = make_float4(w[0], w[1], w[2], w[3]);
-            pp[1] = make_float4(w[4], w[5], w[6], w[7]);
-            a.mq[e0 >> 3] = mq_new;
+            const uint32_t off4 = (uint32_t(il) * uint32_t(a.cols) + geo.col0) * 4u;
+            st<float4>(tb.p, off4, make_float4(w[0], w[1], w[2], w[3]));
+            st<float4>(tb.p, off4 + 16, make_float4(w[4], w[5], w[6], w[7]));
+            st<uint32_t>(tb.mq, off4 >> 3, mq_new);
             if (geo.l == 0) {
-                a.ms[i * a.nb + geo.cb] = s_new;
-                if (rmax > 0.0f) atomic_max_nonneg(a.r_new + i, rmax);
+                st<float>(tb.ms, (uint32_t(il) * uint32_t(a.nb) + uint32_t(geo.cb)) * 4u, s_new);
+                if (rmax > 0.0f) atomic_max_nonneg(tb.r_new + il, rmax);
             }
             cur = nxt;
-            i = inext;
+            il = inext;
         }
     }
 
     // column maxima: combine the gy groups that share a column block, then one atomic per column
 #pragma unroll
-    for (int e = 0; e < 8; ++e) s_col[geo.grp * 128 + geo.l * 8 + e] = cmax[e];
+    for (int e = 0; e < 8; ++e) s.col[geo.grp * 128 + geo.l * 8 + e] = cmax[e];
     __syncthreads();
     for (int t = threadIdx.x; t < a.gx * 128; t += kThreads) {
         const int gi = t >> 7;
         float m = 0.0f;
-        for (int y = 0; y < a.gy; ++y) m = fmaxf(m, s_col[((y * a.gx + gi) << 7) + (t & 127)]);
+        for (int y = 0; y < a.gy; ++y) m = fmaxf(m, s.col[((y * a.gx + gi) << 7) + (t & 127)]);
         const int cbi = geo.strip * a.gx + gi;
         if (cbi < a.nb && m > 0.0f) atomic_max_nonneg(a.c_new + int64_t(cbi) * 128 + (t & 127), m);
     }
 }
 
-// The last workgroup of pass 2 to finish makes r', c' the state and clears the workspace.  Every
-// other workgroup has read the old r, c before it took its ticket, so overwriting them is safe.
-// Tickets are taken in two levels (kTicketLanes first-level counters, one cache line apart, then
-// one top counter) so that thousands of workgroups do not queue up on a single address.
+// The last workgroup of a tensor's pass 2 to finish makes r', c' the state and clears the
+// workspace.  Every other workgroup has read the old r, c before it took its ticket, so
+// overwriting them is safe.  Tickets are taken in two levels (kTicketLanes first-level counters, one
+// cache line apart, then one top counter) so that thousands of workgroups do not queue up on a
+// single address.  `me` / `participants`: this workgroup's index among, and the number of,
+// workgroups that call this for the tensor.
 constexpr int kTicketLanes = 32;
-constexpr int kTicketStride = 32;   // in 32-bit words: 128 bytes
+constexpr int kTicketStride = 32;                                  // in 32-bit words: 128 bytes
+constexpr int kCounterWords = (1 + kTicketLanes) * kTicketStride;  // per tensor
 
-__device__ __forceinline__ void publish_if_last(const Tensor4& a) {
-    __shared__ int s_last;
+__device__ __forceinline__ void publish_if_last(const Tensor4& a, unsigned int me, unsigned int participants,
+                                                int& s_last) {
     __syncthreads();
     if (threadIdx.x == 0) {
         // No fence: the ticket orders nothing but "this workgroup's loads of r, c have returned",
         // which holds once its waves have computed their codes and reached the barrier above.  (An
         // agent-scope release here would write back the XCD's whole L2 once per workgroup.)
-        const unsigned int n_wg = gridDim.x;
-        const unsigned int lane = blockIdx.x % kTicketLanes;
-        const unsigned int in_lane = n_wg / kTicketLanes + (lane < n_wg % kTicketLanes ? 1u : 0u);
+        const unsigned int lane = me % kTicketLanes;
+        const unsigned int in_lane = participants / kTicketLanes + (lane < participants % kTicketLanes ? 1u : 0u);
         int last = 0;
         if (atomicAdd(a.counter + (1 + lane) * kTicketStride, 1u) == in_lane - 1) {
             a.counter[(1 + lane) * kTicketStride] = 0u;      // this lane is complete: reset it
-            const unsigned int lanes_used = n_wg < kTicketLanes ? n_wg : kTicketLanes;
+            const unsigned int lanes_used = participants < kTicketLanes ? participants : kTicketLanes;
             last = atomicAdd(a.counter, 1u) == lanes_used - 1;
         }
         s_last = last;
@@ -312,13 +373,13 @@ struct Row2 {                      // everything pass 2 reads for one row of one
 };
 
 template <bool BF16>
-__device__ __forceinline__ Row2<BF16> load_row2(const Tensor4& a, const Geo& g, int64_t i) {
+__device__ __forceinline__ Row2<BF16> load_row2(const TileBase& b, const Tensor4& a, const Geo& g, int il) {
     Row2<BF16> r;
-    const int64_t e0 = i * a.cols + g.col0;
-    r.g = load_grad_regs<BF16>(a.g, e0);
-    r.vq = a.vq[e0 >> 3];
-    r.r_old = a.r[i];
-    r.r_new = a.r_new[i];
+    const uint32_t off4 = (uint32_t(il) * uint32_t(a.cols) + g.col0) * 4u;
+    r.g = load_grad_regs<BF16>(b.g, off4);
+    r.vq = ld<uint32_t>(b.vq, off4 >> 3);
+    r.r_old = ld<float>(b.r, uint32_t(il) * 4u);
+    r.r_new = ld<float>(b.r_new, uint32_t(il) * 4u);
     return r;
 }
 
@@ -335,14 +396,14 @@ __device__ __forceinline__ uint32_t pass2_row(const Hyper& h, const Row2<BF16>& 
         codes_to_float(row.vq, qf);
         const float r16 = row.r_old * 0.0625f;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) vt[e] = moment_v(h, dequant_v16(qf[e], fminf(r16, cold16[e])), g[e]);
+        for (int e = 0; e < 8; ++e) vt[e] = moment_v(h, dequant_v16(qf[e], min_nonneg(r16, cold16[e])), g[e]);
         const float inv_r = approx_inv(row.r_new);
         // even elements collect in the bytes of `lo`, odd ones in `hi`; word = lo | hi << 4
         uint32_t lo = 0, hi = 0;
         float fmin_ = 0.5f, fmax_ = 0.5f, fa, fb;
 #define LPMM_V2(K)                                                                                        \
-        lo = quant_v_code_fast<K>(vt[2 * K], fmaxf(inv_r, inv_cnew[2 * K]), lo, fa);                      \
-        hi = quant_v_code_fast<K>(vt[2 * K + 1], fmaxf(inv_r, inv_cnew[2 * K + 1]), hi, fb);              \
+        lo = quant_v_code_fast<K>(vt[2 * K], max_nonneg(inv_r, inv_cnew[2 * K]), lo, fa);                 \
+        hi = quant_v_code_fast<K>(vt[2 * K + 1], max_nonneg(inv_r, inv_cnew[2 * K + 1]), hi, fb);         \
         fmin_ = fminf(fminf(fmin_, fa), fb);                                                              \
         fmax_ = fmaxf(fmaxf(fmax_, fa), fb);
         LPMM_V2(0) LPMM_V2(1) LPMM_V2(2) LPMM_V2(3)
@@ -361,43 +422,40 @@ __device__ __forceinline__ uint32_t pass2_row(const Hyper& h, const Row2<BF16>& 
 }
 
 template <bool BF16>
-__global__ __launch_bounds__(kThreads) void pass2_fast(const Tensor4 a, const Hyper h) {
-    const int wg = logical_wg();
-    if (wg < a.n_wg) {
-        const Geo geo = geometry(a, wg);
-        if (geo.active) {
-            float cold[8], cold16[8], cnew[8], inv_cnew[8];
-            load8(a.c + geo.col0, cold);
-            load8(a.c_new + geo.col0, cnew);
-            bool cols_tame = true;
+__device__ __forceinline__ void pass2_fast_tile(const Tensor4& a, const Hyper& h, int wg) {
+    const Geo geo = geometry(a, wg);
+    if (!geo.active) return;
+    const TileBase tb = tile_base<BF16>(a, geo.row0);
+    float cold[8], cold16[8], cnew[8], inv_cnew[8];
+    load8(a.c + geo.col0, cold);
+    load8(a.c_new + geo.col0, cnew);
+    bool cols_tame = true;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                cols_tame = cols_tame && scale_is_tame(cold[e]) && scale_is_tame(cnew[e]);
-                cold16[e] = cold[e] * 0.0625f;
-                inv_cnew[e] = approx_inv(cnew[e]);
-            }
-            // two rows per stage, the next stage's loads in flight while this one is computed
-            const int64_t stride = a.gy;
-            int64_t i = geo.row0 + geo.gyi;
-            Row2<BF16> c0, c1;
-            if (i < geo.row1) c0 = load_row2<BF16>(a, geo, i);
-            if (i + stride < geo.row1) c1 = load_row2<BF16>(a, geo, i + stride);
-            while (i < geo.row1) {
-                const int64_t j0 = i + 2 * stride, j1 = i + 3 * stride;
-                Row2<BF16> n0, n1;
-                if (j0 < geo.row1) n0 = load_row2<BF16>(a, geo, j0);
-                if (j1 < geo.row1) n1 = load_row2<BF16>(a, geo, j1);
-                a.vq[(i * a.cols + geo.col0) >> 3] = pass2_row<BF16>(h, c0, cold, cold16, cnew, inv_cnew, cols_tame);
-                if (i + stride < geo.row1)
-                    a.vq[((i + stride) * a.cols + geo.col0) >> 3] =
-                        pass2_row<BF16>(h, c1, cold, cold16, cnew, inv_cnew, cols_tame);
-                c0 = n0;
-                c1 = n1;
-                i = j0;
-            }
-        }
+    for (int e = 0; e < 8; ++e) {
+        cols_tame = cols_tame && scale_is_tame(cold[e]) && scale_is_tame(cnew[e]);
+        cold16[e] = cold[e] * 0.0625f;
+        inv_cnew[e] = approx_inv(cnew[e]);
     }
-    publish_if_last(a);
+    // two rows per stage, the next stage's loads in flight while this one is computed
+    const int stride = a.gy;
+    int il = geo.gyi;
+    Row2<BF16> c0, c1;
+    if (il < geo.n_rows) c0 = load_row2<BF16>(tb, a, geo, il);
+    if (il + stride < geo.n_rows) c1 = load_row2<BF16>(tb, a, geo, il + stride);
+    while (il < geo.n_rows) {
+        const int j0 = il + 2 * stride, j1 = il + 3 * stride;
+        Row2<BF16> n0, n1;
+        if (j0 < geo.n_rows) n0 = load_row2<BF16>(tb, a, geo, j0);
+        if (j1 < geo.n_rows) n1 = load_row2<BF16>(tb, a, geo, j1);
+        const uint32_t off = (uint32_t(il) * uint32_t(a.cols) + geo.col0) >> 1;     // byte offset of the code word
+        st<uint32_t>(tb.vq, off, pass2_row<BF16>(h, c0, cold, cold16, cnew, inv_cnew, cols_tame));
+        if (il + stride < geo.n_rows)
+            st<uint32_t>(tb.vq, off + ((uint32_t(stride) * uint32_t(a.cols)) >> 1),
+                         pass2_row<BF16>(h, c1, cold, cold16, cnew, inv_cnew, cols_tame));
+        c0 = n0;
+        c1 = n1;
+        il = j0;
+    }
 }
 
 // =====================================================================================================
@@ -419,13 +477,13 @@ struct LaneIo {
     int64_t j;      // column of the first element
 };
 
-__device__ __forceinline__ LaneIo lane_io(const Tensor4& a, int64_t lane_global) {
+__device__ __forceinline__ LaneIo lane_io(int64_t P, int64_t cols, int64_t lane_global) {
     LaneIo io;
     io.base = lane_global * 8;
-    const int64_t left = a.P - io.base;
+    const int64_t left = P - io.base;
     io.nv = left >= 8 ? 8 : (left > 0 ? int(left) : 0);
-    io.i = io.nv ? io.base / a.cols : 0;
-    io.j = io.nv ? io.base - io.i * a.cols : 0;
+    io.i = io.nv ? io.base / cols : 0;
+    io.j = io.nv ? io.base - io.i * cols : 0;
     return io;
 }
 
@@ -444,23 +502,15 @@ __device__ __forceinline__ void store_codes(uint32_t* q, const LaneIo& io, uint3
 }
 
 template <bool BF16>
-__global__ __launch_bounds__(kThreads) void pass1_general(const Tensor4 a, const Hyper h) {
-    __shared__ float2 s_deq[256];
-    __shared__ SearchEntry s_search[kBuckets];
-    load_tables(s_deq, s_search);
-    __syncthreads();
-
-    const int64_t t = int64_t(blockIdx.x) * kThreads + threadIdx.x;
+__device__ __forceinline__ void pass1_general_tile(const Tensor4& a, const Hyper& h, int wg, Lds& s) {
+    const int64_t t = int64_t(wg) * kThreads + threadIdx.x;
     const int64_t block = t >> 4;                       // uniform over the group
     if (block * 128 >= a.P) return;                     // whole group past the end
-    const LaneIo io = lane_io(a, t);
+    const LaneIo io = lane_io(a.P, a.cols, t);
 
     float w[8], g[8];
     if (io.nv == 8) {
-        const float4* pp = reinterpret_cast<const float4*>(a.p + io.base);
-        const float4 p0 = pp[0], p1 = pp[1];
-        w[0] = p0.x; w[1] = p0.y; w[2] = p0.z; w[3] = p0.w;
-        w[4] = p1.x; w[5] = p1.y; w[6] = p1.z; w[7] = p1.w;
+        load8(a.p + io.base, w);
         load_grad8<BF16>(a.g, io.base, g);
     } else {
 #pragma unroll
@@ -480,7 +530,7 @@ __global__ __launch_bounds__(kThreads) void pass1_general(const Tensor4 a, const
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         if (e < io.nv) {
-            const float2 tt = s_deq[(mq >> (8 * (e >> 1))) & 255u];
+            const float2 tt = s.deq[(mq >> (8 * (e >> 1))) & 255u];
             const float m_prev = ((e & 1) ? tt.y : tt.x) * s_old;
             const float v_prev = dequant_v((vq >> (4 * e)) & 15u, fminf(a.r[i], a.c[j]));
             mt[e] = moment_m(h, m_prev, g[e]);
@@ -501,7 +551,7 @@ __global__ __launch_bounds__(kThreads) void pass1_general(const Tensor4 a, const
     uint32_t mq_new = 0;
 #pragma unroll
     for (int e = 0; e < 8; ++e)
-        if (e < io.nv) mq_new |= quant_m_code(s_search, mt[e], s_new) << (4 * e);
+        if (e < io.nv) mq_new |= quant_m_code(s.search, mt[e], s_new) << (4 * e);
 
     if (io.nv == 8) {
         float4* pp = reinterpret_cast<float4*>(a.p + io.base);
@@ -517,49 +567,155 @@ __global__ __launch_bounds__(kThreads) void pass1_general(const Tensor4 a, const
 }
 
 template <bool BF16>
-__global__ __launch_bounds__(kThreads) void pass2_general(const Tensor4 a, const Hyper h) {
-    const int64_t t = int64_t(blockIdx.x) * kThreads + threadIdx.x;
-    const LaneIo io = lane_io(a, t);
-    if (io.nv) {
-        float g[8];
-        if (io.nv == 8) {
-            load_grad8<BF16>(a.g, io.base, g);
-        } else {
+__device__ __forceinline__ void pass2_general_tile(const Tensor4& a, const Hyper& h, int wg) {
+    const int64_t t = int64_t(wg) * kThreads + threadIdx.x;
+    const LaneIo io = lane_io(a.P, a.cols, t);
+    if (!io.nv) return;
+    float g[8];
+    if (io.nv == 8) {
+        load_grad8<BF16>(a.g, io.base, g);
+    } else {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) g[e] = e < io.nv ? load_grad1<BF16>(a.g, io.base + e) : 0.0f;
-        }
-        const uint32_t vq = load_codes(a.vq, io);
-        uint32_t vq_new = 0;
-        int64_t i = io.i, j = io.j;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            if (e < io.nv) {
-                const float v_prev = dequant_v((vq >> (4 * e)) & 15u, fminf(a.r[i], a.c[j]));
-                const float vt = moment_v(h, v_prev, g[e]);
-                vq_new |= quant_v_code(vt, fminf(a.r_new[i], a.c_new[j])) << (4 * e);
-                if (++j == a.cols) { j = 0; ++i; }
-            }
-        }
-        store_codes(a.vq, io, vq_new);
+        for (int e = 0; e < 8; ++e) g[e] = e < io.nv ? load_grad1<BF16>(a.g, io.base + e) : 0.0f;
     }
-    publish_if_last(a);
+    const uint32_t vq = load_codes(a.vq, io);
+    uint32_t vq_new = 0;
+    int64_t i = io.i, j = io.j;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        if (e < io.nv) {
+            const float v_prev = dequant_v((vq >> (4 * e)) & 15u, fminf(a.r[i], a.c[j]));
+            const float vt = moment_v(h, v_prev, g[e]);
+            vq_new |= quant_v_code(vt, fminf(a.r_new[i], a.c_new[j])) << (4 * e);
+            if (++j == a.cols) { j = 0; ++i; }
+        }
+    }
+    store_codes(a.vq, io, vq_new);
 }
 
 // =====================================================================================================
 // Uncompressed fp32 states (tensors that are not quantized): Alg. 3 with identity compression.
+// One workgroup handles kElemsPerWg32 consecutive elements.
 // =====================================================================================================
+
+template <bool BF16>
+__device__ __forceinline__ void adamw32_tile(float* p, const void* g, float* m, float* v, int64_t n,
+                                             const Hyper& h, int wg) {
+    const int64_t base = int64_t(wg) * kElemsPerWg32;
+#pragma unroll 4
+    for (int k = 0; k < kElemsPerWg32 / kThreads; ++k) {
+        const int64_t idx = base + int64_t(k) * kThreads + threadIdx.x;
+        if (idx < n) {
+            const float gi = load_grad1<BF16>(g, idx);
+            const float mt = moment_m(h, m[idx], gi);
+            const float vt = moment_v(h, v[idx], gi);
+            m[idx] = mt;
+            v[idx] = vt;
+            p[idx] = param_update(h, p[idx], mt, vt);
+        }
+    }
+}
+
+// =====================================================================================================
+// Kernels for one tensor: two launches per step.
+// =====================================================================================================
+
+template <bool BF16>
+__global__ __launch_bounds__(kThreads) void pass1_fast(const Tensor4 a, const Hyper h) {
+    __shared__ Lds s;
+    const int wg = logical_wg();
+    if (wg >= a.n_wg) return;
+    load_tables(s);
+    pass1_fast_tile<BF16>(a, h, wg, s);
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(kThreads) void pass2_fast(const Tensor4 a, const Hyper h) {
+    __shared__ int s_last;
+    const int wg = logical_wg();
+    if (wg < a.n_wg) pass2_fast_tile<BF16>(a, h, wg);
+    publish_if_last(a, blockIdx.x, gridDim.x, s_last);
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(kThreads) void pass1_general(const Tensor4 a, const Hyper h) {
+    __shared__ Lds s;
+    load_tables(s);
+    pass1_general_tile<BF16>(a, h, blockIdx.x, s);
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(kThreads) void pass2_general(const Tensor4 a, const Hyper h) {
+    __shared__ int s_last;
+    pass2_general_tile<BF16>(a, h, blockIdx.x);
+    publish_if_last(a, blockIdx.x, gridDim.x, s_last);
+}
 
 template <bool BF16>
 __global__ __launch_bounds__(kThreads) void adamw32_kernel(float* p, const void* g, float* m, float* v,
                                                            int64_t n, const Hyper h) {
-    const int64_t stride = int64_t(gridDim.x) * kThreads;
-    for (int64_t idx = int64_t(blockIdx.x) * kThreads + threadIdx.x; idx < n; idx += stride) {
-        const float gi = load_grad1<BF16>(g, idx);
-        const float mt = moment_m(h, m[idx], gi);
-        const float vt = moment_v(h, v[idx], gi);
-        m[idx] = mt;
-        v[idx] = vt;
-        p[idx] = param_update(h, p[idx], mt, vt);
+    adamw32_tile<BF16>(p, g, m, v, n, h, blockIdx.x);
+}
+
+// =====================================================================================================
+// Phase kernel of the multi-tensor step.  A phase runs the "A" work of one set of tensors (pass 1
+// of quantized tensors, the whole update of fp32-state tensors) together with the "B" work of the
+// previous set (pass 2).  The two kinds are interleaved in proportion, so that at any time each CU
+// holds memory-bound pass-1 workgroups next to arithmetic-bound pass-2 workgroups.
+// =====================================================================================================
+
+struct Segment {        // a run of workgroups that work on one tensor
+    int wg_begin;       // first workgroup of the run, in its kind's numbering
+    int tensor;         // index into the tensor table
+};
+
+struct Phase {
+    const Tensor4* tensors;
+    const Segment* seg_a;   // n_seg_a entries
+    const Segment* seg_b;   // n_seg_b entries
+    int n_seg_a, n_seg_b;
+    int n_a, n_b;           // workgroups of each kind
+};
+
+__device__ __forceinline__ int find_segment(const Segment* seg, int n_seg, int wg) {
+    int lo = 0, hi = n_seg - 1;
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) >> 1;
+        if (seg[mid].wg_begin <= wg) lo = mid; else hi = mid - 1;
+    }
+    return lo;
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(kThreads) void phase_kernel(const Phase ph, const Hyper h) {
+    __shared__ Lds s;
+    const int x = logical_wg();
+    const int n = ph.n_a + ph.n_b;
+    if (x >= n) return;
+    // B workgroups sit at the positions where floor(x * n_b / n) steps up
+    const int b_before = int((int64_t(x) * ph.n_b) / n);
+    const int b_after = int((int64_t(x + 1) * ph.n_b) / n);
+    if (b_after > b_before) {
+        const int sgi = find_segment(ph.seg_b, ph.n_seg_b, b_before);
+        const Segment sg = ph.seg_b[sgi];
+        const Tensor4 a = ph.tensors[sg.tensor];
+        const int wg = b_before - sg.wg_begin;
+        if (a.kind == kQuantFast) pass2_fast_tile<BF16>(a, h, wg);
+        else pass2_general_tile<BF16>(a, h, wg);
+        publish_if_last(a, wg, a.n_wg, s.last);
+    } else {
+        const int xa = x - b_before;
+        const int sgi = find_segment(ph.seg_a, ph.n_seg_a, xa);
+        const Segment sg = ph.seg_a[sgi];
+        const Tensor4 a = ph.tensors[sg.tensor];
+        const int wg = xa - sg.wg_begin;
+        if (a.kind == kFp32State) {
+            adamw32_tile<BF16>(a.p, a.g, reinterpret_cast<float*>(a.mq), reinterpret_cast<float*>(a.vq), a.P, h, wg);
+        } else {
+            load_tables(s);
+            if (a.kind == kQuantFast) pass1_fast_tile<BF16>(a, h, wg, s);
+            else pass1_general_tile<BF16>(a, h, wg, s);
+        }
     }
 }
 
@@ -577,16 +733,9 @@ struct QuantArgs {
     int64_t rows, cols, P;
 };
 
-__device__ __forceinline__ Tensor4 as_tensor(const QuantArgs& q) {
-    Tensor4 a{};
-    a.rows = q.rows; a.cols = q.cols; a.P = q.P;
-    return a;
-}
-
 __global__ __launch_bounds__(kThreads) void dequant_m_kernel(const QuantArgs q) {
-    const Tensor4 a = as_tensor(q);
     const int64_t t = int64_t(blockIdx.x) * kThreads + threadIdx.x;
-    const LaneIo io = lane_io(a, t);
+    const LaneIo io = lane_io(q.P, q.cols, t);
     if (!io.nv) return;
     const uint32_t w = load_codes(q.q_in, io);
     const float s = q.sa[t >> 4];
@@ -595,9 +744,8 @@ __global__ __launch_bounds__(kThreads) void dequant_m_kernel(const QuantArgs q) 
 }
 
 __global__ __launch_bounds__(kThreads) void dequant_v_kernel(const QuantArgs q) {
-    const Tensor4 a = as_tensor(q);
     const int64_t t = int64_t(blockIdx.x) * kThreads + threadIdx.x;
-    const LaneIo io = lane_io(a, t);
+    const LaneIo io = lane_io(q.P, q.cols, t);
     if (!io.nv) return;
     const uint32_t w = load_codes(q.q_in, io);
     int64_t i = io.i, j = io.j;
@@ -608,34 +756,30 @@ __global__ __launch_bounds__(kThreads) void dequant_v_kernel(const QuantArgs q) 
 }
 
 __global__ __launch_bounds__(kThreads) void quant_m_kernel(const QuantArgs q) {
-    __shared__ float2 s_deq[256];
-    __shared__ SearchEntry s_search[kBuckets];
-    load_tables(s_deq, s_search);
-    __syncthreads();
-    const Tensor4 a = as_tensor(q);
+    __shared__ Lds s;
+    load_tables(s);
     const int64_t t = int64_t(blockIdx.x) * kThreads + threadIdx.x;
     if ((t >> 4) * 128 >= q.P) return;
-    const LaneIo io = lane_io(a, t);
+    const LaneIo io = lane_io(q.P, q.cols, t);
     float x[8], amax = 0.0f;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         x[e] = e < io.nv ? q.x_in[io.base + e] : 0.0f;
         amax = fmaxf(amax, fabsf(x[e]));
     }
-    const float s = row16_allmax(amax);
+    const float sc = row16_allmax(amax);
     uint32_t w = 0;
 #pragma unroll
     for (int e = 0; e < 8; ++e)
-        if (e < io.nv) w |= quant_m_code(s_search, x[e], s) << (4 * e);
+        if (e < io.nv) w |= quant_m_code(s.search, x[e], sc) << (4 * e);
     if (io.nv) store_codes(q.q_out, io, w);
-    if ((threadIdx.x & 15) == 0) q.sa[t >> 4] = s;
+    if ((threadIdx.x & 15) == 0) q.sa[t >> 4] = sc;
 }
 
 // second moment, stage 1: row / column maxima into sa / sb (which must be zero on entry)
 __global__ __launch_bounds__(kThreads) void quant_v_max_kernel(const QuantArgs q) {
-    const Tensor4 a = as_tensor(q);
     const int64_t t = int64_t(blockIdx.x) * kThreads + threadIdx.x;
-    const LaneIo io = lane_io(a, t);
+    const LaneIo io = lane_io(q.P, q.cols, t);
     int64_t i = io.i, j = io.j;
     for (int e = 0; e < io.nv; ++e) {
         const float x = q.x_in[io.base + e];
@@ -647,9 +791,8 @@ __global__ __launch_bounds__(kThreads) void quant_v_max_kernel(const QuantArgs q
 
 // second moment, stage 2: codes against min(r_i, c_j)
 __global__ __launch_bounds__(kThreads) void quant_v_code_kernel(const QuantArgs q) {
-    const Tensor4 a = as_tensor(q);
     const int64_t t = int64_t(blockIdx.x) * kThreads + threadIdx.x;
-    const LaneIo io = lane_io(a, t);
+    const LaneIo io = lane_io(q.P, q.cols, t);
     if (!io.nv) return;
     uint32_t w = 0;
     int64_t i = io.i, j = io.j;

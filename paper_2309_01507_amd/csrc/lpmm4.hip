@@ -6,7 +6,9 @@
 
 #include <cmath>
 #include <cstdlib>
+#include <memory>
 #include <mutex>
+#include <unordered_map>
 #include <vector>
 
 #include "../../include/lpmm4.h"
@@ -17,6 +19,7 @@ namespace {
 using namespace lpmm;
 
 constexpr int kMaxDevices = 16;
+static_assert(kCounterWords * 4 <= 8192, "counter block");
 constexpr size_t kCounterBytes = 8192;  // tail of the workspace: ticket counters of pass 2, one cache line apart
 
 struct DeviceCtx {
@@ -110,28 +113,39 @@ int pad8(int64_t n) { return int(round_up(n, kXcds)); }
 
 // Geometry of the fast path.  gx column blocks share a workgroup (so that one workgroup touches
 // whole 128-byte lines of codes and runs of block scales), gy = 16/gx groups walk interleaved
-// rows of the same column blocks and combine their column maxima in LDS.
-void fast_geometry(Tensor4* a, int n_cu) {
+// rows of the same column blocks and combine their column maxima in LDS.  rw_hint > 0 fixes the
+// rows per workgroup; otherwise they are chosen so that the tensor alone fills the chip.
+void fast_geometry(Tensor4* a, int n_cu, int64_t rw_hint) {
     a->nb = int(a->cols / LPMM_BLOCK);
     int gx = env_int("LPMM_GX", 4);
+    if (gx < 1 || gx > 16 || (gx & (gx - 1))) gx = 4;
     while (gx > 1 && (a->nb % gx) != 0) gx >>= 1;
-    if (gx < 1 || gx > 16 || (gx & (gx - 1))) gx = 1;
     a->gx = gx;
     a->gy = 16 / gx;
     a->strips = a->nb / gx;
-    // rows per workgroup: enough workgroups to fill the chip several times, and each group walks
-    // at least a few rows so that the column atomics are amortized
-    const int64_t target_wg = int64_t(n_cu) * env_int("LPMM_WG_PER_CU", 8);
     int64_t rw = env_int("LPMM_RW", 0);
+    if (rw <= 0) rw = rw_hint;
     if (rw <= 0) {
+        // enough workgroups to fill the chip several times, and each group walks at least a few
+        // rows so that the column atomics and the table load are amortized
+        const int64_t target_wg = int64_t(n_cu) * env_int("LPMM_WG_PER_CU", 8);
         rw = (a->rows * a->strips + target_wg - 1) / target_wg;
         const int64_t min_rw = int64_t(a->gy) * 4;
         if (rw < min_rw) rw = min_rw;
     }
+    const int64_t cap = (int64_t(1) << 29) / a->cols;     // lane offsets inside a tile stay below 2^31 bytes
+    if (rw > cap) rw = cap;
     rw = round_up(rw, a->gy);
+    if (rw > cap) rw -= a->gy;
     if (rw > a->rows) rw = round_up(a->rows, a->gy);
+    if (rw < a->gy) rw = a->gy;
     a->rw = int(rw);
     a->n_wg = int(a->strips * ((a->rows + rw - 1) / rw));
+}
+
+bool fast_eligible(int64_t cols, const float* v_colmax) {
+    return (cols % LPMM_BLOCK) == 0 && cols <= (int64_t(1) << 24) && aligned(v_colmax, 16) &&
+           !env_int("LPMM_FORCE_GENERAL", 0);
 }
 
 template <bool BF16>
@@ -139,8 +153,7 @@ int launch_step(const Tensor4& t, const Hyper& h, bool fast, hipStream_t s) {
     const bool rec = g_prof.on && g_prof.calls < g_prof.max_calls;
     const int64_t call = g_prof.calls;
     if (rec) LPMM_HIP(hipEventRecord(prof_event(call, 0), s));
-    const int64_t lanes = (t.P + 7) / 8;
-    const int grid = fast ? pad8(t.n_wg) : int((lanes + kThreads - 1) / kThreads);
+    const int grid = fast ? pad8(t.n_wg) : t.n_wg;
     if (fast) hipLaunchKernelGGL(pass1_fast<BF16>, dim3(grid), dim3(kThreads), 0, s, t, h);
     else hipLaunchKernelGGL(pass1_general<BF16>, dim3(grid), dim3(kThreads), 0, s, t, h);
     LPMM_HIP(hipGetLastError());
@@ -189,8 +202,10 @@ int step_impl(bool bf16, void* param, const void* grad, uint8_t* m_codes, float*
     t.rows = rows;
     t.cols = cols;
     t.P = rows * cols;
-    const bool fast = (cols % LPMM_BLOCK) == 0 && aligned(v_colmax, 16) && !env_int("LPMM_FORCE_GENERAL", 0);
-    if (fast) fast_geometry(&t, ctx->n_cu);
+    const bool fast = fast_eligible(cols, v_colmax);
+    t.kind = fast ? kQuantFast : kQuantGeneral;
+    if (fast) fast_geometry(&t, ctx->n_cu, 0);
+    else t.n_wg = int((((t.P + 7) / 8) + kThreads - 1) / kThreads);
     hipStream_t s = static_cast<hipStream_t>(stream);
     return bf16 ? launch_step<true>(t, h, fast, s) : launch_step<false>(t, h, fast, s);
 }
@@ -201,6 +216,49 @@ int grid_for(int64_t items, int64_t per_thread, int max_blocks = 1 << 20) {
     if (blocks < 1) blocks = 1;
     if (blocks > max_blocks) blocks = max_blocks;
     return int(blocks);
+}
+
+// ---- multi-tensor plans ---------------------------------------------------------------------------
+
+struct PhaseLaunch {
+    Phase ph;
+    int grid;
+};
+
+struct PlanHost {
+    std::vector<char> staging;          // host image of the device tables (kept for the async copy)
+    std::vector<PhaseLaunch> phases;
+    bool bf16 = false;
+    int device = 0;
+};
+
+std::unordered_map<void*, std::unique_ptr<PlanHost>> g_plans;
+
+struct PlanLayout {
+    size_t off_tensors, off_segments, off_counters, off_floats, total;
+    int64_t n_segments;
+};
+
+bool desc_shape_ok(const lpmm_tensor_desc& d) {
+    int64_t shape[2] = {d.rows, d.cols}, r, c;
+    return check_shape(shape, &r, &c) == LPMM_OK && (d.kind == LPMM_KIND_4BIT || d.kind == LPMM_KIND_FP32);
+}
+
+bool plan_layout(const lpmm_tensor_desc* descs, int64_t n, PlanLayout* L) {
+    if (!descs || n < 1 || n > (1 << 20)) return false;
+    int64_t floats = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        if (!desc_shape_ok(descs[i])) return false;
+        if (descs[i].kind == LPMM_KIND_4BIT) floats += round_up(descs[i].rows, 64) + round_up(descs[i].cols, 64);
+    }
+    L->n_segments = 2 * n + 2;           // every tensor appears at most once as A and once as B work
+    size_t off = 0;
+    L->off_tensors = off;   off += size_t(round_up(n * int64_t(sizeof(Tensor4)), 256));
+    L->off_segments = off;  off += size_t(round_up(L->n_segments * int64_t(sizeof(Segment)), 256));
+    L->off_counters = off;  off += size_t(n) * kCounterWords * sizeof(unsigned int);
+    L->off_floats = off;    off += size_t(floats) * sizeof(float);
+    L->total = size_t(round_up(int64_t(off), 256));
+    return true;
 }
 
 int fill(void* dst, int64_t n, uint8_t value, int64_t last_index, uint8_t last, hipStream_t s) {
@@ -345,7 +403,7 @@ int lpmm_adamw32_step(void* param, const void* grad, float* m, float* v, int64_t
     const int rc = make_hyper(lr, beta1, beta2, eps, weight_decay, step, &h);
     if (rc) return rc;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const int grid = grid_for(numel, 1, 8192);
+    const int grid = int((numel + kElemsPerWg32 - 1) / kElemsPerWg32);
     if (grad_dtype == LPMM_GRAD_BF16)
         hipLaunchKernelGGL(adamw32_kernel<true>, dim3(grid), dim3(kThreads), 0, s,
                            static_cast<float*>(param), grad, m, v, numel, h);
@@ -413,6 +471,155 @@ int lpmm_quant_state(int which, const float* in, const int64_t shape[2], uint8_t
         LPMM_HIP(hipGetLastError());
     }
     return LPMM_OK;
+}
+
+size_t lpmm_adamw4_plan_bytes(const lpmm_tensor_desc* descs, int64_t n) {
+    PlanLayout L;
+    return plan_layout(descs, n, &L) ? L.total : 0;
+}
+
+int lpmm_adamw4_plan_build(const lpmm_tensor_desc* descs, int64_t n, int grad_dtype, void* plan,
+                           size_t plan_bytes, void* stream) {
+    PlanLayout L;
+    if (!plan_layout(descs, n, &L)) return LPMM_EINVAL;
+    if (!plan || !aligned(plan, 256) || plan_bytes < L.total) return LPMM_EINVAL;
+    if (grad_dtype != LPMM_GRAD_F32 && grad_dtype != LPMM_GRAD_BF16) return LPMM_EINVAL;
+    DeviceCtx* ctx;
+    int rc = current_ctx(&ctx);          // the lookup tables are uploaded by lpmm_adamw4_init
+    if (rc) return rc;
+    int dev = 0;
+    LPMM_HIP(hipGetDevice(&dev));
+
+    auto host = std::make_unique<PlanHost>();
+    host->bf16 = grad_dtype == LPMM_GRAD_BF16;
+    host->device = dev;
+    host->staging.assign(L.off_counters, 0);
+    Tensor4* tens = reinterpret_cast<Tensor4*>(host->staging.data() + L.off_tensors);
+    Segment* segs = reinterpret_cast<Segment*>(host->staging.data() + L.off_segments);
+    char* dplan = static_cast<char*>(plan);
+    const Tensor4* d_tens = reinterpret_cast<const Tensor4*>(dplan + L.off_tensors);
+    const Segment* d_segs = reinterpret_cast<const Segment*>(dplan + L.off_segments);
+    float* d_floats = reinterpret_cast<float*>(dplan + L.off_floats);
+    unsigned int* d_counters = reinterpret_cast<unsigned int*>(dplan + L.off_counters);
+
+    const int64_t rw_hint = env_int("LPMM_MULTI_RW", 64);
+    int64_t fofs = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        const lpmm_tensor_desc& d = descs[i];
+        const size_t galign = grad_dtype == LPMM_GRAD_F32 ? 4 : 2;
+        Tensor4 t{};
+        t.rows = d.rows; t.cols = d.cols; t.P = d.rows * d.cols;
+        t.p = static_cast<float*>(d.param);
+        t.g = d.grad;
+        t.mq = static_cast<uint32_t*>(d.m_state);
+        t.vq = static_cast<uint32_t*>(d.v_state);
+        if (!d.param || !d.grad || !d.m_state || !d.v_state) return LPMM_EINVAL;
+        if (d.kind == LPMM_KIND_FP32) {
+            if (!aligned(d.param, 4) || !aligned(d.m_state, 4) || !aligned(d.v_state, 4) || !aligned(d.grad, galign))
+                return LPMM_EINVAL;
+            t.kind = kFp32State;
+            t.n_wg = int((t.P + kElemsPerWg32 - 1) / kElemsPerWg32);
+        } else {
+            if (!d.m_blockscale || !d.v_rowmax || !d.v_colmax) return LPMM_EINVAL;
+            if (!aligned(d.param, 16) || !aligned(d.grad, 16) || !aligned(d.m_state, 4) || !aligned(d.v_state, 4) ||
+                !aligned(d.m_blockscale, 4) || !aligned(d.v_rowmax, 4) || !aligned(d.v_colmax, 4))
+                return LPMM_EINVAL;
+            t.ms = d.m_blockscale;
+            t.r = d.v_rowmax;
+            t.c = d.v_colmax;
+            t.r_new = d_floats + fofs;
+            fofs += round_up(d.rows, 64);
+            t.c_new = d_floats + fofs;
+            fofs += round_up(d.cols, 64);
+            t.counter = d_counters + i * kCounterWords;
+            if (fast_eligible(d.cols, d.v_colmax)) {
+                t.kind = kQuantFast;
+                fast_geometry(&t, ctx->n_cu, rw_hint);
+            } else {
+                t.kind = kQuantGeneral;
+                t.n_wg = int((((t.P + 7) / 8) + kThreads - 1) / kThreads);
+            }
+        }
+        tens[i] = t;
+    }
+
+    // groups of consecutive tensors; phase j = A work of group j + B work of group j-1
+    const int64_t group_params = int64_t(env_int("LPMM_PHASE_MPARAMS", 128)) << 20;
+    std::vector<std::pair<int64_t, int64_t>> groups;      // [first, last)
+    for (int64_t i = 0; i < n;) {
+        int64_t j = i, acc = 0;
+        while (j < n && (j == i || acc + tens[j].P <= group_params)) acc += tens[j++].P;
+        groups.emplace_back(i, j);
+        i = j;
+    }
+    int64_t sofs = 0;
+    for (size_t j = 0; j <= groups.size(); ++j) {
+        PhaseLaunch pl{};
+        pl.ph.tensors = d_tens;
+        pl.ph.seg_a = d_segs + sofs;
+        if (j < groups.size())
+            for (int64_t i = groups[j].first; i < groups[j].second; ++i) {
+                segs[sofs++] = Segment{pl.ph.n_a, int(i)};
+                pl.ph.n_seg_a++;
+                pl.ph.n_a += tens[i].n_wg;
+            }
+        pl.ph.seg_b = d_segs + sofs;
+        if (j >= 1)
+            for (int64_t i = groups[j - 1].first; i < groups[j - 1].second; ++i) {
+                if (tens[i].kind == kFp32State) continue;
+                segs[sofs++] = Segment{pl.ph.n_b, int(i)};
+                pl.ph.n_seg_b++;
+                pl.ph.n_b += tens[i].n_wg;
+            }
+        if (pl.ph.n_a + pl.ph.n_b == 0) continue;
+        if (int64_t(pl.ph.n_a) + pl.ph.n_b > (int64_t(1) << 30)) return LPMM_EINVAL;
+        pl.grid = pad8(int64_t(pl.ph.n_a) + pl.ph.n_b);
+        host->phases.push_back(pl);
+    }
+
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    LPMM_HIP(hipMemsetAsync(dplan + L.off_counters, 0, L.total - L.off_counters, s));
+    LPMM_HIP(hipMemcpyAsync(dplan, host->staging.data(), L.off_counters, hipMemcpyHostToDevice, s));
+    std::lock_guard<std::mutex> lock(g_mu);
+    g_plans[plan] = std::move(host);
+    return LPMM_OK;
+}
+
+int lpmm_adamw4_step_multi(void* plan, float lr, float beta1, float beta2, float eps, float weight_decay,
+                           int64_t step, void* stream) {
+    Hyper h;
+    const int rc = make_hyper(lr, beta1, beta2, eps, weight_decay, step, &h);
+    if (rc) return rc;
+    const PlanHost* host = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_mu);
+        auto it = g_plans.find(plan);
+        if (it == g_plans.end()) return LPMM_EINVAL;
+        host = it->second.get();
+    }
+    int dev = 0;
+    LPMM_HIP(hipGetDevice(&dev));
+    if (dev != host->device) return LPMM_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    for (const PhaseLaunch& pl : host->phases) {
+        const bool rec = g_prof.on && g_prof.calls < g_prof.max_calls;
+        const int64_t call = g_prof.calls;
+        if (rec) LPMM_HIP(hipEventRecord(prof_event(call, 0), s));
+        if (host->bf16) hipLaunchKernelGGL(phase_kernel<true>, dim3(pl.grid), dim3(kThreads), 0, s, pl.ph, h);
+        else hipLaunchKernelGGL(phase_kernel<false>, dim3(pl.grid), dim3(kThreads), 0, s, pl.ph, h);
+        LPMM_HIP(hipGetLastError());
+        if (rec) {
+            LPMM_HIP(hipEventRecord(prof_event(call, 1), s));
+            LPMM_HIP(hipEventRecord(prof_event(call, 2), s));
+            g_prof.calls = call + 1;
+        }
+    }
+    return LPMM_OK;
+}
+
+int lpmm_adamw4_plan_release(void* plan) {
+    std::lock_guard<std::mutex> lock(g_mu);
+    return g_plans.erase(plan) ? LPMM_OK : LPMM_EINVAL;
 }
 
 int lpmm_profile_begin(int64_t max_calls) {
