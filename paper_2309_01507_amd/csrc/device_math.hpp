@@ -25,20 +25,22 @@ struct Hyper {
 
 // ---- cross-lane reductions inside one DPP row (16 lanes = one 128-element block) ----------------
 
+// Maximum over the 16 lanes of a row of a value that is >= +0 in every lane, result in every lane
+// of the row.  Non-negative floats order like their bit patterns, so the unsigned integer maximum is
+// used: 0 is its identity, which lets each step fold into one v_max_u32 with a DPP operand, and no
+// NaN canonicalization is needed.  All 16 lanes of the row must be active.
 template <int CTRL>
-__device__ __forceinline__ float dpp_f32(float x) {
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL,
-                                                                 0xF, 0xF, false));
+__device__ __forceinline__ uint32_t dpp_umax(uint32_t x) {
+    const uint32_t y = uint32_t(__builtin_amdgcn_update_dpp(0, int(x), CTRL, 0xF, 0xF, false));
+    return x > y ? x : y;
 }
-
-// Maximum over the 16 lanes of a row, result in every lane of the row.  Inputs must be >= 0 or all
-// lanes of the row must be active (both hold where this is used).
-__device__ __forceinline__ float row16_allmax(float x) {
-    x = fmaxf(x, dpp_f32<0xB1>(x));    // quad_perm [1,0,3,2]: lane ^ 1
-    x = fmaxf(x, dpp_f32<0x4E>(x));    // quad_perm [2,3,0,1]: lane ^ 2
-    x = fmaxf(x, dpp_f32<0x141>(x));   // row_half_mirror: other quad of the half row
-    x = fmaxf(x, dpp_f32<0x140>(x));   // row_mirror: other half of the row
-    return x;
+__device__ __forceinline__ float row16_allmax(float v) {
+    uint32_t x = __float_as_uint(v);
+    x = dpp_umax<0xB1>(x);    // quad_perm [1,0,3,2]: lane ^ 1
+    x = dpp_umax<0x4E>(x);    // quad_perm [2,3,0,1]: lane ^ 2
+    x = dpp_umax<0x141>(x);   // row_half_mirror: other quad of the half row
+    x = dpp_umax<0x140>(x);   // row_mirror: other half of the row
+    return __uint_as_float(x);
 }
 
 // ---- gradient element access ---------------------------------------------------------------------
@@ -162,7 +164,9 @@ __device__ __forceinline__ float dequant_v16(float qf, float s16) { return __bui
 // ---- float maximum through an integer atomic (values >= +0 only: bit order == value order) --------
 
 __device__ __forceinline__ void atomic_max_nonneg(float* addr, float v) {
+#ifndef LPMM_EXPERIMENT_NO_ATOMICS
     atomicMax(reinterpret_cast<unsigned int*>(addr), __float_as_uint(v));
+#endif
 }
 
 }  // namespace lpmm

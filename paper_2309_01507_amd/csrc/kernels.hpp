@@ -226,6 +226,77 @@ __device__ __forceinline__ Row1<BF16> load_row1(const TileBase& b, const Tensor4
     return r;
 }
 
+// One row of pass 1 for one lane: `cur` holds what was loaded for row `il` of the tile.
+template <bool BF16>
+__device__ __forceinline__ void pass1_row(const Tensor4& a, const Hyper& h, const TileBase& tb, const Geo& geo,
+                                          const Lds& s, const Row1<BF16>& cur, int il, const float cold16[8],
+                                          bool cols_tame, float cmax[8]) {
+    float w[8] = {cur.p0.x, cur.p0.y, cur.p0.z, cur.p0.w, cur.p1.x, cur.p1.y, cur.p1.z, cur.p1.w};
+    float g[8];
+    unpack_grad<BF16>(cur.g, g);
+    float mt[8], vt[8], amax = 0.0f, rmax = 0.0f;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const float2 t = s.deq[(cur.mq >> (8 * k)) & 255u];
+        mt[2 * k] = t.x * cur.s_old;          // decompress: T_DE[code] * block scale
+        mt[2 * k + 1] = t.y * cur.s_old;
+    }
+    // the wave takes the exact route for this row if any of its scales is extreme
+    const bool tame_in = cols_tame && scale_is_tame(cur.r_old);
+    if (__builtin_expect(__ballot(!tame_in) == 0, 1)) {
+        float qf[8];
+        codes_to_float(cur.vq, qf);
+        const float r16 = cur.r_old * 0.0625f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) vt[e] = dequant_v16(qf[e], min_nonneg(r16, cold16[e]));
+    } else {
+        float cold[8];
+        load8(a.c + geo.col0, cold);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) vt[e] = dequant_v((cur.vq >> (4 * e)) & 15u, fminf(cur.r_old, cold[e]));
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        mt[e] = moment_m(h, mt[e], g[e]);
+        vt[e] = moment_v(h, vt[e], g[e]);
+        w[e] = param_update(h, w[e], mt[e], vt[e]);
+        amax = fmaxf(amax, fabsf(mt[e]));
+        rmax = fmaxf(rmax, vt[e]);
+        cmax[e] = fmaxf(cmax[e], vt[e]);
+    }
+    const float s_new = row16_allmax(amax);     // block absmax of m_t
+    rmax = row16_allmax(rmax);
+
+    uint32_t mq_new = 0;
+    float slack = 1.0f;
+    if (scale_is_tame(s_new)) {
+        const float inv_s = approx_inv(s_new);
+#pragma unroll
+        for (int e = 0; e < 8; e += 2) {
+            float sa, sb;
+            mq_new |= quant_m_code_fast(s.search, mt[e], inv_s, sa) << (4 * e);
+            mq_new |= quant_m_code_fast(s.search, mt[e + 1], inv_s, sb) << (4 * e + 4);
+            slack = fminf(fminf(slack, sa), sb);
+        }
+    } else {
+        slack = -1.0f;
+    }
+    if (__builtin_expect(__ballot(slack < 0.0f) != 0, 0)) {
+        mq_new = 0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) mq_new |= quant_m_code(s.search, mt[e], s_new) << (4 * e);
+    }
+
+    const uint32_t off4 = (uint32_t(il) * uint32_t(a.cols) + geo.col0) * 4u;
+    st<float4>(tb.p, off4, make_float4(w[0], w[1], w[2], w[3]));
+    st<float4>(tb.p, off4 + 16, make_float4(w[4], w[5], w[6], w[7]));
+    st<uint32_t>(tb.mq, off4 >> 3, mq_new);
+    if (geo.l == 0) {
+        st<float>(tb.ms, (uint32_t(il) * uint32_t(a.nb) + uint32_t(geo.cb)) * 4u, s_new);
+        if (rmax > 0.0f) atomic_max_nonneg(tb.r_new + il, rmax);
+    }
+}
+
 template <bool BF16>
 __device__ __forceinline__ void pass1_fast_tile(const Tensor4& a, const Hyper& h, int wg, Lds& s) {
     const Geo geo = geometry(a, wg);
@@ -235,87 +306,37 @@ __device__ __forceinline__ void pass1_fast_tile(const Tensor4& a, const Hyper& h
     for (int e = 0; e < 8; ++e) cmax[e] = 0.0f;
 
     if (geo.active) {
-        float cold[8], cold16[8];
-        load8(a.c + geo.col0, cold);
+        float cold16[8];
+        load8(a.c + geo.col0, cold16);
         bool cols_tame = true;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            cols_tame = cols_tame && scale_is_tame(cold[e]);
-            cold16[e] = cold[e] * 0.0625f;
+            cols_tame = cols_tame && scale_is_tame(cold16[e]);
+            cold16[e] *= 0.0625f;
         }
+        // rows of this group: il, il + gy, ...; the loads of two rows are in flight while a third
+        // is computed (three register sets take turns, the loop is unrolled by three)
+        const int stp = a.gy, n = geo.n_rows;
         int il = geo.gyi;
-        Row1<BF16> cur;
-        if (il < geo.n_rows) cur = load_row1<BF16>(tb, a, geo, il);
-        while (il < geo.n_rows) {
-            const int inext = il + a.gy;
-            Row1<BF16> nxt;
-            if (inext < geo.n_rows) nxt = load_row1<BF16>(tb, a, geo, inext);
-
-            float w[8] = {cur.p0.x, cur.p0.y, cur.p0.z, cur.p0.w, cur.p1.x, cur.p1.y, cur.p1.z, cur.p1.w};
-            float g[8];
-            unpack_grad<BF16>(cur.g, g);
-            float mt[8], vt[8], amax = 0.0f, rmax = 0.0f;
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const float2 t = s.deq[(cur.mq >> (8 * k)) & 255u];
-                mt[2 * k] = t.x * cur.s_old;          // decompress: T_DE[code] * block scale
-                mt[2 * k + 1] = t.y * cur.s_old;
-            }
-            // the wave takes the exact route for this row if any of its scales is extreme
-            const bool tame_in = cols_tame && scale_is_tame(cur.r_old);
-            if (__builtin_expect(__ballot(!tame_in) == 0, 1)) {
-                float qf[8];
-                codes_to_float(cur.vq, qf);
-                const float r16 = cur.r_old * 0.0625f;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) vt[e] = dequant_v16(qf[e], min_nonneg(r16, cold16[e]));
-            } else {
-#pragma unroll
-                for (int e = 0; e < 8; ++e) vt[e] = dequant_v((cur.vq >> (4 * e)) & 15u, fminf(cur.r_old, cold[e]));
-            }
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                mt[e] = moment_m(h, mt[e], g[e]);
-                vt[e] = moment_v(h, vt[e], g[e]);
-                w[e] = param_update(h, w[e], mt[e], vt[e]);
-                amax = fmaxf(amax, fabsf(mt[e]));
-                rmax = fmaxf(rmax, vt[e]);
-                cmax[e] = fmaxf(cmax[e], vt[e]);
-            }
-            const float s_new = row16_allmax(amax);     // block absmax of m_t
-            rmax = row16_allmax(rmax);
-
-            uint32_t mq_new = 0;
-            float slack = 1.0f;
-            if (scale_is_tame(s_new)) {
-                const float inv_s = approx_inv(s_new);
-#pragma unroll
-                for (int e = 0; e < 8; e += 2) {
-                    float sa, sb;
-                    mq_new |= quant_m_code_fast(s.search, mt[e], inv_s, sa) << (4 * e);
-                    mq_new |= quant_m_code_fast(s.search, mt[e + 1], inv_s, sb) << (4 * e + 4);
-                    slack = fminf(fminf(slack, sa), sb);
-                }
-            } else {
-                slack = -1.0f;
-            }
-            if (__builtin_expect(__ballot(slack < 0.0f) != 0, 0)) {
-                mq_new = 0;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) mq_new |= quant_m_code(s.search, mt[e], s_new) << (4 * e);
-            }
-
-            const uint32_t off4 = (uint32_t(il) * uint32_t(a.cols) + geo.col0) * 4u;
-            st<float4>(tb.p, off4, make_float4(w[0], w[1], w[2], w[3]));
-            st<float4>(tb.p, off4 + 16, make_float4(w[4], w[5], w[6], w[7]));
-            st<uint32_t>(tb.mq, off4 >> 3, mq_new);
-            if (geo.l == 0) {
-                st<float>(tb.ms, (uint32_t(il) * uint32_t(a.nb) + uint32_t(geo.cb)) * 4u, s_new);
-                if (rmax > 0.0f) atomic_max_nonneg(tb.r_new + il, rmax);
-            }
-            cur = nxt;
-            il = inext;
+        Row1<BF16> r0, r1, r2;
+        if (il < n) r0 = load_row1<BF16>(tb, a, geo, il);
+        if (il + stp < n) r1 = load_row1<BF16>(tb, a, geo, il + stp);
+        load_tables(s);               // the first rows' loads are in flight while the tables arrive
+        while (il < n) {
+            if (il + 2 * stp < n) r2 = load_row1<BF16>(tb, a, geo, il + 2 * stp);
+            pass1_row<BF16>(a, h, tb, geo, s, r0, il, cold16, cols_tame, cmax);
+            il += stp;
+            if (il >= n) break;
+            if (il + 2 * stp < n) r0 = load_row1<BF16>(tb, a, geo, il + 2 * stp);
+            pass1_row<BF16>(a, h, tb, geo, s, r1, il, cold16, cols_tame, cmax);
+            il += stp;
+            if (il >= n) break;
+            if (il + 2 * stp < n) r1 = load_row1<BF16>(tb, a, geo, il + 2 * stp);
+            pass1_row<BF16>(a, h, tb, geo, s, r2, il, cold16, cols_tame, cmax);
+            il += stp;
         }
+    } else {
+        load_tables(s);               // keeps the workgroup's barriers matched
     }
 
     // column maxima: combine the gy groups that share a column block, then one atomic per column
@@ -384,8 +405,8 @@ __device__ __forceinline__ Row2<BF16> load_row2(const TileBase& b, const Tensor4
 }
 
 template <bool BF16>
-__device__ __forceinline__ uint32_t pass2_row(const Hyper& h, const Row2<BF16>& row, const float cold[8],
-                                              const float cold16[8], const float cnew[8],
+__device__ __forceinline__ uint32_t pass2_row(const Tensor4& a, const Hyper& h, const Geo& geo,
+                                              const Row2<BF16>& row, const float cold16[8],
                                               const float inv_cnew[8], bool cols_tame) {
     float g[8], vt[8];
     unpack_grad<BF16>(row.g, g);
@@ -411,10 +432,14 @@ __device__ __forceinline__ uint32_t pass2_row(const Hyper& h, const Row2<BF16>& 
         const bool near = fmin_ < kMarginV || fmax_ > 1.0f - kMarginV;
         if (__builtin_expect(__ballot(near) == 0, 1)) return lo | (hi << 4);
     } else {
+        float cold[8];
+        load8(a.c + geo.col0, cold);
 #pragma unroll
         for (int e = 0; e < 8; ++e)
             vt[e] = moment_v(h, dequant_v((row.vq >> (4 * e)) & 15u, fminf(row.r_old, cold[e])), g[e]);
     }
+    float cnew[8];
+    load8(a.c_new + geo.col0, cnew);
     uint32_t out = 0;
 #pragma unroll
     for (int e = 0; e < 8; ++e) out |= quant_v_code(vt[e], fminf(row.r_new, cnew[e])) << (4 * e);
@@ -426,15 +451,15 @@ __device__ __forceinline__ void pass2_fast_tile(const Tensor4& a, const Hyper& h
     const Geo geo = geometry(a, wg);
     if (!geo.active) return;
     const TileBase tb = tile_base<BF16>(a, geo.row0);
-    float cold[8], cold16[8], cnew[8], inv_cnew[8];
-    load8(a.c + geo.col0, cold);
-    load8(a.c_new + geo.col0, cnew);
+    float cold16[8], inv_cnew[8];
+    load8(a.c + geo.col0, cold16);
+    load8(a.c_new + geo.col0, inv_cnew);
     bool cols_tame = true;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-        cols_tame = cols_tame && scale_is_tame(cold[e]) && scale_is_tame(cnew[e]);
-        cold16[e] = cold[e] * 0.0625f;
-        inv_cnew[e] = approx_inv(cnew[e]);
+        cols_tame = cols_tame && scale_is_tame(cold16[e]) && scale_is_tame(inv_cnew[e]);
+        cold16[e] *= 0.0625f;
+        inv_cnew[e] = approx_inv(inv_cnew[e]);
     }
     // two rows per stage, the next stage's loads in flight while this one is computed
     const int stride = a.gy;
@@ -448,10 +473,10 @@ __device__ __forceinline__ void pass2_fast_tile(const Tensor4& a, const Hyper& h
         if (j0 < geo.n_rows) n0 = load_row2<BF16>(tb, a, geo, j0);
         if (j1 < geo.n_rows) n1 = load_row2<BF16>(tb, a, geo, j1);
         const uint32_t off = (uint32_t(il) * uint32_t(a.cols) + geo.col0) >> 1;     // byte offset of the code word
-        st<uint32_t>(tb.vq, off, pass2_row<BF16>(h, c0, cold, cold16, cnew, inv_cnew, cols_tame));
+        st<uint32_t>(tb.vq, off, pass2_row<BF16>(a, h, geo, c0, cold16, inv_cnew, cols_tame));
         if (il + stride < geo.n_rows)
             st<uint32_t>(tb.vq, off + ((uint32_t(stride) * uint32_t(a.cols)) >> 1),
-                         pass2_row<BF16>(h, c1, cold, cold16, cnew, inv_cnew, cols_tame));
+                         pass2_row<BF16>(a, h, geo, c1, cold16, inv_cnew, cols_tame));
         c0 = n0;
         c1 = n1;
         il = j0;
@@ -625,7 +650,6 @@ __global__ __launch_bounds__(kThreads) void pass1_fast(const Tensor4 a, const Hy
     __shared__ Lds s;
     const int wg = logical_wg();
     if (wg >= a.n_wg) return;
-    load_tables(s);
     pass1_fast_tile<BF16>(a, h, wg, s);
 }
 
@@ -669,21 +693,22 @@ struct Segment {        // a run of workgroups that work on one tensor
     int tensor;         // index into the tensor table
 };
 
+constexpr int kMaxSeg = 32;   // tensors per kind in one phase; the tables travel as kernel arguments
+
 struct Phase {
     const Tensor4* tensors;
-    const Segment* seg_a;   // n_seg_a entries
-    const Segment* seg_b;   // n_seg_b entries
     int n_seg_a, n_seg_b;
     int n_a, n_b;           // workgroups of each kind
+    Segment seg_a[kMaxSeg];
+    Segment seg_b[kMaxSeg];
 };
 
-__device__ __forceinline__ int find_segment(const Segment* seg, int n_seg, int wg) {
-    int lo = 0, hi = n_seg - 1;
-    while (lo < hi) {
-        const int mid = (lo + hi + 1) >> 1;
-        if (seg[mid].wg_begin <= wg) lo = mid; else hi = mid - 1;
-    }
-    return lo;
+// last segment whose first workgroup is <= wg (segments are sorted; a short uniform scan)
+__device__ __forceinline__ Segment find_segment(const Segment* seg, int n_seg, int wg) {
+    Segment r = seg[0];
+    for (int k = 1; k < n_seg; ++k)
+        if (seg[k].wg_begin <= wg) r = seg[k];
+    return r;
 }
 
 template <bool BF16>
@@ -696,8 +721,7 @@ __global__ __launch_bounds__(kThreads) void phase_kernel(const Phase ph, const H
     const int b_before = int((int64_t(x) * ph.n_b) / n);
     const int b_after = int((int64_t(x + 1) * ph.n_b) / n);
     if (b_after > b_before) {
-        const int sgi = find_segment(ph.seg_b, ph.n_seg_b, b_before);
-        const Segment sg = ph.seg_b[sgi];
+        const Segment sg = find_segment(ph.seg_b, ph.n_seg_b, b_before);
         const Tensor4 a = ph.tensors[sg.tensor];
         const int wg = b_before - sg.wg_begin;
         if (a.kind == kQuantFast) pass2_fast_tile<BF16>(a, h, wg);
@@ -705,16 +729,16 @@ __global__ __launch_bounds__(kThreads) void phase_kernel(const Phase ph, const H
         publish_if_last(a, wg, a.n_wg, s.last);
     } else {
         const int xa = x - b_before;
-        const int sgi = find_segment(ph.seg_a, ph.n_seg_a, xa);
-        const Segment sg = ph.seg_a[sgi];
+        const Segment sg = find_segment(ph.seg_a, ph.n_seg_a, xa);
         const Tensor4 a = ph.tensors[sg.tensor];
         const int wg = xa - sg.wg_begin;
         if (a.kind == kFp32State) {
             adamw32_tile<BF16>(a.p, a.g, reinterpret_cast<float*>(a.mq), reinterpret_cast<float*>(a.vq), a.P, h, wg);
+        } else if (a.kind == kQuantFast) {
+            pass1_fast_tile<BF16>(a, h, wg, s);
         } else {
             load_tables(s);
-            if (a.kind == kQuantFast) pass1_fast_tile<BF16>(a, h, wg, s);
-            else pass1_general_tile<BF16>(a, h, wg, s);
+            pass1_general_tile<BF16>(a, h, wg, s);
         }
     }
 }

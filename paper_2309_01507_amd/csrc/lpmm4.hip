@@ -235,8 +235,7 @@ struct PlanHost {
 std::unordered_map<void*, std::unique_ptr<PlanHost>> g_plans;
 
 struct PlanLayout {
-    size_t off_tensors, off_segments, off_counters, off_floats, total;
-    int64_t n_segments;
+    size_t off_tensors, off_counters, off_floats, total;
 };
 
 bool desc_shape_ok(const lpmm_tensor_desc& d) {
@@ -251,10 +250,8 @@ bool plan_layout(const lpmm_tensor_desc* descs, int64_t n, PlanLayout* L) {
         if (!desc_shape_ok(descs[i])) return false;
         if (descs[i].kind == LPMM_KIND_4BIT) floats += round_up(descs[i].rows, 64) + round_up(descs[i].cols, 64);
     }
-    L->n_segments = 2 * n + 2;           // every tensor appears at most once as A and once as B work
     size_t off = 0;
     L->off_tensors = off;   off += size_t(round_up(n * int64_t(sizeof(Tensor4)), 256));
-    L->off_segments = off;  off += size_t(round_up(L->n_segments * int64_t(sizeof(Segment)), 256));
     L->off_counters = off;  off += size_t(n) * kCounterWords * sizeof(unsigned int);
     L->off_floats = off;    off += size_t(floats) * sizeof(float);
     L->total = size_t(round_up(int64_t(off), 256));
@@ -495,10 +492,8 @@ int lpmm_adamw4_plan_build(const lpmm_tensor_desc* descs, int64_t n, int grad_dt
     host->device = dev;
     host->staging.assign(L.off_counters, 0);
     Tensor4* tens = reinterpret_cast<Tensor4*>(host->staging.data() + L.off_tensors);
-    Segment* segs = reinterpret_cast<Segment*>(host->staging.data() + L.off_segments);
     char* dplan = static_cast<char*>(plan);
     const Tensor4* d_tens = reinterpret_cast<const Tensor4*>(dplan + L.off_tensors);
-    const Segment* d_segs = reinterpret_cast<const Segment*>(dplan + L.off_segments);
     float* d_floats = reinterpret_cast<float*>(dplan + L.off_floats);
     unsigned int* d_counters = reinterpret_cast<unsigned int*>(dplan + L.off_counters);
 
@@ -548,27 +543,22 @@ int lpmm_adamw4_plan_build(const lpmm_tensor_desc* descs, int64_t n, int grad_dt
     std::vector<std::pair<int64_t, int64_t>> groups;      // [first, last)
     for (int64_t i = 0; i < n;) {
         int64_t j = i, acc = 0;
-        while (j < n && (j == i || acc + tens[j].P <= group_params)) acc += tens[j++].P;
+        while (j < n && j - i < kMaxSeg && (j == i || acc + tens[j].P <= group_params)) acc += tens[j++].P;
         groups.emplace_back(i, j);
         i = j;
     }
-    int64_t sofs = 0;
     for (size_t j = 0; j <= groups.size(); ++j) {
         PhaseLaunch pl{};
         pl.ph.tensors = d_tens;
-        pl.ph.seg_a = d_segs + sofs;
         if (j < groups.size())
             for (int64_t i = groups[j].first; i < groups[j].second; ++i) {
-                segs[sofs++] = Segment{pl.ph.n_a, int(i)};
-                pl.ph.n_seg_a++;
+                pl.ph.seg_a[pl.ph.n_seg_a++] = Segment{pl.ph.n_a, int(i)};
                 pl.ph.n_a += tens[i].n_wg;
             }
-        pl.ph.seg_b = d_segs + sofs;
         if (j >= 1)
             for (int64_t i = groups[j - 1].first; i < groups[j - 1].second; ++i) {
                 if (tens[i].kind == kFp32State) continue;
-                segs[sofs++] = Segment{pl.ph.n_b, int(i)};
-                pl.ph.n_seg_b++;
+                pl.ph.seg_b[pl.ph.n_seg_b++] = Segment{pl.ph.n_b, int(i)};
                 pl.ph.n_b += tens[i].n_wg;
             }
         if (pl.ph.n_a + pl.ph.n_b == 0) continue;
