@@ -133,9 +133,11 @@ int lpmm_quant_state(int which, const float* in, const int64_t shape[2], uint8_t
 /* ---- many tensors in one call ---------------------------------------------------------------------
  * The same step for a whole parameter set (Alg. 1: "perform the optimizer steps separately for each
  * layer" -- here all layers are enqueued by one call).  A plan is built once for a list of tensors;
- * lpmm_adamw4_step_multi then enqueues a short sequence of launches, each of which runs pass 1 of one
- * group of tensors next to pass 2 of the previous group.  Results are identical to calling the
- * single-tensor entry points one tensor at a time. */
+ * lpmm_adamw4_step_multi then enqueues a short sequence of launches: pass 1 of one group of tensors
+ * runs on `stream` while pass 2 of the previous group runs beside it on a second stream that the
+ * plan owns (same priority; `stream` waits for it before the call's work counts as complete, so the
+ * usual stream ordering holds for the caller).  Results are identical to calling the single-tensor
+ * entry points one tensor at a time. */
 
 #define LPMM_KIND_4BIT 0   /* quantized states as in lpmm_adamw4_step */
 #define LPMM_KIND_FP32 1   /* uncompressed fp32 states as in lpmm_adamw32_step */
@@ -182,9 +184,10 @@ int lpmm_adamw4_plan_release(void* plan);
  * recorded launches pairs / launches (later ones run unrecorded).  Creates host-side event objects only.
  * lpmm_profile_end: waits for the recorded events and stops recording.  Single-tensor steps: ms[0]
  * = summed duration in milliseconds of the recorded pass-1 launches, ms[1] = of the pass-2 launches,
- * *n_calls = recorded calls.  Multi-tensor steps: ms[0] = summed duration of the recorded phase
- * launches, ms[1] = 0, *n_calls = recorded launches.  (Do not mix the two kinds between one begin
- * and end.)  ms, n_calls: host.  Not thread-safe. */
+ * *n_calls = recorded calls.  Multi-tensor steps: ms[0] = summed duration of the recorded launches
+ * that carry pass 1 (their pass-2 companions run beside them on the plan's second stream), ms[1]
+ * = 0, *n_calls = recorded launches.  (Do not mix the two kinds between one begin and end.)
+ * ms, n_calls: host.  Not thread-safe. */
 int lpmm_profile_begin(int64_t max_calls);
 int lpmm_profile_end(double ms[2], int64_t* n_calls);
 

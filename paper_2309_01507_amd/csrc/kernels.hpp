@@ -1,8 +1,8 @@
 // Kernels of the 4-bit AdamW step (gfx950, wave64, 256-thread workgroups).
 //
-// Work unit: a "group" of 16 consecutive lanes (one DPP row) owns one 128-element block of the
-// row-major flattening; each lane owns 8 consecutive elements, i.e. one 32-bit word of 4-bit codes
-// of each moment, one 128-bit word of bf16 gradient and two 128-bit words of fp32 parameter.
+// Work unit: a group of lanes owns one 128-element block of the row-major flattening.  On the fast
+// path (cols % 128 == 0) that is 32 lanes with 4 consecutive elements each; on the general path 16
+// lanes (one DPP row) with 8 consecutive elements each.
 //
 // One step is two passes, because every v code needs the complete row and column maxima of the
 // updated second moment (rank-1 normalization, paper Sec. 4.2):
@@ -41,7 +41,7 @@ struct Tensor4 {
     int64_t rows, cols, P;
     // geometry of the fast path (cols % 128 == 0)
     int nb;                 // column blocks per row = cols / 128
-    int gx, gy;             // a workgroup's 16 groups: gx column blocks x gy row phases
+    int gx, gy;             // a workgroup's 8 groups: gx column blocks x gy row phases
     int rw;                 // rows per workgroup tile; rw * cols < 2^29
     int strips;             // nb / gx
     int n_wg;               // workgroups per pass
@@ -63,8 +63,7 @@ __device__ __forceinline__ int logical_wg() {
 struct Lds {
     float2 deq[256];
     SearchEntry search[kBuckets];
-    float col[16 * 128];
-    int last;
+    float col[8 * 128];
 };
 
 __device__ __forceinline__ void load_tables(Lds& s) {
@@ -133,31 +132,65 @@ __device__ __forceinline__ void unpack_grad(const GradRegs<BF16>& r, float out[8
     }
 }
 
-// float(code) of a lane's 8 codes: split the word into low and high nibbles (kept opaque so that
-// the byte-to-float converts are used), then one convert per element
-__device__ __forceinline__ void codes_to_float(uint32_t w, float qf[8]) {
-    uint32_t lo = w & 0x0F0F0F0Fu, hi = (w >> 4) & 0x0F0F0F0Fu;
-    asm("" : "+v"(lo));
-    asm("" : "+v"(hi));
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        qf[2 * k] = float((lo >> (8 * k)) & 255u);
-        qf[2 * k + 1] = float((hi >> (8 * k)) & 255u);
+// =====================================================================================================
+// Fast path: cols % 128 == 0, so a block never straddles a row.  Here a lane owns FOUR consecutive
+// elements of a row and a group of 32 lanes (half a wave) owns one 128-element block: every 128-bit
+// parameter access of a wave is then one contiguous kilobyte, and the small per-lane register
+// footprint lets six or more waves share a SIMD.  A group walks down the rows of one column block
+// with the old and the running new column maxima of its 4 columns in registers.  Addresses are a
+// uniform tile base plus a 32-bit lane offset; the loads of the next two rows are in flight while
+// a row is computed.
+// =====================================================================================================
+
+constexpr int kGroups = 8;          // 32-lane groups per workgroup
+
+// maximum over the 32 lanes of a group of a value that is >= +0 everywhere, result in all 32 lanes
+__device__ __forceinline__ float group32_allmax(float v) {
+    uint32_t x = __float_as_uint(row16_allmax(v));
+    // lane ^ 16 inside each half wave: swizzle in bit mode (and 0x1F, or 0, xor 0x10)
+    const uint32_t y = uint32_t(__builtin_amdgcn_ds_swizzle(int(x), 0x401F));
+    return __uint_as_float(x > y ? x : y);
+}
+
+template <bool BF16> struct GradRegs4;
+template <> struct GradRegs4<true> { uint2 w; };
+template <> struct GradRegs4<false> { float4 a; };
+
+// gradient of a lane's 4 elements; off4 is the byte offset the elements have in an fp32 array
+template <bool BF16>
+__device__ __forceinline__ GradRegs4<BF16> load_grad_regs4(const void* g_tile, uint32_t off4) {
+    GradRegs4<BF16> r;
+    if constexpr (BF16) r.w = ld<uint2>(g_tile, off4 >> 1);
+    else r.a = ld<float4>(g_tile, off4);
+    return r;
+}
+template <bool BF16>
+__device__ __forceinline__ void unpack_grad4(const GradRegs4<BF16>& r, float out[4]) {
+    if constexpr (BF16) {
+        out[0] = bf16_lo(r.w.x); out[1] = bf16_hi(r.w.x);
+        out[2] = bf16_lo(r.w.y); out[3] = bf16_hi(r.w.y);
+    } else {
+        out[0] = r.a.x; out[1] = r.a.y; out[2] = r.a.z; out[3] = r.a.w;
     }
 }
 
-// =====================================================================================================
-// Fast path: cols % 128 == 0, so a block never straddles a row and a group can walk down the rows
-// of one column block with the 8 old and 8 running new column maxima of its lane in registers.
-// Addresses are a uniform tile base plus a 32-bit lane offset; the loads of the next row are
-// issued before the current row is computed.
-// =====================================================================================================
+// float(code) of a lane's 4 codes (16 bits): split into low and high nibbles (kept opaque so that
+// the byte-to-float converts are used), then one convert per element
+__device__ __forceinline__ void codes_to_float4(uint32_t w, float qf[4]) {
+    uint32_t lo = w & 0x0F0Fu, hi = (w >> 4) & 0x0F0Fu;
+    asm("" : "+v"(lo));
+    asm("" : "+v"(hi));
+    qf[0] = float(lo & 255u);
+    qf[1] = float(hi & 255u);
+    qf[2] = float((lo >> 8) & 255u);
+    qf[3] = float((hi >> 8) & 255u);
+}
 
 struct Geo {            // where this group works
     int strip, grp, l, gxi, gyi, cb;
     int64_t row0;
     int n_rows;         // rows of this tile
-    uint32_t col0;
+    uint32_t col0;      // first of the lane's 4 columns
     bool active;
 };
 
@@ -165,15 +198,15 @@ __device__ __forceinline__ Geo geometry(const Tensor4& a, int wg) {
     Geo g;
     g.strip = wg % a.strips;
     const int tile = wg / a.strips;
-    g.grp = threadIdx.x >> 4;
-    g.l = threadIdx.x & 15;
+    g.grp = threadIdx.x >> 5;
+    g.l = threadIdx.x & 31;
     g.gxi = g.grp % a.gx;
     g.gyi = g.grp / a.gx;
     g.cb = g.strip * a.gx + g.gxi;
     g.row0 = int64_t(tile) * a.rw;
     const int64_t left = a.rows - g.row0;
     g.n_rows = left < a.rw ? int(left) : a.rw;
-    g.col0 = uint32_t(g.cb) * 128u + uint32_t(g.l) * 8u;
+    g.col0 = uint32_t(g.cb) * 128u + uint32_t(g.l) * 4u;
     g.active = g.cb < a.nb;
     return g;
 }
@@ -182,8 +215,8 @@ __device__ __forceinline__ Geo geometry(const Tensor4& a, int wg) {
 struct TileBase {
     float* p;
     const char* g;
-    uint32_t* mq;
-    uint32_t* vq;
+    uint8_t* mq;
+    uint8_t* vq;
     float* ms;
     const float* r;
     float* r_new;
@@ -195,19 +228,24 @@ __device__ __forceinline__ TileBase tile_base(const Tensor4& a, int64_t row0) {
     const int64_t e = row0 * a.cols;
     b.p = a.p + e;
     b.g = reinterpret_cast<const char*>(a.g) + e * (BF16 ? 2 : 4);
-    b.mq = a.mq + (e >> 3);
-    b.vq = a.vq + (e >> 3);
+    b.mq = reinterpret_cast<uint8_t*>(a.mq) + (e >> 1);
+    b.vq = reinterpret_cast<uint8_t*>(a.vq) + (e >> 1);
     b.ms = a.ms + row0 * a.nb;
     b.r = a.r + row0;
     b.r_new = a.r_new + row0;
     return b;
 }
 
+__device__ __forceinline__ void load4(const float* p, float out[4]) {
+    const float4 a = *reinterpret_cast<const float4*>(p);
+    out[0] = a.x; out[1] = a.y; out[2] = a.z; out[3] = a.w;
+}
+
 template <bool BF16>
 struct Row1 {                      // everything pass 1 reads for one row of one lane
-    float4 p0, p1;
-    GradRegs<BF16> g;
-    uint32_t mq, vq;
+    float4 p;
+    GradRegs4<BF16> g;
+    uint32_t mq, vq;               // 16 bits each: the lane's 4 codes
     float s_old, r_old;
 };
 
@@ -216,11 +254,10 @@ template <bool BF16>
 __device__ __forceinline__ Row1<BF16> load_row1(const TileBase& b, const Tensor4& a, const Geo& g, int il) {
     Row1<BF16> r;
     const uint32_t off4 = (uint32_t(il) * uint32_t(a.cols) + g.col0) * 4u;   // byte offset, fp32 array
-    r.p0 = ld<float4>(b.p, off4);
-    r.p1 = ld<float4>(b.p, off4 + 16);
-    r.g = load_grad_regs<BF16>(b.g, off4);
-    r.mq = ld<uint32_t>(b.mq, off4 >> 3);
-    r.vq = ld<uint32_t>(b.vq, off4 >> 3);
+    r.p = ld<float4>(b.p, off4);
+    r.g = load_grad_regs4<BF16>(b.g, off4);
+    r.mq = ld<uint16_t>(b.mq, off4 >> 3);
+    r.vq = ld<uint16_t>(b.vq, off4 >> 3);
     r.s_old = ld<float>(b.ms, (uint32_t(il) * uint32_t(a.nb) + uint32_t(g.cb)) * 4u);
     r.r_old = ld<float>(b.r, uint32_t(il) * 4u);
     return r;
@@ -229,14 +266,14 @@ __device__ __forceinline__ Row1<BF16> load_row1(const TileBase& b, const Tensor4
 // One row of pass 1 for one lane: `cur` holds what was loaded for row `il` of the tile.
 template <bool BF16>
 __device__ __forceinline__ void pass1_row(const Tensor4& a, const Hyper& h, const TileBase& tb, const Geo& geo,
-                                          const Lds& s, const Row1<BF16>& cur, int il, const float cold16[8],
-                                          bool cols_tame, float cmax[8]) {
-    float w[8] = {cur.p0.x, cur.p0.y, cur.p0.z, cur.p0.w, cur.p1.x, cur.p1.y, cur.p1.z, cur.p1.w};
-    float g[8];
-    unpack_grad<BF16>(cur.g, g);
-    float mt[8], vt[8], amax = 0.0f, rmax = 0.0f;
+                                          const Lds& s, const Row1<BF16>& cur, int il, const float cold16[4],
+                                          bool cols_tame, float cmax[4]) {
+    float w[4] = {cur.p.x, cur.p.y, cur.p.z, cur.p.w};
+    float g[4];
+    unpack_grad4<BF16>(cur.g, g);
+    float mt[4], vt[4], amax = 0.0f, rmax = 0.0f;
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
+    for (int k = 0; k < 2; ++k) {
         const float2 t = s.deq[(cur.mq >> (8 * k)) & 255u];
         mt[2 * k] = t.x * cur.s_old;          // decompress: T_DE[code] * block scale
         mt[2 * k + 1] = t.y * cur.s_old;
@@ -244,19 +281,19 @@ __device__ __forceinline__ void pass1_row(const Tensor4& a, const Hyper& h, cons
     // the wave takes the exact route for this row if any of its scales is extreme
     const bool tame_in = cols_tame && scale_is_tame(cur.r_old);
     if (__builtin_expect(__ballot(!tame_in) == 0, 1)) {
-        float qf[8];
-        codes_to_float(cur.vq, qf);
+        float qf[4];
+        codes_to_float4(cur.vq, qf);
         const float r16 = cur.r_old * 0.0625f;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) vt[e] = dequant_v16(qf[e], min_nonneg(r16, cold16[e]));
+        for (int e = 0; e < 4; ++e) vt[e] = dequant_v16(qf[e], min_nonneg(r16, cold16[e]));
     } else {
-        float cold[8];
-        load8(a.c + geo.col0, cold);
+        float cold[4];
+        load4(a.c + geo.col0, cold);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) vt[e] = dequant_v((cur.vq >> (4 * e)) & 15u, fminf(cur.r_old, cold[e]));
+        for (int e = 0; e < 4; ++e) vt[e] = dequant_v((cur.vq >> (4 * e)) & 15u, fminf(cur.r_old, cold[e]));
     }
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
+    for (int e = 0; e < 4; ++e) {
         mt[e] = moment_m(h, mt[e], g[e]);
         vt[e] = moment_v(h, vt[e], g[e]);
         w[e] = param_update(h, w[e], mt[e], vt[e]);
@@ -264,15 +301,15 @@ __device__ __forceinline__ void pass1_row(const Tensor4& a, const Hyper& h, cons
         rmax = fmaxf(rmax, vt[e]);
         cmax[e] = fmaxf(cmax[e], vt[e]);
     }
-    const float s_new = row16_allmax(amax);     // block absmax of m_t
-    rmax = row16_allmax(rmax);
+    const float s_new = group32_allmax(amax);     // block absmax of m_t
+    rmax = group32_allmax(rmax);
 
     uint32_t mq_new = 0;
     float slack = 1.0f;
     if (scale_is_tame(s_new)) {
         const float inv_s = approx_inv(s_new);
 #pragma unroll
-        for (int e = 0; e < 8; e += 2) {
+        for (int e = 0; e < 4; e += 2) {
             float sa, sb;
             mq_new |= quant_m_code_fast(s.search, mt[e], inv_s, sa) << (4 * e);
             mq_new |= quant_m_code_fast(s.search, mt[e + 1], inv_s, sb) << (4 * e + 4);
@@ -284,33 +321,31 @@ __device__ __forceinline__ void pass1_row(const Tensor4& a, const Hyper& h, cons
     if (__builtin_expect(__ballot(slack < 0.0f) != 0, 0)) {
         mq_new = 0;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) mq_new |= quant_m_code(s.search, mt[e], s_new) << (4 * e);
+        for (int e = 0; e < 4; ++e) mq_new |= quant_m_code(s.search, mt[e], s_new) << (4 * e);
     }
 
     const uint32_t off4 = (uint32_t(il) * uint32_t(a.cols) + geo.col0) * 4u;
     st<float4>(tb.p, off4, make_float4(w[0], w[1], w[2], w[3]));
-    st<float4>(tb.p, off4 + 16, make_float4(w[4], w[5], w[6], w[7]));
-    st<uint32_t>(tb.mq, off4 >> 3, mq_new);
+    st<uint16_t>(tb.mq, off4 >> 3, uint16_t(mq_new));
     if (geo.l == 0) {
         st<float>(tb.ms, (uint32_t(il) * uint32_t(a.nb) + uint32_t(geo.cb)) * 4u, s_new);
         if (rmax > 0.0f) atomic_max_nonneg(tb.r_new + il, rmax);
     }
 }
 
-template <bool BF16>
+// TABLES_READY: the caller has loaded the lookup tables into `s` (and synchronized) already.
+template <bool BF16, bool TABLES_READY>
 __device__ __forceinline__ void pass1_fast_tile(const Tensor4& a, const Hyper& h, int wg, Lds& s) {
     const Geo geo = geometry(a, wg);
     const TileBase tb = tile_base<BF16>(a, geo.row0);
-    float cmax[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) cmax[e] = 0.0f;
+    float cmax[4] = {0.0f, 0.0f, 0.0f, 0.0f};
 
     if (geo.active) {
-        float cold16[8];
-        load8(a.c + geo.col0, cold16);
+        float cold16[4];
+        load4(a.c + geo.col0, cold16);
         bool cols_tame = true;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
+        for (int e = 0; e < 4; ++e) {
             cols_tame = cols_tame && scale_is_tame(cold16[e]);
             cold16[e] *= 0.0625f;
         }
@@ -321,7 +356,7 @@ __device__ __forceinline__ void pass1_fast_tile(const Tensor4& a, const Hyper& h
         Row1<BF16> r0, r1, r2;
         if (il < n) r0 = load_row1<BF16>(tb, a, geo, il);
         if (il + stp < n) r1 = load_row1<BF16>(tb, a, geo, il + stp);
-        load_tables(s);               // the first rows' loads are in flight while the tables arrive
+        if constexpr (!TABLES_READY) load_tables(s);   // the first rows' loads are in flight meanwhile
         while (il < n) {
             if (il + 2 * stp < n) r2 = load_row1<BF16>(tb, a, geo, il + 2 * stp);
             pass1_row<BF16>(a, h, tb, geo, s, r0, il, cold16, cols_tame, cmax);
@@ -336,12 +371,12 @@ __device__ __forceinline__ void pass1_fast_tile(const Tensor4& a, const Hyper& h
             il += stp;
         }
     } else {
-        load_tables(s);               // keeps the workgroup's barriers matched
+        if constexpr (!TABLES_READY) load_tables(s);   // keeps the workgroup's barriers matched
     }
 
     // column maxima: combine the gy groups that share a column block, then one atomic per column
 #pragma unroll
-    for (int e = 0; e < 8; ++e) s.col[geo.grp * 128 + geo.l * 8 + e] = cmax[e];
+    for (int e = 0; e < 4; ++e) s.col[geo.grp * 128 + geo.l * 4 + e] = cmax[e];
     __syncthreads();
     for (int t = threadIdx.x; t < a.gx * 128; t += kThreads) {
         const int gi = t >> 7;
@@ -388,8 +423,8 @@ __device__ __forceinline__ void publish_if_last(const Tensor4& a, unsigned int m
 
 template <bool BF16>
 struct Row2 {                      // everything pass 2 reads for one row of one lane
-    GradRegs<BF16> g;
-    uint32_t vq;
+    GradRegs4<BF16> g;
+    uint32_t vq;                   // 16 bits: the lane's 4 codes
     float r_old, r_new;
 };
 
@@ -397,8 +432,8 @@ template <bool BF16>
 __device__ __forceinline__ Row2<BF16> load_row2(const TileBase& b, const Tensor4& a, const Geo& g, int il) {
     Row2<BF16> r;
     const uint32_t off4 = (uint32_t(il) * uint32_t(a.cols) + g.col0) * 4u;
-    r.g = load_grad_regs<BF16>(b.g, off4);
-    r.vq = ld<uint32_t>(b.vq, off4 >> 3);
+    r.g = load_grad_regs4<BF16>(b.g, off4);
+    r.vq = ld<uint16_t>(b.vq, off4 >> 3);
     r.r_old = ld<float>(b.r, uint32_t(il) * 4u);
     r.r_new = ld<float>(b.r_new, uint32_t(il) * 4u);
     return r;
@@ -406,18 +441,18 @@ __device__ __forceinline__ Row2<BF16> load_row2(const TileBase& b, const Tensor4
 
 template <bool BF16>
 __device__ __forceinline__ uint32_t pass2_row(const Tensor4& a, const Hyper& h, const Geo& geo,
-                                              const Row2<BF16>& row, const float cold16[8],
-                                              const float inv_cnew[8], bool cols_tame) {
-    float g[8], vt[8];
-    unpack_grad<BF16>(row.g, g);
+                                              const Row2<BF16>& row, const float cold16[4],
+                                              const float inv_cnew[4], bool cols_tame) {
+    float g[4], vt[4];
+    unpack_grad4<BF16>(row.g, g);
     const bool tame = cols_tame && scale_is_tame(row.r_old) && scale_is_tame(row.r_new);
     const bool fast = __ballot(!tame) == 0;
     if (__builtin_expect(fast, 1)) {
-        float qf[8];
-        codes_to_float(row.vq, qf);
+        float qf[4];
+        codes_to_float4(row.vq, qf);
         const float r16 = row.r_old * 0.0625f;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) vt[e] = moment_v(h, dequant_v16(qf[e], min_nonneg(r16, cold16[e])), g[e]);
+        for (int e = 0; e < 4; ++e) vt[e] = moment_v(h, dequant_v16(qf[e], min_nonneg(r16, cold16[e])), g[e]);
         const float inv_r = approx_inv(row.r_new);
         // even elements collect in the bytes of `lo`, odd ones in `hi`; word = lo | hi << 4
         uint32_t lo = 0, hi = 0;
@@ -427,22 +462,22 @@ __device__ __forceinline__ uint32_t pass2_row(const Tensor4& a, const Hyper& h, 
         hi = quant_v_code_fast<K>(vt[2 * K + 1], max_nonneg(inv_r, inv_cnew[2 * K + 1]), hi, fb);         \
         fmin_ = fminf(fminf(fmin_, fa), fb);                                                              \
         fmax_ = fmaxf(fmaxf(fmax_, fa), fb);
-        LPMM_V2(0) LPMM_V2(1) LPMM_V2(2) LPMM_V2(3)
+        LPMM_V2(0) LPMM_V2(1)
 #undef LPMM_V2
         const bool near = fmin_ < kMarginV || fmax_ > 1.0f - kMarginV;
         if (__builtin_expect(__ballot(near) == 0, 1)) return lo | (hi << 4);
     } else {
-        float cold[8];
-        load8(a.c + geo.col0, cold);
+        float cold[4];
+        load4(a.c + geo.col0, cold);
 #pragma unroll
-        for (int e = 0; e < 8; ++e)
+        for (int e = 0; e < 4; ++e)
             vt[e] = moment_v(h, dequant_v((row.vq >> (4 * e)) & 15u, fminf(row.r_old, cold[e])), g[e]);
     }
-    float cnew[8];
-    load8(a.c_new + geo.col0, cnew);
+    float cnew[4];
+    load4(a.c_new + geo.col0, cnew);
     uint32_t out = 0;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) out |= quant_v_code(vt[e], fminf(row.r_new, cnew[e])) << (4 * e);
+    for (int e = 0; e < 4; ++e) out |= quant_v_code(vt[e], fminf(row.r_new, cnew[e])) << (4 * e);
     return out;
 }
 
@@ -451,12 +486,12 @@ __device__ __forceinline__ void pass2_fast_tile(const Tensor4& a, const Hyper& h
     const Geo geo = geometry(a, wg);
     if (!geo.active) return;
     const TileBase tb = tile_base<BF16>(a, geo.row0);
-    float cold16[8], inv_cnew[8];
-    load8(a.c + geo.col0, cold16);
-    load8(a.c_new + geo.col0, inv_cnew);
+    float cold16[4], inv_cnew[4];
+    load4(a.c + geo.col0, cold16);
+    load4(a.c_new + geo.col0, inv_cnew);
     bool cols_tame = true;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
+    for (int e = 0; e < 4; ++e) {
         cols_tame = cols_tame && scale_is_tame(cold16[e]) && scale_is_tame(inv_cnew[e]);
         cold16[e] *= 0.0625f;
         inv_cnew[e] = approx_inv(inv_cnew[e]);
@@ -472,11 +507,11 @@ __device__ __forceinline__ void pass2_fast_tile(const Tensor4& a, const Hyper& h
         Row2<BF16> n0, n1;
         if (j0 < geo.n_rows) n0 = load_row2<BF16>(tb, a, geo, j0);
         if (j1 < geo.n_rows) n1 = load_row2<BF16>(tb, a, geo, j1);
-        const uint32_t off = (uint32_t(il) * uint32_t(a.cols) + geo.col0) >> 1;     // byte offset of the code word
-        st<uint32_t>(tb.vq, off, pass2_row<BF16>(a, h, geo, c0, cold16, inv_cnew, cols_tame));
+        const uint32_t off = (uint32_t(il) * uint32_t(a.cols) + geo.col0) >> 1;     // byte offset of the lane's codes
+        st<uint16_t>(tb.vq, off, uint16_t(pass2_row<BF16>(a, h, geo, c0, cold16, inv_cnew, cols_tame)));
         if (il + stride < geo.n_rows)
-            st<uint32_t>(tb.vq, off + ((uint32_t(stride) * uint32_t(a.cols)) >> 1),
-                         pass2_row<BF16>(a, h, geo, c1, cold16, inv_cnew, cols_tame));
+            st<uint16_t>(tb.vq, off + ((uint32_t(stride) * uint32_t(a.cols)) >> 1),
+                         uint16_t(pass2_row<BF16>(a, h, geo, c1, cold16, inv_cnew, cols_tame)));
         c0 = n0;
         c1 = n1;
         il = j0;
@@ -650,7 +685,7 @@ __global__ __launch_bounds__(kThreads) void pass1_fast(const Tensor4 a, const Hy
     __shared__ Lds s;
     const int wg = logical_wg();
     if (wg >= a.n_wg) return;
-    pass1_fast_tile<BF16>(a, h, wg, s);
+    pass1_fast_tile<BF16, false>(a, h, wg, s);
 }
 
 template <bool BF16>
@@ -711,23 +746,28 @@ __device__ __forceinline__ Segment find_segment(const Segment* seg, int n_seg, i
     return r;
 }
 
-template <bool BF16>
+// ROLES: 0 = A and B work interleaved in one launch; 1 = A work only; 2 = B work only.  The
+// single-role kernels exist because a kernel's register and LDS footprint is that of its heaviest
+// path: launched on their own (on a second stream), the light pass-2 workgroups fit into the
+// register space that the resident pass-1 workgroups leave free.
+template <bool BF16, int ROLES>
 __global__ __launch_bounds__(kThreads) void phase_kernel(const Phase ph, const Hyper h) {
-    __shared__ Lds s;
     const int x = logical_wg();
-    const int n = ph.n_a + ph.n_b;
+    const int n = (ROLES == 2 ? 0 : ph.n_a) + (ROLES == 1 ? 0 : ph.n_b);
     if (x >= n) return;
     // B workgroups sit at the positions where floor(x * n_b / n) steps up
-    const int b_before = int((int64_t(x) * ph.n_b) / n);
-    const int b_after = int((int64_t(x + 1) * ph.n_b) / n);
-    if (b_after > b_before) {
+    const int b_before = ROLES == 1 ? 0 : (ROLES == 2 ? x : int((int64_t(x) * ph.n_b) / n));
+    const int b_after = ROLES == 1 ? 0 : (ROLES == 2 ? x + 1 : int((int64_t(x + 1) * ph.n_b) / n));
+    if (ROLES != 1 && b_after > b_before) {
+        __shared__ int s_last;
         const Segment sg = find_segment(ph.seg_b, ph.n_seg_b, b_before);
         const Tensor4 a = ph.tensors[sg.tensor];
         const int wg = b_before - sg.wg_begin;
         if (a.kind == kQuantFast) pass2_fast_tile<BF16>(a, h, wg);
         else pass2_general_tile<BF16>(a, h, wg);
-        publish_if_last(a, wg, a.n_wg, s.last);
-    } else {
+        publish_if_last(a, wg, a.n_wg, s_last);
+    } else if (ROLES != 2) {
+        __shared__ Lds s;
         const int xa = x - b_before;
         const Segment sg = find_segment(ph.seg_a, ph.n_seg_a, xa);
         const Tensor4 a = ph.tensors[sg.tensor];
@@ -735,7 +775,7 @@ __global__ __launch_bounds__(kThreads) void phase_kernel(const Phase ph, const H
         if (a.kind == kFp32State) {
             adamw32_tile<BF16>(a.p, a.g, reinterpret_cast<float*>(a.mq), reinterpret_cast<float*>(a.vq), a.P, h, wg);
         } else if (a.kind == kQuantFast) {
-            pass1_fast_tile<BF16>(a, h, wg, s);
+            pass1_fast_tile<BF16, false>(a, h, wg, s);
         } else {
             load_tables(s);
             pass1_general_tile<BF16>(a, h, wg, s);

@@ -4,6 +4,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdlib>
 #include <memory>
@@ -112,26 +113,24 @@ int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 int pad8(int64_t n) { return int(round_up(n, kXcds)); }
 
 // Geometry of the fast path.  gx column blocks share a workgroup (so that one workgroup touches
-// whole 128-byte lines of codes and runs of block scales), gy = 16/gx groups walk interleaved
+// whole 128-byte lines of codes and runs of block scales), gy = 8/gx groups walk interleaved
 // rows of the same column blocks and combine their column maxima in LDS.  rw_hint > 0 fixes the
 // rows per workgroup; otherwise they are chosen so that the tensor alone fills the chip.
 void fast_geometry(Tensor4* a, int n_cu, int64_t rw_hint) {
     a->nb = int(a->cols / LPMM_BLOCK);
-    int gx = env_int("LPMM_GX", 4);
-    if (gx < 1 || gx > 16 || (gx & (gx - 1))) gx = 4;
+    int gx = env_int("LPMM_GX", 1);
+    if (gx < 1 || gx > kGroups || (gx & (gx - 1))) gx = 1;
     while (gx > 1 && (a->nb % gx) != 0) gx >>= 1;
     a->gx = gx;
-    a->gy = 16 / gx;
+    a->gy = kGroups / gx;
     a->strips = a->nb / gx;
     int64_t rw = env_int("LPMM_RW", 0);
     if (rw <= 0) rw = rw_hint;
     if (rw <= 0) {
-        // enough workgroups to fill the chip several times, and each group walks at least a few
-        // rows so that the column atomics and the table load are amortized
-        const int64_t target_wg = int64_t(n_cu) * env_int("LPMM_WG_PER_CU", 8);
-        rw = (a->rows * a->strips + target_wg - 1) / target_wg;
-        const int64_t min_rw = int64_t(a->gy) * 4;
-        if (rw < min_rw) rw = min_rw;
+        // tall tiles amortize a workgroup's start-up and its column atomics; shrink them only as
+        // far as needed to give every CU a couple of workgroups
+        rw = 64;
+        while (rw > a->gy && a->strips * ((a->rows + rw - 1) / rw) < 2 * int64_t(n_cu)) rw >>= 1;
     }
     const int64_t cap = (int64_t(1) << 29) / a->cols;     // lane offsets inside a tile stay below 2^31 bytes
     if (rw > cap) rw = cap;
@@ -222,7 +221,9 @@ int grid_for(int64_t items, int64_t per_thread, int max_blocks = 1 << 20) {
 
 struct PhaseLaunch {
     Phase ph;
-    int grid;
+    int grid;        // both kinds in one launch
+    int grid_a;      // A work alone
+    int grid_b;      // B work alone
 };
 
 struct PlanHost {
@@ -230,6 +231,16 @@ struct PlanHost {
     std::vector<PhaseLaunch> phases;
     bool bf16 = false;
     int device = 0;
+    // second stream for pass 2 (same priority as any other stream), with its ordering events
+    hipStream_t side = nullptr;
+    std::vector<hipEvent_t> ev_a;       // ev_a[j]: phase j's A work is complete
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    ~PlanHost() {
+        for (hipEvent_t e : ev_a) (void)hipEventDestroy(e);
+        if (ev_fork) (void)hipEventDestroy(ev_fork);
+        if (ev_join) (void)hipEventDestroy(ev_join);
+        if (side) (void)hipStreamDestroy(side);
+    }
 };
 
 std::unordered_map<void*, std::unique_ptr<PlanHost>> g_plans;
@@ -497,7 +508,7 @@ int lpmm_adamw4_plan_build(const lpmm_tensor_desc* descs, int64_t n, int grad_dt
     float* d_floats = reinterpret_cast<float*>(dplan + L.off_floats);
     unsigned int* d_counters = reinterpret_cast<unsigned int*>(dplan + L.off_counters);
 
-    const int64_t rw_hint = env_int("LPMM_MULTI_RW", 64);
+    const int64_t rw_hint = env_int("LPMM_MULTI_RW", 128);
     int64_t fofs = 0;
     for (int64_t i = 0; i < n; ++i) {
         const lpmm_tensor_desc& d = descs[i];
@@ -564,7 +575,16 @@ int lpmm_adamw4_plan_build(const lpmm_tensor_desc* descs, int64_t n, int grad_dt
         if (pl.ph.n_a + pl.ph.n_b == 0) continue;
         if (int64_t(pl.ph.n_a) + pl.ph.n_b > (int64_t(1) << 30)) return LPMM_EINVAL;
         pl.grid = pad8(int64_t(pl.ph.n_a) + pl.ph.n_b);
+        pl.grid_a = pad8(pl.ph.n_a);
+        pl.grid_b = pad8(pl.ph.n_b);
         host->phases.push_back(pl);
+    }
+    if (env_int("LPMM_MULTI_STREAMS", 2) >= 2) {
+        LPMM_HIP(hipStreamCreateWithFlags(&host->side, hipStreamNonBlocking));
+        LPMM_HIP(hipEventCreateWithFlags(&host->ev_fork, hipEventDisableTiming));
+        LPMM_HIP(hipEventCreateWithFlags(&host->ev_join, hipEventDisableTiming));
+        host->ev_a.resize(host->phases.size());
+        for (hipEvent_t& e : host->ev_a) LPMM_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
     }
 
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -591,12 +611,46 @@ int lpmm_adamw4_step_multi(void* plan, float lr, float beta1, float beta2, float
     LPMM_HIP(hipGetDevice(&dev));
     if (dev != host->device) return LPMM_EINVAL;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    const bool bf16 = host->bf16;
+    if (host->side) {
+        // A work of phase j on the caller's stream, B work (pass 2 of the tensors whose pass 1 ran
+        // in phase j-1) on the side stream behind an event; the caller's stream rejoins at the end.
+        hipStream_t s2 = host->side;
+        LPMM_HIP(hipEventRecord(host->ev_fork, s));
+        LPMM_HIP(hipStreamWaitEvent(s2, host->ev_fork, 0));
+        for (size_t j = 0; j < host->phases.size(); ++j) {
+            const PhaseLaunch& pl = host->phases[j];
+            if (pl.ph.n_b > 0) {
+                LPMM_HIP(hipStreamWaitEvent(s2, host->ev_a[j - 1], 0));
+                if (bf16) hipLaunchKernelGGL((phase_kernel<true, 2>), dim3(pl.grid_b), dim3(kThreads), 0, s2, pl.ph, h);
+                else hipLaunchKernelGGL((phase_kernel<false, 2>), dim3(pl.grid_b), dim3(kThreads), 0, s2, pl.ph, h);
+                LPMM_HIP(hipGetLastError());
+            }
+            if (pl.ph.n_a > 0) {
+                const bool rec = g_prof.on && g_prof.calls < g_prof.max_calls;
+                const int64_t call = g_prof.calls;
+                if (rec) LPMM_HIP(hipEventRecord(prof_event(call, 0), s));
+                if (bf16) hipLaunchKernelGGL((phase_kernel<true, 1>), dim3(pl.grid_a), dim3(kThreads), 0, s, pl.ph, h);
+                else hipLaunchKernelGGL((phase_kernel<false, 1>), dim3(pl.grid_a), dim3(kThreads), 0, s, pl.ph, h);
+                LPMM_HIP(hipGetLastError());
+                if (rec) {
+                    LPMM_HIP(hipEventRecord(prof_event(call, 1), s));
+                    LPMM_HIP(hipEventRecord(prof_event(call, 2), s));
+                    g_prof.calls = call + 1;
+                }
+            }
+            LPMM_HIP(hipEventRecord(host->ev_a[j], s));
+        }
+        LPMM_HIP(hipEventRecord(host->ev_join, s2));
+        LPMM_HIP(hipStreamWaitEvent(s, host->ev_join, 0));
+        return LPMM_OK;
+    }
     for (const PhaseLaunch& pl : host->phases) {
         const bool rec = g_prof.on && g_prof.calls < g_prof.max_calls;
         const int64_t call = g_prof.calls;
         if (rec) LPMM_HIP(hipEventRecord(prof_event(call, 0), s));
-        if (host->bf16) hipLaunchKernelGGL(phase_kernel<true>, dim3(pl.grid), dim3(kThreads), 0, s, pl.ph, h);
-        else hipLaunchKernelGGL(phase_kernel<false>, dim3(pl.grid), dim3(kThreads), 0, s, pl.ph, h);
+        if (bf16) hipLaunchKernelGGL((phase_kernel<true, 0>), dim3(pl.grid), dim3(kThreads), 0, s, pl.ph, h);
+        else hipLaunchKernelGGL((phase_kernel<false, 0>), dim3(pl.grid), dim3(kThreads), 0, s, pl.ph, h);
         LPMM_HIP(hipGetLastError());
         if (rec) {
             LPMM_HIP(hipEventRecord(prof_event(call, 1), s));
