@@ -159,9 +159,17 @@ def main():
             "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
             "bytes_per_param": bp1, "launches": n_calls, "avg_launch_ms": round(avg_ms, 5),
             "bytes_per_launch": round(bytes_per_launch),
+            "traffic_source": None,
             "note": "pass 2 of the neighbouring tensor group (%.1f B/param) runs concurrently and shares "
                     "the bandwidth; whole-step figures are in config" % bp2,
         }
+        # HBM bytes per launch measured offline with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/)
+        tpath = os.path.join(ROOT, "profiles", "traffic_phase_kernel_%s.json" % args.config)
+        if os.path.exists(tpath):
+            tr = json.load(open(tpath))
+            if tr.get("launches_per_step") == n_calls // max(args.steps, 1):
+                roofline["traffic"] = tr["hbm_bytes_per_launch"]
+                roofline["traffic_source"] = "profiles/" + os.path.basename(tpath)
     else:
         p1_avg_ms = p1_ms / launches
         p1_bytes_per_launch = bp1 * n_quant * args.steps / launches
