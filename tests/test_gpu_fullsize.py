@@ -1,0 +1,153 @@
+"""GPU parity at the full sizes of the benchmark configurations, in the launch configuration that
+bench.py times (one multi-tensor plan).  Where the oracle can afford the whole set (configs 2-4) every
+tensor is compared element by element for a few steps; for the LLaMA-7B-shaped set (config 5) the plan
+holds all 291 tensors, a sample of tensors (one of every distinct matrix shape) is fed identical
+host-generated inputs and compared element by element, and every quantized tensor is checked through
+properties that hold at any size."""
+import concurrent.futures as cf
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2309_01507_amd as lpmm
+import workloads
+from gpu_util import DEV, PARAM_ATOL, PARAM_RTOL, compare_step, download_state, to_dev
+
+pytestmark = pytest.mark.gpu
+HP = oracle.Hyper()
+POOL = cf.ThreadPoolExecutor(max_workers=8)        # the oracle is single-threaded C++; tensors are independent
+
+
+@pytest.fixture(autouse=True)
+def _announce(request):
+    print(f"\n[gpu-test] {request.node.name}", flush=True)
+    yield
+    torch.cuda.synchronize()
+
+
+def _oracle_step(job):
+    sp, w_ref, st_ref, g, t = job
+    if sp.quantized:
+        return oracle.adamw4_step(w_ref, g, st_ref, HP, t, want_moments=True)
+    oracle.adamw32_step(w_ref, g, st_ref[0], st_ref[1], HP, t)
+    return None, None
+
+
+def _full_set_parity(config, steps, seed):
+    specs = workloads.param_set(config)
+    recipe, bf16 = workloads.GRAD_RECIPE[config], workloads.GRAD_BF16[config]
+    lpmm.ensure_init(4096)
+    dev_t, ref_t, descs = [], [], []
+    for tid, sp in enumerate(specs):
+        w_ref = workloads.weights(seed, tid, sp.rows, sp.cols).reshape(-1)
+        w = to_dev(w_ref.copy())
+        g = torch.empty(sp.numel, dtype=torch.bfloat16 if bf16 else torch.float32, device=DEV)
+        if sp.quantized:
+            st, st_ref = lpmm.new_state(sp.rows, sp.cols, DEV), oracle.state_zero(sp.rows, sp.cols)
+        else:
+            st = (torch.zeros(sp.numel, device=DEV), torch.zeros(sp.numel, device=DEV))
+            st_ref = (np.zeros(sp.numel, np.float32), np.zeros(sp.numel, np.float32))
+        descs.append(lpmm.make_desc(w, g, st, sp.rows, sp.cols))
+        dev_t.append((w, g, st))
+        ref_t.append((w_ref, st_ref))
+    plan = lpmm.new_plan(descs, 1 if bf16 else 0, DEV)
+    for t in range(1, steps + 1):
+        grads = list(POOL.map(lambda a: workloads.grads(seed, a[0], t, a[1].rows, a[1].cols, recipe, bf16).reshape(-1),
+                              enumerate(specs)))
+        for (w, g, st), gn in zip(dev_t, grads):
+            g.copy_(to_dev(gn, bf16))
+        lpmm.lpmm_adamw4_step_multi(plan, HP.lr, HP.beta1, HP.beta2, HP.eps, HP.weight_decay, t)
+        moments = list(POOL.map(_oracle_step, [(sp, wr, sr, gn, t) for sp, (wr, sr), gn in zip(specs, ref_t, grads)]))
+        torch.cuda.synchronize()
+        for sp, (w, g, st), (w_ref, st_ref), (mt, vt) in zip(specs, dev_t, ref_t, moments):
+            tag = f"{config} {sp.name} step {t}"
+            if sp.quantized:
+                assert compare_step(download_state(st), st_ref, w.cpu().numpy(), w_ref, mt, vt, tag) == 0
+            else:
+                np.testing.assert_array_equal(st[0].cpu().numpy(), st_ref[0], err_msg=tag)
+                np.testing.assert_array_equal(st[1].cpu().numpy(), st_ref[1], err_msg=tag)
+                np.testing.assert_allclose(w.cpu().numpy(), w_ref, rtol=PARAM_RTOL, atol=PARAM_ATOL, err_msg=tag)
+    lpmm.lpmm_adamw4_plan_release(plan)
+
+
+def test_config2_bert_base_full_set():
+    _full_set_parity("c2_bert_base", steps=2, seed=21)
+
+
+def test_config3_outlier_matrix_full_size():
+    _full_set_parity("c3_outlier_32000x4096", steps=3, seed=22)
+
+
+def test_config4_gpt2_medium_full_set_bf16():
+    _full_set_parity("c4_gpt2_medium", steps=2, seed=23)
+
+
+def _check_invariants(sp, st, tag):
+    """Properties of a valid 4-bit state that hold at any size: the rank-1 statistics are exactly the
+    row / column maxima of the decompressed second moment, its zero point is absent, and every block
+    of the decompressed first moment stays within its scale."""
+    P = sp.numel
+    out = torch.empty(P, dtype=torch.float32, device=DEV)
+    lpmm.lpmm_dequant_state(1, st.v_codes, st.v_rowmax, st.v_colmax, sp.rows, sp.cols, out)
+    v = out.view(sp.rows, sp.cols)
+    assert torch.equal(v.max(dim=1).values, st.v_rowmax), tag + ": row maxima"
+    assert torch.equal(v.max(dim=0).values, st.v_colmax), tag + ": column maxima"
+    sc = torch.minimum(st.v_rowmax[:, None], st.v_colmax[None, :])
+    assert bool((v >= 0.0625 * sc).all()), tag + ": zero point"
+    del v, sc
+    lpmm.lpmm_dequant_state(0, st.m_codes, st.m_blockscale, None, sp.rows, sp.cols, out)
+    mb = out.view(-1, 128).abs().max(dim=1).values
+    assert bool((mb <= st.m_blockscale).all()) and bool((mb >= 0.8875 * st.m_blockscale * (1 - 1e-6)).all()), \
+        tag + ": block scales"
+
+
+def test_config5_llama_7b_plan_sampled_tensors_and_invariants():
+    config, seed, steps = "c5_llama_7b", 24, 2
+    specs = workloads.param_set(config)
+    sampled = {"l0.q": None, "l0.gate": None, "l0.down": None}            # every distinct layer shape
+    lpmm.ensure_init(4096)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(seed)
+    dev_t, descs = [], []
+    for tid, sp in enumerate(specs):
+        if sp.name in sampled:
+            w_ref = workloads.weights(seed, tid, sp.rows, sp.cols).reshape(-1)
+            sampled[sp.name] = (tid, sp, w_ref, oracle.state_zero(sp.rows, sp.cols))
+            w = to_dev(w_ref.copy())
+        else:
+            w = torch.randn(sp.numel, generator=gen, device=DEV) * 0.02
+        g = torch.empty(sp.numel, dtype=torch.bfloat16, device=DEV)
+        if sp.quantized:
+            st = lpmm.new_state(sp.rows, sp.cols, DEV)
+        else:
+            st = (torch.zeros(sp.numel, device=DEV), torch.zeros(sp.numel, device=DEV))
+        descs.append(lpmm.make_desc(w, g, st, sp.rows, sp.cols))
+        dev_t.append((sp, w, g, st))
+    plan = lpmm.new_plan(descs, 1, DEV)
+    for t in range(1, steps + 1):
+        host_g = {}
+        for name, (tid, sp, w_ref, st_ref) in sampled.items():
+            host_g[name] = workloads.grads(seed, tid, t, sp.rows, sp.cols, "col_lognormal", True).reshape(-1)
+        for sp, w, g, st in dev_t:
+            if sp.name in sampled:
+                g.copy_(to_dev(host_g[sp.name], True))
+            else:
+                sigma = 1e-3 * torch.exp(torch.randn(sp.cols, generator=gen, device=DEV))
+                g.copy_((torch.randn(sp.rows, sp.cols, generator=gen, device=DEV) * sigma[None, :]).reshape(-1))
+        lpmm.lpmm_adamw4_step_multi(plan, HP.lr, HP.beta1, HP.beta2, HP.eps, HP.weight_decay, t)
+        jobs = [(sp, w_ref, st_ref, host_g[name], t) for name, (tid, sp, w_ref, st_ref) in sampled.items()]
+        moments = list(POOL.map(_oracle_step, jobs))
+        torch.cuda.synchronize()
+        by_name = {sp.name: (w, st) for sp, w, g, st in dev_t}
+        for (name, (tid, sp, w_ref, st_ref)), (mt, vt) in zip(sampled.items(), moments):
+            w, st = by_name[name]
+            assert compare_step(download_state(st), st_ref, w.cpu().numpy(), w_ref, mt, vt,
+                                f"c5 {name} step {t}") == 0
+    # properties, on a spread of tensors including both 32000 x 4096 matrices
+    for sp, w, g, st in dev_t:
+        if sp.quantized and (sp.name in ("embed", "lm_head") or sp.name.startswith(("l0.", "l17.", "l31."))):
+            _check_invariants(sp, st, f"c5 {sp.name}")
+    lpmm.lpmm_adamw4_plan_release(plan)
