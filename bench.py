@@ -38,6 +38,8 @@ def main():
     ap.add_argument("--config", default="c5_llama_7b")
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--grad-dtype", choices=["config", "bf16", "f32"], default="config",
+                    help="override the gradient type of the configuration (experiments)")
     ap.add_argument("--launch", choices=["multi", "per-tensor"], default="multi",
                     help="multi: one plan, pass 1 / pass 2 of neighbouring tensor groups share launches; "
                          "per-tensor: two launches per quantized tensor")
@@ -56,7 +58,7 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     specs = workloads.param_set(args.config)
-    bf16 = workloads.GRAD_BF16[args.config]
+    bf16 = workloads.GRAD_BF16[args.config] if args.grad_dtype == "config" else args.grad_dtype == "bf16"
     recipe = workloads.GRAD_RECIPE[args.config]
     lr, b1, b2, eps, wd = 1e-3, 0.9, 0.999, 1e-8, 0.01
 

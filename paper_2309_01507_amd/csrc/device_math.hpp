@@ -126,35 +126,43 @@ __device__ __forceinline__ uint32_t quant_v_code(float vt, float sc) {
 constexpr float kScaleLo = 0x1p-100f;
 constexpr float kScaleHi = 0x1p100f;
 
+// branch-free: zero, or bits inside [bits(2^-100), bits(2^100)] (scales are never negative)
 __device__ __forceinline__ bool scale_is_tame(float s) {
-    return s == 0.0f || (s >= kScaleLo && s <= kScaleHi);
+    const uint32_t u = __float_as_uint(s);
+    constexpr uint32_t lo = 0x0D800000u, hi = 0x71800000u;     // 2^-100, 2^100
+    return bool(int(u - lo <= hi - lo) | int(u == 0u));
 }
 __device__ __forceinline__ float approx_inv(float s) {
     return s == 0.0f ? 0.0f : __builtin_amdgcn_rcpf(s);
 }
 
-// first moment: `slack` = |n' - thr| * 2^21 - |thr| for the one threshold of the bucket; negative
-// means the approximate n' is within 2^-21 |thr| of it and may sit on the wrong side
+// first moment: `dist` = |bits(n') - bits(thr)| for the one threshold of the bucket, i.e. their
+// distance in units in the last place (same sign and neighbouring magnitudes inside a bucket).  The
+// exact n can lie at most 4 ulp of thr away from n' (2^-22 |thr|, an ulp being at least 2^-24 |thr|),
+// so 16 or more -- which stays at least 8 ulp of thr when the two straddle a power of two -- is safe.
+constexpr uint32_t kMinDistM = 16;
+
 __device__ __forceinline__ uint32_t quant_m_code_fast(const SearchEntry* s_search, float mt, float inv_s,
-                                                      float& slack) {
+                                                      uint32_t& dist) {
     const float n = mt * inv_s;
     const SearchEntry e = s_search[__float_as_uint(n) >> kBucketShift];
-    slack = __builtin_fmaf(fabsf(n - e.thr), 0x1p21f, -fabsf(e.thr));
+    dist = __usad(__float_as_uint(n), __float_as_uint(e.thr), 0u);
     return e.base + (n > e.thr ? 1u : 0u);
 }
 
 // second moment: boundaries of the Linear map are the integers of f = 16 n - 1.5 and the code is
 // ceil(f).  The approximate f' is within 2^-17 of the exact one; away from integers
 // round-to-nearest(f' + 0.5) equals ceil(f), and the saturating byte convert both rounds that way and
-// clamps below at 0 (above, n <= 1 keeps the code at 15).  `fr` returns fract(f'): a value within
-// 2^-16 of 0 or 1 sends the row to the exact path.
+// clamps below at 0 (above, n <= 1 keeps the code at 15).  `off` returns fract(f' + 0.5) - 0.5, the
+// signed distance of f' from the integer it is closest to when that distance is small: a magnitude
+// below 2^-16 sends the row to the exact path.
 constexpr float kMarginV = 0x1p-16f;
 
 template <int BYTE>
-__device__ __forceinline__ uint32_t quant_v_code_fast(float vt, float inv_sc, uint32_t packed, float& fr) {
-    const float n = vt * inv_sc;
-    fr = __builtin_amdgcn_fractf(__builtin_fmaf(16.0f, n, -1.5f));
-    return __builtin_amdgcn_cvt_pk_u8_f32(__builtin_fmaf(16.0f, n, -1.0f), BYTE, packed);
+__device__ __forceinline__ uint32_t quant_v_code_fast(float vt, float inv_sc, uint32_t packed, float& off) {
+    const float x = __builtin_fmaf(16.0f, vt * inv_sc, -1.0f);      // f' + 0.5
+    off = __builtin_amdgcn_fractf(x) - 0.5f;                       // 0 when f' sits on an integer
+    return __builtin_amdgcn_cvt_pk_u8_f32(x, BYTE, packed);
 }
 
 // second-moment decompress with the scale already divided by 16 (exact for tame scales):
@@ -164,9 +172,7 @@ __device__ __forceinline__ float dequant_v16(float qf, float s16) { return __bui
 // ---- float maximum through an integer atomic (values >= +0 only: bit order == value order) --------
 
 __device__ __forceinline__ void atomic_max_nonneg(float* addr, float v) {
-#ifndef LPMM_EXPERIMENT_NO_ATOMICS
     atomicMax(reinterpret_cast<unsigned int*>(addr), __float_as_uint(v));
-#endif
 }
 
 }  // namespace lpmm

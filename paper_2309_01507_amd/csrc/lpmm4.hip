@@ -550,7 +550,7 @@ int lpmm_adamw4_plan_build(const lpmm_tensor_desc* descs, int64_t n, int grad_dt
     }
 
     // groups of consecutive tensors; phase j = A work of group j + B work of group j-1
-    const int64_t group_params = int64_t(env_int("LPMM_PHASE_MPARAMS", 128)) << 20;
+    const int64_t group_params = int64_t(env_int("LPMM_PHASE_MPARAMS", 256)) << 20;
     std::vector<std::pair<int64_t, int64_t>> groups;      // [first, last)
     for (int64_t i = 0; i < n;) {
         int64_t j = i, acc = 0;
