@@ -97,10 +97,18 @@ __device__ __forceinline__ float param_update(const Hyper& h, float w, float mt,
 
 // ---- compress ------------------------------------------------------------------------------------
 
+// bucket table entry of a normalized value with |n| <= 1 + 2^-22 (block absmax normalization
+// guarantees it for finite input; a wild index could only come from non-finite input and reads LDS,
+// which cannot fault): round(256 n) lands in the low bits of the fused multiply-add's result
+__device__ __forceinline__ SearchEntry search_entry(const SearchEntry* s_search, float n) {
+    const float x = __builtin_fmaf(n, kBucketScale, kBucketMagic);
+    return s_search[int(__float_as_uint(x) - kBucketMagicBits) + kBucketHalf];
+}
+
 // first moment: n = m_t / s (0 when the block is all zero), code from the bucket table in LDS
 __device__ __forceinline__ uint32_t quant_m_code(const SearchEntry* s_search, float mt, float s) {
     const float n = (s == 0.0f) ? 0.0f : mt / s;
-    const SearchEntry e = s_search[__float_as_uint(n) >> kBucketShift];
+    const SearchEntry e = search_entry(s_search, n);
     return e.base + (n > e.thr ? 1u : 0u);
 }
 
@@ -137,7 +145,9 @@ __device__ __forceinline__ float approx_inv(float s) {
 }
 
 // first moment: `dist` = |bits(n') - bits(thr)| for the one threshold of the bucket, i.e. their
-// distance in units in the last place (same sign and neighbouring magnitudes inside a bucket).  The
+// distance in units in the last place (a bucket that holds a threshold lies on one side of zero, so
+// the two have the same sign and bit patterns order like magnitudes; buckets without one compare
+// against a far-away constant).  The
 // exact n can lie at most 4 ulp of thr away from n' (2^-22 |thr|, an ulp being at least 2^-24 |thr|),
 // so 16 or more -- which stays at least 8 ulp of thr when the two straddle a power of two -- is safe.
 constexpr uint32_t kMinDistM = 16;
@@ -145,7 +155,7 @@ constexpr uint32_t kMinDistM = 16;
 __device__ __forceinline__ uint32_t quant_m_code_fast(const SearchEntry* s_search, float mt, float inv_s,
                                                       uint32_t& dist) {
     const float n = mt * inv_s;
-    const SearchEntry e = s_search[__float_as_uint(n) >> kBucketShift];
+    const SearchEntry e = search_entry(s_search, n);
     dist = __usad(__float_as_uint(n), __float_as_uint(e.thr), 0u);
     return e.base + (n > e.thr ? 1u : 0u);
 }

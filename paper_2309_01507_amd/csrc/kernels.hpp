@@ -23,7 +23,7 @@ namespace lpmm {
 
 // Lookup tables, uploaded once per device at init.
 __device__ float d_byte_decode[512];          // entry b: {T_DE[b & 15], T_DE[b >> 4]}
-__device__ SearchEntry d_search[kBuckets];    // nearest-entry search for the DE map
+__device__ SearchEntry d_search[kBucketsPadded];    // nearest-entry search for the DE map
 
 enum TensorKind : int { kQuantFast = 0, kQuantGeneral = 1, kFp32State = 2 };
 
@@ -44,8 +44,12 @@ struct Tensor4 {
     int gx, gy;             // a workgroup's 8 groups: gx column blocks x gy row phases
     int rw;                 // rows per workgroup tile; rw * cols < 2^29
     int strips;             // nb / gx
-    int n_wg;               // workgroups per pass
+    int n_wg;               // workgroups of pass 1 (general path: of either pass)
     int kind;
+    // pass 2 of the fast path has its own tiling: strips of 256 columns, rw2 rows per workgroup
+    int strips2;            // ceil(nb / 2)
+    int rw2;                // rw2 * cols < 2^29
+    int n_wg2;              // workgroups of pass 2
     int pad_;
 };
 
@@ -62,7 +66,7 @@ __device__ __forceinline__ int logical_wg() {
 
 struct Lds {
     float2 deq[256];
-    SearchEntry search[kBuckets];
+    SearchEntry search[kBucketsPadded];
     float col[8 * 128];
 };
 
@@ -71,7 +75,7 @@ __device__ __forceinline__ void load_tables(Lds& s) {
     for (int i = threadIdx.x; i < 256; i += kThreads) s.deq[i] = gd[i];
     const uint2* gs = reinterpret_cast<const uint2*>(d_search);
     uint2* ss = reinterpret_cast<uint2*>(s.search);
-    for (int i = threadIdx.x; i < kBuckets; i += kThreads) ss[i] = gs[i];
+    for (int i = threadIdx.x; i < kBucketsPadded; i += kThreads) ss[i] = gs[i];
     __syncthreads();
 }
 
@@ -409,6 +413,25 @@ constexpr int kTicketLanes = 32;
 constexpr int kTicketStride = 32;                                  // in 32-bit words: 128 bytes
 constexpr int kCounterWords = (1 + kTicketLanes) * kTicketStride;  // per tensor
 
+// dst[i] = src[i]; src[i] = 0 by one workgroup.  It runs alone at the end of a tensor's pass 2, so
+// what counts is latency: 16 loads per thread are in flight before the first store.
+__device__ __forceinline__ void move_and_clear(float* dst, float* src, int64_t n) {
+    constexpr int kDepth = 16;
+    for (int64_t base = threadIdx.x; base < n; base += int64_t(kThreads) * kDepth) {
+        float v[kDepth];
+#pragma unroll
+        for (int u = 0; u < kDepth; ++u) {
+            const int64_t i = base + int64_t(u) * kThreads;
+            v[u] = i < n ? src[i] : 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < kDepth; ++u) {
+            const int64_t i = base + int64_t(u) * kThreads;
+            if (i < n) { dst[i] = v[u]; src[i] = 0.0f; }
+        }
+    }
+}
+
 __device__ __forceinline__ void publish_if_last(const Tensor4& a, unsigned int me, unsigned int participants,
                                                 int& s_last) {
     __syncthreads();
@@ -428,22 +451,27 @@ __device__ __forceinline__ void publish_if_last(const Tensor4& a, unsigned int m
     }
     __syncthreads();
     if (!s_last) return;
-    for (int64_t i = threadIdx.x; i < a.rows; i += kThreads) { a.r[i] = a.r_new[i]; a.r_new[i] = 0.0f; }
-    for (int64_t j = threadIdx.x; j < a.cols; j += kThreads) { a.c[j] = a.c_new[j]; a.c_new[j] = 0.0f; }
+    move_and_clear(a.r, a.r_new, a.rows);
+    move_and_clear(a.c, a.c_new, a.cols);
     if (threadIdx.x == 0) *a.counter = 0u;
 }
 
+// Pass 2 of the fast path.  Nothing here is reduced over a block, so the layout is chosen for the
+// memory system and for cheap row bookkeeping instead: a wave works on 256 consecutive columns of
+// ONE row (lane l owns columns 4l .. 4l+3 of the strip; 128 contiguous bytes of codes, 512 of bf16
+// gradient), the four waves of a workgroup take rows w, w+4, ... of the tile.  The row index, the two
+// row maxima and everything derived from them are wave-uniform and live in scalar registers.
 template <bool BF16>
 struct Row2 {                      // everything pass 2 reads for one row of one lane
     GradRegs4<BF16> g;
     uint32_t vq;                   // 16 bits: the lane's 4 codes
-    float r_old, r_new;
+    float r_old, r_new;            // the same value in every lane
 };
 
 template <bool BF16>
-__device__ __forceinline__ Row2<BF16> load_row2(const TileBase& b, const Tensor4& a, const Geo& g, int il) {
+__device__ __forceinline__ Row2<BF16> load_row2(const TileBase& b, const Tensor4& a, uint32_t col0, int il) {
     Row2<BF16> r;
-    const uint32_t off4 = (uint32_t(il) * uint32_t(a.cols) + g.col0) * 4u;
+    const uint32_t off4 = (uint32_t(il) * uint32_t(a.cols) + col0) * 4u;
     r.g = load_grad_regs4<BF16>(b.g, off4);
     r.vq = ld<uint16_t>(b.vq, off4 >> 3);
     r.r_old = ld<float>(b.r, uint32_t(il) * 4u);
@@ -451,21 +479,26 @@ __device__ __forceinline__ Row2<BF16> load_row2(const TileBase& b, const Tensor4
     return r;
 }
 
+__device__ __forceinline__ float wave_uniform(float v) {
+    return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(v)));
+}
+
+// new codes of the lane's 4 elements of one row
 template <bool BF16>
-__device__ __forceinline__ uint32_t pass2_row(const Tensor4& a, const Hyper& h, const Geo& geo,
+__device__ __forceinline__ uint32_t pass2_row(const Tensor4& a, const Hyper& h, uint32_t col0,
                                               const Row2<BF16>& row, const float cold16[4],
                                               const float inv_cnew[4], bool cols_tame) {
+    const float r_old = wave_uniform(row.r_old), r_new = wave_uniform(row.r_new);
     float g[4], vt[4];
     unpack_grad4<BF16>(row.g, g);
-    const bool tame = bool(int(cols_tame) & int(scale_is_tame(row.r_old)) & int(scale_is_tame(row.r_new)));
-    const bool fast = __ballot(!tame) == 0;
-    if (__builtin_expect(fast, 1)) {
+    // cols_tame is wave-uniform: the whole wave takes one route
+    if (__builtin_expect(cols_tame && scale_is_tame(r_old) && scale_is_tame(r_new), 1)) {
         float qf[4];
         codes_to_float4(row.vq, qf);
-        const float r16 = row.r_old * 0.0625f;
+        const float r16 = r_old * 0.0625f;
 #pragma unroll
         for (int e = 0; e < 4; ++e) vt[e] = moment_v(h, dequant_v16(qf[e], min_nonneg(r16, cold16[e])), g[e]);
-        const float inv_r = approx_inv(row.r_new);
+        const float inv_r = approx_inv(r_new);
         // even elements collect in the bytes of `lo`, odd ones in `hi`; word = lo | hi << 4
         uint32_t lo = 0, hi = 0;
         float closest = 0.5f, fa, fb;
@@ -478,53 +511,64 @@ __device__ __forceinline__ uint32_t pass2_row(const Tensor4& a, const Hyper& h, 
         if (__builtin_expect(__ballot(closest < kMarginV) == 0, 1)) return lo | (hi << 4);
     } else {
         float cold[4];
-        load4(a.c + geo.col0, cold);
+        load4(a.c + col0, cold);
 #pragma unroll
         for (int e = 0; e < 4; ++e)
-            vt[e] = moment_v(h, dequant_v((row.vq >> (4 * e)) & 15u, fminf(row.r_old, cold[e])), g[e]);
+            vt[e] = moment_v(h, dequant_v((row.vq >> (4 * e)) & 15u, fminf(r_old, cold[e])), g[e]);
     }
     float cnew[4];
-    load4(a.c_new + geo.col0, cnew);
+    load4(a.c_new + col0, cnew);
     uint32_t out = 0;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) out |= quant_v_code(vt[e], fminf(row.r_new, cnew[e])) << (4 * e);
+    for (int e = 0; e < 4; ++e) out |= quant_v_code(vt[e], fminf(r_new, cnew[e])) << (4 * e);
     return out;
 }
 
+constexpr int kWaves = kThreads / 64;
+
 template <bool BF16>
 __device__ __forceinline__ void pass2_fast_tile(const Tensor4& a, const Hyper& h, int wg) {
-    const Geo geo = geometry(a, wg);
-    if (!geo.active) return;
-    const TileBase tb = tile_base<BF16>(a, geo.row0);
+    const int strip = wg % a.strips2, tile = wg / a.strips2;
+    const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
+    const uint32_t col0 = uint32_t(strip) * 256u + (threadIdx.x & 63u) * 4u;
+    if (col0 >= uint32_t(a.cols)) return;        // odd number of column blocks: upper half of the last strip
+    const int64_t row0 = int64_t(tile) * a.rw2;
+    const int64_t left = a.rows - row0;
+    const int n = left < a.rw2 ? int(left) : a.rw2;
+    const TileBase tb = tile_base<BF16>(a, row0);
     float cold16[4], inv_cnew[4];
-    load4(a.c + geo.col0, cold16);
-    load4(a.c_new + geo.col0, inv_cnew);
-    bool cols_tame = true;
+    load4(a.c + col0, cold16);
+    load4(a.c_new + col0, inv_cnew);
+    bool lane_tame = true;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-        cols_tame = bool(int(cols_tame) & int(scale_is_tame(cold16[e])) & int(scale_is_tame(inv_cnew[e])));
+        lane_tame = bool(int(lane_tame) & int(scale_is_tame(cold16[e])) & int(scale_is_tame(inv_cnew[e])));
         cold16[e] *= 0.0625f;
         inv_cnew[e] = approx_inv(inv_cnew[e]);
     }
-    // two rows per stage, the next stage's loads in flight while this one is computed
-    const int stride = a.gy;
-    int il = geo.gyi;
-    Row2<BF16> c0, c1;
-    if (il < geo.n_rows) c0 = load_row2<BF16>(tb, a, geo, il);
-    if (il + stride < geo.n_rows) c1 = load_row2<BF16>(tb, a, geo, il + stride);
-    while (il < geo.n_rows) {
-        const int j0 = il + 2 * stride, j1 = il + 3 * stride;
-        Row2<BF16> n0, n1;
-        if (j0 < geo.n_rows) n0 = load_row2<BF16>(tb, a, geo, j0);
-        if (j1 < geo.n_rows) n1 = load_row2<BF16>(tb, a, geo, j1);
-        const uint32_t off = (uint32_t(il) * uint32_t(a.cols) + geo.col0) >> 1;     // byte offset of the lane's codes
-        st<uint16_t>(tb.vq, off, uint16_t(pass2_row<BF16>(a, h, geo, c0, cold16, inv_cnew, cols_tame)));
-        if (il + stride < geo.n_rows)
-            st<uint16_t>(tb.vq, off + ((uint32_t(stride) * uint32_t(a.cols)) >> 1),
-                         uint16_t(pass2_row<BF16>(a, h, geo, c1, cold16, inv_cnew, cols_tame)));
-        c0 = n0;
-        c1 = n1;
-        il = j0;
+    const bool cols_tame = __ballot(!lane_tame) == 0;
+    // the loads of two rows are in flight while a third is computed (three register sets take
+    // turns, the loop is unrolled by three)
+    const uint32_t row_bytes = uint32_t(a.cols) >> 1;               // bytes of codes per row
+    auto put = [&](int il, uint32_t codes) {
+        st<uint16_t>(tb.vq, uint32_t(il) * row_bytes + (col0 >> 1), uint16_t(codes));
+    };
+    int il = wave;
+    Row2<BF16> r0, r1, r2;
+    if (il < n) r0 = load_row2<BF16>(tb, a, col0, il);
+    if (il + kWaves < n) r1 = load_row2<BF16>(tb, a, col0, il + kWaves);
+    while (il < n) {
+        if (il + 2 * kWaves < n) r2 = load_row2<BF16>(tb, a, col0, il + 2 * kWaves);
+        put(il, pass2_row<BF16>(a, h, col0, r0, cold16, inv_cnew, cols_tame));
+        il += kWaves;
+        if (il >= n) break;
+        if (il + 2 * kWaves < n) r0 = load_row2<BF16>(tb, a, col0, il + 2 * kWaves);
+        put(il, pass2_row<BF16>(a, h, col0, r1, cold16, inv_cnew, cols_tame));
+        il += kWaves;
+        if (il >= n) break;
+        if (il + 2 * kWaves < n) r1 = load_row2<BF16>(tb, a, col0, il + 2 * kWaves);
+        put(il, pass2_row<BF16>(a, h, col0, r2, cold16, inv_cnew, cols_tame));
+        il += kWaves;
     }
 }
 
@@ -702,7 +746,7 @@ template <bool BF16>
 __global__ __launch_bounds__(kThreads) void pass2_fast(const Tensor4 a, const Hyper h) {
     __shared__ int s_last;
     const int wg = logical_wg();
-    if (wg < a.n_wg) pass2_fast_tile<BF16>(a, h, wg);
+    if (wg < a.n_wg2) pass2_fast_tile<BF16>(a, h, wg);
     publish_if_last(a, blockIdx.x, gridDim.x, s_last);
 }
 
@@ -775,7 +819,7 @@ __global__ __launch_bounds__(kThreads) void phase_kernel(const Phase ph, const H
         const int wg = b_before - sg.wg_begin;
         if (a.kind == kQuantFast) pass2_fast_tile<BF16>(a, h, wg);
         else pass2_general_tile<BF16>(a, h, wg);
-        publish_if_last(a, wg, a.n_wg, s_last);
+        publish_if_last(a, wg, a.n_wg2, s_last);
     } else if (ROLES != 2) {
         __shared__ Lds s;
         const int xa = x - b_before;

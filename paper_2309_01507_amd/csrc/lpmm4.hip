@@ -51,7 +51,7 @@ hipEvent_t prof_event(int64_t call, int which) {
 struct HostTables {
     float de[kCodes], lin[kCodes], thr[kCodes - 1];
     float byte_decode[512];
-    SearchEntry search[kBuckets];
+    SearchEntry search[kBucketsPadded];
     bool ok;
     HostTables() {
         build_de_signed(de);
@@ -116,7 +116,7 @@ int pad8(int64_t n) { return int(round_up(n, kXcds)); }
 // whole 128-byte lines of codes and runs of block scales), gy = 8/gx groups walk interleaved
 // rows of the same column blocks and combine their column maxima in LDS.  rw_hint > 0 fixes the
 // rows per workgroup; otherwise they are chosen so that the tensor alone fills the chip.
-void fast_geometry(Tensor4* a, int n_cu, int64_t rw_hint) {
+void fast_geometry(Tensor4* a, int n_cu, int64_t rw_hint, int64_t rw2_hint) {
     a->nb = int(a->cols / LPMM_BLOCK);
     int gx = env_int("LPMM_GX", 1);
     if (gx < 1 || gx > kGroups || (gx & (gx - 1))) gx = 1;
@@ -140,6 +140,19 @@ void fast_geometry(Tensor4* a, int n_cu, int64_t rw_hint) {
     if (rw < a->gy) rw = a->gy;
     a->rw = int(rw);
     a->n_wg = int(a->strips * ((a->rows + rw - 1) / rw));
+    // pass 2: strips of 256 columns, a wave per row
+    a->strips2 = (a->nb + 1) / 2;
+    int64_t rw2 = env_int("LPMM_RW2", 0);
+    if (rw2 <= 0) rw2 = rw2_hint;
+    if (rw2 <= 0) {
+        rw2 = 64;
+        while (rw2 > kWaves && a->strips2 * ((a->rows + rw2 - 1) / rw2) < 2 * int64_t(n_cu)) rw2 >>= 1;
+    }
+    if (rw2 > cap) rw2 = cap;
+    if (rw2 > a->rows) rw2 = a->rows;
+    if (rw2 < 1) rw2 = 1;
+    a->rw2 = int(rw2);
+    a->n_wg2 = int(a->strips2 * ((a->rows + rw2 - 1) / rw2));
 }
 
 bool fast_eligible(int64_t cols, const float* v_colmax) {
@@ -157,7 +170,7 @@ int launch_step(const Tensor4& t, const Hyper& h, bool fast, hipStream_t s) {
     else hipLaunchKernelGGL(pass1_general<BF16>, dim3(grid), dim3(kThreads), 0, s, t, h);
     LPMM_HIP(hipGetLastError());
     if (rec) LPMM_HIP(hipEventRecord(prof_event(call, 1), s));
-    if (fast) hipLaunchKernelGGL(pass2_fast<BF16>, dim3(grid), dim3(kThreads), 0, s, t, h);
+    if (fast) hipLaunchKernelGGL(pass2_fast<BF16>, dim3(pad8(t.n_wg2)), dim3(kThreads), 0, s, t, h);
     else hipLaunchKernelGGL(pass2_general<BF16>, dim3(grid), dim3(kThreads), 0, s, t, h);
     LPMM_HIP(hipGetLastError());
     if (rec) {
@@ -203,8 +216,8 @@ int step_impl(bool bf16, void* param, const void* grad, uint8_t* m_codes, float*
     t.P = rows * cols;
     const bool fast = fast_eligible(cols, v_colmax);
     t.kind = fast ? kQuantFast : kQuantGeneral;
-    if (fast) fast_geometry(&t, ctx->n_cu, 0);
-    else t.n_wg = int((((t.P + 7) / 8) + kThreads - 1) / kThreads);
+    if (fast) fast_geometry(&t, ctx->n_cu, 0, 0);
+    else t.n_wg = t.n_wg2 = int((((t.P + 7) / 8) + kThreads - 1) / kThreads);
     hipStream_t s = static_cast<hipStream_t>(stream);
     return bf16 ? launch_step<true>(t, h, fast, s) : launch_step<false>(t, h, fast, s);
 }
@@ -233,13 +246,17 @@ struct PlanHost {
     int device = 0;
     // second stream for pass 2 (same priority as any other stream), with its ordering events
     hipStream_t side = nullptr;
+    hipStream_t side_a = nullptr;       // optional: pass 1 of odd phases, so that consecutive pass-1 launches overlap their tails
+    hipEvent_t ev_join_a = nullptr;
     std::vector<hipEvent_t> ev_a;       // ev_a[j]: phase j's A work is complete
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     ~PlanHost() {
         for (hipEvent_t e : ev_a) (void)hipEventDestroy(e);
         if (ev_fork) (void)hipEventDestroy(ev_fork);
         if (ev_join) (void)hipEventDestroy(ev_join);
+        if (ev_join_a) (void)hipEventDestroy(ev_join_a);
         if (side) (void)hipStreamDestroy(side);
+        if (side_a) (void)hipStreamDestroy(side_a);
     }
 };
 
@@ -509,6 +526,7 @@ int lpmm_adamw4_plan_build(const lpmm_tensor_desc* descs, int64_t n, int grad_dt
     unsigned int* d_counters = reinterpret_cast<unsigned int*>(dplan + L.off_counters);
 
     const int64_t rw_hint = env_int("LPMM_MULTI_RW", 128);
+    const int64_t rw2_hint = env_int("LPMM_MULTI_RW2", 128);
     int64_t fofs = 0;
     for (int64_t i = 0; i < n; ++i) {
         const lpmm_tensor_desc& d = descs[i];
@@ -524,7 +542,7 @@ int lpmm_adamw4_plan_build(const lpmm_tensor_desc* descs, int64_t n, int grad_dt
             if (!aligned(d.param, 4) || !aligned(d.m_state, 4) || !aligned(d.v_state, 4) || !aligned(d.grad, galign))
                 return LPMM_EINVAL;
             t.kind = kFp32State;
-            t.n_wg = int((t.P + kElemsPerWg32 - 1) / kElemsPerWg32);
+            t.n_wg = t.n_wg2 = int((t.P + kElemsPerWg32 - 1) / kElemsPerWg32);
         } else {
             if (!d.m_blockscale || !d.v_rowmax || !d.v_colmax) return LPMM_EINVAL;
             if (!aligned(d.param, 16) || !aligned(d.grad, 16) || !aligned(d.m_state, 4) || !aligned(d.v_state, 4) ||
@@ -540,17 +558,17 @@ int lpmm_adamw4_plan_build(const lpmm_tensor_desc* descs, int64_t n, int grad_dt
             t.counter = d_counters + i * kCounterWords;
             if (fast_eligible(d.cols, d.v_colmax)) {
                 t.kind = kQuantFast;
-                fast_geometry(&t, ctx->n_cu, rw_hint);
+                fast_geometry(&t, ctx->n_cu, rw_hint, rw2_hint);
             } else {
                 t.kind = kQuantGeneral;
-                t.n_wg = int((((t.P + 7) / 8) + kThreads - 1) / kThreads);
+                t.n_wg = t.n_wg2 = int((((t.P + 7) / 8) + kThreads - 1) / kThreads);
             }
         }
         tens[i] = t;
     }
 
     // groups of consecutive tensors; phase j = A work of group j + B work of group j-1
-    const int64_t group_params = int64_t(env_int("LPMM_PHASE_MPARAMS", 256)) << 20;
+    const int64_t group_params = int64_t(env_int("LPMM_PHASE_MPARAMS", 2048)) << 20;
     std::vector<std::pair<int64_t, int64_t>> groups;      // [first, last)
     for (int64_t i = 0; i < n;) {
         int64_t j = i, acc = 0;
@@ -570,7 +588,7 @@ int lpmm_adamw4_plan_build(const lpmm_tensor_desc* descs, int64_t n, int grad_dt
             for (int64_t i = groups[j - 1].first; i < groups[j - 1].second; ++i) {
                 if (tens[i].kind == kFp32State) continue;
                 pl.ph.seg_b[pl.ph.n_seg_b++] = Segment{pl.ph.n_b, int(i)};
-                pl.ph.n_b += tens[i].n_wg;
+                pl.ph.n_b += tens[i].n_wg2;
             }
         if (pl.ph.n_a + pl.ph.n_b == 0) continue;
         if (int64_t(pl.ph.n_a) + pl.ph.n_b > (int64_t(1) << 30)) return LPMM_EINVAL;
@@ -583,6 +601,10 @@ int lpmm_adamw4_plan_build(const lpmm_tensor_desc* descs, int64_t n, int grad_dt
         LPMM_HIP(hipStreamCreateWithFlags(&host->side, hipStreamNonBlocking));
         LPMM_HIP(hipEventCreateWithFlags(&host->ev_fork, hipEventDisableTiming));
         LPMM_HIP(hipEventCreateWithFlags(&host->ev_join, hipEventDisableTiming));
+        if (env_int("LPMM_MULTI_STREAMS", 2) >= 3) {
+            LPMM_HIP(hipStreamCreateWithFlags(&host->side_a, hipStreamNonBlocking));
+            LPMM_HIP(hipEventCreateWithFlags(&host->ev_join_a, hipEventDisableTiming));
+        }
         host->ev_a.resize(host->phases.size());
         for (hipEvent_t& e : host->ev_a) LPMM_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming));
     }
@@ -618,6 +640,7 @@ int lpmm_adamw4_step_multi(void* plan, float lr, float beta1, float beta2, float
         hipStream_t s2 = host->side;
         LPMM_HIP(hipEventRecord(host->ev_fork, s));
         LPMM_HIP(hipStreamWaitEvent(s2, host->ev_fork, 0));
+        if (host->side_a) LPMM_HIP(hipStreamWaitEvent(host->side_a, host->ev_fork, 0));
         for (size_t j = 0; j < host->phases.size(); ++j) {
             const PhaseLaunch& pl = host->phases[j];
             if (pl.ph.n_b > 0) {
@@ -626,23 +649,28 @@ int lpmm_adamw4_step_multi(void* plan, float lr, float beta1, float beta2, float
                 else hipLaunchKernelGGL((phase_kernel<false, 2>), dim3(pl.grid_b), dim3(kThreads), 0, s2, pl.ph, h);
                 LPMM_HIP(hipGetLastError());
             }
+            hipStream_t sa = (host->side_a && (j & 1)) ? host->side_a : s;
             if (pl.ph.n_a > 0) {
                 const bool rec = g_prof.on && g_prof.calls < g_prof.max_calls;
                 const int64_t call = g_prof.calls;
-                if (rec) LPMM_HIP(hipEventRecord(prof_event(call, 0), s));
-                if (bf16) hipLaunchKernelGGL((phase_kernel<true, 1>), dim3(pl.grid_a), dim3(kThreads), 0, s, pl.ph, h);
-                else hipLaunchKernelGGL((phase_kernel<false, 1>), dim3(pl.grid_a), dim3(kThreads), 0, s, pl.ph, h);
+                if (rec) LPMM_HIP(hipEventRecord(prof_event(call, 0), sa));
+                if (bf16) hipLaunchKernelGGL((phase_kernel<true, 1>), dim3(pl.grid_a), dim3(kThreads), 0, sa, pl.ph, h);
+                else hipLaunchKernelGGL((phase_kernel<false, 1>), dim3(pl.grid_a), dim3(kThreads), 0, sa, pl.ph, h);
                 LPMM_HIP(hipGetLastError());
                 if (rec) {
-                    LPMM_HIP(hipEventRecord(prof_event(call, 1), s));
-                    LPMM_HIP(hipEventRecord(prof_event(call, 2), s));
+                    LPMM_HIP(hipEventRecord(prof_event(call, 1), sa));
+                    LPMM_HIP(hipEventRecord(prof_event(call, 2), sa));
                     g_prof.calls = call + 1;
                 }
             }
-            LPMM_HIP(hipEventRecord(host->ev_a[j], s));
+            LPMM_HIP(hipEventRecord(host->ev_a[j], sa));
         }
         LPMM_HIP(hipEventRecord(host->ev_join, s2));
         LPMM_HIP(hipStreamWaitEvent(s, host->ev_join, 0));
+        if (host->side_a) {
+            LPMM_HIP(hipEventRecord(host->ev_join_a, host->side_a));
+            LPMM_HIP(hipStreamWaitEvent(s, host->ev_join_a, 0));
+        }
         return LPMM_OK;
     }
     for (const PhaseLaunch& pl : host->phases) {

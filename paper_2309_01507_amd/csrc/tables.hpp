@@ -8,9 +8,12 @@
 //
 // Nearest-entry search M(n) = argmin_i |n - T(i)| (Sec. 2.2), lowest index on a tie, is done in
 // the kernels as   code = #{k : n > thr_k},  thr_k = largest float <= (T(k)+T(k+1))/2,
-// which is the same function of a float n.  To avoid 15 compares per element the float line is cut
-// into buckets by the top 11 bits of n (sign, exponent, two mantissa bits); every bucket holds at
-// most one threshold, so   code = base[bucket] + (n > thr[bucket]).
+// which is the same function of a float n.  To avoid 15 compares per element the interval [-1, 1]
+// is cut into 513 buckets, bucket(n) = round-to-nearest-even(256 n) + 256, computed by one fused
+// multiply-add with a constant whose unit in the last place is 1 (the rounding of that operation is
+// the rounding to an integer, and the integer sits in the low bits of the result).  bucket() is a
+// non-decreasing function of n and no bucket holds two thresholds, so
+//   code = base[bucket] + (n > thr[bucket]).
 #pragma once
 
 #include <cmath>
@@ -21,9 +24,12 @@
 namespace lpmm {
 
 constexpr int kCodes = 16;
-constexpr int kBucketBits = 11;
-constexpr int kBuckets = 1 << kBucketBits;   // 2048
-constexpr int kBucketShift = 32 - kBucketBits;
+constexpr int kBucketHalf = 256;                    // buckets per unit of n
+constexpr int kBuckets = 2 * kBucketHalf + 1;       // 513: n = -1 ... +1
+constexpr int kBucketsPadded = 520;                 // table length (multiple of 8 entries)
+constexpr float kBucketScale = float(kBucketHalf);
+constexpr float kBucketMagic = 12582912.0f;         // 1.5 * 2^23: floats in [2^23, 2^24) are the integers
+constexpr uint32_t kBucketMagicBits = 0x4B400000u;  // its bit pattern
 
 // Buckets without a threshold compare against a value no normalized input reaches (|n| <= 1 up to
 // rounding); it is finite so that distance arithmetic on it stays finite.
@@ -75,37 +81,41 @@ inline void build_thresholds(const float T[kCodes], float thr[kCodes - 1]) {
     }
 }
 
-// Bucket table over all float bit patterns.  Returns false if some bucket would need two
-// thresholds (then the bucket width is too coarse for this map).
-inline bool build_search(const float thr[kCodes - 1], SearchEntry tab[kBuckets]) {
-    const float inf = std::numeric_limits<float>::infinity();
-    for (int b = 0; b < kBuckets; ++b) {
-        const uint32_t lo_bits = uint32_t(b) << kBucketShift;
-        const uint32_t hi_bits = lo_bits | ((1u << kBucketShift) - 1u);
-        const bool neg = (b >> (kBucketBits - 1)) != 0;
-        const int expo = (b >> 2) & 0xFF;
-        SearchEntry e{kNoThreshold, 0};
-        if (expo == 0xFF) {           // inf / NaN patterns: behave like the brute-force argmin -> code 0
-            e.thr = inf;
-            tab[b] = e;
-            continue;
+// Bucket of a normalized value.  The kernels only ever look up |n| <= 1 + 2^-22 and skip the
+// clamp; the host version clamps so that any finite n gets the code of the nearest end bucket.
+inline int search_bucket(float n) {
+    const float x = std::fmaf(n, kBucketScale, kBucketMagic);
+    if (!(x >= kBucketMagic - kBucketScale)) return 0;
+    if (x > kBucketMagic + kBucketScale) return kBuckets - 1;
+    return int(f2u(x) - kBucketMagicBits) + kBucketHalf;
+}
+
+// Returns false if some bucket would need two thresholds (then the buckets are too coarse for this
+// map) or a threshold lies outside [-1, 1].
+inline bool build_search(const float thr[kCodes - 1], SearchEntry tab[kBucketsPadded]) {
+    int owner[kBuckets];
+    for (int b = 0; b < kBuckets; ++b) owner[b] = -1;
+    for (int k = 0; k + 1 < kCodes; ++k) {
+        if (!(std::fabs(thr[k]) <= 1.0f)) return false;
+        const int b = search_bucket(thr[k]);
+        if (owner[b] >= 0) return false;
+        owner[b] = k;
+    }
+    uint32_t below = 0;
+    for (int b = 0; b < kBucketsPadded; ++b) {
+        SearchEntry e{kNoThreshold, below};
+        if (b < kBuckets && owner[b] >= 0) {
+            e.thr = thr[owner[b]];
+            below++;
         }
-        // value interval [a, z] covered by the bucket (bit patterns grow away from zero)
-        const float a = neg ? u2f(hi_bits) : u2f(lo_bits);
-        const float z = neg ? u2f(lo_bits) : u2f(hi_bits);
-        int own = 0;
-        for (int k = 0; k + 1 < kCodes; ++k) {
-            if (thr[k] < a) e.base++;
-            else if (thr[k] <= z) { e.thr = thr[k]; own++; }
-        }
-        if (own > 1) return false;
         tab[b] = e;
     }
     return true;
 }
 
-inline int search_code(const SearchEntry tab[kBuckets], float n) {
-    const SearchEntry& e = tab[f2u(n) >> kBucketShift];
+inline int search_code(const SearchEntry tab[kBucketsPadded], float n) {
+    if (!std::isfinite(n)) return 0;    // every distance is inf or NaN: the brute-force argmin keeps index 0
+    const SearchEntry& e = tab[search_bucket(n)];
     return int(e.base) + (n > e.thr ? 1 : 0);
 }
 
