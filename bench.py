@@ -195,7 +195,7 @@ def main():
         w = workloads.weights(args.seed, 0, rows, cols).reshape(-1)
         st = oracle.state_zero(rows, cols)
         hp = oracle.Hyper(lr, b1, b2, eps, wd)
-        n_cpu_steps = 10
+        n_cpu_steps = 20
         gs = [workloads.grads(args.seed, 0, s, rows, cols, recipe, bf16).reshape(-1) for s in (1, 2)]
         c0 = time.perf_counter()
         for s in range(1, n_cpu_steps + 1):
