@@ -19,10 +19,6 @@
 
 #include "device_math.hpp"
 
-#ifndef LPMM_P1_DEPTH
-#define LPMM_P1_DEPTH 3
-#endif
-
 namespace lpmm {
 
 // Lookup tables, uploaded once per device at init.
@@ -57,6 +53,50 @@ struct Tensor4 {
     int pad_;
 };
 
+// The tensor table of a plan lives in device memory.  A pointer read from memory is a generic
+// pointer to the compiler, and accesses through it would become flat instructions: slower, and
+// counted together with LDS traffic, so that every wait for a table lookup would also wait for the
+// rows being prefetched.  On the device the table is therefore read through a twin of Tensor4 whose
+// pointer members are typed as global memory (same layout), and converted member by member.
+#if defined(__HIP_DEVICE_COMPILE__)
+#define LPMM_AS_GLOBAL __attribute__((address_space(1)))
+struct Tensor4Table {
+    float LPMM_AS_GLOBAL* p;
+    const void LPMM_AS_GLOBAL* g;
+    uint32_t LPMM_AS_GLOBAL* mq;
+    float LPMM_AS_GLOBAL* ms;
+    uint32_t LPMM_AS_GLOBAL* vq;
+    float LPMM_AS_GLOBAL* r;
+    float LPMM_AS_GLOBAL* c;
+    float LPMM_AS_GLOBAL* r_new;
+    float LPMM_AS_GLOBAL* c_new;
+    unsigned int LPMM_AS_GLOBAL* counter;
+    int64_t rows, cols, P;
+    int nb, gx, gy, rw, strips, n_wg, kind, strips2, rw2, n_wg2, pad_;
+};
+static_assert(sizeof(Tensor4Table) == sizeof(Tensor4), "the table twin must mirror Tensor4");
+__device__ __forceinline__ Tensor4 from_table(const Tensor4Table& t) {
+    Tensor4 a;
+    a.p = (float*)t.p;
+    a.g = (const void*)t.g;
+    a.mq = (uint32_t*)t.mq;
+    a.ms = (float*)t.ms;
+    a.vq = (uint32_t*)t.vq;
+    a.r = (float*)t.r;
+    a.c = (float*)t.c;
+    a.r_new = (float*)t.r_new;
+    a.c_new = (float*)t.c_new;
+    a.counter = (unsigned int*)t.counter;
+    a.rows = t.rows; a.cols = t.cols; a.P = t.P;
+    a.nb = t.nb; a.gx = t.gx; a.gy = t.gy; a.rw = t.rw; a.strips = t.strips; a.n_wg = t.n_wg; a.kind = t.kind;
+    a.strips2 = t.strips2; a.rw2 = t.rw2; a.n_wg2 = t.n_wg2; a.pad_ = 0;
+    return a;
+}
+#else
+typedef Tensor4 Tensor4Table;
+__host__ __device__ inline Tensor4 from_table(const Tensor4& t) { return t; }   // host pass: only parsed, never run
+#endif
+
 constexpr int kThreads = 256;
 constexpr int kXcds = 8;
 constexpr int kElemsPerWg32 = kThreads * 16;   // fp32-state path: elements per workgroup
@@ -68,10 +108,19 @@ __device__ __forceinline__ int logical_wg() {
     return (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
 }
 
+constexpr int kWaitVmcnt0 = 0x0F70;   // s_waitcnt vmcnt(0) only: expcnt and lgkmcnt fields at their maxima
+constexpr int kMaxRowSlots = 512;    // rows of a pass-1 tile x column blocks of its strip (rw * gx)
+
 struct Lds {
     float2 deq[256];
     SearchEntry search[kBucketsPadded];
     float col[8 * 128];
+    // per row and column block of the tile: new block scale of m and the block's maximum of v_t.
+    // They leave for global memory at the end of the tile, so that the row loop issues the same
+    // memory instructions on every path (loads, the parameter store, the code store) and nothing
+    // that depends on the lane.
+    float blk_scale[kMaxRowSlots];
+    float blk_vmax[kMaxRowSlots];
 };
 
 __device__ __forceinline__ void load_tables(Lds& s) {
@@ -113,6 +162,37 @@ __device__ __forceinline__ void st_stream4(void* base, uint32_t byte_off, float4
     const v4f_t v = {f.x, f.y, f.z, f.w};
     const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(base, 0, 0x7FFFFFFF, kRawBufferWord3);
     __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u_t, v), rsrc, int(byte_off), 0, kPolicyNtSc1);
+}
+
+// Bounds-checked loads of the fast path.  A tile's arrays are described by raw buffer resources
+// whose length is the tile's; a load beyond it returns zero and touches no memory.  The row
+// prefetch can therefore run unconditionally past the end of a tile: no branch around the loads, so
+// the compiler counts outstanding loads exactly and never waits for a row it has just requested.
+typedef uint32_t v2u_t __attribute__((ext_vector_type(2)));
+typedef __amdgpu_buffer_rsrc_t Rsrc;
+constexpr int kPolicyNt = 2;
+__device__ __forceinline__ Rsrc tile_rsrc(const void* base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, int(bytes), kRawBufferWord3);
+}
+__device__ __forceinline__ float4 buf_ld_f4_stream(Rsrc r, uint32_t off) {
+    const v4f_t v = __builtin_bit_cast(v4f_t, __builtin_amdgcn_raw_buffer_load_b128(r, int(off), 0, kPolicyNt));
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ float4 buf_ld_f4(Rsrc r, uint32_t off) {
+    const v4f_t v = __builtin_bit_cast(v4f_t, __builtin_amdgcn_raw_buffer_load_b128(r, int(off), 0, 0));
+    return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ uint2 buf_ld_u2(Rsrc r, uint32_t off) {
+    const v2u_t v = __builtin_amdgcn_raw_buffer_load_b64(r, int(off), 0, 0);
+    return make_uint2(v.x, v.y);
+}
+// Kept 16 bits wide until it is used: widening right here would put an instruction that needs the
+// value directly behind the load, and with it a wait for a row that was only just requested.
+__device__ __forceinline__ uint16_t buf_ld_u16(Rsrc r, uint32_t off) {
+    return uint16_t(__builtin_amdgcn_raw_buffer_load_b16(r, int(off), 0, 0));
+}
+__device__ __forceinline__ float buf_ld_f(Rsrc r, uint32_t off) {
+    return __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, int(off), 0, 0));
 }
 
 template <typename T>
@@ -186,10 +266,10 @@ template <> struct GradRegs4<false> { float4 a; };
 
 // gradient of a lane's 4 elements; off4 is the byte offset the elements have in an fp32 array
 template <bool BF16>
-__device__ __forceinline__ GradRegs4<BF16> load_grad_regs4(const void* g_tile, uint32_t off4) {
+__device__ __forceinline__ GradRegs4<BF16> load_grad_regs4(Rsrc g_tile, uint32_t off4) {
     GradRegs4<BF16> r;
-    if constexpr (BF16) r.w = ld<uint2>(g_tile, off4 >> 1);
-    else r.a = ld<float4>(g_tile, off4);
+    if constexpr (BF16) r.w = buf_ld_u2(g_tile, off4 >> 1);
+    else r.a = buf_ld_f4(g_tile, off4);
     return r;
 }
 template <bool BF16>
@@ -212,6 +292,14 @@ __device__ __forceinline__ void codes_to_float4(uint32_t w, float qf[4]) {
     qf[1] = float(hi & 255u);
     qf[2] = float((lo >> 8) & 255u);
     qf[3] = float((hi >> 8) & 255u);
+}
+
+// il * pitch + x for a row index and a pitch that both fit 24 bits (rows of a tile; cols <= 2^24).
+// The 24-bit multiply-add is a single 32-bit instruction; a full 32-bit multiply-add would go through
+// the 64-bit one, whose unused upper addend register the compiler may alias with a register that a
+// prefetch is still loading into, which turns into a wait for that prefetch.
+__device__ __forceinline__ uint32_t row_offset(int il, int64_t pitch, uint32_t x) {
+    return __umul24(uint32_t(il), uint32_t(pitch)) + x;
 }
 
 struct Geo {            // where this group works
@@ -248,12 +336,15 @@ struct TileBase {
     float* ms;
     const float* r;
     float* r_new;
+    // the same arrays as bounds-checked resources of n_rows rows, for the loads
+    Rsrc rp, rg, rmq, rvq, rms, rr, rr_new;
 };
 
 template <bool BF16>
-__device__ __forceinline__ TileBase tile_base(const Tensor4& a, int64_t row0) {
+__device__ __forceinline__ TileBase tile_base(const Tensor4& a, int64_t row0, int n_rows) {
     TileBase b;
     const int64_t e = row0 * a.cols;
+    const uint32_t elems = uint32_t(n_rows) * uint32_t(a.cols);       // < 2^29
     b.p = a.p + e;
     b.g = reinterpret_cast<const char*>(a.g) + e * (BF16 ? 2 : 4);
     b.mq = reinterpret_cast<uint8_t*>(a.mq) + (e >> 1);
@@ -261,6 +352,13 @@ __device__ __forceinline__ TileBase tile_base(const Tensor4& a, int64_t row0) {
     b.ms = a.ms + row0 * a.nb;
     b.r = a.r + row0;
     b.r_new = a.r_new + row0;
+    b.rp = tile_rsrc(b.p, elems * 4u);
+    b.rg = tile_rsrc(b.g, elems * (BF16 ? 2u : 4u));
+    b.rmq = tile_rsrc(b.mq, elems >> 1);
+    b.rvq = tile_rsrc(b.vq, elems >> 1);
+    b.rms = tile_rsrc(b.ms, uint32_t(n_rows) * uint32_t(a.nb) * 4u);
+    b.rr = tile_rsrc(b.r, uint32_t(n_rows) * 4u);
+    b.rr_new = tile_rsrc(b.r_new, uint32_t(n_rows) * 4u);
     return b;
 }
 
@@ -273,36 +371,36 @@ template <bool BF16>
 struct Row1 {                      // everything pass 1 reads for one row of one lane
     float4 p;
     GradRegs4<BF16> g;
-    uint32_t mq, vq;               // 16 bits each: the lane's 4 codes
+    uint16_t mq, vq;               // the lane's 4 codes of each moment
     float s_old, r_old;
 };
 
-// il = row index inside the tile
+// il = row index inside the tile; rows at or beyond the tile's end read as zeros
 template <bool BF16>
 __device__ __forceinline__ Row1<BF16> load_row1(const TileBase& b, const Tensor4& a, const Geo& g, int il) {
     Row1<BF16> r;
-    const uint32_t off4 = (uint32_t(il) * uint32_t(a.cols) + g.col0) * 4u;   // byte offset, fp32 array
-    r.p = ld_stream4(b.p, off4);
-    r.g = load_grad_regs4<BF16>(b.g, off4);
-    r.mq = ld<uint16_t>(b.mq, off4 >> 3);
-    r.vq = ld<uint16_t>(b.vq, off4 >> 3);
-    r.s_old = ld<float>(b.ms, (uint32_t(il) * uint32_t(a.nb) + uint32_t(g.cb)) * 4u);
-    r.r_old = ld<float>(b.r, uint32_t(il) * 4u);
+    const uint32_t off4 = row_offset(il, a.cols, g.col0) * 4u;   // byte offset, fp32 array
+    r.p = buf_ld_f4_stream(b.rp, off4);
+    r.g = load_grad_regs4<BF16>(b.rg, off4);
+    r.mq = buf_ld_u16(b.rmq, off4 >> 3);
+    r.vq = buf_ld_u16(b.rvq, off4 >> 3);
+    r.s_old = buf_ld_f(b.rms, row_offset(il, a.nb, uint32_t(g.cb)) * 4u);
+    r.r_old = buf_ld_f(b.rr, uint32_t(il) * 4u);
     return r;
 }
 
 // One row of pass 1 for one lane: `cur` holds what was loaded for row `il` of the tile.
-template <bool BF16>
+template <bool BF16, class Mid>
 __device__ __forceinline__ void pass1_row(const Tensor4& a, const Hyper& h, const TileBase& tb, const Geo& geo,
-                                          const Lds& s, const Row1<BF16>& cur, int il, const float cold16[4],
-                                          bool cols_tame, float cmax[4]) {
+                                          Lds& s, const Row1<BF16>& cur, int il, const float cold16[4],
+                                          bool cols_tame, float cmax[4], Mid mid) {
     float w[4] = {cur.p.x, cur.p.y, cur.p.z, cur.p.w};
     float g[4];
     unpack_grad4<BF16>(cur.g, g);
     float mt[4], vt[4], amax = 0.0f, rmax = 0.0f;
 #pragma unroll
     for (int k = 0; k < 2; ++k) {
-        const float2 t = s.deq[(cur.mq >> (8 * k)) & 255u];
+        const float2 t = s.deq[(uint32_t(cur.mq) >> (8 * k)) & 255u];
         mt[2 * k] = t.x * cur.s_old;          // decompress: T_DE[code] * block scale
         mt[2 * k + 1] = t.y * cur.s_old;
     }
@@ -318,7 +416,7 @@ __device__ __forceinline__ void pass1_row(const Tensor4& a, const Hyper& h, cons
         float cold[4];
         load4(a.c + geo.col0, cold);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) vt[e] = dequant_v((cur.vq >> (4 * e)) & 15u, fminf(cur.r_old, cold[e]));
+        for (int e = 0; e < 4; ++e) vt[e] = dequant_v((uint32_t(cur.vq) >> (4 * e)) & 15u, fminf(cur.r_old, cold[e]));
     }
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
@@ -329,6 +427,11 @@ __device__ __forceinline__ void pass1_row(const Tensor4& a, const Hyper& h, cons
         rmax = max_nonneg(rmax, vt[e]);
         cmax[e] = max_nonneg(cmax[e], vt[e]);
     }
+    // the caller's prefetch of a later row is issued here, in the middle of the row's arithmetic:
+    // by now the previous row's stores have been acknowledged, and loads queue behind older stores
+    __builtin_amdgcn_sched_barrier(0);
+    mid();
+    __builtin_amdgcn_sched_barrier(0);
     const float s_new = group32_allmax(amax);     // block absmax of m_t
     rmax = group32_allmax(rmax);
 
@@ -350,12 +453,12 @@ __device__ __forceinline__ void pass1_row(const Tensor4& a, const Hyper& h, cons
         for (int e = 0; e < 4; ++e) mq_new |= quant_m_code(s.search, mt[e], s_new) << (4 * e);
     }
 
-    const uint32_t off4 = (uint32_t(il) * uint32_t(a.cols) + geo.col0) * 4u;
+    const uint32_t off4 = row_offset(il, a.cols, geo.col0) * 4u;
     st_stream4(tb.p, off4, make_float4(w[0], w[1], w[2], w[3]));
     st<uint16_t>(tb.mq, off4 >> 3, uint16_t(mq_new));
     if (geo.l == 0) {
-        st<float>(tb.ms, (uint32_t(il) * uint32_t(a.nb) + uint32_t(geo.cb)) * 4u, s_new);
-        if (rmax > 0.0f) atomic_max_nonneg(tb.r_new + il, rmax);
+        s.blk_scale[il * a.gx + geo.gxi] = s_new;
+        s.blk_vmax[il * a.gx + geo.gxi] = rmax;
     }
 }
 
@@ -363,7 +466,7 @@ __device__ __forceinline__ void pass1_row(const Tensor4& a, const Hyper& h, cons
 template <bool BF16, bool TABLES_READY>
 __device__ __forceinline__ void pass1_fast_tile(const Tensor4& a, const Hyper& h, int wg, Lds& s) {
     const Geo geo = geometry(a, wg);
-    const TileBase tb = tile_base<BF16>(a, geo.row0);
+    const TileBase tb = tile_base<BF16>(a, geo.row0, geo.n_rows);
     float cmax[4] = {0.0f, 0.0f, 0.0f, 0.0f};
 
     if (geo.active) {
@@ -376,41 +479,37 @@ __device__ __forceinline__ void pass1_fast_tile(const Tensor4& a, const Hyper& h
             cold16[e] *= 0.0625f;
         }
         // rows of this group: il, il + gy, ...; the loads of two rows are in flight while a third
-        // is computed (three register sets take turns, the loop is unrolled by three)
+        // is computed (three register sets take turns, the loop is unrolled by three); the prefetch is
+        // unconditional, rows past the tile come back as zeros and are never used
         const int stp = a.gy, n = geo.n_rows;
         int il = geo.gyi;
-#if LPMM_P1_DEPTH == 2
-        Row1<BF16> r0, r1;
-        if (il < n) r0 = load_row1<BF16>(tb, a, geo, il);
-        if constexpr (!TABLES_READY) load_tables(s);
-        while (il < n) {
-            if (il + stp < n) r1 = load_row1<BF16>(tb, a, geo, il + stp);
-            pass1_row<BF16>(a, h, tb, geo, s, r0, il, cold16, cols_tame, cmax);
-            il += stp;
-            if (il >= n) break;
-            if (il + stp < n) r0 = load_row1<BF16>(tb, a, geo, il + stp);
-            pass1_row<BF16>(a, h, tb, geo, s, r1, il, cold16, cols_tame, cmax);
-            il += stp;
-        }
-#else
-        Row1<BF16> r0, r1, r2;
-        if (il < n) r0 = load_row1<BF16>(tb, a, geo, il);
-        if (il + stp < n) r1 = load_row1<BF16>(tb, a, geo, il + stp);
+        Row1<BF16> r0 = load_row1<BF16>(tb, a, geo, il);
+        Row1<BF16> r1 = load_row1<BF16>(tb, a, geo, il + stp);
+        Row1<BF16> r2;
         if constexpr (!TABLES_READY) load_tables(s);   // the first rows' loads are in flight meanwhile
-        while (il < n) {
-            if (il + 2 * stp < n) r2 = load_row1<BF16>(tb, a, geo, il + 2 * stp);
-            pass1_row<BF16>(a, h, tb, geo, s, r0, il, cold16, cols_tame, cmax);
-            il += stp;
-            if (il >= n) break;
-            if (il + 2 * stp < n) r0 = load_row1<BF16>(tb, a, geo, il + 2 * stp);
-            pass1_row<BF16>(a, h, tb, geo, s, r1, il, cold16, cols_tame, cmax);
-            il += stp;
-            if (il >= n) break;
-            if (il + 2 * stp < n) r1 = load_row1<BF16>(tb, a, geo, il + 2 * stp);
-            pass1_row<BF16>(a, h, tb, geo, s, r2, il, cold16, cols_tame, cmax);
-            il += stp;
+        // Everything requested so far has to be here before the first row anyway.  Saying so with an
+        // explicit wait gives the loop a start-up state with nothing outstanding; otherwise the
+        // start-up's own (tight) wait counts are merged into the loop head and drain the prefetch
+        // in every round.
+        __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
+        // Rounds of three rows while all three exist; the loop has no exit in its middle, so that
+        // every path through it sees the same queue of outstanding loads and the compiler's wait
+        // counts are exact (an early exit would join a path on which the newest prefetch is still
+        // pending, and the loop head would then wait for it).  At most two rows remain afterwards.
+        auto none = [] {};
+        while (il + 2 * stp < n) {
+            pass1_row<BF16>(a, h, tb, geo, s, r0, il, cold16, cols_tame, cmax,
+                            [&] { r2 = load_row1<BF16>(tb, a, geo, il + 2 * stp); });
+            pass1_row<BF16>(a, h, tb, geo, s, r1, il + stp, cold16, cols_tame, cmax,
+                            [&] { r0 = load_row1<BF16>(tb, a, geo, il + 3 * stp); });
+            pass1_row<BF16>(a, h, tb, geo, s, r2, il + 2 * stp, cold16, cols_tame, cmax,
+                            [&] { r1 = load_row1<BF16>(tb, a, geo, il + 4 * stp); });
+            il += 3 * stp;
         }
-#endif
+        if (il < n) {
+            pass1_row<BF16>(a, h, tb, geo, s, r0, il, cold16, cols_tame, cmax, none);
+            if (il + stp < n) pass1_row<BF16>(a, h, tb, geo, s, r1, il + stp, cold16, cols_tame, cmax, none);
+        }
     } else {
         if constexpr (!TABLES_READY) load_tables(s);   // keeps the workgroup's barriers matched
     }
@@ -419,6 +518,15 @@ __device__ __forceinline__ void pass1_fast_tile(const Tensor4& a, const Hyper& h
 #pragma unroll
     for (int e = 0; e < 4; ++e) s.col[geo.grp * 128 + geo.l * 4 + e] = cmax[e];
     __syncthreads();
+    // block scales to the state, block maxima of v_t into the row maxima
+    for (int t = threadIdx.x; t < geo.n_rows * a.gx; t += kThreads) {
+        const int il = t / a.gx, cbi = geo.strip * a.gx + t % a.gx;
+        if (cbi < a.nb) {
+            st<float>(tb.ms, row_offset(il, a.nb, uint32_t(cbi)) * 4u, s.blk_scale[t]);
+            const float m = s.blk_vmax[t];
+            if (m > 0.0f) atomic_max_nonneg(tb.r_new + il, m);
+        }
+    }
     for (int t = threadIdx.x; t < a.gx * 128; t += kThreads) {
         const int gi = t >> 7;
         float m = 0.0f;
@@ -489,18 +597,18 @@ __device__ __forceinline__ void publish_if_last(const Tensor4& a, unsigned int m
 template <bool BF16>
 struct Row2 {                      // everything pass 2 reads for one row of one lane
     GradRegs4<BF16> g;
-    uint32_t vq;                   // 16 bits: the lane's 4 codes
+    uint16_t vq;                   // the lane's 4 codes
     float r_old, r_new;            // the same value in every lane
 };
 
 template <bool BF16>
 __device__ __forceinline__ Row2<BF16> load_row2(const TileBase& b, const Tensor4& a, uint32_t col0, int il) {
     Row2<BF16> r;
-    const uint32_t off4 = (uint32_t(il) * uint32_t(a.cols) + col0) * 4u;
-    r.g = load_grad_regs4<BF16>(b.g, off4);
-    r.vq = ld<uint16_t>(b.vq, off4 >> 3);
-    r.r_old = ld<float>(b.r, uint32_t(il) * 4u);
-    r.r_new = ld<float>(b.r_new, uint32_t(il) * 4u);
+    const uint32_t off4 = row_offset(il, a.cols, col0) * 4u;
+    r.g = load_grad_regs4<BF16>(b.rg, off4);
+    r.vq = buf_ld_u16(b.rvq, off4 >> 3);
+    r.r_old = buf_ld_f(b.rr, uint32_t(il) * 4u);
+    r.r_new = buf_ld_f(b.rr_new, uint32_t(il) * 4u);
     return r;
 }
 
@@ -539,7 +647,7 @@ __device__ __forceinline__ uint32_t pass2_row(const Tensor4& a, const Hyper& h, 
         load4(a.c + col0, cold);
 #pragma unroll
         for (int e = 0; e < 4; ++e)
-            vt[e] = moment_v(h, dequant_v((row.vq >> (4 * e)) & 15u, fminf(r_old, cold[e])), g[e]);
+            vt[e] = moment_v(h, dequant_v((uint32_t(row.vq) >> (4 * e)) & 15u, fminf(r_old, cold[e])), g[e]);
     }
     float cnew[4];
     load4(a.c_new + col0, cnew);
@@ -560,7 +668,7 @@ __device__ __forceinline__ void pass2_fast_tile(const Tensor4& a, const Hyper& h
     const int64_t row0 = int64_t(tile) * a.rw2;
     const int64_t left = a.rows - row0;
     const int n = left < a.rw2 ? int(left) : a.rw2;
-    const TileBase tb = tile_base<BF16>(a, row0);
+    const TileBase tb = tile_base<BF16>(a, row0, n);
     float cold16[4], inv_cnew[4];
     load4(a.c + col0, cold16);
     load4(a.c_new + col0, inv_cnew);
@@ -573,27 +681,28 @@ __device__ __forceinline__ void pass2_fast_tile(const Tensor4& a, const Hyper& h
     }
     const bool cols_tame = __ballot(!lane_tame) == 0;
     // the loads of two rows are in flight while a third is computed (three register sets take
-    // turns, the loop is unrolled by three)
+    // turns, the loop is unrolled by three); rows past the tile read as zeros and are never used
     const uint32_t row_bytes = uint32_t(a.cols) >> 1;               // bytes of codes per row
     auto put = [&](int il, uint32_t codes) {
-        st<uint16_t>(tb.vq, uint32_t(il) * row_bytes + (col0 >> 1), uint16_t(codes));
+        st<uint16_t>(tb.vq, __umul24(uint32_t(il), row_bytes) + (col0 >> 1), uint16_t(codes));
     };
     int il = wave;
-    Row2<BF16> r0, r1, r2;
-    if (il < n) r0 = load_row2<BF16>(tb, a, col0, il);
-    if (il + kWaves < n) r1 = load_row2<BF16>(tb, a, col0, il + kWaves);
-    while (il < n) {
-        if (il + 2 * kWaves < n) r2 = load_row2<BF16>(tb, a, col0, il + 2 * kWaves);
+    Row2<BF16> r0 = load_row2<BF16>(tb, a, col0, il);
+    Row2<BF16> r1 = load_row2<BF16>(tb, a, col0, il + kWaves);
+    Row2<BF16> r2;
+    __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);     // loop start-up state: nothing outstanding (see pass 1)
+    while (il + 2 * kWaves < n) {        // rounds of three rows, no exit in the middle (see pass 1)
+        r2 = load_row2<BF16>(tb, a, col0, il + 2 * kWaves);
         put(il, pass2_row<BF16>(a, h, col0, r0, cold16, inv_cnew, cols_tame));
-        il += kWaves;
-        if (il >= n) break;
-        if (il + 2 * kWaves < n) r0 = load_row2<BF16>(tb, a, col0, il + 2 * kWaves);
-        put(il, pass2_row<BF16>(a, h, col0, r1, cold16, inv_cnew, cols_tame));
-        il += kWaves;
-        if (il >= n) break;
-        if (il + 2 * kWaves < n) r1 = load_row2<BF16>(tb, a, col0, il + 2 * kWaves);
-        put(il, pass2_row<BF16>(a, h, col0, r2, cold16, inv_cnew, cols_tame));
-        il += kWaves;
+        r0 = load_row2<BF16>(tb, a, col0, il + 3 * kWaves);
+        put(il + kWaves, pass2_row<BF16>(a, h, col0, r1, cold16, inv_cnew, cols_tame));
+        r1 = load_row2<BF16>(tb, a, col0, il + 4 * kWaves);
+        put(il + 2 * kWaves, pass2_row<BF16>(a, h, col0, r2, cold16, inv_cnew, cols_tame));
+        il += 3 * kWaves;
+    }
+    if (il < n) {
+        put(il, pass2_row<BF16>(a, h, col0, r0, cold16, inv_cnew, cols_tame));
+        if (il + kWaves < n) put(il + kWaves, pass2_row<BF16>(a, h, col0, r1, cold16, inv_cnew, cols_tame));
     }
 }
 
@@ -810,7 +919,7 @@ struct Segment {        // a run of workgroups that work on one tensor
 constexpr int kMaxSeg = 32;   // tensors per kind in one phase; the tables travel as kernel arguments
 
 struct Phase {
-    const Tensor4* tensors;
+    const Tensor4Table* tensors;
     int n_seg_a, n_seg_b;
     int n_a, n_b;           // workgroups of each kind
     Segment seg_a[kMaxSeg];
@@ -840,7 +949,7 @@ __global__ __launch_bounds__(kThreads) void phase_kernel(const Phase ph, const H
     if (ROLES != 1 && b_after > b_before) {
         __shared__ int s_last;
         const Segment sg = find_segment(ph.seg_b, ph.n_seg_b, b_before);
-        const Tensor4 a = ph.tensors[sg.tensor];
+        const Tensor4 a = from_table(ph.tensors[sg.tensor]);
         const int wg = b_before - sg.wg_begin;
         if (a.kind == kQuantFast) pass2_fast_tile<BF16>(a, h, wg);
         else pass2_general_tile<BF16>(a, h, wg);
@@ -849,7 +958,7 @@ __global__ __launch_bounds__(kThreads) void phase_kernel(const Phase ph, const H
         __shared__ Lds s;
         const int xa = x - b_before;
         const Segment sg = find_segment(ph.seg_a, ph.n_seg_a, xa);
-        const Tensor4 a = ph.tensors[sg.tensor];
+        const Tensor4 a = from_table(ph.tensors[sg.tensor]);
         const int wg = xa - sg.wg_begin;
         if (a.kind == kFp32State) {
             adamw32_tile<BF16>(a.p, a.g, reinterpret_cast<float*>(a.mq), reinterpret_cast<float*>(a.vq), a.P, h, wg);

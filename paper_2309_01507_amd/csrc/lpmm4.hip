@@ -134,8 +134,9 @@ void fast_geometry(Tensor4* a, int n_cu, int64_t rw_hint, int64_t rw2_hint) {
     }
     const int64_t cap = (int64_t(1) << 29) / a->cols;     // lane offsets inside a tile stay below 2^31 bytes
     if (rw > cap) rw = cap;
+    if (rw * gx > kMaxRowSlots) rw = kMaxRowSlots / gx;    // per-row results of a tile are staged in LDS
     rw = round_up(rw, a->gy);
-    if (rw > cap) rw -= a->gy;
+    if (rw > cap || rw * gx > kMaxRowSlots) rw -= a->gy;
     if (rw > a->rows) rw = round_up(a->rows, a->gy);
     if (rw < a->gy) rw = a->gy;
     a->rw = int(rw);
@@ -578,7 +579,7 @@ int lpmm_adamw4_plan_build(const lpmm_tensor_desc* descs, int64_t n, int grad_dt
     }
     for (size_t j = 0; j <= groups.size(); ++j) {
         PhaseLaunch pl{};
-        pl.ph.tensors = d_tens;
+        pl.ph.tensors = reinterpret_cast<const Tensor4Table*>(d_tens);
         if (j < groups.size())
             for (int64_t i = groups[j].first; i < groups[j].second; ++i) {
                 pl.ph.seg_a[pl.ph.n_seg_a++] = Segment{pl.ph.n_a, int(i)};
