@@ -57,10 +57,17 @@ def lib() -> ctypes.CDLL:
         L.oracle_adamw4_step.argtypes = [f32p, f32p, u8p, f32p, u8p, f32p, f32p, i64, i64,
                                          cf, cf, cf, cf, cf, i64, f32p, f32p]
         L.oracle_state_zero.argtypes = [u8p, f32p, u8p, f32p, f32p, i64, i64]
+        L.oracle_quant_v_block.argtypes = [f32p, i64, u8p, f32p]
+        L.oracle_dequant_v_block.argtypes = [u8p, f32p, i64, f32p]
+        L.oracle_adamw4_b128_step.argtypes = [f32p, f32p, u8p, f32p, u8p, f32p, i64,
+                                              cf, cf, cf, cf, cf, i64, f32p, f32p]
+        L.oracle_state_zero_b128.argtypes = [u8p, f32p, u8p, f32p, i64]
         for name in ("oracle_table_linear", "oracle_table_de", "oracle_table_de_f64",
                      "oracle_step_table", "oracle_nearest_codes", "oracle_quant_m",
                      "oracle_dequant_m", "oracle_quant_v", "oracle_dequant_v",
-                     "oracle_adamw32_step", "oracle_adamw4_step", "oracle_state_zero"):
+                     "oracle_adamw32_step", "oracle_adamw4_step", "oracle_state_zero",
+                     "oracle_quant_v_block", "oracle_dequant_v_block", "oracle_adamw4_b128_step",
+                     "oracle_state_zero_b128"):
             getattr(L, name).restype = None
         _lib = L
     return _lib
@@ -151,6 +158,21 @@ def dequant_v(codes: np.ndarray, r: np.ndarray, c: np.ndarray) -> np.ndarray:
     return out
 
 
+def quant_v_block(x: np.ndarray):
+    """B128/Linear compress of a non-negative flat tensor (second moment of 1-D / flattened tensors)."""
+    x = np.ascontiguousarray(x, np.float32).reshape(-1)
+    codes = np.zeros(codes_bytes(x.size), np.uint8)
+    scales = np.zeros(n_blocks(x.size), np.float32)
+    lib().oracle_quant_v_block(_f32(x), x.size, _u8(codes), _f32(scales))
+    return codes, scales
+
+
+def dequant_v_block(codes: np.ndarray, scales: np.ndarray, P: int) -> np.ndarray:
+    out = np.empty(P, np.float32)
+    lib().oracle_dequant_v_block(_u8(codes), _f32(scales), P, _f32(out))
+    return out
+
+
 def unpack_codes(codes: np.ndarray, P: int) -> np.ndarray:
     """Byte k holds element 2k in its low nibble and element 2k+1 in its high nibble."""
     out = np.empty(codes.size * 2, np.uint8)
@@ -214,3 +236,39 @@ def adamw4_step(w: np.ndarray, g: np.ndarray, st: State4, hp: Hyper, t: int, wan
 def adamw32_step(w: np.ndarray, g: np.ndarray, m: np.ndarray, v: np.ndarray, hp: Hyper, t: int):
     lib().oracle_adamw32_step(_f32(w), _f32(g), _f32(m), _f32(v), w.size, hp.lr, hp.beta1, hp.beta2,
                               hp.eps, hp.weight_decay, t)
+
+
+@dataclass
+class StateB128:
+    """Compressed state of a flat tensor of P elements, both moments block-wise (B128)."""
+    P: int
+    m_codes: np.ndarray
+    m_scales: np.ndarray
+    v_codes: np.ndarray
+    v_scales: np.ndarray
+
+    def copy(self) -> "StateB128":
+        return StateB128(self.P, self.m_codes.copy(), self.m_scales.copy(), self.v_codes.copy(),
+                         self.v_scales.copy())
+
+
+def state_zero_b128(P: int) -> StateB128:
+    st = StateB128(P, np.zeros(codes_bytes(P), np.uint8), np.zeros(n_blocks(P), np.float32),
+                   np.zeros(codes_bytes(P), np.uint8), np.zeros(n_blocks(P), np.float32))
+    lib().oracle_state_zero_b128(_u8(st.m_codes), _f32(st.m_scales), _u8(st.v_codes), _f32(st.v_scales), P)
+    return st
+
+
+def adamw4_b128_step(w: np.ndarray, g: np.ndarray, st: StateB128, hp: Hyper, t: int, want_moments=False):
+    """In place on w (float32, P) and st; second moment compressed block-wise."""
+    assert w.size == st.P == g.size
+    mt = vt = None
+    null = ctypes.POINTER(ctypes.c_float)()
+    if want_moments:
+        mt = np.empty(w.size, np.float32)
+        vt = np.empty(w.size, np.float32)
+    lib().oracle_adamw4_b128_step(_f32(w), _f32(g), _u8(st.m_codes), _f32(st.m_scales), _u8(st.v_codes),
+                                  _f32(st.v_scales), st.P, hp.lr, hp.beta1, hp.beta2, hp.eps,
+                                  hp.weight_decay, t, _f32(mt) if want_moments else null,
+                                  _f32(vt) if want_moments else null)
+    return mt, vt

@@ -14,6 +14,10 @@
 //   * Sec. 3: block size 128 for the first moment.
 //   * Sec. 4.1 and App. D.2: the zero-excluding Linear map T(i) = (i+1)/2^b.
 //   * Sec. 4.2: rank-1 normalization, r_i = max_j x_ij, c_j = max_i x_ij, n_ij = x_ij / min(r_i, c_j).
+//   * Sec. 4.2, last paragraph: for 1-dimensional tensors rank-1 normalization degenerates, and
+//     block-wise normalization with block size 128 is used for the second moment instead (the
+//     mapping stays the Linear one).  App. C.1 (LLaMA): FSDP packs parameters into 1-dimensional
+//     arrays, so that run used this form for every tensor.  Functions *_v_block / *_b128_*.
 //   * App. D.1: signed normalization n = sign(x) N(|x|).
 //   * App. D.2: the dynamic-exponent (DE) map: sign bit, E leading zeros, indicator bit,
 //     F fraction bits; value 10^-E * fraction[k]; two special bit patterns; sorted list.
@@ -37,7 +41,8 @@
 //
 // Parity status: every function below is pinned by the CPU tests against values the paper prints,
 // closed forms, brute force, invariants or an fp64 library AdamW, EXCEPT the multi-step trajectory
-// of the full quantized step, for which the paper prints nothing: "parity unpinned" beyond its parts.
+// of the full quantized step (either second-moment form), for which the paper prints nothing:
+// "parity unpinned" beyond its parts.
 //
 // Build: g++ -O2 -std=c++17 -ffp-contract=off -fPIC -shared lpmm_oracle.cpp -o liblpmm_oracle.so
 
@@ -195,6 +200,33 @@ void dequant_v(const uint8_t* codes, const float* r, const float* c, int64_t row
 }
 
 // ---------------------------------------------------------------------------------------------
+// Second moment of 1-dimensional (or flattened) tensors: B128 normalization (Sec. 2.2 block-wise
+// normalization with the block size of Sec. 3, chosen by Sec. 4.2 for this case) + Linear map.
+// The moment is non-negative, so the block's scale max|x| is max x.
+// ---------------------------------------------------------------------------------------------
+
+void quant_v_block(const float* x, int64_t P, uint8_t* codes, float* scales) {
+    const float* T = tables().lin;
+    std::memset(codes, 0, size_t((P + 1) / 2));
+    const int64_t nblk = (P + kBlock - 1) / kBlock;
+    for (int64_t k = 0; k < nblk; ++k) {
+        const int64_t lo = k * kBlock, hi = std::min(P, lo + kBlock);
+        float s = 0.0f;
+        for (int64_t i = lo; i < hi; ++i) s = std::max(s, std::fabs(x[i]));
+        scales[k] = s;
+        for (int64_t i = lo; i < hi; ++i) {
+            const float n = (s == 0.0f) ? 0.0f : x[i] / s;
+            put_code(codes, i, nearest_code(T, kCodes, n));
+        }
+    }
+}
+
+void dequant_v_block(const uint8_t* codes, const float* scales, int64_t P, float* out) {
+    const float* T = tables().lin;
+    for (int64_t i = 0; i < P; ++i) out[i] = T[get_code(codes, i)] * scales[i / kBlock];
+}
+
+// ---------------------------------------------------------------------------------------------
 // The optimizer rule A of Alg. 1: Adam (Eq. 1) with decoupled weight decay, on precise states.
 // m and v are updated in place (m_{t-1} -> m_t); w is updated in place.
 // ---------------------------------------------------------------------------------------------
@@ -292,6 +324,35 @@ void oracle_adamw4_step(float* w, const float* g, uint8_t* m_codes, float* m_sca
     if (v_t_out) std::memcpy(v_t_out, v.data(), sizeof(float) * size_t(P));
     quant_m(m.data(), P, m_codes, m_scales);                      // Alg. 3: compress
     quant_v(v.data(), rows, cols, v_codes, v_r, v_c);
+}
+
+// The same step for a 1-dimensional or flattened tensor of P elements: the second moment is
+// compressed block-wise (B128/Linear) instead of rank-1 (Sec. 4.2, last paragraph).  Everything is
+// local to a block of 128 elements.
+void oracle_quant_v_block(const float* x, int64_t P, uint8_t* codes, float* scales) {
+    quant_v_block(x, P, codes, scales);
+}
+void oracle_dequant_v_block(const uint8_t* codes, const float* scales, int64_t P, float* out) {
+    dequant_v_block(codes, scales, P, out);
+}
+void oracle_adamw4_b128_step(float* w, const float* g, uint8_t* m_codes, float* m_scales,
+                             uint8_t* v_codes, float* v_scales, int64_t P, float lr, float beta1,
+                             float beta2, float eps, float wd, int64_t t, float* m_t_out,
+                             float* v_t_out) {
+    std::vector<float> m(static_cast<size_t>(P)), v(static_cast<size_t>(P));
+    dequant_m(m_codes, m_scales, P, m.data());                    // Alg. 3: decompress
+    dequant_v_block(v_codes, v_scales, P, v.data());
+    adamw_rule(w, m.data(), v.data(), g, P, lr, beta1, beta2, eps, wd, t);   // Eq. 1
+    if (m_t_out) std::memcpy(m_t_out, m.data(), sizeof(float) * size_t(P));
+    if (v_t_out) std::memcpy(v_t_out, v.data(), sizeof(float) * size_t(P));
+    quant_m(m.data(), P, m_codes, m_scales);                      // Alg. 3: compress
+    quant_v_block(v.data(), P, v_codes, v_scales);
+}
+void oracle_state_zero_b128(uint8_t* m_codes, float* m_scales, uint8_t* v_codes, float* v_scales,
+                            int64_t P) {
+    std::vector<float> z(static_cast<size_t>(P), 0.0f);
+    quant_m(z.data(), P, m_codes, m_scales);
+    quant_v_block(z.data(), P, v_codes, v_scales);
 }
 
 // The zero initial state of Alg. 3 (m_0 = v_0 = 0): m codes all point at the table's 0 entry with
