@@ -7,6 +7,11 @@ tensor the fp32-state AdamW kernel.  All inputs are synthetic, seeded and reside
 timed region starts.  Prints ONE JSON line (see the keys at the bottom).
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c5_llama_7b] [--no-cpu-baseline]
+
+With --second-moment b128 every quantized tensor is taken flat and its second moment is compressed
+block-wise (what the method uses for 1-dimensional and flattened parameters): the step is then one
+kernel that touches every byte once.  The default (rank1) is the configuration the headline metric
+is quoted on.
 """
 import argparse
 import json
@@ -30,6 +35,12 @@ def bytes_per_param(bf16: bool):
     return p1, p2
 
 
+# block-wise second moment, one pass: param read+write 8, grad 4 or 2, both moments' codes read+write 2,
+# both moments' block scales read+write 16/128
+def bytes_per_param_b128(bf16: bool):
+    return 8.0 + (2.0 if bf16 else 4.0) + 2.0 + 16.0 / 128.0
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -40,6 +51,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--grad-dtype", choices=["config", "bf16", "f32"], default="config",
                     help="override the gradient type of the configuration (experiments)")
+    ap.add_argument("--second-moment", choices=["rank1", "b128"], default="rank1",
+                    help="rank1: rank-1/Linear second moment of 2-D tensors (two passes, the headline "
+                         "configuration); b128: every tensor flat with a block-wise second moment (one pass)")
     ap.add_argument("--launch", choices=["multi", "per-tensor"], default="multi",
                     help="multi: one plan, pass 1 / pass 2 of neighbouring tensor groups share launches; "
                          "per-tensor: two launches per quantized tensor")
@@ -89,7 +103,9 @@ def main():
                 z[zero, :] = 0.0
             gs.append(z.reshape(-1).to(torch.bfloat16) if bf16 else z.reshape(-1).contiguous())
             del z
-        if sp.quantized:
+        if sp.quantized and args.second_moment == "b128":
+            tensors.append(("q", sp, p, gs, lpmm.new_state_b128(sp.numel, dev)))
+        elif sp.quantized:
             st = lpmm.new_state(sp.rows, sp.cols, dev)
             max_rc = max(max_rc, sp.rows + sp.cols)
             tensors.append(("q", sp, p, gs, st))
@@ -102,7 +118,11 @@ def main():
 
     n_params = sum(sp.numel for sp in specs)
     n_quant = sum(sp.numel for sp in specs if sp.quantized)
-    step4 = lpmm.lpmm_adamw4_step_bf16g if bf16 else lpmm.lpmm_adamw4_step
+    b128 = args.second_moment == "b128"
+    if b128:
+        step4 = lpmm.lpmm_adamw4_b128_step_bf16g if bf16 else lpmm.lpmm_adamw4_b128_step
+    else:
+        step4 = lpmm.lpmm_adamw4_step_bf16g if bf16 else lpmm.lpmm_adamw4_step
 
     # one plan per gradient set (a plan refers to its buffers by address)
     plans = []
@@ -139,7 +159,7 @@ def main():
     value = n_params / (elapsed / args.steps)
 
     # ---- the same K steps again with HIP events around every launch of the step -------------------------
-    bp1, bp2 = bytes_per_param(bf16)
+    bp1, bp2 = (bytes_per_param_b128(bf16), 0.0) if b128 else bytes_per_param(bf16)
     n_small = n_params - n_quant
     small_bytes = (24.0 + (2.0 if bf16 else 4.0)) * n_small      # fp32-state AdamW: p, m, v read+write, g read
     n_q_tensors = sum(1 for x in tensors if x[0] == "q")
@@ -157,16 +177,18 @@ def main():
         avg_ms = p1_ms / launches
         achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9
         roofline = {
-            "bound": "hbm", "kernel": "phase_kernel<roles=1> (pass 1)", "achieved": round(achieved, 1),
+            "bound": "hbm", "kernel": "phase_kernel<roles=1> (%s)" % ("the whole block-wise step" if b128 else "pass 1"),
+            "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
             "bytes_per_param": bp1, "launches": n_calls, "avg_launch_ms": round(avg_ms, 5),
             "bytes_per_launch": round(bytes_per_launch),
             "traffic_source": None,
-            "note": "pass 2 of the neighbouring tensor group (%.1f B/param) runs concurrently and shares "
-                    "the bandwidth; whole-step figures are in config" % bp2,
+            "note": ("one pass: this kernel is the whole step" if b128 else
+                     "pass 2 of the neighbouring tensor group (%.1f B/param) runs concurrently and shares "
+                     "the bandwidth; whole-step figures are in config" % bp2),
         }
         # HBM bytes per launch measured offline with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/)
-        tpath = os.path.join(ROOT, "profiles", "traffic_phase_kernel_%s.json" % args.config)
+        tpath = os.path.join(ROOT, "profiles", "traffic_phase_kernel_%s%s.json" % (args.config, "_b128" if b128 else ""))
         if os.path.exists(tpath):
             tr = json.load(open(tpath))
             if tr.get("launches_per_step") == n_calls // max(args.steps, 1):
@@ -177,7 +199,8 @@ def main():
         p1_bytes_per_launch = bp1 * n_quant * args.steps / launches
         achieved = p1_bytes_per_launch / (p1_avg_ms * 1e-3) / 1e9
         roofline = {
-            "bound": "hbm", "kernel": "pass1_fast", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+            "bound": "hbm", "kernel": "b128_kernel" if b128 else "pass1_fast", "achieved": round(achieved, 1),
+            "peak": HBM_PEAK_GBPS,
             "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
             "bytes_per_param": bp1, "launches": n_calls, "avg_launch_ms": round(p1_avg_ms, 5),
             "bytes_per_launch": round(p1_bytes_per_launch),
@@ -193,13 +216,14 @@ def main():
         rows = min(big.rows, max(1, (24 << 20) // big.cols))        # about 25 M parameters of that tensor
         cols = big.cols
         w = workloads.weights(args.seed, 0, rows, cols).reshape(-1)
-        st = oracle.state_zero(rows, cols)
+        st = oracle.state_zero_b128(rows * cols) if b128 else oracle.state_zero(rows, cols)
+        cpu_step = oracle.adamw4_b128_step if b128 else oracle.adamw4_step
         hp = oracle.Hyper(lr, b1, b2, eps, wd)
         n_cpu_steps = 20
         gs = [workloads.grads(args.seed, 0, s, rows, cols, recipe, bf16).reshape(-1) for s in (1, 2)]
         c0 = time.perf_counter()
         for s in range(1, n_cpu_steps + 1):
-            oracle.adamw4_step(w, gs[s % 2], st, hp, s)
+            cpu_step(w, gs[s % 2], st, hp, s)
         cdt = time.perf_counter() - c0
         cpu = {"value": round(rows * cols * n_cpu_steps / cdt, 1), "unit": "params/s", "cores": 1,
                "kind": "oracle",
@@ -214,12 +238,16 @@ def main():
         "data": "synthetic",
         "config": {"workload": args.config, "tensors": len(specs), "params": n_params,
                    "quantized_params": n_quant, "grad_dtype": "bf16" if bf16 else "f32",
+                   "second_moment": "block-wise B128/Linear on flattened tensors, one pass" if b128
+                   else "rank-1/Linear, two passes",
                    "grad_recipe": recipe,
-                   "launch": ("multi-tensor plan, %d pass-1 launches per step on the caller's stream, "
-                              "pass 2 on a second stream" % (n_calls // max(args.steps, 1)))
-                   if plans else "per-tensor, 2 kernels per quantized tensor",
-                   "hbm_gbps_two_pass_model": round(total_gbps, 1),
-                   "hbm_frac_two_pass_model": round(total_gbps / HBM_PEAK_GBPS, 4)},
+                   "launch": (("multi-tensor plan, %d launches per step" if b128 else
+                               "multi-tensor plan, %d pass-1 launches per step on the caller's stream, "
+                               "pass 2 on a second stream") % (n_calls // max(args.steps, 1)))
+                   if plans else "per-tensor, %d kernel%s per quantized tensor" % ((1, "") if b128 else (2, "s")),
+                   ("hbm_gbps_one_pass_model" if b128 else "hbm_gbps_two_pass_model"): round(total_gbps, 1),
+                   ("hbm_frac_one_pass_model" if b128 else "hbm_frac_two_pass_model"):
+                       round(total_gbps / HBM_PEAK_GBPS, 4)},
         "roofline": roofline, "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)

@@ -110,6 +110,38 @@ int lpmm_adamw4_step_bf16g(void* param, const void* grad, uint8_t* m_codes, floa
                            const int64_t shape[2], float lr, float beta1, float beta2, float eps,
                            float weight_decay, int64_t step, void* stream);
 
+/* ---- block-wise second moment: 1-dimensional and flattened tensors ---------------------------------
+ * Rank-1 normalization needs a 2-dimensional shape; for a 1-dimensional tensor it degenerates and the
+ * paper uses block-wise normalization with block size 128 for the second moment as well (Sec. 4.2,
+ * last paragraph), keeping the Linear map of Sec. 4.1.  The same holds when a framework hands the
+ * optimizer flattened parameters (App. C.1: the LLaMA runs under FSDP).  State of such a tensor of
+ * `numel` elements:
+ *   m_codes, m_blockscale   as above
+ *   v_codes      uint8[(numel+1)/2]        code q stands for (q+1)/16
+ *   v_blockscale float[ceil(numel/128)]    maximum of block k = elements [128k, 128k+127]
+ * zero state: m codes 7, v codes 0, all scales 0.  Everything is local to a block, so the step is
+ * ONE kernel that touches every byte once (no workspace; lpmm_adamw4_init must still have run on the
+ * current device: the lookup tables live there).  param, grad 16-byte aligned, the rest 4-byte. */
+
+/* sizes[4] (host, out): bytes of m_codes, m_blockscale, v_codes, v_blockscale. */
+int lpmm_adamw4_b128_state_sizes(int64_t numel, size_t sizes[4]);
+
+/* Writes the zero state on `stream`. */
+int lpmm_adamw4_b128_state_zero(uint8_t* m_codes, float* m_blockscale, uint8_t* v_codes,
+                                float* v_blockscale, int64_t numel, void* stream);
+
+/* One AdamW step (App. E Alg. 3 with the block-wise second moment), in place on param and the four
+ * state buffers; grad (float[numel]) is read only.  Hyper-parameters and `step` as lpmm_adamw4_step. */
+int lpmm_adamw4_b128_step(void* param, const void* grad, uint8_t* m_codes, float* m_blockscale,
+                          uint8_t* v_codes, float* v_blockscale, int64_t numel, float lr, float beta1,
+                          float beta2, float eps, float weight_decay, int64_t step, void* stream);
+
+/* Same step with a bf16 gradient buffer. */
+int lpmm_adamw4_b128_step_bf16g(void* param, const void* grad, uint8_t* m_codes, float* m_blockscale,
+                                uint8_t* v_codes, float* v_blockscale, int64_t numel, float lr,
+                                float beta1, float beta2, float eps, float weight_decay, int64_t step,
+                                void* stream);
+
 /* AdamW step with uncompressed fp32 states, for tensors that are not quantized (App. C.1: size
  * <= 4096, biases and normalization vectors): Alg. 3 with compress = decompress = identity.
  * param, m, v: float[numel] in place; grad: float or bf16 [numel] per grad_dtype. */
@@ -120,6 +152,7 @@ int lpmm_adamw32_step(void* param, const void* grad, float* m, float* v, int64_t
 /* Decompress one moment to fp32 (the dequantizer N^-1 o T of Sec. 2.2).
  * which = 0: first moment, scale_a = m_blockscale, scale_b ignored (may be NULL).
  * which = 1: second moment, scale_a = v_rowmax, scale_b = v_colmax.
+ * which = 2: block-wise second moment, scale_a = v_blockscale, scale_b ignored (may be NULL).
  * out: float[P]. */
 int lpmm_dequant_state(int which, const uint8_t* codes, const float* scale_a, const float* scale_b,
                        const int64_t shape[2], float* out, void* stream);
@@ -141,6 +174,9 @@ int lpmm_quant_state(int which, const float* in, const int64_t shape[2], uint8_t
 
 #define LPMM_KIND_4BIT 0   /* quantized states as in lpmm_adamw4_step */
 #define LPMM_KIND_FP32 1   /* uncompressed fp32 states as in lpmm_adamw32_step */
+#define LPMM_KIND_4BIT_B128 2   /* quantized states, block-wise second moment, as in lpmm_adamw4_b128_step:
+                                   v_rowmax points at v_blockscale, v_colmax is ignored, the tensor is the
+                                   rows*cols elements taken flat */
 
 typedef struct lpmm_tensor_desc {
     void* param;            /* float[rows*cols], in place */

@@ -9,4 +9,6 @@ from .binding import (  # noqa: F401
     lpmm_adamw32_step, lpmm_dequant_state, lpmm_quant_state, ensure_init, new_state,
     lpmm_profile_begin, lpmm_profile_end, TensorDesc, make_desc, new_plan, KIND_4BIT, KIND_FP32,
     lpmm_adamw4_plan_bytes, lpmm_adamw4_plan_build, lpmm_adamw4_step_multi, lpmm_adamw4_plan_release,
+    StateB128, new_state_b128, KIND_4BIT_B128, lpmm_adamw4_b128_state_sizes, lpmm_adamw4_b128_state_zero,
+    lpmm_adamw4_b128_step, lpmm_adamw4_b128_step_bf16g,
 )

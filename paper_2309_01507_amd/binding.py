@@ -72,6 +72,11 @@ def lib() -> ctypes.CDLL:
         L.lpmm_adamw4_step.argtypes = step_args
         L.lpmm_adamw4_step_bf16g.argtypes = step_args
         L.lpmm_adamw32_step.argtypes = [_VP] * 4 + [_I64, ctypes.c_int] + [_F] * 5 + [_I64, _VP]
+        L.lpmm_adamw4_b128_state_sizes.argtypes = [_I64, _VP]
+        L.lpmm_adamw4_b128_state_zero.argtypes = [_VP] * 4 + [_I64, _VP]
+        b128_args = [_VP] * 6 + [_I64] + [_F] * 5 + [_I64, _VP]
+        L.lpmm_adamw4_b128_step.argtypes = b128_args
+        L.lpmm_adamw4_b128_step_bf16g.argtypes = b128_args
         L.lpmm_dequant_state.argtypes = [ctypes.c_int, _VP, _VP, _VP, _VP, _VP, _VP]
         L.lpmm_quant_state.argtypes = [ctypes.c_int, _VP, _VP, _VP, _VP, _VP, _VP]
         L.lpmm_adamw4_plan_bytes.argtypes = [_VP, _I64]
@@ -225,6 +230,62 @@ def lpmm_adamw4_step_bf16g(param, grad, st: State4, lr, beta1, beta2, eps, weigh
     _step("lpmm_adamw4_step_bf16g", param, grad, st, lr, beta1, beta2, eps, weight_decay, step, stream)
 
 
+# ---- block-wise second moment (1-D / flattened tensors) ------------------------------------------------
+
+@dataclass
+class StateB128:
+    """The four device buffers of a flat tensor's optimizer state, both moments block-wise."""
+    numel: int
+    m_codes: "object"
+    m_blockscale: "object"
+    v_codes: "object"
+    v_blockscale: "object"
+
+
+def lpmm_adamw4_b128_state_sizes(numel: int):
+    sizes = (ctypes.c_size_t * 4)()
+    _check(lib().lpmm_adamw4_b128_state_sizes(int(numel), ctypes.addressof(sizes)),
+           "lpmm_adamw4_b128_state_sizes")
+    return [int(s) for s in sizes]
+
+
+def lpmm_adamw4_b128_state_zero(st: StateB128, stream=None) -> None:
+    _check(lib().lpmm_adamw4_b128_state_zero(_ptr(st.m_codes), _ptr(st.m_blockscale), _ptr(st.v_codes),
+                                             _ptr(st.v_blockscale), int(st.numel), _stream(stream)),
+           "lpmm_adamw4_b128_state_zero")
+
+
+def new_state_b128(numel: int, device="cuda") -> StateB128:
+    """Allocate (torch) and zero (library) the block-wise state of a flat tensor."""
+    import torch
+    sz = lpmm_adamw4_b128_state_sizes(numel)
+    pad4 = lambda n: (n + 3) // 4 * 4
+    st = StateB128(numel,
+                   torch.empty(pad4(sz[0]), dtype=torch.uint8, device=device)[:sz[0]],
+                   torch.empty(sz[1] // 4, dtype=torch.float32, device=device),
+                   torch.empty(pad4(sz[2]), dtype=torch.uint8, device=device)[:sz[2]],
+                   torch.empty(sz[3] // 4, dtype=torch.float32, device=device))
+    lpmm_adamw4_b128_state_zero(st)
+    return st
+
+
+def _b128_step(fn_name, param, grad, st: StateB128, lr, beta1, beta2, eps, weight_decay, step, stream):
+    fn = getattr(lib(), fn_name)
+    _check(fn(_ptr(param), _ptr(grad), _ptr(st.m_codes), _ptr(st.m_blockscale), _ptr(st.v_codes),
+              _ptr(st.v_blockscale), int(st.numel), lr, beta1, beta2, eps, weight_decay, int(step),
+              _stream(stream)), fn_name)
+
+
+def lpmm_adamw4_b128_step(param, grad, st: StateB128, lr, beta1, beta2, eps, weight_decay, step, stream=None):
+    _b128_step("lpmm_adamw4_b128_step", param, grad, st, lr, beta1, beta2, eps, weight_decay, step, stream)
+
+
+def lpmm_adamw4_b128_step_bf16g(param, grad, st: StateB128, lr, beta1, beta2, eps, weight_decay, step,
+                                stream=None):
+    _b128_step("lpmm_adamw4_b128_step_bf16g", param, grad, st, lr, beta1, beta2, eps, weight_decay, step,
+               stream)
+
+
 def lpmm_adamw32_step(param, grad, m, v, numel, grad_dtype, lr, beta1, beta2, eps, weight_decay, step,
                       stream=None):
     _check(lib().lpmm_adamw32_step(_ptr(param), _ptr(grad), _ptr(m), _ptr(v), int(numel),
@@ -248,7 +309,7 @@ def lpmm_quant_state(which: int, x, rows, cols, codes, scale_a, scale_b, stream=
 
 # ---- many tensors in one call ------------------------------------------------------------------------
 
-KIND_4BIT, KIND_FP32 = 0, 1
+KIND_4BIT, KIND_FP32, KIND_4BIT_B128 = 0, 1, 2
 
 
 class TensorDesc(ctypes.Structure):
@@ -259,7 +320,12 @@ class TensorDesc(ctypes.Structure):
 
 
 def make_desc(param, grad, state, rows=None, cols=None) -> TensorDesc:
-    """state: a State4 (4-bit) or a (m, v) pair of fp32 tensors (then rows, cols must be given)."""
+    """state: a State4 (4-bit, rank-1 second moment), a StateB128 (4-bit, block-wise second moment)
+    or a (m, v) pair of fp32 tensors (then rows, cols must be given)."""
+    if isinstance(state, StateB128):
+        return TensorDesc(_ptr(param), _ptr(grad), _ptr(state.m_codes), _ptr(state.m_blockscale),
+                          _ptr(state.v_codes), _ptr(state.v_blockscale), None, 1, state.numel,
+                          KIND_4BIT_B128, 0)
     if isinstance(state, State4):
         return TensorDesc(_ptr(param), _ptr(grad), _ptr(state.m_codes), _ptr(state.m_blockscale),
                           _ptr(state.v_codes), _ptr(state.v_rowmax), _ptr(state.v_colmax), state.rows,

@@ -25,7 +25,7 @@ namespace lpmm {
 __device__ float d_byte_decode[512];          // entry b: {T_DE[b & 15], T_DE[b >> 4]}
 __device__ SearchEntry d_search[kBucketsPadded];    // nearest-entry search for the DE map
 
-enum TensorKind : int { kQuantFast = 0, kQuantGeneral = 1, kFp32State = 2 };
+enum TensorKind : int { kQuantFast = 0, kQuantGeneral = 1, kFp32State = 2, kQuantBlockV = 3 };
 
 struct Tensor4 {
     float* p;               // parameters, fp32 [P]
@@ -33,7 +33,7 @@ struct Tensor4 {
     uint32_t* mq;           // first-moment codes, 8 per word   (kFp32State: float* m)
     float* ms;              // first-moment block scales
     uint32_t* vq;           // second-moment codes              (kFp32State: float* v)
-    float* r;               // row maxima (state)
+    float* r;               // row maxima (state)               (kQuantBlockV: block scales of v)
     float* c;               // column maxima (state)
     float* r_new;           // workspace: row maxima of v_t (zero between steps)
     float* c_new;           // workspace: column maxima of v_t (zero between steps)
@@ -707,6 +707,244 @@ __device__ __forceinline__ void pass2_fast_tile(const Tensor4& a, const Hyper& h
 }
 
 // =====================================================================================================
+// Block-wise second moment (1-dimensional or flattened tensors; Sec. 4.2, last paragraph): both
+// moments are normalized per block of 128 elements, nothing crosses a block, and the whole step is
+// ONE pass.  Same lane layout as pass 1 (4 elements per lane, 32 lanes per block); a workgroup's 8
+// groups take 8 consecutive blocks per round (4 KiB of parameters), `rounds` rounds per tile.  The
+// tensor is a.P elements, a.r holds the second moment's block scales.  The tile routine covers whole
+// blocks; a ragged last block is done by b128_tail_block.
+// =====================================================================================================
+
+struct TileB {
+    float* p;
+    uint8_t* mq;
+    uint8_t* vq;
+    float* ms;
+    float* vs;
+    Rsrc rp, rg, rmq, rvq, rms, rvs;      // bounds-checked views of the tile, for the loads
+};
+
+template <bool BF16>
+__device__ __forceinline__ TileB tile_b128(const Tensor4& a, int64_t blk0, int n_blk) {
+    TileB b;
+    const int64_t e = blk0 * 128;
+    const uint32_t elems = uint32_t(n_blk) * 128u;
+    b.p = a.p + e;
+    b.mq = reinterpret_cast<uint8_t*>(a.mq) + (e >> 1);
+    b.vq = reinterpret_cast<uint8_t*>(a.vq) + (e >> 1);
+    b.ms = a.ms + blk0;
+    b.vs = a.r + blk0;
+    b.rp = tile_rsrc(b.p, elems * 4u);
+    b.rg = tile_rsrc(reinterpret_cast<const char*>(a.g) + e * (BF16 ? 2 : 4), elems * (BF16 ? 2u : 4u));
+    b.rmq = tile_rsrc(b.mq, elems >> 1);
+    b.rvq = tile_rsrc(b.vq, elems >> 1);
+    b.rms = tile_rsrc(b.ms, uint32_t(n_blk) * 4u);
+    b.rvs = tile_rsrc(b.vs, uint32_t(n_blk) * 4u);
+    return b;
+}
+
+template <bool BF16>
+struct RowB {                      // everything the step reads for one block, per lane
+    float4 p;
+    GradRegs4<BF16> g;
+    uint16_t mq, vq;               // the lane's 4 codes of each moment
+    float sm_old, sv_old;          // the block's two scales
+};
+
+// ib = block index inside the tile; blocks at or beyond the tile's end read as zeros
+template <bool BF16>
+__device__ __forceinline__ RowB<BF16> load_rowb(const TileB& b, int ib, int l) {
+    RowB<BF16> r;
+    const uint32_t off4 = (uint32_t(ib) * 128u + uint32_t(l) * 4u) * 4u;
+    r.p = buf_ld_f4_stream(b.rp, off4);
+    r.g = load_grad_regs4<BF16>(b.rg, off4);
+    r.mq = buf_ld_u16(b.rmq, off4 >> 3);
+    r.vq = buf_ld_u16(b.rvq, off4 >> 3);
+    r.sm_old = buf_ld_f(b.rms, uint32_t(ib) * 4u);
+    r.sv_old = buf_ld_f(b.rvs, uint32_t(ib) * 4u);
+    return r;
+}
+
+template <bool BF16, class Mid>
+__device__ __forceinline__ void b128_row(const Hyper& h, const TileB& tb, Lds& s, const RowB<BF16>& cur,
+                                         int ib, int l, Mid mid) {
+    float w[4] = {cur.p.x, cur.p.y, cur.p.z, cur.p.w};
+    float g[4];
+    unpack_grad4<BF16>(cur.g, g);
+    float mt[4], vt[4], amax = 0.0f, vmax = 0.0f;
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        const float2 t = s.deq[(uint32_t(cur.mq) >> (8 * k)) & 255u];
+        mt[2 * k] = t.x * cur.sm_old;         // decompress: T_DE[code] * block scale
+        mt[2 * k + 1] = t.y * cur.sm_old;
+    }
+    if (__builtin_expect(__ballot(!scale_is_tame(cur.sv_old)) == 0, 1)) {
+        float qf[4];
+        codes_to_float4(cur.vq, qf);
+        const float s16 = cur.sv_old * 0.0625f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) vt[e] = dequant_v16(qf[e], s16);
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) vt[e] = dequant_v((uint32_t(cur.vq) >> (4 * e)) & 15u, cur.sv_old);
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        mt[e] = moment_m(h, mt[e], g[e]);
+        vt[e] = moment_v(h, vt[e], g[e]);
+        w[e] = param_update(h, w[e], mt[e], vt[e]);
+        amax = fmaxf(amax, fabsf(mt[e]));
+        vmax = max_nonneg(vmax, vt[e]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    mid();                                        // the caller's prefetch of a later block
+    __builtin_amdgcn_sched_barrier(0);
+    const float sm_new = group32_allmax(amax);    // block absmax of m_t
+    const float sv_new = group32_allmax(vmax);    // block maximum of v_t
+
+    uint32_t mq_new = 0;
+    uint32_t dist = scale_is_tame(sm_new) ? 0xFFFFFFFFu : 0u;
+    {
+        const float inv_s = approx_inv(sm_new);
+#pragma unroll
+        for (int e = 0; e < 4; e += 2) {
+            uint32_t da, db;
+            mq_new |= quant_m_code_fast(s.search, mt[e], inv_s, da) << (4 * e);
+            mq_new |= quant_m_code_fast(s.search, mt[e + 1], inv_s, db) << (4 * e + 4);
+            dist = min(min(dist, da), db);
+        }
+    }
+    if (__builtin_expect(__ballot(dist < kMinDistM) != 0, 0)) {
+        mq_new = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) mq_new |= quant_m_code(s.search, mt[e], sm_new) << (4 * e);
+    }
+
+    uint32_t vq_new;
+    {
+        const float inv_s = approx_inv(sv_new);
+        uint32_t lo = 0, hi = 0;
+        float closest = scale_is_tame(sv_new) ? 0.5f : 0.0f, fa, fb;
+#define LPMM_VB(K)                                                               \
+        lo = quant_v_code_fast<K>(vt[2 * K], inv_s, lo, fa);                     \
+        hi = quant_v_code_fast<K>(vt[2 * K + 1], inv_s, hi, fb);                 \
+        closest = fminf(fminf(closest, fabsf(fa)), fabsf(fb));
+        LPMM_VB(0) LPMM_VB(1)
+#undef LPMM_VB
+        vq_new = lo | (hi << 4);
+        if (__builtin_expect(__ballot(closest < kMarginV) != 0, 0)) {
+            vq_new = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) vq_new |= quant_v_code(vt[e], sv_new) << (4 * e);
+        }
+    }
+
+    const uint32_t off4 = (uint32_t(ib) * 128u + uint32_t(l) * 4u) * 4u;
+    st_stream4(tb.p, off4, make_float4(w[0], w[1], w[2], w[3]));
+    st<uint16_t>(tb.mq, off4 >> 3, uint16_t(mq_new));
+    st<uint16_t>(tb.vq, off4 >> 3, uint16_t(vq_new));
+    if (l == 0) {
+        s.blk_scale[ib] = sm_new;
+        s.blk_vmax[ib] = sv_new;
+    }
+}
+
+constexpr int kB128MaxRounds = kMaxRowSlots / kGroups;     // block results of a tile are staged in LDS
+
+// tile `wg` of a tensor: blocks [wg * 8 * a.rw, ...) where a.rw = rounds per tile, a.nb = whole blocks
+template <bool BF16>
+__device__ __forceinline__ void b128_tile(const Tensor4& a, const Hyper& h, int wg, Lds& s) {
+    const int64_t blk0 = int64_t(wg) * kGroups * a.rw;
+    const int64_t left = int64_t(a.nb) - blk0;
+    const int n = left < int64_t(kGroups) * a.rw ? int(left) : kGroups * a.rw;     // blocks of this tile
+    const TileB tb = tile_b128<BF16>(a, blk0, n);
+    const int grp = threadIdx.x >> 5, l = threadIdx.x & 31;
+    constexpr int stp = kGroups;
+    int ib = grp;
+    RowB<BF16> r0 = load_rowb<BF16>(tb, ib, l);
+    RowB<BF16> r1 = load_rowb<BF16>(tb, ib + stp, l);
+    RowB<BF16> r2;
+    load_tables(s);                                // the first blocks' loads are in flight meanwhile
+    __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);       // loop start-up state: nothing outstanding (see pass 1)
+    auto none = [] {};
+    while (ib + 2 * stp < n) {                     // rounds of three blocks, no exit in the middle
+        b128_row<BF16>(h, tb, s, r0, ib, l, [&] { r2 = load_rowb<BF16>(tb, ib + 2 * stp, l); });
+        b128_row<BF16>(h, tb, s, r1, ib + stp, l, [&] { r0 = load_rowb<BF16>(tb, ib + 3 * stp, l); });
+        b128_row<BF16>(h, tb, s, r2, ib + 2 * stp, l, [&] { r1 = load_rowb<BF16>(tb, ib + 4 * stp, l); });
+        ib += 3 * stp;
+    }
+    if (ib < n) {
+        b128_row<BF16>(h, tb, s, r0, ib, l, none);
+        if (ib + stp < n) b128_row<BF16>(h, tb, s, r1, ib + stp, l, none);
+    }
+    __syncthreads();
+    for (int t = threadIdx.x; t < n; t += kThreads) {      // the tile's new block scales, contiguous
+        tb.ms[t] = s.blk_scale[t];
+        tb.vs[t] = s.blk_vmax[t];
+    }
+}
+
+// The last, partial block of a tensor whose size is not a multiple of 128 (a.P - 128 * a.nb
+// elements, an even number).  One lane per element pair, exact arithmetic, reductions through LDS.
+template <bool BF16>
+__device__ __forceinline__ void b128_tail_block(const Tensor4& a, const Hyper& h, Lds& s) {
+    const int64_t e0 = int64_t(a.nb) * 128;
+    const int n = int(a.P - e0);                   // 1..127
+    const int t = threadIdx.x;
+    const bool on = t < (n + 1) / 2;               // this lane's pair: elements e0 + 2t, e0 + 2t + 1
+    float mt[2] = {0.0f, 0.0f}, vt[2] = {0.0f, 0.0f};
+    const float sm_old = a.ms[a.nb], sv_old = a.r[a.nb];
+    uint32_t bm = 0, bv = 0;
+    if (on) {
+        bm = reinterpret_cast<const uint8_t*>(a.mq)[(e0 >> 1) + t];
+        bv = reinterpret_cast<const uint8_t*>(a.vq)[(e0 >> 1) + t];
+    }
+    for (int k = 0; k < 2; ++k) {
+        const int64_t e = e0 + 2 * t + k;
+        if (on && e < a.P) {
+            const float2 dq = s.deq[bm];
+            const float g = load_grad1<BF16>(a.g, e);
+            mt[k] = moment_m(h, (k ? dq.y : dq.x) * sm_old, g);
+            vt[k] = moment_v(h, dequant_v((bv >> (4 * k)) & 15u, sv_old), g);
+            a.p[e] = param_update(h, a.p[e], mt[k], vt[k]);
+        }
+    }
+    s.col[t] = fmaxf(fabsf(mt[0]), fabsf(mt[1]));
+    s.col[kThreads + t] = fmaxf(vt[0], vt[1]);
+    __syncthreads();
+    float sm_new = 0.0f, sv_new = 0.0f;
+    for (int i = 0; i < 64; ++i) {                 // every lane reduces the 64 pairs itself
+        sm_new = fmaxf(sm_new, s.col[i]);
+        sv_new = fmaxf(sv_new, s.col[kThreads + i]);
+    }
+    if (on) {
+        uint32_t qm = 0, qv = 0;
+        for (int k = 0; k < 2; ++k)
+            if (e0 + 2 * t + k < a.P) {
+                qm |= quant_m_code(s.search, mt[k], sm_new) << (4 * k);
+                qv |= quant_v_code(vt[k], sv_new) << (4 * k);
+            }
+        reinterpret_cast<uint8_t*>(a.mq)[(e0 >> 1) + t] = uint8_t(qm);
+        reinterpret_cast<uint8_t*>(a.vq)[(e0 >> 1) + t] = uint8_t(qv);
+    }
+    if (t == 0) {
+        a.ms[a.nb] = sm_new;
+        a.r[a.nb] = sv_new;
+    }
+}
+
+// workgroups [0, n_wg2) run tiles of whole blocks, workgroup n_wg2 (if n_wg > n_wg2) the partial block
+template <bool BF16>
+__device__ __forceinline__ void b128_work(const Tensor4& a, const Hyper& h, int wg, Lds& s) {
+    if (wg < a.n_wg2) {
+        b128_tile<BF16>(a, h, wg, s);
+    } else {
+        load_tables(s);
+        b128_tail_block<BF16>(a, h, s);
+    }
+}
+
+// =====================================================================================================
 // General path: any rows x cols.  Lane t owns flat elements [8t, 8t+8); a group is still one block
 // of 128, but a lane's elements may lie in different rows, so row and column indices are tracked
 // per element and the maxima go straight to atomics (skipped when they cannot raise the value).
@@ -885,6 +1123,13 @@ __global__ __launch_bounds__(kThreads) void pass2_fast(const Tensor4 a, const Hy
 }
 
 template <bool BF16>
+__global__ __launch_bounds__(kThreads) void b128_kernel(const Tensor4 a, const Hyper h) {
+    __shared__ Lds s;
+    const int wg = logical_wg();
+    if (wg < a.n_wg) b128_work<BF16>(a, h, wg, s);
+}
+
+template <bool BF16>
 __global__ __launch_bounds__(kThreads) void pass1_general(const Tensor4 a, const Hyper h) {
     __shared__ Lds s;
     load_tables(s);
@@ -964,6 +1209,8 @@ __global__ __launch_bounds__(kThreads) void phase_kernel(const Phase ph, const H
             adamw32_tile<BF16>(a.p, a.g, reinterpret_cast<float*>(a.mq), reinterpret_cast<float*>(a.vq), a.P, h, wg);
         } else if (a.kind == kQuantFast) {
             pass1_fast_tile<BF16, false>(a, h, wg, s);
+        } else if (a.kind == kQuantBlockV) {
+            b128_work<BF16>(a, h, wg, s);
         } else {
             load_tables(s);
             pass1_general_tile<BF16>(a, h, wg, s);
@@ -1005,6 +1252,16 @@ __global__ __launch_bounds__(kThreads) void dequant_v_kernel(const QuantArgs q) 
         q.x_out[io.base + e] = dequant_v((w >> (4 * e)) & 15u, fminf(q.sa[i], q.sb[j]));
         if (++j == q.cols) { j = 0; ++i; }
     }
+}
+
+// second moment with block scales (1-dimensional / flattened tensors)
+__global__ __launch_bounds__(kThreads) void dequant_vb_kernel(const QuantArgs q) {
+    const int64_t t = int64_t(blockIdx.x) * kThreads + threadIdx.x;
+    const LaneIo io = lane_io(q.P, q.cols, t);
+    if (!io.nv) return;
+    const uint32_t w = load_codes(q.q_in, io);
+    const float s = q.sa[t >> 4];
+    for (int e = 0; e < io.nv; ++e) q.x_out[io.base + e] = dequant_v((w >> (4 * e)) & 15u, s);
 }
 
 __global__ __launch_bounds__(kThreads) void quant_m_kernel(const QuantArgs q) {

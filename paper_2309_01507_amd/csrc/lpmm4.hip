@@ -156,6 +156,24 @@ void fast_geometry(Tensor4* a, int n_cu, int64_t rw_hint, int64_t rw2_hint) {
     a->n_wg2 = int(a->strips2 * ((a->rows + rw2 - 1) / rw2));
 }
 
+// Tiling of a tensor whose second moment is block-wise: `rw` rounds of 8 blocks per workgroup over
+// the whole blocks, plus one workgroup for a partial last block.  rounds_hint > 0 fixes the rounds.
+void b128_geometry(Tensor4* a, int n_cu, int64_t rounds_hint) {
+    a->nb = int(a->P / LPMM_BLOCK);
+    int64_t rounds = env_int("LPMM_B128_ROUNDS", 0);
+    if (rounds <= 0) rounds = rounds_hint;
+    if (rounds <= 0) {
+        rounds = 16;
+        while (rounds > 1 && (a->nb + kGroups * rounds - 1) / (kGroups * rounds) < 2 * int64_t(n_cu)) rounds >>= 1;
+    }
+    if (rounds > kB128MaxRounds) rounds = kB128MaxRounds;
+    if (rounds < 1) rounds = 1;
+    a->rw = int(rounds);
+    a->n_wg2 = int((a->nb + kGroups * rounds - 1) / (kGroups * rounds));
+    a->n_wg = a->n_wg2 + ((a->P % LPMM_BLOCK) ? 1 : 0);
+    a->gx = 1; a->gy = kGroups; a->strips = 1; a->strips2 = 1; a->rw2 = 1;
+}
+
 bool fast_eligible(int64_t cols, const float* v_colmax) {
     return (cols % LPMM_BLOCK) == 0 && cols <= (int64_t(1) << 24) && aligned(v_colmax, 16) &&
            !env_int("LPMM_FORCE_GENERAL", 0);
@@ -223,6 +241,47 @@ int step_impl(bool bf16, void* param, const void* grad, uint8_t* m_codes, float*
     return bf16 ? launch_step<true>(t, h, fast, s) : launch_step<false>(t, h, fast, s);
 }
 
+int b128_step_impl(bool bf16, void* param, const void* grad, uint8_t* m_codes, float* m_blockscale,
+                   uint8_t* v_codes, float* v_blockscale, int64_t numel, float lr, float beta1, float beta2,
+                   float eps, float wd, int64_t step, void* stream) {
+    if (numel < 1 || numel > (int64_t(1) << 37)) return LPMM_EINVAL;
+    if (!param || !grad || !m_codes || !m_blockscale || !v_codes || !v_blockscale) return LPMM_EINVAL;
+    if (!aligned(param, 16) || !aligned(grad, 16) || !aligned(m_codes, 4) || !aligned(v_codes, 4) ||
+        !aligned(m_blockscale, 4) || !aligned(v_blockscale, 4))
+        return LPMM_EINVAL;
+    Hyper h;
+    int rc = make_hyper(lr, beta1, beta2, eps, wd, step, &h);
+    if (rc) return rc;
+    DeviceCtx* ctx;
+    rc = current_ctx(&ctx);      // the lookup tables live in device memory filled by init
+    if (rc) return rc;
+    Tensor4 t{};
+    t.p = static_cast<float*>(param);
+    t.g = grad;
+    t.mq = reinterpret_cast<uint32_t*>(m_codes);
+    t.ms = m_blockscale;
+    t.vq = reinterpret_cast<uint32_t*>(v_codes);
+    t.r = v_blockscale;
+    t.rows = 1;
+    t.cols = numel;
+    t.P = numel;
+    t.kind = kQuantBlockV;
+    b128_geometry(&t, ctx->n_cu, 0);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const bool rec = g_prof.on && g_prof.calls < g_prof.max_calls;
+    const int64_t call = g_prof.calls;
+    if (rec) LPMM_HIP(hipEventRecord(prof_event(call, 0), s));
+    if (bf16) hipLaunchKernelGGL(b128_kernel<true>, dim3(pad8(t.n_wg)), dim3(kThreads), 0, s, t, h);
+    else hipLaunchKernelGGL(b128_kernel<false>, dim3(pad8(t.n_wg)), dim3(kThreads), 0, s, t, h);
+    LPMM_HIP(hipGetLastError());
+    if (rec) {
+        LPMM_HIP(hipEventRecord(prof_event(call, 1), s));
+        LPMM_HIP(hipEventRecord(prof_event(call, 2), s));
+        g_prof.calls = call + 1;
+    }
+    return LPMM_OK;
+}
+
 int grid_for(int64_t items, int64_t per_thread, int max_blocks = 1 << 20) {
     const int64_t threads = (items + per_thread - 1) / per_thread;
     int64_t blocks = (threads + kThreads - 1) / kThreads;
@@ -269,7 +328,7 @@ struct PlanLayout {
 
 bool desc_shape_ok(const lpmm_tensor_desc& d) {
     int64_t shape[2] = {d.rows, d.cols}, r, c;
-    return check_shape(shape, &r, &c) == LPMM_OK && (d.kind == LPMM_KIND_4BIT || d.kind == LPMM_KIND_FP32);
+    return check_shape(shape, &r, &c) == LPMM_OK && (d.kind == LPMM_KIND_4BIT || d.kind == LPMM_KIND_FP32 || d.kind == LPMM_KIND_4BIT_B128);
 }
 
 bool plan_layout(const lpmm_tensor_desc* descs, int64_t n, PlanLayout* L) {
@@ -417,6 +476,41 @@ int lpmm_adamw4_step_bf16g(void* param, const void* grad, uint8_t* m_codes, floa
                      beta1, beta2, eps, weight_decay, step, stream);
 }
 
+int lpmm_adamw4_b128_state_sizes(int64_t numel, size_t sizes[4]) {
+    if (numel < 1 || numel > (int64_t(1) << 37) || !sizes) return LPMM_EINVAL;
+    sizes[0] = sizes[2] = size_t((numel + 1) / 2);
+    sizes[1] = sizes[3] = size_t((numel + LPMM_BLOCK - 1) / LPMM_BLOCK) * sizeof(float);
+    return LPMM_OK;
+}
+
+int lpmm_adamw4_b128_state_zero(uint8_t* m_codes, float* m_blockscale, uint8_t* v_codes, float* v_blockscale,
+                                int64_t numel, void* stream) {
+    size_t sz[4];
+    const int rc = lpmm_adamw4_b128_state_sizes(numel, sz);
+    if (rc) return rc;
+    if (!m_codes || !m_blockscale || !v_codes || !v_blockscale) return LPMM_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int r = fill(m_codes, int64_t(sz[0]), 0x77, (numel & 1) ? int64_t(sz[0]) - 1 : -1, 0x07, s);
+    if (!r) r = fill(m_blockscale, int64_t(sz[1]), 0, -1, 0, s);
+    if (!r) r = fill(v_codes, int64_t(sz[2]), 0, -1, 0, s);
+    if (!r) r = fill(v_blockscale, int64_t(sz[3]), 0, -1, 0, s);
+    return r;
+}
+
+int lpmm_adamw4_b128_step(void* param, const void* grad, uint8_t* m_codes, float* m_blockscale,
+                          uint8_t* v_codes, float* v_blockscale, int64_t numel, float lr, float beta1,
+                          float beta2, float eps, float weight_decay, int64_t step, void* stream) {
+    return b128_step_impl(false, param, grad, m_codes, m_blockscale, v_codes, v_blockscale, numel, lr, beta1,
+                          beta2, eps, weight_decay, step, stream);
+}
+
+int lpmm_adamw4_b128_step_bf16g(void* param, const void* grad, uint8_t* m_codes, float* m_blockscale,
+                                uint8_t* v_codes, float* v_blockscale, int64_t numel, float lr, float beta1,
+                                float beta2, float eps, float weight_decay, int64_t step, void* stream) {
+    return b128_step_impl(true, param, grad, m_codes, m_blockscale, v_codes, v_blockscale, numel, lr, beta1,
+                          beta2, eps, weight_decay, step, stream);
+}
+
 int lpmm_adamw32_step(void* param, const void* grad, float* m, float* v, int64_t numel, int grad_dtype,
                       float lr, float beta1, float beta2, float eps, float weight_decay, int64_t step,
                       void* stream) {
@@ -445,7 +539,7 @@ int lpmm_dequant_state(int which, const uint8_t* codes, const float* scale_a, co
     int64_t rows, cols;
     const int rc = check_shape(shape, &rows, &cols);
     if (rc) return rc;
-    if ((which != 0 && which != 1) || !codes || !scale_a || !out || (which == 1 && !scale_b))
+    if ((which != 0 && which != 1 && which != 2) || !codes || !scale_a || !out || (which == 1 && !scale_b))
         return LPMM_EINVAL;
     if (!aligned(codes, 4) || !aligned(out, 4)) return LPMM_EINVAL;
     DeviceCtx* ctx;
@@ -460,7 +554,8 @@ int lpmm_dequant_state(int which, const uint8_t* codes, const float* scale_a, co
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int grid = grid_for(q.P, 8);
     if (which == 0) hipLaunchKernelGGL(dequant_m_kernel, dim3(grid), dim3(kThreads), 0, s, q);
-    else hipLaunchKernelGGL(dequant_v_kernel, dim3(grid), dim3(kThreads), 0, s, q);
+    else if (which == 1) hipLaunchKernelGGL(dequant_v_kernel, dim3(grid), dim3(kThreads), 0, s, q);
+    else hipLaunchKernelGGL(dequant_vb_kernel, dim3(grid), dim3(kThreads), 0, s, q);
     LPMM_HIP(hipGetLastError());
     return LPMM_OK;
 }
@@ -544,6 +639,15 @@ int lpmm_adamw4_plan_build(const lpmm_tensor_desc* descs, int64_t n, int grad_dt
                 return LPMM_EINVAL;
             t.kind = kFp32State;
             t.n_wg = t.n_wg2 = int((t.P + kElemsPerWg32 - 1) / kElemsPerWg32);
+        } else if (d.kind == LPMM_KIND_4BIT_B128) {
+            if (!d.m_blockscale || !d.v_rowmax) return LPMM_EINVAL;
+            if (!aligned(d.param, 16) || !aligned(d.grad, 16) || !aligned(d.m_state, 4) || !aligned(d.v_state, 4) ||
+                !aligned(d.m_blockscale, 4) || !aligned(d.v_rowmax, 4))
+                return LPMM_EINVAL;
+            t.ms = d.m_blockscale;
+            t.r = d.v_rowmax;                      // block scales of the second moment
+            t.kind = kQuantBlockV;
+            b128_geometry(&t, ctx->n_cu, env_int("LPMM_MULTI_B128_ROUNDS", 16));
         } else {
             if (!d.m_blockscale || !d.v_rowmax || !d.v_colmax) return LPMM_EINVAL;
             if (!aligned(d.param, 16) || !aligned(d.grad, 16) || !aligned(d.m_state, 4) || !aligned(d.v_state, 4) ||
@@ -587,7 +691,7 @@ int lpmm_adamw4_plan_build(const lpmm_tensor_desc* descs, int64_t n, int grad_dt
             }
         if (j >= 1)
             for (int64_t i = groups[j - 1].first; i < groups[j - 1].second; ++i) {
-                if (tens[i].kind == kFp32State) continue;
+                if (tens[i].kind == kFp32State || tens[i].kind == kQuantBlockV) continue;
                 pl.ph.seg_b[pl.ph.n_seg_b++] = Segment{pl.ph.n_b, int(i)};
                 pl.ph.n_b += tens[i].n_wg2;
             }

@@ -151,3 +151,72 @@ def test_config5_llama_7b_plan_sampled_tensors_and_invariants():
         if sp.quantized and (sp.name in ("embed", "lm_head") or sp.name.startswith(("l0.", "l17.", "l31."))):
             _check_invariants(sp, st, f"c5 {sp.name}")
     lpmm.lpmm_adamw4_plan_release(plan)
+
+
+def _oracle_step_b128(job):
+    w_ref, st_ref, g, t = job
+    return oracle.adamw4_b128_step(w_ref, g, st_ref, HP, t, want_moments=True)
+
+
+def test_config5_flattened_block_wise_second_moment_plan():
+    """The 7B-shaped set with every tensor taken flat (how the paper's LLaMA runs saw them under FSDP,
+    App. C.1): one plan of block-wise tensors, the launch configuration bench.py times for this
+    variant.  Two layer tensors and a ragged slice are compared element by element; block invariants
+    are checked on a spread of tensors."""
+    from test_gpu_b128 import compare as compare_b128, download as download_b128
+    config, seed, steps = "c5_llama_7b", 25, 2
+    specs = workloads.param_set(config)
+    sampled = {"l0.q": None, "l0.gate": None}
+    lpmm.ensure_init(4096)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(seed)
+    dev_t, descs = [], []
+    for tid, sp in enumerate(specs):
+        if sp.name in sampled:
+            w_ref = workloads.weights(seed, tid, sp.rows, sp.cols).reshape(-1)
+            sampled[sp.name] = (tid, sp, w_ref, oracle.state_zero_b128(sp.numel))
+            w = to_dev(w_ref.copy())
+        else:
+            w = torch.randn(sp.numel, generator=gen, device=DEV) * 0.02
+        g = torch.empty(sp.numel, dtype=torch.bfloat16, device=DEV)
+        if sp.quantized:
+            st = lpmm.new_state_b128(sp.numel, DEV)
+            descs.append(lpmm.make_desc(w, g, st))
+        else:
+            st = (torch.zeros(sp.numel, device=DEV), torch.zeros(sp.numel, device=DEV))
+            descs.append(lpmm.make_desc(w, g, st, sp.rows, sp.cols))
+        dev_t.append((sp, w, g, st))
+    plan = lpmm.new_plan(descs, 1, DEV)
+    for t in range(1, steps + 1):
+        host_g = {}
+        for name, (tid, sp, w_ref, st_ref) in sampled.items():
+            host_g[name] = workloads.grads(seed, tid, t, sp.rows, sp.cols, "col_lognormal", True).reshape(-1)
+        for sp, w, g, st in dev_t:
+            if sp.name in sampled:
+                g.copy_(to_dev(host_g[sp.name], True))
+            else:
+                sigma = 1e-3 * torch.exp(torch.randn(sp.cols, generator=gen, device=DEV))
+                g.copy_((torch.randn(sp.rows, sp.cols, generator=gen, device=DEV) * sigma[None, :]).reshape(-1))
+        lpmm.lpmm_adamw4_step_multi(plan, HP.lr, HP.beta1, HP.beta2, HP.eps, HP.weight_decay, t)
+        jobs = [(w_ref, st_ref, host_g[name], t) for name, (tid, sp, w_ref, st_ref) in sampled.items()]
+        moments = list(POOL.map(_oracle_step_b128, jobs))
+        torch.cuda.synchronize()
+        by_name = {sp.name: (w, st) for sp, w, g, st in dev_t}
+        for (name, (tid, sp, w_ref, st_ref)), (mt, vt) in zip(sampled.items(), moments):
+            w, st = by_name[name]
+            assert compare_b128(download_b128(st), st_ref, w.cpu().numpy(), w_ref, mt, vt,
+                                f"c5 flat {name} step {t}") == 0
+    # properties that hold at any size: block scales are the block maxima of the decompressed moments
+    for sp, w, g, st in dev_t:
+        if sp.quantized and (sp.name in ("embed", "lm_head") or sp.name.startswith(("l0.", "l17.", "l31."))):
+            out = torch.empty(sp.numel, dtype=torch.float32, device=DEV)
+            lpmm.lpmm_dequant_state(2, st.v_codes, st.v_blockscale, None, 1, sp.numel, out)
+            vb = out.view(-1, 128)
+            assert torch.equal(vb.max(dim=1).values, st.v_blockscale), f"c5 flat {sp.name}: v block scales"
+            assert bool((vb >= 0.0625 * st.v_blockscale[:, None]).all()), f"c5 flat {sp.name}: zero point"
+            lpmm.lpmm_dequant_state(0, st.m_codes, st.m_blockscale, None, 1, sp.numel, out)
+            mb = out.view(-1, 128).abs().max(dim=1).values
+            assert bool((mb <= st.m_blockscale).all()) and bool((mb >= 0.8875 * st.m_blockscale * (1 - 1e-6)).all()), \
+                f"c5 flat {sp.name}: m block scales"
+            del out, vb, mb
+    lpmm.lpmm_adamw4_plan_release(plan)
