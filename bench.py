@@ -177,7 +177,7 @@ def main():
         avg_ms = p1_ms / launches
         achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9
         roofline = {
-            "bound": "hbm", "kernel": "phase_kernel<roles=1> (%s)" % ("the whole block-wise step" if b128 else "pass 1"),
+            "bound": "hbm", "kernel": ("phase_kernel<roles=3> (the whole block-wise step)" if b128 else "phase_kernel<roles=1> (pass 1)"),
             "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
             "bytes_per_param": bp1, "launches": n_calls, "avg_launch_ms": round(avg_ms, 5),

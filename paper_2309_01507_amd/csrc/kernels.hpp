@@ -389,6 +389,15 @@ __device__ __forceinline__ Row1<BF16> load_row1(const TileBase& b, const Tensor4
     return r;
 }
 
+// Raise a running maximum in global memory, reading it first: the value only grows during a kernel,
+// so an atomic that cannot change it is skipped.  For the general path, which would otherwise send
+// an atomic per element.
+__device__ __forceinline__ void raise_max(float* addr, float v) {
+    if (v > 0.0f && __float_as_uint(v) > __hip_atomic_load(reinterpret_cast<unsigned int*>(addr),
+                                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+        atomic_max_nonneg(addr, v);
+}
+
 // One row of pass 1 for one lane: `cur` holds what was loaded for row `il` of the tile.
 template <bool BF16, class Mid>
 __device__ __forceinline__ void pass1_row(const Tensor4& a, const Hyper& h, const TileBase& tb, const Geo& geo,
@@ -524,7 +533,9 @@ __device__ __forceinline__ void pass1_fast_tile(const Tensor4& a, const Hyper& h
         if (cbi < a.nb) {
             st<float>(tb.ms, row_offset(il, a.nb, uint32_t(cbi)) * 4u, s.blk_scale[t]);
             const float m = s.blk_vmax[t];
-            if (m > 0.0f) atomic_max_nonneg(tb.r_new + il, m);
+            if (m > 0.0f) atomic_max_nonneg(tb.r_new + il, m);     // unconditionally: reading the running
+            // maximum first (to skip atomics that cannot raise it) costs a round trip at the end of every tile
+            // and was measured to be slower
         }
     }
     for (int t = threadIdx.x; t < a.gx * 128; t += kThreads) {
@@ -950,11 +961,6 @@ __device__ __forceinline__ void b128_work(const Tensor4& a, const Hyper& h, int 
 // per element and the maxima go straight to atomics (skipped when they cannot raise the value).
 // =====================================================================================================
 
-__device__ __forceinline__ void raise_max(float* addr, float v) {
-    if (v > 0.0f && __float_as_uint(v) > __hip_atomic_load(reinterpret_cast<unsigned int*>(addr),
-                                                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
-        atomic_max_nonneg(addr, v);
-}
 
 struct LaneIo {
     int64_t base;   // first flat element of the lane
@@ -1179,19 +1185,21 @@ __device__ __forceinline__ Segment find_segment(const Segment* seg, int n_seg, i
     return r;
 }
 
-// ROLES: 0 = A and B work interleaved in one launch; 1 = A work only; 2 = B work only.  The
+// ROLES: 0 = A and B work interleaved in one launch; 1 = A work only; 2 = B work only; 3 = A work
+// only of a group without rank-1 tensors (block-wise and fp32-state tensors: no pass-1 code).  The
 // single-role kernels exist because a kernel's register and LDS footprint is that of its heaviest
 // path: launched on their own (on a second stream), the light pass-2 workgroups fit into the
 // register space that the resident pass-1 workgroups leave free.
 template <bool BF16, int ROLES>
 __global__ __launch_bounds__(kThreads) void phase_kernel(const Phase ph, const Hyper h) {
     const int x = logical_wg();
-    const int n = (ROLES == 2 ? 0 : ph.n_a) + (ROLES == 1 ? 0 : ph.n_b);
+    constexpr bool kOnlyA = ROLES == 1 || ROLES == 3;
+    const int n = (ROLES == 2 ? 0 : ph.n_a) + (kOnlyA ? 0 : ph.n_b);
     if (x >= n) return;
     // B workgroups sit at the positions where floor(x * n_b / n) steps up
-    const int b_before = ROLES == 1 ? 0 : (ROLES == 2 ? x : int((int64_t(x) * ph.n_b) / n));
-    const int b_after = ROLES == 1 ? 0 : (ROLES == 2 ? x + 1 : int((int64_t(x + 1) * ph.n_b) / n));
-    if (ROLES != 1 && b_after > b_before) {
+    const int b_before = kOnlyA ? 0 : (ROLES == 2 ? x : int((int64_t(x) * ph.n_b) / n));
+    const int b_after = kOnlyA ? 0 : (ROLES == 2 ? x + 1 : int((int64_t(x + 1) * ph.n_b) / n));
+    if (!kOnlyA && b_after > b_before) {
         __shared__ int s_last;
         const Segment sg = find_segment(ph.seg_b, ph.n_seg_b, b_before);
         const Tensor4 a = from_table(ph.tensors[sg.tensor]);
@@ -1207,10 +1215,12 @@ __global__ __launch_bounds__(kThreads) void phase_kernel(const Phase ph, const H
         const int wg = xa - sg.wg_begin;
         if (a.kind == kFp32State) {
             adamw32_tile<BF16>(a.p, a.g, reinterpret_cast<float*>(a.mq), reinterpret_cast<float*>(a.vq), a.P, h, wg);
-        } else if (a.kind == kQuantFast) {
-            pass1_fast_tile<BF16, false>(a, h, wg, s);
         } else if (a.kind == kQuantBlockV) {
             b128_work<BF16>(a, h, wg, s);
+        } else if (ROLES == 3) {
+            // not reached: the host launches this variant only for groups without rank-1 tensors
+        } else if (a.kind == kQuantFast) {
+            pass1_fast_tile<BF16, false>(a, h, wg, s);
         } else {
             load_tables(s);
             pass1_general_tile<BF16>(a, h, wg, s);

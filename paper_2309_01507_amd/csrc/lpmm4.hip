@@ -297,6 +297,7 @@ struct PhaseLaunch {
     int grid;        // both kinds in one launch
     int grid_a;      // A work alone
     int grid_b;      // B work alone
+    bool a_has_rank1;   // some A tensor takes pass 1 of the rank-1 path (else the lighter kernel variant runs)
 };
 
 struct PlanHost {
@@ -621,7 +622,7 @@ int lpmm_adamw4_plan_build(const lpmm_tensor_desc* descs, int64_t n, int grad_dt
     float* d_floats = reinterpret_cast<float*>(dplan + L.off_floats);
     unsigned int* d_counters = reinterpret_cast<unsigned int*>(dplan + L.off_counters);
 
-    const int64_t rw_hint = env_int("LPMM_MULTI_RW", 128);
+    const int64_t rw_hint = env_int("LPMM_MULTI_RW", 64);
     const int64_t rw2_hint = env_int("LPMM_MULTI_RW2", 128);
     int64_t fofs = 0;
     for (int64_t i = 0; i < n; ++i) {
@@ -647,7 +648,7 @@ int lpmm_adamw4_plan_build(const lpmm_tensor_desc* descs, int64_t n, int grad_dt
             t.ms = d.m_blockscale;
             t.r = d.v_rowmax;                      // block scales of the second moment
             t.kind = kQuantBlockV;
-            b128_geometry(&t, ctx->n_cu, env_int("LPMM_MULTI_B128_ROUNDS", 16));
+            b128_geometry(&t, ctx->n_cu, env_int("LPMM_MULTI_B128_ROUNDS", 4));
         } else {
             if (!d.m_blockscale || !d.v_rowmax || !d.v_colmax) return LPMM_EINVAL;
             if (!aligned(d.param, 16) || !aligned(d.grad, 16) || !aligned(d.m_state, 4) || !aligned(d.v_state, 4) ||
@@ -687,6 +688,7 @@ int lpmm_adamw4_plan_build(const lpmm_tensor_desc* descs, int64_t n, int grad_dt
         if (j < groups.size())
             for (int64_t i = groups[j].first; i < groups[j].second; ++i) {
                 pl.ph.seg_a[pl.ph.n_seg_a++] = Segment{pl.ph.n_a, int(i)};
+                if (tens[i].kind == kQuantFast || tens[i].kind == kQuantGeneral) pl.a_has_rank1 = true;
                 pl.ph.n_a += tens[i].n_wg;
             }
         if (j >= 1)
@@ -759,8 +761,13 @@ int lpmm_adamw4_step_multi(void* plan, float lr, float beta1, float beta2, float
                 const bool rec = g_prof.on && g_prof.calls < g_prof.max_calls;
                 const int64_t call = g_prof.calls;
                 if (rec) LPMM_HIP(hipEventRecord(prof_event(call, 0), sa));
-                if (bf16) hipLaunchKernelGGL((phase_kernel<true, 1>), dim3(pl.grid_a), dim3(kThreads), 0, sa, pl.ph, h);
-                else hipLaunchKernelGGL((phase_kernel<false, 1>), dim3(pl.grid_a), dim3(kThreads), 0, sa, pl.ph, h);
+                if (pl.a_has_rank1) {
+                    if (bf16) hipLaunchKernelGGL((phase_kernel<true, 1>), dim3(pl.grid_a), dim3(kThreads), 0, sa, pl.ph, h);
+                    else hipLaunchKernelGGL((phase_kernel<false, 1>), dim3(pl.grid_a), dim3(kThreads), 0, sa, pl.ph, h);
+                } else {
+                    if (bf16) hipLaunchKernelGGL((phase_kernel<true, 3>), dim3(pl.grid_a), dim3(kThreads), 0, sa, pl.ph, h);
+                    else hipLaunchKernelGGL((phase_kernel<false, 3>), dim3(pl.grid_a), dim3(kThreads), 0, sa, pl.ph, h);
+                }
                 LPMM_HIP(hipGetLastError());
                 if (rec) {
                     LPMM_HIP(hipEventRecord(prof_event(call, 1), sa));
