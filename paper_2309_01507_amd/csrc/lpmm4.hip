@@ -116,7 +116,18 @@ int pad8(int64_t n) { return int(round_up(n, kXcds)); }
 // whole 128-byte lines of codes and runs of block scales), gy = 8/gx groups walk interleaved
 // rows of the same column blocks and combine their column maxima in LDS.  rw_hint > 0 fixes the
 // rows per workgroup; otherwise they are chosen so that the tensor alone fills the chip.
-void fast_geometry(Tensor4* a, int n_cu, int64_t rw_hint, int64_t rw2_hint) {
+// log2 of the smallest S in {1, 2, 4, 8}, S <= max_s, for which S rows of `row_bytes` bytes are a multiple
+// of 32 KiB; 0 if there is none.  Rows in flight side by side then lie 32 KiB apart, which is what the
+// memory system serves fastest (measured).
+int row_spacing_log2(int64_t row_bytes, int64_t max_s, const char* env) {
+    const int forced = env_int(env, -1);
+    if (forced >= 0 && forced <= 3 && (int64_t(1) << forced) <= max_s) return forced;
+    for (int l = 0; l <= 3 && (int64_t(1) << l) <= max_s; ++l)
+        if (((row_bytes << l) % 32768) == 0) return l;
+    return 0;
+}
+
+void fast_geometry(Tensor4* a, int n_cu, int64_t rw_hint, int64_t rw2_hint, int grad_bytes) {
     a->nb = int(a->cols / LPMM_BLOCK);
     int gx = env_int("LPMM_GX", 1);
     if (gx < 1 || gx > kGroups || (gx & (gx - 1))) gx = 1;
@@ -141,6 +152,7 @@ void fast_geometry(Tensor4* a, int n_cu, int64_t rw_hint, int64_t rw2_hint) {
     if (rw < a->gy) rw = a->gy;
     a->rw = int(rw);
     a->n_wg = int(a->strips * ((a->rows + rw - 1) / rw));
+    a->rs = row_spacing_log2(a->cols * 4, rw / a->gy, "LPMM_RS");      // the parameters' rows
     // pass 2: strips of 256 columns, a wave per row
     a->strips2 = (a->nb + 1) / 2;
     int64_t rw2 = env_int("LPMM_RW2", 0);
@@ -154,6 +166,7 @@ void fast_geometry(Tensor4* a, int n_cu, int64_t rw_hint, int64_t rw2_hint) {
     if (rw2 < 1) rw2 = 1;
     a->rw2 = int(rw2);
     a->n_wg2 = int(a->strips2 * ((a->rows + rw2 - 1) / rw2));
+    a->rs2 = row_spacing_log2(a->cols * grad_bytes, rw2 / kWaves, "LPMM_RS2");   // pass 2 mostly reads the gradient
 }
 
 // Tiling of a tensor whose second moment is block-wise: `rw` rounds of 8 blocks per workgroup over
@@ -235,7 +248,7 @@ int step_impl(bool bf16, void* param, const void* grad, uint8_t* m_codes, float*
     t.P = rows * cols;
     const bool fast = fast_eligible(cols, v_colmax);
     t.kind = fast ? kQuantFast : kQuantGeneral;
-    if (fast) fast_geometry(&t, ctx->n_cu, 0, 0);
+    if (fast) fast_geometry(&t, ctx->n_cu, 0, 0, bf16 ? 2 : 4);
     else t.n_wg = t.n_wg2 = int((((t.P + 7) / 8) + kThreads - 1) / kThreads);
     hipStream_t s = static_cast<hipStream_t>(stream);
     return bf16 ? launch_step<true>(t, h, fast, s) : launch_step<false>(t, h, fast, s);
@@ -664,7 +677,7 @@ int lpmm_adamw4_plan_build(const lpmm_tensor_desc* descs, int64_t n, int grad_dt
             t.counter = d_counters + i * kCounterWords;
             if (fast_eligible(d.cols, d.v_colmax)) {
                 t.kind = kQuantFast;
-                fast_geometry(&t, ctx->n_cu, rw_hint, rw2_hint);
+                fast_geometry(&t, ctx->n_cu, rw_hint, rw2_hint, grad_dtype == LPMM_GRAD_BF16 ? 2 : 4);
             } else {
                 t.kind = kQuantGeneral;
                 t.n_wg = t.n_wg2 = int((((t.P + 7) / 8) + kThreads - 1) / kThreads);

@@ -98,3 +98,26 @@ def test_argument_errors_are_reported_before_any_gpu_work():
     assert b"invalid" in L.lpmm_strerror(-1) and b"workspace" in L.lpmm_strerror(-4)
     # a well-formed call before init (or without a GPU) is refused, not executed
     assert call() in (-2, -3)
+
+
+def test_block_wise_state_sizes_and_argument_errors():
+    assert lpmm.lpmm_adamw4_b128_state_sizes(4096) == [2048, 128, 2048, 128]
+    assert lpmm.lpmm_adamw4_b128_state_sizes(129) == [65, 8, 65, 8]          # odd size, 2 blocks
+    L = lpmm.lib()
+    sizes = (ctypes.c_size_t * 4)()
+    assert L.lpmm_adamw4_b128_state_sizes(0, ctypes.addressof(sizes)) == -1
+    assert L.lpmm_adamw4_b128_state_sizes(16, None) == -1
+    buf = ctypes.create_string_buffer(4096 + 256)
+    p = (ctypes.addressof(buf) + 255) // 256 * 256
+    ok_h = [1e-3, 0.9, 0.999, 1e-8, 0.01]
+
+    def call(ptrs=None, numel=256, h=ok_h, step=1):
+        ptrs = ptrs or [p] * 6
+        return L.lpmm_adamw4_b128_step(*ptrs, numel, *[ctypes.c_float(x) for x in h], step, None)
+
+    assert call(step=0) == -1
+    assert call(numel=0) == -1
+    assert call(h=[1e-3, 0.9, 1.0, 1e-8, 0.01]) == -1
+    assert call(ptrs=[p] * 5 + [None]) == -1                    # null block-scale pointer
+    assert call(ptrs=[p + 8] + [p] * 5) == -1                   # parameters must be 16-byte aligned
+    assert call() in (-2, -3)                                   # well-formed, but no initialized GPU here
