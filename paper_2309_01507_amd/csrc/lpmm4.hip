@@ -116,13 +116,17 @@ int pad8(int64_t n) { return int(round_up(n, kXcds)); }
 // whole 128-byte lines of codes and runs of block scales), gy = 8/gx groups walk interleaved
 // rows of the same column blocks and combine their column maxima in LDS.  rw_hint > 0 fixes the
 // rows per workgroup; otherwise they are chosen so that the tensor alone fills the chip.
-// log2 of the smallest S in {1, 2, 4, 8}, S <= max_s, for which S rows of `row_bytes` bytes are a multiple
-// of 32 KiB; 0 if there is none.  Rows in flight side by side then lie 32 KiB apart, which is what the
-// memory system serves fastest (measured).
-int row_spacing_log2(int64_t row_bytes, int64_t max_s, const char* env) {
+// log2 of the smallest S in {1, 2, 4, 8} for which S rows of `row_bytes` bytes are a multiple of 32 KiB; 0 if
+// there is none.  Rows in flight side by side then lie 32 KiB apart, which is what the memory system serves
+// fastest (measured).  S must divide `per_group`, the rows of a tile that one group (or wave) takes: only
+// then does row(k) = g*S + k%S + (k/S)*groups*S enumerate every row of the tile exactly once.
+int row_spacing_log2(int64_t row_bytes, int64_t rows_per_tile, int groups, const char* env) {
+    if (rows_per_tile % groups) return 0;
+    const int64_t per_group = rows_per_tile / groups;
+    auto fits = [&](int l) { return l >= 0 && l <= 3 && (per_group % (int64_t(1) << l)) == 0; };
     const int forced = env_int(env, -1);
-    if (forced >= 0 && forced <= 3 && (int64_t(1) << forced) <= max_s) return forced;
-    for (int l = 0; l <= 3 && (int64_t(1) << l) <= max_s; ++l)
+    if (forced >= 0) return fits(forced) ? forced : 0;
+    for (int l = 0; fits(l); ++l)
         if (((row_bytes << l) % 32768) == 0) return l;
     return 0;
 }
@@ -152,7 +156,7 @@ void fast_geometry(Tensor4* a, int n_cu, int64_t rw_hint, int64_t rw2_hint, int 
     if (rw < a->gy) rw = a->gy;
     a->rw = int(rw);
     a->n_wg = int(a->strips * ((a->rows + rw - 1) / rw));
-    a->rs = row_spacing_log2(a->cols * 4, rw / a->gy, "LPMM_RS");      // the parameters' rows
+    a->rs = row_spacing_log2(a->cols * 4, rw, a->gy, "LPMM_RS");      // the parameters' rows
     // pass 2: strips of 256 columns, a wave per row
     a->strips2 = (a->nb + 1) / 2;
     int64_t rw2 = env_int("LPMM_RW2", 0);
@@ -166,7 +170,7 @@ void fast_geometry(Tensor4* a, int n_cu, int64_t rw_hint, int64_t rw2_hint, int 
     if (rw2 < 1) rw2 = 1;
     a->rw2 = int(rw2);
     a->n_wg2 = int(a->strips2 * ((a->rows + rw2 - 1) / rw2));
-    a->rs2 = row_spacing_log2(a->cols * grad_bytes, rw2 / kWaves, "LPMM_RS2");   // pass 2 mostly reads the gradient
+    a->rs2 = row_spacing_log2(a->cols * grad_bytes, rw2, kWaves, "LPMM_RS2");   // pass 2 mostly reads the gradient
 }
 
 // Tiling of a tensor whose second moment is block-wise: `rw` rounds of 8 blocks per workgroup over

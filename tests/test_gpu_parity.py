@@ -115,6 +115,10 @@ def test_zero_state_matches_oracle():
     (1, 5000, "iid"),                  # one row
     (300, 1, "iid"),                   # one column
     (1, 1, "iid"), (1, 2, "iid"),      # degenerate
+    (20, 4096, "iid"),                 # rows per group (3) not divisible by the preferred row spacing (2)
+    (100, 1024, "col_lognormal"),      # 4 KiB rows: row spacing 8, ragged second tile
+    (150, 4096, "iid"),                # row spacing 2 in pass 1 and 4 in pass 2, ragged last tiles
+    (72, 2048, "iid"),                 # row spacing 4, 9 rows per group in one tile
 ])
 def test_step_parity_small(rows, cols, recipe):
     assert run_parity(rows, cols, steps=6, recipe=recipe, seed=3) == 0
@@ -141,6 +145,9 @@ def test_other_hyperparameters(hp):
     assert run_parity(128, 256, steps=5, recipe="col_lognormal", seed=6, hp=hp) == 0
 
 
+ALL_KNOBS = ("LPMM_GX", "LPMM_RW", "LPMM_RW2", "LPMM_RS", "LPMM_RS2", "LPMM_FORCE_GENERAL")
+
+
 def test_launch_geometry_does_not_change_results():
     """Maxima are order-independent, so every tiling of the fast path and the general path must give
     identical bits; a difference would be a race or an indexing error."""
@@ -150,10 +157,12 @@ def test_launch_geometry_does_not_change_results():
     grads = [workloads.grads(7, 0, t, rows, cols, "col_lognormal").reshape(-1) for t in (1, 2, 3)]
     results = []
     knobs = [{}, {"LPMM_GX": "1"}, {"LPMM_GX": "8", "LPMM_RW": "16"}, {"LPMM_GX": "2", "LPMM_RW": "300"},
+             {"LPMM_RS": "0", "LPMM_RS2": "0"}, {"LPMM_RW": "64", "LPMM_RS": "3", "LPMM_RW2": "32", "LPMM_RS2": "3"},
+             {"LPMM_RW": "40", "LPMM_RS": "2", "LPMM_RW2": "24", "LPMM_RS2": "1"},
              {"LPMM_FORCE_GENERAL": "1"}]
     try:
         for env in knobs:
-            for k in ("LPMM_GX", "LPMM_RW", "LPMM_FORCE_GENERAL"):
+            for k in ALL_KNOBS:
                 os.environ.pop(k, None)
             os.environ.update(env)
             w = to_dev(w0.copy())
@@ -163,7 +172,7 @@ def test_launch_geometry_does_not_change_results():
             torch.cuda.synchronize()
             results.append((download_state(st), w.cpu().numpy()))
     finally:
-        for k in ("LPMM_GX", "LPMM_RW", "LPMM_FORCE_GENERAL"):
+        for k in ALL_KNOBS:
             os.environ.pop(k, None)
     ref_st, ref_w = results[0]
     for st, w in results[1:]:
