@@ -733,10 +733,13 @@ __device__ __forceinline__ void pass2_fast_tile(const Tensor4& a, const Hyper& h
 // =====================================================================================================
 // Block-wise second moment (1-dimensional or flattened tensors; Sec. 4.2, last paragraph): both
 // moments are normalized per block of 128 elements, nothing crosses a block, and the whole step is
-// ONE pass.  Same lane layout as pass 1 (4 elements per lane, 32 lanes per block); a workgroup's 8
-// groups take 8 consecutive blocks per round (4 KiB of parameters), `rounds` rounds per tile.  The
-// tensor is a.P elements, a.r holds the second moment's block scales.  The tile routine covers whole
-// blocks; a ragged last block is done by b128_tail_block.
+// ONE pass.  Same lane layout as pass 1 (4 elements per lane, 32 lanes per block).  The 8 groups of a
+// workgroup work 64 blocks = 32 KiB of parameters apart (the distance the memory system serves
+// fastest, as for the rows of pass 1): the tensor is cut into super-tiles of 8 x 64 blocks, group g
+// owns blocks [64 g, 64 g + 64) of a super-tile, and a workgroup takes `rounds` consecutive blocks of
+// each of the 8 ranges, so 64 / rounds workgroups share a super-tile.  The tensor is a.P elements,
+// a.r holds the second moment's block scales.  The tile routine covers whole blocks; a ragged last
+// block is done by b128_tail_block.
 // =====================================================================================================
 
 struct TileB {
@@ -775,7 +778,9 @@ struct RowB {                      // everything the step reads for one block, p
     float sm_old, sv_old;          // the block's two scales
 };
 
-// ib = block index inside the tile; blocks at or beyond the tile's end read as zeros
+constexpr int kNoBlock = 1 << 22;     // a block index whose offsets lie beyond any tile: loads return zeros
+
+// ib = block index inside the (super-)tile; blocks at or beyond its end read as zeros
 template <bool BF16>
 __device__ __forceinline__ RowB<BF16> load_rowb(const TileB& b, int ib, int l) {
     RowB<BF16> r;
@@ -791,7 +796,7 @@ __device__ __forceinline__ RowB<BF16> load_rowb(const TileB& b, int ib, int l) {
 
 template <bool BF16, class Mid>
 __device__ __forceinline__ void b128_row(const Hyper& h, const TileB& tb, Lds& s, const RowB<BF16>& cur,
-                                         int ib, int l, Mid mid) {
+                                         int ib, int slot, int l, Mid mid) {
     float w[4] = {cur.p.x, cur.p.y, cur.p.z, cur.p.w};
     float g[4];
     unpack_grad4<BF16>(cur.g, g);
@@ -868,43 +873,58 @@ __device__ __forceinline__ void b128_row(const Hyper& h, const TileB& tb, Lds& s
     st<uint16_t>(tb.mq, off4 >> 3, uint16_t(mq_new));
     st<uint16_t>(tb.vq, off4 >> 3, uint16_t(vq_new));
     if (l == 0) {
-        s.blk_scale[ib] = sm_new;
-        s.blk_vmax[ib] = sv_new;
+        s.blk_scale[slot] = sm_new;
+        s.blk_vmax[slot] = sv_new;
     }
 }
 
-constexpr int kB128MaxRounds = kMaxRowSlots / kGroups;     // block results of a tile are staged in LDS
+constexpr int kB128Stride = 64;                            // blocks between the groups of a workgroup
+constexpr int kB128Super = kGroups * kB128Stride;          // blocks of a super-tile
+constexpr int kB128MaxRounds = kB128Stride;                // block results of a tile are staged in LDS
+static_assert(kGroups * kB128MaxRounds <= kMaxRowSlots, "LDS staging of block results");
 
-// tile `wg` of a tensor: blocks [wg * 8 * a.rw, ...) where a.rw = rounds per tile, a.nb = whole blocks
+// workgroup `wg` of a tensor: super-tile wg / slices, slice wg % slices of each group's range, where
+// slices = 64 / a.rw and a.rw = rounds (a power of two); a.nb = whole blocks of the tensor
 template <bool BF16>
 __device__ __forceinline__ void b128_tile(const Tensor4& a, const Hyper& h, int wg, Lds& s) {
-    const int64_t blk0 = int64_t(wg) * kGroups * a.rw;
-    const int64_t left = int64_t(a.nb) - blk0;
-    const int n = left < int64_t(kGroups) * a.rw ? int(left) : kGroups * a.rw;     // blocks of this tile
-    const TileB tb = tile_b128<BF16>(a, blk0, n);
+    const int rounds = a.rw, slices = kB128Stride / rounds;
+    const int64_t sup0 = int64_t(wg / slices) * kB128Super;
+    const int64_t left = int64_t(a.nb) - sup0;
+    const int n_sup = left < kB128Super ? int(left) : kB128Super;      // blocks of this super-tile that exist
+    const TileB tb = tile_b128<BF16>(a, sup0, n_sup > 0 ? n_sup : 0);
     const int grp = threadIdx.x >> 5, l = threadIdx.x & 31;
-    constexpr int stp = kGroups;
-    int ib = grp;
-    RowB<BF16> r0 = load_rowb<BF16>(tb, ib, l);
-    RowB<BF16> r1 = load_rowb<BF16>(tb, ib + stp, l);
+    const int slice0 = (wg % slices) * rounds;
+    const int first = grp * kB128Stride + slice0;                      // the group's first block in the super-tile
+    int nv = n_sup - first;                                            // the group's blocks: 0 .. rounds
+    nv = nv < 0 ? 0 : (nv > rounds ? rounds : nv);
+    // blocks past the group's share must not be fetched (inside the super-tile they are real blocks,
+    // another workgroup's): they get an index beyond every tile
+    auto blk = [&](int k) { return k < nv ? first + k : kNoBlock; };
+    const int slot0 = grp * rounds;
+    int k = 0;
+    RowB<BF16> r0 = load_rowb<BF16>(tb, blk(0), l);
+    RowB<BF16> r1 = load_rowb<BF16>(tb, blk(1), l);
     RowB<BF16> r2;
     load_tables(s);                                // the first blocks' loads are in flight meanwhile
     __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);       // loop start-up state: nothing outstanding (see pass 1)
     auto none = [] {};
-    while (ib + 2 * stp < n) {                     // rounds of three blocks, no exit in the middle
-        b128_row<BF16>(h, tb, s, r0, ib, l, [&] { r2 = load_rowb<BF16>(tb, ib + 2 * stp, l); });
-        b128_row<BF16>(h, tb, s, r1, ib + stp, l, [&] { r0 = load_rowb<BF16>(tb, ib + 3 * stp, l); });
-        b128_row<BF16>(h, tb, s, r2, ib + 2 * stp, l, [&] { r1 = load_rowb<BF16>(tb, ib + 4 * stp, l); });
-        ib += 3 * stp;
+    while (k + 2 < nv) {                           // rounds of three blocks, no exit in the middle
+        b128_row<BF16>(h, tb, s, r0, first + k, slot0 + k, l, [&] { r2 = load_rowb<BF16>(tb, blk(k + 2), l); });
+        b128_row<BF16>(h, tb, s, r1, first + k + 1, slot0 + k + 1, l, [&] { r0 = load_rowb<BF16>(tb, blk(k + 3), l); });
+        b128_row<BF16>(h, tb, s, r2, first + k + 2, slot0 + k + 2, l, [&] { r1 = load_rowb<BF16>(tb, blk(k + 4), l); });
+        k += 3;
     }
-    if (ib < n) {
-        b128_row<BF16>(h, tb, s, r0, ib, l, none);
-        if (ib + stp < n) b128_row<BF16>(h, tb, s, r1, ib + stp, l, none);
+    if (k < nv) {
+        b128_row<BF16>(h, tb, s, r0, first + k, slot0 + k, l, none);
+        if (k + 1 < nv) b128_row<BF16>(h, tb, s, r1, first + k + 1, slot0 + k + 1, l, none);
     }
     __syncthreads();
-    for (int t = threadIdx.x; t < n; t += kThreads) {      // the tile's new block scales, contiguous
-        tb.ms[t] = s.blk_scale[t];
-        tb.vs[t] = s.blk_vmax[t];
+    for (int t = threadIdx.x; t < kGroups * rounds; t += kThreads) {   // new block scales: 8 contiguous runs
+        const int b = (t / rounds) * kB128Stride + slice0 + t % rounds;
+        if (b < n_sup) {
+            tb.ms[b] = s.blk_scale[t];
+            tb.vs[b] = s.blk_vmax[t];
+        }
     }
 }
 

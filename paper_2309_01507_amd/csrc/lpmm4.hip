@@ -173,20 +173,23 @@ void fast_geometry(Tensor4* a, int n_cu, int64_t rw_hint, int64_t rw2_hint, int 
     a->rs2 = row_spacing_log2(a->cols * grad_bytes, rw2, kWaves, "LPMM_RS2");   // pass 2 mostly reads the gradient
 }
 
-// Tiling of a tensor whose second moment is block-wise: `rw` rounds of 8 blocks per workgroup over
-// the whole blocks, plus one workgroup for a partial last block.  rounds_hint > 0 fixes the rounds.
+// Tiling of a tensor whose second moment is block-wise: super-tiles of 8 x 64 blocks, each shared by
+// 64 / rounds workgroups (rounds: a power of two, blocks that a group takes in a row), plus one workgroup
+// for a partial last block.  rounds_hint > 0 fixes the rounds.
 void b128_geometry(Tensor4* a, int n_cu, int64_t rounds_hint) {
     a->nb = int(a->P / LPMM_BLOCK);
-    int64_t rounds = env_int("LPMM_B128_ROUNDS", 0);
-    if (rounds <= 0) rounds = rounds_hint;
-    if (rounds <= 0) {
-        rounds = 16;
-        while (rounds > 1 && (a->nb + kGroups * rounds - 1) / (kGroups * rounds) < 2 * int64_t(n_cu)) rounds >>= 1;
+    const int64_t supers = (a->nb + kB128Super - 1) / kB128Super;
+    int64_t want = env_int("LPMM_B128_ROUNDS", 0);
+    if (want <= 0) want = rounds_hint;
+    int64_t rounds = 16;
+    if (want > 0) {
+        rounds = 1;
+        while (rounds * 2 <= want && rounds * 2 <= kB128MaxRounds) rounds *= 2;      // round down to a power of two
+    } else {
+        while (rounds > 1 && supers * (kB128Stride / rounds) < 2 * int64_t(n_cu)) rounds >>= 1;
     }
-    if (rounds > kB128MaxRounds) rounds = kB128MaxRounds;
-    if (rounds < 1) rounds = 1;
     a->rw = int(rounds);
-    a->n_wg2 = int((a->nb + kGroups * rounds - 1) / (kGroups * rounds));
+    a->n_wg2 = int(supers * (kB128Stride / rounds));
     a->n_wg = a->n_wg2 + ((a->P % LPMM_BLOCK) ? 1 : 0);
     a->gx = 1; a->gy = kGroups; a->strips = 1; a->strips2 = 1; a->rw2 = 1;
 }
@@ -665,7 +668,7 @@ int lpmm_adamw4_plan_build(const lpmm_tensor_desc* descs, int64_t n, int grad_dt
             t.ms = d.m_blockscale;
             t.r = d.v_rowmax;                      // block scales of the second moment
             t.kind = kQuantBlockV;
-            b128_geometry(&t, ctx->n_cu, env_int("LPMM_MULTI_B128_ROUNDS", 4));
+            b128_geometry(&t, ctx->n_cu, env_int("LPMM_MULTI_B128_ROUNDS", 8));
         } else {
             if (!d.m_blockscale || !d.v_rowmax || !d.v_colmax) return LPMM_EINVAL;
             if (!aligned(d.param, 16) || !aligned(d.grad, 16) || !aligned(d.m_state, 4) || !aligned(d.v_state, 4) ||
