@@ -180,12 +180,14 @@ __device__ __forceinline__ float4 buf_ld_f4_stream(Rsrc r, uint32_t off) {
     const v4f_t v = __builtin_bit_cast(v4f_t, __builtin_amdgcn_raw_buffer_load_b128(r, int(off), 0, kPolicyNt));
     return make_float4(v.x, v.y, v.z, v.w);
 }
+template <int POLICY = 0>
 __device__ __forceinline__ float4 buf_ld_f4(Rsrc r, uint32_t off) {
-    const v4f_t v = __builtin_bit_cast(v4f_t, __builtin_amdgcn_raw_buffer_load_b128(r, int(off), 0, 0));
+    const v4f_t v = __builtin_bit_cast(v4f_t, __builtin_amdgcn_raw_buffer_load_b128(r, int(off), 0, POLICY));
     return make_float4(v.x, v.y, v.z, v.w);
 }
+template <int POLICY = 0>
 __device__ __forceinline__ uint2 buf_ld_u2(Rsrc r, uint32_t off) {
-    const v2u_t v = __builtin_amdgcn_raw_buffer_load_b64(r, int(off), 0, 0);
+    const v2u_t v = __builtin_amdgcn_raw_buffer_load_b64(r, int(off), 0, POLICY);
     return make_uint2(v.x, v.y);
 }
 // Kept 16 bits wide until it is used: widening right here would put an instruction that needs the
@@ -266,12 +268,13 @@ template <bool BF16> struct GradRegs4;
 template <> struct GradRegs4<true> { uint2 w; };
 template <> struct GradRegs4<false> { float4 a; };
 
-// gradient of a lane's 4 elements; off4 is the byte offset the elements have in an fp32 array
-template <bool BF16>
+// gradient of a lane's 4 elements; off4 is the byte offset the elements have in an fp32 array.
+// POLICY = kPolicyNt where the gradient is read for the last time in the step.
+template <bool BF16, int POLICY = 0>
 __device__ __forceinline__ GradRegs4<BF16> load_grad_regs4(Rsrc g_tile, uint32_t off4) {
     GradRegs4<BF16> r;
-    if constexpr (BF16) r.w = buf_ld_u2(g_tile, off4 >> 1);
-    else r.a = buf_ld_f4(g_tile, off4);
+    if constexpr (BF16) r.w = buf_ld_u2<POLICY>(g_tile, off4 >> 1);
+    else r.a = buf_ld_f4<POLICY>(g_tile, off4);
     return r;
 }
 template <bool BF16>
@@ -625,7 +628,7 @@ template <bool BF16>
 __device__ __forceinline__ Row2<BF16> load_row2(const TileBase& b, const Tensor4& a, uint32_t col0, int il) {
     Row2<BF16> r;
     const uint32_t off4 = row_offset(il, a.cols, col0) * 4u;
-    r.g = load_grad_regs4<BF16>(b.rg, off4);
+    r.g = load_grad_regs4<BF16, kPolicyNt>(b.rg, off4);    // last use of the gradient in this step
     r.vq = buf_ld_u16(b.rvq, off4 >> 3);
     r.r_old = buf_ld_f(b.rr, uint32_t(il) * 4u);
     r.r_new = buf_ld_f(b.rr_new, uint32_t(il) * 4u);
@@ -786,7 +789,7 @@ __device__ __forceinline__ RowB<BF16> load_rowb(const TileB& b, int ib, int l) {
     RowB<BF16> r;
     const uint32_t off4 = (uint32_t(ib) * 128u + uint32_t(l) * 4u) * 4u;
     r.p = buf_ld_f4_stream(b.rp, off4);
-    r.g = load_grad_regs4<BF16>(b.rg, off4);
+    r.g = load_grad_regs4<BF16, kPolicyNt>(b.rg, off4);              // read once per step
     r.mq = buf_ld_u16(b.rmq, off4 >> 3);
     r.vq = buf_ld_u16(b.rvq, off4 >> 3);
     r.sm_old = buf_ld_f(b.rms, uint32_t(ib) * 4u);
