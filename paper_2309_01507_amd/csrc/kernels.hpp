@@ -12,9 +12,12 @@
 //   pass 2: recompute v_t with the identical operation sequence, compress it against
 //           min(r'_i, c'_j) (Linear map), and let the last workgroup publish r', c' as the new
 //           state and clear the workspace.
+// For 1-dimensional or flattened tensors the second moment is block-wise like the first (Sec. 4.2,
+// last paragraph); then nothing crosses a block and the step is ONE pass (b128_*).
 // The bodies are "tile" functions; thin __global__ wrappers run them for one tensor (two launches
-// per step), and the phase kernel runs pass 1 of one set of tensors next to pass 2 of the previous
-// set, so that the arithmetic-heavy pass 2 hides under the memory-bound pass 1.
+// per step, one for the block-wise form), and the phase kernels run pass 1 of one set of tensors
+// next to pass 2 of the previous set, so that the arithmetic-heavy pass 2 hides under the
+// memory-bound pass 1.
 #pragma once
 
 #include "device_math.hpp"
@@ -40,16 +43,16 @@ struct Tensor4 {
     unsigned int* counter;  // workspace: ticket counters of pass 2 (zero between steps)
     int64_t rows, cols, P;
     // geometry of the fast path (cols % 128 == 0)
-    int nb;                 // column blocks per row = cols / 128
+    int nb;                 // column blocks per row = cols / 128    (kQuantBlockV: whole blocks of the tensor)
     int gx, gy;             // a workgroup's 8 groups: gx column blocks x gy row phases
-    int rw;                 // rows per workgroup tile; rw * cols < 2^29
+    int rw;                 // rows per workgroup tile; rw * cols < 2^29   (kQuantBlockV: blocks a group takes in a row)
     int strips;             // nb / gx
-    int n_wg;               // workgroups of pass 1 (general path: of either pass)
+    int n_wg;               // workgroups of pass 1 (general path: of either pass; kQuantBlockV: of the step)
     int kind;
     // pass 2 of the fast path has its own tiling: strips of 256 columns, rw2 rows per workgroup
     int strips2;            // ceil(nb / 2)
     int rw2;                // rw2 * cols < 2^29
-    int n_wg2;              // workgroups of pass 2
+    int n_wg2;              // workgroups of pass 2                 (kQuantBlockV: workgroups on whole blocks)
     // log2 of the row spacing of pass 1 / pass 2: the 2^rs (2^rs2) rows that a group (a wave) takes in a
     // row are consecutive, and the groups (waves) that run side by side are 2^rs rows apart
     int rs, rs2;
@@ -246,12 +249,12 @@ __device__ __forceinline__ void unpack_grad(const GradRegs<BF16>& r, float out[8
 
 // =====================================================================================================
 // Fast path: cols % 128 == 0, so a block never straddles a row.  Here a lane owns FOUR consecutive
-// elements of a row and a group of 32 lanes (half a wave) owns one 128-element block: every 128-bit
-// parameter access of a wave is then one contiguous kilobyte, and the small per-lane register
-// footprint lets six or more waves share a SIMD.  A group walks down the rows of one column block
-// with the old and the running new column maxima of its 4 columns in registers.  Addresses are a
-// uniform tile base plus a 32-bit lane offset; the loads of the next two rows are in flight while
-// a row is computed.
+// elements of a row and a group of 32 lanes (half a wave) owns one 128-element block: a group's
+// 128-bit parameter access is 512 contiguous bytes, and the per-lane register footprint lets five
+// waves share a SIMD.  A group walks down rows of one column block with the old and the running new
+// column maxima of its 4 columns in registers.  Loads go through bounds-checked buffer resources of
+// the tile (uniform base, 32-bit lane offsets); the loads of the next two rows are in flight while a
+// row is computed.
 // =====================================================================================================
 
 constexpr int kGroups = 8;          // 32-lane groups per workgroup
