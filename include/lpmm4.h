@@ -158,7 +158,7 @@ int lpmm_dequant_state(int which, const uint8_t* codes, const float* scale_a, co
                        const int64_t shape[2], float* out, void* stream);
 
 /* Compress an fp32 moment into 4-bit state (the quantizer M o N of Sec. 2.2), same `which` and
- * scale arguments as lpmm_dequant_state, all outputs.  in: float[P]; for which = 1 the values
+ * scale arguments as lpmm_dequant_state, all outputs.  in: float[P]; for which = 1 and 2 the values
  * must be >= 0.  For which = 1 needs lpmm_adamw4_init (it uses no workspace but the tables). */
 int lpmm_quant_state(int which, const float* in, const int64_t shape[2], uint8_t* codes,
                      float* scale_a, float* scale_b, void* stream);

@@ -1334,6 +1334,26 @@ __global__ __launch_bounds__(kThreads) void quant_m_kernel(const QuantArgs q) {
     if ((threadIdx.x & 15) == 0) q.sa[t >> 4] = sc;
 }
 
+// block-wise second moment (values >= 0): block maximum, Linear map
+__global__ __launch_bounds__(kThreads) void quant_vb_kernel(const QuantArgs q) {
+    const int64_t t = int64_t(blockIdx.x) * kThreads + threadIdx.x;
+    if ((t >> 4) * 128 >= q.P) return;
+    const LaneIo io = lane_io(q.P, q.cols, t);
+    float x[8], vmax = 0.0f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        x[e] = e < io.nv ? q.x_in[io.base + e] : 0.0f;
+        vmax = fmaxf(vmax, fabsf(x[e]));
+    }
+    const float sc = row16_allmax(vmax);
+    uint32_t w = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+        if (e < io.nv) w |= quant_v_code(x[e], sc) << (4 * e);
+    if (io.nv) store_codes(q.q_out, io, w);
+    if ((threadIdx.x & 15) == 0) q.sa[t >> 4] = sc;
+}
+
 // second moment, stage 1: row / column maxima into sa / sb (which must be zero on entry)
 __global__ __launch_bounds__(kThreads) void quant_v_max_kernel(const QuantArgs q) {
     const int64_t t = int64_t(blockIdx.x) * kThreads + threadIdx.x;

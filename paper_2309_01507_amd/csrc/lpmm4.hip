@@ -586,7 +586,7 @@ int lpmm_quant_state(int which, const float* in, const int64_t shape[2], uint8_t
     int64_t rows, cols;
     const int rc = check_shape(shape, &rows, &cols);
     if (rc) return rc;
-    if ((which != 0 && which != 1) || !codes || !scale_a || !in || (which == 1 && !scale_b))
+    if ((which != 0 && which != 1 && which != 2) || !codes || !scale_a || !in || (which == 1 && !scale_b))
         return LPMM_EINVAL;
     if (!aligned(codes, 4) || !aligned(in, 4)) return LPMM_EINVAL;
     DeviceCtx* ctx;
@@ -602,6 +602,9 @@ int lpmm_quant_state(int which, const float* in, const int64_t shape[2], uint8_t
     const int grid = grid_for(q.P, 8);
     if (which == 0) {
         hipLaunchKernelGGL(quant_m_kernel, dim3(grid), dim3(kThreads), 0, s, q);
+        LPMM_HIP(hipGetLastError());
+    } else if (which == 2) {
+        hipLaunchKernelGGL(quant_vb_kernel, dim3(grid), dim3(kThreads), 0, s, q);
         LPMM_HIP(hipGetLastError());
     } else {
         int r = fill(scale_a, rows * int64_t(sizeof(float)), 0, -1, 0, s);

@@ -151,6 +151,22 @@ def test_dequant_matches_oracle():
     np.testing.assert_array_equal(out.cpu().numpy(), oracle.dequant_v_block(codes, scales, P))
 
 
+def test_quant_matches_oracle():
+    rng = np.random.default_rng(8)
+    P = 128 * 11 + 30
+    x = (rng.standard_normal(P).astype(np.float32) * np.float32(2e-3)) ** 2
+    x[256:384] = 0.0                                   # a zero block
+    x[500] = 7.0                                       # an outlier
+    want_codes, want_scales = oracle.quant_v_block(x)
+    lpmm.ensure_init(4096)
+    codes = torch.zeros((want_codes.size + 3) // 4 * 4, dtype=torch.uint8, device=DEV)
+    scales = torch.empty(want_scales.size, device=DEV)
+    lpmm.lpmm_quant_state(2, to_dev(x), 1, P, codes, scales, None)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(scales.cpu().numpy(), want_scales)
+    np.testing.assert_array_equal(codes.cpu().numpy()[:want_codes.size], want_codes)
+
+
 def test_plan_with_mixed_kinds():
     """One plan holding rank-1 tensors, block-wise tensors and fp32-state tensors."""
     from test_gpu_multi import HP
