@@ -231,6 +231,14 @@ def main():
                          f"{rows * cols} params), {cdt:.1f} s; host has {os.cpu_count()} logical cpus"}
 
     total_gbps = ((bp1 + bp2) * n_quant + small_bytes) / (elapsed / args.steps) / 1e9
+    # every stream touched once (what a single pass would move): param 8, grad, codes 2, block scales and,
+    # for the rank-1 form, one more float per 128 elements standing in for the row / column maxima
+    floor_bpp = 8.0 + (2.0 if bf16 else 4.0) + 2.0 + (16.0 if b128 else 8.0) / 128.0
+    floor_gbps = (floor_bpp * n_quant + small_bytes) / (elapsed / args.steps) / 1e9
+    if plans:
+        kernels_per_step = (n_calls // max(args.steps, 1)) * (1 if b128 else 2)
+    else:
+        kernels_per_step = n_q_tensors * (1 if b128 else 2) + (len(tensors) - n_q_tensors)
     out = {
         "metric": "params updated/sec per 4-bit AdamW step", "value": round(value, 1), "unit": "params/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
@@ -245,6 +253,8 @@ def main():
                                "multi-tensor plan, %d pass-1 launches per step on the caller's stream, "
                                "pass 2 on a second stream") % (n_calls // max(args.steps, 1)))
                    if plans else "per-tensor, %d kernel%s per quantized tensor" % ((1, "") if b128 else (2, "s")),
+                   "kernels_per_step": kernels_per_step,
+                   "hbm_gbps_one_touch_floor": round(floor_gbps, 1),
                    ("hbm_gbps_one_pass_model" if b128 else "hbm_gbps_two_pass_model"): round(total_gbps, 1),
                    ("hbm_frac_one_pass_model" if b128 else "hbm_frac_two_pass_model"):
                        round(total_gbps / HBM_PEAK_GBPS, 4)},
