@@ -1206,7 +1206,7 @@ struct Segment {        // a run of workgroups that work on one tensor
     int tensor;         // index into the tensor table
 };
 
-constexpr int kMaxSeg = 32;   // tensors per kind in one phase; the tables travel as kernel arguments
+constexpr int kMaxSeg = 128;  // tensors per kind in one phase; the tables travel as kernel arguments (2 KiB)
 
 struct Phase {
     const Tensor4Table* tensors;
@@ -1216,12 +1216,15 @@ struct Phase {
     Segment seg_b[kMaxSeg];
 };
 
-// last segment whose first workgroup is <= wg (segments are sorted; a short uniform scan)
+// last segment whose first workgroup is <= wg (segments are sorted by wg_begin, seg[0].wg_begin = 0;
+// a uniform binary search on scalar registers)
 __device__ __forceinline__ Segment find_segment(const Segment* seg, int n_seg, int wg) {
-    Segment r = seg[0];
-    for (int k = 1; k < n_seg; ++k)
-        if (seg[k].wg_begin <= wg) r = seg[k];
-    return r;
+    int lo = 0, hi = n_seg;                 // answer in [lo, hi)
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (seg[mid].wg_begin <= wg) lo = mid; else hi = mid;
+    }
+    return seg[lo];
 }
 
 // ROLES: 0 = A and B work interleaved in one launch; 1 = A work only; 2 = B work only; 3 = A work

@@ -727,7 +727,8 @@ int lpmm_adamw4_plan_build(const lpmm_tensor_desc* descs, int64_t n, int grad_dt
         pl.grid_b = pad8(pl.ph.n_b);
         host->phases.push_back(pl);
     }
-    if (env_int("LPMM_MULTI_STREAMS", 2) >= 2) {
+    // a second stream pays only if some pass 2 has a pass 1 of another group to run beside
+    if (env_int("LPMM_MULTI_STREAMS", 2) >= 2 && groups.size() > 1) {
         LPMM_HIP(hipStreamCreateWithFlags(&host->side, hipStreamNonBlocking));
         LPMM_HIP(hipEventCreateWithFlags(&host->ev_fork, hipEventDisableTiming));
         LPMM_HIP(hipEventCreateWithFlags(&host->ev_join, hipEventDisableTiming));
@@ -809,11 +810,20 @@ int lpmm_adamw4_step_multi(void* plan, float lr, float beta1, float beta2, float
         return LPMM_OK;
     }
     for (const PhaseLaunch& pl : host->phases) {
-        const bool rec = g_prof.on && g_prof.calls < g_prof.max_calls;
+        // as on the two-stream route, only launches that carry pass 1 are timed
+        const bool rec = g_prof.on && g_prof.calls < g_prof.max_calls && pl.ph.n_a > 0;
         const int64_t call = g_prof.calls;
         if (rec) LPMM_HIP(hipEventRecord(prof_event(call, 0), s));
-        if (bf16) hipLaunchKernelGGL((phase_kernel<true, 0>), dim3(pl.grid), dim3(kThreads), 0, s, pl.ph, h);
-        else hipLaunchKernelGGL((phase_kernel<false, 0>), dim3(pl.grid), dim3(kThreads), 0, s, pl.ph, h);
+        // a launch that holds only one kind of work takes that kind's (lighter) kernel
+        const int roles = pl.ph.n_b == 0 ? (pl.a_has_rank1 ? 1 : 3) : (pl.ph.n_a == 0 ? 2 : 0);
+#define LPMM_LAUNCH_PHASE(R)                                                                                  \
+        if (bf16) hipLaunchKernelGGL((phase_kernel<true, R>), dim3(pl.grid), dim3(kThreads), 0, s, pl.ph, h); \
+        else hipLaunchKernelGGL((phase_kernel<false, R>), dim3(pl.grid), dim3(kThreads), 0, s, pl.ph, h);
+        if (roles == 1) { LPMM_LAUNCH_PHASE(1) }
+        else if (roles == 2) { LPMM_LAUNCH_PHASE(2) }
+        else if (roles == 3) { LPMM_LAUNCH_PHASE(3) }
+        else { LPMM_LAUNCH_PHASE(0) }
+#undef LPMM_LAUNCH_PHASE
         LPMM_HIP(hipGetLastError());
         if (rec) {
             LPMM_HIP(hipEventRecord(prof_event(call, 1), s));
