@@ -302,7 +302,9 @@ int b128_step_impl(bool bf16, void* param, const void* grad, uint8_t* m_codes, f
     return LPMM_OK;
 }
 
-int grid_for(int64_t items, int64_t per_thread, int max_blocks = 1 << 20) {
+// Workgroups for `items` items at `per_thread` per thread.  Kernels that are not grid-stride loops must
+// get the full count (the default cap is the largest grid HIP takes; 2^40 elements stay far below it).
+int grid_for(int64_t items, int64_t per_thread, int max_blocks = 0x7FFFFFFF) {
     const int64_t threads = (items + per_thread - 1) / per_thread;
     int64_t blocks = (threads + kThreads - 1) / kThreads;
     if (blocks < 1) blocks = 1;

@@ -220,3 +220,64 @@ def test_config5_flattened_block_wise_second_moment_plan():
                 f"c5 flat {sp.name}: m block scales"
             del out, vb, mb
     lpmm.lpmm_adamw4_plan_release(plan)
+
+
+def test_more_than_2_31_elements_block_wise():
+    """64-bit indexing: a flat tensor of 2^31 + 2^20 + 130 elements.  Blocks are independent, so the
+    oracle checks the first and the last stretch of the tensor on their own."""
+    from test_gpu_b128 import compare as compare_b128
+    P = (1 << 31) + (1 << 20) + 130
+    head, tail0 = 128 * 1024, P - (128 * 1024 + 130)          # tail starts at a block boundary
+    assert tail0 % 128 == 0
+    lpmm.ensure_init(4096)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(26)
+    w = torch.empty(P, device=DEV).normal_(0.0, 0.02, generator=gen)
+    g = torch.empty(P, dtype=torch.bfloat16, device=DEV)
+    st = lpmm.new_state_b128(P, DEV)
+    refs = []
+    for lo, hi in ((0, head), (tail0, P)):
+        refs.append((lo, hi, w[lo:hi].cpu().numpy().copy(), oracle.state_zero_b128(hi - lo)))
+    for t in (1, 2):
+        g.copy_((torch.empty(P, device=DEV).normal_(0.0, 1e-3, generator=gen)).to(torch.bfloat16))
+        lpmm.lpmm_adamw4_b128_step_bf16g(w, g, st, HP.lr, HP.beta1, HP.beta2, HP.eps, HP.weight_decay, t)
+        torch.cuda.synchronize()
+        for lo, hi, w_ref, st_ref in refs:
+            gn = g[lo:hi].float().cpu().numpy()
+            mt, vt = oracle.adamw4_b128_step(w_ref, gn, st_ref, HP, t, want_moments=True)
+            b0, b1 = lo // 128, (hi + 127) // 128
+            got = oracle.StateB128(hi - lo, st.m_codes[lo // 2:(hi + 1) // 2].cpu().numpy(), st.m_blockscale[b0:b1].cpu().numpy(),
+                                   st.v_codes[lo // 2:(hi + 1) // 2].cpu().numpy(), st.v_blockscale[b0:b1].cpu().numpy())
+            assert compare_b128(got, st_ref, w[lo:hi].cpu().numpy(), w_ref, mt, vt, f"2^31+ [{lo}, {hi}) step {t}") == 0
+    # somewhere in the middle, beyond 2^31: block scales are the block maxima of the decompressed moments
+    lo = (1 << 31) + 128 * 1000
+    sl = slice(lo // 2, lo // 2 + 64 * 512)
+    out = torch.empty(128 * 512, device=DEV)
+    lpmm.lpmm_dequant_state(2, st.v_codes[sl], st.v_blockscale[lo // 128: lo // 128 + 512], None, 1, 128 * 512, out)
+    assert torch.equal(out.view(-1, 128).max(dim=1).values, st.v_blockscale[lo // 128: lo // 128 + 512])
+    assert bool((st.v_blockscale[lo // 128: lo // 128 + 512] > 0).all())
+
+
+def test_more_than_2_31_elements_rank1_invariants():
+    """64-bit indexing on the rank-1 path: 40960 x 57344 = 2.35 G elements, one step from the zero state,
+    then the properties that hold at any size."""
+    rows, cols = 40960, 57344
+    sp = workloads.TensorSpec("big", rows, cols)
+    lpmm.ensure_init(rows + cols)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(27)
+    w = torch.empty(rows * cols, device=DEV).normal_(0.0, 0.02, generator=gen)
+    w0_tail = w[-4096:].clone()
+    g = torch.empty(rows * cols, dtype=torch.bfloat16, device=DEV)
+    g.copy_((torch.empty(rows * cols, device=DEV).normal_(0.0, 1e-3, generator=gen)).to(torch.bfloat16))
+    st = lpmm.new_state(rows, cols, DEV)
+    lpmm.lpmm_adamw4_step_bf16g(w, g, st, HP.lr, HP.beta1, HP.beta2, HP.eps, HP.weight_decay, 1)
+    torch.cuda.synchronize()
+    _check_invariants(sp, st, "2.35 G elements")
+    # step 1 from the zero state is plain AdamW: w' = w - lr (g / (|g| + eps') + wd w) up to rounding
+    gt = g[-4096:].float()
+    want = w0_tail - HP.lr * (gt / (gt.abs() + HP.eps) + HP.weight_decay * w0_tail)
+    assert torch.allclose(w[-4096:], want, rtol=1e-4, atol=1e-6)
+    # row maxima of v_1 = (1 - beta2) g^2 over the last rows, from the gradient itself
+    v_last = ((1 - np.float32(HP.beta2)) * g[-cols:].float()) * g[-cols:].float()
+    assert torch.equal(v_last.max(), st.v_rowmax[-1])
