@@ -195,7 +195,7 @@ void b128_geometry(Tensor4* a, int n_cu, int64_t rounds_hint) {
 }
 
 bool fast_eligible(int64_t cols, const float* v_colmax) {
-    return (cols % LPMM_BLOCK) == 0 && cols <= (int64_t(1) << 24) && aligned(v_colmax, 16) &&
+    return (cols % LPMM_BLOCK) == 0 && cols < (int64_t(1) << 24) && aligned(v_colmax, 16) &&     // 24-bit row offsets
            !env_int("LPMM_FORCE_GENERAL", 0);
 }
 

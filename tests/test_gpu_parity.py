@@ -119,6 +119,10 @@ def test_zero_state_matches_oracle():
     (100, 1024, "col_lognormal"),      # 4 KiB rows: row spacing 8, ragged second tile
     (150, 4096, "iid"),                # row spacing 2 in pass 1 and 4 in pass 2, ragged last tiles
     (72, 2048, "iid"),                 # row spacing 4, 9 rows per group in one tile
+    (1, 4096, "iid"),                  # fast path with a single row
+    (3, 128, "col_lognormal"),         # fast path, one column block, fewer rows than groups
+    (5000, 128, "iid"),                # tall and one block wide: many row tiles of one strip
+    (2, 1280, "iid"),                  # 10 column blocks: fine for pass 2; see (203, 384) for a half-empty last strip
 ])
 def test_step_parity_small(rows, cols, recipe):
     assert run_parity(rows, cols, steps=6, recipe=recipe, seed=3) == 0
