@@ -62,12 +62,15 @@ def lib() -> ctypes.CDLL:
         L.oracle_adamw4_b128_step.argtypes = [f32p, f32p, u8p, f32p, u8p, f32p, i64,
                                               cf, cf, cf, cf, cf, i64, f32p, f32p]
         L.oracle_state_zero_b128.argtypes = [u8p, f32p, u8p, f32p, i64]
+        L.oracle_adamw4_factor_step.argtypes = [f32p, f32p, u8p, f32p, f32p, f32p, i64, i64,
+                                                cf, cf, cf, cf, cf, i64, f32p, f32p]
+        L.oracle_state_zero_factor.argtypes = [u8p, f32p, f32p, f32p, i64, i64]
         for name in ("oracle_table_linear", "oracle_table_de", "oracle_table_de_f64",
                      "oracle_step_table", "oracle_nearest_codes", "oracle_quant_m",
                      "oracle_dequant_m", "oracle_quant_v", "oracle_dequant_v",
                      "oracle_adamw32_step", "oracle_adamw4_step", "oracle_state_zero",
                      "oracle_quant_v_block", "oracle_dequant_v_block", "oracle_adamw4_b128_step",
-                     "oracle_state_zero_b128"):
+                     "oracle_state_zero_b128", "oracle_adamw4_factor_step", "oracle_state_zero_factor"):
             getattr(L, name).restype = None
         _lib = L
     return _lib
@@ -271,4 +274,44 @@ def adamw4_b128_step(w: np.ndarray, g: np.ndarray, st: StateB128, hp: Hyper, t: 
                                   _f32(st.v_scales), st.P, hp.lr, hp.beta1, hp.beta2, hp.eps,
                                   hp.weight_decay, t, _f32(mt) if want_moments else null,
                                   _f32(vt) if want_moments else null)
+    return mt, vt
+
+
+@dataclass
+class StateFactor:
+    """State of one rows x cols tensor under "4-bit Factor": compressed first moment, row and column
+    statistics of the second."""
+    rows: int
+    cols: int
+    m_codes: np.ndarray
+    m_scales: np.ndarray
+    v_row: np.ndarray
+    v_col: np.ndarray
+
+    def copy(self) -> "StateFactor":
+        return StateFactor(self.rows, self.cols, self.m_codes.copy(), self.m_scales.copy(),
+                           self.v_row.copy(), self.v_col.copy())
+
+
+def state_zero_factor(rows: int, cols: int) -> StateFactor:
+    P = rows * cols
+    st = StateFactor(rows, cols, np.zeros(codes_bytes(P), np.uint8), np.zeros(n_blocks(P), np.float32),
+                     np.ones(rows, np.float32), np.ones(cols, np.float32))
+    lib().oracle_state_zero_factor(_u8(st.m_codes), _f32(st.m_scales), _f32(st.v_row), _f32(st.v_col),
+                                   rows, cols)
+    return st
+
+
+def adamw4_factor_step(w: np.ndarray, g: np.ndarray, st: StateFactor, hp: Hyper, t: int, want_moments=False):
+    """In place on w (float32, rows*cols) and st; second moment factorized (Sec. 4.3)."""
+    assert w.size == st.rows * st.cols == g.size
+    mt = vt = None
+    null = ctypes.POINTER(ctypes.c_float)()
+    if want_moments:
+        mt = np.empty(w.size, np.float32)
+        vt = np.empty(w.size, np.float32)
+    lib().oracle_adamw4_factor_step(_f32(w), _f32(g), _u8(st.m_codes), _f32(st.m_scales), _f32(st.v_row),
+                                    _f32(st.v_col), st.rows, st.cols, hp.lr, hp.beta1, hp.beta2, hp.eps,
+                                    hp.weight_decay, t, _f32(mt) if want_moments else null,
+                                    _f32(vt) if want_moments else null)
     return mt, vt

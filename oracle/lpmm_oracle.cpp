@@ -18,6 +18,10 @@
 //     block-wise normalization with block size 128 is used for the second moment instead (the
 //     mapping stays the Linear one).  App. C.1 (LLaMA): FSDP packs parameters into 1-dimensional
 //     arrays, so that run used this form for every tensor.  Functions *_v_block / *_b128_*.
+//   * Sec. 4.3 and Sec. 5 ("4-bit Factor"): for tensors with two dimensions the second moment is
+//     not stored per element but factorized the way the cited Adafactor method does it: one
+//     statistic per row and one per column, v_ij reconstructed as row_i * col_j / sum(row).  The
+//     first moment stays B128/DE.  Functions *_factor_*.
 //   * App. D.1: signed normalization n = sign(x) N(|x|).
 //   * App. D.2: the dynamic-exponent (DE) map: sign bit, E leading zeros, indicator bit,
 //     F fraction bits; value 10^-E * fraction[k]; two special bit patterns; sorted list.
@@ -38,10 +42,16 @@
 //   * A zero scale (all-zero block, untouched row/column, the zero initial state) gives n := 0.
 //   * Scales are fp32.  Two codes per byte: element 2k in bits 0..3, element 2k+1 in bits 4..7.
 //   * Blocks are [128k, 128k+127] of the row-major flattening; the last one may be short.
+//   * 4-bit Factor: the paper gives no formulas, only the citation.  Reading: the optimizer stays the
+//     AdamW of Eq. 1 (same beta2, same bias correction, same eps; none of the cited method's own extras:
+//     no update clipping, no relative step size, no decay-rate schedule, no 1e-30 added to g^2);
+//     R_t = beta2 R_{t-1} + (1-beta2) rowsum(g^2), C_t likewise with column sums, and
+//     v_t[i][j] = R_t[i] C_t[j] / sum_i R_t[i] (0 when the sum is 0) takes the place of v_t.
+//     R and C are stored in fp32; nothing integer depends on them, so they are computed in double.
 //
 // Parity status: every function below is pinned by the CPU tests against values the paper prints,
 // closed forms, brute force, invariants or an fp64 library AdamW, EXCEPT the multi-step trajectory
-// of the full quantized step (either second-moment form), for which the paper prints nothing:
+// of the full quantized step (any second-moment form), for which the paper prints nothing:
 // "parity unpinned" beyond its parts.
 //
 // Build: g++ -O2 -std=c++17 -ffp-contract=off -fPIC -shared lpmm_oracle.cpp -o liblpmm_oracle.so
@@ -353,6 +363,60 @@ void oracle_state_zero_b128(uint8_t* m_codes, float* m_scales, uint8_t* v_codes,
     std::vector<float> z(static_cast<size_t>(P), 0.0f);
     quant_m(z.data(), P, m_codes, m_scales);
     quant_v_block(z.data(), P, v_codes, v_scales);
+}
+
+// One step of "4-bit Factor" on one rows x cols tensor (Sec. 4.3; Alg. 3 with the second moment kept
+// as row and column statistics instead of a compressed tensor).  R (rows floats) and C (cols floats)
+// are updated in place.  v_t_out (rows*cols floats, may be null) receives the reconstructed second
+// moment the update used, m_t_out the precise first moment.
+void oracle_adamw4_factor_step(float* w, const float* g, uint8_t* m_codes, float* m_scales, float* R,
+                               float* C, int64_t rows, int64_t cols, float lr, float beta1,
+                               float beta2, float eps, float wd, int64_t t, float* m_t_out,
+                               float* v_t_out) {
+    const int64_t P = rows * cols;
+    std::vector<float> m(static_cast<size_t>(P));
+    dequant_m(m_codes, m_scales, P, m.data());                    // Alg. 3: decompress
+
+    // row and column sums of the squared gradient, then their moving averages (the role v_t has in Eq. 1)
+    std::vector<double> row_sq(static_cast<size_t>(rows), 0.0), col_sq(static_cast<size_t>(cols), 0.0);
+    for (int64_t i = 0; i < rows; ++i)
+        for (int64_t j = 0; j < cols; ++j) {
+            const double sq = double(g[i * cols + j]) * double(g[i * cols + j]);
+            row_sq[size_t(i)] += sq;
+            col_sq[size_t(j)] += sq;
+        }
+    const double b2 = double(beta2);
+    for (int64_t i = 0; i < rows; ++i) R[i] = float(b2 * double(R[i]) + (1.0 - b2) * row_sq[size_t(i)]);
+    for (int64_t j = 0; j < cols; ++j) C[j] = float(b2 * double(C[j]) + (1.0 - b2) * col_sq[size_t(j)]);
+    double total = 0.0;
+    for (int64_t i = 0; i < rows; ++i) total += double(R[i]);
+
+    const float omb1 = 1.0f - beta1;
+    const double bc1 = 1.0 - std::pow(double(beta1), double(t));
+    const double bc2 = 1.0 - std::pow(b2, double(t));
+    for (int64_t i = 0; i < rows; ++i)
+        for (int64_t j = 0; j < cols; ++j) {
+            const int64_t e = i * cols + j;
+            const float mt = std::fmaf(beta1, m[size_t(e)], omb1 * g[e]);      // Eq. 1, as in adamw_rule
+            m[size_t(e)] = mt;
+            const double vt = total > 0.0 ? double(R[i]) * double(C[j]) / total : 0.0;
+            if (v_t_out) v_t_out[e] = float(vt);
+            const double mhat = double(mt) / bc1;
+            const double vhat = vt / bc2;
+            const double wi = double(w[e]);
+            w[e] = float(wi - double(lr) * (mhat / (std::sqrt(vhat) + double(eps)) + double(wd) * wi));
+        }
+    if (m_t_out) std::memcpy(m_t_out, m.data(), sizeof(float) * size_t(P));
+    quant_m(m.data(), P, m_codes, m_scales);                      // Alg. 3: compress
+}
+// zero state of the factorized form: m as everywhere, R = C = 0
+void oracle_state_zero_factor(uint8_t* m_codes, float* m_scales, float* R, float* C, int64_t rows,
+                              int64_t cols) {
+    const int64_t P = rows * cols;
+    std::vector<float> z(static_cast<size_t>(P), 0.0f);
+    quant_m(z.data(), P, m_codes, m_scales);
+    for (int64_t i = 0; i < rows; ++i) R[i] = 0.0f;
+    for (int64_t j = 0; j < cols; ++j) C[j] = 0.0f;
 }
 
 // The zero initial state of Alg. 3 (m_0 = v_0 = 0): m codes all point at the table's 0 entry with
