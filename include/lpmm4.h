@@ -142,6 +142,42 @@ int lpmm_adamw4_b128_step_bf16g(void* param, const void* grad, uint8_t* m_codes,
                                 float beta1, float beta2, float eps, float weight_decay, int64_t step,
                                 void* stream);
 
+/* ---- factorized second moment ("4-bit Factor") ------------------------------------------------------
+ * Sec. 4.3 and Sec. 5: for tensors with two dimensions the second moment is not stored per element
+ * but factorized as in the cited Adafactor method: one statistic per row and one per column; the
+ * first moment stays B128 / dynamic-exponent, the optimizer stays the AdamW of Eq. 1.  The paper
+ * gives no formulas for this variant; the reading implemented here:
+ *   R_t[i] = beta2 R_{t-1}[i] + (1-beta2) sum_j g_ij^2      C_t[j] = beta2 C_{t-1}[j] + (1-beta2) sum_i g_ij^2
+ *   v_t[i][j] = R_t[i] C_t[j] / sum_i R_t[i]   (0 where that sum is 0)   in place of Eq. 1's v_t,
+ * with Eq. 1's bias corrections and eps, and none of the cited method's own extras (update clipping,
+ * relative step size, decay-rate schedule, the constant added to g^2).  State of a rows x cols tensor:
+ *   m_codes, m_blockscale   as above
+ *   v_row  float[rows]      R            v_col  float[cols]      C          zero state: all 0
+ * (1-dimensional second moments are quantized instead: lpmm_adamw4_b128_step.)  Two kernels are
+ * enqueued: one reads the gradient and accumulates the sums (fp32 atomics: R, C and the parameters
+ * may differ in their last bits from run to run; the first moment does not), one updates.  Needs
+ * lpmm_adamw4_init on the current device with rows + cols within the workspace.  param, grad 16-byte
+ * aligned, the rest 4-byte. */
+
+/* sizes[4] (host, out): bytes of m_codes, m_blockscale, v_row, v_col. */
+int lpmm_adamw4_factor_state_sizes(const int64_t shape[2], size_t sizes[4]);
+
+/* Writes the zero state on `stream`. */
+int lpmm_adamw4_factor_state_zero(uint8_t* m_codes, float* m_blockscale, float* v_row, float* v_col,
+                                  const int64_t shape[2], void* stream);
+
+/* One step, in place on param and the four state buffers; grad (float[rows*cols]) is read only.
+ * Hyper-parameters and `step` as lpmm_adamw4_step. */
+int lpmm_adamw4_factor_step(void* param, const void* grad, uint8_t* m_codes, float* m_blockscale,
+                            float* v_row, float* v_col, const int64_t shape[2], float lr, float beta1,
+                            float beta2, float eps, float weight_decay, int64_t step, void* stream);
+
+/* Same step with a bf16 gradient buffer. */
+int lpmm_adamw4_factor_step_bf16g(void* param, const void* grad, uint8_t* m_codes, float* m_blockscale,
+                                  float* v_row, float* v_col, const int64_t shape[2], float lr,
+                                  float beta1, float beta2, float eps, float weight_decay, int64_t step,
+                                  void* stream);
+
 /* AdamW step with uncompressed fp32 states, for tensors that are not quantized (App. C.1: size
  * <= 4096, biases and normalization vectors): Alg. 3 with compress = decompress = identity.
  * param, m, v: float[numel] in place; grad: float or bf16 [numel] per grad_dtype. */

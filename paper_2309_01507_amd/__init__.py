@@ -11,4 +11,6 @@ from .binding import (  # noqa: F401
     lpmm_adamw4_plan_bytes, lpmm_adamw4_plan_build, lpmm_adamw4_step_multi, lpmm_adamw4_plan_release,
     StateB128, new_state_b128, KIND_4BIT_B128, lpmm_adamw4_b128_state_sizes, lpmm_adamw4_b128_state_zero,
     lpmm_adamw4_b128_step, lpmm_adamw4_b128_step_bf16g,
+    StateFactor, new_state_factor, lpmm_adamw4_factor_state_sizes, lpmm_adamw4_factor_state_zero,
+    lpmm_adamw4_factor_step, lpmm_adamw4_factor_step_bf16g,
 )

@@ -77,6 +77,11 @@ def lib() -> ctypes.CDLL:
         b128_args = [_VP] * 6 + [_I64] + [_F] * 5 + [_I64, _VP]
         L.lpmm_adamw4_b128_step.argtypes = b128_args
         L.lpmm_adamw4_b128_step_bf16g.argtypes = b128_args
+        L.lpmm_adamw4_factor_state_sizes.argtypes = [_VP, _VP]
+        L.lpmm_adamw4_factor_state_zero.argtypes = [_VP] * 4 + [_VP, _VP]
+        factor_args = [_VP] * 6 + [_VP] + [_F] * 5 + [_I64, _VP]
+        L.lpmm_adamw4_factor_step.argtypes = factor_args
+        L.lpmm_adamw4_factor_step_bf16g.argtypes = factor_args
         L.lpmm_dequant_state.argtypes = [ctypes.c_int, _VP, _VP, _VP, _VP, _VP, _VP]
         L.lpmm_quant_state.argtypes = [ctypes.c_int, _VP, _VP, _VP, _VP, _VP, _VP]
         L.lpmm_adamw4_plan_bytes.argtypes = [_VP, _I64]
@@ -284,6 +289,65 @@ def lpmm_adamw4_b128_step_bf16g(param, grad, st: StateB128, lr, beta1, beta2, ep
                                 stream=None):
     _b128_step("lpmm_adamw4_b128_step_bf16g", param, grad, st, lr, beta1, beta2, eps, weight_decay, step,
                stream)
+
+
+# ---- factorized second moment ("4-bit Factor") ------------------------------------------------------------
+
+@dataclass
+class StateFactor:
+    """The four device buffers of one rows x cols tensor's state with a factorized second moment."""
+    rows: int
+    cols: int
+    m_codes: "object"
+    m_blockscale: "object"
+    v_row: "object"
+    v_col: "object"
+
+
+def lpmm_adamw4_factor_state_sizes(rows: int, cols: int):
+    sizes = (ctypes.c_size_t * 4)()
+    shape = _SHAPE(int(rows), int(cols))
+    _check(lib().lpmm_adamw4_factor_state_sizes(ctypes.addressof(shape), ctypes.addressof(sizes)),
+           "lpmm_adamw4_factor_state_sizes")
+    return [int(s) for s in sizes]
+
+
+def lpmm_adamw4_factor_state_zero(st: StateFactor, stream=None) -> None:
+    shape = _SHAPE(st.rows, st.cols)
+    _check(lib().lpmm_adamw4_factor_state_zero(_ptr(st.m_codes), _ptr(st.m_blockscale), _ptr(st.v_row),
+                                               _ptr(st.v_col), ctypes.addressof(shape), _stream(stream)),
+           "lpmm_adamw4_factor_state_zero")
+
+
+def new_state_factor(rows: int, cols: int, device="cuda") -> StateFactor:
+    """Allocate (torch) and zero (library) the state of a rows x cols tensor, second moment factorized."""
+    import torch
+    sz = lpmm_adamw4_factor_state_sizes(rows, cols)
+    pad4 = lambda n: (n + 3) // 4 * 4
+    st = StateFactor(rows, cols,
+                     torch.empty(pad4(sz[0]), dtype=torch.uint8, device=device)[:sz[0]],
+                     torch.empty(sz[1] // 4, dtype=torch.float32, device=device),
+                     torch.empty(sz[2] // 4, dtype=torch.float32, device=device),
+                     torch.empty(sz[3] // 4, dtype=torch.float32, device=device))
+    lpmm_adamw4_factor_state_zero(st)
+    return st
+
+
+def _factor_step(fn_name, param, grad, st: StateFactor, lr, beta1, beta2, eps, weight_decay, step, stream):
+    fn = getattr(lib(), fn_name)
+    shape = _SHAPE(st.rows, st.cols)
+    _check(fn(_ptr(param), _ptr(grad), _ptr(st.m_codes), _ptr(st.m_blockscale), _ptr(st.v_row), _ptr(st.v_col),
+              ctypes.addressof(shape), lr, beta1, beta2, eps, weight_decay, int(step), _stream(stream)), fn_name)
+
+
+def lpmm_adamw4_factor_step(param, grad, st: StateFactor, lr, beta1, beta2, eps, weight_decay, step, stream=None):
+    _factor_step("lpmm_adamw4_factor_step", param, grad, st, lr, beta1, beta2, eps, weight_decay, step, stream)
+
+
+def lpmm_adamw4_factor_step_bf16g(param, grad, st: StateFactor, lr, beta1, beta2, eps, weight_decay, step,
+                                  stream=None):
+    _factor_step("lpmm_adamw4_factor_step_bf16g", param, grad, st, lr, beta1, beta2, eps, weight_decay, step,
+                 stream)
 
 
 def lpmm_adamw32_step(param, grad, m, v, numel, grad_dtype, lr, beta1, beta2, eps, weight_decay, step,

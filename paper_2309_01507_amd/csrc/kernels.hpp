@@ -28,7 +28,7 @@ namespace lpmm {
 __device__ float d_byte_decode[512];          // entry b: {T_DE[b & 15], T_DE[b >> 4]}
 __device__ SearchEntry d_search[kBucketsPadded];    // nearest-entry search for the DE map
 
-enum TensorKind : int { kQuantFast = 0, kQuantGeneral = 1, kFp32State = 2, kQuantBlockV = 3 };
+enum TensorKind : int { kQuantFast = 0, kQuantGeneral = 1, kFp32State = 2, kQuantBlockV = 3, kFactorFast = 4, kFactorGeneral = 5 };
 
 struct Tensor4 {
     float* p;               // parameters, fp32 [P]
@@ -36,23 +36,25 @@ struct Tensor4 {
     uint32_t* mq;           // first-moment codes, 8 per word   (kFp32State: float* m)
     float* ms;              // first-moment block scales
     uint32_t* vq;           // second-moment codes              (kFp32State: float* v)
-    float* r;               // row maxima (state)               (kQuantBlockV: block scales of v)
-    float* c;               // column maxima (state)
-    float* r_new;           // workspace: row maxima of v_t (zero between steps)
-    float* c_new;           // workspace: column maxima of v_t (zero between steps)
-    unsigned int* counter;  // workspace: ticket counters of pass 2 (zero between steps)
+    float* r;               // row maxima (state)               (kQuantBlockV: block scales of v; kFactor*: row statistics)
+    float* c;               // column maxima (state)            (kFactor*: column statistics)
+    float* r_new;           // workspace: row maxima of v_t (zero between steps)      (kFactor*: row sums of g^2)
+    float* c_new;           // workspace: column maxima of v_t (zero between steps)   (kFactor*: column sums of g^2)
+    unsigned int* counter;  // workspace: ticket counters of pass 2 (zero between steps); kFactor*: also two float sums
     int64_t rows, cols, P;
     // geometry of the fast path (cols % 128 == 0)
     int nb;                 // column blocks per row = cols / 128    (kQuantBlockV: whole blocks of the tensor)
     int gx, gy;             // a workgroup's 8 groups: gx column blocks x gy row phases
     int rw;                 // rows per workgroup tile; rw * cols < 2^29   (kQuantBlockV: blocks a group takes in a row)
     int strips;             // nb / gx
-    int n_wg;               // workgroups of pass 1 (general path: of either pass; kQuantBlockV: of the step)
+    int n_wg;               // workgroups of pass 1 (general path: of either pass; kQuantBlockV: of the step;
+                            // kFactor*: of the statistics pass, which is tiled like pass 2)
     int kind;
     // pass 2 of the fast path has its own tiling: strips of 256 columns, rw2 rows per workgroup
     int strips2;            // ceil(nb / 2)
     int rw2;                // rw2 * cols < 2^29
-    int n_wg2;              // workgroups of pass 2                 (kQuantBlockV: workgroups on whole blocks)
+    int n_wg2;              // workgroups of pass 2                 (kQuantBlockV: workgroups on whole blocks;
+                            // kFactor*: of the update pass, which is tiled like pass 1)
     // log2 of the row spacing of pass 1 / pass 2: the 2^rs (2^rs2) rows that a group (a wave) takes in a
     // row are consecutive, and the groups (waves) that run side by side are 2^rs rows apart
     int rs, rs2;
@@ -591,8 +593,9 @@ __device__ __forceinline__ void move_and_clear(float* dst, float* src, int64_t n
     }
 }
 
-__device__ __forceinline__ void publish_if_last(const Tensor4& a, unsigned int me, unsigned int participants,
-                                                int& s_last) {
+// true in every thread of the one workgroup that arrives last
+__device__ __forceinline__ bool last_to_arrive(const Tensor4& a, unsigned int me, unsigned int participants,
+                                               int& s_last) {
     __syncthreads();
     if (threadIdx.x == 0) {
         // No fence: the ticket orders nothing but "this workgroup's loads of r, c have returned",
@@ -609,7 +612,12 @@ __device__ __forceinline__ void publish_if_last(const Tensor4& a, unsigned int m
         s_last = last;
     }
     __syncthreads();
-    if (!s_last) return;
+    return s_last != 0;
+}
+
+__device__ __forceinline__ void publish_if_last(const Tensor4& a, unsigned int me, unsigned int participants,
+                                                int& s_last) {
+    if (!last_to_arrive(a, me, participants, s_last)) return;
     move_and_clear(a.r, a.r_new, a.rows);
     move_and_clear(a.c, a.c_new, a.cols);
     if (threadIdx.x == 0) *a.counter = 0u;
@@ -1125,6 +1133,373 @@ __device__ __forceinline__ void pass2_general_tile(const Tensor4& a, const Hyper
 }
 
 // =====================================================================================================
+// Factorized second moment ("4-bit Factor", Sec. 4.3): for a rows x cols tensor the second moment is
+// kept as row statistics R and column statistics C, moving averages (with beta2, as v_t in Eq. 1) of
+// the row and column sums of g^2, and v_t[i][j] = R_i C_j / sum_i R_i takes the place of Eq. 1's v_t.
+// The first moment is compressed as everywhere (B128 + signed dynamic-exponent map).
+//
+// Two passes, because every element's update needs the complete sums of its row and column:
+//   statistics pass: reads the gradient only; row and column sums of g^2 into the workspace (float
+//                    atomics), plus two scalars: the sum of all g^2 and the sum of the old R.
+//   update pass:     R_t[i] = beta2 R[i] + (1-beta2) rowsum_i, C_t[j] likewise, sum R_t = beta2 sum R +
+//                    (1-beta2) sum g^2; decompress m, Eq. 1 with the reconstructed v_t, parameter
+//                    update, compress m_t.  The last workgroup writes R_t, C_t to the state (the same
+//                    expression every workgroup evaluated) and clears the workspace.
+// Nothing integer depends on the second moment here, so the sums are plain fp32 in whatever order
+// the atomics arrive: R, C and the parameters vary in their last bits from run to run; the first
+// moment's codes and scales do not.
+// =====================================================================================================
+
+constexpr int kTotNew = 8, kTotOld = 9;     // words of the counter block that hold the two float sums
+
+__device__ __forceinline__ void atomic_add_f32(float* addr, float v) { (void)unsafeAtomicAdd(addr, v); }
+
+// new statistic from the old one and this step's sum of squares
+__device__ __forceinline__ float stat_ema(const Hyper& h, float old, float sum_sq) {
+    return __builtin_fmaf(h.beta2, old, h.omb2 * sum_sq);
+}
+__device__ __forceinline__ float factor_inv_total(const Tensor4& a, const Hyper& h) {
+    const float* tot = reinterpret_cast<const float*>(a.counter);
+    const float total = stat_ema(h, tot[kTotOld], tot[kTotNew]);
+    return total > 0.0f ? 1.0f / total : 0.0f;          // all-zero statistics: v_t = 0
+}
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_fadd(float x) {
+    return x + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, false));
+}
+// sum over the 64 lanes of a wave, the same value in every lane (fixed order)
+__device__ __forceinline__ float wave_sum(float v) {
+    v = dpp_fadd<0xB1>(v);      // lane ^ 1
+    v = dpp_fadd<0x4E>(v);      // lane ^ 2
+    v = dpp_fadd<0x141>(v);     // other quad of the half row
+    v = dpp_fadd<0x140>(v);     // other half of the row of 16
+    v += __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(v), 0x401F));     // lane ^ 16
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0)) +
+           __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
+}
+
+// Statistics pass, fast path (cols % 128 == 0).  Tiled like pass 2: a wave works on 256 consecutive
+// columns of one row, the four waves of a workgroup take rows w, w+4, ... of a tile of rw2 rows.  Row
+// sums are staged in LDS, column sums are combined over the four waves in LDS; one atomic per row and
+// per column of the tile.
+template <bool BF16>
+__device__ __forceinline__ void factor_stats_tile(const Tensor4& a, int wg, Lds& s) {
+    const int strip = wg % a.strips2, tile = wg / a.strips2;
+    const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
+    const int lane = threadIdx.x & 63;
+    const uint32_t col0 = uint32_t(strip) * 256u + uint32_t(lane) * 4u;
+    const bool live = col0 < uint32_t(a.cols);      // odd number of column blocks: upper half of the last strip
+    const int64_t row0 = int64_t(tile) * a.rw2;
+    const int64_t left = a.rows - row0;
+    const int n = left < a.rw2 ? int(left) : a.rw2;
+    const Rsrc rg = tile_rsrc(reinterpret_cast<const char*>(a.g) + row0 * a.cols * (BF16 ? 2 : 4),
+                              uint32_t(n) * uint32_t(a.cols) * (BF16 ? 2u : 4u));
+    float cacc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    auto ld = [&](int il) { return load_grad_regs4<BF16>(rg, row_offset(il, a.cols, col0) * 4u); };
+    auto one = [&](const GradRegs4<BF16>& r, int il) {
+        float g[4];
+        unpack_grad4<BF16>(r, g);
+        float sq[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            sq[e] = live ? g[e] * g[e] : 0.0f;
+            cacc[e] += sq[e];
+        }
+        const float rsum = wave_sum((sq[0] + sq[1]) + (sq[2] + sq[3]));
+        if (lane == 0) s.blk_scale[il] = rsum;
+    };
+    // rows in the order of pass 2; loads of two rows in flight while a third is summed
+    const int rs = a.rs2;
+    const int row_w = wave << rs, hop = kWaves << rs, low = (1 << rs) - 1;
+    auto row = [&](int k) { return row_w + (k & low) + (k >> rs) * hop; };
+    int k = 0;
+    GradRegs4<BF16> r0 = ld(row(0)), r1 = ld(row(1)), r2;
+    __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
+    while (row(k + 2) < n) {
+        r2 = ld(row(k + 2));
+        one(r0, row(k));
+        r0 = ld(row(k + 3));
+        one(r1, row(k + 1));
+        r1 = ld(row(k + 4));
+        one(r2, row(k + 2));
+        k += 3;
+    }
+    if (row(k) < n) {
+        one(r0, row(k));
+        if (row(k + 1) < n) one(r1, row(k + 1));
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) s.col[wave * 256 + lane * 4 + e] = cacc[e];
+    __syncthreads();
+    for (int t = threadIdx.x; t < n; t += kThreads) atomic_add_f32(a.r_new + row0 + t, s.blk_scale[t]);
+    {
+        const int t = threadIdx.x;
+        const float csum = (s.col[t] + s.col[256 + t]) + (s.col[512 + t] + s.col[768 + t]);
+        const int64_t col = int64_t(strip) * 256 + t;
+        if (col < a.cols) atomic_add_f32(a.c_new + col, csum);
+    }
+    float* tot = reinterpret_cast<float*>(a.counter);
+    if (wave == 0) {                 // the tile's share of the sum of all g^2
+        float part = 0.0f;
+        for (int t = lane; t < n; t += 64) part += s.blk_scale[t];
+        part = wave_sum(part);
+        if (lane == 0) atomic_add_f32(tot + kTotNew, part);
+    } else if (wave == 1 && strip == 0) {   // the old statistics of the tile's rows, once per row
+        float part = 0.0f;
+        for (int t = lane; t < n; t += 64) part += a.r[row0 + t];
+        part = wave_sum(part);
+        if (lane == 0) atomic_add_f32(tot + kTotOld, part);
+    }
+}
+
+template <bool BF16>
+struct RowF {                      // everything the update pass reads for one row of one lane
+    float4 p;
+    GradRegs4<BF16> g;
+    uint16_t mq;
+    float s_old, r_old, r_sum;
+};
+
+template <bool BF16>
+__device__ __forceinline__ RowF<BF16> load_rowf(const TileBase& b, const Tensor4& a, const Geo& g, int il) {
+    RowF<BF16> r;
+    const uint32_t off4 = row_offset(il, a.cols, g.col0) * 4u;
+    r.p = buf_ld_f4_stream(b.rp, off4);
+    r.g = load_grad_regs4<BF16, kPolicyNt>(b.rg, off4);     // last use of the gradient in this step
+    r.mq = buf_ld_u16(b.rmq, off4 >> 3);
+    r.s_old = buf_ld_f(b.rms, row_offset(il, a.nb, uint32_t(g.cb)) * 4u);
+    r.r_old = buf_ld_f(b.rr, uint32_t(il) * 4u);
+    r.r_sum = buf_ld_f(b.rr_new, uint32_t(il) * 4u);
+    return r;
+}
+
+// One row of the update pass for one lane; ct[e] = C_t of the lane's columns.
+template <bool BF16, class Mid>
+__device__ __forceinline__ void factor_row(const Tensor4& a, const Hyper& h, const TileBase& tb, const Geo& geo,
+                                           Lds& s, const RowF<BF16>& cur, int il, const float ct[4],
+                                           float inv_total, Mid mid) {
+    float w[4] = {cur.p.x, cur.p.y, cur.p.z, cur.p.w};
+    float g[4];
+    unpack_grad4<BF16>(cur.g, g);
+    float mt[4], amax = 0.0f;
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        const float2 t = s.deq[(uint32_t(cur.mq) >> (8 * k)) & 255u];
+        mt[2 * k] = t.x * cur.s_old;
+        mt[2 * k + 1] = t.y * cur.s_old;
+    }
+    const float rn = stat_ema(h, cur.r_old, cur.r_sum) * inv_total;      // R_t[i] / sum R_t
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        mt[e] = moment_m(h, mt[e], g[e]);
+        w[e] = param_update(h, w[e], mt[e], rn * ct[e]);
+        amax = fmaxf(amax, fabsf(mt[e]));
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    mid();                                    // the caller's prefetch (see pass 1)
+    __builtin_amdgcn_sched_barrier(0);
+    const float s_new = group32_allmax(amax);
+
+    uint32_t mq_new = 0;
+    uint32_t dist = scale_is_tame(s_new) ? 0xFFFFFFFFu : 0u;
+    {
+        const float inv_s = approx_inv(s_new);
+#pragma unroll
+        for (int e = 0; e < 4; e += 2) {
+            uint32_t da, db;
+            mq_new |= quant_m_code_fast(s.search, mt[e], inv_s, da) << (4 * e);
+            mq_new |= quant_m_code_fast(s.search, mt[e + 1], inv_s, db) << (4 * e + 4);
+            dist = min(min(dist, da), db);
+        }
+    }
+    if (__builtin_expect(__ballot(dist < kMinDistM) != 0, 0)) {
+        mq_new = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) mq_new |= quant_m_code(s.search, mt[e], s_new) << (4 * e);
+    }
+    const uint32_t off4 = row_offset(il, a.cols, geo.col0) * 4u;
+    st_stream4(tb.p, off4, make_float4(w[0], w[1], w[2], w[3]));
+    st<uint16_t>(tb.mq, off4 >> 3, uint16_t(mq_new));
+    if (geo.l == 0) s.blk_scale[il * a.gx + geo.gxi] = s_new;
+}
+
+// Update pass, fast path: tiled and pipelined like pass 1.
+template <bool BF16>
+__device__ __forceinline__ void factor_update_tile(const Tensor4& a, const Hyper& h, int wg, Lds& s) {
+    const Geo geo = geometry(a, wg);
+    const TileBase tb = tile_base<BF16>(a, geo.row0, geo.n_rows);
+    if (geo.active) {
+        float ct[4], csum[4];
+        load4(a.c + geo.col0, ct);
+        load4(a.c_new + geo.col0, csum);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) ct[e] = stat_ema(h, ct[e], csum[e]);
+        const float inv_total = factor_inv_total(a, h);
+        const int n = geo.n_rows, rs = a.rs;
+        const int row_g = geo.gyi << rs, hop = a.gy << rs, low = (1 << rs) - 1;
+        auto row = [&](int k) { return row_g + (k & low) + (k >> rs) * hop; };
+        int k = 0;
+        RowF<BF16> r0 = load_rowf<BF16>(tb, a, geo, row(0));
+        RowF<BF16> r1 = load_rowf<BF16>(tb, a, geo, row(1));
+        RowF<BF16> r2;
+        load_tables(s);
+        __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
+        auto none = [] {};
+        while (row(k + 2) < n) {
+            factor_row<BF16>(a, h, tb, geo, s, r0, row(k), ct, inv_total,
+                             [&] { r2 = load_rowf<BF16>(tb, a, geo, row(k + 2)); });
+            factor_row<BF16>(a, h, tb, geo, s, r1, row(k + 1), ct, inv_total,
+                             [&] { r0 = load_rowf<BF16>(tb, a, geo, row(k + 3)); });
+            factor_row<BF16>(a, h, tb, geo, s, r2, row(k + 2), ct, inv_total,
+                             [&] { r1 = load_rowf<BF16>(tb, a, geo, row(k + 4)); });
+            k += 3;
+        }
+        if (row(k) < n) {
+            factor_row<BF16>(a, h, tb, geo, s, r0, row(k), ct, inv_total, none);
+            if (row(k + 1) < n) factor_row<BF16>(a, h, tb, geo, s, r1, row(k + 1), ct, inv_total, none);
+        }
+    } else {
+        load_tables(s);
+    }
+    __syncthreads();
+    for (int t = threadIdx.x; t < geo.n_rows * a.gx; t += kThreads) {
+        const int il = t / a.gx, cbi = geo.strip * a.gx + t % a.gx;
+        if (cbi < a.nb) st<float>(tb.ms, row_offset(il, a.nb, uint32_t(cbi)) * 4u, s.blk_scale[t]);
+    }
+}
+
+// stat[i] = stat_ema(stat[i], sum[i]); sum[i] = 0, by one workgroup (see move_and_clear)
+__device__ __forceinline__ void ema_and_clear(const Hyper& h, float* stat, float* sum, int64_t n) {
+    constexpr int kDepth = 8;
+    for (int64_t base = threadIdx.x; base < n; base += int64_t(kThreads) * kDepth) {
+        float o[kDepth], v[kDepth];
+#pragma unroll
+        for (int u = 0; u < kDepth; ++u) {
+            const int64_t i = base + int64_t(u) * kThreads;
+            o[u] = i < n ? stat[i] : 0.0f;
+            v[u] = i < n ? sum[i] : 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < kDepth; ++u) {
+            const int64_t i = base + int64_t(u) * kThreads;
+            if (i < n) { stat[i] = stat_ema(h, o[u], v[u]); sum[i] = 0.0f; }
+        }
+    }
+}
+
+// The last workgroup of a tensor's update pass makes R_t, C_t the state and clears the workspace;
+// every other workgroup has read the old statistics and the sums before it took its ticket.
+__device__ __forceinline__ void factor_publish_if_last(const Tensor4& a, const Hyper& h, unsigned int me,
+                                                       unsigned int participants, int& s_last) {
+    if (!last_to_arrive(a, me, participants, s_last)) return;
+    ema_and_clear(h, a.r, a.r_new, a.rows);
+    ema_and_clear(h, a.c, a.c_new, a.cols);
+    if (threadIdx.x == 0) {
+        *a.counter = 0u;
+        a.counter[kTotNew] = 0u;
+        a.counter[kTotOld] = 0u;
+    }
+}
+
+// General path of the factorized form (any rows x cols): lane t owns flat elements [8t, 8t+8), row and
+// column tracked per element, one atomic per element and column.  Correct, not tuned.
+template <bool BF16>
+__device__ __forceinline__ void factor_stats_general_tile(const Tensor4& a, int wg, int n_wg, Lds& s) {
+    const int64_t t = int64_t(wg) * kThreads + threadIdx.x;
+    const LaneIo io = lane_io(a.P, a.cols, t);
+    float part = 0.0f, old = 0.0f;
+    if (io.nv) {
+        float g[8];
+        if (io.nv == 8) {
+            load_grad8<BF16>(a.g, io.base, g);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) g[e] = e < io.nv ? load_grad1<BF16>(a.g, io.base + e) : 0.0f;
+        }
+        int64_t i = io.i, j = io.j, run_row = io.i;
+        float run = 0.0f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            if (e < io.nv) {
+                const float sq = g[e] * g[e];
+                if (i != run_row) { atomic_add_f32(a.r_new + run_row, run); run_row = i; run = 0.0f; }
+                run += sq;
+                part += sq;
+                atomic_add_f32(a.c_new + j, sq);
+                if (++j == a.cols) { j = 0; ++i; }
+            }
+        }
+        atomic_add_f32(a.r_new + run_row, run);
+    }
+    for (int64_t i = t; i < a.rows; i += int64_t(n_wg) * kThreads) old += a.r[i];
+    part = wave_sum(part);
+    old = wave_sum(old);
+    if ((threadIdx.x & 63) == 0) { s.col[threadIdx.x >> 6] = part; s.col[8 + (threadIdx.x >> 6)] = old; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        float* tot = reinterpret_cast<float*>(a.counter);
+        atomic_add_f32(tot + kTotNew, (s.col[0] + s.col[1]) + (s.col[2] + s.col[3]));
+        atomic_add_f32(tot + kTotOld, (s.col[8] + s.col[9]) + (s.col[10] + s.col[11]));
+    }
+}
+
+template <bool BF16>
+__device__ __forceinline__ void factor_update_general_tile(const Tensor4& a, const Hyper& h, int wg, Lds& s) {
+    const int64_t t = int64_t(wg) * kThreads + threadIdx.x;
+    const int64_t block = t >> 4;                       // uniform over the 16 lanes of a block
+    if (block * 128 >= a.P) return;
+    const LaneIo io = lane_io(a.P, a.cols, t);
+    float w[8], g[8];
+    if (io.nv == 8) {
+        load8(a.p + io.base, w);
+        load_grad8<BF16>(a.g, io.base, g);
+    } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            w[e] = e < io.nv ? a.p[io.base + e] : 0.0f;
+            g[e] = e < io.nv ? load_grad1<BF16>(a.g, io.base + e) : 0.0f;
+        }
+    }
+    const uint32_t mq = load_codes(a.mq, io);
+    const float s_old = a.ms[block];
+    const float inv_total = factor_inv_total(a, h);
+    float mt[8], amax = 0.0f;
+    int64_t i = io.i, j = io.j;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        if (e < io.nv) {
+            const float2 tt = s.deq[(mq >> (8 * (e >> 1))) & 255u];
+            const float m_prev = ((e & 1) ? tt.y : tt.x) * s_old;
+            mt[e] = moment_m(h, m_prev, g[e]);
+            const float rn = stat_ema(h, a.r[i], a.r_new[i]) * inv_total;
+            const float vt = rn * stat_ema(h, a.c[j], a.c_new[j]);
+            w[e] = param_update(h, w[e], mt[e], vt);
+            amax = fmaxf(amax, fabsf(mt[e]));
+            if (++j == a.cols) { j = 0; ++i; }
+        } else {
+            mt[e] = 0.0f;
+        }
+    }
+    const float s_new = row16_allmax(amax);
+    uint32_t mq_new = 0;
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+        if (e < io.nv) mq_new |= quant_m_code(s.search, mt[e], s_new) << (4 * e);
+    if (io.nv == 8) {
+        float4* pp = reinterpret_cast<float4*>(a.p + io.base);
+        pp[0] = make_float4(w[0], w[1], w[2], w[3]);
+        pp[1] = make_float4(w[4], w[5], w[6], w[7]);
+    } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            if (e < io.nv) a.p[io.base + e] = w[e];
+    }
+    if (io.nv) store_codes(a.mq, io, mq_new);
+    if ((threadIdx.x & 15) == 0) a.ms[block] = s_new;
+}
+
+// =====================================================================================================
 // Uncompressed fp32 states (tensors that are not quantized): Alg. 3 with identity compression.
 // One workgroup handles kElemsPerWg32 consecutive elements.
 // =====================================================================================================
@@ -1172,6 +1547,37 @@ __global__ __launch_bounds__(kThreads) void b128_kernel(const Tensor4 a, const H
     __shared__ Lds s;
     const int wg = logical_wg();
     if (wg < a.n_wg) b128_work<BF16>(a, h, wg, s);
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(kThreads) void factor_stats_fast(const Tensor4 a) {
+    __shared__ Lds s;
+    const int wg = logical_wg();
+    if (wg < a.n_wg) factor_stats_tile<BF16>(a, wg, s);
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(kThreads) void factor_update_fast(const Tensor4 a, const Hyper h) {
+    __shared__ Lds s;
+    __shared__ int s_last;
+    const int wg = logical_wg();
+    if (wg < a.n_wg2) factor_update_tile<BF16>(a, h, wg, s);
+    factor_publish_if_last(a, h, blockIdx.x, gridDim.x, s_last);
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(kThreads) void factor_stats_general(const Tensor4 a) {
+    __shared__ Lds s;
+    factor_stats_general_tile<BF16>(a, blockIdx.x, gridDim.x, s);
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(kThreads) void factor_update_general(const Tensor4 a, const Hyper h) {
+    __shared__ Lds s;
+    __shared__ int s_last;
+    load_tables(s);
+    factor_update_general_tile<BF16>(a, h, blockIdx.x, s);
+    factor_publish_if_last(a, h, blockIdx.x, gridDim.x, s_last);
 }
 
 template <bool BF16>

@@ -302,6 +302,78 @@ int b128_step_impl(bool bf16, void* param, const void* grad, uint8_t* m_codes, f
     return LPMM_OK;
 }
 
+// Tiling of a tensor with a factorized second moment: the statistics pass is tiled like pass 2 and is the
+// step's first ("A") launch, the update pass is tiled like pass 1 and is the second ("B") one.
+void factor_geometry(Tensor4* a, int n_cu, int64_t rw_hint, int64_t rw2_hint, int grad_bytes, bool fast) {
+    if (fast) {
+        fast_geometry(a, n_cu, rw_hint, rw2_hint, grad_bytes);
+        if (a->rw2 > kMaxRowSlots) {          // row sums of a statistics tile are staged in LDS
+            a->rw2 = kMaxRowSlots;
+            a->n_wg2 = int(a->strips2 * ((a->rows + a->rw2 - 1) / a->rw2));
+            a->rs2 = row_spacing_log2(a->cols * grad_bytes, a->rw2, kWaves, "LPMM_RS2");
+        }
+        std::swap(a->n_wg, a->n_wg2);
+        a->kind = kFactorFast;
+    } else {
+        a->n_wg = a->n_wg2 = int((((a->P + 7) / 8) + kThreads - 1) / kThreads);
+        a->kind = kFactorGeneral;
+    }
+}
+
+int factor_step_impl(bool bf16, void* param, const void* grad, uint8_t* m_codes, float* m_blockscale,
+                     float* v_row, float* v_col, const int64_t* shape, float lr, float beta1, float beta2,
+                     float eps, float wd, int64_t step, void* stream) {
+    int64_t rows, cols;
+    int rc = check_shape(shape, &rows, &cols);
+    if (rc) return rc;
+    if (!param || !grad || !m_codes || !m_blockscale || !v_row || !v_col) return LPMM_EINVAL;
+    if (!aligned(param, 16) || !aligned(grad, 16) || !aligned(m_codes, 4) || !aligned(m_blockscale, 4) ||
+        !aligned(v_row, 4) || !aligned(v_col, 4))
+        return LPMM_EINVAL;
+    Hyper h;
+    rc = make_hyper(lr, beta1, beta2, eps, wd, step, &h);
+    if (rc) return rc;
+    DeviceCtx* ctx;
+    rc = current_ctx(&ctx);
+    if (rc) return rc;
+    const int64_t rows_pad = round_up(rows, 64), cols_pad = round_up(cols, 64);
+    if (rows_pad + cols_pad > ctx->cap_floats) return LPMM_EWORKSPACE;
+    Tensor4 t{};
+    t.p = static_cast<float*>(param);
+    t.g = grad;
+    t.mq = reinterpret_cast<uint32_t*>(m_codes);
+    t.ms = m_blockscale;
+    t.r = v_row;
+    t.c = v_col;
+    t.r_new = ctx->ws;
+    t.c_new = ctx->ws + rows_pad;
+    t.counter = ctx->counter;
+    t.rows = rows;
+    t.cols = cols;
+    t.P = rows * cols;
+    const bool fast = fast_eligible(cols, v_col);
+    factor_geometry(&t, ctx->n_cu, 0, 0, bf16 ? 2 : 4, fast);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const bool rec = g_prof.on && g_prof.calls < g_prof.max_calls;
+    const int64_t call = g_prof.calls;
+    if (rec) LPMM_HIP(hipEventRecord(prof_event(call, 0), s));
+#define LPMM_LAUNCH_FACTOR(B)                                                                                      \
+    if (fast) hipLaunchKernelGGL(factor_stats_fast<B>, dim3(pad8(t.n_wg)), dim3(kThreads), 0, s, t);               \
+    else hipLaunchKernelGGL(factor_stats_general<B>, dim3(t.n_wg), dim3(kThreads), 0, s, t);                       \
+    LPMM_HIP(hipGetLastError());                                                                                   \
+    if (rec) LPMM_HIP(hipEventRecord(prof_event(call, 1), s));                                                     \
+    if (fast) hipLaunchKernelGGL(factor_update_fast<B>, dim3(pad8(t.n_wg2)), dim3(kThreads), 0, s, t, h);          \
+    else hipLaunchKernelGGL(factor_update_general<B>, dim3(t.n_wg2), dim3(kThreads), 0, s, t, h);                  \
+    LPMM_HIP(hipGetLastError());
+    if (bf16) { LPMM_LAUNCH_FACTOR(true) } else { LPMM_LAUNCH_FACTOR(false) }
+#undef LPMM_LAUNCH_FACTOR
+    if (rec) {
+        LPMM_HIP(hipEventRecord(prof_event(call, 2), s));
+        g_prof.calls = call + 1;
+    }
+    return LPMM_OK;
+}
+
 // Workgroups for `items` items at `per_thread` per thread.  Kernels that are not grid-stride loops must
 // get the full count (the default cap is the largest grid HIP takes; 2^40 elements stay far below it).
 int grid_for(int64_t items, int64_t per_thread, int max_blocks = 0x7FFFFFFF) {
@@ -532,6 +604,48 @@ int lpmm_adamw4_b128_step_bf16g(void* param, const void* grad, uint8_t* m_codes,
                                 float beta2, float eps, float weight_decay, int64_t step, void* stream) {
     return b128_step_impl(true, param, grad, m_codes, m_blockscale, v_codes, v_blockscale, numel, lr, beta1,
                           beta2, eps, weight_decay, step, stream);
+}
+
+int lpmm_adamw4_factor_state_sizes(const int64_t shape[2], size_t sizes[4]) {
+    int64_t rows, cols;
+    const int rc = check_shape(shape, &rows, &cols);
+    if (rc) return rc;
+    if (!sizes) return LPMM_EINVAL;
+    const int64_t P = rows * cols;
+    sizes[0] = size_t((P + 1) / 2);
+    sizes[1] = size_t((P + LPMM_BLOCK - 1) / LPMM_BLOCK) * sizeof(float);
+    sizes[2] = size_t(rows) * sizeof(float);
+    sizes[3] = size_t(cols) * sizeof(float);
+    return LPMM_OK;
+}
+
+int lpmm_adamw4_factor_state_zero(uint8_t* m_codes, float* m_blockscale, float* v_row, float* v_col,
+                                  const int64_t shape[2], void* stream) {
+    size_t sz[4];
+    const int rc = lpmm_adamw4_factor_state_sizes(shape, sz);
+    if (rc) return rc;
+    if (!m_codes || !m_blockscale || !v_row || !v_col) return LPMM_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t P = shape[0] * shape[1];
+    int r = fill(m_codes, int64_t(sz[0]), 0x77, (P & 1) ? int64_t(sz[0]) - 1 : -1, 0x07, s);
+    if (!r) r = fill(m_blockscale, int64_t(sz[1]), 0, -1, 0, s);
+    if (!r) r = fill(v_row, int64_t(sz[2]), 0, -1, 0, s);
+    if (!r) r = fill(v_col, int64_t(sz[3]), 0, -1, 0, s);
+    return r;
+}
+
+int lpmm_adamw4_factor_step(void* param, const void* grad, uint8_t* m_codes, float* m_blockscale, float* v_row,
+                            float* v_col, const int64_t shape[2], float lr, float beta1, float beta2, float eps,
+                            float weight_decay, int64_t step, void* stream) {
+    return factor_step_impl(false, param, grad, m_codes, m_blockscale, v_row, v_col, shape, lr, beta1, beta2,
+                            eps, weight_decay, step, stream);
+}
+
+int lpmm_adamw4_factor_step_bf16g(void* param, const void* grad, uint8_t* m_codes, float* m_blockscale,
+                                  float* v_row, float* v_col, const int64_t shape[2], float lr, float beta1,
+                                  float beta2, float eps, float weight_decay, int64_t step, void* stream) {
+    return factor_step_impl(true, param, grad, m_codes, m_blockscale, v_row, v_col, shape, lr, beta1, beta2,
+                            eps, weight_decay, step, stream);
 }
 
 int lpmm_adamw32_step(void* param, const void* grad, float* m, float* v, int64_t numel, int grad_dtype,
