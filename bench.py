@@ -41,6 +41,13 @@ def bytes_per_param_b128(bf16: bool):
     return 8.0 + (2.0 if bf16 else 4.0) + 2.0 + 16.0 / 128.0
 
 
+# factorized second moment, two passes.  Update pass: param read+write 8, grad 4 or 2, m codes read+write 1, block
+# scales read+write 8/128.  Statistics pass: grad 4 or 2.
+def bytes_per_param_factor(bf16: bool):
+    g = 2.0 if bf16 else 4.0
+    return 8.0 + g + 1.0 + 8.0 / 128.0, g
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -51,9 +58,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--grad-dtype", choices=["config", "bf16", "f32"], default="config",
                     help="override the gradient type of the configuration (experiments)")
-    ap.add_argument("--second-moment", choices=["rank1", "b128"], default="rank1",
+    ap.add_argument("--second-moment", choices=["rank1", "b128", "factor"], default="rank1",
                     help="rank1: rank-1/Linear second moment of 2-D tensors (two passes, the headline "
-                         "configuration); b128: every tensor flat with a block-wise second moment (one pass)")
+                         "configuration); b128: every tensor flat with a block-wise second moment (one pass); "
+                         "factor: row / column statistics instead of a per-element second moment (two passes)")
     ap.add_argument("--launch", choices=["multi", "per-tensor"], default="multi",
                     help="multi: one plan, pass 1 / pass 2 of neighbouring tensor groups share launches; "
                          "per-tensor: two launches per quantized tensor")
@@ -106,7 +114,7 @@ def main():
         if sp.quantized and args.second_moment == "b128":
             tensors.append(("q", sp, p, gs, lpmm.new_state_b128(sp.numel, dev)))
         elif sp.quantized:
-            st = lpmm.new_state(sp.rows, sp.cols, dev)
+            st = (lpmm.new_state_factor if args.second_moment == "factor" else lpmm.new_state)(sp.rows, sp.cols, dev)
             max_rc = max(max_rc, sp.rows + sp.cols)
             tensors.append(("q", sp, p, gs, st))
         else:
@@ -119,7 +127,10 @@ def main():
     n_params = sum(sp.numel for sp in specs)
     n_quant = sum(sp.numel for sp in specs if sp.quantized)
     b128 = args.second_moment == "b128"
-    if b128:
+    factor = args.second_moment == "factor"
+    if factor:
+        step4 = lpmm.lpmm_adamw4_factor_step_bf16g if bf16 else lpmm.lpmm_adamw4_factor_step
+    elif b128:
         step4 = lpmm.lpmm_adamw4_b128_step_bf16g if bf16 else lpmm.lpmm_adamw4_b128_step
     else:
         step4 = lpmm.lpmm_adamw4_step_bf16g if bf16 else lpmm.lpmm_adamw4_step
@@ -159,7 +170,9 @@ def main():
     value = n_params / (elapsed / args.steps)
 
     # ---- the same K steps again with HIP events around every launch of the step -------------------------
-    bp1, bp2 = (bytes_per_param_b128(bf16), 0.0) if b128 else bytes_per_param(bf16)
+    # bp1: the recorded (dominant) kernel, bp2: the other pass
+    bp1, bp2 = ((bytes_per_param_b128(bf16), 0.0) if b128 else bytes_per_param_factor(bf16) if factor
+                else bytes_per_param(bf16))
     n_small = n_params - n_quant
     small_bytes = (24.0 + (2.0 if bf16 else 4.0)) * n_small      # fp32-state AdamW: p, m, v read+write, g read
     n_q_tensors = sum(1 for x in tensors if x[0] == "q")
@@ -170,25 +183,33 @@ def main():
     torch.cuda.synchronize()
     p1_ms, p2_ms, n_calls = lpmm.lpmm_profile_end()
     launches = max(n_calls, 1)
+    if factor and not plans:
+        p1_ms, p2_ms = p2_ms, p1_ms          # per tensor the statistics pass is recorded first; the update pass dominates
     if plans:
         # the recorded launches are the pass-1 kernels (pass 1 of a tensor group plus the fp32-state
         # tensors); pass 2 of the previous group runs beside them on the plan's second stream
-        bytes_per_launch = (bp1 * n_quant + small_bytes) * args.steps / launches
+        # (a factorized plan's recorded launches are its update passes, on the second stream; the fp32-state
+        # tensors ride with the statistics passes)
+        bytes_per_launch = (bp1 * n_quant + (0.0 if factor else small_bytes)) * args.steps / launches
         avg_ms = p1_ms / launches
         achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9
         roofline = {
-            "bound": "hbm", "kernel": ("phase_kernel<roles=3> (the whole block-wise step)" if b128 else "phase_kernel<roles=1> (pass 1)"),
+            "bound": "hbm", "kernel": ("phase_kernel<roles=3> (the whole block-wise step)" if b128 else
+                                       "factor_phase_kernel<roles=2> (update pass)" if factor else
+                                       "phase_kernel<roles=1> (pass 1)"),
             "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
             "bytes_per_param": bp1, "launches": n_calls, "avg_launch_ms": round(avg_ms, 5),
             "bytes_per_launch": round(bytes_per_launch),
             "traffic_source": None,
             "note": ("one pass: this kernel is the whole step" if b128 else
+                     "the statistics pass of the next tensor group (%.1f B/param) runs concurrently and shares "
+                     "the bandwidth; whole-step figures are in config" % bp2 if factor else
                      "pass 2 of the neighbouring tensor group (%.1f B/param) runs concurrently and shares "
                      "the bandwidth; whole-step figures are in config" % bp2),
         }
         # HBM bytes per launch measured offline with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/)
-        tpath = os.path.join(ROOT, "profiles", "traffic_phase_kernel_%s%s.json" % (args.config, "_b128" if b128 else ""))
+        tpath = os.path.join(ROOT, "profiles", "traffic_phase_kernel_%s%s.json" % (args.config, "_b128" if b128 else "_factor" if factor else ""))
         if os.path.exists(tpath):
             tr = json.load(open(tpath))
             if tr.get("launches_per_step") == n_calls // max(args.steps, 1):
@@ -199,12 +220,13 @@ def main():
         p1_bytes_per_launch = bp1 * n_quant * args.steps / launches
         achieved = p1_bytes_per_launch / (p1_avg_ms * 1e-3) / 1e9
         roofline = {
-            "bound": "hbm", "kernel": "b128_kernel" if b128 else "pass1_fast", "achieved": round(achieved, 1),
+            "bound": "hbm", "kernel": "b128_kernel" if b128 else "factor_update_fast" if factor else "pass1_fast",
+            "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
             "bytes_per_param": bp1, "launches": n_calls, "avg_launch_ms": round(p1_avg_ms, 5),
             "bytes_per_launch": round(p1_bytes_per_launch),
-            "pass2": {"bytes_per_param": bp2, "avg_launch_ms": round(p2_ms / launches, 5),
+            ("statistics_pass" if factor else "pass2"): {"bytes_per_param": bp2, "avg_launch_ms": round(p2_ms / launches, 5),
                       "achieved": round(bp2 * n_quant * args.steps / max(p2_ms, 1e-9) / 1e6, 1)},
         }
 
@@ -216,8 +238,9 @@ def main():
         rows = min(big.rows, max(1, (24 << 20) // big.cols))        # about 25 M parameters of that tensor
         cols = big.cols
         w = workloads.weights(args.seed, 0, rows, cols).reshape(-1)
-        st = oracle.state_zero_b128(rows * cols) if b128 else oracle.state_zero(rows, cols)
-        cpu_step = oracle.adamw4_b128_step if b128 else oracle.adamw4_step
+        st = (oracle.state_zero_b128(rows * cols) if b128 else oracle.state_zero_factor(rows, cols) if factor
+              else oracle.state_zero(rows, cols))
+        cpu_step = oracle.adamw4_b128_step if b128 else oracle.adamw4_factor_step if factor else oracle.adamw4_step
         hp = oracle.Hyper(lr, b1, b2, eps, wd)
         n_cpu_steps = 20
         gs = [workloads.grads(args.seed, 0, s, rows, cols, recipe, bf16).reshape(-1) for s in (1, 2)]
@@ -233,10 +256,10 @@ def main():
     total_gbps = ((bp1 + bp2) * n_quant + small_bytes) / (elapsed / args.steps) / 1e9
     # every stream touched once (what a single pass would move): param 8, grad, codes 2, block scales and,
     # for the rank-1 form, one more float per 128 elements standing in for the row / column maxima
-    floor_bpp = 8.0 + (2.0 if bf16 else 4.0) + 2.0 + (16.0 if b128 else 8.0) / 128.0
+    floor_bpp = 8.0 + (2.0 if bf16 else 4.0) + (1.0 if factor else 2.0) + (16.0 if b128 else 8.0) / 128.0
     floor_gbps = (floor_bpp * n_quant + small_bytes) / (elapsed / args.steps) / 1e9
     if plans:
-        kernels_per_step = (n_calls // max(args.steps, 1)) * (1 if b128 else 2)
+        kernels_per_step = (n_calls // max(args.steps, 1)) * (1 if b128 else 2)     # as many A as B launches
     else:
         kernels_per_step = n_q_tensors * (1 if b128 else 2) + (len(tensors) - n_q_tensors)
     out = {
@@ -247,9 +270,12 @@ def main():
         "config": {"workload": args.config, "tensors": len(specs), "params": n_params,
                    "quantized_params": n_quant, "grad_dtype": "bf16" if bf16 else "f32",
                    "second_moment": "block-wise B128/Linear on flattened tensors, one pass" if b128
+                   else "factorized (row and column statistics), two passes" if factor
                    else "rank-1/Linear, two passes",
                    "grad_recipe": recipe,
                    "launch": (("multi-tensor plan, %d launches per step" if b128 else
+                               "multi-tensor plan, %d update launches per step on a second stream, the statistics "
+                               "passes on the caller's stream" if factor else
                                "multi-tensor plan, %d pass-1 launches per step on the caller's stream, "
                                "pass 2 on a second stream") % (n_calls // max(args.steps, 1)))
                    if plans else "per-tensor, %d kernel%s per quantized tensor" % ((1, "") if b128 else (2, "s")),

@@ -214,6 +214,11 @@ int lpmm_quant_state(int which, const float* in, const int64_t shape[2], uint8_t
                                    v_rowmax points at v_blockscale, v_colmax is ignored, the tensor is the
                                    rows*cols elements taken flat */
 
+#define LPMM_KIND_4BIT_FACTOR 3 /* quantized first moment, factorized second moment, as in lpmm_adamw4_factor_step:
+                                   v_state is ignored (may be NULL), v_rowmax points at v_row, v_colmax at v_col.
+                                   A plan holds LPMM_KIND_4BIT or LPMM_KIND_4BIT_FACTOR tensors, not both (they
+                                   are two optimizers); either may be mixed with the other two kinds */
+
 typedef struct lpmm_tensor_desc {
     void* param;            /* float[rows*cols], in place */
     const void* grad;       /* float or bf16 [rows*cols] (one type for the whole plan) */

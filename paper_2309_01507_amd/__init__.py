@@ -12,5 +12,5 @@ from .binding import (  # noqa: F401
     StateB128, new_state_b128, KIND_4BIT_B128, lpmm_adamw4_b128_state_sizes, lpmm_adamw4_b128_state_zero,
     lpmm_adamw4_b128_step, lpmm_adamw4_b128_step_bf16g,
     StateFactor, new_state_factor, lpmm_adamw4_factor_state_sizes, lpmm_adamw4_factor_state_zero,
-    lpmm_adamw4_factor_step, lpmm_adamw4_factor_step_bf16g,
+    lpmm_adamw4_factor_step, lpmm_adamw4_factor_step_bf16g, KIND_4BIT_FACTOR,
 )

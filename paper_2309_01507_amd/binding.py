@@ -373,7 +373,7 @@ def lpmm_quant_state(which: int, x, rows, cols, codes, scale_a, scale_b, stream=
 
 # ---- many tensors in one call ------------------------------------------------------------------------
 
-KIND_4BIT, KIND_FP32, KIND_4BIT_B128 = 0, 1, 2
+KIND_4BIT, KIND_FP32, KIND_4BIT_B128, KIND_4BIT_FACTOR = 0, 1, 2, 3
 
 
 class TensorDesc(ctypes.Structure):
@@ -386,6 +386,9 @@ class TensorDesc(ctypes.Structure):
 def make_desc(param, grad, state, rows=None, cols=None) -> TensorDesc:
     """state: a State4 (4-bit, rank-1 second moment), a StateB128 (4-bit, block-wise second moment)
     or a (m, v) pair of fp32 tensors (then rows, cols must be given)."""
+    if isinstance(state, StateFactor):
+        return TensorDesc(_ptr(param), _ptr(grad), _ptr(state.m_codes), _ptr(state.m_blockscale), None,
+                          _ptr(state.v_row), _ptr(state.v_col), state.rows, state.cols, KIND_4BIT_FACTOR, 0)
     if isinstance(state, StateB128):
         return TensorDesc(_ptr(param), _ptr(grad), _ptr(state.m_codes), _ptr(state.m_blockscale),
                           _ptr(state.v_codes), _ptr(state.v_blockscale), None, 1, state.numel,

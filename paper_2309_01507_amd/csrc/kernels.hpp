@@ -1676,6 +1676,43 @@ __global__ __launch_bounds__(kThreads) void phase_kernel(const Phase ph, const H
     }
 }
 
+// The same for a plan whose 2-dimensional tensors keep a factorized second moment: "A" work is the
+// statistics pass (next to block-wise and fp32-state tensors, which are complete after it), "B" work
+// the update pass.  ROLES: 0 = both interleaved, 1 = A only, 2 = B only.  Separate kernels, so that the
+// rank-1 kernels above keep their register footprint.
+template <bool BF16, int ROLES>
+__global__ __launch_bounds__(kThreads) void factor_phase_kernel(const Phase ph, const Hyper h) {
+    __shared__ Lds s;
+    const int x = logical_wg();
+    const int n = (ROLES == 2 ? 0 : ph.n_a) + (ROLES == 1 ? 0 : ph.n_b);
+    if (x >= n) return;
+    const int b_before = ROLES == 1 ? 0 : (ROLES == 2 ? x : int((int64_t(x) * ph.n_b) / n));
+    const int b_after = ROLES == 1 ? 0 : (ROLES == 2 ? x + 1 : int((int64_t(x + 1) * ph.n_b) / n));
+    if (ROLES != 1 && b_after > b_before) {
+        __shared__ int s_last;
+        const Segment sg = find_segment(ph.seg_b, ph.n_seg_b, b_before);
+        const Tensor4 a = from_table(ph.tensors[sg.tensor]);
+        const int wg = b_before - sg.wg_begin;
+        if (a.kind == kFactorFast) {
+            factor_update_tile<BF16>(a, h, wg, s);
+        } else {
+            load_tables(s);
+            factor_update_general_tile<BF16>(a, h, wg, s);
+        }
+        factor_publish_if_last(a, h, wg, a.n_wg2, s_last);
+    } else if (ROLES != 2) {
+        const int xa = x - b_before;
+        const Segment sg = find_segment(ph.seg_a, ph.n_seg_a, xa);
+        const Tensor4 a = from_table(ph.tensors[sg.tensor]);
+        const int wg = xa - sg.wg_begin;
+        if (a.kind == kFp32State)
+            adamw32_tile<BF16>(a.p, a.g, reinterpret_cast<float*>(a.mq), reinterpret_cast<float*>(a.vq), a.P, h, wg);
+        else if (a.kind == kQuantBlockV) b128_work<BF16>(a, h, wg, s);
+        else if (a.kind == kFactorFast) factor_stats_tile<BF16>(a, wg, s);
+        else factor_stats_general_tile<BF16>(a, wg, a.n_wg, s);
+    }
+}
+
 // =====================================================================================================
 // Stand-alone decompress / compress of one moment, and the zero state.
 // =====================================================================================================

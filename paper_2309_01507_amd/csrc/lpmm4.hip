@@ -398,6 +398,7 @@ struct PlanHost {
     std::vector<char> staging;          // host image of the device tables (kept for the async copy)
     std::vector<PhaseLaunch> phases;
     bool bf16 = false;
+    bool factor = false;                // the plan's 2-dimensional tensors keep a factorized second moment
     int device = 0;
     // second stream for pass 2 (same priority as any other stream), with its ordering events
     hipStream_t side = nullptr;
@@ -423,16 +424,22 @@ struct PlanLayout {
 
 bool desc_shape_ok(const lpmm_tensor_desc& d) {
     int64_t shape[2] = {d.rows, d.cols}, r, c;
-    return check_shape(shape, &r, &c) == LPMM_OK && (d.kind == LPMM_KIND_4BIT || d.kind == LPMM_KIND_FP32 || d.kind == LPMM_KIND_4BIT_B128);
+    return check_shape(shape, &r, &c) == LPMM_OK && (d.kind == LPMM_KIND_4BIT || d.kind == LPMM_KIND_FP32 ||
+                                                     d.kind == LPMM_KIND_4BIT_B128 || d.kind == LPMM_KIND_4BIT_FACTOR);
 }
 
 bool plan_layout(const lpmm_tensor_desc* descs, int64_t n, PlanLayout* L) {
     if (!descs || n < 1 || n > (1 << 20)) return false;
     int64_t floats = 0;
+    bool rank1 = false, factor = false;
     for (int64_t i = 0; i < n; ++i) {
         if (!desc_shape_ok(descs[i])) return false;
-        if (descs[i].kind == LPMM_KIND_4BIT) floats += round_up(descs[i].rows, 64) + round_up(descs[i].cols, 64);
+        if (descs[i].kind == LPMM_KIND_4BIT || descs[i].kind == LPMM_KIND_4BIT_FACTOR)
+            floats += round_up(descs[i].rows, 64) + round_up(descs[i].cols, 64);
+        if (descs[i].kind == LPMM_KIND_4BIT) rank1 = true;
+        if (descs[i].kind == LPMM_KIND_4BIT_FACTOR) factor = true;
     }
+    if (rank1 && factor) return false;       // two different optimizers: one plan holds one of them
     size_t off = 0;
     L->off_tensors = off;   off += size_t(round_up(n * int64_t(sizeof(Tensor4)), 256));
     L->off_counters = off;  off += size_t(n) * kCounterWords * sizeof(unsigned int);
@@ -773,8 +780,26 @@ int lpmm_adamw4_plan_build(const lpmm_tensor_desc* descs, int64_t n, int grad_dt
         t.g = d.grad;
         t.mq = static_cast<uint32_t*>(d.m_state);
         t.vq = static_cast<uint32_t*>(d.v_state);
-        if (!d.param || !d.grad || !d.m_state || !d.v_state) return LPMM_EINVAL;
-        if (d.kind == LPMM_KIND_FP32) {
+        if (!d.param || !d.grad || !d.m_state) return LPMM_EINVAL;
+        if (!d.v_state && d.kind != LPMM_KIND_4BIT_FACTOR) return LPMM_EINVAL;
+        if (d.kind == LPMM_KIND_4BIT_FACTOR) {
+            if (!d.m_blockscale || !d.v_rowmax || !d.v_colmax) return LPMM_EINVAL;
+            if (!aligned(d.param, 16) || !aligned(d.grad, 16) || !aligned(d.m_state, 4) ||
+                !aligned(d.m_blockscale, 4) || !aligned(d.v_rowmax, 4) || !aligned(d.v_colmax, 4))
+                return LPMM_EINVAL;
+            t.vq = nullptr;
+            t.ms = d.m_blockscale;
+            t.r = d.v_rowmax;                      // row statistics
+            t.c = d.v_colmax;                      // column statistics
+            t.r_new = d_floats + fofs;
+            fofs += round_up(d.rows, 64);
+            t.c_new = d_floats + fofs;
+            fofs += round_up(d.cols, 64);
+            t.counter = d_counters + i * kCounterWords;
+            factor_geometry(&t, ctx->n_cu, rw_hint, rw2_hint, grad_dtype == LPMM_GRAD_BF16 ? 2 : 4,
+                            fast_eligible(d.cols, d.v_colmax));
+            host->factor = true;
+        } else if (d.kind == LPMM_KIND_FP32) {
             if (!aligned(d.param, 4) || !aligned(d.m_state, 4) || !aligned(d.v_state, 4) || !aligned(d.grad, galign))
                 return LPMM_EINVAL;
             t.kind = kFp32State;
@@ -881,6 +906,23 @@ int lpmm_adamw4_step_multi(void* plan, float lr, float beta1, float beta2, float
     if (dev != host->device) return LPMM_EINVAL;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool bf16 = host->bf16;
+    // roles: 0 = A and B work in one launch, 1 = A only, 2 = B only, 3 = A only without rank-1 tensors
+    auto launch = [&](int roles, int grid, hipStream_t on, const PhaseLaunch& pl) {
+#define LPMM_PHASE_CASE(K, R)                                                                               \
+        if (bf16) hipLaunchKernelGGL((K<true, R>), dim3(grid), dim3(kThreads), 0, on, pl.ph, h);            \
+        else hipLaunchKernelGGL((K<false, R>), dim3(grid), dim3(kThreads), 0, on, pl.ph, h);
+        if (host->factor) {
+            if (roles == 0) { LPMM_PHASE_CASE(factor_phase_kernel, 0) }
+            else if (roles == 2) { LPMM_PHASE_CASE(factor_phase_kernel, 2) }
+            else { LPMM_PHASE_CASE(factor_phase_kernel, 1) }
+        } else {
+            if (roles == 0) { LPMM_PHASE_CASE(phase_kernel, 0) }
+            else if (roles == 1) { LPMM_PHASE_CASE(phase_kernel, 1) }
+            else if (roles == 2) { LPMM_PHASE_CASE(phase_kernel, 2) }
+            else { LPMM_PHASE_CASE(phase_kernel, 3) }
+        }
+#undef LPMM_PHASE_CASE
+    };
     if (host->side) {
         // A work of phase j on the caller's stream, B work (pass 2 of the tensors whose pass 1 ran
         // in phase j-1) on the side stream behind an event; the caller's stream rejoins at the end.
@@ -892,22 +934,24 @@ int lpmm_adamw4_step_multi(void* plan, float lr, float beta1, float beta2, float
             const PhaseLaunch& pl = host->phases[j];
             if (pl.ph.n_b > 0) {
                 LPMM_HIP(hipStreamWaitEvent(s2, host->ev_a[j - 1], 0));
-                if (bf16) hipLaunchKernelGGL((phase_kernel<true, 2>), dim3(pl.grid_b), dim3(kThreads), 0, s2, pl.ph, h);
-                else hipLaunchKernelGGL((phase_kernel<false, 2>), dim3(pl.grid_b), dim3(kThreads), 0, s2, pl.ph, h);
+                // a factorized plan's heavy kernel is its B work (the update pass): that one is timed
+                const bool rec = host->factor && g_prof.on && g_prof.calls < g_prof.max_calls;
+                const int64_t call = g_prof.calls;
+                if (rec) LPMM_HIP(hipEventRecord(prof_event(call, 0), s2));
+                launch(2, pl.grid_b, s2, pl);
                 LPMM_HIP(hipGetLastError());
+                if (rec) {
+                    LPMM_HIP(hipEventRecord(prof_event(call, 1), s2));
+                    LPMM_HIP(hipEventRecord(prof_event(call, 2), s2));
+                    g_prof.calls = call + 1;
+                }
             }
             hipStream_t sa = (host->side_a && (j & 1)) ? host->side_a : s;
             if (pl.ph.n_a > 0) {
-                const bool rec = g_prof.on && g_prof.calls < g_prof.max_calls;
+                const bool rec = !host->factor && g_prof.on && g_prof.calls < g_prof.max_calls;
                 const int64_t call = g_prof.calls;
                 if (rec) LPMM_HIP(hipEventRecord(prof_event(call, 0), sa));
-                if (pl.a_has_rank1) {
-                    if (bf16) hipLaunchKernelGGL((phase_kernel<true, 1>), dim3(pl.grid_a), dim3(kThreads), 0, sa, pl.ph, h);
-                    else hipLaunchKernelGGL((phase_kernel<false, 1>), dim3(pl.grid_a), dim3(kThreads), 0, sa, pl.ph, h);
-                } else {
-                    if (bf16) hipLaunchKernelGGL((phase_kernel<true, 3>), dim3(pl.grid_a), dim3(kThreads), 0, sa, pl.ph, h);
-                    else hipLaunchKernelGGL((phase_kernel<false, 3>), dim3(pl.grid_a), dim3(kThreads), 0, sa, pl.ph, h);
-                }
+                launch(pl.a_has_rank1 ? 1 : 3, pl.grid_a, sa, pl);
                 LPMM_HIP(hipGetLastError());
                 if (rec) {
                     LPMM_HIP(hipEventRecord(prof_event(call, 1), sa));
@@ -926,20 +970,13 @@ int lpmm_adamw4_step_multi(void* plan, float lr, float beta1, float beta2, float
         return LPMM_OK;
     }
     for (const PhaseLaunch& pl : host->phases) {
-        // as on the two-stream route, only launches that carry pass 1 are timed
-        const bool rec = g_prof.on && g_prof.calls < g_prof.max_calls && pl.ph.n_a > 0;
+        // as on the two-stream route, only launches that carry pass 1 (factorized plans: the update pass) are timed
+        const bool rec = g_prof.on && g_prof.calls < g_prof.max_calls && (host->factor ? pl.ph.n_b > 0 : pl.ph.n_a > 0);
         const int64_t call = g_prof.calls;
         if (rec) LPMM_HIP(hipEventRecord(prof_event(call, 0), s));
         // a launch that holds only one kind of work takes that kind's (lighter) kernel
         const int roles = pl.ph.n_b == 0 ? (pl.a_has_rank1 ? 1 : 3) : (pl.ph.n_a == 0 ? 2 : 0);
-#define LPMM_LAUNCH_PHASE(R)                                                                                  \
-        if (bf16) hipLaunchKernelGGL((phase_kernel<true, R>), dim3(pl.grid), dim3(kThreads), 0, s, pl.ph, h); \
-        else hipLaunchKernelGGL((phase_kernel<false, R>), dim3(pl.grid), dim3(kThreads), 0, s, pl.ph, h);
-        if (roles == 1) { LPMM_LAUNCH_PHASE(1) }
-        else if (roles == 2) { LPMM_LAUNCH_PHASE(2) }
-        else if (roles == 3) { LPMM_LAUNCH_PHASE(3) }
-        else { LPMM_LAUNCH_PHASE(0) }
-#undef LPMM_LAUNCH_PHASE
+        launch(roles, pl.grid, s, pl);
         LPMM_HIP(hipGetLastError());
         if (rec) {
             LPMM_HIP(hipEventRecord(prof_event(call, 1), s));

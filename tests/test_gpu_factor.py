@@ -211,3 +211,74 @@ def test_bad_arguments_are_rejected():
     big = (ctypes.c_int64 * 2)(1 << 31, 128)          # rows + cols beyond any registered workspace
     assert L.lpmm_adamw4_factor_step(*args(shape=big)) != 0
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("env", [{}, {"LPMM_PHASE_MPARAMS": "1"}, {"LPMM_PHASE_MPARAMS": "1", "LPMM_MULTI_STREAMS": "1"}],
+                         ids=["one-group", "two-streams", "fused-launches"])
+def test_plan_with_factorized_block_wise_and_fp32_tensors(env):
+    """A "4-bit Factor" parameter set in one plan: matrices factorized, a large 1-dimensional tensor
+    block-wise, small ones with fp32 states."""
+    from test_gpu_b128 import compare as compare_b128, download as download_b128
+    hp = oracle.Hyper()
+    seed = 54
+    shapes = [("w1", 256, 384, "factor"), ("flat", 1, 128 * 300 + 20, "b128"), ("ln", 1, 512, "fp32"),
+              ("w2", 300, 1024, "factor"), ("odd", 37, 200, "factor"), ("w3", 1024, 256, "factor")]
+    for k in ("LPMM_PHASE_MPARAMS", "LPMM_MULTI_STREAMS"):
+        os.environ.pop(k, None)
+    os.environ.update(env)
+    try:
+        lpmm.ensure_init(4096)
+        dev, ref, descs = [], [], []
+        for tid, (name, rows, cols, kind) in enumerate(shapes):
+            P = rows * cols
+            w_ref = workloads.weights(seed, tid, rows, cols).reshape(-1)
+            w, g = to_dev(w_ref.copy()), torch.empty(P, dtype=torch.float32, device=DEV)
+            if kind == "factor":
+                st, st_ref = lpmm.new_state_factor(rows, cols, DEV), oracle.state_zero_factor(rows, cols)
+                descs.append(lpmm.make_desc(w, g, st))
+            elif kind == "b128":
+                st, st_ref = lpmm.new_state_b128(P, DEV), oracle.state_zero_b128(P)
+                descs.append(lpmm.make_desc(w, g, st))
+            else:
+                st = (torch.zeros(P, device=DEV), torch.zeros(P, device=DEV))
+                st_ref = (np.zeros(P, np.float32), np.zeros(P, np.float32))
+                descs.append(lpmm.make_desc(w, g, st, rows, cols))
+            dev.append((w, g, st))
+            ref.append((w_ref, st_ref))
+        plan = lpmm.new_plan(descs, 0, DEV)
+        for t in (1, 2, 3):
+            grads = [workloads.grads(seed, tid, t, rows, cols, "col_lognormal").reshape(-1)
+                     for tid, (_, rows, cols, _) in enumerate(shapes)]
+            for (w, g, st), gn in zip(dev, grads):
+                g.copy_(to_dev(gn))
+            lpmm.lpmm_adamw4_step_multi(plan, hp.lr, hp.beta1, hp.beta2, hp.eps, hp.weight_decay, t)
+            torch.cuda.synchronize()
+            for (name, rows, cols, kind), (w, g, st), (w_ref, st_ref), gn in zip(shapes, dev, ref, grads):
+                tag = f"{name} step {t}"
+                if kind == "factor":
+                    mt, _ = oracle.adamw4_factor_step(w_ref, gn, st_ref, hp, t, want_moments=True)
+                    assert compare(download(st), st_ref, w.cpu().numpy(), w_ref, mt, tag) == 0
+                    # carry the oracle's values forward (in place: the plan refers to these buffers)
+                    st.v_row.copy_(to_dev(st_ref.v_row))
+                    st.v_col.copy_(to_dev(st_ref.v_col))
+                    w.copy_(to_dev(w_ref))
+                elif kind == "b128":
+                    mt, vt = oracle.adamw4_b128_step(w_ref, gn, st_ref, hp, t, want_moments=True)
+                    assert compare_b128(download_b128(st), st_ref, w.cpu().numpy(), w_ref, mt, vt, tag) == 0
+                else:
+                    oracle.adamw32_step(w_ref, gn, st_ref[0], st_ref[1], hp, t)
+                    np.testing.assert_array_equal(st[0].cpu().numpy(), st_ref[0], err_msg=tag)
+                    np.testing.assert_allclose(w.cpu().numpy(), w_ref, rtol=PARAM_RTOL, atol=PARAM_ATOL, err_msg=tag)
+        lpmm.lpmm_adamw4_plan_release(plan)
+    finally:
+        for k in env:
+            os.environ.pop(k, None)
+
+
+def test_plan_rejects_rank1_and_factorized_tensors_together():
+    lpmm.ensure_init(4096)
+    w, g = torch.zeros(64 * 128, device=DEV), torch.zeros(64 * 128, device=DEV)
+    d1 = lpmm.make_desc(w, g, lpmm.new_state(64, 128, DEV))
+    d2 = lpmm.make_desc(w, g, lpmm.new_state_factor(64, 128, DEV))
+    assert lpmm.lpmm_adamw4_plan_bytes([d1, d2]) == 0
+    assert lpmm.lpmm_adamw4_plan_bytes([d2]) > 0
