@@ -222,6 +222,83 @@ def test_config5_flattened_block_wise_second_moment_plan():
     lpmm.lpmm_adamw4_plan_release(plan)
 
 
+def _oracle_step_factor(job):
+    w_ref, st_ref, g, t = job
+    return oracle.adamw4_factor_step(w_ref, g, st_ref, HP, t, want_moments=True)
+
+
+def test_config5_factorized_second_moment_plan():
+    """The 7B-shaped set as "4-bit Factor" (Sec. 4.3): one plan, the launch configuration bench.py times for
+    this variant.  One tensor of every layer shape is compared element by element; on a spread of tensors the
+    statistics are checked against torch's fp64 row / column sums of the gradient that was fed, and the first
+    moment through its block invariants."""
+    from test_gpu_factor import STAT_RTOL, compare as compare_factor, download as download_factor
+    config, seed, steps = "c5_llama_7b", 26, 2
+    specs = workloads.param_set(config)
+    sampled = {"l0.q": None, "l0.gate": None, "l0.down": None}
+    spread = lambda sp: sp.quantized and (sp.name in ("embed", "lm_head") or sp.name.startswith(("l0.", "l17.", "l31.")))
+    lpmm.ensure_init(65536)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(seed)
+    dev_t, descs = [], []
+    for tid, sp in enumerate(specs):
+        if sp.name in sampled:
+            w_ref = workloads.weights(seed, tid, sp.rows, sp.cols).reshape(-1)
+            sampled[sp.name] = (tid, sp, w_ref, oracle.state_zero_factor(sp.rows, sp.cols))
+            w = to_dev(w_ref.copy())
+        else:
+            w = torch.randn(sp.numel, generator=gen, device=DEV) * 0.02
+        g = torch.empty(sp.numel, dtype=torch.bfloat16, device=DEV)
+        if sp.quantized:
+            st = lpmm.new_state_factor(sp.rows, sp.cols, DEV)
+            descs.append(lpmm.make_desc(w, g, st))
+        else:
+            st = (torch.zeros(sp.numel, device=DEV), torch.zeros(sp.numel, device=DEV))
+            descs.append(lpmm.make_desc(w, g, st, sp.rows, sp.cols))
+        dev_t.append((sp, w, g, st))
+    plan = lpmm.new_plan(descs, 1, DEV)
+    b2 = float(np.float32(HP.beta2))
+    for t in range(1, steps + 1):
+        host_g = {}
+        for name, (tid, sp, w_ref, st_ref) in sampled.items():
+            host_g[name] = workloads.grads(seed, tid, t, sp.rows, sp.cols, "col_lognormal", True).reshape(-1)
+        want = {}
+        for sp, w, g, st in dev_t:
+            if sp.name in sampled:
+                g.copy_(to_dev(host_g[sp.name], True))
+            else:
+                sigma = 1e-3 * torch.exp(torch.randn(sp.cols, generator=gen, device=DEV))
+                g.copy_((torch.randn(sp.rows, sp.cols, generator=gen, device=DEV) * sigma[None, :]).reshape(-1))
+            if spread(sp):
+                sq = g.view(sp.rows, sp.cols).double() ** 2
+                want[sp.name] = (b2 * st.v_row.double() + (1 - b2) * sq.sum(dim=1),
+                                 b2 * st.v_col.double() + (1 - b2) * sq.sum(dim=0))
+                del sq
+        lpmm.lpmm_adamw4_step_multi(plan, HP.lr, HP.beta1, HP.beta2, HP.eps, HP.weight_decay, t)
+        jobs = [(w_ref, st_ref, host_g[name], t) for name, (tid, sp, w_ref, st_ref) in sampled.items()]
+        moments = list(POOL.map(_oracle_step_factor, jobs))
+        torch.cuda.synchronize()
+        by_name = {sp.name: (w, st) for sp, w, g, st in dev_t}
+        for (name, (tid, sp, w_ref, st_ref)), (mt, _) in zip(sampled.items(), moments):
+            w, st = by_name[name]
+            assert compare_factor(download_factor(st), st_ref, w.cpu().numpy(), w_ref, mt, f"c5 factor {name} step {t}") == 0
+        for sp, w, g, st in dev_t:
+            if spread(sp):
+                r, c = want[sp.name]
+                torch.testing.assert_close(st.v_row.double(), r, rtol=STAT_RTOL, atol=0, msg=f"c5 factor {sp.name} step {t}: R")
+                torch.testing.assert_close(st.v_col.double(), c, rtol=STAT_RTOL, atol=0, msg=f"c5 factor {sp.name} step {t}: C")
+                assert bool(torch.isfinite(w).all()), f"c5 factor {sp.name}: parameters"
+    for sp, w, g, st in dev_t:
+        if spread(sp):
+            out = torch.empty(sp.numel, dtype=torch.float32, device=DEV)
+            lpmm.lpmm_dequant_state(0, st.m_codes, st.m_blockscale, None, 1, sp.numel, out)
+            mb = out.view(-1, 128).abs().max(dim=1).values
+            assert bool((mb <= st.m_blockscale).all()) and bool((mb >= 0.8875 * st.m_blockscale * (1 - 1e-6)).all()), \
+                f"c5 factor {sp.name}: m block scales"
+            del out, mb
+    lpmm.lpmm_adamw4_plan_release(plan)
+
+
 def test_more_than_2_31_elements_block_wise():
     """64-bit indexing: a flat tensor of 2^31 + 2^20 + 130 elements.  Blocks are independent, so the
     oracle checks the first and the last stretch of the tensor on their own."""
