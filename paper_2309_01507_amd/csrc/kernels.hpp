@@ -58,6 +58,8 @@ struct Tensor4 {
     // log2 of the row spacing of pass 1 / pass 2: the 2^rs (2^rs2) rows that a group (a wave) takes in a
     // row are consecutive, and the groups (waves) that run side by side are 2^rs rows apart
     int rs, rs2;
+    int tot_slots;          // kFactor*: slots that each of the two float sums is spread over (1, 2, 4 or 8)
+    int pad_;
 };
 
 // The tensor table of a plan lives in device memory.  A pointer read from memory is a generic
@@ -79,7 +81,7 @@ struct Tensor4Table {
     float LPMM_AS_GLOBAL* c_new;
     unsigned int LPMM_AS_GLOBAL* counter;
     int64_t rows, cols, P;
-    int nb, gx, gy, rw, strips, n_wg, kind, strips2, rw2, n_wg2, rs, rs2;
+    int nb, gx, gy, rw, strips, n_wg, kind, strips2, rw2, n_wg2, rs, rs2, tot_slots, pad_;
 };
 static_assert(sizeof(Tensor4Table) == sizeof(Tensor4), "the table twin must mirror Tensor4");
 __device__ __forceinline__ Tensor4 from_table(const Tensor4Table& t) {
@@ -97,6 +99,7 @@ __device__ __forceinline__ Tensor4 from_table(const Tensor4Table& t) {
     a.rows = t.rows; a.cols = t.cols; a.P = t.P;
     a.nb = t.nb; a.gx = t.gx; a.gy = t.gy; a.rw = t.rw; a.strips = t.strips; a.n_wg = t.n_wg; a.kind = t.kind;
     a.strips2 = t.strips2; a.rw2 = t.rw2; a.n_wg2 = t.n_wg2; a.rs = t.rs; a.rs2 = t.rs2;
+    a.tot_slots = t.tot_slots; a.pad_ = 0;
     return a;
 }
 #else
@@ -572,7 +575,9 @@ __device__ __forceinline__ void pass1_fast_tile(const Tensor4& a, const Hyper& h
 // workgroups that call this for the tensor.
 constexpr int kTicketLanes = 32;
 constexpr int kTicketStride = 32;                                  // in 32-bit words: 128 bytes
-constexpr int kCounterWords = (1 + kTicketLanes) * kTicketStride;  // per tensor
+constexpr int kMaxTotSlots = 8;                                    // lines behind the ticket counters, for the
+                                                                   // factorized step's two float sums
+constexpr int kCounterWords = (1 + kTicketLanes + kMaxTotSlots) * kTicketStride;  // per tensor
 
 // dst[i] = src[i]; src[i] = 0 by one workgroup.  It runs alone at the end of a tensor's pass 2, so
 // what counts is latency: 16 loads per thread are in flight before the first store.
@@ -1150,7 +1155,14 @@ __device__ __forceinline__ void pass2_general_tile(const Tensor4& a, const Hyper
 // moment's codes and scales do not.
 // =====================================================================================================
 
-constexpr int kTotNew = 8, kTotOld = 9;     // words of the counter block that hold the two float sums
+// The two float sums live in the counter block, behind the ticket counters.  Each is spread over
+// a.tot_slots slots (a power of two; a workgroup adds to slot = its index modulo the count), one slot
+// per 128-byte line, because atomics on one line queue up behind each other even when their addresses
+// differ; readers add the slots in a fixed order.  A tensor stepped on its own has all its workgroups
+// arrive at once and takes 8 slots; in a plan the tensors' workgroups arrive spread out, one slot
+// serves, and the update pass has fewer lines to read.
+__device__ __forceinline__ int tot_new_word(int slot) { return (1 + kTicketLanes + slot) * kTicketStride; }      // sum of g^2
+__device__ __forceinline__ int tot_old_word(int slot) { return (1 + kTicketLanes + slot) * kTicketStride + 1; }  // sum of the old R
 
 __device__ __forceinline__ void atomic_add_f32(float* addr, float v) { (void)unsafeAtomicAdd(addr, v); }
 
@@ -1160,7 +1172,12 @@ __device__ __forceinline__ float stat_ema(const Hyper& h, float old, float sum_s
 }
 __device__ __forceinline__ float factor_inv_total(const Tensor4& a, const Hyper& h) {
     const float* tot = reinterpret_cast<const float*>(a.counter);
-    const float total = stat_ema(h, tot[kTotOld], tot[kTotNew]);
+    float sum_new = 0.0f, sum_old = 0.0f;
+    for (int k = 0; k < a.tot_slots; ++k) {
+        sum_new += tot[tot_new_word(k)];
+        sum_old += tot[tot_old_word(k)];
+    }
+    const float total = stat_ema(h, sum_old, sum_new);
     return total > 0.0f ? 1.0f / total : 0.0f;          // all-zero statistics: v_t = 0
 }
 
@@ -1244,12 +1261,12 @@ __device__ __forceinline__ void factor_stats_tile(const Tensor4& a, int wg, Lds&
         float part = 0.0f;
         for (int t = lane; t < n; t += 64) part += s.blk_scale[t];
         part = wave_sum(part);
-        if (lane == 0) atomic_add_f32(tot + kTotNew, part);
+        if (lane == 0) atomic_add_f32(tot + tot_new_word(wg & (a.tot_slots - 1)), part);
     } else if (wave == 1 && strip == 0) {   // the old statistics of the tile's rows, once per row
         float part = 0.0f;
         for (int t = lane; t < n; t += 64) part += a.r[row0 + t];
         part = wave_sum(part);
-        if (lane == 0) atomic_add_f32(tot + kTotOld, part);
+        if (lane == 0) atomic_add_f32(tot + tot_old_word(tile & (a.tot_slots - 1)), part);
     }
 }
 
@@ -1333,9 +1350,6 @@ __device__ __forceinline__ void factor_update_tile(const Tensor4& a, const Hyper
         float ct[4], csum[4];
         load4(a.c + geo.col0, ct);
         load4(a.c_new + geo.col0, csum);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) ct[e] = stat_ema(h, ct[e], csum[e]);
-        const float inv_total = factor_inv_total(a, h);
         const int n = geo.n_rows, rs = a.rs;
         const int row_g = geo.gyi << rs, hop = a.gy << rs, low = (1 << rs) - 1;
         auto row = [&](int k) { return row_g + (k & low) + (k >> rs) * hop; };
@@ -1344,6 +1358,9 @@ __device__ __forceinline__ void factor_update_tile(const Tensor4& a, const Hyper
         RowF<BF16> r1 = load_rowf<BF16>(tb, a, geo, row(1));
         RowF<BF16> r2;
         load_tables(s);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) ct[e] = stat_ema(h, ct[e], csum[e]);
+        const float inv_total = factor_inv_total(a, h);
         __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
         auto none = [] {};
         while (row(k + 2) < n) {
@@ -1395,10 +1412,10 @@ __device__ __forceinline__ void factor_publish_if_last(const Tensor4& a, const H
     if (!last_to_arrive(a, me, participants, s_last)) return;
     ema_and_clear(h, a.r, a.r_new, a.rows);
     ema_and_clear(h, a.c, a.c_new, a.cols);
-    if (threadIdx.x == 0) {
-        *a.counter = 0u;
-        a.counter[kTotNew] = 0u;
-        a.counter[kTotOld] = 0u;
+    if (threadIdx.x == 0) *a.counter = 0u;
+    if (int(threadIdx.x) < a.tot_slots) {
+        a.counter[tot_new_word(threadIdx.x)] = 0u;
+        a.counter[tot_old_word(threadIdx.x)] = 0u;
     }
 }
 
@@ -1439,8 +1456,8 @@ __device__ __forceinline__ void factor_stats_general_tile(const Tensor4& a, int 
     __syncthreads();
     if (threadIdx.x == 0) {
         float* tot = reinterpret_cast<float*>(a.counter);
-        atomic_add_f32(tot + kTotNew, (s.col[0] + s.col[1]) + (s.col[2] + s.col[3]));
-        atomic_add_f32(tot + kTotOld, (s.col[8] + s.col[9]) + (s.col[10] + s.col[11]));
+        atomic_add_f32(tot + tot_new_word(wg & (a.tot_slots - 1)), (s.col[0] + s.col[1]) + (s.col[2] + s.col[3]));
+        atomic_add_f32(tot + tot_old_word(wg & (a.tot_slots - 1)), (s.col[8] + s.col[9]) + (s.col[10] + s.col[11]));
     }
 }
 

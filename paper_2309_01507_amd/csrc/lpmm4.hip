@@ -304,7 +304,9 @@ int b128_step_impl(bool bf16, void* param, const void* grad, uint8_t* m_codes, f
 
 // Tiling of a tensor with a factorized second moment: the statistics pass is tiled like pass 2 and is the
 // step's first ("A") launch, the update pass is tiled like pass 1 and is the second ("B") one.
-void factor_geometry(Tensor4* a, int n_cu, int64_t rw_hint, int64_t rw2_hint, int grad_bytes, bool fast) {
+void factor_geometry(Tensor4* a, int n_cu, int64_t rw_hint, int64_t rw2_hint, int grad_bytes, bool fast,
+                     int tot_slots) {
+    a->tot_slots = tot_slots;
     if (fast) {
         fast_geometry(a, n_cu, rw_hint, rw2_hint, grad_bytes);
         if (a->rw2 > kMaxRowSlots) {          // row sums of a statistics tile are staged in LDS
@@ -352,7 +354,7 @@ int factor_step_impl(bool bf16, void* param, const void* grad, uint8_t* m_codes,
     t.cols = cols;
     t.P = rows * cols;
     const bool fast = fast_eligible(cols, v_col);
-    factor_geometry(&t, ctx->n_cu, 0, 0, bf16 ? 2 : 4, fast);
+    factor_geometry(&t, ctx->n_cu, 0, 0, bf16 ? 2 : 4, fast, kMaxTotSlots);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool rec = g_prof.on && g_prof.calls < g_prof.max_calls;
     const int64_t call = g_prof.calls;
@@ -797,7 +799,7 @@ int lpmm_adamw4_plan_build(const lpmm_tensor_desc* descs, int64_t n, int grad_dt
             fofs += round_up(d.cols, 64);
             t.counter = d_counters + i * kCounterWords;
             factor_geometry(&t, ctx->n_cu, rw_hint, rw2_hint, grad_dtype == LPMM_GRAD_BF16 ? 2 : 4,
-                            fast_eligible(d.cols, d.v_colmax));
+                            fast_eligible(d.cols, d.v_colmax), 1);
             host->factor = true;
         } else if (d.kind == LPMM_KIND_FP32) {
             if (!aligned(d.param, 4) || !aligned(d.m_state, 4) || !aligned(d.v_state, 4) || !aligned(d.grad, galign))

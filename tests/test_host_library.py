@@ -121,3 +121,36 @@ def test_block_wise_state_sizes_and_argument_errors():
     assert call(ptrs=[p] * 5 + [None]) == -1                    # null block-scale pointer
     assert call(ptrs=[p + 8] + [p] * 5) == -1                   # parameters must be 16-byte aligned
     assert call() in (-2, -3)                                   # well-formed, but no initialized GPU here
+
+
+def test_factorized_state_sizes_and_argument_errors():
+    assert lpmm.lpmm_adamw4_factor_state_sizes(32, 128) == [2048, 128, 128, 512]
+    assert lpmm.lpmm_adamw4_factor_state_sizes(3, 43) == [65, 8, 12, 172]      # 129 elements: odd, 2 blocks
+    L = lpmm.lib()
+    sizes = (ctypes.c_size_t * 4)()
+    bad = (ctypes.c_int64 * 2)(0, 5)
+    ok = (ctypes.c_int64 * 2)(2, 128)
+    assert L.lpmm_adamw4_factor_state_sizes(ctypes.addressof(bad), ctypes.addressof(sizes)) == -1
+    assert L.lpmm_adamw4_factor_state_sizes(ctypes.addressof(ok), None) == -1
+    assert L.lpmm_adamw4_factor_state_sizes(None, ctypes.addressof(sizes)) == -1
+    buf = ctypes.create_string_buffer(4096 + 256)
+    p = (ctypes.addressof(buf) + 255) // 256 * 256
+    ok_h = [1e-3, 0.9, 0.999, 1e-8, 0.01]
+
+    def call(ptrs=None, shape=ok, h=ok_h, step=1):
+        ptrs = ptrs or [p] * 6
+        return L.lpmm_adamw4_factor_step(*ptrs, ctypes.addressof(shape) if shape is not None else None,
+                                         *[ctypes.c_float(x) for x in h], step, None)
+
+    assert call(step=0) == -1
+    assert call(shape=bad) == -1
+    assert call(shape=None) == -1
+    assert call(h=[1e-3, 1.0, 0.999, 1e-8, 0.01]) == -1
+    assert call(h=[-1e-3, 0.9, 0.999, 1e-8, 0.01]) == -1
+    assert call(ptrs=[p] * 4 + [None, p]) == -1                 # null row statistics
+    assert call(ptrs=[p, p + 8] + [p] * 4) == -1                # the gradient must be 16-byte aligned
+    assert call() in (-2, -3)                                   # well-formed, but no initialized GPU here
+    d = lpmm.TensorDesc(p, p, p, p, None, p, p, 2, 128, lpmm.KIND_4BIT_FACTOR, 0)
+    r1 = lpmm.TensorDesc(p, p, p, p, p, p, p, 2, 128, lpmm.KIND_4BIT, 0)
+    assert lpmm.lpmm_adamw4_plan_bytes([d]) > 0
+    assert lpmm.lpmm_adamw4_plan_bytes([d, r1]) == 0            # two optimizers in one plan
