@@ -62,6 +62,12 @@ def lib() -> ctypes.CDLL:
         L.oracle_adamw4_b128_step.argtypes = [f32p, f32p, u8p, f32p, u8p, f32p, i64,
                                               cf, cf, cf, cf, cf, i64, f32p, f32p]
         L.oracle_state_zero_b128.argtypes = [u8p, f32p, u8p, f32p, i64]
+        i64p = ctypes.POINTER(ctypes.c_int64)
+        L.oracle_quant_v_nd.argtypes = [f32p, i64p, ctypes.c_int, u8p, f32p]
+        L.oracle_dequant_v_nd.argtypes = [u8p, f32p, i64p, ctypes.c_int, f32p]
+        L.oracle_adamw4_nd_step.argtypes = [f32p, f32p, u8p, f32p, u8p, f32p, i64p, ctypes.c_int,
+                                            cf, cf, cf, cf, cf, i64, f32p, f32p]
+        L.oracle_state_zero_nd.argtypes = [u8p, f32p, u8p, f32p, i64p, ctypes.c_int]
         L.oracle_adamw4_factor_step.argtypes = [f32p, f32p, u8p, f32p, f32p, f32p, i64, i64,
                                                 cf, cf, cf, cf, cf, i64, f32p, f32p]
         L.oracle_state_zero_factor.argtypes = [u8p, f32p, f32p, f32p, i64, i64]
@@ -70,7 +76,8 @@ def lib() -> ctypes.CDLL:
                      "oracle_dequant_m", "oracle_quant_v", "oracle_dequant_v",
                      "oracle_adamw32_step", "oracle_adamw4_step", "oracle_state_zero",
                      "oracle_quant_v_block", "oracle_dequant_v_block", "oracle_adamw4_b128_step",
-                     "oracle_state_zero_b128", "oracle_adamw4_factor_step", "oracle_state_zero_factor"):
+                     "oracle_state_zero_b128", "oracle_adamw4_factor_step", "oracle_state_zero_factor",
+                     "oracle_quant_v_nd", "oracle_dequant_v_nd", "oracle_adamw4_nd_step", "oracle_state_zero_nd"):
             getattr(L, name).restype = None
         _lib = L
     return _lib
@@ -314,4 +321,65 @@ def adamw4_factor_step(w: np.ndarray, g: np.ndarray, st: StateFactor, hp: Hyper,
                                     _f32(st.v_col), st.rows, st.cols, hp.lr, hp.beta1, hp.beta2, hp.eps,
                                     hp.weight_decay, t, _f32(mt) if want_moments else null,
                                     _f32(vt) if want_moments else null)
+    return mt, vt
+
+
+# ---- rank-1 normalization of tensors with any number of dimensions (App. F Alg. 4) ----------------------
+
+def _dims(shape):
+    return (ctypes.c_int64 * len(shape))(*[int(d) for d in shape])
+
+
+def quant_v_nd(x: np.ndarray):
+    """x: float32 array with p >= 1 dimensions, >= 0.  Returns (codes, stats); stats = the p statistics vectors
+    one after the other."""
+    x = np.ascontiguousarray(x, np.float32)
+    codes = np.zeros(codes_bytes(x.size), np.uint8)
+    stats = np.zeros(sum(x.shape), np.float32)
+    lib().oracle_quant_v_nd(_f32(x), _dims(x.shape), x.ndim, _u8(codes), _f32(stats))
+    return codes, stats
+
+
+def dequant_v_nd(codes: np.ndarray, stats: np.ndarray, shape) -> np.ndarray:
+    out = np.empty(int(np.prod(shape)), np.float32)
+    lib().oracle_dequant_v_nd(_u8(codes), _f32(stats), _dims(shape), len(shape), _f32(out))
+    return out.reshape(shape)
+
+
+@dataclass
+class StateND:
+    """Compressed state of a tensor with p dimensions (rank-1 second moment in its general form)."""
+    shape: tuple
+    m_codes: np.ndarray
+    m_scales: np.ndarray
+    v_codes: np.ndarray
+    v_stats: np.ndarray
+
+    def copy(self) -> "StateND":
+        return StateND(self.shape, self.m_codes.copy(), self.m_scales.copy(), self.v_codes.copy(),
+                       self.v_stats.copy())
+
+
+def state_zero_nd(shape) -> StateND:
+    shape = tuple(int(d) for d in shape)
+    P = int(np.prod(shape))
+    st = StateND(shape, np.zeros(codes_bytes(P), np.uint8), np.zeros(n_blocks(P), np.float32),
+                 np.zeros(codes_bytes(P), np.uint8), np.ones(sum(shape), np.float32))
+    lib().oracle_state_zero_nd(_u8(st.m_codes), _f32(st.m_scales), _u8(st.v_codes), _f32(st.v_stats),
+                               _dims(shape), len(shape))
+    return st
+
+
+def adamw4_nd_step(w: np.ndarray, g: np.ndarray, st: StateND, hp: Hyper, t: int, want_moments=False):
+    P = int(np.prod(st.shape))
+    assert w.size == P == g.size
+    mt = vt = None
+    null = ctypes.POINTER(ctypes.c_float)()
+    if want_moments:
+        mt = np.empty(P, np.float32)
+        vt = np.empty(P, np.float32)
+    lib().oracle_adamw4_nd_step(_f32(w), _f32(g), _u8(st.m_codes), _f32(st.m_scales), _u8(st.v_codes),
+                                _f32(st.v_stats), _dims(st.shape), len(st.shape), hp.lr, hp.beta1, hp.beta2,
+                                hp.eps, hp.weight_decay, t, _f32(mt) if want_moments else null,
+                                _f32(vt) if want_moments else null)
     return mt, vt

@@ -18,6 +18,9 @@
 //     block-wise normalization with block size 128 is used for the second moment instead (the
 //     mapping stays the Linear one).  App. C.1 (LLaMA): FSDP packs parameters into 1-dimensional
 //     arrays, so that run used this form for every tensor.  Functions *_v_block / *_b128_*.
+//   * App. F Alg. 4: rank-1 normalization of a tensor with p dimensions: one statistic per index of
+//     every dimension (the maximum of |x| over all other indices), an element's scale is the minimum
+//     of its p statistics.  Functions *_v_nd / *_nd_*.  (The second moment is >= 0, so |x| = x.)
 //   * Sec. 4.3 and Sec. 5 ("4-bit Factor"): for tensors with two dimensions the second moment is
 //     not stored per element but factorized the way the cited Adafactor method does it: one
 //     statistic per row and one per column, v_ij reconstructed as row_i * col_j / sum(row).  The
@@ -210,6 +213,57 @@ void dequant_v(const uint8_t* codes, const float* r, const float* c, int64_t row
 }
 
 // ---------------------------------------------------------------------------------------------
+// Second moment of a tensor with p >= 1 dimensions: rank-1 normalization in its general form
+// (App. F Alg. 4) + Linear map.  dims[0..p) is the shape (row-major: the last index runs fastest),
+// stats holds mu_1 (dims[0] floats), then mu_2 (dims[1] floats), ... one after the other.
+// ---------------------------------------------------------------------------------------------
+
+// the p indices of flat element e
+void unravel(int64_t e, const int64_t* dims, int p, int64_t* idx) {
+    for (int r = p - 1; r >= 0; --r) {
+        idx[r] = e % dims[r];
+        e /= dims[r];
+    }
+}
+
+void quant_v_nd(const float* x, const int64_t* dims, int p, uint8_t* codes, float* stats) {
+    const float* T = tables().lin;
+    int64_t P = 1, n_stats = 0;
+    std::vector<int64_t> first(static_cast<size_t>(p));          // where mu_r starts inside stats
+    for (int r = 0; r < p; ++r) { first[size_t(r)] = n_stats; n_stats += dims[r]; P *= dims[r]; }
+    std::memset(codes, 0, size_t((P + 1) / 2));
+    for (int64_t k = 0; k < n_stats; ++k) stats[k] = 0.0f;
+    std::vector<int64_t> idx(static_cast<size_t>(p));
+    for (int64_t e = 0; e < P; ++e) {                            // Alg. 4, first loop: the statistics
+        unravel(e, dims, p, idx.data());
+        for (int r = 0; r < p; ++r) {
+            float& mu = stats[first[size_t(r)] + idx[size_t(r)]];
+            mu = std::max(mu, x[e]);
+        }
+    }
+    for (int64_t e = 0; e < P; ++e) {                            // second loop: M = min over the dimensions
+        unravel(e, dims, p, idx.data());
+        float M = stats[first[0] + idx[0]];
+        for (int r = 1; r < p; ++r) M = std::min(M, stats[first[size_t(r)] + idx[size_t(r)]]);
+        const float n = (M == 0.0f) ? 0.0f : x[e] / M;
+        put_code(codes, e, nearest_code(T, kCodes, n));
+    }
+}
+
+void dequant_v_nd(const uint8_t* codes, const float* stats, const int64_t* dims, int p, float* out) {
+    const float* T = tables().lin;
+    int64_t P = 1, n_stats = 0;
+    std::vector<int64_t> first(static_cast<size_t>(p)), idx(static_cast<size_t>(p));
+    for (int r = 0; r < p; ++r) { first[size_t(r)] = n_stats; n_stats += dims[r]; P *= dims[r]; }
+    for (int64_t e = 0; e < P; ++e) {
+        unravel(e, dims, p, idx.data());
+        float M = stats[first[0] + idx[0]];
+        for (int r = 1; r < p; ++r) M = std::min(M, stats[first[size_t(r)] + idx[size_t(r)]]);
+        out[e] = T[get_code(codes, e)] * M;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Second moment of 1-dimensional (or flattened) tensors: B128 normalization (Sec. 2.2 block-wise
 // normalization with the block size of Sec. 3, chosen by Sec. 4.2 for this case) + Linear map.
 // The moment is non-negative, so the block's scale max|x| is max x.
@@ -363,6 +417,37 @@ void oracle_state_zero_b128(uint8_t* m_codes, float* m_scales, uint8_t* v_codes,
     std::vector<float> z(static_cast<size_t>(P), 0.0f);
     quant_m(z.data(), P, m_codes, m_scales);
     quant_v_block(z.data(), P, v_codes, v_scales);
+}
+
+// One step of 4-bit AdamW on a tensor with p dimensions (Alg. 3 with the rank-1 normalization of
+// App. F Alg. 4 for the second moment).  v_stats: the p statistics vectors one after the other.
+void oracle_quant_v_nd(const float* x, const int64_t* dims, int p, uint8_t* codes, float* stats) {
+    quant_v_nd(x, dims, p, codes, stats);
+}
+void oracle_dequant_v_nd(const uint8_t* codes, const float* stats, const int64_t* dims, int p, float* out) {
+    dequant_v_nd(codes, stats, dims, p, out);
+}
+void oracle_adamw4_nd_step(float* w, const float* g, uint8_t* m_codes, float* m_scales, uint8_t* v_codes,
+                           float* v_stats, const int64_t* dims, int p, float lr, float beta1, float beta2,
+                           float eps, float wd, int64_t t, float* m_t_out, float* v_t_out) {
+    int64_t P = 1;
+    for (int r = 0; r < p; ++r) P *= dims[r];
+    std::vector<float> m(static_cast<size_t>(P)), v(static_cast<size_t>(P));
+    dequant_m(m_codes, m_scales, P, m.data());                    // Alg. 3: decompress
+    dequant_v_nd(v_codes, v_stats, dims, p, v.data());
+    adamw_rule(w, m.data(), v.data(), g, P, lr, beta1, beta2, eps, wd, t);   // Eq. 1
+    if (m_t_out) std::memcpy(m_t_out, m.data(), sizeof(float) * size_t(P));
+    if (v_t_out) std::memcpy(v_t_out, v.data(), sizeof(float) * size_t(P));
+    quant_m(m.data(), P, m_codes, m_scales);                      // Alg. 3: compress
+    quant_v_nd(v.data(), dims, p, v_codes, v_stats);
+}
+void oracle_state_zero_nd(uint8_t* m_codes, float* m_scales, uint8_t* v_codes, float* v_stats,
+                          const int64_t* dims, int p) {
+    int64_t P = 1;
+    for (int r = 0; r < p; ++r) P *= dims[r];
+    std::vector<float> z(static_cast<size_t>(P), 0.0f);
+    quant_m(z.data(), P, m_codes, m_scales);
+    quant_v_nd(z.data(), dims, p, v_codes, v_stats);
 }
 
 // One step of "4-bit Factor" on one rows x cols tensor (Sec. 4.3; Alg. 3 with the second moment kept
