@@ -178,6 +178,43 @@ int lpmm_adamw4_factor_step_bf16g(void* param, const void* grad, uint8_t* m_code
                                   float beta1, float beta2, float eps, float weight_decay, int64_t step,
                                   void* stream);
 
+/* ---- rank-1 normalization for tensors with more than two dimensions ------------------------------------
+ * App. F Alg. 4: a tensor of shape d_1 x ... x d_p keeps one statistic per index of every dimension
+ * (the maximum of the second moment over all other indices); an element's scale is the minimum of
+ * its p statistics.  The kernels see the tensor as a matrix of d_1 rows and d_2 * ... * d_p columns.
+ * State (2 <= ndim <= 8, row-major, last index fastest):
+ *   m_codes, m_blockscale, v_codes   as for lpmm_adamw4_step, with rows*cols = d_1 * ... * d_p
+ *   v_row  float[d_1]                         statistics of dimension 1
+ *   v_col  float[cols + d_2 + ... + d_p]      first the cols = d_2*...*d_p column scales (for each column the
+ *                                             minimum of the other dimensions' statistics at its index; derived,
+ *                                             kept so that the step need not rebuild them), then the statistics
+ *                                             of dimensions 2..p one after the other
+ * zero state: m codes 7, everything else 0.  (v_codes, v_row, v_col) decompress with
+ * lpmm_dequant_state(which = 1, shape = {d_1, cols}).  With ndim = 2 the results equal lpmm_adamw4_step's.
+ * Four kernels are enqueued (the two passes, and two small ones between them that turn column maxima into
+ * the new statistics and column scales).  Needs lpmm_adamw4_init with d_1 + cols + d_2 + ... + d_p (+ 128)
+ * floats of workspace, i.e. that number passed as max_rows_plus_cols.  Alignment as lpmm_adamw4_step. */
+
+/* sizes[5] (host, out): bytes of m_codes, m_blockscale, v_codes, v_row, v_col. */
+int lpmm_adamw4_nd_state_sizes(const int64_t* dims, int ndim, size_t sizes[5]);
+
+/* Writes the zero state on `stream`. */
+int lpmm_adamw4_nd_state_zero(uint8_t* m_codes, float* m_blockscale, uint8_t* v_codes, float* v_row,
+                              float* v_col, const int64_t* dims, int ndim, void* stream);
+
+/* One AdamW step (App. E Alg. 3), in place on param and the five state buffers; grad is read only.
+ * dims: host array of ndim sizes.  Hyper-parameters and `step` as lpmm_adamw4_step. */
+int lpmm_adamw4_nd_step(void* param, const void* grad, uint8_t* m_codes, float* m_blockscale,
+                        uint8_t* v_codes, float* v_row, float* v_col, const int64_t* dims, int ndim,
+                        float lr, float beta1, float beta2, float eps, float weight_decay, int64_t step,
+                        void* stream);
+
+/* Same step with a bf16 gradient buffer. */
+int lpmm_adamw4_nd_step_bf16g(void* param, const void* grad, uint8_t* m_codes, float* m_blockscale,
+                              uint8_t* v_codes, float* v_row, float* v_col, const int64_t* dims, int ndim,
+                              float lr, float beta1, float beta2, float eps, float weight_decay,
+                              int64_t step, void* stream);
+
 /* AdamW step with uncompressed fp32 states, for tensors that are not quantized (App. C.1: size
  * <= 4096, biases and normalization vectors): Alg. 3 with compress = decompress = identity.
  * param, m, v: float[numel] in place; grad: float or bf16 [numel] per grad_dtype. */

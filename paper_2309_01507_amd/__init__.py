@@ -13,4 +13,6 @@ from .binding import (  # noqa: F401
     lpmm_adamw4_b128_step, lpmm_adamw4_b128_step_bf16g,
     StateFactor, new_state_factor, lpmm_adamw4_factor_state_sizes, lpmm_adamw4_factor_state_zero,
     lpmm_adamw4_factor_step, lpmm_adamw4_factor_step_bf16g, KIND_4BIT_FACTOR,
+    StateND, new_state_nd, lpmm_adamw4_nd_state_sizes, lpmm_adamw4_nd_state_zero, lpmm_adamw4_nd_step,
+    lpmm_adamw4_nd_step_bf16g,
 )

@@ -77,6 +77,11 @@ def lib() -> ctypes.CDLL:
         b128_args = [_VP] * 6 + [_I64] + [_F] * 5 + [_I64, _VP]
         L.lpmm_adamw4_b128_step.argtypes = b128_args
         L.lpmm_adamw4_b128_step_bf16g.argtypes = b128_args
+        L.lpmm_adamw4_nd_state_sizes.argtypes = [_VP, ctypes.c_int, _VP]
+        L.lpmm_adamw4_nd_state_zero.argtypes = [_VP] * 5 + [_VP, ctypes.c_int, _VP]
+        nd_args = [_VP] * 7 + [_VP, ctypes.c_int] + [_F] * 5 + [_I64, _VP]
+        L.lpmm_adamw4_nd_step.argtypes = nd_args
+        L.lpmm_adamw4_nd_step_bf16g.argtypes = nd_args
         L.lpmm_adamw4_factor_state_sizes.argtypes = [_VP, _VP]
         L.lpmm_adamw4_factor_state_zero.argtypes = [_VP] * 4 + [_VP, _VP]
         factor_args = [_VP] * 6 + [_VP] + [_F] * 5 + [_I64, _VP]
@@ -348,6 +353,70 @@ def lpmm_adamw4_factor_step_bf16g(param, grad, st: StateFactor, lr, beta1, beta2
                                   stream=None):
     _factor_step("lpmm_adamw4_factor_step_bf16g", param, grad, st, lr, beta1, beta2, eps, weight_decay, step,
                  stream)
+
+
+# ---- rank-1 second moment of tensors with more than two dimensions ----------------------------------------
+
+@dataclass
+class StateND:
+    """The five device buffers of the state of a tensor with 2..8 dimensions (see lpmm4.h for v_col's layout)."""
+    shape: tuple
+    m_codes: "object"
+    m_blockscale: "object"
+    v_codes: "object"
+    v_row: "object"
+    v_col: "object"
+
+
+def _dims(shape):
+    return (ctypes.c_int64 * len(shape))(*[int(d) for d in shape])
+
+
+def lpmm_adamw4_nd_state_sizes(shape):
+    sizes = (ctypes.c_size_t * 5)()
+    dims = _dims(shape)
+    _check(lib().lpmm_adamw4_nd_state_sizes(ctypes.addressof(dims), len(shape), ctypes.addressof(sizes)),
+           "lpmm_adamw4_nd_state_sizes")
+    return [int(s) for s in sizes]
+
+
+def lpmm_adamw4_nd_state_zero(st: StateND, stream=None) -> None:
+    dims = _dims(st.shape)
+    _check(lib().lpmm_adamw4_nd_state_zero(_ptr(st.m_codes), _ptr(st.m_blockscale), _ptr(st.v_codes), _ptr(st.v_row),
+                                           _ptr(st.v_col), ctypes.addressof(dims), len(st.shape), _stream(stream)),
+           "lpmm_adamw4_nd_state_zero")
+
+
+def new_state_nd(shape, device="cuda") -> StateND:
+    """Allocate (torch) and zero (library) the state of a tensor with 2..8 dimensions."""
+    import torch
+    shape = tuple(int(d) for d in shape)
+    sz = lpmm_adamw4_nd_state_sizes(shape)
+    pad4 = lambda n: (n + 3) // 4 * 4
+    st = StateND(shape,
+                 torch.empty(pad4(sz[0]), dtype=torch.uint8, device=device)[:sz[0]],
+                 torch.empty(sz[1] // 4, dtype=torch.float32, device=device),
+                 torch.empty(pad4(sz[2]), dtype=torch.uint8, device=device)[:sz[2]],
+                 torch.empty(sz[3] // 4, dtype=torch.float32, device=device),
+                 torch.empty(sz[4] // 4, dtype=torch.float32, device=device))
+    lpmm_adamw4_nd_state_zero(st)
+    return st
+
+
+def _nd_step(fn_name, param, grad, st: StateND, lr, beta1, beta2, eps, weight_decay, step, stream):
+    fn = getattr(lib(), fn_name)
+    dims = _dims(st.shape)
+    _check(fn(_ptr(param), _ptr(grad), _ptr(st.m_codes), _ptr(st.m_blockscale), _ptr(st.v_codes), _ptr(st.v_row),
+              _ptr(st.v_col), ctypes.addressof(dims), len(st.shape), lr, beta1, beta2, eps, weight_decay, int(step),
+              _stream(stream)), fn_name)
+
+
+def lpmm_adamw4_nd_step(param, grad, st: StateND, lr, beta1, beta2, eps, weight_decay, step, stream=None):
+    _nd_step("lpmm_adamw4_nd_step", param, grad, st, lr, beta1, beta2, eps, weight_decay, step, stream)
+
+
+def lpmm_adamw4_nd_step_bf16g(param, grad, st: StateND, lr, beta1, beta2, eps, weight_decay, step, stream=None):
+    _nd_step("lpmm_adamw4_nd_step_bf16g", param, grad, st, lr, beta1, beta2, eps, weight_decay, step, stream)
 
 
 def lpmm_adamw32_step(param, grad, m, v, numel, grad_dtype, lr, beta1, beta2, eps, weight_decay, step,

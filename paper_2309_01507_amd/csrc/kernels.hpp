@@ -59,7 +59,8 @@ struct Tensor4 {
     // row are consecutive, and the groups (waves) that run side by side are 2^rs rows apart
     int rs, rs2;
     int tot_slots;          // kFactor*: slots that each of the two float sums is spread over (1, 2, 4 or 8)
-    int pad_;
+    int c_extra;            // floats behind c_new (and room behind c) that the publishing workgroup moves and clears
+                            // along with the column maxima (tensors with more than two dimensions)
 };
 
 // The tensor table of a plan lives in device memory.  A pointer read from memory is a generic
@@ -81,7 +82,7 @@ struct Tensor4Table {
     float LPMM_AS_GLOBAL* c_new;
     unsigned int LPMM_AS_GLOBAL* counter;
     int64_t rows, cols, P;
-    int nb, gx, gy, rw, strips, n_wg, kind, strips2, rw2, n_wg2, rs, rs2, tot_slots, pad_;
+    int nb, gx, gy, rw, strips, n_wg, kind, strips2, rw2, n_wg2, rs, rs2, tot_slots, c_extra;
 };
 static_assert(sizeof(Tensor4Table) == sizeof(Tensor4), "the table twin must mirror Tensor4");
 __device__ __forceinline__ Tensor4 from_table(const Tensor4Table& t) {
@@ -99,7 +100,7 @@ __device__ __forceinline__ Tensor4 from_table(const Tensor4Table& t) {
     a.rows = t.rows; a.cols = t.cols; a.P = t.P;
     a.nb = t.nb; a.gx = t.gx; a.gy = t.gy; a.rw = t.rw; a.strips = t.strips; a.n_wg = t.n_wg; a.kind = t.kind;
     a.strips2 = t.strips2; a.rw2 = t.rw2; a.n_wg2 = t.n_wg2; a.rs = t.rs; a.rs2 = t.rs2;
-    a.tot_slots = t.tot_slots; a.pad_ = 0;
+    a.tot_slots = t.tot_slots; a.c_extra = t.c_extra;
     return a;
 }
 #else
@@ -624,7 +625,7 @@ __device__ __forceinline__ void publish_if_last(const Tensor4& a, unsigned int m
                                                 int& s_last) {
     if (!last_to_arrive(a, me, participants, s_last)) return;
     move_and_clear(a.r, a.r_new, a.rows);
-    move_and_clear(a.c, a.c_new, a.cols);
+    move_and_clear(a.c, a.c_new, a.cols + a.c_extra);
     if (threadIdx.x == 0) *a.counter = 0u;
 }
 
@@ -1089,7 +1090,22 @@ __device__ __forceinline__ void pass1_general_tile(const Tensor4& a, const Hyper
             mt[e] = 0.0f;
         }
     }
-    if (io.nv) raise_max(a.r_new + run_row, run_max);
+    // The lane's last row usually is its neighbours' too (rows are contiguous runs of lanes): combine
+    // over the wave first, one atomic per row and wave.  (Atomics on one address, and on one 128-byte
+    // line, queue up behind each other.)  Lanes that returned above are the wave's highest.
+    {
+        const int lane = threadIdx.x & 63;
+        const uint64_t act = __ballot(true);
+        long long rr = io.nv ? (long long)run_row : -1ll - lane;
+        float rm = run_max;
+        for (int d = 1; d < 64; d <<= 1) {
+            const float om = __shfl_down(rm, d);
+            const long long orow = __shfl_down(rr, d);
+            if (lane + d < 64 && ((act >> (lane + d)) & 1) && orow == rr) rm = fmaxf(rm, om);
+        }
+        const long long prev = __shfl_up(rr, 1);
+        if (io.nv && (lane == 0 || prev != rr)) raise_max(a.r_new + rr, rm);
+    }
 
     const float s_new = row16_allmax(amax);
     uint32_t mq_new = 0;
@@ -1691,6 +1707,64 @@ __global__ __launch_bounds__(kThreads) void phase_kernel(const Phase ph, const H
             pass1_general_tile<BF16>(a, h, wg, s);
         }
     }
+}
+
+// =====================================================================================================
+// Rank-1 normalization of a tensor with more than two dimensions (App. F Alg. 4): one statistic per
+// index of every dimension, an element's scale is the minimum of its statistics.  Seen as a matrix of
+// d_1 rows and d_2 * ... * d_p columns, the scale is min(mu_1[i], colscale[col]) with colscale[col] =
+// min over the other dimensions of their statistic at the column's index: the two passes of the
+// matrix step run unchanged on (mu_1, colscale), and two small kernels between them turn the column
+// maxima of v_t into the new statistics (reduce) and those into the new colscale (expand).
+// =====================================================================================================
+
+constexpr int kMaxInnerDims = 7;
+
+struct InnerDims {                  // dimensions 2..p
+    int n;
+    int64_t d[kMaxInnerDims];       // sizes
+    int64_t first[kMaxInnerDims];   // where each dimension's statistics start in the statistics array
+};
+
+// One workgroup per statistic: mu_new[first[r] + j] = max of colmax over the columns whose index in inner
+// dimension r is j (cols / d_r of them: col = a * d_r * inner + j * inner + b).  No atomics: with a small
+// dimension (a 3 x 3 kernel) thousands of columns share a statistic, and atomics on one address queue up.
+__global__ __launch_bounds__(kThreads) void nd_reduce_kernel(const float* colmax, float* mu_new, int64_t cols,
+                                                             const InnerDims dm) {
+    __shared__ float s_part[kThreads / 64];
+    int r = 0;
+    int64_t j = blockIdx.x;                 // which statistic: dimension r, index j
+    while (r < dm.n - 1 && j >= dm.d[r]) { j -= dm.d[r]; ++r; }
+    int64_t inner = 1;
+    for (int q = r + 1; q < dm.n; ++q) inner *= dm.d[q];
+    const int64_t count = cols / dm.d[r];
+    float m = 0.0f;
+    for (int64_t k = threadIdx.x; k < count; k += kThreads) {
+        const int64_t a = k / inner, b = k - a * inner;
+        m = fmaxf(m, colmax[(a * dm.d[r] + j) * inner + b]);
+    }
+    m = row16_allmax(m);                    // values are >= +0
+    m = fmaxf(m, __shfl_xor(m, 16));
+    m = fmaxf(m, __shfl_xor(m, 32));
+    if ((threadIdx.x & 63) == 0) s_part[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) mu_new[dm.first[r] + j] = fmaxf(fmaxf(s_part[0], s_part[1]), fmaxf(s_part[2], s_part[3]));
+}
+
+// colscale[col] = min over the inner dimensions of mu[first[r] + idx_r(col)]
+__global__ __launch_bounds__(kThreads) void nd_expand_kernel(const float* mu, float* colscale, int64_t cols,
+                                                             const InnerDims dm) {
+    const int64_t col = int64_t(blockIdx.x) * kThreads + threadIdx.x;
+    if (col >= cols) return;
+    int64_t rest = col;
+    float m = 0.0f;
+    for (int r = dm.n - 1; r >= 0; --r) {
+        const int64_t idx = rest % dm.d[r];
+        rest /= dm.d[r];
+        const float v = mu[dm.first[r] + idx];
+        m = (r == dm.n - 1) ? v : fminf(m, v);
+    }
+    colscale[col] = m;
 }
 
 // The same for a plan whose 2-dimensional tensors keep a factorized second moment: "A" work is the

@@ -302,6 +302,95 @@ int b128_step_impl(bool bf16, void* param, const void* grad, uint8_t* m_codes, f
     return LPMM_OK;
 }
 
+// Workgroups for `items` items at `per_thread` per thread.  Kernels that are not grid-stride loops must
+// get the full count (the default cap is the largest grid HIP takes; 2^40 elements stay far below it).
+int grid_for(int64_t items, int64_t per_thread, int max_blocks = 0x7FFFFFFF) {
+    const int64_t threads = (items + per_thread - 1) / per_thread;
+    int64_t blocks = (threads + kThreads - 1) / kThreads;
+    if (blocks < 1) blocks = 1;
+    if (blocks > max_blocks) blocks = max_blocks;
+    return int(blocks);
+}
+
+// shape of a tensor with p >= 2 dimensions as the matrix the kernels see, plus its inner dimensions
+int nd_shape(const int64_t* dims, int ndim, int64_t* rows, int64_t* cols, int64_t* ext, InnerDims* dm) {
+    if (!dims || ndim < 2 || ndim > 1 + kMaxInnerDims) return LPMM_EINVAL;
+    int64_t c = 1, e = 0;
+    InnerDims d{};
+    d.n = ndim - 1;
+    for (int r = 1; r < ndim; ++r) {
+        if (dims[r] < 1 || dims[r] > (int64_t(1) << 31)) return LPMM_EINVAL;
+        if (c > (int64_t(1) << 31) / dims[r]) return LPMM_EINVAL;
+        c *= dims[r];
+        d.d[r - 1] = dims[r];
+        d.first[r - 1] = e;
+        e += dims[r];
+    }
+    const int64_t shape[2] = {dims[0], c};
+    const int rc = check_shape(shape, rows, cols);
+    if (rc) return rc;
+    *ext = e;
+    if (dm) *dm = d;
+    return LPMM_OK;
+}
+
+int nd_step_impl(bool bf16, void* param, const void* grad, uint8_t* m_codes, float* m_blockscale,
+                 uint8_t* v_codes, float* v_row, float* v_col, const int64_t* dims, int ndim, float lr,
+                 float beta1, float beta2, float eps, float wd, int64_t step, void* stream) {
+    int64_t rows, cols, ext;
+    InnerDims dm;
+    int rc = nd_shape(dims, ndim, &rows, &cols, &ext, &dm);
+    if (rc) return rc;
+    if (!param || !grad || !m_codes || !m_blockscale || !v_codes || !v_row || !v_col) return LPMM_EINVAL;
+    if (!aligned(param, 16) || !aligned(grad, 16) || !aligned(m_codes, 4) || !aligned(v_codes, 4) ||
+        !aligned(m_blockscale, 4) || !aligned(v_row, 4) || !aligned(v_col, 4))
+        return LPMM_EINVAL;
+    Hyper h;
+    rc = make_hyper(lr, beta1, beta2, eps, wd, step, &h);
+    if (rc) return rc;
+    DeviceCtx* ctx;
+    rc = current_ctx(&ctx);
+    if (rc) return rc;
+    const int64_t rows_pad = round_up(rows, 64);
+    if (rows_pad + round_up(cols + ext, 64) > ctx->cap_floats) return LPMM_EWORKSPACE;
+    Tensor4 t{};
+    t.p = static_cast<float*>(param);
+    t.g = grad;
+    t.mq = reinterpret_cast<uint32_t*>(m_codes);
+    t.ms = m_blockscale;
+    t.vq = reinterpret_cast<uint32_t*>(v_codes);
+    t.r = v_row;
+    t.c = v_col;                          // [cols] column scales, then [ext] the inner dimensions' statistics
+    t.r_new = ctx->ws;
+    t.c_new = ctx->ws + rows_pad;         // [cols] column maxima of v_t, then [ext] the new statistics
+    t.c_extra = int(ext);
+    t.counter = ctx->counter;
+    t.rows = rows;
+    t.cols = cols;
+    t.P = rows * cols;
+    const bool fast = fast_eligible(cols, v_col);
+    t.kind = fast ? kQuantFast : kQuantGeneral;
+    if (fast) fast_geometry(&t, ctx->n_cu, 0, 0, bf16 ? 2 : 4);
+    else t.n_wg = t.n_wg2 = int((((t.P + 7) / 8) + kThreads - 1) / kThreads);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int grid = fast ? pad8(t.n_wg) : t.n_wg;
+    const int grid_cols = grid_for(cols, 1);
+#define LPMM_ND_LAUNCH(B)                                                                                         \
+    if (fast) hipLaunchKernelGGL(pass1_fast<B>, dim3(grid), dim3(kThreads), 0, s, t, h);                          \
+    else hipLaunchKernelGGL(pass1_general<B>, dim3(grid), dim3(kThreads), 0, s, t, h);                            \
+    LPMM_HIP(hipGetLastError());                                                                                  \
+    hipLaunchKernelGGL(nd_reduce_kernel, dim3(int(ext)), dim3(kThreads), 0, s, t.c_new, t.c_new + cols, cols, dm);  \
+    LPMM_HIP(hipGetLastError());                                                                                  \
+    hipLaunchKernelGGL(nd_expand_kernel, dim3(grid_cols), dim3(kThreads), 0, s, t.c_new + cols, t.c_new, cols, dm); \
+    LPMM_HIP(hipGetLastError());                                                                                  \
+    if (fast) hipLaunchKernelGGL(pass2_fast<B>, dim3(pad8(t.n_wg2)), dim3(kThreads), 0, s, t, h);                 \
+    else hipLaunchKernelGGL(pass2_general<B>, dim3(grid), dim3(kThreads), 0, s, t, h);                            \
+    LPMM_HIP(hipGetLastError());
+    if (bf16) { LPMM_ND_LAUNCH(true) } else { LPMM_ND_LAUNCH(false) }
+#undef LPMM_ND_LAUNCH
+    return LPMM_OK;
+}
+
 // Tiling of a tensor with a factorized second moment: the statistics pass is tiled like pass 2 and is the
 // step's first ("A") launch, the update pass is tiled like pass 1 and is the second ("B") one.
 void factor_geometry(Tensor4* a, int n_cu, int64_t rw_hint, int64_t rw2_hint, int grad_bytes, bool fast,
@@ -374,16 +463,6 @@ int factor_step_impl(bool bf16, void* param, const void* grad, uint8_t* m_codes,
         g_prof.calls = call + 1;
     }
     return LPMM_OK;
-}
-
-// Workgroups for `items` items at `per_thread` per thread.  Kernels that are not grid-stride loops must
-// get the full count (the default cap is the largest grid HIP takes; 2^40 elements stay far below it).
-int grid_for(int64_t items, int64_t per_thread, int max_blocks = 0x7FFFFFFF) {
-    const int64_t threads = (items + per_thread - 1) / per_thread;
-    int64_t blocks = (threads + kThreads - 1) / kThreads;
-    if (blocks < 1) blocks = 1;
-    if (blocks > max_blocks) blocks = max_blocks;
-    return int(blocks);
 }
 
 // ---- multi-tensor plans ---------------------------------------------------------------------------
@@ -655,6 +734,52 @@ int lpmm_adamw4_factor_step_bf16g(void* param, const void* grad, uint8_t* m_code
                                   float beta2, float eps, float weight_decay, int64_t step, void* stream) {
     return factor_step_impl(true, param, grad, m_codes, m_blockscale, v_row, v_col, shape, lr, beta1, beta2,
                             eps, weight_decay, step, stream);
+}
+
+int lpmm_adamw4_nd_state_sizes(const int64_t* dims, int ndim, size_t sizes[5]) {
+    int64_t rows, cols, ext;
+    const int rc = nd_shape(dims, ndim, &rows, &cols, &ext, nullptr);
+    if (rc) return rc;
+    if (!sizes) return LPMM_EINVAL;
+    const int64_t P = rows * cols;
+    sizes[0] = size_t((P + 1) / 2);
+    sizes[1] = size_t((P + LPMM_BLOCK - 1) / LPMM_BLOCK) * sizeof(float);
+    sizes[2] = size_t((P + 1) / 2);
+    sizes[3] = size_t(rows) * sizeof(float);
+    sizes[4] = size_t(cols + ext) * sizeof(float);
+    return LPMM_OK;
+}
+
+int lpmm_adamw4_nd_state_zero(uint8_t* m_codes, float* m_blockscale, uint8_t* v_codes, float* v_row, float* v_col,
+                              const int64_t* dims, int ndim, void* stream) {
+    size_t sz[5];
+    const int rc = lpmm_adamw4_nd_state_sizes(dims, ndim, sz);
+    if (rc) return rc;
+    if (!m_codes || !m_blockscale || !v_codes || !v_row || !v_col) return LPMM_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int64_t P = 1;
+    for (int r = 0; r < ndim; ++r) P *= dims[r];
+    int r = fill(m_codes, int64_t(sz[0]), 0x77, (P & 1) ? int64_t(sz[0]) - 1 : -1, 0x07, s);
+    if (!r) r = fill(m_blockscale, int64_t(sz[1]), 0, -1, 0, s);
+    if (!r) r = fill(v_codes, int64_t(sz[2]), 0, -1, 0, s);
+    if (!r) r = fill(v_row, int64_t(sz[3]), 0, -1, 0, s);
+    if (!r) r = fill(v_col, int64_t(sz[4]), 0, -1, 0, s);
+    return r;
+}
+
+int lpmm_adamw4_nd_step(void* param, const void* grad, uint8_t* m_codes, float* m_blockscale, uint8_t* v_codes,
+                        float* v_row, float* v_col, const int64_t* dims, int ndim, float lr, float beta1,
+                        float beta2, float eps, float weight_decay, int64_t step, void* stream) {
+    return nd_step_impl(false, param, grad, m_codes, m_blockscale, v_codes, v_row, v_col, dims, ndim, lr, beta1,
+                        beta2, eps, weight_decay, step, stream);
+}
+
+int lpmm_adamw4_nd_step_bf16g(void* param, const void* grad, uint8_t* m_codes, float* m_blockscale,
+                              uint8_t* v_codes, float* v_row, float* v_col, const int64_t* dims, int ndim,
+                              float lr, float beta1, float beta2, float eps, float weight_decay, int64_t step,
+                              void* stream) {
+    return nd_step_impl(true, param, grad, m_codes, m_blockscale, v_codes, v_row, v_col, dims, ndim, lr, beta1,
+                        beta2, eps, weight_decay, step, stream);
 }
 
 int lpmm_adamw32_step(void* param, const void* grad, float* m, float* v, int64_t numel, int grad_dtype,

@@ -1,0 +1,167 @@
+"""GPU parity tests of the 4-bit AdamW step on tensors with more than two dimensions (rank-1 normalization in
+the general form of App. F Alg. 4) against the CPU oracle, element by element: codes, block scales and all
+statistics bit-exact, parameters within 1e-5 relative / 1e-7 absolute."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2309_01507_amd as lpmm
+import workloads
+from gpu_util import DEV, compare_step, download_state, gpu_step, to_dev
+
+pytestmark = pytest.mark.gpu
+HP = oracle.Hyper()
+
+
+@pytest.fixture(autouse=True)
+def _announce(request):
+    print(f"\n[gpu-test] {request.node.name}", flush=True)
+    yield
+    torch.cuda.synchronize()
+
+
+def _colscale(stats, shape):
+    """minimum over dimensions 2..p of their statistics, per column of the d_1 x (d_2*...*d_p) matrix"""
+    parts = np.split(stats, np.cumsum(shape)[:-1])
+    inner = shape[1:]
+    M = None
+    for r, mu in enumerate(parts[1:]):
+        sh = [1] * len(inner)
+        sh[r] = -1
+        b = np.broadcast_to(mu.reshape(sh), inner)
+        M = b if M is None else np.minimum(M, b)
+    return np.ascontiguousarray(M).reshape(-1)
+
+
+def as_matrix_state(st_ref: oracle.StateND) -> oracle.State4:
+    """the oracle's N-dimensional state in the layout the matrix comparison helper takes"""
+    rows = st_ref.shape[0]
+    cols = int(np.prod(st_ref.shape[1:]))
+    return oracle.State4(rows, cols, st_ref.m_codes, st_ref.m_scales, st_ref.v_codes, st_ref.v_stats[:rows],
+                         _colscale(st_ref.v_stats, st_ref.shape))
+
+
+def download(st: lpmm.StateND):
+    f = lambda t: t.cpu().numpy().copy()
+    rows = st.shape[0]
+    cols = int(np.prod(st.shape[1:]))
+    v_col = f(st.v_col)
+    got = oracle.State4(rows, cols, f(st.m_codes), f(st.m_blockscale), f(st.v_codes), f(st.v_row), v_col[:cols])
+    return got, v_col[cols:]
+
+
+def run(shape, steps, recipe="col_lognormal", bf16=False, seed=61, env=None):
+    rows, cols = shape[0], int(np.prod(shape[1:]))
+    for k in ("LPMM_FORCE_GENERAL", "LPMM_RW", "LPMM_RW2", "LPMM_GX"):
+        os.environ.pop(k, None)
+    os.environ.update(env or {})
+    try:
+        lpmm.ensure_init(rows + cols + sum(shape[1:]) + 128)
+        w_ref = workloads.weights(seed, 0, rows, cols).reshape(-1)
+        st_ref = oracle.state_zero_nd(shape)
+        w = to_dev(w_ref.copy())
+        st = lpmm.new_state_nd(shape, DEV)
+        fn = lpmm.lpmm_adamw4_nd_step_bf16g if bf16 else lpmm.lpmm_adamw4_nd_step
+        flips = 0
+        for t in range(1, steps + 1):
+            g = workloads.grads(seed, 0, t, rows, cols, recipe, bf16).reshape(-1)
+            mt, vt = oracle.adamw4_nd_step(w_ref, g, st_ref, HP, t, want_moments=True)
+            fn(w, to_dev(g, bf16), st, HP.lr, HP.beta1, HP.beta2, HP.eps, HP.weight_decay, t)
+            torch.cuda.synchronize()
+            got, inner_stats = download(st)
+            tag = f"{shape} {recipe} step {t}"
+            np.testing.assert_array_equal(inner_stats, st_ref.v_stats[rows:], err_msg=f"{tag}: statistics of dimensions 2..p")
+            flips += compare_step(got, as_matrix_state(st_ref), w.cpu().numpy(), w_ref, mt, vt, tag)
+        return flips
+    finally:
+        for k in (env or {}):
+            os.environ.pop(k, None)
+
+
+def test_zero_state_matches_oracle():
+    for shape in ((4, 3, 5), (8, 2, 2, 16)):
+        st, ref = lpmm.new_state_nd(shape, DEV), oracle.state_zero_nd(shape)
+        got, inner = download(st)
+        np.testing.assert_array_equal(got.m_codes, ref.m_codes)
+        np.testing.assert_array_equal(got.v_codes, ref.v_codes)
+        assert not got.v_r.any() and not got.v_c.any() and not inner.any() and not ref.v_stats.any()
+
+
+@pytest.mark.parametrize("shape", [(64, 8, 16), (96, 32, 3, 3), (40, 4, 4, 8), (256, 64, 2), (3, 5, 7), (16, 3, 3, 3),
+                                   (10, 2, 3, 4, 5), (5, 1, 128), (7, 128, 1), (2, 2, 2, 2, 2, 2, 2, 2)])
+def test_step_parity(shape):
+    # inner sizes whose product is a multiple of 128 take the tiled kernels, the others the general ones; conv-like
+    # shapes, unit dimensions, the maximum number of dimensions
+    assert run(shape, steps=3) == 0
+
+
+def test_bf16_gradients_and_outliers():
+    assert run((128, 16, 4, 4), steps=3, bf16=True) == 0
+    assert run((300, 8, 8, 2), steps=4, recipe="outlier_sparse") == 0
+
+
+def test_general_kernels_on_a_tiled_shape():
+    assert run((64, 8, 16), steps=3, env={"LPMM_FORCE_GENERAL": "1"}) == 0
+
+
+def test_two_dimensions_equal_the_matrix_step():
+    rows, cols = 200, 384
+    lpmm.ensure_init(4096)
+    w0 = workloads.weights(62, 0, rows, cols).reshape(-1)
+    wa, sa = to_dev(w0.copy()), lpmm.new_state(rows, cols, DEV)
+    wb, sb = to_dev(w0.copy()), lpmm.new_state_nd((rows, cols), DEV)
+    for t in (1, 2, 3):
+        g = to_dev(workloads.grads(62, 0, t, rows, cols, "col_lognormal").reshape(-1))
+        gpu_step(wa, g, sa, HP, t)
+        lpmm.lpmm_adamw4_nd_step(wb, g, sb, HP.lr, HP.beta1, HP.beta2, HP.eps, HP.weight_decay, t)
+    torch.cuda.synchronize()
+    assert torch.equal(wa, wb) and torch.equal(sa.m_codes, sb.m_codes) and torch.equal(sa.v_codes, sb.v_codes)
+    assert torch.equal(sa.v_rowmax, sb.v_row)
+    assert torch.equal(sa.v_colmax, sb.v_col[:cols]) and torch.equal(sa.v_colmax, sb.v_col[cols:])
+
+
+def test_workspace_is_left_clean_and_dequant_works():
+    """After an N-dimensional step the shared workspace must be zero again (a matrix step that follows relies
+    on it), and (v_codes, v_row, v_col) decompress through the matrix entry point."""
+    shape = (48, 4, 32)
+    rows, cols = 48, 128
+    lpmm.ensure_init(4096)
+    w_ref, st_ref = workloads.weights(63, 0, rows, cols).reshape(-1), oracle.state_zero_nd(shape)
+    w, st = to_dev(w_ref.copy()), lpmm.new_state_nd(shape, DEV)
+    w2_ref, st2_ref = workloads.weights(63, 1, rows, cols).reshape(-1), oracle.state_zero(rows, cols)
+    w2, st2 = to_dev(w2_ref.copy()), lpmm.new_state(rows, cols, DEV)
+    for t in (1, 2):
+        g = workloads.grads(63, 0, t, rows, cols, "col_lognormal").reshape(-1)
+        oracle.adamw4_nd_step(w_ref, g, st_ref, HP, t)
+        lpmm.lpmm_adamw4_nd_step(w, to_dev(g), st, HP.lr, HP.beta1, HP.beta2, HP.eps, HP.weight_decay, t)
+        mt, vt = oracle.adamw4_step(w2_ref, g, st2_ref, HP, t, want_moments=True)
+        gpu_step(w2, to_dev(g), st2, HP, t)
+        torch.cuda.synchronize()
+        assert compare_step(download_state(st2), st2_ref, w2.cpu().numpy(), w2_ref, mt, vt, f"matrix step {t}") == 0
+    out = torch.empty(rows * cols, device=DEV)
+    lpmm.lpmm_dequant_state(1, st.v_codes, st.v_row, st.v_col, rows, cols, out)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(out.cpu().numpy(),
+                                  oracle.dequant_v_nd(st_ref.v_codes, st_ref.v_stats, shape).reshape(-1))
+
+
+def test_bad_arguments_are_rejected():
+    import ctypes
+    L = lpmm.lib()
+    sizes = (ctypes.c_size_t * 5)()
+    for bad in ((5,), (0, 3, 4), (2,) * 9, (4, -1, 2)):
+        dims = (ctypes.c_int64 * len(bad))(*bad)
+        assert L.lpmm_adamw4_nd_state_sizes(ctypes.addressof(dims), len(bad), ctypes.addressof(sizes)) != 0
+    assert lpmm.lpmm_adamw4_nd_state_sizes((4, 3, 5)) == [30, 4, 30, 16, (15 + 8) * 4]
+    shape = (8, 4, 32)
+    lpmm.ensure_init(4096)
+    st = lpmm.new_state_nd(shape, DEV)
+    w, g = torch.zeros(1024, device=DEV), torch.zeros(1024, device=DEV)
+    with pytest.raises(lpmm.LpmmError):
+        lpmm.lpmm_adamw4_nd_step(w, g, st, 1e-3, 0.9, 0.999, 1e-8, 0.0, 0)
+    huge = lpmm.StateND((1 << 30, 1 << 8, 2), st.m_codes, st.m_blockscale, st.v_codes, st.v_row, st.v_col)
+    with pytest.raises(lpmm.LpmmError):                      # far beyond any registered workspace: rejected before a launch
+        lpmm.lpmm_adamw4_nd_step(w, g, huge, 1e-3, 0.9, 0.999, 1e-8, 0.0, 1)

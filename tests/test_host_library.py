@@ -154,3 +154,23 @@ def test_factorized_state_sizes_and_argument_errors():
     r1 = lpmm.TensorDesc(p, p, p, p, p, p, p, 2, 128, lpmm.KIND_4BIT, 0)
     assert lpmm.lpmm_adamw4_plan_bytes([d]) > 0
     assert lpmm.lpmm_adamw4_plan_bytes([d, r1]) == 0            # two optimizers in one plan
+
+
+def test_nd_state_sizes_and_argument_errors():
+    assert lpmm.lpmm_adamw4_nd_state_sizes((4, 3, 5)) == [30, 4, 30, 16, (15 + 8) * 4]
+    assert lpmm.lpmm_adamw4_nd_state_sizes((32, 128)) == [2048, 128, 2048, 128, (128 + 128) * 4]
+    L = lpmm.lib()
+    sizes = (ctypes.c_size_t * 5)()
+    for bad in ((5,), (0, 3, 4), (2,) * 9, (4, -1, 2), (1 << 31, 1 << 31, 4)):
+        dims = (ctypes.c_int64 * len(bad))(*bad)
+        assert L.lpmm_adamw4_nd_state_sizes(ctypes.addressof(dims), len(bad), ctypes.addressof(sizes)) == -1
+    dims = (ctypes.c_int64 * 3)(2, 4, 32)
+    assert L.lpmm_adamw4_nd_state_sizes(ctypes.addressof(dims), 3, None) == -1
+    assert L.lpmm_adamw4_nd_state_sizes(None, 3, ctypes.addressof(sizes)) == -1
+    buf = ctypes.create_string_buffer(4096 + 256)
+    p = (ctypes.addressof(buf) + 255) // 256 * 256
+    h = [ctypes.c_float(x) for x in (1e-3, 0.9, 0.999, 1e-8, 0.01)]
+    assert L.lpmm_adamw4_nd_step(*([p] * 7), ctypes.addressof(dims), 3, *h, 0, None) == -1       # step 0
+    assert L.lpmm_adamw4_nd_step(*([p] * 6 + [None]), ctypes.addressof(dims), 3, *h, 1, None) == -1
+    assert L.lpmm_adamw4_nd_step(*([p] * 7), ctypes.addressof(dims), 1, *h, 1, None) == -1       # one dimension
+    assert L.lpmm_adamw4_nd_step(*([p] * 7), ctypes.addressof(dims), 3, *h, 1, None) in (-2, -3) # no GPU here
