@@ -68,6 +68,8 @@ def lib() -> ctypes.CDLL:
         L.oracle_adamw4_nd_step.argtypes = [f32p, f32p, u8p, f32p, u8p, f32p, i64p, ctypes.c_int,
                                             cf, cf, cf, cf, cf, i64, f32p, f32p]
         L.oracle_state_zero_nd.argtypes = [u8p, f32p, u8p, f32p, i64p, ctypes.c_int]
+        L.oracle_sgdm32_step.argtypes = [f32p, f32p, f32p, i64, cf, cf]
+        L.oracle_sgdm4_step.argtypes = [f32p, f32p, u8p, f32p, i64, cf, cf, f32p]
         L.oracle_adamw4_factor_step.argtypes = [f32p, f32p, u8p, f32p, f32p, f32p, i64, i64,
                                                 cf, cf, cf, cf, cf, i64, f32p, f32p]
         L.oracle_state_zero_factor.argtypes = [u8p, f32p, f32p, f32p, i64, i64]
@@ -77,7 +79,8 @@ def lib() -> ctypes.CDLL:
                      "oracle_adamw32_step", "oracle_adamw4_step", "oracle_state_zero",
                      "oracle_quant_v_block", "oracle_dequant_v_block", "oracle_adamw4_b128_step",
                      "oracle_state_zero_b128", "oracle_adamw4_factor_step", "oracle_state_zero_factor",
-                     "oracle_quant_v_nd", "oracle_dequant_v_nd", "oracle_adamw4_nd_step", "oracle_state_zero_nd"):
+                     "oracle_quant_v_nd", "oracle_dequant_v_nd", "oracle_adamw4_nd_step", "oracle_state_zero_nd",
+                     "oracle_sgdm32_step", "oracle_sgdm4_step"):
             getattr(L, name).restype = None
         _lib = L
     return _lib
@@ -383,3 +386,34 @@ def adamw4_nd_step(w: np.ndarray, g: np.ndarray, st: StateND, hp: Hyper, t: int,
                                 hp.eps, hp.weight_decay, t, _f32(mt) if want_moments else null,
                                 _f32(vt) if want_moments else null)
     return mt, vt
+
+
+# ---- SGD with momentum, momentum compressed to 4 bits (App. E Alg. 2) ---------------------------------------
+
+@dataclass
+class StateSgdm:
+    """Compressed momentum of a flat tensor of P elements."""
+    P: int
+    m_codes: np.ndarray
+    m_scales: np.ndarray
+
+    def copy(self) -> "StateSgdm":
+        return StateSgdm(self.P, self.m_codes.copy(), self.m_scales.copy())
+
+
+def state_zero_sgdm(P: int) -> StateSgdm:
+    codes, scales = quant_m(np.zeros(P, np.float32))
+    return StateSgdm(P, codes, scales)
+
+
+def sgdm4_step(w: np.ndarray, g: np.ndarray, st: StateSgdm, lr: float, beta: float, want_moment=False):
+    assert w.size == st.P == g.size
+    mt = np.empty(w.size, np.float32) if want_moment else None
+    null = ctypes.POINTER(ctypes.c_float)()
+    lib().oracle_sgdm4_step(_f32(w), _f32(g), _u8(st.m_codes), _f32(st.m_scales), st.P, lr, beta,
+                            _f32(mt) if want_moment else null)
+    return mt
+
+
+def sgdm32_step(w: np.ndarray, g: np.ndarray, m: np.ndarray, lr: float, beta: float):
+    lib().oracle_sgdm32_step(_f32(w), _f32(g), _f32(m), w.size, lr, beta)

@@ -21,6 +21,8 @@
 //   * App. F Alg. 4: rank-1 normalization of a tensor with p dimensions: one statistic per index of
 //     every dimension (the maximum of |x| over all other indices), an element's scale is the minimum
 //     of its p statistics.  Functions *_v_nd / *_nd_*.  (The second moment is >= 0, so |x| = x.)
+//   * App. E Alg. 2: compression-based SGD with momentum: m_t = beta m_{t-1} + g, theta -= alpha m_t,
+//     the momentum compressed like Adam's first moment (B128 + signed DE map).  Functions *_sgdm*.
 //   * Sec. 4.3 and Sec. 5 ("4-bit Factor"): for tensors with two dimensions the second moment is
 //     not stored per element but factorized the way the cited Adafactor method does it: one
 //     statistic per row and one per column, v_ij reconstructed as row_i * col_j / sum(row).  The
@@ -314,6 +316,17 @@ void adamw_rule(float* w, float* m, float* v, const float* g, int64_t P, float l
     }
 }
 
+// The rule of Alg. 2 on a precise momentum buffer: m_t = beta m_{t-1} + g_t, theta_t = theta_{t-1} - alpha m_t.
+// The momentum decides integer codes afterwards, so it is one fused multiply-add in fp32 on both sides;
+// the parameter is evaluated in double and rounded once.  No weight decay, no dampening: Alg. 2 has none.
+void sgdm_rule(float* w, float* m, const float* g, int64_t P, float lr, float beta) {
+    for (int64_t i = 0; i < P; ++i) {
+        const float mt = std::fmaf(beta, m[i], g[i]);
+        m[i] = mt;
+        w[i] = float(double(w[i]) - double(lr) * double(mt));
+    }
+}
+
 }  // namespace
 
 extern "C" {
@@ -448,6 +461,20 @@ void oracle_state_zero_nd(uint8_t* m_codes, float* m_scales, uint8_t* v_codes, f
     std::vector<float> z(static_cast<size_t>(P), 0.0f);
     quant_m(z.data(), P, m_codes, m_scales);
     quant_v_nd(z.data(), dims, p, v_codes, v_stats);
+}
+
+// SGD with momentum (Alg. 2) on an uncompressed fp32 momentum buffer (tensors that are not quantized), and
+// with the momentum compressed to 4 bits (B128 + signed DE map, the first-moment quantizer of Sec. 3).
+void oracle_sgdm32_step(float* w, const float* g, float* m, int64_t P, float lr, float beta) {
+    sgdm_rule(w, m, g, P, lr, beta);
+}
+void oracle_sgdm4_step(float* w, const float* g, uint8_t* m_codes, float* m_scales, int64_t P, float lr,
+                       float beta, float* m_t_out) {
+    std::vector<float> m(static_cast<size_t>(P));
+    dequant_m(m_codes, m_scales, P, m.data());                    // Alg. 2: decompress
+    sgdm_rule(w, m.data(), g, P, lr, beta);
+    if (m_t_out) std::memcpy(m_t_out, m.data(), sizeof(float) * size_t(P));
+    quant_m(m.data(), P, m_codes, m_scales);                      // Alg. 2: compress
 }
 
 // One step of "4-bit Factor" on one rows x cols tensor (Sec. 4.3; Alg. 3 with the second moment kept
