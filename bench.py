@@ -62,6 +62,9 @@ def main():
                     help="rank1: rank-1/Linear second moment of 2-D tensors (two passes, the headline "
                          "configuration); b128: every tensor flat with a block-wise second moment (one pass); "
                          "factor: row / column statistics instead of a per-element second moment (two passes)")
+    ap.add_argument("--optimizer", choices=["adamw", "sgdm"], default="adamw",
+                    help="adamw: the 4-bit AdamW step (the headline metric); sgdm: SGD with momentum and 4-bit "
+                         "momentum (App. E Alg. 2), every tensor flat, one pass")
     ap.add_argument("--launch", choices=["multi", "per-tensor"], default="multi",
                     help="multi: one plan, pass 1 / pass 2 of neighbouring tensor groups share launches; "
                          "per-tensor: two launches per quantized tensor")
@@ -111,7 +114,10 @@ def main():
                 z[zero, :] = 0.0
             gs.append(z.reshape(-1).to(torch.bfloat16) if bf16 else z.reshape(-1).contiguous())
             del z
-        if sp.quantized and args.second_moment == "b128":
+        if args.optimizer == "sgdm":
+            tensors.append(("q", sp, p, gs, lpmm.new_state_sgdm(sp.numel, dev)) if sp.quantized else
+                           ("f", sp, p, gs, torch.zeros(sp.numel, device=dev)))
+        elif sp.quantized and args.second_moment == "b128":
             tensors.append(("q", sp, p, gs, lpmm.new_state_b128(sp.numel, dev)))
         elif sp.quantized:
             st = (lpmm.new_state_factor if args.second_moment == "factor" else lpmm.new_state)(sp.rows, sp.cols, dev)
@@ -126,9 +132,13 @@ def main():
 
     n_params = sum(sp.numel for sp in specs)
     n_quant = sum(sp.numel for sp in specs if sp.quantized)
-    b128 = args.second_moment == "b128"
-    factor = args.second_moment == "factor"
-    if factor:
+    sgdm = args.optimizer == "sgdm"
+    b128 = args.second_moment == "b128" and not sgdm
+    factor = args.second_moment == "factor" and not sgdm
+    momentum = 0.9
+    if sgdm:
+        step4 = lpmm.lpmm_sgdm4_step_bf16g if bf16 else lpmm.lpmm_sgdm4_step
+    elif factor:
         step4 = lpmm.lpmm_adamw4_factor_step_bf16g if bf16 else lpmm.lpmm_adamw4_factor_step
     elif b128:
         step4 = lpmm.lpmm_adamw4_b128_step_bf16g if bf16 else lpmm.lpmm_adamw4_b128_step
@@ -139,16 +149,27 @@ def main():
     plans = []
     if args.launch == "multi":
         for k in range(n_grad_sets):
-            descs = [lpmm.make_desc(p, gs[k], st, sp.rows, sp.cols) for kind, sp, p, gs, st in tensors]
+            if sgdm:
+                descs = [lpmm.make_desc_sgdm(p, gs[k], st, sp.numel) for kind, sp, p, gs, st in tensors]
+            else:
+                descs = [lpmm.make_desc(p, gs[k], st, sp.rows, sp.cols) for kind, sp, p, gs, st in tensors]
             plans.append(lpmm.new_plan(descs, 1 if bf16 else 0, dev))
 
     def one_step(t):
         k = t % n_grad_sets
         if plans:
-            lpmm.lpmm_adamw4_step_multi(plans[k], lr, b1, b2, eps, wd, t)
+            if sgdm:
+                lpmm.lpmm_sgdm4_step_multi(plans[k], lr, momentum)
+            else:
+                lpmm.lpmm_adamw4_step_multi(plans[k], lr, b1, b2, eps, wd, t)
             return
         for kind, sp, p, gs, st in tensors:
-            if kind == "q":
+            if sgdm:
+                if kind == "q":
+                    step4(p, gs[k], st, lr, momentum)
+                else:
+                    lpmm.lpmm_sgdm32_step(p, gs[k], st, sp.numel, 1 if bf16 else 0, lr, momentum)
+            elif kind == "q":
                 step4(p, gs[k], st, lr, b1, b2, eps, wd, t)
             else:
                 lpmm.lpmm_adamw32_step(p, gs[k], st[0], st[1], sp.numel, 1 if bf16 else 0, lr, b1, b2, eps,
@@ -172,9 +193,11 @@ def main():
     # ---- the same K steps again with HIP events around every launch of the step -------------------------
     # bp1: the recorded (dominant) kernel, bp2: the other pass
     bp1, bp2 = ((bytes_per_param_b128(bf16), 0.0) if b128 else bytes_per_param_factor(bf16) if factor
+                else (bytes_per_param_factor(bf16)[0], 0.0) if sgdm    # param 8, grad, m codes 1, block scales 8/128
                 else bytes_per_param(bf16))
+    one_pass = b128 or sgdm
     n_small = n_params - n_quant
-    small_bytes = (24.0 + (2.0 if bf16 else 4.0)) * n_small      # fp32-state AdamW: p, m, v read+write, g read
+    small_bytes = ((16.0 if sgdm else 24.0) + (2.0 if bf16 else 4.0)) * n_small   # fp32 states: p, m (, v) read+write, g read
     n_q_tensors = sum(1 for x in tensors if x[0] == "q")
     lpmm.lpmm_profile_begin(max(n_q_tensors, 64) * args.steps)
     for _ in range(args.steps):
@@ -194,7 +217,8 @@ def main():
         avg_ms = p1_ms / launches
         achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9
         roofline = {
-            "bound": "hbm", "kernel": ("phase_kernel<roles=3> (the whole block-wise step)" if b128 else
+            "bound": "hbm", "kernel": ("sgdm_phase_kernel (the whole step)" if sgdm else
+                                       "phase_kernel<roles=3> (the whole block-wise step)" if b128 else
                                        "factor_phase_kernel<roles=2> (update pass)" if factor else
                                        "phase_kernel<roles=1> (pass 1)"),
             "achieved": round(achieved, 1),
@@ -202,14 +226,14 @@ def main():
             "bytes_per_param": bp1, "launches": n_calls, "avg_launch_ms": round(avg_ms, 5),
             "bytes_per_launch": round(bytes_per_launch),
             "traffic_source": None,
-            "note": ("one pass: this kernel is the whole step" if b128 else
+            "note": ("one pass: this kernel is the whole step" if one_pass else
                      "the statistics pass of the next tensor group (%.1f B/param) runs concurrently and shares "
                      "the bandwidth; whole-step figures are in config" % bp2 if factor else
                      "pass 2 of the neighbouring tensor group (%.1f B/param) runs concurrently and shares "
                      "the bandwidth; whole-step figures are in config" % bp2),
         }
         # HBM bytes per launch measured offline with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/)
-        tpath = os.path.join(ROOT, "profiles", "traffic_phase_kernel_%s%s.json" % (args.config, "_b128" if b128 else "_factor" if factor else ""))
+        tpath = os.path.join(ROOT, "profiles", "traffic_phase_kernel_%s%s.json" % (args.config, "_sgdm" if sgdm else "_b128" if b128 else "_factor" if factor else ""))
         if os.path.exists(tpath):
             tr = json.load(open(tpath))
             if tr.get("launches_per_step") == n_calls // max(args.steps, 1):
@@ -220,7 +244,7 @@ def main():
         p1_bytes_per_launch = bp1 * n_quant * args.steps / launches
         achieved = p1_bytes_per_launch / (p1_avg_ms * 1e-3) / 1e9
         roofline = {
-            "bound": "hbm", "kernel": "b128_kernel" if b128 else "factor_update_fast" if factor else "pass1_fast",
+            "bound": "hbm", "kernel": "sgdm4_kernel" if sgdm else "b128_kernel" if b128 else "factor_update_fast" if factor else "pass1_fast",
             "achieved": round(achieved, 1),
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
@@ -238,9 +262,12 @@ def main():
         rows = min(big.rows, max(1, (24 << 20) // big.cols))        # about 25 M parameters of that tensor
         cols = big.cols
         w = workloads.weights(args.seed, 0, rows, cols).reshape(-1)
-        st = (oracle.state_zero_b128(rows * cols) if b128 else oracle.state_zero_factor(rows, cols) if factor
-              else oracle.state_zero(rows, cols))
-        cpu_step = oracle.adamw4_b128_step if b128 else oracle.adamw4_factor_step if factor else oracle.adamw4_step
+        st = (oracle.state_zero_sgdm(rows * cols) if sgdm else oracle.state_zero_b128(rows * cols) if b128
+              else oracle.state_zero_factor(rows, cols) if factor else oracle.state_zero(rows, cols))
+        if sgdm:
+            cpu_step = lambda w_, g_, st_, hp_, s_: oracle.sgdm4_step(w_, g_, st_, lr, momentum)
+        else:
+            cpu_step = oracle.adamw4_b128_step if b128 else oracle.adamw4_factor_step if factor else oracle.adamw4_step
         hp = oracle.Hyper(lr, b1, b2, eps, wd)
         n_cpu_steps = 20
         gs = [workloads.grads(args.seed, 0, s, rows, cols, recipe, bf16).reshape(-1) for s in (1, 2)]
@@ -256,33 +283,34 @@ def main():
     total_gbps = ((bp1 + bp2) * n_quant + small_bytes) / (elapsed / args.steps) / 1e9
     # every stream touched once (what a single pass would move): param 8, grad, codes 2, block scales and,
     # for the rank-1 form, one more float per 128 elements standing in for the row / column maxima
-    floor_bpp = 8.0 + (2.0 if bf16 else 4.0) + (1.0 if factor else 2.0) + (16.0 if b128 else 8.0) / 128.0
+    floor_bpp = 8.0 + (2.0 if bf16 else 4.0) + (1.0 if factor or sgdm else 2.0) + (16.0 if b128 else 8.0) / 128.0
     floor_gbps = (floor_bpp * n_quant + small_bytes) / (elapsed / args.steps) / 1e9
     if plans:
-        kernels_per_step = (n_calls // max(args.steps, 1)) * (1 if b128 else 2)     # as many A as B launches
+        kernels_per_step = (n_calls // max(args.steps, 1)) * (1 if one_pass else 2)     # as many A as B launches
     else:
-        kernels_per_step = n_q_tensors * (1 if b128 else 2) + (len(tensors) - n_q_tensors)
+        kernels_per_step = n_q_tensors * (1 if one_pass else 2) + (len(tensors) - n_q_tensors)
     out = {
-        "metric": "params updated/sec per 4-bit AdamW step", "value": round(value, 1), "unit": "params/s",
+        "metric": "params updated/sec per 4-bit SGDM step" if sgdm else "params updated/sec per 4-bit AdamW step", "value": round(value, 1), "unit": "params/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": args.config, "tensors": len(specs), "params": n_params,
                    "quantized_params": n_quant, "grad_dtype": "bf16" if bf16 else "f32",
-                   "second_moment": "block-wise B128/Linear on flattened tensors, one pass" if b128
+                   "second_moment": "none (SGD with momentum, App. E Alg. 2), flattened tensors, one pass" if sgdm
+                   else "block-wise B128/Linear on flattened tensors, one pass" if b128
                    else "factorized (row and column statistics), two passes" if factor
                    else "rank-1/Linear, two passes",
                    "grad_recipe": recipe,
-                   "launch": (("multi-tensor plan, %d launches per step" if b128 else
+                   "launch": (("multi-tensor plan, %d launches per step" if one_pass else
                                "multi-tensor plan, %d update launches per step on a second stream, the statistics "
                                "passes on the caller's stream" if factor else
                                "multi-tensor plan, %d pass-1 launches per step on the caller's stream, "
                                "pass 2 on a second stream") % (n_calls // max(args.steps, 1)))
-                   if plans else "per-tensor, %d kernel%s per quantized tensor" % ((1, "") if b128 else (2, "s")),
+                   if plans else "per-tensor, %d kernel%s per quantized tensor" % ((1, "") if one_pass else (2, "s")),
                    "kernels_per_step": kernels_per_step,
                    "hbm_gbps_one_touch_floor": round(floor_gbps, 1),
-                   ("hbm_gbps_one_pass_model" if b128 else "hbm_gbps_two_pass_model"): round(total_gbps, 1),
-                   ("hbm_frac_one_pass_model" if b128 else "hbm_frac_two_pass_model"):
+                   ("hbm_gbps_one_pass_model" if one_pass else "hbm_gbps_two_pass_model"): round(total_gbps, 1),
+                   ("hbm_frac_one_pass_model" if one_pass else "hbm_frac_two_pass_model"):
                        round(total_gbps / HBM_PEAK_GBPS, 4)},
         "roofline": roofline, "cpu_baseline": cpu,
     }

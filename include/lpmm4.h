@@ -215,6 +215,33 @@ int lpmm_adamw4_nd_step_bf16g(void* param, const void* grad, uint8_t* m_codes, f
                               float lr, float beta1, float beta2, float eps, float weight_decay,
                               int64_t step, void* stream);
 
+/* ---- SGD with momentum, 4-bit momentum -------------------------------------------------------------------
+ * App. E Alg. 2: m_t = momentum * m_{t-1} + g, param -= lr * m_t (the precise m_t), m compressed like
+ * Adam's first moment (block size 128, signed dynamic-exponent map).  No weight decay, no dampening, no
+ * bias correction: the algorithm has none.  State of a tensor of `numel` elements (any shape, taken flat):
+ *   m_codes uint8[(numel+1)/2], m_blockscale float[ceil(numel/128)]      zero state: codes 7, scales 0
+ * One kernel, every byte touched once.  Needs lpmm_adamw4_init on the current device (lookup tables).
+ * param, grad 16-byte aligned, the rest 4-byte. */
+
+/* sizes[2] (host, out): bytes of m_codes, m_blockscale. */
+int lpmm_sgdm4_state_sizes(int64_t numel, size_t sizes[2]);
+
+/* Writes the zero state on `stream`. */
+int lpmm_sgdm4_state_zero(uint8_t* m_codes, float* m_blockscale, int64_t numel, void* stream);
+
+/* One step, in place on param and the two state buffers; grad (float[numel]) is read only.
+ * lr >= 0 finite, 0 <= momentum < 1. */
+int lpmm_sgdm4_step(void* param, const void* grad, uint8_t* m_codes, float* m_blockscale, int64_t numel,
+                    float lr, float momentum, void* stream);
+
+/* Same step with a bf16 gradient buffer. */
+int lpmm_sgdm4_step_bf16g(void* param, const void* grad, uint8_t* m_codes, float* m_blockscale,
+                          int64_t numel, float lr, float momentum, void* stream);
+
+/* The same rule with an uncompressed fp32 momentum buffer m[numel], for tensors that are not quantized. */
+int lpmm_sgdm32_step(void* param, const void* grad, float* m, int64_t numel, int grad_dtype, float lr,
+                     float momentum, void* stream);
+
 /* AdamW step with uncompressed fp32 states, for tensors that are not quantized (App. C.1: size
  * <= 4096, biases and normalization vectors): Alg. 3 with compress = decompress = identity.
  * param, m, v: float[numel] in place; grad: float or bf16 [numel] per grad_dtype. */
@@ -256,6 +283,11 @@ int lpmm_quant_state(int which, const float* in, const int64_t shape[2], uint8_t
                                    A plan holds LPMM_KIND_4BIT or LPMM_KIND_4BIT_FACTOR tensors, not both (they
                                    are two optimizers); either may be mixed with the other two kinds */
 
+#define LPMM_KIND_SGDM_4BIT 4   /* SGD with momentum, 4-bit momentum, as in lpmm_sgdm4_step: m_state = m_codes,
+                                   m_blockscale; the v_* members are ignored; the tensor is taken flat */
+#define LPMM_KIND_SGDM_FP32 5   /* SGD with momentum, fp32 momentum, as in lpmm_sgdm32_step: m_state = float m[] */
+                                /* SGDM kinds make a plan of their own, stepped by lpmm_sgdm4_step_multi */
+
 typedef struct lpmm_tensor_desc {
     void* param;            /* float[rows*cols], in place */
     const void* grad;       /* float or bf16 [rows*cols] (one type for the whole plan) */
@@ -287,6 +319,10 @@ int lpmm_adamw4_plan_build(const lpmm_tensor_desc* descs, int64_t n, int grad_dt
  * as they share no tensor; two steps of the same plan must not overlap. */
 int lpmm_adamw4_step_multi(void* plan, float lr, float beta1, float beta2, float eps,
                            float weight_decay, int64_t step, void* stream);
+
+/* One SGD-with-momentum step for every tensor of a plan built from LPMM_KIND_SGDM_* tensors only
+ * (lpmm_adamw4_step_multi rejects such a plan, and this call rejects the others). */
+int lpmm_sgdm4_step_multi(void* plan, float lr, float momentum, void* stream);
 
 /* Forgets the host-side record of a plan (the device memory stays the caller's). */
 int lpmm_adamw4_plan_release(void* plan);

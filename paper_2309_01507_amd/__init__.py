@@ -15,4 +15,6 @@ from .binding import (  # noqa: F401
     lpmm_adamw4_factor_step, lpmm_adamw4_factor_step_bf16g, KIND_4BIT_FACTOR,
     StateND, new_state_nd, lpmm_adamw4_nd_state_sizes, lpmm_adamw4_nd_state_zero, lpmm_adamw4_nd_step,
     lpmm_adamw4_nd_step_bf16g,
+    StateSgdm, new_state_sgdm, lpmm_sgdm4_state_sizes, lpmm_sgdm4_state_zero, lpmm_sgdm4_step, lpmm_sgdm4_step_bf16g,
+    lpmm_sgdm32_step, lpmm_sgdm4_step_multi, make_desc_sgdm, KIND_SGDM_4BIT, KIND_SGDM_FP32,
 )

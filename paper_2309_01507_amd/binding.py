@@ -82,6 +82,12 @@ def lib() -> ctypes.CDLL:
         nd_args = [_VP] * 7 + [_VP, ctypes.c_int] + [_F] * 5 + [_I64, _VP]
         L.lpmm_adamw4_nd_step.argtypes = nd_args
         L.lpmm_adamw4_nd_step_bf16g.argtypes = nd_args
+        L.lpmm_sgdm4_state_sizes.argtypes = [_I64, _VP]
+        L.lpmm_sgdm4_state_zero.argtypes = [_VP, _VP, _I64, _VP]
+        L.lpmm_sgdm4_step.argtypes = [_VP] * 4 + [_I64, _F, _F, _VP]
+        L.lpmm_sgdm4_step_bf16g.argtypes = [_VP] * 4 + [_I64, _F, _F, _VP]
+        L.lpmm_sgdm32_step.argtypes = [_VP] * 3 + [_I64, ctypes.c_int, _F, _F, _VP]
+        L.lpmm_sgdm4_step_multi.argtypes = [_VP, _F, _F, _VP]
         L.lpmm_adamw4_factor_state_sizes.argtypes = [_VP, _VP]
         L.lpmm_adamw4_factor_state_zero.argtypes = [_VP] * 4 + [_VP, _VP]
         factor_args = [_VP] * 6 + [_VP] + [_F] * 5 + [_I64, _VP]
@@ -419,6 +425,63 @@ def lpmm_adamw4_nd_step_bf16g(param, grad, st: StateND, lr, beta1, beta2, eps, w
     _nd_step("lpmm_adamw4_nd_step_bf16g", param, grad, st, lr, beta1, beta2, eps, weight_decay, step, stream)
 
 
+# ---- SGD with momentum, 4-bit momentum ------------------------------------------------------------------------
+
+@dataclass
+class StateSgdm:
+    """The two device buffers of a flat tensor's compressed momentum."""
+    numel: int
+    m_codes: "object"
+    m_blockscale: "object"
+
+
+def lpmm_sgdm4_state_sizes(numel: int):
+    sizes = (ctypes.c_size_t * 2)()
+    _check(lib().lpmm_sgdm4_state_sizes(int(numel), ctypes.addressof(sizes)), "lpmm_sgdm4_state_sizes")
+    return [int(s) for s in sizes]
+
+
+def lpmm_sgdm4_state_zero(st: StateSgdm, stream=None) -> None:
+    _check(lib().lpmm_sgdm4_state_zero(_ptr(st.m_codes), _ptr(st.m_blockscale), int(st.numel), _stream(stream)),
+           "lpmm_sgdm4_state_zero")
+
+
+def new_state_sgdm(numel: int, device="cuda") -> StateSgdm:
+    import torch
+    sz = lpmm_sgdm4_state_sizes(numel)
+    st = StateSgdm(numel, torch.empty((sz[0] + 3) // 4 * 4, dtype=torch.uint8, device=device)[:sz[0]],
+                   torch.empty(sz[1] // 4, dtype=torch.float32, device=device))
+    lpmm_sgdm4_state_zero(st)
+    return st
+
+
+def lpmm_sgdm4_step(param, grad, st: StateSgdm, lr, momentum, stream=None):
+    _check(lib().lpmm_sgdm4_step(_ptr(param), _ptr(grad), _ptr(st.m_codes), _ptr(st.m_blockscale), int(st.numel),
+                                 lr, momentum, _stream(stream)), "lpmm_sgdm4_step")
+
+
+def lpmm_sgdm4_step_bf16g(param, grad, st: StateSgdm, lr, momentum, stream=None):
+    _check(lib().lpmm_sgdm4_step_bf16g(_ptr(param), _ptr(grad), _ptr(st.m_codes), _ptr(st.m_blockscale),
+                                       int(st.numel), lr, momentum, _stream(stream)), "lpmm_sgdm4_step_bf16g")
+
+
+def lpmm_sgdm32_step(param, grad, m, numel, grad_dtype, lr, momentum, stream=None):
+    _check(lib().lpmm_sgdm32_step(_ptr(param), _ptr(grad), _ptr(m), int(numel), int(grad_dtype), lr, momentum,
+                                  _stream(stream)), "lpmm_sgdm32_step")
+
+
+def lpmm_sgdm4_step_multi(plan, lr, momentum, stream=None) -> None:
+    _check(lib().lpmm_sgdm4_step_multi(_ptr(plan), lr, momentum, _stream(stream)), "lpmm_sgdm4_step_multi")
+
+
+def make_desc_sgdm(param, grad, state, numel=None) -> "TensorDesc":
+    """state: a StateSgdm (4-bit momentum) or one fp32 momentum tensor (then numel must be given)."""
+    if isinstance(state, StateSgdm):
+        return TensorDesc(_ptr(param), _ptr(grad), _ptr(state.m_codes), _ptr(state.m_blockscale), None, None, None,
+                          1, state.numel, KIND_SGDM_4BIT, 0)
+    return TensorDesc(_ptr(param), _ptr(grad), _ptr(state), None, None, None, None, 1, int(numel), KIND_SGDM_FP32, 0)
+
+
 def lpmm_adamw32_step(param, grad, m, v, numel, grad_dtype, lr, beta1, beta2, eps, weight_decay, step,
                       stream=None):
     _check(lib().lpmm_adamw32_step(_ptr(param), _ptr(grad), _ptr(m), _ptr(v), int(numel),
@@ -442,7 +505,7 @@ def lpmm_quant_state(which: int, x, rows, cols, codes, scale_a, scale_b, stream=
 
 # ---- many tensors in one call ------------------------------------------------------------------------
 
-KIND_4BIT, KIND_FP32, KIND_4BIT_B128, KIND_4BIT_FACTOR = 0, 1, 2, 3
+KIND_4BIT, KIND_FP32, KIND_4BIT_B128, KIND_4BIT_FACTOR, KIND_SGDM_4BIT, KIND_SGDM_FP32 = 0, 1, 2, 3, 4, 5
 
 
 class TensorDesc(ctypes.Structure):

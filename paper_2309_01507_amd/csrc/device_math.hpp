@@ -95,6 +95,15 @@ __device__ __forceinline__ float param_update(const Hyper& h, float w, float mt,
     return __builtin_fmaf(-h.step_size, x, wdec);
 }
 
+// ---- SGD with momentum (App. E Alg. 2) on one element: h.beta1 is the momentum, h.step_size the rate ----
+
+__device__ __forceinline__ float moment_sgdm(const Hyper& h, float m_prev, float g) {
+    return __builtin_fmaf(h.beta1, m_prev, g);
+}
+__device__ __forceinline__ float param_sgdm(const Hyper& h, float w, float mt) {
+    return __builtin_fmaf(-h.step_size, mt, w);
+}
+
 // ---- compress ------------------------------------------------------------------------------------
 
 // bucket table entry of a normalized value with |n| <= 1 + 2^-22 (block absmax normalization

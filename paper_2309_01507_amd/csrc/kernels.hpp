@@ -28,7 +28,8 @@ namespace lpmm {
 __device__ float d_byte_decode[512];          // entry b: {T_DE[b & 15], T_DE[b >> 4]}
 __device__ SearchEntry d_search[kBucketsPadded];    // nearest-entry search for the DE map
 
-enum TensorKind : int { kQuantFast = 0, kQuantGeneral = 1, kFp32State = 2, kQuantBlockV = 3, kFactorFast = 4, kFactorGeneral = 5 };
+enum TensorKind : int { kQuantFast = 0, kQuantGeneral = 1, kFp32State = 2, kQuantBlockV = 3, kFactorFast = 4, kFactorGeneral = 5,
+                        kSgdmBlock = 6, kSgdmFp32 = 7 };
 
 struct Tensor4 {
     float* p;               // parameters, fp32 [P]
@@ -801,20 +802,26 @@ struct RowB {                      // everything the step reads for one block, p
 constexpr int kNoBlock = 1 << 22;     // a block index whose offsets lie beyond any tile: loads return zeros
 
 // ib = block index inside the (super-)tile; blocks at or beyond its end read as zeros
-template <bool BF16>
+// SGDM: the tensor has no second moment (SGD with momentum, App. E Alg. 2)
+template <bool BF16, bool SGDM = false>
 __device__ __forceinline__ RowB<BF16> load_rowb(const TileB& b, int ib, int l) {
     RowB<BF16> r;
     const uint32_t off4 = (uint32_t(ib) * 128u + uint32_t(l) * 4u) * 4u;
     r.p = buf_ld_f4_stream(b.rp, off4);
     r.g = load_grad_regs4<BF16, kPolicyNt>(b.rg, off4);              // read once per step
     r.mq = buf_ld_u16(b.rmq, off4 >> 3);
-    r.vq = buf_ld_u16(b.rvq, off4 >> 3);
     r.sm_old = buf_ld_f(b.rms, uint32_t(ib) * 4u);
-    r.sv_old = buf_ld_f(b.rvs, uint32_t(ib) * 4u);
+    if constexpr (SGDM) {
+        r.vq = 0;
+        r.sv_old = 0.0f;
+    } else {
+        r.vq = buf_ld_u16(b.rvq, off4 >> 3);
+        r.sv_old = buf_ld_f(b.rvs, uint32_t(ib) * 4u);
+    }
     return r;
 }
 
-template <bool BF16, class Mid>
+template <bool BF16, bool SGDM, class Mid>
 __device__ __forceinline__ void b128_row(const Hyper& h, const TileB& tb, Lds& s, const RowB<BF16>& cur,
                                          int ib, int slot, int l, Mid mid) {
     float w[4] = {cur.p.x, cur.p.y, cur.p.z, cur.p.w};
@@ -827,29 +834,39 @@ __device__ __forceinline__ void b128_row(const Hyper& h, const TileB& tb, Lds& s
         mt[2 * k] = t.x * cur.sm_old;         // decompress: T_DE[code] * block scale
         mt[2 * k + 1] = t.y * cur.sm_old;
     }
-    if (__builtin_expect(__ballot(!scale_is_tame(cur.sv_old)) == 0, 1)) {
-        float qf[4];
-        codes_to_float4(cur.vq, qf);
-        const float s16 = cur.sv_old * 0.0625f;
+    if constexpr (SGDM) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) vt[e] = dequant_v16(qf[e], s16);
+        for (int e = 0; e < 4; ++e) {
+            mt[e] = moment_sgdm(h, mt[e], g[e]);
+            w[e] = param_sgdm(h, w[e], mt[e]);
+            amax = fmaxf(amax, fabsf(mt[e]));
+            vt[e] = 0.0f;
+        }
     } else {
+        if (__builtin_expect(__ballot(!scale_is_tame(cur.sv_old)) == 0, 1)) {
+            float qf[4];
+            codes_to_float4(cur.vq, qf);
+            const float s16 = cur.sv_old * 0.0625f;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) vt[e] = dequant_v((uint32_t(cur.vq) >> (4 * e)) & 15u, cur.sv_old);
-    }
+            for (int e = 0; e < 4; ++e) vt[e] = dequant_v16(qf[e], s16);
+        } else {
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        mt[e] = moment_m(h, mt[e], g[e]);
-        vt[e] = moment_v(h, vt[e], g[e]);
-        w[e] = param_update(h, w[e], mt[e], vt[e]);
-        amax = fmaxf(amax, fabsf(mt[e]));
-        vmax = max_nonneg(vmax, vt[e]);
+            for (int e = 0; e < 4; ++e) vt[e] = dequant_v((uint32_t(cur.vq) >> (4 * e)) & 15u, cur.sv_old);
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            mt[e] = moment_m(h, mt[e], g[e]);
+            vt[e] = moment_v(h, vt[e], g[e]);
+            w[e] = param_update(h, w[e], mt[e], vt[e]);
+            amax = fmaxf(amax, fabsf(mt[e]));
+            vmax = max_nonneg(vmax, vt[e]);
+        }
     }
     __builtin_amdgcn_sched_barrier(0);
     mid();                                        // the caller's prefetch of a later block
     __builtin_amdgcn_sched_barrier(0);
     const float sm_new = group32_allmax(amax);    // block absmax of m_t
-    const float sv_new = group32_allmax(vmax);    // block maximum of v_t
+    const float sv_new = SGDM ? 0.0f : group32_allmax(vmax);    // block maximum of v_t
 
     uint32_t mq_new = 0;
     uint32_t dist = scale_is_tame(sm_new) ? 0xFFFFFFFFu : 0u;
@@ -869,8 +886,8 @@ __device__ __forceinline__ void b128_row(const Hyper& h, const TileB& tb, Lds& s
         for (int e = 0; e < 4; ++e) mq_new |= quant_m_code(s.search, mt[e], sm_new) << (4 * e);
     }
 
-    uint32_t vq_new;
-    {
+    uint32_t vq_new = 0;
+    if constexpr (!SGDM) {
         const float inv_s = approx_inv(sv_new);
         uint32_t lo = 0, hi = 0;
         float closest = scale_is_tame(sv_new) ? 0.5f : 0.0f, fa, fb;
@@ -891,10 +908,10 @@ __device__ __forceinline__ void b128_row(const Hyper& h, const TileB& tb, Lds& s
     const uint32_t off4 = (uint32_t(ib) * 128u + uint32_t(l) * 4u) * 4u;
     st_stream4(tb.p, off4, make_float4(w[0], w[1], w[2], w[3]));
     st<uint16_t>(tb.mq, off4 >> 3, uint16_t(mq_new));
-    st<uint16_t>(tb.vq, off4 >> 3, uint16_t(vq_new));
+    if constexpr (!SGDM) st<uint16_t>(tb.vq, off4 >> 3, uint16_t(vq_new));
     if (l == 0) {
         s.blk_scale[slot] = sm_new;
-        s.blk_vmax[slot] = sv_new;
+        if constexpr (!SGDM) s.blk_vmax[slot] = sv_new;
     }
 }
 
@@ -905,7 +922,7 @@ static_assert(kGroups * kB128MaxRounds <= kMaxRowSlots, "LDS staging of block re
 
 // workgroup `wg` of a tensor: super-tile wg / slices, slice wg % slices of each group's range, where
 // slices = 64 / a.rw and a.rw = rounds (a power of two); a.nb = whole blocks of the tensor
-template <bool BF16>
+template <bool BF16, bool SGDM = false>
 __device__ __forceinline__ void b128_tile(const Tensor4& a, const Hyper& h, int wg, Lds& s) {
     const int rounds = a.rw, slices = kB128Stride / rounds;
     const int64_t sup0 = int64_t(wg / slices) * kB128Super;
@@ -922,55 +939,60 @@ __device__ __forceinline__ void b128_tile(const Tensor4& a, const Hyper& h, int 
     auto blk = [&](int k) { return k < nv ? first + k : kNoBlock; };
     const int slot0 = grp * rounds;
     int k = 0;
-    RowB<BF16> r0 = load_rowb<BF16>(tb, blk(0), l);
-    RowB<BF16> r1 = load_rowb<BF16>(tb, blk(1), l);
+    RowB<BF16> r0 = load_rowb<BF16, SGDM>(tb, blk(0), l);
+    RowB<BF16> r1 = load_rowb<BF16, SGDM>(tb, blk(1), l);
     RowB<BF16> r2;
     load_tables(s);                                // the first blocks' loads are in flight meanwhile
     __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);       // loop start-up state: nothing outstanding (see pass 1)
     auto none = [] {};
     while (k + 2 < nv) {                           // rounds of three blocks, no exit in the middle
-        b128_row<BF16>(h, tb, s, r0, first + k, slot0 + k, l, [&] { r2 = load_rowb<BF16>(tb, blk(k + 2), l); });
-        b128_row<BF16>(h, tb, s, r1, first + k + 1, slot0 + k + 1, l, [&] { r0 = load_rowb<BF16>(tb, blk(k + 3), l); });
-        b128_row<BF16>(h, tb, s, r2, first + k + 2, slot0 + k + 2, l, [&] { r1 = load_rowb<BF16>(tb, blk(k + 4), l); });
+        b128_row<BF16, SGDM>(h, tb, s, r0, first + k, slot0 + k, l, [&] { r2 = load_rowb<BF16, SGDM>(tb, blk(k + 2), l); });
+        b128_row<BF16, SGDM>(h, tb, s, r1, first + k + 1, slot0 + k + 1, l, [&] { r0 = load_rowb<BF16, SGDM>(tb, blk(k + 3), l); });
+        b128_row<BF16, SGDM>(h, tb, s, r2, first + k + 2, slot0 + k + 2, l, [&] { r1 = load_rowb<BF16, SGDM>(tb, blk(k + 4), l); });
         k += 3;
     }
     if (k < nv) {
-        b128_row<BF16>(h, tb, s, r0, first + k, slot0 + k, l, none);
-        if (k + 1 < nv) b128_row<BF16>(h, tb, s, r1, first + k + 1, slot0 + k + 1, l, none);
+        b128_row<BF16, SGDM>(h, tb, s, r0, first + k, slot0 + k, l, none);
+        if (k + 1 < nv) b128_row<BF16, SGDM>(h, tb, s, r1, first + k + 1, slot0 + k + 1, l, none);
     }
     __syncthreads();
     for (int t = threadIdx.x; t < kGroups * rounds; t += kThreads) {   // new block scales: 8 contiguous runs
         const int b = (t / rounds) * kB128Stride + slice0 + t % rounds;
         if (b < n_sup) {
             tb.ms[b] = s.blk_scale[t];
-            tb.vs[b] = s.blk_vmax[t];
+            if constexpr (!SGDM) tb.vs[b] = s.blk_vmax[t];
         }
     }
 }
 
 // The last, partial block of a tensor whose size is not a multiple of 128 (a.P - 128 * a.nb
 // elements, an even number).  One lane per element pair, exact arithmetic, reductions through LDS.
-template <bool BF16>
+template <bool BF16, bool SGDM = false>
 __device__ __forceinline__ void b128_tail_block(const Tensor4& a, const Hyper& h, Lds& s) {
     const int64_t e0 = int64_t(a.nb) * 128;
     const int n = int(a.P - e0);                   // 1..127
     const int t = threadIdx.x;
     const bool on = t < (n + 1) / 2;               // this lane's pair: elements e0 + 2t, e0 + 2t + 1
     float mt[2] = {0.0f, 0.0f}, vt[2] = {0.0f, 0.0f};
-    const float sm_old = a.ms[a.nb], sv_old = a.r[a.nb];
+    const float sm_old = a.ms[a.nb], sv_old = SGDM ? 0.0f : a.r[a.nb];
     uint32_t bm = 0, bv = 0;
     if (on) {
         bm = reinterpret_cast<const uint8_t*>(a.mq)[(e0 >> 1) + t];
-        bv = reinterpret_cast<const uint8_t*>(a.vq)[(e0 >> 1) + t];
+        if constexpr (!SGDM) bv = reinterpret_cast<const uint8_t*>(a.vq)[(e0 >> 1) + t];
     }
     for (int k = 0; k < 2; ++k) {
         const int64_t e = e0 + 2 * t + k;
         if (on && e < a.P) {
             const float2 dq = s.deq[bm];
             const float g = load_grad1<BF16>(a.g, e);
-            mt[k] = moment_m(h, (k ? dq.y : dq.x) * sm_old, g);
-            vt[k] = moment_v(h, dequant_v((bv >> (4 * k)) & 15u, sv_old), g);
-            a.p[e] = param_update(h, a.p[e], mt[k], vt[k]);
+            if constexpr (SGDM) {
+                mt[k] = moment_sgdm(h, (k ? dq.y : dq.x) * sm_old, g);
+                a.p[e] = param_sgdm(h, a.p[e], mt[k]);
+            } else {
+                mt[k] = moment_m(h, (k ? dq.y : dq.x) * sm_old, g);
+                vt[k] = moment_v(h, dequant_v((bv >> (4 * k)) & 15u, sv_old), g);
+                a.p[e] = param_update(h, a.p[e], mt[k], vt[k]);
+            }
         }
     }
     s.col[t] = fmaxf(fabsf(mt[0]), fabsf(mt[1]));
@@ -986,25 +1008,25 @@ __device__ __forceinline__ void b128_tail_block(const Tensor4& a, const Hyper& h
         for (int k = 0; k < 2; ++k)
             if (e0 + 2 * t + k < a.P) {
                 qm |= quant_m_code(s.search, mt[k], sm_new) << (4 * k);
-                qv |= quant_v_code(vt[k], sv_new) << (4 * k);
+                if constexpr (!SGDM) qv |= quant_v_code(vt[k], sv_new) << (4 * k);
             }
         reinterpret_cast<uint8_t*>(a.mq)[(e0 >> 1) + t] = uint8_t(qm);
-        reinterpret_cast<uint8_t*>(a.vq)[(e0 >> 1) + t] = uint8_t(qv);
+        if constexpr (!SGDM) reinterpret_cast<uint8_t*>(a.vq)[(e0 >> 1) + t] = uint8_t(qv);
     }
     if (t == 0) {
         a.ms[a.nb] = sm_new;
-        a.r[a.nb] = sv_new;
+        if constexpr (!SGDM) a.r[a.nb] = sv_new;
     }
 }
 
 // workgroups [0, n_wg2) run tiles of whole blocks, workgroup n_wg2 (if n_wg > n_wg2) the partial block
-template <bool BF16>
+template <bool BF16, bool SGDM = false>
 __device__ __forceinline__ void b128_work(const Tensor4& a, const Hyper& h, int wg, Lds& s) {
     if (wg < a.n_wg2) {
-        b128_tile<BF16>(a, h, wg, s);
+        b128_tile<BF16, SGDM>(a, h, wg, s);
     } else {
         load_tables(s);
-        b128_tail_block<BF16>(a, h, s);
+        b128_tail_block<BF16, SGDM>(a, h, s);
     }
 }
 
@@ -1555,6 +1577,21 @@ __device__ __forceinline__ void adamw32_tile(float* p, const void* g, float* m, 
     }
 }
 
+// SGD with momentum on an uncompressed fp32 buffer (tensors that are not quantized)
+template <bool BF16>
+__device__ __forceinline__ void sgdm32_tile(float* p, const void* g, float* m, int64_t n, const Hyper& h, int wg) {
+    const int64_t base = int64_t(wg) * kElemsPerWg32;
+#pragma unroll 4
+    for (int k = 0; k < kElemsPerWg32 / kThreads; ++k) {
+        const int64_t idx = base + int64_t(k) * kThreads + threadIdx.x;
+        if (idx < n) {
+            const float mt = moment_sgdm(h, m[idx], load_grad1<BF16>(g, idx));
+            m[idx] = mt;
+            p[idx] = param_sgdm(h, p[idx], mt);
+        }
+    }
+}
+
 // =====================================================================================================
 // Kernels for one tensor: two launches per step.
 // =====================================================================================================
@@ -1611,6 +1648,18 @@ __global__ __launch_bounds__(kThreads) void factor_update_general(const Tensor4 
     load_tables(s);
     factor_update_general_tile<BF16>(a, h, blockIdx.x, s);
     factor_publish_if_last(a, h, blockIdx.x, gridDim.x, s_last);
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(kThreads) void sgdm4_kernel(const Tensor4 a, const Hyper h) {
+    __shared__ Lds s;
+    const int wg = logical_wg();
+    if (wg < a.n_wg) b128_work<BF16, true>(a, h, wg, s);
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(kThreads) void sgdm32_kernel(float* p, const void* g, float* m, int64_t n, const Hyper h) {
+    sgdm32_tile<BF16>(p, g, m, n, h, blockIdx.x);
 }
 
 template <bool BF16>
@@ -1802,6 +1851,19 @@ __global__ __launch_bounds__(kThreads) void factor_phase_kernel(const Phase ph, 
         else if (a.kind == kFactorFast) factor_stats_tile<BF16>(a, wg, s);
         else factor_stats_general_tile<BF16>(a, wg, a.n_wg, s);
     }
+}
+
+// A plan of SGD-with-momentum tensors (App. E Alg. 2): everything is one pass, so only "A" work exists.
+template <bool BF16>
+__global__ __launch_bounds__(kThreads) void sgdm_phase_kernel(const Phase ph, const Hyper h) {
+    __shared__ Lds s;
+    const int x = logical_wg();
+    if (x >= ph.n_a) return;
+    const Segment sg = find_segment(ph.seg_a, ph.n_seg_a, x);
+    const Tensor4 a = from_table(ph.tensors[sg.tensor]);
+    const int wg = x - sg.wg_begin;
+    if (a.kind == kSgdmFp32) sgdm32_tile<BF16>(a.p, a.g, reinterpret_cast<float*>(a.mq), a.P, h, wg);
+    else b128_work<BF16, true>(a, h, wg, s);
 }
 
 // =====================================================================================================

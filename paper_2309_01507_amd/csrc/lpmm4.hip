@@ -312,6 +312,51 @@ int grid_for(int64_t items, int64_t per_thread, int max_blocks = 0x7FFFFFFF) {
     return int(blocks);
 }
 
+int make_sgdm_hyper(float lr, float momentum, Hyper* h) {
+    if (!finite_nonneg(lr) || !(momentum >= 0.0f && momentum < 1.0f)) return LPMM_EINVAL;
+    *h = Hyper{};
+    h->beta1 = momentum;
+    h->step_size = lr;
+    return LPMM_OK;
+}
+
+int sgdm4_step_impl(bool bf16, void* param, const void* grad, uint8_t* m_codes, float* m_blockscale, int64_t numel,
+                    float lr, float momentum, void* stream) {
+    if (numel < 1 || numel > (int64_t(1) << 37)) return LPMM_EINVAL;
+    if (!param || !grad || !m_codes || !m_blockscale) return LPMM_EINVAL;
+    if (!aligned(param, 16) || !aligned(grad, 16) || !aligned(m_codes, 4) || !aligned(m_blockscale, 4))
+        return LPMM_EINVAL;
+    Hyper h;
+    int rc = make_sgdm_hyper(lr, momentum, &h);
+    if (rc) return rc;
+    DeviceCtx* ctx;
+    rc = current_ctx(&ctx);      // the lookup tables live in device memory filled by init
+    if (rc) return rc;
+    Tensor4 t{};
+    t.p = static_cast<float*>(param);
+    t.g = grad;
+    t.mq = reinterpret_cast<uint32_t*>(m_codes);
+    t.ms = m_blockscale;
+    t.rows = 1;
+    t.cols = numel;
+    t.P = numel;
+    b128_geometry(&t, ctx->n_cu, 0);
+    t.kind = kSgdmBlock;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const bool rec = g_prof.on && g_prof.calls < g_prof.max_calls;
+    const int64_t call = g_prof.calls;
+    if (rec) LPMM_HIP(hipEventRecord(prof_event(call, 0), s));
+    if (bf16) hipLaunchKernelGGL(sgdm4_kernel<true>, dim3(pad8(t.n_wg)), dim3(kThreads), 0, s, t, h);
+    else hipLaunchKernelGGL(sgdm4_kernel<false>, dim3(pad8(t.n_wg)), dim3(kThreads), 0, s, t, h);
+    LPMM_HIP(hipGetLastError());
+    if (rec) {
+        LPMM_HIP(hipEventRecord(prof_event(call, 1), s));
+        LPMM_HIP(hipEventRecord(prof_event(call, 2), s));
+        g_prof.calls = call + 1;
+    }
+    return LPMM_OK;
+}
+
 // shape of a tensor with p >= 2 dimensions as the matrix the kernels see, plus its inner dimensions
 int nd_shape(const int64_t* dims, int ndim, int64_t* rows, int64_t* cols, int64_t* ext, InnerDims* dm) {
     if (!dims || ndim < 2 || ndim > 1 + kMaxInnerDims) return LPMM_EINVAL;
@@ -480,6 +525,7 @@ struct PlanHost {
     std::vector<PhaseLaunch> phases;
     bool bf16 = false;
     bool factor = false;                // the plan's 2-dimensional tensors keep a factorized second moment
+    bool sgdm = false;                  // a plan of SGD-with-momentum tensors (lpmm_sgdm4_step_multi)
     int device = 0;
     // second stream for pass 2 (same priority as any other stream), with its ordering events
     hipStream_t side = nullptr;
@@ -506,7 +552,8 @@ struct PlanLayout {
 bool desc_shape_ok(const lpmm_tensor_desc& d) {
     int64_t shape[2] = {d.rows, d.cols}, r, c;
     return check_shape(shape, &r, &c) == LPMM_OK && (d.kind == LPMM_KIND_4BIT || d.kind == LPMM_KIND_FP32 ||
-                                                     d.kind == LPMM_KIND_4BIT_B128 || d.kind == LPMM_KIND_4BIT_FACTOR);
+                                                     d.kind == LPMM_KIND_4BIT_B128 || d.kind == LPMM_KIND_4BIT_FACTOR ||
+                                                     d.kind == LPMM_KIND_SGDM_4BIT || d.kind == LPMM_KIND_SGDM_FP32);
 }
 
 bool plan_layout(const lpmm_tensor_desc* descs, int64_t n, PlanLayout* L) {
@@ -520,7 +567,11 @@ bool plan_layout(const lpmm_tensor_desc* descs, int64_t n, PlanLayout* L) {
         if (descs[i].kind == LPMM_KIND_4BIT) rank1 = true;
         if (descs[i].kind == LPMM_KIND_4BIT_FACTOR) factor = true;
     }
+    int64_t n_sgdm = 0;
+    for (int64_t i = 0; i < n; ++i)
+        if (descs[i].kind == LPMM_KIND_SGDM_4BIT || descs[i].kind == LPMM_KIND_SGDM_FP32) ++n_sgdm;
     if (rank1 && factor) return false;       // two different optimizers: one plan holds one of them
+    if (n_sgdm != 0 && n_sgdm != n) return false;
     size_t off = 0;
     L->off_tensors = off;   off += size_t(round_up(n * int64_t(sizeof(Tensor4)), 256));
     L->off_counters = off;  off += size_t(n) * kCounterWords * sizeof(unsigned int);
@@ -782,6 +833,52 @@ int lpmm_adamw4_nd_step_bf16g(void* param, const void* grad, uint8_t* m_codes, f
                         beta2, eps, weight_decay, step, stream);
 }
 
+int lpmm_sgdm4_state_sizes(int64_t numel, size_t sizes[2]) {
+    if (numel < 1 || numel > (int64_t(1) << 37) || !sizes) return LPMM_EINVAL;
+    sizes[0] = size_t((numel + 1) / 2);
+    sizes[1] = size_t((numel + LPMM_BLOCK - 1) / LPMM_BLOCK) * sizeof(float);
+    return LPMM_OK;
+}
+
+int lpmm_sgdm4_state_zero(uint8_t* m_codes, float* m_blockscale, int64_t numel, void* stream) {
+    size_t sz[2];
+    const int rc = lpmm_sgdm4_state_sizes(numel, sz);
+    if (rc) return rc;
+    if (!m_codes || !m_blockscale) return LPMM_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int r = fill(m_codes, int64_t(sz[0]), 0x77, (numel & 1) ? int64_t(sz[0]) - 1 : -1, 0x07, s);
+    if (!r) r = fill(m_blockscale, int64_t(sz[1]), 0, -1, 0, s);
+    return r;
+}
+
+int lpmm_sgdm4_step(void* param, const void* grad, uint8_t* m_codes, float* m_blockscale, int64_t numel, float lr,
+                    float momentum, void* stream) {
+    return sgdm4_step_impl(false, param, grad, m_codes, m_blockscale, numel, lr, momentum, stream);
+}
+
+int lpmm_sgdm4_step_bf16g(void* param, const void* grad, uint8_t* m_codes, float* m_blockscale, int64_t numel,
+                          float lr, float momentum, void* stream) {
+    return sgdm4_step_impl(true, param, grad, m_codes, m_blockscale, numel, lr, momentum, stream);
+}
+
+int lpmm_sgdm32_step(void* param, const void* grad, float* m, int64_t numel, int grad_dtype, float lr,
+                     float momentum, void* stream) {
+    if (!param || !grad || !m || numel < 1) return LPMM_EINVAL;
+    if (grad_dtype != LPMM_GRAD_F32 && grad_dtype != LPMM_GRAD_BF16) return LPMM_EINVAL;
+    if (!aligned(param, 4) || !aligned(m, 4) || !aligned(grad, grad_dtype == LPMM_GRAD_F32 ? 4 : 2)) return LPMM_EINVAL;
+    Hyper h;
+    const int rc = make_sgdm_hyper(lr, momentum, &h);
+    if (rc) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int grid = int((numel + kElemsPerWg32 - 1) / kElemsPerWg32);
+    if (grad_dtype == LPMM_GRAD_BF16)
+        hipLaunchKernelGGL(sgdm32_kernel<true>, dim3(grid), dim3(kThreads), 0, s, static_cast<float*>(param), grad, m, numel, h);
+    else
+        hipLaunchKernelGGL(sgdm32_kernel<false>, dim3(grid), dim3(kThreads), 0, s, static_cast<float*>(param), grad, m, numel, h);
+    LPMM_HIP(hipGetLastError());
+    return LPMM_OK;
+}
+
 int lpmm_adamw32_step(void* param, const void* grad, float* m, float* v, int64_t numel, int grad_dtype,
                       float lr, float beta1, float beta2, float eps, float weight_decay, int64_t step,
                       void* stream) {
@@ -908,8 +1005,24 @@ int lpmm_adamw4_plan_build(const lpmm_tensor_desc* descs, int64_t n, int grad_dt
         t.mq = static_cast<uint32_t*>(d.m_state);
         t.vq = static_cast<uint32_t*>(d.v_state);
         if (!d.param || !d.grad || !d.m_state) return LPMM_EINVAL;
-        if (!d.v_state && d.kind != LPMM_KIND_4BIT_FACTOR) return LPMM_EINVAL;
-        if (d.kind == LPMM_KIND_4BIT_FACTOR) {
+        const bool is_sgdm = d.kind == LPMM_KIND_SGDM_4BIT || d.kind == LPMM_KIND_SGDM_FP32;
+        if (!d.v_state && d.kind != LPMM_KIND_4BIT_FACTOR && !is_sgdm) return LPMM_EINVAL;
+        if (d.kind == LPMM_KIND_SGDM_FP32) {
+            if (!aligned(d.param, 4) || !aligned(d.m_state, 4) || !aligned(d.grad, galign)) return LPMM_EINVAL;
+            t.vq = nullptr;
+            t.kind = kSgdmFp32;
+            t.n_wg = t.n_wg2 = int((t.P + kElemsPerWg32 - 1) / kElemsPerWg32);
+            host->sgdm = true;
+        } else if (d.kind == LPMM_KIND_SGDM_4BIT) {
+            if (!d.m_blockscale) return LPMM_EINVAL;
+            if (!aligned(d.param, 16) || !aligned(d.grad, 16) || !aligned(d.m_state, 4) || !aligned(d.m_blockscale, 4))
+                return LPMM_EINVAL;
+            t.vq = nullptr;
+            t.ms = d.m_blockscale;
+            b128_geometry(&t, ctx->n_cu, env_int("LPMM_MULTI_B128_ROUNDS", 8));
+            t.kind = kSgdmBlock;
+            host->sgdm = true;
+        } else if (d.kind == LPMM_KIND_4BIT_FACTOR) {
             if (!d.m_blockscale || !d.v_rowmax || !d.v_colmax) return LPMM_EINVAL;
             if (!aligned(d.param, 16) || !aligned(d.grad, 16) || !aligned(d.m_state, 4) ||
                 !aligned(d.m_blockscale, 4) || !aligned(d.v_rowmax, 4) || !aligned(d.v_colmax, 4))
@@ -984,7 +1097,9 @@ int lpmm_adamw4_plan_build(const lpmm_tensor_desc* descs, int64_t n, int grad_dt
             }
         if (j >= 1)
             for (int64_t i = groups[j - 1].first; i < groups[j - 1].second; ++i) {
-                if (tens[i].kind == kFp32State || tens[i].kind == kQuantBlockV) continue;
+                if (tens[i].kind == kFp32State || tens[i].kind == kQuantBlockV || tens[i].kind == kSgdmBlock ||
+                    tens[i].kind == kSgdmFp32)
+                    continue;
                 pl.ph.seg_b[pl.ph.n_seg_b++] = Segment{pl.ph.n_b, int(i)};
                 pl.ph.n_b += tens[i].n_wg2;
             }
@@ -996,7 +1111,7 @@ int lpmm_adamw4_plan_build(const lpmm_tensor_desc* descs, int64_t n, int grad_dt
         host->phases.push_back(pl);
     }
     // a second stream pays only if some pass 2 has a pass 1 of another group to run beside
-    if (env_int("LPMM_MULTI_STREAMS", 2) >= 2 && groups.size() > 1) {
+    if (env_int("LPMM_MULTI_STREAMS", 2) >= 2 && groups.size() > 1 && !host->sgdm) {
         LPMM_HIP(hipStreamCreateWithFlags(&host->side, hipStreamNonBlocking));
         LPMM_HIP(hipEventCreateWithFlags(&host->ev_fork, hipEventDisableTiming));
         LPMM_HIP(hipEventCreateWithFlags(&host->ev_join, hipEventDisableTiming));
@@ -1030,7 +1145,7 @@ int lpmm_adamw4_step_multi(void* plan, float lr, float beta1, float beta2, float
     }
     int dev = 0;
     LPMM_HIP(hipGetDevice(&dev));
-    if (dev != host->device) return LPMM_EINVAL;
+    if (dev != host->device || host->sgdm) return LPMM_EINVAL;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool bf16 = host->bf16;
     // roles: 0 = A and B work in one launch, 1 = A only, 2 = B only, 3 = A only without rank-1 tensors
@@ -1104,6 +1219,38 @@ int lpmm_adamw4_step_multi(void* plan, float lr, float beta1, float beta2, float
         // a launch that holds only one kind of work takes that kind's (lighter) kernel
         const int roles = pl.ph.n_b == 0 ? (pl.a_has_rank1 ? 1 : 3) : (pl.ph.n_a == 0 ? 2 : 0);
         launch(roles, pl.grid, s, pl);
+        LPMM_HIP(hipGetLastError());
+        if (rec) {
+            LPMM_HIP(hipEventRecord(prof_event(call, 1), s));
+            LPMM_HIP(hipEventRecord(prof_event(call, 2), s));
+            g_prof.calls = call + 1;
+        }
+    }
+    return LPMM_OK;
+}
+
+int lpmm_sgdm4_step_multi(void* plan, float lr, float momentum, void* stream) {
+    Hyper h;
+    const int rc = make_sgdm_hyper(lr, momentum, &h);
+    if (rc) return rc;
+    const PlanHost* host = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_mu);
+        auto it = g_plans.find(plan);
+        if (it == g_plans.end()) return LPMM_EINVAL;
+        host = it->second.get();
+    }
+    int dev = 0;
+    LPMM_HIP(hipGetDevice(&dev));
+    if (dev != host->device || !host->sgdm) return LPMM_EINVAL;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    for (const PhaseLaunch& pl : host->phases) {
+        if (pl.ph.n_a == 0) continue;
+        const bool rec = g_prof.on && g_prof.calls < g_prof.max_calls;
+        const int64_t call = g_prof.calls;
+        if (rec) LPMM_HIP(hipEventRecord(prof_event(call, 0), s));
+        if (host->bf16) hipLaunchKernelGGL(sgdm_phase_kernel<true>, dim3(pl.grid_a), dim3(kThreads), 0, s, pl.ph, h);
+        else hipLaunchKernelGGL(sgdm_phase_kernel<false>, dim3(pl.grid_a), dim3(kThreads), 0, s, pl.ph, h);
         LPMM_HIP(hipGetLastError());
         if (rec) {
             LPMM_HIP(hipEventRecord(prof_event(call, 1), s));

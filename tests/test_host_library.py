@@ -174,3 +174,26 @@ def test_nd_state_sizes_and_argument_errors():
     assert L.lpmm_adamw4_nd_step(*([p] * 6 + [None]), ctypes.addressof(dims), 3, *h, 1, None) == -1
     assert L.lpmm_adamw4_nd_step(*([p] * 7), ctypes.addressof(dims), 1, *h, 1, None) == -1       # one dimension
     assert L.lpmm_adamw4_nd_step(*([p] * 7), ctypes.addressof(dims), 3, *h, 1, None) in (-2, -3) # no GPU here
+
+
+def test_sgdm_state_sizes_and_argument_errors():
+    assert lpmm.lpmm_sgdm4_state_sizes(4096) == [2048, 128]
+    assert lpmm.lpmm_sgdm4_state_sizes(129) == [65, 8]
+    L = lpmm.lib()
+    sizes = (ctypes.c_size_t * 2)()
+    assert L.lpmm_sgdm4_state_sizes(0, ctypes.addressof(sizes)) == -1
+    assert L.lpmm_sgdm4_state_sizes(16, None) == -1
+    buf = ctypes.create_string_buffer(4096 + 256)
+    p = (ctypes.addressof(buf) + 255) // 256 * 256
+    f = ctypes.c_float
+    assert L.lpmm_sgdm4_step(p, p, p, p, 256, f(0.1), f(1.0), None) == -1          # momentum must stay below 1
+    assert L.lpmm_sgdm4_step(p, p, p, p, 256, f(-0.1), f(0.9), None) == -1
+    assert L.lpmm_sgdm4_step(p, p, p, None, 256, f(0.1), f(0.9), None) == -1
+    assert L.lpmm_sgdm4_step(p + 4, p, p, p, 256, f(0.1), f(0.9), None) == -1
+    assert L.lpmm_sgdm4_step(p, p, p, p, 0, f(0.1), f(0.9), None) == -1
+    assert L.lpmm_sgdm4_step(p, p, p, p, 256, f(0.1), f(0.9), None) in (-2, -3)    # well-formed, but no GPU here
+    assert L.lpmm_sgdm32_step(p, p, p, 256, 7, f(0.1), f(0.9), None) == -1         # unknown gradient type
+    assert L.lpmm_sgdm4_step_multi(p, f(0.1), f(0.9), None) == -1                  # not a plan
+    d = lpmm.TensorDesc(p, p, p, p, None, None, None, 1, 256, lpmm.KIND_SGDM_4BIT, 0)
+    a = lpmm.TensorDesc(p, p, p, p, p, p, p, 2, 128, lpmm.KIND_4BIT, 0)
+    assert lpmm.lpmm_adamw4_plan_bytes([d]) > 0 and lpmm.lpmm_adamw4_plan_bytes([d, a]) == 0
