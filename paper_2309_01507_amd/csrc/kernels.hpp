@@ -60,6 +60,8 @@ struct Tensor4 {
     // row are consecutive, and the groups (waves) that run side by side are 2^rs rows apart
     int rs, rs2;
     int tot_slots;          // kFactor*: slots that each of the two float sums is spread over (1, 2, 4 or 8)
+    int flat;               // kQuantFast: pass 1 uses the flat tiling (a group walks along a row)
+    int pad_;
     int c_extra;            // floats behind c_new (and room behind c) that the publishing workgroup moves and clears
                             // along with the column maxima (tensors with more than two dimensions)
 };
@@ -83,7 +85,7 @@ struct Tensor4Table {
     float LPMM_AS_GLOBAL* c_new;
     unsigned int LPMM_AS_GLOBAL* counter;
     int64_t rows, cols, P;
-    int nb, gx, gy, rw, strips, n_wg, kind, strips2, rw2, n_wg2, rs, rs2, tot_slots, c_extra;
+    int nb, gx, gy, rw, strips, n_wg, kind, strips2, rw2, n_wg2, rs, rs2, tot_slots, flat, pad_, c_extra;
 };
 static_assert(sizeof(Tensor4Table) == sizeof(Tensor4), "the table twin must mirror Tensor4");
 __device__ __forceinline__ Tensor4 from_table(const Tensor4Table& t) {
@@ -101,7 +103,7 @@ __device__ __forceinline__ Tensor4 from_table(const Tensor4Table& t) {
     a.rows = t.rows; a.cols = t.cols; a.P = t.P;
     a.nb = t.nb; a.gx = t.gx; a.gy = t.gy; a.rw = t.rw; a.strips = t.strips; a.n_wg = t.n_wg; a.kind = t.kind;
     a.strips2 = t.strips2; a.rw2 = t.rw2; a.n_wg2 = t.n_wg2; a.rs = t.rs; a.rs2 = t.rs2;
-    a.tot_slots = t.tot_slots; a.c_extra = t.c_extra;
+    a.tot_slots = t.tot_slots; a.flat = t.flat; a.pad_ = 0; a.c_extra = t.c_extra;
     return a;
 }
 #else
@@ -127,6 +129,7 @@ struct Lds {
     float2 deq[256];
     SearchEntry search[kBucketsPadded];
     float col[8 * 128];
+    float cold[8 * 128];        // flat tiling of pass 1: the strip's old column maxima / 16
     // per row and column block of the tile: new block scale of m and the block's maximum of v_t.
     // They leave for global memory at the end of the tile, so that the row loop issues the same
     // memory instructions on every path (loads, the parameter store, the code store) and nothing
@@ -566,6 +569,173 @@ __device__ __forceinline__ void pass1_fast_tile(const Tensor4& a, const Hyper& h
         for (int y = 0; y < a.gy; ++y) m = fmaxf(m, s.col[((y * a.gx + gi) << 7) + (t & 127)]);
         const int cbi = geo.strip * a.gx + gi;
         if (cbi < a.nb && m > 0.0f) atomic_max_nonneg(a.c_new + int64_t(cbi) * 128 + (t & 127), m);
+    }
+}
+
+// =====================================================================================================
+// Pass 1, "flat" tiling: a workgroup's tile is rw rows x up to 8 column blocks (4 KiB of parameters
+// per row), and a group walks ALONG a row -- the strip's blocks one after the other, then its next
+// row -- so that each of the 8 groups reads and writes runs of 4 KiB instead of 512 bytes per row.
+// The price: a lane's 4 columns change with every block, so the old column maxima of the strip sit in
+// LDS (read per block) and the running new ones are raised there with LDS atomics.  Rows are dealt to
+// the groups as in the tiling above (spacing 2^rs).  Everything else is pass1_row's arithmetic.
+// =====================================================================================================
+
+constexpr int kFlatBlocks = 8;
+
+template <bool BF16>
+__device__ __forceinline__ Row1<BF16> load_unit(const TileBase& b, const Tensor4& a, int il, int cb, int l) {
+    Row1<BF16> r;
+    const uint32_t off4 = row_offset(il, a.cols, uint32_t(cb) * 128u + uint32_t(l) * 4u) * 4u;
+    r.p = buf_ld_f4_stream(b.rp, off4);
+    r.g = load_grad_regs4<BF16>(b.rg, off4);
+    r.mq = buf_ld_u16(b.rmq, off4 >> 3);
+    r.vq = buf_ld_u16(b.rvq, off4 >> 3);
+    r.s_old = buf_ld_f(b.rms, row_offset(il, a.nb, uint32_t(cb)) * 4u);
+    r.r_old = buf_ld_f(b.rr, uint32_t(il) * 4u);
+    return r;
+}
+
+// One block of one row.  j = block inside the strip, cb = its column block in the tensor; row_run carries the
+// row's maximum of v_t from block to block.
+template <bool BF16, class Mid>
+__device__ __forceinline__ void flat_unit(const Tensor4& a, const Hyper& h, const TileBase& tb, Lds& s,
+                                          const Row1<BF16>& cur, int il, int j, int cb, int l, int nbk,
+                                          bool cols_tame, float& row_run, Mid mid) {
+    float w[4] = {cur.p.x, cur.p.y, cur.p.z, cur.p.w};
+    float g[4];
+    unpack_grad4<BF16>(cur.g, g);
+    float mt[4], vt[4], amax = 0.0f, rmax = 0.0f;
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        const float2 t = s.deq[(uint32_t(cur.mq) >> (8 * k)) & 255u];
+        mt[2 * k] = t.x * cur.s_old;
+        mt[2 * k + 1] = t.y * cur.s_old;
+    }
+    const uint32_t col0 = uint32_t(cb) * 128u + uint32_t(l) * 4u;
+    const bool tame_in = bool(int(cols_tame) & int(scale_is_tame(cur.r_old)));
+    if (__builtin_expect(__ballot(!tame_in) == 0, 1)) {
+        float qf[4];
+        codes_to_float4(cur.vq, qf);
+        const float r16 = cur.r_old * 0.0625f;
+        const float4 c16 = *reinterpret_cast<const float4*>(&s.cold[j * 128 + l * 4]);
+        const float cold16[4] = {c16.x, c16.y, c16.z, c16.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) vt[e] = dequant_v16(qf[e], min_nonneg(r16, cold16[e]));
+    } else {
+        float cold[4];
+        load4(a.c + col0, cold);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) vt[e] = dequant_v((uint32_t(cur.vq) >> (4 * e)) & 15u, fminf(cur.r_old, cold[e]));
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        mt[e] = moment_m(h, mt[e], g[e]);
+        vt[e] = moment_v(h, vt[e], g[e]);
+        w[e] = param_update(h, w[e], mt[e], vt[e]);
+        amax = fmaxf(amax, fabsf(mt[e]));
+        rmax = max_nonneg(rmax, vt[e]);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    mid();
+    __builtin_amdgcn_sched_barrier(0);
+    // running column maxima of the strip: LDS atomics on the float bits (values are >= +0)
+    unsigned int* cbits = reinterpret_cast<unsigned int*>(&s.col[j * 128 + l * 4]);
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+        (void)__hip_atomic_fetch_max(cbits + e, __float_as_uint(vt[e]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    const float s_new = group32_allmax(amax);
+    rmax = group32_allmax(rmax);
+    row_run = j == 0 ? rmax : max_nonneg(row_run, rmax);
+
+    uint32_t mq_new = 0;
+    uint32_t dist = scale_is_tame(s_new) ? 0xFFFFFFFFu : 0u;
+    {
+        const float inv_s = approx_inv(s_new);
+#pragma unroll
+        for (int e = 0; e < 4; e += 2) {
+            uint32_t da, db;
+            mq_new |= quant_m_code_fast(s.search, mt[e], inv_s, da) << (4 * e);
+            mq_new |= quant_m_code_fast(s.search, mt[e + 1], inv_s, db) << (4 * e + 4);
+            dist = min(min(dist, da), db);
+        }
+    }
+    if (__builtin_expect(__ballot(dist < kMinDistM) != 0, 0)) {
+        mq_new = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) mq_new |= quant_m_code(s.search, mt[e], s_new) << (4 * e);
+    }
+    const uint32_t off4 = row_offset(il, a.cols, col0) * 4u;
+    st_stream4(tb.p, off4, make_float4(w[0], w[1], w[2], w[3]));
+    st<uint16_t>(tb.mq, off4 >> 3, uint16_t(mq_new));
+    if (l == 0) {
+        s.blk_scale[il * kFlatBlocks + j] = s_new;
+        if (j == nbk - 1) s.blk_vmax[il] = row_run;
+    }
+}
+
+// a.strips = ceil(nb / 8) strips, a.rw rows per tile (at most 64), a.rs the row spacing, a.n_wg workgroups
+template <bool BF16>
+__device__ __forceinline__ void pass1_flat_tile(const Tensor4& a, const Hyper& h, int wg, Lds& s) {
+    const int strip = wg % a.strips, tile = wg / a.strips;
+    const int grp = threadIdx.x >> 5, l = threadIdx.x & 31;
+    const int cb0 = strip * kFlatBlocks;
+    const int left_b = a.nb - cb0;
+    const int nbk = left_b < kFlatBlocks ? left_b : kFlatBlocks;         // blocks of this strip, 1..8
+    const int64_t row0 = int64_t(tile) * a.rw;
+    const int64_t left = a.rows - row0;
+    const int n = left < a.rw ? int(left) : a.rw;
+    const TileBase tb = tile_base<BF16>(a, row0, n);
+    // units of this group in the order it takes them: unit q = block q % nbk of its row number q / nbk
+    const int rs = a.rs;
+    const int row_g = grp << rs, hop = kGroups << rs, low = (1 << rs) - 1;
+    auto row = [&](int k) { return row_g + (k & low) + (k >> rs) * hop; };
+    const uint32_t inv_nbk = (65536u + uint32_t(nbk) - 1u) / uint32_t(nbk);   // q / nbk == (q * inv_nbk) >> 16 for q < 9000
+    auto krow = [&](int q) { return int((uint32_t(q) * inv_nbk) >> 16); };
+    auto blk = [&](int q) { return q - krow(q) * nbk; };
+    auto fetch = [&](int q) { return load_unit<BF16>(tb, a, row(krow(q)), cb0 + blk(q), l); };
+    int q = 0;
+    Row1<BF16> r0 = fetch(0);
+    Row1<BF16> r1 = fetch(1);
+    Row1<BF16> r2;
+    // the strip's old column maxima (scaled) and zeroed running maxima into LDS, then the tables
+    bool tame = true;
+    for (int t = threadIdx.x; t < nbk * 128; t += kThreads) {
+        const float c = a.c[cb0 * 128 + t];
+        tame = bool(int(tame) & int(scale_is_tame(c)));
+        s.cold[t] = c * 0.0625f;
+        s.col[t] = 0.0f;
+    }
+    const bool cols_tame = !__syncthreads_or(int(!tame));
+    load_tables(s);
+    __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
+    float row_run = 0.0f;
+    auto none = [] {};
+    auto unit = [&](const Row1<BF16>& cur, int qq, auto mid) {
+        flat_unit<BF16>(a, h, tb, s, cur, row(krow(qq)), blk(qq), cb0 + blk(qq), l, nbk, cols_tame, row_run, mid);
+    };
+    while (row(krow(q + 2)) < n) {
+        unit(r0, q, [&] { r2 = fetch(q + 2); });
+        unit(r1, q + 1, [&] { r0 = fetch(q + 3); });
+        unit(r2, q + 2, [&] { r1 = fetch(q + 4); });
+        q += 3;
+    }
+    if (row(krow(q)) < n) {
+        unit(r0, q, none);
+        if (row(krow(q + 1)) < n) unit(r1, q + 1, none);
+    }
+    __syncthreads();
+    for (int t = threadIdx.x; t < n * kFlatBlocks; t += kThreads) {
+        const int il = t / kFlatBlocks, j = t % kFlatBlocks;
+        if (j < nbk) st<float>(tb.ms, row_offset(il, a.nb, uint32_t(cb0 + j)) * 4u, s.blk_scale[t]);
+    }
+    for (int t = threadIdx.x; t < n; t += kThreads) {
+        const float m = s.blk_vmax[t];
+        if (m > 0.0f) atomic_max_nonneg(tb.r_new + t, m);
+    }
+    for (int t = threadIdx.x; t < nbk * 128; t += kThreads) {
+        const float m = s.col[t];
+        if (m > 0.0f) atomic_max_nonneg(a.c_new + cb0 * 128 + t, m);
     }
 }
 
@@ -1601,7 +1771,8 @@ __global__ __launch_bounds__(kThreads) void pass1_fast(const Tensor4 a, const Hy
     __shared__ Lds s;
     const int wg = logical_wg();
     if (wg >= a.n_wg) return;
-    pass1_fast_tile<BF16, false>(a, h, wg, s);
+    if (a.flat) pass1_flat_tile<BF16>(a, h, wg, s);
+    else pass1_fast_tile<BF16, false>(a, h, wg, s);
 }
 
 template <bool BF16>
@@ -1750,7 +1921,8 @@ __global__ __launch_bounds__(kThreads) void phase_kernel(const Phase ph, const H
         } else if (ROLES == 3) {
             // not reached: the host launches this variant only for groups without rank-1 tensors
         } else if (a.kind == kQuantFast) {
-            pass1_fast_tile<BF16, false>(a, h, wg, s);
+            if (a.flat) pass1_flat_tile<BF16>(a, h, wg, s);
+            else pass1_fast_tile<BF16, false>(a, h, wg, s);
         } else {
             load_tables(s);
             pass1_general_tile<BF16>(a, h, wg, s);

@@ -131,7 +131,7 @@ int row_spacing_log2(int64_t row_bytes, int64_t rows_per_tile, int groups, const
     return 0;
 }
 
-void fast_geometry(Tensor4* a, int n_cu, int64_t rw_hint, int64_t rw2_hint, int grad_bytes) {
+void fast_geometry(Tensor4* a, int n_cu, int64_t rw_hint, int64_t rw2_hint, int grad_bytes, bool flat_default = false) {
     a->nb = int(a->cols / LPMM_BLOCK);
     int gx = env_int("LPMM_GX", 1);
     if (gx < 1 || gx > kGroups || (gx & (gx - 1))) gx = 1;
@@ -140,7 +140,7 @@ void fast_geometry(Tensor4* a, int n_cu, int64_t rw_hint, int64_t rw2_hint, int 
     a->gy = kGroups / gx;
     a->strips = a->nb / gx;
     int64_t rw = env_int("LPMM_RW", 0);
-    if (rw <= 0) rw = rw_hint;
+    if (rw <= 0) rw = rw_hint < 0 ? 64 : rw_hint;       // rw_hint: 0 = a tensor on its own (sized below), -1 = in a plan
     if (rw <= 0) {
         // tall tiles amortize a workgroup's start-up and its column atomics; shrink them only as
         // far as needed to give every CU a couple of workgroups
@@ -157,6 +157,28 @@ void fast_geometry(Tensor4* a, int n_cu, int64_t rw_hint, int64_t rw2_hint, int 
     a->rw = int(rw);
     a->n_wg = int(a->strips * ((a->rows + rw - 1) / rw));
     a->rs = row_spacing_log2(a->cols * 4, rw, a->gy, "LPMM_RS");      // the parameters' rows
+    a->flat = 0;
+    // Flat tiling of pass 1 (strips of 8 column blocks, the 8 groups take rows, each walks along its row): the
+    // caller decides (flat_default); LPMM_FLAT = 0 / 1 overrides.
+    const int flat_env = env_int("LPMM_FLAT", -1);
+    const bool want_flat = flat_env >= 0 ? flat_env != 0 : flat_default;
+    if (want_flat && a->kind == kQuantFast) {
+        a->flat = 1;
+        a->gx = 1; a->gy = kGroups;
+        a->strips = (a->nb + kFlatBlocks - 1) / kFlatBlocks;
+        int64_t rwf = env_int("LPMM_RW", 0);
+        if (rwf <= 0) rwf = rw_hint > 0 ? rw_hint : 32;
+        if (rwf > 64) rwf = 64;                                   // rw * 8 block results are staged in LDS
+        const int64_t capf = (int64_t(1) << 29) / a->cols;
+        if (rwf > capf) rwf = capf;
+        rwf = round_up(rwf, kGroups);
+        if (rwf > capf || rwf > 64) rwf -= kGroups;
+        if (rwf > a->rows) rwf = round_up(a->rows, kGroups);
+        if (rwf < kGroups) rwf = kGroups;
+        a->rw = int(rwf);
+        a->n_wg = int(a->strips * ((a->rows + rwf - 1) / rwf));
+        a->rs = row_spacing_log2(a->cols * 4, rwf, kGroups, "LPMM_RS");
+    }
     // pass 2: strips of 256 columns, a wave per row
     a->strips2 = (a->nb + 1) / 2;
     int64_t rw2 = env_int("LPMM_RW2", 0);
@@ -441,6 +463,7 @@ int nd_step_impl(bool bf16, void* param, const void* grad, uint8_t* m_codes, flo
 void factor_geometry(Tensor4* a, int n_cu, int64_t rw_hint, int64_t rw2_hint, int grad_bytes, bool fast,
                      int tot_slots) {
     a->tot_slots = tot_slots;
+    a->kind = fast ? kFactorFast : kFactorGeneral;
     if (fast) {
         fast_geometry(a, n_cu, rw_hint, rw2_hint, grad_bytes);
         if (a->rw2 > kMaxRowSlots) {          // row sums of a statistics tile are staged in LDS
@@ -992,8 +1015,30 @@ int lpmm_adamw4_plan_build(const lpmm_tensor_desc* descs, int64_t n, int grad_dt
     float* d_floats = reinterpret_cast<float*>(dplan + L.off_floats);
     unsigned int* d_counters = reinterpret_cast<unsigned int*>(dplan + L.off_counters);
 
-    const int64_t rw_hint = env_int("LPMM_MULTI_RW", 64);
+    const int64_t rw_hint = env_int("LPMM_MULTI_RW", -1);      // -1: the plan defaults (64 rows, 32 for the flat tiling)
     const int64_t rw2_hint = env_int("LPMM_MULTI_RW2", 128);
+    // Flat tiling of pass 1 for the large tensors of this plan?  Measured: 3-4 % faster on the 7B-shaped set, where
+    // pass 1 runs beside pass 2 of the previous group; 4 % slower for one large tensor alone (one group, the passes
+    // run one after the other); slower on sets of small tensors, whose tiles become too few; and a launch that
+    // mixes many cheap tiles with a few four times more expensive flat ones loses 20 % to imbalance between the
+    // XCDs.  So: only in plans with several groups whose rank-1 parameters are at least 90 % in large tensors.
+    constexpr int64_t kFlatMinElems = int64_t(1) << 23;
+    bool plan_flat = false;
+    {
+        const int64_t gp = int64_t(env_int("LPMM_PHASE_MPARAMS", 2048)) << 20;
+        int64_t p_rank1 = 0, p_big = 0, acc = 0, in_group = 0, n_groups = 0;
+        for (int64_t i = 0; i < n; ++i) {
+            const int64_t P = descs[i].rows * descs[i].cols;
+            if (descs[i].kind == LPMM_KIND_4BIT && fast_eligible(descs[i].cols, descs[i].v_colmax)) {
+                p_rank1 += P;
+                if (P >= kFlatMinElems) p_big += P;
+            }
+            if (in_group == 0 || in_group >= kMaxSeg || acc + P > gp) { ++n_groups; acc = 0; in_group = 0; }
+            acc += P;
+            ++in_group;
+        }
+        plan_flat = n_groups > 1 && p_rank1 > 0 && p_big * 10 >= p_rank1 * 9;
+    }
     int64_t fofs = 0;
     for (int64_t i = 0; i < n; ++i) {
         const lpmm_tensor_desc& d = descs[i];
@@ -1068,7 +1113,8 @@ int lpmm_adamw4_plan_build(const lpmm_tensor_desc* descs, int64_t n, int grad_dt
             t.counter = d_counters + i * kCounterWords;
             if (fast_eligible(d.cols, d.v_colmax)) {
                 t.kind = kQuantFast;
-                fast_geometry(&t, ctx->n_cu, rw_hint, rw2_hint, grad_dtype == LPMM_GRAD_BF16 ? 2 : 4);
+                fast_geometry(&t, ctx->n_cu, rw_hint, rw2_hint, grad_dtype == LPMM_GRAD_BF16 ? 2 : 4,
+                              plan_flat && t.P >= kFlatMinElems);
             } else {
                 t.kind = kQuantGeneral;
                 t.n_wg = t.n_wg2 = int((((t.P + 7) / 8) + kThreads - 1) / kThreads);

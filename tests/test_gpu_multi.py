@@ -24,7 +24,7 @@ def _announce(request):
 
 def _run_set(specs, recipe, bf16, steps, seed, env=None):
     """specs: list of workloads.TensorSpec.  Runs `steps` multi-tensor steps and the oracle side by side."""
-    for k in ("LPMM_PHASE_MPARAMS", "LPMM_MULTI_RW"):
+    for k in ("LPMM_PHASE_MPARAMS", "LPMM_MULTI_RW", "LPMM_FLAT"):
         os.environ.pop(k, None)
     os.environ.update(env or {})
     try:
@@ -77,7 +77,8 @@ def _mini_transformer():
     return out
 
 
-@pytest.mark.parametrize("env", [{}, {"LPMM_PHASE_MPARAMS": "1"}, {"LPMM_PHASE_MPARAMS": "1", "LPMM_MULTI_RW": "8"}])
+@pytest.mark.parametrize("env", [{}, {"LPMM_PHASE_MPARAMS": "1"}, {"LPMM_PHASE_MPARAMS": "1", "LPMM_MULTI_RW": "8"},
+                                 {"LPMM_PHASE_MPARAMS": "1", "LPMM_FLAT": "1"}, {"LPMM_FLAT": "1", "LPMM_MULTI_RW": "24"}])
 def test_multi_matches_oracle_fp32_grads(env):
     """Default grouping (everything in one group), and tiny groups so that many phases overlap
     pass 1 of one group with pass 2 of the previous one."""

@@ -149,7 +149,7 @@ def test_other_hyperparameters(hp):
     assert run_parity(128, 256, steps=5, recipe="col_lognormal", seed=6, hp=hp) == 0
 
 
-ALL_KNOBS = ("LPMM_GX", "LPMM_RW", "LPMM_RW2", "LPMM_RS", "LPMM_RS2", "LPMM_FORCE_GENERAL")
+ALL_KNOBS = ("LPMM_GX", "LPMM_RW", "LPMM_RW2", "LPMM_RS", "LPMM_RS2", "LPMM_FORCE_GENERAL", "LPMM_FLAT")
 
 
 def test_launch_geometry_does_not_change_results():
@@ -163,6 +163,7 @@ def test_launch_geometry_does_not_change_results():
     knobs = [{}, {"LPMM_GX": "1"}, {"LPMM_GX": "8", "LPMM_RW": "16"}, {"LPMM_GX": "2", "LPMM_RW": "300"},
              {"LPMM_RS": "0", "LPMM_RS2": "0"}, {"LPMM_RW": "64", "LPMM_RS": "3", "LPMM_RW2": "32", "LPMM_RS2": "3"},
              {"LPMM_RW": "40", "LPMM_RS": "2", "LPMM_RW2": "24", "LPMM_RS2": "1"},
+             {"LPMM_FLAT": "1"}, {"LPMM_FLAT": "1", "LPMM_RW": "16", "LPMM_RS": "1"}, {"LPMM_FLAT": "1", "LPMM_RW": "300"},
              {"LPMM_FORCE_GENERAL": "1"}]
     try:
         for env in knobs:
