@@ -20,6 +20,8 @@
 // memory-bound pass 1.
 #pragma once
 
+#include <cstddef>
+
 #include "device_math.hpp"
 
 namespace lpmm {
@@ -1238,84 +1240,129 @@ __device__ __forceinline__ void store_codes(uint32_t* q, const LaneIo& io, uint3
     for (int k = 0; k < (io.nv + 1) / 2; ++k) b[k] = uint8_t(w >> (8 * k));
 }
 
+// A workgroup of the general pass 1 takes a.rw (1..16, chosen by the host) consecutive chunks of 2048 elements.  The maxima of v_t
+// are first combined in LDS (integer atomics on the float bits), indexed by the column -- possible when the
+// tensor has at most kGenColsLds columns, which is the usual case for shapes that miss the fast path (narrow
+// matrices) -- and by the row relative to the workgroup's first row; one global atomic per column and row
+// that the workgroup touched follows at its end.  Wider tensors, or rows shorter than 9 elements, send their
+// maxima to global atomics directly (read first, skipped when they cannot raise the value).
+constexpr int kGenChunkElems = kThreads * 8;             // a.rw chunks of this many elements per workgroup
+constexpr int kGenMaxChunks = 16;
+constexpr int kGenColsLds = 2048;                        // s.col and s.cold together
+constexpr int kGenRowsLds = 2 * kMaxRowSlots;            // s.blk_scale and s.blk_vmax together
+
 template <bool BF16>
 __device__ __forceinline__ void pass1_general_tile(const Tensor4& a, const Hyper& h, int wg, Lds& s) {
-    const int64_t t = int64_t(wg) * kThreads + threadIdx.x;
-    const int64_t block = t >> 4;                       // uniform over the group
-    if (block * 128 >= a.P) return;                     // whole group past the end
-    const LaneIo io = lane_io(a.P, a.cols, t);
+    static_assert(offsetof(Lds, cold) == offsetof(Lds, col) + sizeof(float) * 1024, "col and cold are one array here");
+    static_assert(offsetof(Lds, blk_vmax) == offsetof(Lds, blk_scale) + sizeof(float) * kMaxRowSlots, "row slots");
+    unsigned int* col_l = reinterpret_cast<unsigned int*>(s.col);          // [kGenColsLds]
+    unsigned int* row_l = reinterpret_cast<unsigned int*>(s.blk_scale);    // [kGenRowsLds]
+    const int n_chunks = a.rw;
+    const int64_t e_first = int64_t(wg) * n_chunks * kGenChunkElems;
+    const int64_t e_end = e_first + int64_t(n_chunks) * kGenChunkElems < a.P ? e_first + int64_t(n_chunks) * kGenChunkElems : a.P;
+    const int64_t i0 = e_first / a.cols;                                   // first row this workgroup touches
+    const int64_t n_rows_wg = (e_end - 1) / a.cols - i0 + 1;
+    const bool cols_in_lds = a.cols <= kGenColsLds;
+    const bool rows_in_lds = n_rows_wg <= kGenRowsLds;
+    if (cols_in_lds)
+        for (int t = threadIdx.x; t < int(a.cols); t += kThreads) col_l[t] = 0u;
+    if (rows_in_lds)
+        for (int t = threadIdx.x; t < int(n_rows_wg); t += kThreads) row_l[t] = 0u;
+    load_tables(s);                                                        // its barrier covers the zeroing too
+    auto raise_col = [&](int64_t j, float v) {
+        if (cols_in_lds) (void)__hip_atomic_fetch_max(col_l + j, __float_as_uint(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        else raise_max(a.c_new + j, v);
+    };
+    auto raise_row = [&](int64_t i, float v) {
+        if (rows_in_lds) (void)__hip_atomic_fetch_max(row_l + (i - i0), __float_as_uint(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        else raise_max(a.r_new + i, v);
+    };
+    for (int c = 0; c < n_chunks; ++c) {
+        const int64_t t = (int64_t(wg) * n_chunks + c) * kThreads + threadIdx.x;
+        const int64_t block = t >> 4;                       // uniform over the 16 lanes of a block
+        const bool alive = block * 128 < a.P;               // dead lanes are the highest of the last chunk
+        const LaneIo io = lane_io(a.P, a.cols, t);
+        float w[8], g[8];
+        if (io.nv == 8) {
+            load8(a.p + io.base, w);
+            load_grad8<BF16>(a.g, io.base, g);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                w[e] = e < io.nv ? a.p[io.base + e] : 0.0f;
+                g[e] = e < io.nv ? load_grad1<BF16>(a.g, io.base + e) : 0.0f;
+            }
+        }
+        const uint32_t mq = io.nv ? load_codes(a.mq, io) : 0u;
+        const uint32_t vq = io.nv ? load_codes(a.vq, io) : 0u;
+        const float s_old = alive ? a.ms[block] : 0.0f;
 
-    float w[8], g[8];
-    if (io.nv == 8) {
-        load8(a.p + io.base, w);
-        load_grad8<BF16>(a.g, io.base, g);
-    } else {
+        float mt[8], amax = 0.0f;
+        int64_t i = io.i, j = io.j;
+        int64_t run_row = io.i;
+        float run_max = 0.0f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            w[e] = e < io.nv ? a.p[io.base + e] : 0.0f;
-            g[e] = e < io.nv ? load_grad1<BF16>(a.g, io.base + e) : 0.0f;
+            if (e < io.nv) {
+                const float2 tt = s.deq[(mq >> (8 * (e >> 1))) & 255u];
+                const float m_prev = ((e & 1) ? tt.y : tt.x) * s_old;
+                const float v_prev = dequant_v((vq >> (4 * e)) & 15u, fminf(a.r[i], a.c[j]));
+                mt[e] = moment_m(h, m_prev, g[e]);
+                const float vt = moment_v(h, v_prev, g[e]);
+                w[e] = param_update(h, w[e], mt[e], vt);
+                amax = fmaxf(amax, fabsf(mt[e]));
+                if (i != run_row) { raise_row(run_row, run_max); run_row = i; run_max = 0.0f; }
+                run_max = fmaxf(run_max, vt);
+                raise_col(j, vt);
+                if (++j == a.cols) { j = 0; ++i; }
+            } else {
+                mt[e] = 0.0f;
+            }
         }
-    }
-    const uint32_t mq = load_codes(a.mq, io);
-    const uint32_t vq = load_codes(a.vq, io);
-    const float s_old = a.ms[block];
-
-    float mt[8], amax = 0.0f;
-    int64_t i = io.i, j = io.j;
-    int64_t run_row = io.i;
-    float run_max = 0.0f;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        if (e < io.nv) {
-            const float2 tt = s.deq[(mq >> (8 * (e >> 1))) & 255u];
-            const float m_prev = ((e & 1) ? tt.y : tt.x) * s_old;
-            const float v_prev = dequant_v((vq >> (4 * e)) & 15u, fminf(a.r[i], a.c[j]));
-            mt[e] = moment_m(h, m_prev, g[e]);
-            const float vt = moment_v(h, v_prev, g[e]);
-            w[e] = param_update(h, w[e], mt[e], vt);
-            amax = fmaxf(amax, fabsf(mt[e]));
-            if (i != run_row) { raise_max(a.r_new + run_row, run_max); run_row = i; run_max = 0.0f; }
-            run_max = fmaxf(run_max, vt);
-            raise_max(a.c_new + j, vt);
-            if (++j == a.cols) { j = 0; ++i; }
-        } else {
-            mt[e] = 0.0f;
+        // The lane's last row usually is its neighbours' too (rows are contiguous runs of lanes): combine
+        // over the wave first, one atomic per row and wave.
+        {
+            const int lane = threadIdx.x & 63;
+            long long rr = io.nv ? (long long)run_row : -1ll - lane;
+            float rm = run_max;
+            for (int d = 1; d < 64; d <<= 1) {
+                const float om = __shfl_down(rm, d);
+                const long long orow = __shfl_down(rr, d);
+                if (lane + d < 64 && orow == rr) rm = fmaxf(rm, om);
+            }
+            const long long prev = __shfl_up(rr, 1);
+            if (io.nv && (lane == 0 || prev != rr)) raise_row(rr, rm);
         }
-    }
-    // The lane's last row usually is its neighbours' too (rows are contiguous runs of lanes): combine
-    // over the wave first, one atomic per row and wave.  (Atomics on one address, and on one 128-byte
-    // line, queue up behind each other.)  Lanes that returned above are the wave's highest.
-    {
-        const int lane = threadIdx.x & 63;
-        const uint64_t act = __ballot(true);
-        long long rr = io.nv ? (long long)run_row : -1ll - lane;
-        float rm = run_max;
-        for (int d = 1; d < 64; d <<= 1) {
-            const float om = __shfl_down(rm, d);
-            const long long orow = __shfl_down(rr, d);
-            if (lane + d < 64 && ((act >> (lane + d)) & 1) && orow == rr) rm = fmaxf(rm, om);
-        }
-        const long long prev = __shfl_up(rr, 1);
-        if (io.nv && (lane == 0 || prev != rr)) raise_max(a.r_new + rr, rm);
-    }
 
-    const float s_new = row16_allmax(amax);
-    uint32_t mq_new = 0;
-#pragma unroll
-    for (int e = 0; e < 8; ++e)
-        if (e < io.nv) mq_new |= quant_m_code(s.search, mt[e], s_new) << (4 * e);
-
-    if (io.nv == 8) {
-        float4* pp = reinterpret_cast<float4*>(a.p + io.base);
-        pp[0] = make_float4(w[0], w[1], w[2], w[3]);
-        pp[1] = make_float4(w[4], w[5], w[6], w[7]);
-    } else {
+        const float s_new = row16_allmax(amax);
+        uint32_t mq_new = 0;
 #pragma unroll
         for (int e = 0; e < 8; ++e)
-            if (e < io.nv) a.p[io.base + e] = w[e];
+            if (e < io.nv) mq_new |= quant_m_code(s.search, mt[e], s_new) << (4 * e);
+
+        if (io.nv == 8) {
+            float4* pp = reinterpret_cast<float4*>(a.p + io.base);
+            pp[0] = make_float4(w[0], w[1], w[2], w[3]);
+            pp[1] = make_float4(w[4], w[5], w[6], w[7]);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                if (e < io.nv) a.p[io.base + e] = w[e];
+        }
+        if (io.nv) store_codes(a.mq, io, mq_new);
+        if (alive && (threadIdx.x & 15) == 0) a.ms[block] = s_new;
     }
-    if (io.nv) store_codes(a.mq, io, mq_new);
-    if ((threadIdx.x & 15) == 0) a.ms[block] = s_new;
+    __syncthreads();
+    if (cols_in_lds)
+        for (int t = threadIdx.x; t < int(a.cols); t += kThreads) {
+            const unsigned int m = col_l[t];
+            if (m) atomicMax(reinterpret_cast<unsigned int*>(a.c_new) + t, m);
+        }
+    if (rows_in_lds)
+        for (int t = threadIdx.x; t < int(n_rows_wg); t += kThreads) {
+            const unsigned int m = row_l[t];
+            if (m) atomicMax(reinterpret_cast<unsigned int*>(a.r_new) + i0 + t, m);
+        }
 }
 
 template <bool BF16>
@@ -1628,13 +1675,39 @@ __device__ __forceinline__ void factor_publish_if_last(const Tensor4& a, const H
 }
 
 // General path of the factorized form (any rows x cols): lane t owns flat elements [8t, 8t+8), row and
-// column tracked per element, one atomic per element and column.  Correct, not tuned.
+// column tracked per element.  The statistics pass works like the general pass 1: a.rw consecutive chunks of
+// 2048 elements per workgroup, sums combined in LDS (float atomics) by column (tensors of at most 2048
+// columns) and by row relative to the workgroup's first row, one global atomic per touched column and row at
+// the end; wider tensors add straight to global memory.
 template <bool BF16>
 __device__ __forceinline__ void factor_stats_general_tile(const Tensor4& a, int wg, int n_wg, Lds& s) {
-    const int64_t t = int64_t(wg) * kThreads + threadIdx.x;
-    const LaneIo io = lane_io(a.P, a.cols, t);
+    float* col_l = s.col;                  // [kGenColsLds] (col and cold)
+    float* row_l = s.blk_scale;            // [kGenRowsLds] (blk_scale and blk_vmax)
+    const int n_chunks = a.rw;
+    const int64_t e_first = int64_t(wg) * n_chunks * kGenChunkElems;
+    const int64_t e_end = e_first + int64_t(n_chunks) * kGenChunkElems < a.P ? e_first + int64_t(n_chunks) * kGenChunkElems : a.P;
+    const int64_t i0 = e_first / a.cols;
+    const int64_t n_rows_wg = (e_end - 1) / a.cols - i0 + 1;
+    const bool cols_in_lds = a.cols <= kGenColsLds;
+    const bool rows_in_lds = n_rows_wg <= kGenRowsLds;
+    if (cols_in_lds)
+        for (int t = threadIdx.x; t < int(a.cols); t += kThreads) col_l[t] = 0.0f;
+    if (rows_in_lds)
+        for (int t = threadIdx.x; t < int(n_rows_wg); t += kThreads) row_l[t] = 0.0f;
+    __syncthreads();
+    auto add_col = [&](int64_t j, float v) {
+        if (cols_in_lds) (void)__hip_atomic_fetch_add(col_l + j, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        else atomic_add_f32(a.c_new + j, v);
+    };
+    auto add_row = [&](int64_t i, float v) {
+        if (rows_in_lds) (void)__hip_atomic_fetch_add(row_l + (i - i0), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        else atomic_add_f32(a.r_new + i, v);
+    };
     float part = 0.0f, old = 0.0f;
-    if (io.nv) {
+    const int lane = threadIdx.x & 63;
+    for (int c = 0; c < n_chunks; ++c) {
+        const int64_t t = (int64_t(wg) * n_chunks + c) * kThreads + threadIdx.x;
+        const LaneIo io = lane_io(a.P, a.cols, t);
         float g[8];
         if (io.nv == 8) {
             load_grad8<BF16>(a.g, io.base, g);
@@ -1648,25 +1721,46 @@ __device__ __forceinline__ void factor_stats_general_tile(const Tensor4& a, int 
         for (int e = 0; e < 8; ++e) {
             if (e < io.nv) {
                 const float sq = g[e] * g[e];
-                if (i != run_row) { atomic_add_f32(a.r_new + run_row, run); run_row = i; run = 0.0f; }
+                if (i != run_row) { add_row(run_row, run); run_row = i; run = 0.0f; }
                 run += sq;
                 part += sq;
-                atomic_add_f32(a.c_new + j, sq);
+                add_col(j, sq);
                 if (++j == a.cols) { j = 0; ++i; }
             }
         }
-        atomic_add_f32(a.r_new + run_row, run);
+        // the lane's last row usually is its neighbours' too: add up over the wave first (rows are contiguous
+        // runs of lanes, so lane k ends up with the sum over lanes k.. of its row), one atomic per row and wave
+        long long rr = io.nv ? (long long)run_row : -1ll - lane;
+        float rsum = run;
+        for (int d = 1; d < 64; d <<= 1) {
+            const float os = __shfl_down(rsum, d);
+            const long long orow = __shfl_down(rr, d);
+            if (lane + d < 64 && orow == rr) rsum += os;
+        }
+        const long long prev = __shfl_up(rr, 1);
+        if (io.nv && (lane == 0 || prev != rr)) add_row(rr, rsum);
     }
-    for (int64_t i = t; i < a.rows; i += int64_t(n_wg) * kThreads) old += a.r[i];
+    for (int64_t i = int64_t(wg) * kThreads + threadIdx.x; i < a.rows; i += int64_t(n_wg) * kThreads) old += a.r[i];
     part = wave_sum(part);
     old = wave_sum(old);
-    if ((threadIdx.x & 63) == 0) { s.col[threadIdx.x >> 6] = part; s.col[8 + (threadIdx.x >> 6)] = old; }
+    __shared__ float s_tot[2 * kThreads / 64];
+    if (lane == 0) { s_tot[threadIdx.x >> 6] = part; s_tot[4 + (threadIdx.x >> 6)] = old; }
     __syncthreads();
     if (threadIdx.x == 0) {
         float* tot = reinterpret_cast<float*>(a.counter);
-        atomic_add_f32(tot + tot_new_word(wg & (a.tot_slots - 1)), (s.col[0] + s.col[1]) + (s.col[2] + s.col[3]));
-        atomic_add_f32(tot + tot_old_word(wg & (a.tot_slots - 1)), (s.col[8] + s.col[9]) + (s.col[10] + s.col[11]));
+        atomic_add_f32(tot + tot_new_word(wg & (a.tot_slots - 1)), (s_tot[0] + s_tot[1]) + (s_tot[2] + s_tot[3]));
+        atomic_add_f32(tot + tot_old_word(wg & (a.tot_slots - 1)), (s_tot[4] + s_tot[5]) + (s_tot[6] + s_tot[7]));
     }
+    if (cols_in_lds)
+        for (int t = threadIdx.x; t < int(a.cols); t += kThreads) {
+            const float v = col_l[t];
+            if (v != 0.0f) atomic_add_f32(a.c_new + t, v);
+        }
+    if (rows_in_lds)
+        for (int t = threadIdx.x; t < int(n_rows_wg); t += kThreads) {
+            const float v = row_l[t];
+            if (v != 0.0f) atomic_add_f32(a.r_new + i0 + t, v);
+        }
 }
 
 template <bool BF16>
@@ -1836,7 +1930,6 @@ __global__ __launch_bounds__(kThreads) void sgdm32_kernel(float* p, const void* 
 template <bool BF16>
 __global__ __launch_bounds__(kThreads) void pass1_general(const Tensor4 a, const Hyper h) {
     __shared__ Lds s;
-    load_tables(s);
     pass1_general_tile<BF16>(a, h, blockIdx.x, s);
 }
 
@@ -1924,7 +2017,6 @@ __global__ __launch_bounds__(kThreads) void phase_kernel(const Phase ph, const H
             if (a.flat) pass1_flat_tile<BF16>(a, h, wg, s);
             else pass1_fast_tile<BF16, false>(a, h, wg, s);
         } else {
-            load_tables(s);
             pass1_general_tile<BF16>(a, h, wg, s);
         }
     }

@@ -221,6 +221,19 @@ bool fast_eligible(int64_t cols, const float* v_colmax) {
            !env_int("LPMM_FORCE_GENERAL", 0);
 }
 
+// general path: pass 2 takes one chunk of 2048 elements per workgroup, pass 1 several consecutive ones (the
+// more, the fewer atomics leave the workgroup; few enough that the tensor alone still fills the chip)
+void general_geometry(Tensor4* a, int n_cu) {
+    const int64_t chunks = (a->P + kGenChunkElems - 1) / kGenChunkElems;
+    int64_t per_wg = env_int("LPMM_GEN_CHUNKS", 0);
+    if (per_wg <= 0) per_wg = chunks / (4 * int64_t(n_cu));
+    if (per_wg < 1) per_wg = 1;
+    if (per_wg > kGenMaxChunks) per_wg = kGenMaxChunks;
+    a->rw = int(per_wg);
+    a->n_wg = int((chunks + per_wg - 1) / per_wg);
+    a->n_wg2 = int(chunks);
+}
+
 template <bool BF16>
 int launch_step(const Tensor4& t, const Hyper& h, bool fast, hipStream_t s) {
     const bool rec = g_prof.on && g_prof.calls < g_prof.max_calls;
@@ -232,7 +245,7 @@ int launch_step(const Tensor4& t, const Hyper& h, bool fast, hipStream_t s) {
     LPMM_HIP(hipGetLastError());
     if (rec) LPMM_HIP(hipEventRecord(prof_event(call, 1), s));
     if (fast) hipLaunchKernelGGL(pass2_fast<BF16>, dim3(pad8(t.n_wg2)), dim3(kThreads), 0, s, t, h);
-    else hipLaunchKernelGGL(pass2_general<BF16>, dim3(grid), dim3(kThreads), 0, s, t, h);
+    else hipLaunchKernelGGL(pass2_general<BF16>, dim3(t.n_wg2), dim3(kThreads), 0, s, t, h);
     LPMM_HIP(hipGetLastError());
     if (rec) {
         LPMM_HIP(hipEventRecord(prof_event(call, 2), s));
@@ -278,7 +291,7 @@ int step_impl(bool bf16, void* param, const void* grad, uint8_t* m_codes, float*
     const bool fast = fast_eligible(cols, v_colmax);
     t.kind = fast ? kQuantFast : kQuantGeneral;
     if (fast) fast_geometry(&t, ctx->n_cu, 0, 0, bf16 ? 2 : 4);
-    else t.n_wg = t.n_wg2 = int((((t.P + 7) / 8) + kThreads - 1) / kThreads);
+    else general_geometry(&t, ctx->n_cu);
     hipStream_t s = static_cast<hipStream_t>(stream);
     return bf16 ? launch_step<true>(t, h, fast, s) : launch_step<false>(t, h, fast, s);
 }
@@ -438,7 +451,7 @@ int nd_step_impl(bool bf16, void* param, const void* grad, uint8_t* m_codes, flo
     const bool fast = fast_eligible(cols, v_col);
     t.kind = fast ? kQuantFast : kQuantGeneral;
     if (fast) fast_geometry(&t, ctx->n_cu, 0, 0, bf16 ? 2 : 4);
-    else t.n_wg = t.n_wg2 = int((((t.P + 7) / 8) + kThreads - 1) / kThreads);
+    else general_geometry(&t, ctx->n_cu);
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int grid = fast ? pad8(t.n_wg) : t.n_wg;
     const int grid_cols = grid_for(cols, 1);
@@ -451,7 +464,7 @@ int nd_step_impl(bool bf16, void* param, const void* grad, uint8_t* m_codes, flo
     hipLaunchKernelGGL(nd_expand_kernel, dim3(grid_cols), dim3(kThreads), 0, s, t.c_new + cols, t.c_new, cols, dm); \
     LPMM_HIP(hipGetLastError());                                                                                  \
     if (fast) hipLaunchKernelGGL(pass2_fast<B>, dim3(pad8(t.n_wg2)), dim3(kThreads), 0, s, t, h);                 \
-    else hipLaunchKernelGGL(pass2_general<B>, dim3(grid), dim3(kThreads), 0, s, t, h);                            \
+    else hipLaunchKernelGGL(pass2_general<B>, dim3(t.n_wg2), dim3(kThreads), 0, s, t, h);                         \
     LPMM_HIP(hipGetLastError());
     if (bf16) { LPMM_ND_LAUNCH(true) } else { LPMM_ND_LAUNCH(false) }
 #undef LPMM_ND_LAUNCH
@@ -474,7 +487,7 @@ void factor_geometry(Tensor4* a, int n_cu, int64_t rw_hint, int64_t rw2_hint, in
         std::swap(a->n_wg, a->n_wg2);
         a->kind = kFactorFast;
     } else {
-        a->n_wg = a->n_wg2 = int((((a->P + 7) / 8) + kThreads - 1) / kThreads);
+        general_geometry(a, n_cu);          // statistics pass: several chunks per workgroup; update pass: one
         a->kind = kFactorGeneral;
     }
 }
@@ -1117,7 +1130,7 @@ int lpmm_adamw4_plan_build(const lpmm_tensor_desc* descs, int64_t n, int grad_dt
                               plan_flat && t.P >= kFlatMinElems);
             } else {
                 t.kind = kQuantGeneral;
-                t.n_wg = t.n_wg2 = int((((t.P + 7) / 8) + kThreads - 1) / kThreads);
+                general_geometry(&t, ctx->n_cu);
             }
         }
         tens[i] = t;
