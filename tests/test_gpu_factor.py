@@ -20,7 +20,7 @@ from gpu_util import DEV, PARAM_ATOL, PARAM_RTOL, assert_codes_match, to_dev
 
 pytestmark = pytest.mark.gpu
 STAT_RTOL = 2e-5
-KNOBS = ("LPMM_GX", "LPMM_RW", "LPMM_RW2", "LPMM_RS", "LPMM_RS2", "LPMM_FORCE_GENERAL")
+KNOBS = ("LPMM_GX", "LPMM_RW", "LPMM_RW2", "LPMM_RS", "LPMM_RS2", "LPMM_FORCE_GENERAL", "LPMM_GEN_CHUNKS")
 
 
 @pytest.fixture(autouse=True)
@@ -103,7 +103,8 @@ def test_step_parity_fast_path(rows, cols):
     assert run(rows, cols, steps=3) == 0
 
 
-@pytest.mark.parametrize("rows,cols", [(37, 200), (5, 7), (1, 999), (1000, 3), (129, 127), (2, 4100)])
+@pytest.mark.parametrize("rows,cols", [(37, 200), (5, 7), (1, 999), (1000, 3), (129, 127), (2, 4100), (700, 192),
+                                       (9, 2100), (40000, 3), (2000, 9)])
 def test_step_parity_general_path(rows, cols):
     assert run(rows, cols, steps=3) == 0
 
@@ -134,7 +135,8 @@ def test_zero_gradient_from_the_zero_state():
                                  {"LPMM_RS": "0", "LPMM_RS2": "0", "LPMM_RW2": "1000"},
                                  {"LPMM_RW": "64", "LPMM_RS": "3", "LPMM_RW2": "32", "LPMM_RS2": "3"},
                                  {"LPMM_RW": "40", "LPMM_RS": "2", "LPMM_RW2": "24", "LPMM_RS2": "1"},
-                                 {"LPMM_FORCE_GENERAL": "1"}])
+                                 {"LPMM_FORCE_GENERAL": "1"}, {"LPMM_FORCE_GENERAL": "1", "LPMM_GEN_CHUNKS": "1"},
+                                 {"LPMM_FORCE_GENERAL": "1", "LPMM_GEN_CHUNKS": "16"}])
 def test_other_launch_geometries(env):
     assert run(300, 1024, steps=3, env=env) == 0
 

@@ -123,6 +123,10 @@ def test_zero_state_matches_oracle():
     (3, 128, "col_lognormal"),         # fast path, one column block, fewer rows than groups
     (5000, 128, "iid"),                # tall and one block wide: many row tiles of one strip
     (2, 1280, "iid"),                  # 10 column blocks: fine for pass 2; see (203, 384) for a half-empty last strip
+    (700, 192, "col_lognormal"),       # general path, narrow: several chunks per workgroup, maxima combined in LDS
+    (9, 2100, "iid"),                  # general path, more columns than the LDS column array holds
+    (40000, 3, "iid"),                 # general path, more rows per workgroup than the LDS row array holds
+    (2000, 9, "col_lognormal"),        # general path, rows of 9 elements: lanes straddle rows
 ])
 def test_step_parity_small(rows, cols, recipe):
     assert run_parity(rows, cols, steps=6, recipe=recipe, seed=3) == 0
@@ -149,7 +153,7 @@ def test_other_hyperparameters(hp):
     assert run_parity(128, 256, steps=5, recipe="col_lognormal", seed=6, hp=hp) == 0
 
 
-ALL_KNOBS = ("LPMM_GX", "LPMM_RW", "LPMM_RW2", "LPMM_RS", "LPMM_RS2", "LPMM_FORCE_GENERAL", "LPMM_FLAT")
+ALL_KNOBS = ("LPMM_GX", "LPMM_RW", "LPMM_RW2", "LPMM_RS", "LPMM_RS2", "LPMM_FORCE_GENERAL", "LPMM_FLAT", "LPMM_GEN_CHUNKS")
 
 
 def test_launch_geometry_does_not_change_results():
@@ -164,7 +168,8 @@ def test_launch_geometry_does_not_change_results():
              {"LPMM_RS": "0", "LPMM_RS2": "0"}, {"LPMM_RW": "64", "LPMM_RS": "3", "LPMM_RW2": "32", "LPMM_RS2": "3"},
              {"LPMM_RW": "40", "LPMM_RS": "2", "LPMM_RW2": "24", "LPMM_RS2": "1"},
              {"LPMM_FLAT": "1"}, {"LPMM_FLAT": "1", "LPMM_RW": "16", "LPMM_RS": "1"}, {"LPMM_FLAT": "1", "LPMM_RW": "300"},
-             {"LPMM_FORCE_GENERAL": "1"}]
+             {"LPMM_FORCE_GENERAL": "1"}, {"LPMM_FORCE_GENERAL": "1", "LPMM_GEN_CHUNKS": "1"},
+             {"LPMM_FORCE_GENERAL": "1", "LPMM_GEN_CHUNKS": "16"}]
     try:
         for env in knobs:
             for k in ALL_KNOBS:
