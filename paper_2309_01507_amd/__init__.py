@@ -3,7 +3,7 @@
 The library is loaded on first use; nothing here computes anything on the CPU.
 """
 from .binding import (  # noqa: F401
-    LpmmError, State4, lib, lib_path, build_library,
+    LpmmError, State4, lib, lib_path, build_library, GRAD_F32, GRAD_BF16,
     lpmm_table, lpmm_host_nearest_codes, lpmm_adamw4_workspace_bytes, lpmm_adamw4_init,
     lpmm_adamw4_state_sizes, lpmm_adamw4_state_zero, lpmm_adamw4_step, lpmm_adamw4_step_bf16g,
     lpmm_adamw32_step, lpmm_dequant_state, lpmm_quant_state, ensure_init, new_state,
