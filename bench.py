@@ -281,6 +281,10 @@ def main():
                          f"{rows * cols} params), {cdt:.1f} s; host has {os.cpu_count()} logical cpus"}
 
     total_gbps = ((bp1 + bp2) * n_quant + small_bytes) / (elapsed / args.steps) / 1e9
+    # the same roofline for all kernels of a step together (they overlap on two streams, so a single kernel's
+    # duration includes the slow-down from its neighbour): algorithmic bytes of the step / wall time of the step
+    roofline["whole_step"] = {"achieved": round(total_gbps, 1), "frac": round(total_gbps / HBM_PEAK_GBPS, 4),
+                              "bytes_per_param": bp1 + bp2, "ms": round(ms_per_step, 4)}
     # every stream touched once (what a single pass would move): param 8, grad, codes 2, block scales and,
     # for the rank-1 form, one more float per 128 elements standing in for the row / column maxima
     floor_bpp = 8.0 + (2.0 if bf16 else 4.0) + (1.0 if factor or sgdm else 2.0) + (16.0 if b128 else 8.0) / 128.0
