@@ -288,6 +288,9 @@ int lpmm_quant_state(int which, const float* in, const int64_t shape[2], uint8_t
 #define LPMM_KIND_SGDM_FP32 5   /* SGD with momentum, fp32 momentum, as in lpmm_sgdm32_step: m_state = float m[] */
                                 /* SGDM kinds make a plan of their own, stepped by lpmm_sgdm4_step_multi */
 
+#define LPMM_FLAG_NO_DECAY 1    /* this tensor takes no weight decay (biases and normalization weights are commonly
+                                   excluded); lpmm_adamw4_step_multi then uses weight_decay = 0 for it */
+
 typedef struct lpmm_tensor_desc {
     void* param;            /* float[rows*cols], in place */
     const void* grad;       /* float or bf16 [rows*cols] (one type for the whole plan) */
@@ -298,7 +301,7 @@ typedef struct lpmm_tensor_desc {
     float* v_colmax;        /* 4BIT only */
     int64_t rows, cols;
     int32_t kind;           /* LPMM_KIND_* */
-    int32_t reserved;       /* 0 */
+    int32_t flags;          /* LPMM_FLAG_* bits, 0 for none */
 } lpmm_tensor_desc;
 
 /* Bytes of device memory a plan for these tensors needs (descriptor tables, per-tensor row/column

@@ -506,32 +506,35 @@ def lpmm_quant_state(which: int, x, rows, cols, codes, scale_a, scale_b, stream=
 # ---- many tensors in one call ------------------------------------------------------------------------
 
 KIND_4BIT, KIND_FP32, KIND_4BIT_B128, KIND_4BIT_FACTOR, KIND_SGDM_4BIT, KIND_SGDM_FP32 = 0, 1, 2, 3, 4, 5
+FLAG_NO_DECAY = 1
 
 
 class TensorDesc(ctypes.Structure):
     """Mirror of lpmm_tensor_desc."""
     _fields_ = [("param", _VP), ("grad", _VP), ("m_state", _VP), ("m_blockscale", _VP), ("v_state", _VP),
                 ("v_rowmax", _VP), ("v_colmax", _VP), ("rows", _I64), ("cols", _I64),
-                ("kind", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+                ("kind", ctypes.c_int32), ("flags", ctypes.c_int32)]
 
 
-def make_desc(param, grad, state, rows=None, cols=None) -> TensorDesc:
-    """state: a State4 (4-bit, rank-1 second moment), a StateB128 (4-bit, block-wise second moment)
-    or a (m, v) pair of fp32 tensors (then rows, cols must be given)."""
+def make_desc(param, grad, state, rows=None, cols=None, no_decay=False) -> TensorDesc:
+    """state: a State4 (4-bit, rank-1 second moment), a StateB128 (4-bit, block-wise second moment), a StateFactor
+    (factorized second moment) or a (m, v) pair of fp32 tensors (then rows, cols must be given).
+    no_decay: the plan's weight decay does not apply to this tensor."""
+    flags = FLAG_NO_DECAY if no_decay else 0
     if isinstance(state, StateFactor):
         return TensorDesc(_ptr(param), _ptr(grad), _ptr(state.m_codes), _ptr(state.m_blockscale), None,
-                          _ptr(state.v_row), _ptr(state.v_col), state.rows, state.cols, KIND_4BIT_FACTOR, 0)
+                          _ptr(state.v_row), _ptr(state.v_col), state.rows, state.cols, KIND_4BIT_FACTOR, flags)
     if isinstance(state, StateB128):
         return TensorDesc(_ptr(param), _ptr(grad), _ptr(state.m_codes), _ptr(state.m_blockscale),
                           _ptr(state.v_codes), _ptr(state.v_blockscale), None, 1, state.numel,
-                          KIND_4BIT_B128, 0)
+                          KIND_4BIT_B128, flags)
     if isinstance(state, State4):
         return TensorDesc(_ptr(param), _ptr(grad), _ptr(state.m_codes), _ptr(state.m_blockscale),
                           _ptr(state.v_codes), _ptr(state.v_rowmax), _ptr(state.v_colmax), state.rows,
-                          state.cols, KIND_4BIT, 0)
+                          state.cols, KIND_4BIT, flags)
     m, v = state
     return TensorDesc(_ptr(param), _ptr(grad), _ptr(m), None, _ptr(v), None, None, int(rows), int(cols),
-                      KIND_FP32, 0)
+                      KIND_FP32, flags)
 
 
 def lpmm_adamw4_plan_bytes(descs) -> int:

@@ -63,7 +63,7 @@ struct Tensor4 {
     int rs, rs2;
     int tot_slots;          // kFactor*: slots that each of the two float sums is spread over (1, 2, 4 or 8)
     int flat;               // kQuantFast: pass 1 uses the flat tiling (a group walks along a row)
-    int pad_;
+    int no_decay;           // plans: this tensor takes no weight decay
     int c_extra;            // floats behind c_new (and room behind c) that the publishing workgroup moves and clears
                             // along with the column maxima (tensors with more than two dimensions)
 };
@@ -87,7 +87,7 @@ struct Tensor4Table {
     float LPMM_AS_GLOBAL* c_new;
     unsigned int LPMM_AS_GLOBAL* counter;
     int64_t rows, cols, P;
-    int nb, gx, gy, rw, strips, n_wg, kind, strips2, rw2, n_wg2, rs, rs2, tot_slots, flat, pad_, c_extra;
+    int nb, gx, gy, rw, strips, n_wg, kind, strips2, rw2, n_wg2, rs, rs2, tot_slots, flat, no_decay, c_extra;
 };
 static_assert(sizeof(Tensor4Table) == sizeof(Tensor4), "the table twin must mirror Tensor4");
 __device__ __forceinline__ Tensor4 from_table(const Tensor4Table& t) {
@@ -105,7 +105,7 @@ __device__ __forceinline__ Tensor4 from_table(const Tensor4Table& t) {
     a.rows = t.rows; a.cols = t.cols; a.P = t.P;
     a.nb = t.nb; a.gx = t.gx; a.gy = t.gy; a.rw = t.rw; a.strips = t.strips; a.n_wg = t.n_wg; a.kind = t.kind;
     a.strips2 = t.strips2; a.rw2 = t.rw2; a.n_wg2 = t.n_wg2; a.rs = t.rs; a.rs2 = t.rs2;
-    a.tot_slots = t.tot_slots; a.flat = t.flat; a.pad_ = 0; a.c_extra = t.c_extra;
+    a.tot_slots = t.tot_slots; a.flat = t.flat; a.no_decay = t.no_decay; a.c_extra = t.c_extra;
     return a;
 }
 #else
@@ -1968,6 +1968,13 @@ struct Phase {
     Segment seg_b[kMaxSeg];
 };
 
+// the hyper-parameters as they apply to one tensor of a plan
+__device__ __forceinline__ Hyper for_tensor(const Hyper& h, const Tensor4& a) {
+    Hyper t = h;
+    if (a.no_decay) t.lr_wd = 0.0f;
+    return t;
+}
+
 // last segment whose first workgroup is <= wg (segments are sorted by wg_begin, seg[0].wg_begin = 0;
 // a uniform binary search on scalar registers)
 __device__ __forceinline__ Segment find_segment(const Segment* seg, int n_seg, int wg) {
@@ -2006,18 +2013,19 @@ __global__ __launch_bounds__(kThreads) void phase_kernel(const Phase ph, const H
         const int xa = x - b_before;
         const Segment sg = find_segment(ph.seg_a, ph.n_seg_a, xa);
         const Tensor4 a = from_table(ph.tensors[sg.tensor]);
+        const Hyper ht = for_tensor(h, a);
         const int wg = xa - sg.wg_begin;
         if (a.kind == kFp32State) {
-            adamw32_tile<BF16>(a.p, a.g, reinterpret_cast<float*>(a.mq), reinterpret_cast<float*>(a.vq), a.P, h, wg);
+            adamw32_tile<BF16>(a.p, a.g, reinterpret_cast<float*>(a.mq), reinterpret_cast<float*>(a.vq), a.P, ht, wg);
         } else if (a.kind == kQuantBlockV) {
-            b128_work<BF16>(a, h, wg, s);
+            b128_work<BF16>(a, ht, wg, s);
         } else if (ROLES == 3) {
             // not reached: the host launches this variant only for groups without rank-1 tensors
         } else if (a.kind == kQuantFast) {
-            if (a.flat) pass1_flat_tile<BF16>(a, h, wg, s);
-            else pass1_fast_tile<BF16, false>(a, h, wg, s);
+            if (a.flat) pass1_flat_tile<BF16>(a, ht, wg, s);
+            else pass1_fast_tile<BF16, false>(a, ht, wg, s);
         } else {
-            pass1_general_tile<BF16>(a, h, wg, s);
+            pass1_general_tile<BF16>(a, ht, wg, s);
         }
     }
 }
@@ -2096,12 +2104,13 @@ __global__ __launch_bounds__(kThreads) void factor_phase_kernel(const Phase ph, 
         __shared__ int s_last;
         const Segment sg = find_segment(ph.seg_b, ph.n_seg_b, b_before);
         const Tensor4 a = from_table(ph.tensors[sg.tensor]);
+        const Hyper ht = for_tensor(h, a);
         const int wg = b_before - sg.wg_begin;
         if (a.kind == kFactorFast) {
-            factor_update_tile<BF16>(a, h, wg, s);
+            factor_update_tile<BF16>(a, ht, wg, s);
         } else {
             load_tables(s);
-            factor_update_general_tile<BF16>(a, h, wg, s);
+            factor_update_general_tile<BF16>(a, ht, wg, s);
         }
         factor_publish_if_last(a, h, wg, a.n_wg2, s_last);
     } else if (ROLES != 2) {
@@ -2109,9 +2118,10 @@ __global__ __launch_bounds__(kThreads) void factor_phase_kernel(const Phase ph, 
         const Segment sg = find_segment(ph.seg_a, ph.n_seg_a, xa);
         const Tensor4 a = from_table(ph.tensors[sg.tensor]);
         const int wg = xa - sg.wg_begin;
+        const Hyper ht = for_tensor(h, a);
         if (a.kind == kFp32State)
-            adamw32_tile<BF16>(a.p, a.g, reinterpret_cast<float*>(a.mq), reinterpret_cast<float*>(a.vq), a.P, h, wg);
-        else if (a.kind == kQuantBlockV) b128_work<BF16>(a, h, wg, s);
+            adamw32_tile<BF16>(a.p, a.g, reinterpret_cast<float*>(a.mq), reinterpret_cast<float*>(a.vq), a.P, ht, wg);
+        else if (a.kind == kQuantBlockV) b128_work<BF16>(a, ht, wg, s);
         else if (a.kind == kFactorFast) factor_stats_tile<BF16>(a, wg, s);
         else factor_stats_general_tile<BF16>(a, wg, a.n_wg, s);
     }

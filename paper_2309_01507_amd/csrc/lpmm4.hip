@@ -1058,6 +1058,8 @@ int lpmm_adamw4_plan_build(const lpmm_tensor_desc* descs, int64_t n, int grad_dt
         const size_t galign = grad_dtype == LPMM_GRAD_F32 ? 4 : 2;
         Tensor4 t{};
         t.rows = d.rows; t.cols = d.cols; t.P = d.rows * d.cols;
+        if (d.flags & ~LPMM_FLAG_NO_DECAY) return LPMM_EINVAL;
+        t.no_decay = (d.flags & LPMM_FLAG_NO_DECAY) ? 1 : 0;
         t.p = static_cast<float*>(d.param);
         t.g = d.grad;
         t.mq = static_cast<uint32_t*>(d.m_state);

@@ -99,3 +99,60 @@ def test_multi_rejects_bad_lists():
     assert lpmm.lpmm_adamw4_plan_bytes([bad]) == 0
     with pytest.raises(lpmm.LpmmError):
         lpmm.lpmm_adamw4_step_multi(torch.zeros(256, dtype=torch.uint8, device=DEV), 1e-3, 0.9, 0.999, 1e-8, 0.0, 1)
+
+
+@pytest.mark.parametrize("second", ["rank1", "factor"])
+def test_per_tensor_no_decay_flag(second):
+    """Tensors flagged LPMM_FLAG_NO_DECAY (biases, normalization weights, here also one matrix) are stepped with
+    weight decay 0, the others with the plan's."""
+    import dataclasses
+    from test_gpu_factor import compare as compare_factor, download as download_factor
+    hp = oracle.Hyper(lr=1e-2, weight_decay=0.2)                  # large enough for a missing decay to show
+    hp0 = dataclasses.replace(hp, weight_decay=0.0)
+    T = workloads.TensorSpec
+    specs = [(T("w1", 256, 384), False), (T("b1", 1, 384, 1), True), (T("w2", 300, 256), True),
+             (T("ln", 1, 256, 1), True), (T("odd", 37, 200), False), (T("b2", 1, 300, 1), False)]
+    lpmm.ensure_init(4096)
+    seed = 17
+    dev_t, ref_t, descs = [], [], []
+    for tid, (sp, nd) in enumerate(specs):
+        w_ref = workloads.weights(seed, tid, sp.rows, sp.cols).reshape(-1)
+        w, g = to_dev(w_ref.copy()), torch.empty(sp.numel, device=DEV)
+        if sp.quantized and second == "factor":
+            st, st_ref = lpmm.new_state_factor(sp.rows, sp.cols, DEV), oracle.state_zero_factor(sp.rows, sp.cols)
+            descs.append(lpmm.make_desc(w, g, st, no_decay=nd))
+        elif sp.quantized:
+            st, st_ref = lpmm.new_state(sp.rows, sp.cols, DEV), oracle.state_zero(sp.rows, sp.cols)
+            descs.append(lpmm.make_desc(w, g, st, no_decay=nd))
+        else:
+            st = (torch.zeros(sp.numel, device=DEV), torch.zeros(sp.numel, device=DEV))
+            st_ref = (np.zeros(sp.numel, np.float32), np.zeros(sp.numel, np.float32))
+            descs.append(lpmm.make_desc(w, g, st, sp.rows, sp.cols, no_decay=nd))
+        dev_t.append((w, g, st))
+        ref_t.append((w_ref, st_ref))
+    plan = lpmm.new_plan(descs, 0, DEV)
+    for t in (1, 2, 3):
+        grads = [workloads.grads(seed, tid, t, sp.rows, sp.cols, "col_lognormal").reshape(-1)
+                 for tid, (sp, _) in enumerate(specs)]
+        for (w, g, st), gn in zip(dev_t, grads):
+            g.copy_(to_dev(gn))
+        lpmm.lpmm_adamw4_step_multi(plan, hp.lr, hp.beta1, hp.beta2, hp.eps, hp.weight_decay, t)
+        torch.cuda.synchronize()
+        for (sp, nd), (w, g, st), (w_ref, st_ref), gn in zip(specs, dev_t, ref_t, grads):
+            h = hp0 if nd else hp
+            tag = f"{sp.name} step {t}"
+            if sp.quantized and second == "factor":
+                mt, _ = oracle.adamw4_factor_step(w_ref, gn, st_ref, h, t, want_moments=True)
+                assert compare_factor(download_factor(st), st_ref, w.cpu().numpy(), w_ref, mt, tag) == 0
+                st.v_row.copy_(to_dev(st_ref.v_row)); st.v_col.copy_(to_dev(st_ref.v_col)); w.copy_(to_dev(w_ref))
+            elif sp.quantized:
+                mt, vt = oracle.adamw4_step(w_ref, gn, st_ref, h, t, want_moments=True)
+                assert compare_step(download_state(st), st_ref, w.cpu().numpy(), w_ref, mt, vt, tag) == 0
+            else:
+                oracle.adamw32_step(w_ref, gn, st_ref[0], st_ref[1], h, t)
+                np.testing.assert_allclose(w.cpu().numpy(), w_ref, rtol=PARAM_RTOL, atol=PARAM_ATOL, err_msg=tag)
+    lpmm.lpmm_adamw4_plan_release(plan)
+    bad = lpmm.make_desc(dev_t[0][0], dev_t[0][1], dev_t[0][2])
+    bad.flags = 6
+    with pytest.raises(lpmm.LpmmError):
+        lpmm.new_plan([bad], 0, DEV)
