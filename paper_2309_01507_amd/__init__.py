@@ -18,3 +18,4 @@ from .binding import (  # noqa: F401
     StateSgdm, new_state_sgdm, lpmm_sgdm4_state_sizes, lpmm_sgdm4_state_zero, lpmm_sgdm4_step, lpmm_sgdm4_step_bf16g,
     lpmm_sgdm32_step, lpmm_sgdm4_step_multi, make_desc_sgdm, KIND_SGDM_4BIT, KIND_SGDM_FP32, FLAG_NO_DECAY,
 )
+from .optim import AdamW4bit, SGDM4bit  # noqa: F401,E402

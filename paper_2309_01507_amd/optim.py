@@ -1,0 +1,141 @@
+"""torch.optim-style front ends over the C ABI: they own the state buffers and one plan per parameter group and
+call lpmm_adamw4_step_multi / lpmm_sgdm4_step_multi.  Orchestration only -- every number is computed by lpmm4.so.
+
+    opt = AdamW4bit(model.parameters(), lr=1e-3, weight_decay=0.01)
+    loss.backward(); opt.step(); opt.zero_grad()
+
+Parameters must be fp32, contiguous and on one GPU; gradients fp32 or bf16 (one type per optimizer).  A plan
+refers to parameter and gradient buffers by address, so it is rebuilt whenever one of them has moved (keep
+gradients in place with zero_grad(set_to_none=False) to avoid that).
+"""
+from __future__ import annotations
+
+import torch
+
+from . import binding as _b
+
+QUANT_MIN_NUMEL = 4096          # App. C.1: tensors of at most 4096 elements keep fp32 states
+
+
+def _default_no_decay(p: torch.Tensor) -> bool:
+    return p.ndim <= 1              # biases and normalization weights
+
+
+class _PlanOptimizer:
+    def __init__(self, params, no_decay):
+        self.params = [p for p in params if p.requires_grad]
+        if not self.params:
+            raise ValueError("no parameters")
+        dev = self.params[0].device
+        for p in self.params:
+            if p.dtype != torch.float32 or not p.is_contiguous() or p.device != dev or dev.type != "cuda":
+                raise ValueError("parameters must be contiguous fp32 tensors on one GPU")
+        self.device = dev
+        self.no_decay = no_decay if callable(no_decay) else (lambda p, flag=bool(no_decay): flag and p.ndim <= 1)
+        self.t = 0
+        self._plan = None
+        self._key = None
+        self._states = None
+
+    # subclasses: _new_state(p) -> state, _desc(p, g, state) -> TensorDesc, _step(plan)
+    def _ensure_plan(self):
+        grads = []
+        for p in self.params:
+            if p.grad is None:
+                raise ValueError("every parameter needs a gradient (frozen parameters: requires_grad=False)")
+            g = p.grad
+            if not g.is_contiguous() or g.dtype not in (torch.float32, torch.bfloat16):
+                raise ValueError("gradients must be contiguous fp32 or bf16")
+            grads.append(g)
+        if len({g.dtype for g in grads}) != 1:
+            raise ValueError("one gradient type per optimizer")
+        key = tuple((p.data_ptr(), g.data_ptr()) for p, g in zip(self.params, grads)) + (grads[0].dtype,)
+        if key == self._key:
+            return
+        with torch.cuda.device(self.device):
+            _b.ensure_init(4096)            # lookup tables; a plan carries its own workspace
+            if self._states is None:
+                self._states = [self._new_state(p) for p in self.params]
+            if self._plan is not None:
+                torch.cuda.synchronize(self.device)
+                _b.lpmm_adamw4_plan_release(self._plan)
+            descs = [self._desc(p, g, st) for p, g, st in zip(self.params, grads, self._states)]
+            self._plan = _b.new_plan(descs, _b.GRAD_BF16 if grads[0].dtype == torch.bfloat16 else _b.GRAD_F32,
+                                     self.device)
+        self._key = key
+
+    @torch.no_grad()
+    def step(self):
+        self._ensure_plan()
+        self.t += 1
+        with torch.cuda.device(self.device):
+            self._step(self._plan)
+
+    def zero_grad(self, set_to_none: bool = False):
+        for p in self.params:
+            if p.grad is not None:
+                if set_to_none:
+                    p.grad = None
+                else:
+                    p.grad.zero_()
+
+    def state_buffers(self):
+        """The device buffers that make up the optimizer state, per parameter (for checkpoints)."""
+        return self._states
+
+    def __del__(self):
+        try:
+            if self._plan is not None:
+                _b.lpmm_adamw4_plan_release(self._plan)
+        except Exception:
+            pass
+
+
+class AdamW4bit(_PlanOptimizer):
+    """4-bit AdamW.  second_moment: "rank1" (rank-1/Linear for matrices, the paper's 4-bit AdamW), "factor" (row and
+    column statistics for matrices, the paper's 4-bit Factor) or "b128" (every tensor flat, block-wise).  Tensors
+    with more than two dimensions are taken as (shape[0], rest) matrices; tensors of at most 4096 elements and
+    1-dimensional ones keep fp32 states (1-dimensional tensors above 4096 elements: block-wise 4-bit states)."""
+
+    def __init__(self, params, lr=1e-3, betas=(0.9, 0.999), eps=1e-8, weight_decay=1e-2, second_moment="rank1",
+                 no_decay=_default_no_decay):
+        super().__init__(params, no_decay)
+        if second_moment not in ("rank1", "factor", "b128"):
+            raise ValueError("second_moment must be rank1, factor or b128")
+        self.lr, self.betas, self.eps, self.weight_decay, self.second_moment = lr, betas, eps, weight_decay, second_moment
+
+    def _new_state(self, p):
+        n = p.numel()
+        if n <= QUANT_MIN_NUMEL:
+            return (torch.zeros(n, device=p.device), torch.zeros(n, device=p.device))
+        if p.ndim <= 1 or self.second_moment == "b128":
+            return _b.new_state_b128(n, p.device)
+        rows, cols = p.shape[0], n // p.shape[0]
+        return (_b.new_state_factor if self.second_moment == "factor" else _b.new_state)(rows, cols, p.device)
+
+    def _desc(self, p, g, st):
+        nd = bool(self.no_decay(p))
+        if isinstance(st, tuple):
+            return _b.make_desc(p, g, st, 1, p.numel(), no_decay=nd)
+        return _b.make_desc(p, g, st, no_decay=nd)
+
+    def _step(self, plan):
+        _b.lpmm_adamw4_step_multi(plan, self.lr, self.betas[0], self.betas[1], self.eps, self.weight_decay, self.t)
+
+
+class SGDM4bit(_PlanOptimizer):
+    """SGD with momentum, momentum in 4 bits (fp32 for tensors of at most 4096 elements); no weight decay."""
+
+    def __init__(self, params, lr=1e-2, momentum=0.9):
+        super().__init__(params, no_decay=False)
+        self.lr, self.momentum = lr, momentum
+
+    def _new_state(self, p):
+        n = p.numel()
+        return torch.zeros(n, device=p.device) if n <= QUANT_MIN_NUMEL else _b.new_state_sgdm(n, p.device)
+
+    def _desc(self, p, g, st):
+        return _b.make_desc_sgdm(p, g, st, p.numel())
+
+    def _step(self, plan):
+        _b.lpmm_sgdm4_step_multi(plan, self.lr, self.momentum)

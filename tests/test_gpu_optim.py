@@ -1,0 +1,116 @@
+"""The torch.optim-style front ends drive the same C ABI: their results must equal the oracle's, tensor by tensor,
+and the first step of 4-bit AdamW must equal torch's fp32 AdamW (the update uses the precise moments)."""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2309_01507_amd as lpmm
+from gpu_util import DEV, PARAM_ATOL, PARAM_RTOL, compare_step, download_state
+from test_gpu_sgdm import compare as compare_sgdm, download as download_sgdm
+
+pytestmark = pytest.mark.gpu
+
+
+def _model(seed):
+    torch.manual_seed(seed)
+    m = torch.nn.Sequential(torch.nn.Linear(256, 384), torch.nn.LayerNorm(384), torch.nn.GELU(),
+                            torch.nn.Linear(384, 130), torch.nn.Linear(130, 8))
+    return m.to(DEV)
+
+
+def _loss(m, step):
+    g = torch.Generator(device="cpu").manual_seed(1000 + step)
+    x = torch.randn(32, 256, generator=g).to(DEV)
+    return (m(x) ** 2).mean()
+
+
+def test_adamw4bit_matches_the_oracle_and_survives_moving_gradients():
+    print("\n[gpu-test] AdamW4bit front end", flush=True)
+    hp = oracle.Hyper(lr=1e-3, weight_decay=0.1)
+    m = _model(1)
+    opt = lpmm.AdamW4bit(m.parameters(), lr=hp.lr, betas=(hp.beta1, hp.beta2), eps=hp.eps, weight_decay=hp.weight_decay)
+    ref = []
+    for p in m.parameters():
+        w = p.detach().cpu().numpy().reshape(-1).copy()
+        if p.numel() > 4096 and p.ndim == 2:
+            ref.append((w, oracle.state_zero(p.shape[0], p.shape[1])))
+        else:
+            ref.append((w, (np.zeros(p.numel(), np.float32), np.zeros(p.numel(), np.float32))))
+    for t in (1, 2, 3, 4):
+        _loss(m, t).backward()
+        grads = [p.grad.detach().cpu().numpy().reshape(-1).copy() for p in m.parameters()]
+        opt.step()
+        torch.cuda.synchronize()
+        for p, st, (w_ref, st_ref), g in zip(m.parameters(), opt.state_buffers(), ref, grads):
+            h = dataclasses.replace(hp, weight_decay=0.0) if p.ndim <= 1 else hp
+            if isinstance(st_ref, tuple):
+                oracle.adamw32_step(w_ref, g, st_ref[0], st_ref[1], h, t)
+                np.testing.assert_allclose(p.detach().cpu().numpy().reshape(-1), w_ref, rtol=PARAM_RTOL, atol=PARAM_ATOL)
+            else:
+                mt, vt = oracle.adamw4_step(w_ref, g, st_ref, h, t, want_moments=True)
+                assert compare_step(download_state(st), st_ref, p.detach().cpu().numpy().reshape(-1), w_ref, mt, vt,
+                                    f"{tuple(p.shape)} step {t}") == 0
+            # both sides continue from the oracle's parameters: the next gradient must be the same on both
+            p.data.copy_(torch.from_numpy(w_ref).view_as(p))
+        opt.zero_grad(set_to_none=(t % 2 == 0))           # every other step the gradients get new addresses
+
+
+def test_first_step_equals_fp32_adamw():
+    print("\n[gpu-test] AdamW4bit step 1 vs torch.optim.AdamW", flush=True)
+    a, b = _model(2), _model(2)
+    decay = [p for p in b.parameters() if p.ndim > 1]
+    no_decay = [p for p in b.parameters() if p.ndim <= 1]
+    ref = torch.optim.AdamW([{"params": decay, "weight_decay": 0.05}, {"params": no_decay, "weight_decay": 0.0}],
+                            lr=2e-3, betas=(0.9, 0.98), eps=1e-6)
+    for second in ("rank1", "factor", "b128"):
+        a.load_state_dict(_model(2).state_dict())
+        opt = lpmm.AdamW4bit(a.parameters(), lr=2e-3, betas=(0.9, 0.98), eps=1e-6, weight_decay=0.05, second_moment=second)
+        _loss(a, 7).backward()
+        opt.step()
+        if second == "rank1":
+            _loss(b, 7).backward()
+            ref.step()
+        torch.cuda.synchronize()
+        for pa, pb in zip(a.parameters(), b.parameters()):
+            if second == "factor" and pa.ndim == 2 and pa.numel() > 4096:
+                continue                                   # the factorized second moment is an approximation
+            torch.testing.assert_close(pa, pb, rtol=2e-5, atol=2e-7)
+        opt.zero_grad(set_to_none=True)
+
+
+def test_sgdm4bit_matches_the_oracle():
+    print("\n[gpu-test] SGDM4bit front end", flush=True)
+    lr, beta = 0.05, 0.9
+    m = _model(3)
+    opt = lpmm.SGDM4bit(m.parameters(), lr=lr, momentum=beta)
+    ref = [(p.detach().cpu().numpy().reshape(-1).copy(),
+            oracle.state_zero_sgdm(p.numel()) if p.numel() > 4096 else np.zeros(p.numel(), np.float32))
+           for p in m.parameters()]
+    for t in (1, 2, 3):
+        _loss(m, t).backward()
+        grads = [p.grad.detach().cpu().numpy().reshape(-1).copy() for p in m.parameters()]
+        opt.step()
+        torch.cuda.synchronize()
+        for p, st, (w_ref, st_ref), g in zip(m.parameters(), opt.state_buffers(), ref, grads):
+            if isinstance(st_ref, np.ndarray):
+                oracle.sgdm32_step(w_ref, g, st_ref, lr, beta)
+                np.testing.assert_allclose(p.detach().cpu().numpy().reshape(-1), w_ref, rtol=PARAM_RTOL, atol=PARAM_ATOL)
+            else:
+                mt = oracle.sgdm4_step(w_ref, g, st_ref, lr, beta, want_moment=True)
+                assert compare_sgdm(download_sgdm(st), st_ref, p.detach().cpu().numpy().reshape(-1), w_ref, mt,
+                                    f"{tuple(p.shape)} step {t}") == 0
+            p.data.copy_(torch.from_numpy(w_ref).view_as(p))
+        opt.zero_grad()
+
+
+def test_bad_parameters_are_rejected():
+    with pytest.raises(ValueError):
+        lpmm.AdamW4bit([torch.zeros(4, 4, device=DEV, dtype=torch.float16, requires_grad=True)])
+    with pytest.raises(ValueError):
+        lpmm.AdamW4bit([torch.zeros(4, 4, requires_grad=True)])          # not on the GPU
+    opt = lpmm.AdamW4bit([torch.zeros(64, 128, device=DEV, requires_grad=True)])
+    with pytest.raises(ValueError):
+        opt.step()                                                       # no gradient yet
