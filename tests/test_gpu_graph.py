@@ -19,7 +19,7 @@ def _states_equal(a, b):
             assert torch.equal(x, y), name
 
 
-@pytest.mark.parametrize("kind", ["rank1", "b128"])
+@pytest.mark.parametrize("kind", ["rank1", "b128", "sgdm", "nd"])
 def test_single_tensor_step_replays_from_a_graph(kind):
     print(f"\n[gpu-test] graph capture {kind}", flush=True)
     rows, cols = 200, 512
@@ -29,13 +29,18 @@ def test_single_tensor_step_replays_from_a_graph(kind):
     grads = [to_dev(workloads.grads(41, 0, t, rows, cols, "col_lognormal").reshape(-1)) for t in (1, 2, 3, 4)]
 
     def fresh():
-        return lpmm.new_state(rows, cols, DEV) if kind == "rank1" else lpmm.new_state_b128(P, DEV)
+        return {"rank1": lambda: lpmm.new_state(rows, cols, DEV), "b128": lambda: lpmm.new_state_b128(P, DEV),
+                "sgdm": lambda: lpmm.new_state_sgdm(P, DEV), "nd": lambda: lpmm.new_state_nd((rows, 4, cols // 4), DEV)}[kind]()
 
     def step(w, g, st, t):
         if kind == "rank1":
             lpmm.lpmm_adamw4_step(w, g, st, *H, t)
-        else:
+        elif kind == "b128":
             lpmm.lpmm_adamw4_b128_step(w, g, st, *H, t)
+        elif kind == "sgdm":
+            lpmm.lpmm_sgdm4_step(w, g, st, 0.05, 0.9)
+        else:
+            lpmm.lpmm_adamw4_nd_step(w, g, st, *H, t)
 
     # eager reference; the captured call has its step number baked in, so the reference uses the same one
     w_ref, st_ref = w0.clone(), fresh()
