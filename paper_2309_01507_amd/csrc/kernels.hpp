@@ -13,7 +13,10 @@
 //           min(r'_i, c'_j) (Linear map), and let the last workgroup publish r', c' as the new
 //           state and clear the workspace.
 // For 1-dimensional or flattened tensors the second moment is block-wise like the first (Sec. 4.2,
-// last paragraph); then nothing crosses a block and the step is ONE pass (b128_*).
+// last paragraph); then nothing crosses a block and the step is ONE pass (b128_*).  The same one-pass
+// code without a second moment is SGD with momentum (App. E Alg. 2).  With a factorized second
+// moment (Sec. 4.3, factor_*) the two passes are: row / column sums of g^2, then the update.  Tensors
+// with more than two dimensions (App. F Alg. 4, nd_*) run the two matrix passes on derived column scales.
 // The bodies are "tile" functions; thin __global__ wrappers run them for one tensor (two launches
 // per step, one for the block-wise form), and the phase kernels run pass 1 of one set of tensors
 // next to pass 2 of the previous set, so that the arithmetic-heavy pass 2 hides under the
@@ -48,9 +51,10 @@ struct Tensor4 {
     // geometry of the fast path (cols % 128 == 0)
     int nb;                 // column blocks per row = cols / 128    (kQuantBlockV: whole blocks of the tensor)
     int gx, gy;             // a workgroup's 8 groups: gx column blocks x gy row phases
-    int rw;                 // rows per workgroup tile; rw * cols < 2^29   (kQuantBlockV: blocks a group takes in a row)
+    int rw;                 // rows per workgroup tile; rw * cols < 2^29   (kQuantBlockV, kSgdmBlock: blocks a group takes in
+                            // a row; general path: chunks of 2048 elements a workgroup of the first pass takes)
     int strips;             // nb / gx
-    int n_wg;               // workgroups of pass 1 (general path: of either pass; kQuantBlockV: of the step;
+    int n_wg;               // workgroups of pass 1 (kQuantBlockV, kSgdmBlock: of the step;
                             // kFactor*: of the statistics pass, which is tiled like pass 2)
     int kind;
     // pass 2 of the fast path has its own tiling: strips of 256 columns, rw2 rows per workgroup
