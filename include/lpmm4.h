@@ -291,6 +291,12 @@ int lpmm_quant_state(int which, const float* in, const int64_t shape[2], uint8_t
 #define LPMM_FLAG_NO_DECAY 1    /* this tensor takes no weight decay (biases and normalization weights are commonly
                                    excluded); lpmm_adamw4_step_multi then uses weight_decay = 0 for it */
 
+#define LPMM_KIND_4BIT_ND 6     /* quantized states of a tensor with more than two dimensions, as in lpmm_adamw4_nd_step:
+                                   rows = d_1, cols = d_2 * ... * d_p, v_rowmax points at v_row, v_colmax at v_col
+                                   (cols + d_2 + ... + d_p floats); the sizes d_2 .. d_p come from the side tables of
+                                   lpmm_adamw4_plan_bytes_nd / lpmm_adamw4_plan_build_nd.  Counts as LPMM_KIND_4BIT
+                                   for the rule about mixing optimizers */
+
 typedef struct lpmm_tensor_desc {
     void* param;            /* float[rows*cols], in place */
     const void* grad;       /* float or bf16 [rows*cols] (one type for the whole plan) */
@@ -316,6 +322,15 @@ size_t lpmm_adamw4_plan_bytes(const lpmm_tensor_desc* descs, int64_t n);
  * if any of them moves.  A small host-side record is kept until lpmm_adamw4_plan_release(plan). */
 int lpmm_adamw4_plan_build(const lpmm_tensor_desc* descs, int64_t n, int grad_dtype, void* plan,
                            size_t plan_bytes, void* stream);
+
+/* The same two calls for lists that hold LPMM_KIND_4BIT_ND tensors.  inner_dims: host array of 7 sizes per tensor
+ * (d_2 .. d_p, unused entries ignored), inner_ndim: host array with p - 1 per tensor, 0 for tensors of other kinds.
+ * Two small kernels per tensor group are enqueued in addition (see lpmm_adamw4_nd_step). */
+size_t lpmm_adamw4_plan_bytes_nd(const lpmm_tensor_desc* descs, int64_t n, const int64_t* inner_dims,
+                                 const int32_t* inner_ndim);
+int lpmm_adamw4_plan_build_nd(const lpmm_tensor_desc* descs, int64_t n, const int64_t* inner_dims,
+                              const int32_t* inner_ndim, int grad_dtype, void* plan, size_t plan_bytes,
+                              void* stream);
 
 /* One step (same t, same hyper-parameters) for every tensor of the plan.  A plan holds its own
  * workspace, so plans (and single-tensor steps) may run concurrently on different streams as long

@@ -82,6 +82,9 @@ def lib() -> ctypes.CDLL:
         nd_args = [_VP] * 7 + [_VP, ctypes.c_int] + [_F] * 5 + [_I64, _VP]
         L.lpmm_adamw4_nd_step.argtypes = nd_args
         L.lpmm_adamw4_nd_step_bf16g.argtypes = nd_args
+        L.lpmm_adamw4_plan_bytes_nd.argtypes = [_VP, _I64, _VP, _VP]
+        L.lpmm_adamw4_plan_bytes_nd.restype = ctypes.c_size_t
+        L.lpmm_adamw4_plan_build_nd.argtypes = [_VP, _I64, _VP, _VP, ctypes.c_int, _VP, ctypes.c_size_t, _VP]
         L.lpmm_sgdm4_state_sizes.argtypes = [_I64, _VP]
         L.lpmm_sgdm4_state_zero.argtypes = [_VP, _VP, _I64, _VP]
         L.lpmm_sgdm4_step.argtypes = [_VP] * 4 + [_I64, _F, _F, _VP]
@@ -505,7 +508,7 @@ def lpmm_quant_state(which: int, x, rows, cols, codes, scale_a, scale_b, stream=
 
 # ---- many tensors in one call ------------------------------------------------------------------------
 
-KIND_4BIT, KIND_FP32, KIND_4BIT_B128, KIND_4BIT_FACTOR, KIND_SGDM_4BIT, KIND_SGDM_FP32 = 0, 1, 2, 3, 4, 5
+KIND_4BIT, KIND_FP32, KIND_4BIT_B128, KIND_4BIT_FACTOR, KIND_SGDM_4BIT, KIND_SGDM_FP32, KIND_4BIT_ND = 0, 1, 2, 3, 4, 5, 6
 FLAG_NO_DECAY = 1
 
 
@@ -524,6 +527,14 @@ def make_desc(param, grad, state, rows=None, cols=None, no_decay=False) -> Tenso
     if isinstance(state, StateFactor):
         return TensorDesc(_ptr(param), _ptr(grad), _ptr(state.m_codes), _ptr(state.m_blockscale), None,
                           _ptr(state.v_row), _ptr(state.v_col), state.rows, state.cols, KIND_4BIT_FACTOR, flags)
+    if isinstance(state, StateND):
+        cols = 1
+        for v in state.shape[1:]:
+            cols *= int(v)
+        d = TensorDesc(_ptr(param), _ptr(grad), _ptr(state.m_codes), _ptr(state.m_blockscale), _ptr(state.v_codes),
+                       _ptr(state.v_row), _ptr(state.v_col), int(state.shape[0]), cols, KIND_4BIT_ND, flags)
+        d.inner = tuple(int(v) for v in state.shape[1:])
+        return d
     if isinstance(state, StateB128):
         return TensorDesc(_ptr(param), _ptr(grad), _ptr(state.m_codes), _ptr(state.m_blockscale),
                           _ptr(state.v_codes), _ptr(state.v_blockscale), None, 1, state.numel,
@@ -537,16 +548,38 @@ def make_desc(param, grad, state, rows=None, cols=None, no_decay=False) -> Tenso
                       KIND_FP32, flags)
 
 
+def _inner_tables(descs):
+    """Side tables for LPMM_KIND_4BIT_ND descriptors (their inner sizes ride on the Python object as `.inner`)."""
+    if not any(getattr(d, "inner", None) for d in descs):
+        return None, None, None
+    dims = (ctypes.c_int64 * (7 * len(descs)))()
+    ndim = (ctypes.c_int32 * len(descs))()
+    for i, d in enumerate(descs):
+        inner = getattr(d, "inner", None) or ()
+        ndim[i] = len(inner)
+        for r, v in enumerate(inner[:7]):       # more than 7 inner sizes: the count alone makes the library refuse
+            dims[7 * i + r] = int(v)
+    return dims, ndim, (ctypes.addressof(dims), ctypes.addressof(ndim))
+
+
 def lpmm_adamw4_plan_bytes(descs) -> int:
     arr = (TensorDesc * len(descs))(*descs)
-    return int(lib().lpmm_adamw4_plan_bytes(ctypes.addressof(arr), len(descs)))
+    dims, ndim, ptrs = _inner_tables(descs)
+    if ptrs is None:
+        return int(lib().lpmm_adamw4_plan_bytes(ctypes.addressof(arr), len(descs)))
+    return int(lib().lpmm_adamw4_plan_bytes_nd(ctypes.addressof(arr), len(descs), *ptrs))
 
 
 def lpmm_adamw4_plan_build(descs, grad_dtype: int, plan, stream=None) -> None:
     arr = (TensorDesc * len(descs))(*descs)
     nbytes = plan.numel() * plan.element_size()
-    _check(lib().lpmm_adamw4_plan_build(ctypes.addressof(arr), len(descs), int(grad_dtype), _ptr(plan), nbytes,
-                                        _stream(stream)), "lpmm_adamw4_plan_build")
+    dims, ndim, ptrs = _inner_tables(descs)
+    if ptrs is None:
+        _check(lib().lpmm_adamw4_plan_build(ctypes.addressof(arr), len(descs), int(grad_dtype), _ptr(plan), nbytes,
+                                            _stream(stream)), "lpmm_adamw4_plan_build")
+    else:
+        _check(lib().lpmm_adamw4_plan_build_nd(ctypes.addressof(arr), len(descs), *ptrs, int(grad_dtype), _ptr(plan),
+                                               nbytes, _stream(stream)), "lpmm_adamw4_plan_build_nd")
 
 
 def lpmm_adamw4_step_multi(plan, lr, beta1, beta2, eps, weight_decay, step, stream=None) -> None:

@@ -70,6 +70,8 @@ struct Tensor4 {
     int no_decay;           // plans: this tensor takes no weight decay
     int c_extra;            // floats behind c_new (and room behind c) that the publishing workgroup moves and clears
                             // along with the column maxima (tensors with more than two dimensions)
+    int nd_index;           // plans: index into the plan's table of inner dimensions, -1 for matrices
+    int pad_;
 };
 
 // The tensor table of a plan lives in device memory.  A pointer read from memory is a generic
@@ -91,7 +93,7 @@ struct Tensor4Table {
     float LPMM_AS_GLOBAL* c_new;
     unsigned int LPMM_AS_GLOBAL* counter;
     int64_t rows, cols, P;
-    int nb, gx, gy, rw, strips, n_wg, kind, strips2, rw2, n_wg2, rs, rs2, tot_slots, flat, no_decay, c_extra;
+    int nb, gx, gy, rw, strips, n_wg, kind, strips2, rw2, n_wg2, rs, rs2, tot_slots, flat, no_decay, c_extra, nd_index, pad_;
 };
 static_assert(sizeof(Tensor4Table) == sizeof(Tensor4), "the table twin must mirror Tensor4");
 __device__ __forceinline__ Tensor4 from_table(const Tensor4Table& t) {
@@ -109,7 +111,7 @@ __device__ __forceinline__ Tensor4 from_table(const Tensor4Table& t) {
     a.rows = t.rows; a.cols = t.cols; a.P = t.P;
     a.nb = t.nb; a.gx = t.gx; a.gy = t.gy; a.rw = t.rw; a.strips = t.strips; a.n_wg = t.n_wg; a.kind = t.kind;
     a.strips2 = t.strips2; a.rw2 = t.rw2; a.n_wg2 = t.n_wg2; a.rs = t.rs; a.rs2 = t.rs2;
-    a.tot_slots = t.tot_slots; a.flat = t.flat; a.no_decay = t.no_decay; a.c_extra = t.c_extra;
+    a.tot_slots = t.tot_slots; a.flat = t.flat; a.no_decay = t.no_decay; a.c_extra = t.c_extra; a.nd_index = t.nd_index; a.pad_ = 0;
     return a;
 }
 #else
@@ -2054,11 +2056,11 @@ struct InnerDims {                  // dimensions 2..p
 // One workgroup per statistic: mu_new[first[r] + j] = max of colmax over the columns whose index in inner
 // dimension r is j (cols / d_r of them: col = a * d_r * inner + j * inner + b).  No atomics: with a small
 // dimension (a 3 x 3 kernel) thousands of columns share a statistic, and atomics on one address queue up.
-__global__ __launch_bounds__(kThreads) void nd_reduce_kernel(const float* colmax, float* mu_new, int64_t cols,
-                                                             const InnerDims dm) {
-    __shared__ float s_part[kThreads / 64];
+// `stat` = which statistic this workgroup computes (0 .. d_2 + ... + d_p - 1).
+__device__ __forceinline__ void nd_reduce_one(const float* colmax, float* mu_new, int64_t cols, const InnerDims& dm,
+                                              int64_t stat, float* s_part) {
     int r = 0;
-    int64_t j = blockIdx.x;                 // which statistic: dimension r, index j
+    int64_t j = stat;
     while (r < dm.n - 1 && j >= dm.d[r]) { j -= dm.d[r]; ++r; }
     int64_t inner = 1;
     for (int q = r + 1; q < dm.n; ++q) inner *= dm.d[q];
@@ -2077,9 +2079,8 @@ __global__ __launch_bounds__(kThreads) void nd_reduce_kernel(const float* colmax
 }
 
 // colscale[col] = min over the inner dimensions of mu[first[r] + idx_r(col)]
-__global__ __launch_bounds__(kThreads) void nd_expand_kernel(const float* mu, float* colscale, int64_t cols,
-                                                             const InnerDims dm) {
-    const int64_t col = int64_t(blockIdx.x) * kThreads + threadIdx.x;
+__device__ __forceinline__ void nd_expand_one(const float* mu, float* colscale, int64_t cols, const InnerDims& dm,
+                                              int64_t col) {
     if (col >= cols) return;
     int64_t rest = col;
     float m = 0.0f;
@@ -2090,6 +2091,45 @@ __global__ __launch_bounds__(kThreads) void nd_expand_kernel(const float* mu, fl
         m = (r == dm.n - 1) ? v : fminf(m, v);
     }
     colscale[col] = m;
+}
+
+__global__ __launch_bounds__(kThreads) void nd_reduce_kernel(const float* colmax, float* mu_new, int64_t cols,
+                                                             const InnerDims dm) {
+    __shared__ float s_part[kThreads / 64];
+    nd_reduce_one(colmax, mu_new, cols, dm, blockIdx.x, s_part);
+}
+
+__global__ __launch_bounds__(kThreads) void nd_expand_kernel(const float* mu, float* colscale, int64_t cols,
+                                                             const InnerDims dm) {
+    nd_expand_one(mu, colscale, cols, dm, int64_t(blockIdx.x) * kThreads + threadIdx.x);
+}
+
+// The two small kernels between the passes for all tensors with more than two dimensions of one group of a plan.
+struct NdPhase {
+    const Tensor4Table* tensors;
+    const InnerDims* dims;          // device table, indexed by Tensor4::nd_index
+    int n_seg, n_r, n_e;            // tensors; workgroups of the reduce and of the expand kernel
+    Segment seg_r[kMaxSeg];         // per tensor: first workgroup of the reduce kernel (one per statistic)
+    Segment seg_e[kMaxSeg];         // per tensor: first workgroup of the expand kernel (one per 256 columns)
+};
+
+__global__ __launch_bounds__(kThreads) void nd_plan_reduce(const NdPhase ph) {
+    __shared__ float s_part[kThreads / 64];
+    const int x = blockIdx.x;
+    if (x >= ph.n_r) return;
+    const Segment sg = find_segment(ph.seg_r, ph.n_seg, x);
+    const Tensor4 a = from_table(ph.tensors[sg.tensor]);
+    const InnerDims dm = ph.dims[a.nd_index];
+    nd_reduce_one(a.c_new, a.c_new + a.cols, a.cols, dm, x - sg.wg_begin, s_part);
+}
+
+__global__ __launch_bounds__(kThreads) void nd_plan_expand(const NdPhase ph) {
+    const int x = blockIdx.x;
+    if (x >= ph.n_e) return;
+    const Segment sg = find_segment(ph.seg_e, ph.n_seg, x);
+    const Tensor4 a = from_table(ph.tensors[sg.tensor]);
+    const InnerDims dm = ph.dims[a.nd_index];
+    nd_expand_one(a.c_new + a.cols, a.c_new, a.cols, dm, int64_t(x - sg.wg_begin) * kThreads + threadIdx.x);
 }
 
 // The same for a plan whose 2-dimensional tensors keep a factorized second moment: "A" work is the

@@ -554,6 +554,9 @@ struct PhaseLaunch {
     int grid_a;      // A work alone
     int grid_b;      // B work alone
     bool a_has_rank1;   // some A tensor takes pass 1 of the rank-1 path (else the lighter kernel variant runs)
+    // tensors with more than two dimensions among the B tensors: two small kernels run before their pass 2
+    NdPhase nd;
+    bool has_nd;
 };
 
 struct PlanHost {
@@ -582,27 +585,53 @@ struct PlanHost {
 std::unordered_map<void*, std::unique_ptr<PlanHost>> g_plans;
 
 struct PlanLayout {
-    size_t off_tensors, off_counters, off_floats, total;
+    size_t off_tensors, off_dims, off_counters, off_floats, total;
+    int64_t n_nd;
 };
 
 bool desc_shape_ok(const lpmm_tensor_desc& d) {
     int64_t shape[2] = {d.rows, d.cols}, r, c;
     return check_shape(shape, &r, &c) == LPMM_OK && (d.kind == LPMM_KIND_4BIT || d.kind == LPMM_KIND_FP32 ||
                                                      d.kind == LPMM_KIND_4BIT_B128 || d.kind == LPMM_KIND_4BIT_FACTOR ||
-                                                     d.kind == LPMM_KIND_SGDM_4BIT || d.kind == LPMM_KIND_SGDM_FP32);
+                                                     d.kind == LPMM_KIND_SGDM_4BIT || d.kind == LPMM_KIND_SGDM_FP32 ||
+                                                     d.kind == LPMM_KIND_4BIT_ND);
 }
 
-bool plan_layout(const lpmm_tensor_desc* descs, int64_t n, PlanLayout* L) {
+// inner dimensions of tensor i of a plan: inner_dims holds kMaxInnerDims sizes per tensor, inner_ndim their count
+// (0 for tensors that are not LPMM_KIND_4BIT_ND).  Fills dm and ext (the number of statistics of those dimensions).
+bool plan_inner_dims(const lpmm_tensor_desc& d, int64_t i, const int64_t* inner_dims, const int32_t* inner_ndim,
+                     InnerDims* dm, int64_t* ext) {
+    if (!inner_dims || !inner_ndim) return false;
+    const int k = inner_ndim[i];
+    if (k < 1 || k > kMaxInnerDims) return false;
+    int64_t dims[1 + kMaxInnerDims];
+    dims[0] = d.rows;
+    for (int r = 0; r < k; ++r) dims[1 + r] = inner_dims[i * kMaxInnerDims + r];
+    int64_t rows, cols;
+    if (nd_shape(dims, 1 + k, &rows, &cols, ext, dm) != LPMM_OK) return false;
+    return cols == d.cols;
+}
+
+bool plan_layout(const lpmm_tensor_desc* descs, int64_t n, const int64_t* inner_dims, const int32_t* inner_ndim,
+                 PlanLayout* L) {
     if (!descs || n < 1 || n > (1 << 20)) return false;
-    int64_t floats = 0;
+    int64_t floats = 0, n_nd = 0;
     bool rank1 = false, factor = false;
     for (int64_t i = 0; i < n; ++i) {
         if (!desc_shape_ok(descs[i])) return false;
         if (descs[i].kind == LPMM_KIND_4BIT || descs[i].kind == LPMM_KIND_4BIT_FACTOR)
             floats += round_up(descs[i].rows, 64) + round_up(descs[i].cols, 64);
-        if (descs[i].kind == LPMM_KIND_4BIT) rank1 = true;
+        if (descs[i].kind == LPMM_KIND_4BIT_ND) {
+            InnerDims dm;
+            int64_t ext;
+            if (!plan_inner_dims(descs[i], i, inner_dims, inner_ndim, &dm, &ext)) return false;
+            floats += round_up(descs[i].rows, 64) + round_up(descs[i].cols + ext, 64);
+            ++n_nd;
+        }
+        if (descs[i].kind == LPMM_KIND_4BIT || descs[i].kind == LPMM_KIND_4BIT_ND) rank1 = true;
         if (descs[i].kind == LPMM_KIND_4BIT_FACTOR) factor = true;
     }
+    L->n_nd = n_nd;
     int64_t n_sgdm = 0;
     for (int64_t i = 0; i < n; ++i)
         if (descs[i].kind == LPMM_KIND_SGDM_4BIT || descs[i].kind == LPMM_KIND_SGDM_FP32) ++n_sgdm;
@@ -610,6 +639,7 @@ bool plan_layout(const lpmm_tensor_desc* descs, int64_t n, PlanLayout* L) {
     if (n_sgdm != 0 && n_sgdm != n) return false;
     size_t off = 0;
     L->off_tensors = off;   off += size_t(round_up(n * int64_t(sizeof(Tensor4)), 256));
+    L->off_dims = off;      off += size_t(round_up(n_nd * int64_t(sizeof(InnerDims)), 256));
     L->off_counters = off;  off += size_t(n) * kCounterWords * sizeof(unsigned int);
     L->off_floats = off;    off += size_t(floats) * sizeof(float);
     L->total = size_t(round_up(int64_t(off), 256));
@@ -1002,14 +1032,25 @@ int lpmm_quant_state(int which, const float* in, const int64_t shape[2], uint8_t
 }
 
 size_t lpmm_adamw4_plan_bytes(const lpmm_tensor_desc* descs, int64_t n) {
+    return lpmm_adamw4_plan_bytes_nd(descs, n, nullptr, nullptr);
+}
+
+size_t lpmm_adamw4_plan_bytes_nd(const lpmm_tensor_desc* descs, int64_t n, const int64_t* inner_dims,
+                                 const int32_t* inner_ndim) {
     PlanLayout L;
-    return plan_layout(descs, n, &L) ? L.total : 0;
+    return plan_layout(descs, n, inner_dims, inner_ndim, &L) ? L.total : 0;
 }
 
 int lpmm_adamw4_plan_build(const lpmm_tensor_desc* descs, int64_t n, int grad_dtype, void* plan,
                            size_t plan_bytes, void* stream) {
+    return lpmm_adamw4_plan_build_nd(descs, n, nullptr, nullptr, grad_dtype, plan, plan_bytes, stream);
+}
+
+int lpmm_adamw4_plan_build_nd(const lpmm_tensor_desc* descs, int64_t n, const int64_t* inner_dims,
+                              const int32_t* inner_ndim, int grad_dtype, void* plan, size_t plan_bytes,
+                              void* stream) {
     PlanLayout L;
-    if (!plan_layout(descs, n, &L)) return LPMM_EINVAL;
+    if (!plan_layout(descs, n, inner_dims, inner_ndim, &L)) return LPMM_EINVAL;
     if (!plan || !aligned(plan, 256) || plan_bytes < L.total) return LPMM_EINVAL;
     if (grad_dtype != LPMM_GRAD_F32 && grad_dtype != LPMM_GRAD_BF16) return LPMM_EINVAL;
     DeviceCtx* ctx;
@@ -1023,9 +1064,12 @@ int lpmm_adamw4_plan_build(const lpmm_tensor_desc* descs, int64_t n, int grad_dt
     host->device = dev;
     host->staging.assign(L.off_counters, 0);
     Tensor4* tens = reinterpret_cast<Tensor4*>(host->staging.data() + L.off_tensors);
+    InnerDims* h_dims = reinterpret_cast<InnerDims*>(host->staging.data() + L.off_dims);
+    int64_t n_nd = 0;
     char* dplan = static_cast<char*>(plan);
     const Tensor4* d_tens = reinterpret_cast<const Tensor4*>(dplan + L.off_tensors);
     float* d_floats = reinterpret_cast<float*>(dplan + L.off_floats);
+    const InnerDims* d_dims = reinterpret_cast<const InnerDims*>(dplan + L.off_dims);
     unsigned int* d_counters = reinterpret_cast<unsigned int*>(dplan + L.off_counters);
 
     const int64_t rw_hint = env_int("LPMM_MULTI_RW", -1);      // -1: the plan defaults (64 rows, 32 for the flat tiling)
@@ -1042,7 +1086,8 @@ int lpmm_adamw4_plan_build(const lpmm_tensor_desc* descs, int64_t n, int grad_dt
         int64_t p_rank1 = 0, p_big = 0, acc = 0, in_group = 0, n_groups = 0;
         for (int64_t i = 0; i < n; ++i) {
             const int64_t P = descs[i].rows * descs[i].cols;
-            if (descs[i].kind == LPMM_KIND_4BIT && fast_eligible(descs[i].cols, descs[i].v_colmax)) {
+            if ((descs[i].kind == LPMM_KIND_4BIT || descs[i].kind == LPMM_KIND_4BIT_ND) &&
+                fast_eligible(descs[i].cols, descs[i].v_colmax)) {
                 p_rank1 += P;
                 if (P >= kFlatMinElems) p_big += P;
             }
@@ -1121,10 +1166,21 @@ int lpmm_adamw4_plan_build(const lpmm_tensor_desc* descs, int64_t n, int grad_dt
             t.ms = d.m_blockscale;
             t.r = d.v_rowmax;
             t.c = d.v_colmax;
+            t.nd_index = -1;
+            int64_t ext = 0;
+            if (d.kind == LPMM_KIND_4BIT_ND) {
+                // more than two dimensions: v_colmax holds the column scales and, behind them, the statistics of
+                // the inner dimensions; the workspace mirrors that layout (see lpmm_adamw4_nd_step)
+                InnerDims dm;
+                if (!plan_inner_dims(d, i, inner_dims, inner_ndim, &dm, &ext)) return LPMM_EINVAL;
+                h_dims[n_nd] = dm;
+                t.nd_index = int(n_nd++);
+                t.c_extra = int(ext);
+            }
             t.r_new = d_floats + fofs;
             fofs += round_up(d.rows, 64);
             t.c_new = d_floats + fofs;
-            fofs += round_up(d.cols, 64);
+            fofs += round_up(d.cols + ext, 64);
             t.counter = d_counters + i * kCounterWords;
             if (fast_eligible(d.cols, d.v_colmax)) {
                 t.kind = kQuantFast;
@@ -1163,7 +1219,17 @@ int lpmm_adamw4_plan_build(const lpmm_tensor_desc* descs, int64_t n, int grad_dt
                     continue;
                 pl.ph.seg_b[pl.ph.n_seg_b++] = Segment{pl.ph.n_b, int(i)};
                 pl.ph.n_b += tens[i].n_wg2;
+                if (tens[i].nd_index >= 0 && (tens[i].kind == kQuantFast || tens[i].kind == kQuantGeneral)) {
+                    pl.has_nd = true;
+                    pl.nd.seg_r[pl.nd.n_seg] = Segment{pl.nd.n_r, int(i)};
+                    pl.nd.seg_e[pl.nd.n_seg] = Segment{pl.nd.n_e, int(i)};
+                    ++pl.nd.n_seg;
+                    pl.nd.n_r += tens[i].c_extra;                                       // one workgroup per statistic
+                    pl.nd.n_e += int((tens[i].cols + kThreads - 1) / kThreads);
+                }
             }
+        pl.nd.tensors = pl.ph.tensors;
+        pl.nd.dims = d_dims;
         if (pl.ph.n_a + pl.ph.n_b == 0) continue;
         if (int64_t(pl.ph.n_a) + pl.ph.n_b > (int64_t(1) << 30)) return LPMM_EINVAL;
         pl.grid = pad8(int64_t(pl.ph.n_a) + pl.ph.n_b);
@@ -1194,6 +1260,15 @@ int lpmm_adamw4_plan_build(const lpmm_tensor_desc* descs, int64_t n, int grad_dt
 
 int lpmm_adamw4_step_multi(void* plan, float lr, float beta1, float beta2, float eps, float weight_decay,
                            int64_t step, void* stream) {
+#define LPMM_CHECK(call) do { const int rc_ = (call); if (rc_) return rc_; } while (0)
+    // column maxima -> new statistics -> new column scales, for the group's tensors with more than two dimensions
+    auto launch_nd = [](const PhaseLaunch& pl, hipStream_t on) -> int {
+        hipLaunchKernelGGL(nd_plan_reduce, dim3(pl.nd.n_r), dim3(kThreads), 0, on, pl.nd);
+        LPMM_HIP(hipGetLastError());
+        hipLaunchKernelGGL(nd_plan_expand, dim3(pl.nd.n_e), dim3(kThreads), 0, on, pl.nd);
+        LPMM_HIP(hipGetLastError());
+        return LPMM_OK;
+    };
     Hyper h;
     const int rc = make_hyper(lr, beta1, beta2, eps, weight_decay, step, &h);
     if (rc) return rc;
@@ -1241,6 +1316,7 @@ int lpmm_adamw4_step_multi(void* plan, float lr, float beta1, float beta2, float
                 const bool rec = host->factor && g_prof.on && g_prof.calls < g_prof.max_calls;
                 const int64_t call = g_prof.calls;
                 if (rec) LPMM_HIP(hipEventRecord(prof_event(call, 0), s2));
+                if (pl.has_nd) LPMM_CHECK(launch_nd(pl, s2));
                 launch(2, pl.grid_b, s2, pl);
                 LPMM_HIP(hipGetLastError());
                 if (rec) {
@@ -1278,6 +1354,7 @@ int lpmm_adamw4_step_multi(void* plan, float lr, float beta1, float beta2, float
         const int64_t call = g_prof.calls;
         if (rec) LPMM_HIP(hipEventRecord(prof_event(call, 0), s));
         // a launch that holds only one kind of work takes that kind's (lighter) kernel
+        if (pl.has_nd) LPMM_CHECK(launch_nd(pl, s));      // the A work of these tensors ran in the previous launch
         const int roles = pl.ph.n_b == 0 ? (pl.a_has_rank1 ? 1 : 3) : (pl.ph.n_a == 0 ? 2 : 0);
         launch(roles, pl.grid, s, pl);
         LPMM_HIP(hipGetLastError());

@@ -94,8 +94,9 @@ class _PlanOptimizer:
 class AdamW4bit(_PlanOptimizer):
     """4-bit AdamW.  second_moment: "rank1" (rank-1/Linear for matrices, the paper's 4-bit AdamW), "factor" (row and
     column statistics for matrices, the paper's 4-bit Factor) or "b128" (every tensor flat, block-wise).  Tensors
-    with more than two dimensions are taken as (shape[0], rest) matrices; tensors of at most 4096 elements and
-    1-dimensional ones keep fp32 states (1-dimensional tensors above 4096 elements: block-wise 4-bit states)."""
+    with 3 to 8 dimensions get one statistic per index of every dimension under "rank1" and are taken as
+    (shape[0], rest) matrices under "factor" (and beyond 8 dimensions); tensors of at most 4096 elements keep fp32
+    states, larger 1-dimensional ones block-wise 4-bit states."""
 
     def __init__(self, params, lr=1e-3, betas=(0.9, 0.999), eps=1e-8, weight_decay=1e-2, second_moment="rank1",
                  no_decay=_default_no_decay):
@@ -111,7 +112,11 @@ class AdamW4bit(_PlanOptimizer):
         if p.ndim <= 1 or self.second_moment == "b128":
             return _b.new_state_b128(n, p.device)
         rows, cols = p.shape[0], n // p.shape[0]
-        return (_b.new_state_factor if self.second_moment == "factor" else _b.new_state)(rows, cols, p.device)
+        if self.second_moment == "factor":
+            return _b.new_state_factor(rows, cols, p.device)
+        if 3 <= p.ndim <= 8:
+            return _b.new_state_nd(tuple(p.shape), p.device)      # rank-1 normalization over every dimension
+        return _b.new_state(rows, cols, p.device)
 
     def _desc(self, p, g, st):
         nd = bool(self.no_decay(p))

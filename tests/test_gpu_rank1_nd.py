@@ -165,3 +165,75 @@ def test_bad_arguments_are_rejected():
     huge = lpmm.StateND((1 << 30, 1 << 8, 2), st.m_codes, st.m_blockscale, st.v_codes, st.v_row, st.v_col)
     with pytest.raises(lpmm.LpmmError):                      # far beyond any registered workspace: rejected before a launch
         lpmm.lpmm_adamw4_nd_step(w, g, huge, 1e-3, 0.9, 0.999, 1e-8, 0.0, 1)
+
+
+@pytest.mark.parametrize("env", [{}, {"LPMM_PHASE_MPARAMS": "1"}, {"LPMM_PHASE_MPARAMS": "1", "LPMM_MULTI_STREAMS": "1"},
+                                 {"LPMM_PHASE_MPARAMS": "1", "LPMM_FLAT": "1"}],
+                         ids=["one-group", "two-streams", "fused-launches", "flat"])
+def test_plan_with_n_dimensional_tensors(env):
+    """Convolution-shaped tensors, matrices and small fp32-state tensors in one plan."""
+    seed = 64
+    items = [("conv1", (64, 32, 3, 3)), ("fc", (256, 384)), ("bias", (384,)), ("conv2", (96, 16, 4, 4)),
+             ("odd", (40, 5, 7)), ("cube", (128, 8, 16)), ("fc2", (300, 256))]
+    for k in ("LPMM_PHASE_MPARAMS", "LPMM_MULTI_STREAMS", "LPMM_FLAT"):
+        os.environ.pop(k, None)
+    os.environ.update(env)
+    try:
+        lpmm.ensure_init(4096)
+        dev, ref, descs = [], [], []
+        for tid, (name, shape) in enumerate(items):
+            P = int(np.prod(shape))
+            rows, cols = shape[0], P // shape[0]
+            w_ref = workloads.weights(seed, tid, rows, cols).reshape(-1)
+            w, g = to_dev(w_ref.copy()), torch.empty(P, device=DEV)
+            if len(shape) > 2:
+                st, st_ref = lpmm.new_state_nd(shape, DEV), oracle.state_zero_nd(shape)
+                descs.append(lpmm.make_desc(w, g, st))
+            elif len(shape) == 2:
+                st, st_ref = lpmm.new_state(rows, cols, DEV), oracle.state_zero(rows, cols)
+                descs.append(lpmm.make_desc(w, g, st))
+            else:
+                st = (torch.zeros(P, device=DEV), torch.zeros(P, device=DEV))
+                st_ref = (np.zeros(P, np.float32), np.zeros(P, np.float32))
+                descs.append(lpmm.make_desc(w, g, st, 1, P))
+            dev.append((w, g, st))
+            ref.append((w_ref, st_ref))
+        plan = lpmm.new_plan(descs, 0, DEV)
+        for t in (1, 2, 3):
+            grads = []
+            for tid, (name, shape) in enumerate(items):
+                P = int(np.prod(shape))
+                grads.append(workloads.grads(seed, tid, t, shape[0], P // shape[0], "col_lognormal").reshape(-1))
+            for (w, g, st), gn in zip(dev, grads):
+                g.copy_(to_dev(gn))
+            lpmm.lpmm_adamw4_step_multi(plan, HP.lr, HP.beta1, HP.beta2, HP.eps, HP.weight_decay, t)
+            torch.cuda.synchronize()
+            for (name, shape), (w, g, st), (w_ref, st_ref), gn in zip(items, dev, ref, grads):
+                tag = f"{name} {shape} step {t}"
+                if len(shape) > 2:
+                    mt, vt = oracle.adamw4_nd_step(w_ref, gn, st_ref, HP, t, want_moments=True)
+                    got, inner = download(st)
+                    np.testing.assert_array_equal(inner, st_ref.v_stats[shape[0]:], err_msg=tag)
+                    assert compare_step(got, as_matrix_state(st_ref), w.cpu().numpy(), w_ref, mt, vt, tag) == 0
+                elif len(shape) == 2:
+                    mt, vt = oracle.adamw4_step(w_ref, gn, st_ref, HP, t, want_moments=True)
+                    assert compare_step(download_state(st), st_ref, w.cpu().numpy(), w_ref, mt, vt, tag) == 0
+                else:
+                    oracle.adamw32_step(w_ref, gn, st_ref[0], st_ref[1], HP, t)
+                    np.testing.assert_array_equal(st[0].cpu().numpy(), st_ref[0], err_msg=tag)
+        lpmm.lpmm_adamw4_plan_release(plan)
+    finally:
+        for k in env:
+            os.environ.pop(k, None)
+
+
+def test_plan_rejects_inner_sizes_that_do_not_match():
+    lpmm.ensure_init(4096)
+    st = lpmm.new_state_nd((8, 4, 32), DEV)
+    w, g = torch.zeros(1024, device=DEV), torch.zeros(1024, device=DEV)
+    d = lpmm.make_desc(w, g, st)
+    assert lpmm.lpmm_adamw4_plan_bytes([d]) > 0
+    d.inner = (4, 31)
+    assert lpmm.lpmm_adamw4_plan_bytes([d]) == 0
+    d.inner = ()
+    assert lpmm.lpmm_adamw4_plan_bytes([d]) == 0

@@ -197,3 +197,21 @@ def test_sgdm_state_sizes_and_argument_errors():
     d = lpmm.TensorDesc(p, p, p, p, None, None, None, 1, 256, lpmm.KIND_SGDM_4BIT, 0)
     a = lpmm.TensorDesc(p, p, p, p, p, p, p, 2, 128, lpmm.KIND_4BIT, 0)
     assert lpmm.lpmm_adamw4_plan_bytes([d]) > 0 and lpmm.lpmm_adamw4_plan_bytes([d, a]) == 0
+
+
+def test_plan_bytes_with_inner_dimension_tables():
+    buf = ctypes.create_string_buffer(4096 + 256)
+    p = (ctypes.addressof(buf) + 255) // 256 * 256
+    d = lpmm.TensorDesc(p, p, p, p, p, p, p, 8, 128, lpmm.KIND_4BIT_ND, 0)
+    assert lpmm.lpmm_adamw4_plan_bytes([d]) == 0                       # no inner sizes given
+    d.inner = (4, 32)
+    with_nd = lpmm.lpmm_adamw4_plan_bytes([d])
+    plain = lpmm.lpmm_adamw4_plan_bytes([lpmm.TensorDesc(p, p, p, p, p, p, p, 8, 128, lpmm.KIND_4BIT, 0)])
+    assert with_nd > plain > 0                                         # the statistics of the inner dimensions
+    d.inner = (4, 31)
+    assert lpmm.lpmm_adamw4_plan_bytes([d]) == 0                       # product differs from cols
+    d.inner = (2,) * 8
+    assert lpmm.lpmm_adamw4_plan_bytes([d]) == 0                       # too many dimensions
+    f = lpmm.TensorDesc(p, p, p, p, None, p, p, 8, 128, lpmm.KIND_4BIT_FACTOR, 0)
+    d.inner = (4, 32)
+    assert lpmm.lpmm_adamw4_plan_bytes([d, f]) == 0                    # rank-1 and factorized tensors do not mix
