@@ -114,3 +114,32 @@ def test_bad_parameters_are_rejected():
     opt = lpmm.AdamW4bit([torch.zeros(64, 128, device=DEV, requires_grad=True)])
     with pytest.raises(ValueError):
         opt.step()                                                       # no gradient yet
+
+
+def test_adamw4bit_with_a_convolution_weight():
+    """A 4-dimensional parameter takes the rank-1 second moment over all its dimensions (App. F Alg. 4)."""
+    import test_gpu_rank1_nd as tn
+    print("\n[gpu-test] AdamW4bit with a conv weight", flush=True)
+    hp = oracle.Hyper(lr=1e-3, weight_decay=0.05)
+    torch.manual_seed(5)
+    conv = torch.nn.Conv2d(16, 64, 3).to(DEV)
+    opt = lpmm.AdamW4bit(conv.parameters(), lr=hp.lr, betas=(hp.beta1, hp.beta2), eps=hp.eps, weight_decay=hp.weight_decay)
+    shape = tuple(conv.weight.shape)
+    w_ref = conv.weight.detach().cpu().numpy().reshape(-1).copy()
+    st_ref = oracle.state_zero_nd(shape)
+    for t in (1, 2, 3):
+        g = torch.Generator(device="cpu").manual_seed(2000 + t)
+        x = torch.randn(4, 16, 12, 12, generator=g).to(DEV)
+        (conv(x) ** 2).mean().backward()
+        gw = conv.weight.grad.detach().cpu().numpy().reshape(-1).copy()
+        opt.step()
+        torch.cuda.synchronize()
+        mt, vt = oracle.adamw4_nd_step(w_ref, gw, st_ref, hp, t, want_moments=True)
+        st = opt.state_buffers()[0]
+        assert isinstance(st, lpmm.StateND)
+        got, inner = tn.download(st)
+        np.testing.assert_array_equal(inner, st_ref.v_stats[shape[0]:])
+        assert compare_step(got, tn.as_matrix_state(st_ref), conv.weight.detach().cpu().numpy().reshape(-1), w_ref, mt, vt,
+                            f"conv step {t}") == 0
+        conv.weight.data.copy_(torch.from_numpy(w_ref).view_as(conv.weight))
+        opt.zero_grad()
