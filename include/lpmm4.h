@@ -342,6 +342,16 @@ int lpmm_adamw4_step_multi(void* plan, float lr, float beta1, float beta2, float
  * (lpmm_adamw4_step_multi rejects such a plan, and this call rejects the others). */
 int lpmm_sgdm4_step_multi(void* plan, float lr, float momentum, void* stream);
 
+/* The same steps with the learning rate and the step number read from DEVICE memory when the kernels run (lr:
+ * one float, step: one int64, values >= 1), for callers that capture the step into a HIP graph and replay it while
+ * a schedule changes the rate and the step counts up: the bias corrections of Eq. 1 are evaluated on the device by
+ * a one-thread kernel enqueued in front of the step's launches (into a slot inside the plan).  The other
+ * hyper-parameters are captured by value.  Nothing is allocated, copied or synchronized.  The caller guarantees
+ * lr >= 0 and step >= 1 (a smaller step is taken as 1); they cannot be checked here. */
+int lpmm_adamw4_step_multi_capturable(void* plan, const float* lr, const int64_t* step, float beta1, float beta2,
+                                      float eps, float weight_decay, void* stream);
+int lpmm_sgdm4_step_multi_capturable(void* plan, const float* lr, float momentum, void* stream);
+
 /* Forgets the host-side record of a plan (the device memory stays the caller's). */
 int lpmm_adamw4_plan_release(void* plan);
 

@@ -91,6 +91,8 @@ def lib() -> ctypes.CDLL:
         L.lpmm_sgdm4_step_bf16g.argtypes = [_VP] * 4 + [_I64, _F, _F, _VP]
         L.lpmm_sgdm32_step.argtypes = [_VP] * 3 + [_I64, ctypes.c_int, _F, _F, _VP]
         L.lpmm_sgdm4_step_multi.argtypes = [_VP, _F, _F, _VP]
+        L.lpmm_adamw4_step_multi_capturable.argtypes = [_VP, _VP, _VP, _F, _F, _F, _F, _VP]
+        L.lpmm_sgdm4_step_multi_capturable.argtypes = [_VP, _VP, _F, _VP]
         L.lpmm_adamw4_factor_state_sizes.argtypes = [_VP, _VP]
         L.lpmm_adamw4_factor_state_zero.argtypes = [_VP] * 4 + [_VP, _VP]
         factor_args = [_VP] * 6 + [_VP] + [_F] * 5 + [_I64, _VP]
@@ -585,6 +587,17 @@ def lpmm_adamw4_plan_build(descs, grad_dtype: int, plan, stream=None) -> None:
 def lpmm_adamw4_step_multi(plan, lr, beta1, beta2, eps, weight_decay, step, stream=None) -> None:
     _check(lib().lpmm_adamw4_step_multi(_ptr(plan), lr, beta1, beta2, eps, weight_decay, int(step),
                                         _stream(stream)), "lpmm_adamw4_step_multi")
+
+
+def lpmm_adamw4_step_multi_capturable(plan, lr_dev, step_dev, beta1, beta2, eps, weight_decay, stream=None) -> None:
+    """lr_dev: float32 tensor of one element on the device, step_dev: int64 tensor of one element on the device."""
+    _check(lib().lpmm_adamw4_step_multi_capturable(_ptr(plan), _ptr(lr_dev), _ptr(step_dev), beta1, beta2, eps,
+                                                   weight_decay, _stream(stream)), "lpmm_adamw4_step_multi_capturable")
+
+
+def lpmm_sgdm4_step_multi_capturable(plan, lr_dev, momentum, stream=None) -> None:
+    _check(lib().lpmm_sgdm4_step_multi_capturable(_ptr(plan), _ptr(lr_dev), momentum, _stream(stream)),
+           "lpmm_sgdm4_step_multi_capturable")
 
 
 def lpmm_adamw4_plan_release(plan) -> None:

@@ -1959,6 +1959,43 @@ __global__ __launch_bounds__(kThreads) void adamw32_kernel(float* p, const void*
 // holds memory-bound pass-1 workgroups next to arithmetic-bound pass-2 workgroups.
 // =====================================================================================================
 
+// Hyper-parameters of a plan's launches: by value, or -- for a step that is captured into a graph and replayed
+// while the learning rate and the step number change -- read from device memory, where a one-thread kernel
+// enqueued in front of the step has put them.
+struct HyperArg {
+    Hyper h;
+    const Hyper* dev;       // non-null: use *dev
+};
+__device__ __forceinline__ Hyper resolve(const HyperArg& a) { return a.dev ? *a.dev : a.h; }
+
+// the host's make_hyper on the device: lr and the step number come from device memory
+__global__ void hyper_prepare_kernel(const float* lr_dev, const int64_t* step_dev, float beta1, float beta2, float eps,
+                                     float wd, Hyper* out) {
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    const double lr = double(*lr_dev);
+    int64_t t = *step_dev;
+    if (t < 1) t = 1;
+    Hyper h;
+    h.beta1 = beta1;
+    h.beta2 = beta2;
+    h.omb1 = 1.0f - beta1;
+    h.omb2 = 1.0f - beta2;
+    h.eps = eps;
+    const double bc1 = 1.0 - pow(double(beta1), double(t));
+    const double bc2 = 1.0 - pow(double(beta2), double(t));
+    h.step_size = float(lr / bc1);
+    h.inv_sqrt_bc2 = float(1.0 / sqrt(bc2));
+    h.lr_wd = float(lr * double(wd));
+    *out = h;
+}
+__global__ void sgdm_hyper_prepare_kernel(const float* lr_dev, float momentum, Hyper* out) {
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    Hyper h{};
+    h.beta1 = momentum;
+    h.step_size = *lr_dev;
+    *out = h;
+}
+
 struct Segment {        // a run of workgroups that work on one tensor
     int wg_begin;       // first workgroup of the run, in its kind's numbering
     int tensor;         // index into the tensor table
@@ -1998,7 +2035,8 @@ __device__ __forceinline__ Segment find_segment(const Segment* seg, int n_seg, i
 // path: launched on their own (on a second stream), the light pass-2 workgroups fit into the
 // register space that the resident pass-1 workgroups leave free.
 template <bool BF16, int ROLES>
-__global__ __launch_bounds__(kThreads) void phase_kernel(const Phase ph, const Hyper h) {
+__global__ __launch_bounds__(kThreads) void phase_kernel(const Phase ph, const HyperArg ha) {
+    const Hyper h = resolve(ha);
     const int x = logical_wg();
     constexpr bool kOnlyA = ROLES == 1 || ROLES == 3;
     const int n = (ROLES == 2 ? 0 : ph.n_a) + (kOnlyA ? 0 : ph.n_b);
@@ -2137,7 +2175,8 @@ __global__ __launch_bounds__(kThreads) void nd_plan_expand(const NdPhase ph) {
 // the update pass.  ROLES: 0 = both interleaved, 1 = A only, 2 = B only.  Separate kernels, so that the
 // rank-1 kernels above keep their register footprint.
 template <bool BF16, int ROLES>
-__global__ __launch_bounds__(kThreads) void factor_phase_kernel(const Phase ph, const Hyper h) {
+__global__ __launch_bounds__(kThreads) void factor_phase_kernel(const Phase ph, const HyperArg ha) {
+    const Hyper h = resolve(ha);
     __shared__ Lds s;
     const int x = logical_wg();
     const int n = (ROLES == 2 ? 0 : ph.n_a) + (ROLES == 1 ? 0 : ph.n_b);
@@ -2173,7 +2212,8 @@ __global__ __launch_bounds__(kThreads) void factor_phase_kernel(const Phase ph, 
 
 // A plan of SGD-with-momentum tensors (App. E Alg. 2): everything is one pass, so only "A" work exists.
 template <bool BF16>
-__global__ __launch_bounds__(kThreads) void sgdm_phase_kernel(const Phase ph, const Hyper h) {
+__global__ __launch_bounds__(kThreads) void sgdm_phase_kernel(const Phase ph, const HyperArg ha) {
+    const Hyper h = resolve(ha);
     __shared__ Lds s;
     const int x = logical_wg();
     if (x >= ph.n_a) return;

@@ -565,6 +565,7 @@ struct PlanHost {
     bool bf16 = false;
     bool factor = false;                // the plan's 2-dimensional tensors keep a factorized second moment
     bool sgdm = false;                  // a plan of SGD-with-momentum tensors (lpmm_sgdm4_step_multi)
+    Hyper* d_hyper = nullptr;           // device slot inside the plan for the hyper-parameters of a captured step
     int device = 0;
     // second stream for pass 2 (same priority as any other stream), with its ordering events
     hipStream_t side = nullptr;
@@ -585,7 +586,7 @@ struct PlanHost {
 std::unordered_map<void*, std::unique_ptr<PlanHost>> g_plans;
 
 struct PlanLayout {
-    size_t off_tensors, off_dims, off_counters, off_floats, total;
+    size_t off_tensors, off_dims, off_hyper, off_counters, off_floats, total;
     int64_t n_nd;
 };
 
@@ -640,6 +641,7 @@ bool plan_layout(const lpmm_tensor_desc* descs, int64_t n, const int64_t* inner_
     size_t off = 0;
     L->off_tensors = off;   off += size_t(round_up(n * int64_t(sizeof(Tensor4)), 256));
     L->off_dims = off;      off += size_t(round_up(n_nd * int64_t(sizeof(InnerDims)), 256));
+    L->off_hyper = off;     off += 256;                       // hyper-parameters of a captured step
     L->off_counters = off;  off += size_t(n) * kCounterWords * sizeof(unsigned int);
     L->off_floats = off;    off += size_t(floats) * sizeof(float);
     L->total = size_t(round_up(int64_t(off), 256));
@@ -1070,6 +1072,7 @@ int lpmm_adamw4_plan_build_nd(const lpmm_tensor_desc* descs, int64_t n, const in
     const Tensor4* d_tens = reinterpret_cast<const Tensor4*>(dplan + L.off_tensors);
     float* d_floats = reinterpret_cast<float*>(dplan + L.off_floats);
     const InnerDims* d_dims = reinterpret_cast<const InnerDims*>(dplan + L.off_dims);
+    host->d_hyper = reinterpret_cast<Hyper*>(dplan + L.off_hyper);
     unsigned int* d_counters = reinterpret_cast<unsigned int*>(dplan + L.off_counters);
 
     const int64_t rw_hint = env_int("LPMM_MULTI_RW", -1);      // -1: the plan defaults (64 rows, 32 for the flat tiling)
@@ -1258,8 +1261,13 @@ int lpmm_adamw4_plan_build_nd(const lpmm_tensor_desc* descs, int64_t n, const in
     return LPMM_OK;
 }
 
-int lpmm_adamw4_step_multi(void* plan, float lr, float beta1, float beta2, float eps, float weight_decay,
-                           int64_t step, void* stream) {
+}  // extern "C"
+
+namespace {
+
+// lr_dev / step_dev non-null: the capturable form, hyper-parameters prepared on the device
+int adamw4_step_multi_impl(void* plan, float lr, const float* lr_dev, float beta1, float beta2, float eps,
+                           float weight_decay, int64_t step, const int64_t* step_dev, void* stream) {
 #define LPMM_CHECK(call) do { const int rc_ = (call); if (rc_) return rc_; } while (0)
     // column maxima -> new statistics -> new column scales, for the group's tensors with more than two dimensions
     auto launch_nd = [](const PhaseLaunch& pl, hipStream_t on) -> int {
@@ -1269,9 +1277,11 @@ int lpmm_adamw4_step_multi(void* plan, float lr, float beta1, float beta2, float
         LPMM_HIP(hipGetLastError());
         return LPMM_OK;
     };
-    Hyper h;
-    const int rc = make_hyper(lr, beta1, beta2, eps, weight_decay, step, &h);
+    const bool capturable = lr_dev != nullptr;
+    HyperArg h{};
+    const int rc = make_hyper(capturable ? 0.0f : lr, beta1, beta2, eps, weight_decay, capturable ? 1 : step, &h.h);
     if (rc) return rc;
+    if (capturable && !step_dev) return LPMM_EINVAL;
     const PlanHost* host = nullptr;
     {
         std::lock_guard<std::mutex> lock(g_mu);
@@ -1284,6 +1294,12 @@ int lpmm_adamw4_step_multi(void* plan, float lr, float beta1, float beta2, float
     if (dev != host->device || host->sgdm) return LPMM_EINVAL;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const bool bf16 = host->bf16;
+    if (capturable) {
+        hipLaunchKernelGGL(hyper_prepare_kernel, dim3(1), dim3(64), 0, s, lr_dev, step_dev, beta1, beta2, eps,
+                           weight_decay, host->d_hyper);
+        LPMM_HIP(hipGetLastError());
+        h.dev = host->d_hyper;
+    }
     // roles: 0 = A and B work in one launch, 1 = A only, 2 = B only, 3 = A only without rank-1 tensors
     auto launch = [&](int roles, int grid, hipStream_t on, const PhaseLaunch& pl) {
 #define LPMM_PHASE_CASE(K, R)                                                                               \
@@ -1367,9 +1383,9 @@ int lpmm_adamw4_step_multi(void* plan, float lr, float beta1, float beta2, float
     return LPMM_OK;
 }
 
-int lpmm_sgdm4_step_multi(void* plan, float lr, float momentum, void* stream) {
-    Hyper h;
-    const int rc = make_sgdm_hyper(lr, momentum, &h);
+int sgdm4_step_multi_impl(void* plan, float lr, const float* lr_dev, float momentum, void* stream) {
+    HyperArg h{};
+    const int rc = make_sgdm_hyper(lr_dev ? 0.0f : lr, momentum, &h.h);
     if (rc) return rc;
     const PlanHost* host = nullptr;
     {
@@ -1382,6 +1398,11 @@ int lpmm_sgdm4_step_multi(void* plan, float lr, float momentum, void* stream) {
     LPMM_HIP(hipGetDevice(&dev));
     if (dev != host->device || !host->sgdm) return LPMM_EINVAL;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (lr_dev) {
+        hipLaunchKernelGGL(sgdm_hyper_prepare_kernel, dim3(1), dim3(64), 0, s, lr_dev, momentum, host->d_hyper);
+        LPMM_HIP(hipGetLastError());
+        h.dev = host->d_hyper;
+    }
     for (const PhaseLaunch& pl : host->phases) {
         if (pl.ph.n_a == 0) continue;
         const bool rec = g_prof.on && g_prof.calls < g_prof.max_calls;
@@ -1397,6 +1418,30 @@ int lpmm_sgdm4_step_multi(void* plan, float lr, float momentum, void* stream) {
         }
     }
     return LPMM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int lpmm_adamw4_step_multi(void* plan, float lr, float beta1, float beta2, float eps, float weight_decay,
+                           int64_t step, void* stream) {
+    return adamw4_step_multi_impl(plan, lr, nullptr, beta1, beta2, eps, weight_decay, step, nullptr, stream);
+}
+
+int lpmm_adamw4_step_multi_capturable(void* plan, const float* lr, const int64_t* step, float beta1, float beta2,
+                                      float eps, float weight_decay, void* stream) {
+    if (!lr || !step) return LPMM_EINVAL;
+    return adamw4_step_multi_impl(plan, 0.0f, lr, beta1, beta2, eps, weight_decay, 1, step, stream);
+}
+
+int lpmm_sgdm4_step_multi(void* plan, float lr, float momentum, void* stream) {
+    return sgdm4_step_multi_impl(plan, lr, nullptr, momentum, stream);
+}
+
+int lpmm_sgdm4_step_multi_capturable(void* plan, const float* lr, float momentum, void* stream) {
+    if (!lr) return LPMM_EINVAL;
+    return sgdm4_step_multi_impl(plan, 0.0f, lr, momentum, stream);
 }
 
 int lpmm_adamw4_plan_release(void* plan) {

@@ -99,11 +99,22 @@ class AdamW4bit(_PlanOptimizer):
     states, larger 1-dimensional ones block-wise 4-bit states."""
 
     def __init__(self, params, lr=1e-3, betas=(0.9, 0.999), eps=1e-8, weight_decay=1e-2, second_moment="rank1",
-                 no_decay=_default_no_decay):
+                 no_decay=_default_no_decay, capturable=False):
         super().__init__(params, no_decay)
         if second_moment not in ("rank1", "factor", "b128"):
             raise ValueError("second_moment must be rank1, factor or b128")
         self.lr, self.betas, self.eps, self.weight_decay, self.second_moment = lr, betas, eps, weight_decay, second_moment
+        # capturable: the learning rate and the step number live on the device, so that step() can be captured
+        # into a graph and replayed (run one step eagerly first: the plan is built then); change the rate with set_lr
+        self.capturable = capturable
+        if capturable:
+            self.lr_dev = torch.full((1,), float(lr), device=self.device)
+            self.step_dev = torch.zeros(1, dtype=torch.int64, device=self.device)
+
+    def set_lr(self, lr: float):
+        self.lr = lr
+        if self.capturable:
+            self.lr_dev.fill_(float(lr))
 
     def _new_state(self, p):
         n = p.numel()
@@ -125,7 +136,12 @@ class AdamW4bit(_PlanOptimizer):
         return _b.make_desc(p, g, st, no_decay=nd)
 
     def _step(self, plan):
-        _b.lpmm_adamw4_step_multi(plan, self.lr, self.betas[0], self.betas[1], self.eps, self.weight_decay, self.t)
+        if self.capturable:
+            self.step_dev += 1
+            _b.lpmm_adamw4_step_multi_capturable(plan, self.lr_dev, self.step_dev, self.betas[0], self.betas[1],
+                                                 self.eps, self.weight_decay)
+        else:
+            _b.lpmm_adamw4_step_multi(plan, self.lr, self.betas[0], self.betas[1], self.eps, self.weight_decay, self.t)
 
 
 class SGDM4bit(_PlanOptimizer):

@@ -127,3 +127,68 @@ def test_plan_step_replays_from_a_graph(env):
     finally:
         for k in env:
             os.environ.pop(k, None)
+
+
+@pytest.mark.parametrize("env", [{}, {"LPMM_PHASE_MPARAMS": "1"}], ids=["one-stream", "two-streams"])
+def test_capturable_plan_step_follows_lr_and_step_on_the_device(env):
+    """The capturable entry point reads the learning rate and the step number from device memory: one captured
+    step, replayed while both change, must follow the eager steps with the same values (moments and their codes
+    bit for bit; parameters to rounding: the bias corrections are evaluated on the device)."""
+    import os
+    print(f"\n[gpu-test] capturable plan step {env}", flush=True)
+    T = workloads.TensorSpec
+    specs = [T("a", 256, 768), T("b", 1024, 256), T("bias", 1, 768, 1), T("odd", 37, 200)]
+    os.environ.update(env)
+    try:
+        lpmm.ensure_init(4096)
+
+        def build():
+            ts, descs = [], []
+            for tid, sp in enumerate(specs):
+                w = to_dev(workloads.weights(44, tid, sp.rows, sp.cols).reshape(-1))
+                g = torch.zeros(sp.numel, device=DEV)
+                if sp.quantized:
+                    st = lpmm.new_state(sp.rows, sp.cols, DEV)
+                    descs.append(lpmm.make_desc(w, g, st))
+                    bufs = [getattr(st, n) for n in vars(st) if torch.is_tensor(getattr(st, n))]
+                else:
+                    st = (torch.zeros(sp.numel, device=DEV), torch.zeros(sp.numel, device=DEV))
+                    descs.append(lpmm.make_desc(w, g, st, sp.rows, sp.cols))
+                    bufs = list(st)
+                ts.append((w, g, bufs))
+            return ts, lpmm.new_plan(descs, 0, DEV)
+
+        ref, plan_ref = build()
+        cap, plan_cap = build()
+        lr_dev = torch.zeros(1, device=DEV)
+        step_dev = torch.zeros(1, dtype=torch.int64, device=DEV)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        s = torch.cuda.Stream()
+        s.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(s):
+            with torch.cuda.graph(graph, stream=s):
+                lpmm.lpmm_adamw4_step_multi_capturable(plan_cap, lr_dev, step_dev, 0.9, 0.999, 1e-8, 0.01)
+        torch.cuda.synchronize()
+        for t in (1, 2, 3, 4):
+            lr = 1e-3 * (1.0 - 0.1 * t)                       # a schedule
+            for tid, sp in enumerate(specs):
+                gn = to_dev(workloads.grads(44, tid, t, sp.rows, sp.cols, "col_lognormal").reshape(-1))
+                ref[tid][1].copy_(gn)
+                cap[tid][1].copy_(gn)
+            lr_dev.fill_(lr)
+            step_dev.fill_(t)
+            torch.cuda.synchronize()
+            lpmm.lpmm_adamw4_step_multi(plan_ref, lr, 0.9, 0.999, 1e-8, 0.01, t)
+            graph.replay()
+            torch.cuda.synchronize()
+            for sp, (w, _, bufs), (w2, _, bufs2) in zip(specs, ref, cap):
+                torch.testing.assert_close(w2, w, rtol=1e-6, atol=1e-9, msg=f"{sp.name} step {t}")
+                for x, y in zip(bufs, bufs2):
+                    assert torch.equal(x, y), f"{sp.name} step {t}"
+                w2.copy_(w)                                   # keep the two sides on identical parameters
+        lpmm.lpmm_adamw4_plan_release(plan_ref)
+        lpmm.lpmm_adamw4_plan_release(plan_cap)
+    finally:
+        for k in env:
+            os.environ.pop(k, None)

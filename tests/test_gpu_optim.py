@@ -143,3 +143,39 @@ def test_adamw4bit_with_a_convolution_weight():
                             f"conv step {t}") == 0
         conv.weight.data.copy_(torch.from_numpy(w_ref).view_as(conv.weight))
         opt.zero_grad()
+
+
+def test_capturable_optimizer_step_in_a_graph():
+    """opt.step() of a capturable AdamW4bit captured once and replayed equals the eager optimizer step for step."""
+    print("\n[gpu-test] capturable AdamW4bit in a graph", flush=True)
+    a, b = _model(6), _model(6)
+    oa = lpmm.AdamW4bit(a.parameters(), lr=1e-3, weight_decay=0.05, capturable=True)
+    ob = lpmm.AdamW4bit(b.parameters(), lr=1e-3, weight_decay=0.05)
+    for m, o in ((a, oa), (b, ob)):                      # one eager step each: builds the plans, gradients stay in place
+        _loss(m, 0).backward()
+        o.step()
+        o.zero_grad()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        with torch.cuda.graph(graph, stream=s):
+            oa.step()
+    torch.cuda.synchronize()
+    oa.t -= 1                                             # the capture ran nothing on the device; undo the host-side count
+    for t in (1, 2, 3):
+        lr = 1e-3 / (1 + t)
+        oa.set_lr(lr)
+        ob.set_lr(lr)
+        for m in (a, b):
+            for p in m.parameters():
+                p.grad.zero_()
+            _loss(m, t).backward()
+        torch.cuda.synchronize()
+        graph.replay()
+        ob.step()
+        torch.cuda.synchronize()
+        for pa, pb in zip(a.parameters(), b.parameters()):
+            torch.testing.assert_close(pa, pb, rtol=1e-6, atol=1e-9)
+            pa.data.copy_(pb.data)
