@@ -299,6 +299,64 @@ def test_config5_factorized_second_moment_plan():
     lpmm.lpmm_adamw4_plan_release(plan)
 
 
+def _oracle_step_sgdm(job):
+    w_ref, st_ref, g, lr, beta = job
+    return oracle.sgdm4_step(w_ref, g, st_ref, lr, beta, want_moment=True)
+
+
+def test_config5_sgdm_plan():
+    """The 7B-shaped set under SGD with momentum (App. E Alg. 2), the launch configuration of bench.py --optimizer
+    sgdm: two tensors element by element, block invariants of the momentum on a spread of tensors."""
+    from test_gpu_sgdm import compare as compare_sgdm, download as download_sgdm
+    config, seed, steps, lr, beta = "c5_llama_7b", 28, 2, 0.01, 0.9
+    specs = workloads.param_set(config)
+    sampled = {"l0.q": None, "l0.down": None}
+    lpmm.ensure_init(4096)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(seed)
+    dev_t, descs = [], []
+    for tid, sp in enumerate(specs):
+        if sp.name in sampled:
+            w_ref = workloads.weights(seed, tid, sp.rows, sp.cols).reshape(-1)
+            sampled[sp.name] = (tid, sp, w_ref, oracle.state_zero_sgdm(sp.numel))
+            w = to_dev(w_ref.copy())
+        else:
+            w = torch.randn(sp.numel, generator=gen, device=DEV) * 0.02
+        g = torch.empty(sp.numel, dtype=torch.bfloat16, device=DEV)
+        st = lpmm.new_state_sgdm(sp.numel, DEV) if sp.quantized else torch.zeros(sp.numel, device=DEV)
+        descs.append(lpmm.make_desc_sgdm(w, g, st, sp.numel))
+        dev_t.append((sp, w, g, st))
+    plan = lpmm.new_plan(descs, 1, DEV)
+    for t in range(1, steps + 1):
+        host_g = {}
+        for name, (tid, sp, w_ref, st_ref) in sampled.items():
+            host_g[name] = workloads.grads(seed, tid, t, sp.rows, sp.cols, "col_lognormal", True).reshape(-1)
+        for sp, w, g, st in dev_t:
+            if sp.name in sampled:
+                g.copy_(to_dev(host_g[sp.name], True))
+            else:
+                sigma = 1e-3 * torch.exp(torch.randn(sp.cols, generator=gen, device=DEV))
+                g.copy_((torch.randn(sp.rows, sp.cols, generator=gen, device=DEV) * sigma[None, :]).reshape(-1))
+        lpmm.lpmm_sgdm4_step_multi(plan, lr, beta)
+        jobs = [(w_ref, st_ref, host_g[name], lr, beta) for name, (tid, sp, w_ref, st_ref) in sampled.items()]
+        moments = list(POOL.map(_oracle_step_sgdm, jobs))
+        torch.cuda.synchronize()
+        by_name = {sp.name: (w, st) for sp, w, g, st in dev_t}
+        for (name, (tid, sp, w_ref, st_ref)), mt in zip(sampled.items(), moments):
+            w, st = by_name[name]
+            assert compare_sgdm(download_sgdm(st), st_ref, w.cpu().numpy(), w_ref, mt, f"c5 sgdm {name} step {t}") == 0
+    for sp, w, g, st in dev_t:
+        if sp.quantized and (sp.name in ("embed", "lm_head") or sp.name.startswith(("l0.", "l17.", "l31."))):
+            out = torch.empty(sp.numel, dtype=torch.float32, device=DEV)
+            lpmm.lpmm_dequant_state(0, st.m_codes, st.m_blockscale, None, 1, sp.numel, out)
+            mb = out.view(-1, 128).abs().max(dim=1).values
+            assert bool((mb <= st.m_blockscale).all()) and bool((mb >= 0.8875 * st.m_blockscale * (1 - 1e-6)).all()), \
+                f"c5 sgdm {sp.name}: momentum block scales"
+            assert bool(torch.isfinite(w).all())
+            del out, mb
+    lpmm.lpmm_adamw4_plan_release(plan)
+
+
 def test_more_than_2_31_elements_block_wise():
     """64-bit indexing: a flat tensor of 2^31 + 2^20 + 130 elements.  Blocks are independent, so the
     oracle checks the first and the last stretch of the tensor on their own."""
