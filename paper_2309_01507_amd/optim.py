@@ -83,6 +83,42 @@ class _PlanOptimizer:
         """The device buffers that make up the optimizer state, per parameter (for checkpoints)."""
         return self._states
 
+    @staticmethod
+    def _tensors_of(st):
+        if torch.is_tensor(st):
+            return {"m": st}
+        if isinstance(st, tuple):
+            return {"m": st[0], "v": st[1]}
+        return {k: v for k, v in vars(st).items() if torch.is_tensor(v)}
+
+    def state_dict(self):
+        """Step count and a copy of every state buffer (the buffers ARE the whole optimizer state).  States exist
+        after the first step."""
+        if self._states is None:
+            return {"t": self.t, "states": None}
+        return {"t": self.t, "states": [{k: v.clone() for k, v in self._tensors_of(st).items()} for st in self._states]}
+
+    def load_state_dict(self, sd):
+        """Into an optimizer over the same parameters (same shapes, same second-moment kind); the buffers keep
+        their addresses, so the plan stays valid."""
+        if sd["states"] is None:
+            return
+        if self._states is None:
+            with torch.cuda.device(self.device):
+                _b.ensure_init(4096)
+                self._states = [self._new_state(p) for p in self.params]
+        if len(sd["states"]) != len(self._states):
+            raise ValueError("state of a different parameter list")
+        for st, saved in zip(self._states, sd["states"]):
+            mine = self._tensors_of(st)
+            if set(mine) != set(saved) or any(mine[k].shape != saved[k].shape for k in mine):
+                raise ValueError("state of a different shape or kind")
+            for k in mine:
+                mine[k].copy_(saved[k])
+        self.t = int(sd["t"])
+        if getattr(self, "capturable", False):
+            self.step_dev.fill_(self.t)
+
     def __del__(self):
         try:
             if self._plan is not None:

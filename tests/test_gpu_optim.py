@@ -179,3 +179,32 @@ def test_capturable_optimizer_step_in_a_graph():
         for pa, pb in zip(a.parameters(), b.parameters()):
             torch.testing.assert_close(pa, pb, rtol=1e-6, atol=1e-9)
             pa.data.copy_(pb.data)
+
+
+def test_state_dict_round_trip_resumes_bit_for_bit():
+    """6 steps == 3 steps, state_dict into a fresh optimizer, 3 more steps."""
+    print("\n[gpu-test] AdamW4bit state_dict", flush=True)
+
+    def run(m, opt, steps):
+        for t in steps:
+            _loss(m, t).backward()
+            opt.step()
+            opt.zero_grad()
+
+    a = _model(8)
+    oa = lpmm.AdamW4bit(a.parameters(), lr=1e-3)
+    run(a, oa, range(1, 7))
+    b = _model(8)
+    ob = lpmm.AdamW4bit(b.parameters(), lr=1e-3)
+    run(b, ob, range(1, 4))
+    sd, weights = ob.state_dict(), {k: v.clone() for k, v in b.state_dict().items()}
+    c = _model(9)                                         # other initial weights: everything must come from the checkpoint
+    c.load_state_dict(weights)
+    oc = lpmm.AdamW4bit(c.parameters(), lr=1e-3)
+    oc.load_state_dict(sd)
+    run(c, oc, range(4, 7))
+    torch.cuda.synchronize()
+    for pa, pc in zip(a.parameters(), c.parameters()):
+        assert torch.equal(pa, pc)
+    with pytest.raises(ValueError):
+        lpmm.AdamW4bit(_model(8).parameters(), second_moment="b128").load_state_dict(sd)
