@@ -11,6 +11,11 @@
  *   second moment: rank-1 normalization n_ij = x_ij / min(r_i, c_j) with r_i = max_j x_ij,
  *                  c_j = max_i x_ij (Sec. 4.2), Linear map T(i) = (i+1)/16 without zero (Sec. 4.1).
  *
+ * Further sections below: the block-wise second moment for 1-dimensional / flattened tensors (Sec. 4.2),
+ * the factorized second moment of "4-bit Factor" (Sec. 4.3), rank-1 normalization for more than two
+ * dimensions (App. F Alg. 4), SGD with momentum (App. E Alg. 2), stand-alone compress / decompress,
+ * plans (many tensors per call), and the plan steps with device-resident learning rate and step number.
+ *
  * Conventions for every call
  *   - All data pointers are DEVICE pointers unless the comment says "host".  The caller owns every
  *     buffer; the library allocates no device memory and never frees anything.
