@@ -142,6 +142,14 @@ def test_config1_full():
     assert run_parity(1024, 1024, steps=10, recipe="iid", seed=1) == 0
 
 
+@pytest.mark.parametrize("rows,cols,steps", [(192, 256, 300), (37, 200, 150)])
+def test_long_run_stays_in_step(rows, cols, steps):
+    """Hundreds of steps, fast and general path: a gradient mean that persists and then dies away takes the
+    moments through growth, sign-stable first moments and shrinking scales; codes and scales stay bit for bit
+    with the oracle's at every step."""
+    assert run_parity(rows, cols, steps=steps, recipe="drift", seed=8) == 0
+
+
 def test_outlier_sparse_rows():
     """Config 3's structure at reduced size: x1e3 rows/columns, 90 % zero rows per step, rows that
     never receive a gradient (zero scale -> n := 0)."""

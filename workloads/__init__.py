@@ -20,7 +20,7 @@ import numpy as np
 QUANT_MIN_NUMEL = 4096  # App. C.1 of the paper: tensors of size <= 4096 keep fp32 states
 
 _PURPOSE = {"weight": 1, "grad": 2, "col_sigma": 3, "row_outlier": 4, "col_outlier": 5,
-            "row_zero": 6}
+            "row_zero": 6, "grad_mean": 7}
 
 
 def rng(seed: int, purpose: str, tensor_id: int = 0, step: int = 0) -> np.random.Generator:
@@ -148,6 +148,10 @@ def grads(seed: int, tensor_id: int, step: int, rows: int, cols: int, recipe: st
         zero = rng(seed, "row_zero", tensor_id, step + 1).random(rows) < 0.9
         zero[never] = True
         out[zero, :] = 0.0
+    elif recipe == "drift":                  # long runs: a persistent mean that dies away under the column noise
+        sig = col_sigma(seed, tensor_id, cols)[None, :]
+        mean = rng(seed, "grad_mean", tensor_id).standard_normal((rows, cols), dtype=np.float32)
+        out = (z + mean * np.float32(3.0 * np.exp(-step / 40.0))) * sig
     else:
         raise KeyError(recipe)
     out = np.ascontiguousarray(out, np.float32)
