@@ -94,6 +94,12 @@ def test_bf16_gradients_and_column_structure():
     assert run(256, 1536, steps=4, recipe="col_lognormal", bf16=True) == 0
 
 
+def test_long_run_stays_in_step():
+    """200 steps with a gradient mean that persists and then dies away: growing, then shrinking block scales."""
+    assert run(96, 256, steps=200, recipe="drift") == 0
+    assert run(7, 333, steps=100, recipe="drift") == 0           # ragged last block
+
+
 def test_outliers_and_zero_stretches():
     # config-3 style gradient: most rows zero in a step (whole blocks keep scale 0 or decay), a few
     # rows and columns 1000x larger

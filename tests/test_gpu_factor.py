@@ -114,6 +114,12 @@ def test_bf16_gradients():
     assert run(50, 333, steps=3, bf16=True) == 0
 
 
+def test_long_run_stays_in_step():
+    """150 steps with a gradient mean that persists and then dies away, fast and general path."""
+    assert run(192, 256, steps=150, recipe="drift") == 0
+    assert run(37, 200, steps=100, recipe="drift") == 0
+
+
 def test_outliers_and_zero_rows():
     # most rows zero in a step (their statistic only decays), a few rows and columns 1000x larger
     assert run(1200, 512, steps=5, recipe="outlier_sparse") == 0

@@ -103,6 +103,11 @@ def test_bf16_gradients_and_outliers():
     assert run((300, 8, 8, 2), steps=4, recipe="outlier_sparse") == 0
 
 
+def test_long_run_stays_in_step():
+    """150 steps with a gradient mean that persists and then dies away, four dimensions."""
+    assert run((24, 16, 4, 4), steps=150, recipe="drift") == 0
+
+
 def test_general_kernels_on_a_tiled_shape():
     assert run((64, 8, 16), steps=3, env={"LPMM_FORCE_GENERAL": "1"}) == 0
 

@@ -76,6 +76,12 @@ def test_bf16_gradients_outliers_and_other_hyperparameters():
     assert run(5, 128 * 40 + 64, steps=4, lr=0.5, beta=0.99) == 0
 
 
+def test_long_run_stays_in_step():
+    """200 steps with a gradient mean that persists and then dies away: a momentum buffer with a stable sign."""
+    assert run(96, 256, steps=200, recipe="drift") == 0
+    assert run(7, 333, steps=100, recipe="drift") == 0           # ragged last block
+
+
 def test_fp32_momentum_step():
     rng = np.random.default_rng(72)
     P = 5000
