@@ -138,7 +138,7 @@ def test_step_parity_bf16_gradients():
 
 
 def test_config1_full():
-    """BASELINE config 1: one 1024 x 1024 fp32 matrix, 10 steps, fresh gradients each step."""
+    """Configuration c1: one 1024 x 1024 fp32 matrix, 10 steps, fresh gradients each step."""
     assert run_parity(1024, 1024, steps=10, recipe="iid", seed=1) == 0
 
 

@@ -55,7 +55,7 @@ class TensorSpec:
 
     @property
     def quantized(self) -> bool:
-        """Paper's rule (App. C.1) plus BASELINE's configs: 2-D tensors above 4096 elements are
+        """Paper's rule (App. C.1) as applied to the benchmark configurations: 2-D tensors above 4096 elements are
         quantized; 1-D biases / norm vectors keep fp32 states."""
         return self.ndim >= 2 and self.numel > QUANT_MIN_NUMEL
 
