@@ -280,11 +280,30 @@ def main():
                "sample": f"{n_cpu_steps} steps on the first {rows} rows of '{big.name}' ({rows}x{cols}, "
                          f"{rows * cols} params), {cdt:.1f} s; host has {os.cpu_count()} logical cpus"}
 
+    # For scale: what a plain device-to-device copy reaches on this machine (torch's copy kernel, 1 GiB read + 1 GiB
+    # written per call), outside every timed region above.
+    copy_gbps = None
+    try:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            dst.copy_(src)
+        e1.record()
+        torch.cuda.synchronize()
+        copy_gbps = round(10 * 2.0 * src.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
+        del src, dst
+    except RuntimeError:
+        pass
+
     total_gbps = ((bp1 + bp2) * n_quant + small_bytes) / (elapsed / args.steps) / 1e9
     # the same roofline for all kernels of a step together (they overlap on two streams, so a single kernel's
     # duration includes the slow-down from its neighbour): algorithmic bytes of the step / wall time of the step
     roofline["whole_step"] = {"achieved": round(total_gbps, 1), "frac": round(total_gbps / HBM_PEAK_GBPS, 4),
                               "bytes_per_param": bp1 + bp2, "ms": round(ms_per_step, 4)}
+    roofline["plain_copy_gbps_on_this_box"] = copy_gbps
     # every stream touched once (what a single pass would move): param 8, grad, codes 2, block scales and,
     # for the rank-1 form, one more float per 128 elements standing in for the row / column maxima
     floor_bpp = 8.0 + (2.0 if bf16 else 4.0) + (1.0 if factor or sgdm else 2.0) + (16.0 if b128 else 8.0) / 128.0
