@@ -394,12 +394,20 @@ __device__ __forceinline__ void load4(const float* p, float out[4]) {
 }
 
 template <bool BF16>
-struct Row1 {                      // everything pass 1 reads for one row of one lane
+struct Row1 {                      // everything pass 1 prefetches for one row of one lane
     float4 p;
     GradRegs4<BF16> g;
     uint16_t mq, vq;               // the lane's 4 codes of each moment
-    float s_old, r_old;
 };
+
+// The old block scales of m and the old row maxima of v of a tile are not prefetched per row (each would be a
+// load of 4 bytes that all 32 lanes of a group share): the tile stages them in LDS once, in the slots that
+// later take the new block scales and the new row maxima (s.blk_scale, s.blk_vmax).  A slot's old value is
+// read by the same group that replaces it, earlier in program order.
+
+// parameters and first-moment codes of a lane's 4 elements, through the tile's bounds-checked resources (no
+// registers for a second set of base addresses)
+__device__ __forceinline__ void store_row1(const TileBase& tb, uint32_t off4, const float w[4], uint32_t mq_new);
 
 // il = row index inside the tile; rows at or beyond the tile's end read as zeros
 template <bool BF16>
@@ -410,9 +418,13 @@ __device__ __forceinline__ Row1<BF16> load_row1(const TileBase& b, const Tensor4
     r.g = load_grad_regs4<BF16>(b.rg, off4);
     r.mq = buf_ld_u16(b.rmq, off4 >> 3);
     r.vq = buf_ld_u16(b.rvq, off4 >> 3);
-    r.s_old = buf_ld_f(b.rms, row_offset(il, a.nb, uint32_t(g.cb)) * 4u);
-    r.r_old = buf_ld_f(b.rr, uint32_t(il) * 4u);
     return r;
+}
+
+__device__ __forceinline__ void store_row1(const TileBase& tb, uint32_t off4, const float w[4], uint32_t mq_new) {
+    const v4f_t v = {w[0], w[1], w[2], w[3]};
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u_t, v), tb.rp, int(off4), 0, kPolicyNtSc1);
+    __builtin_amdgcn_raw_buffer_store_b16(short(mq_new), tb.rmq, int(off4 >> 3), 0, 0);
 }
 
 // Raise a running maximum in global memory, reading it first: the value only grows during a kernel,
@@ -433,25 +445,27 @@ __device__ __forceinline__ void pass1_row(const Tensor4& a, const Hyper& h, cons
     float g[4];
     unpack_grad4<BF16>(cur.g, g);
     float mt[4], vt[4], amax = 0.0f, rmax = 0.0f;
+    const int slot = il * a.gx + geo.gxi;
+    const float s_old = s.blk_scale[slot], r_old = s.blk_vmax[slot];     // staged by the tile
 #pragma unroll
     for (int k = 0; k < 2; ++k) {
         const float2 t = s.deq[(uint32_t(cur.mq) >> (8 * k)) & 255u];
-        mt[2 * k] = t.x * cur.s_old;          // decompress: T_DE[code] * block scale
-        mt[2 * k + 1] = t.y * cur.s_old;
+        mt[2 * k] = t.x * s_old;              // decompress: T_DE[code] * block scale
+        mt[2 * k + 1] = t.y * s_old;
     }
     // the wave takes the exact route for this row if any of its scales is extreme
-    const bool tame_in = bool(int(cols_tame) & int(scale_is_tame(cur.r_old)));
+    const bool tame_in = bool(int(cols_tame) & int(scale_is_tame(r_old)));
     if (__builtin_expect(__ballot(!tame_in) == 0, 1)) {
         float qf[4];
         codes_to_float4(cur.vq, qf);
-        const float r16 = cur.r_old * 0.0625f;
+        const float r16 = r_old * 0.0625f;
 #pragma unroll
         for (int e = 0; e < 4; ++e) vt[e] = dequant_v16(qf[e], min_nonneg(r16, cold16[e]));
     } else {
         float cold[4];
         load4(a.c + geo.col0, cold);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) vt[e] = dequant_v((uint32_t(cur.vq) >> (4 * e)) & 15u, fminf(cur.r_old, cold[e]));
+        for (int e = 0; e < 4; ++e) vt[e] = dequant_v((uint32_t(cur.vq) >> (4 * e)) & 15u, fminf(r_old, cold[e]));
     }
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
@@ -488,12 +502,10 @@ __device__ __forceinline__ void pass1_row(const Tensor4& a, const Hyper& h, cons
         for (int e = 0; e < 4; ++e) mq_new |= quant_m_code(s.search, mt[e], s_new) << (4 * e);
     }
 
-    const uint32_t off4 = row_offset(il, a.cols, geo.col0) * 4u;
-    st_stream4(tb.p, off4, make_float4(w[0], w[1], w[2], w[3]));
-    st<uint16_t>(tb.mq, off4 >> 3, uint16_t(mq_new));
+    store_row1(tb, row_offset(il, a.cols, geo.col0) * 4u, w, mq_new);
     if (geo.l == 0) {
-        s.blk_scale[il * a.gx + geo.gxi] = s_new;
-        s.blk_vmax[il * a.gx + geo.gxi] = rmax;
+        s.blk_scale[slot] = s_new;
+        s.blk_vmax[slot] = rmax;
     }
 }
 
@@ -504,6 +516,12 @@ __device__ __forceinline__ void pass1_fast_tile(const Tensor4& a, const Hyper& h
     const TileBase tb = tile_base<BF16>(a, geo.row0, geo.n_rows);
     float cmax[4] = {0.0f, 0.0f, 0.0f, 0.0f};
 
+    // old block scales and old row maxima of the tile into the slots of the new ones
+    for (int t = threadIdx.x; t < geo.n_rows * a.gx; t += kThreads) {
+        const int il = t / a.gx, cbi = geo.strip * a.gx + t % a.gx;
+        s.blk_scale[t] = cbi < a.nb ? tb.ms[row_offset(il, a.nb, uint32_t(cbi))] : 0.0f;
+        s.blk_vmax[t] = tb.r[il];
+    }
     if (geo.active) {
         float cold16[4];
         load4(a.c + geo.col0, cold16);
@@ -528,7 +546,9 @@ __device__ __forceinline__ void pass1_fast_tile(const Tensor4& a, const Hyper& h
         Row1<BF16> r0 = load_row1<BF16>(tb, a, geo, row(0));
         Row1<BF16> r1 = load_row1<BF16>(tb, a, geo, row(1));
         Row1<BF16> r2;
-        if constexpr (!TABLES_READY) load_tables(s);   // the first rows' loads are in flight meanwhile
+        // the first rows' loads are in flight meanwhile; the barrier also publishes the staged scales
+        if constexpr (!TABLES_READY) load_tables(s);
+        else __syncthreads();
         // Everything requested so far has to be here before the first row anyway.  Saying so with an
         // explicit wait gives the loop a start-up state with nothing outstanding; otherwise the
         // start-up's own (tight) wait counts are merged into the loop head and drain the prefetch
@@ -554,6 +574,7 @@ __device__ __forceinline__ void pass1_fast_tile(const Tensor4& a, const Hyper& h
         }
     } else {
         if constexpr (!TABLES_READY) load_tables(s);   // keeps the workgroup's barriers matched
+        else __syncthreads();
     }
 
     // column maxima: combine the gy groups that share a column block, then one atomic per column
@@ -599,8 +620,6 @@ __device__ __forceinline__ Row1<BF16> load_unit(const TileBase& b, const Tensor4
     r.g = load_grad_regs4<BF16>(b.rg, off4);
     r.mq = buf_ld_u16(b.rmq, off4 >> 3);
     r.vq = buf_ld_u16(b.rvq, off4 >> 3);
-    r.s_old = buf_ld_f(b.rms, row_offset(il, a.nb, uint32_t(cb)) * 4u);
-    r.r_old = buf_ld_f(b.rr, uint32_t(il) * 4u);
     return r;
 }
 
@@ -614,18 +633,20 @@ __device__ __forceinline__ void flat_unit(const Tensor4& a, const Hyper& h, cons
     float g[4];
     unpack_grad4<BF16>(cur.g, g);
     float mt[4], vt[4], amax = 0.0f, rmax = 0.0f;
+    const float s_old = s.blk_scale[il * kFlatBlocks + j];     // staged by the tile; replaced below
+    const float r_old = s.blk_vmax[il];                        // likewise; replaced after the row's last block
 #pragma unroll
     for (int k = 0; k < 2; ++k) {
         const float2 t = s.deq[(uint32_t(cur.mq) >> (8 * k)) & 255u];
-        mt[2 * k] = t.x * cur.s_old;
-        mt[2 * k + 1] = t.y * cur.s_old;
+        mt[2 * k] = t.x * s_old;
+        mt[2 * k + 1] = t.y * s_old;
     }
     const uint32_t col0 = uint32_t(cb) * 128u + uint32_t(l) * 4u;
-    const bool tame_in = bool(int(cols_tame) & int(scale_is_tame(cur.r_old)));
+    const bool tame_in = bool(int(cols_tame) & int(scale_is_tame(r_old)));
     if (__builtin_expect(__ballot(!tame_in) == 0, 1)) {
         float qf[4];
         codes_to_float4(cur.vq, qf);
-        const float r16 = cur.r_old * 0.0625f;
+        const float r16 = r_old * 0.0625f;
         const float4 c16 = *reinterpret_cast<const float4*>(&s.cold[j * 128 + l * 4]);
         const float cold16[4] = {c16.x, c16.y, c16.z, c16.w};
 #pragma unroll
@@ -634,7 +655,7 @@ __device__ __forceinline__ void flat_unit(const Tensor4& a, const Hyper& h, cons
         float cold[4];
         load4(a.c + col0, cold);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) vt[e] = dequant_v((uint32_t(cur.vq) >> (4 * e)) & 15u, fminf(cur.r_old, cold[e]));
+        for (int e = 0; e < 4; ++e) vt[e] = dequant_v((uint32_t(cur.vq) >> (4 * e)) & 15u, fminf(r_old, cold[e]));
     }
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
@@ -673,9 +694,7 @@ __device__ __forceinline__ void flat_unit(const Tensor4& a, const Hyper& h, cons
 #pragma unroll
         for (int e = 0; e < 4; ++e) mq_new |= quant_m_code(s.search, mt[e], s_new) << (4 * e);
     }
-    const uint32_t off4 = row_offset(il, a.cols, col0) * 4u;
-    st_stream4(tb.p, off4, make_float4(w[0], w[1], w[2], w[3]));
-    st<uint16_t>(tb.mq, off4 >> 3, uint16_t(mq_new));
+    store_row1(tb, row_offset(il, a.cols, col0) * 4u, w, mq_new);
     if (l == 0) {
         s.blk_scale[il * kFlatBlocks + j] = s_new;
         if (j == nbk - 1) s.blk_vmax[il] = row_run;
@@ -714,6 +733,12 @@ __device__ __forceinline__ void pass1_flat_tile(const Tensor4& a, const Hyper& h
         s.cold[t] = c * 0.0625f;
         s.col[t] = 0.0f;
     }
+    // old block scales and old row maxima of the tile into the slots of the new ones
+    for (int t = threadIdx.x; t < n * kFlatBlocks; t += kThreads) {
+        const int il = t / kFlatBlocks, j = t % kFlatBlocks;
+        s.blk_scale[t] = j < nbk ? tb.ms[row_offset(il, a.nb, uint32_t(cb0 + j))] : 0.0f;
+    }
+    for (int t = threadIdx.x; t < n; t += kThreads) s.blk_vmax[t] = tb.r[t];
     const bool cols_tame = !__syncthreads_or(int(!tame));
     load_tables(s);
     __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
