@@ -1561,7 +1561,6 @@ struct RowF {                      // everything the update pass reads for one r
     float4 p;
     GradRegs4<BF16> g;
     uint16_t mq;
-    float s_old, r_old, r_sum;
 };
 
 template <bool BF16>
@@ -1571,28 +1570,26 @@ __device__ __forceinline__ RowF<BF16> load_rowf(const TileBase& b, const Tensor4
     r.p = buf_ld_f4_stream(b.rp, off4);
     r.g = load_grad_regs4<BF16, kPolicyNt>(b.rg, off4);     // last use of the gradient in this step
     r.mq = buf_ld_u16(b.rmq, off4 >> 3);
-    r.s_old = buf_ld_f(b.rms, row_offset(il, a.nb, uint32_t(g.cb)) * 4u);
-    r.r_old = buf_ld_f(b.rr, uint32_t(il) * 4u);
-    r.r_sum = buf_ld_f(b.rr_new, uint32_t(il) * 4u);
     return r;
 }
 
-// One row of the update pass for one lane; ct[e] = C_t of the lane's columns.
+// One row of the update pass for one lane; ct[e] = C_t of the lane's columns.  The row's old block scale and
+// R_t[i] / sum R_t come from LDS, where the tile staged them (see pass 1).
 template <bool BF16, class Mid>
 __device__ __forceinline__ void factor_row(const Tensor4& a, const Hyper& h, const TileBase& tb, const Geo& geo,
-                                           Lds& s, const RowF<BF16>& cur, int il, const float ct[4],
-                                           float inv_total, Mid mid) {
+                                           Lds& s, const RowF<BF16>& cur, int il, const float ct[4], Mid mid) {
     float w[4] = {cur.p.x, cur.p.y, cur.p.z, cur.p.w};
     float g[4];
     unpack_grad4<BF16>(cur.g, g);
     float mt[4], amax = 0.0f;
+    const int slot = il * a.gx + geo.gxi;
+    const float s_old = s.blk_scale[slot], rn = s.blk_vmax[slot];
 #pragma unroll
     for (int k = 0; k < 2; ++k) {
         const float2 t = s.deq[(uint32_t(cur.mq) >> (8 * k)) & 255u];
-        mt[2 * k] = t.x * cur.s_old;
-        mt[2 * k + 1] = t.y * cur.s_old;
+        mt[2 * k] = t.x * s_old;
+        mt[2 * k + 1] = t.y * s_old;
     }
-    const float rn = stat_ema(h, cur.r_old, cur.r_sum) * inv_total;      // R_t[i] / sum R_t
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
         mt[e] = moment_m(h, mt[e], g[e]);
@@ -1621,10 +1618,8 @@ __device__ __forceinline__ void factor_row(const Tensor4& a, const Hyper& h, con
 #pragma unroll
         for (int e = 0; e < 4; ++e) mq_new |= quant_m_code(s.search, mt[e], s_new) << (4 * e);
     }
-    const uint32_t off4 = row_offset(il, a.cols, geo.col0) * 4u;
-    st_stream4(tb.p, off4, make_float4(w[0], w[1], w[2], w[3]));
-    st<uint16_t>(tb.mq, off4 >> 3, uint16_t(mq_new));
-    if (geo.l == 0) s.blk_scale[il * a.gx + geo.gxi] = s_new;
+    store_row1(tb, row_offset(il, a.cols, geo.col0) * 4u, w, mq_new);
+    if (geo.l == 0) s.blk_scale[slot] = s_new;
 }
 
 // Update pass, fast path: tiled and pipelined like pass 1.
@@ -1632,38 +1627,41 @@ template <bool BF16>
 __device__ __forceinline__ void factor_update_tile(const Tensor4& a, const Hyper& h, int wg, Lds& s) {
     const Geo geo = geometry(a, wg);
     const TileBase tb = tile_base<BF16>(a, geo.row0, geo.n_rows);
+    const int n = geo.n_rows, rs = a.rs;
+    const int row_g = geo.gyi << rs, hop = a.gy << rs, low = (1 << rs) - 1;
+    auto row = [&](int k) { return row_g + (k & low) + (k >> rs) * hop; };
+    float ct[4] = {0.0f, 0.0f, 0.0f, 0.0f}, csum[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    RowF<BF16> r0{}, r1{}, r2;
     if (geo.active) {
-        float ct[4], csum[4];
         load4(a.c + geo.col0, ct);
         load4(a.c_new + geo.col0, csum);
-        const int n = geo.n_rows, rs = a.rs;
-        const int row_g = geo.gyi << rs, hop = a.gy << rs, low = (1 << rs) - 1;
-        auto row = [&](int k) { return row_g + (k & low) + (k >> rs) * hop; };
-        int k = 0;
-        RowF<BF16> r0 = load_rowf<BF16>(tb, a, geo, row(0));
-        RowF<BF16> r1 = load_rowf<BF16>(tb, a, geo, row(1));
-        RowF<BF16> r2;
-        load_tables(s);
+        r0 = load_rowf<BF16>(tb, a, geo, row(0));
+        r1 = load_rowf<BF16>(tb, a, geo, row(1));
+    }
+    // per row of the tile: the old block scales of m, and R_t[i] / sum R_t once instead of in every lane
+    const float inv_total = factor_inv_total(a, h);
+    for (int t = threadIdx.x; t < n * a.gx; t += kThreads) {
+        const int il = t / a.gx, cbi = geo.strip * a.gx + t % a.gx;
+        s.blk_scale[t] = cbi < a.nb ? tb.ms[row_offset(il, a.nb, uint32_t(cbi))] : 0.0f;
+        s.blk_vmax[t] = stat_ema(h, tb.r[il], tb.r_new[il]) * inv_total;
+    }
+    load_tables(s);          // its barrier also publishes the staged values
+    if (geo.active) {
 #pragma unroll
         for (int e = 0; e < 4; ++e) ct[e] = stat_ema(h, ct[e], csum[e]);
-        const float inv_total = factor_inv_total(a, h);
         __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
+        int k = 0;
         auto none = [] {};
         while (row(k + 2) < n) {
-            factor_row<BF16>(a, h, tb, geo, s, r0, row(k), ct, inv_total,
-                             [&] { r2 = load_rowf<BF16>(tb, a, geo, row(k + 2)); });
-            factor_row<BF16>(a, h, tb, geo, s, r1, row(k + 1), ct, inv_total,
-                             [&] { r0 = load_rowf<BF16>(tb, a, geo, row(k + 3)); });
-            factor_row<BF16>(a, h, tb, geo, s, r2, row(k + 2), ct, inv_total,
-                             [&] { r1 = load_rowf<BF16>(tb, a, geo, row(k + 4)); });
+            factor_row<BF16>(a, h, tb, geo, s, r0, row(k), ct, [&] { r2 = load_rowf<BF16>(tb, a, geo, row(k + 2)); });
+            factor_row<BF16>(a, h, tb, geo, s, r1, row(k + 1), ct, [&] { r0 = load_rowf<BF16>(tb, a, geo, row(k + 3)); });
+            factor_row<BF16>(a, h, tb, geo, s, r2, row(k + 2), ct, [&] { r1 = load_rowf<BF16>(tb, a, geo, row(k + 4)); });
             k += 3;
         }
         if (row(k) < n) {
-            factor_row<BF16>(a, h, tb, geo, s, r0, row(k), ct, inv_total, none);
-            if (row(k + 1) < n) factor_row<BF16>(a, h, tb, geo, s, r1, row(k + 1), ct, inv_total, none);
+            factor_row<BF16>(a, h, tb, geo, s, r0, row(k), ct, none);
+            if (row(k + 1) < n) factor_row<BF16>(a, h, tb, geo, s, r1, row(k + 1), ct, none);
         }
-    } else {
-        load_tables(s);
     }
     __syncthreads();
     for (int t = threadIdx.x; t < geo.n_rows * a.gx; t += kThreads) {
