@@ -999,8 +999,7 @@ struct RowB {                      // everything the step reads for one block, p
     float4 p;
     GradRegs4<BF16> g;
     uint16_t mq, vq;               // the lane's 4 codes of each moment
-    float sm_old, sv_old;          // the block's two scales
-};
+};                                 // (the block's two old scales come from LDS, staged by the tile as in pass 1)
 
 constexpr int kNoBlock = 1 << 22;     // a block index whose offsets lie beyond any tile: loads return zeros
 
@@ -1013,14 +1012,8 @@ __device__ __forceinline__ RowB<BF16> load_rowb(const TileB& b, int ib, int l) {
     r.p = buf_ld_f4_stream(b.rp, off4);
     r.g = load_grad_regs4<BF16, kPolicyNt>(b.rg, off4);              // read once per step
     r.mq = buf_ld_u16(b.rmq, off4 >> 3);
-    r.sm_old = buf_ld_f(b.rms, uint32_t(ib) * 4u);
-    if constexpr (SGDM) {
-        r.vq = 0;
-        r.sv_old = 0.0f;
-    } else {
-        r.vq = buf_ld_u16(b.rvq, off4 >> 3);
-        r.sv_old = buf_ld_f(b.rvs, uint32_t(ib) * 4u);
-    }
+    if constexpr (SGDM) r.vq = 0;
+    else r.vq = buf_ld_u16(b.rvq, off4 >> 3);
     return r;
 }
 
@@ -1031,11 +1024,13 @@ __device__ __forceinline__ void b128_row(const Hyper& h, const TileB& tb, Lds& s
     float g[4];
     unpack_grad4<BF16>(cur.g, g);
     float mt[4], vt[4], amax = 0.0f, vmax = 0.0f;
+    const float sm_old = s.blk_scale[slot];
+    const float sv_old = SGDM ? 0.0f : s.blk_vmax[slot];
 #pragma unroll
     for (int k = 0; k < 2; ++k) {
         const float2 t = s.deq[(uint32_t(cur.mq) >> (8 * k)) & 255u];
-        mt[2 * k] = t.x * cur.sm_old;         // decompress: T_DE[code] * block scale
-        mt[2 * k + 1] = t.y * cur.sm_old;
+        mt[2 * k] = t.x * sm_old;             // decompress: T_DE[code] * block scale
+        mt[2 * k + 1] = t.y * sm_old;
     }
     if constexpr (SGDM) {
 #pragma unroll
@@ -1046,15 +1041,15 @@ __device__ __forceinline__ void b128_row(const Hyper& h, const TileB& tb, Lds& s
             vt[e] = 0.0f;
         }
     } else {
-        if (__builtin_expect(__ballot(!scale_is_tame(cur.sv_old)) == 0, 1)) {
+        if (__builtin_expect(__ballot(!scale_is_tame(sv_old)) == 0, 1)) {
             float qf[4];
             codes_to_float4(cur.vq, qf);
-            const float s16 = cur.sv_old * 0.0625f;
+            const float s16 = sv_old * 0.0625f;
 #pragma unroll
             for (int e = 0; e < 4; ++e) vt[e] = dequant_v16(qf[e], s16);
         } else {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) vt[e] = dequant_v((uint32_t(cur.vq) >> (4 * e)) & 15u, cur.sv_old);
+            for (int e = 0; e < 4; ++e) vt[e] = dequant_v((uint32_t(cur.vq) >> (4 * e)) & 15u, sv_old);
         }
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -1109,9 +1104,12 @@ __device__ __forceinline__ void b128_row(const Hyper& h, const TileB& tb, Lds& s
     }
 
     const uint32_t off4 = (uint32_t(ib) * 128u + uint32_t(l) * 4u) * 4u;
-    st_stream4(tb.p, off4, make_float4(w[0], w[1], w[2], w[3]));
-    st<uint16_t>(tb.mq, off4 >> 3, uint16_t(mq_new));
-    if constexpr (!SGDM) st<uint16_t>(tb.vq, off4 >> 3, uint16_t(vq_new));
+    {   // through the tile's bounds-checked resources: no registers for a second set of base addresses
+        const v4f_t v = {w[0], w[1], w[2], w[3]};
+        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u_t, v), tb.rp, int(off4), 0, kPolicyNtSc1);
+        __builtin_amdgcn_raw_buffer_store_b16(short(mq_new), tb.rmq, int(off4 >> 3), 0, 0);
+        if constexpr (!SGDM) __builtin_amdgcn_raw_buffer_store_b16(short(vq_new), tb.rvq, int(off4 >> 3), 0, 0);
+    }
     if (l == 0) {
         s.blk_scale[slot] = sm_new;
         if constexpr (!SGDM) s.blk_vmax[slot] = sv_new;
@@ -1145,7 +1143,13 @@ __device__ __forceinline__ void b128_tile(const Tensor4& a, const Hyper& h, int 
     RowB<BF16> r0 = load_rowb<BF16, SGDM>(tb, blk(0), l);
     RowB<BF16> r1 = load_rowb<BF16, SGDM>(tb, blk(1), l);
     RowB<BF16> r2;
-    load_tables(s);                                // the first blocks' loads are in flight meanwhile
+    for (int t = threadIdx.x; t < kGroups * rounds; t += kThreads) {   // old block scales into the slots of the new ones
+        const int b = (t / rounds) * kB128Stride + slice0 + t % rounds;
+        s.blk_scale[t] = b < n_sup ? tb.ms[b] : 0.0f;
+        if constexpr (!SGDM) s.blk_vmax[t] = b < n_sup ? tb.vs[b] : 0.0f;
+    }
+    load_tables(s);                                // the first blocks' loads are in flight meanwhile; its barrier
+                                                   // also publishes the staged scales
     __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);       // loop start-up state: nothing outstanding (see pass 1)
     auto none = [] {};
     while (k + 2 < nv) {                           // rounds of three blocks, no exit in the middle
