@@ -1101,7 +1101,6 @@ int lpmm_adamw4_plan_build_nd(const lpmm_tensor_desc* descs, int64_t n, const in
         }
         plan_flat = n_groups > 1 && p_rank1 > 0 && p_big * 10 >= p_rank1 * 9;
     }
-    host->flat = plan_flat;
     int64_t fofs = 0;
     for (int64_t i = 0; i < n; ++i) {
         const lpmm_tensor_desc& d = descs[i];
@@ -1191,6 +1190,7 @@ int lpmm_adamw4_plan_build_nd(const lpmm_tensor_desc* descs, int64_t n, const in
                 t.kind = kQuantFast;
                 fast_geometry(&t, ctx->n_cu, rw_hint, rw2_hint, grad_dtype == LPMM_GRAD_BF16 ? 2 : 4,
                               plan_flat && t.P >= kFlatMinElems);
+                if (t.flat) host->flat = true;
             } else {
                 t.kind = kQuantGeneral;
                 general_geometry(&t, ctx->n_cu);
