@@ -1306,7 +1306,7 @@ int adamw4_step_multi_impl(void* plan, float lr, const float* lr_dev, float beta
     // five workgroups share a CU: two waves per SIMD already saturate pass 1 on large tensors, and more of them only
     // take issue slots and memory queues from the pass 2 that runs beside (measured on the 7B-shaped set: 1 % less
     // time per step with bf16 gradients, 1-3 % with fp32 gradients; sets of small tensors lose 4 %, so not there).
-    const unsigned lds_pad = unsigned(env_int("LPMM_P1_LDS_PAD", host->flat ? 22528 : 0));
+    const unsigned lds_pad = unsigned(std::clamp(env_int("LPMM_P1_LDS_PAD", host->flat ? 22528 : 0), 0, 45056));
     // roles: 0 = A and B work in one launch, 1 = A only, 2 = B only, 3 = A only without rank-1 tensors
     auto launch = [&](int roles, int grid, hipStream_t on, const PhaseLaunch& pl) {
 #define LPMM_PHASE_CASE(K, R)                                                                               \
