@@ -566,6 +566,7 @@ struct PlanHost {
     bool factor = false;                // the plan's 2-dimensional tensors keep a factorized second moment
     bool sgdm = false;                  // a plan of SGD-with-momentum tensors (lpmm_sgdm4_step_multi)
     bool flat = false;                  // large tensors, several groups: pass 1 uses the flat tiling
+    int64_t params = 0;                 // parameters of all tensors of the plan
     Hyper* d_hyper = nullptr;           // device slot inside the plan for the hyper-parameters of a captured step
     int device = 0;
     // second stream for pass 2 (same priority as any other stream), with its ordering events
@@ -1197,6 +1198,7 @@ int lpmm_adamw4_plan_build_nd(const lpmm_tensor_desc* descs, int64_t n, const in
             }
         }
         tens[i] = t;
+        host->params += t.P;
     }
 
     // groups of consecutive tensors; phase j = A work of group j + B work of group j-1
@@ -1267,6 +1269,14 @@ int lpmm_adamw4_plan_build_nd(const lpmm_tensor_desc* descs, int64_t n, const in
 
 namespace {
 
+// One-pass kernels (block-wise AdamW, SGDM) of plans of 2^30 parameters or more run with four workgroups per CU
+// instead of the seven or eight that their registers allow, by way of unused dynamic LDS: 1 % less time per step on
+// the 7B-shaped set (more resident waves only lengthen every wave's queueing), 2-3 % more on the 354 M set, whose
+// launches are short, hence the size condition.  LPMM_P3_LDS_PAD overrides the number of bytes.
+unsigned one_pass_lds_pad(const PlanHost& host) {
+    return unsigned(std::clamp(env_int("LPMM_P3_LDS_PAD", host.params >= (int64_t(1) << 30) ? 14336 : 0), 0, 45056));
+}
+
 // lr_dev / step_dev non-null: the capturable form, hyper-parameters prepared on the device
 int adamw4_step_multi_impl(void* plan, float lr, const float* lr_dev, float beta1, float beta2, float eps,
                            float weight_decay, int64_t step, const int64_t* step_dev, void* stream) {
@@ -1307,11 +1317,12 @@ int adamw4_step_multi_impl(void* plan, float lr, const float* lr_dev, float beta
     // take issue slots and memory queues from the pass 2 that runs beside (measured on the 7B-shaped set: 1 % less
     // time per step with bf16 gradients, 1-3 % with fp32 gradients; sets of small tensors lose 4 %, so not there).
     const unsigned lds_pad = unsigned(std::clamp(env_int("LPMM_P1_LDS_PAD", host->flat ? 22528 : 0), 0, 45056));
+    const unsigned pad3 = one_pass_lds_pad(*host);
     // roles: 0 = A and B work in one launch, 1 = A only, 2 = B only, 3 = A only without rank-1 tensors
     auto launch = [&](int roles, int grid, hipStream_t on, const PhaseLaunch& pl) {
 #define LPMM_PHASE_CASE(K, R)                                                                               \
-        if (bf16) hipLaunchKernelGGL((K<true, R>), dim3(grid), dim3(kThreads), (R == 1 ? lds_pad : 0), on, pl.ph, h);            \
-        else hipLaunchKernelGGL((K<false, R>), dim3(grid), dim3(kThreads), (R == 1 ? lds_pad : 0), on, pl.ph, h);
+        if (bf16) hipLaunchKernelGGL((K<true, R>), dim3(grid), dim3(kThreads), (R == 1 ? lds_pad : R == 3 ? pad3 : 0), on, pl.ph, h);            \
+        else hipLaunchKernelGGL((K<false, R>), dim3(grid), dim3(kThreads), (R == 1 ? lds_pad : R == 3 ? pad3 : 0), on, pl.ph, h);
         if (host->factor) {
             if (roles == 0) { LPMM_PHASE_CASE(factor_phase_kernel, 0) }
             else if (roles == 2) { LPMM_PHASE_CASE(factor_phase_kernel, 2) }
@@ -1415,8 +1426,9 @@ int sgdm4_step_multi_impl(void* plan, float lr, const float* lr_dev, float momen
         const bool rec = g_prof.on && g_prof.calls < g_prof.max_calls;
         const int64_t call = g_prof.calls;
         if (rec) LPMM_HIP(hipEventRecord(prof_event(call, 0), s));
-        if (host->bf16) hipLaunchKernelGGL(sgdm_phase_kernel<true>, dim3(pl.grid_a), dim3(kThreads), 0, s, pl.ph, h);
-        else hipLaunchKernelGGL(sgdm_phase_kernel<false>, dim3(pl.grid_a), dim3(kThreads), 0, s, pl.ph, h);
+        const unsigned pads = one_pass_lds_pad(*host);
+        if (host->bf16) hipLaunchKernelGGL(sgdm_phase_kernel<true>, dim3(pl.grid_a), dim3(kThreads), pads, s, pl.ph, h);
+        else hipLaunchKernelGGL(sgdm_phase_kernel<false>, dim3(pl.grid_a), dim3(kThreads), pads, s, pl.ph, h);
         LPMM_HIP(hipGetLastError());
         if (rec) {
             LPMM_HIP(hipEventRecord(prof_event(call, 1), s));
