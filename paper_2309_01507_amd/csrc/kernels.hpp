@@ -362,8 +362,8 @@ struct TileBase {
     float* ms;
     const float* r;
     float* r_new;
-    // the same arrays as bounds-checked resources of n_rows rows, for the loads
-    Rsrc rp, rg, rmq, rvq, rms, rr, rr_new;
+    // the same arrays as bounds-checked resources of n_rows rows, for the loads and the row stores
+    Rsrc rp, rg, rmq, rvq, rr, rr_new;
 };
 
 template <bool BF16>
@@ -382,7 +382,6 @@ __device__ __forceinline__ TileBase tile_base(const Tensor4& a, int64_t row0, in
     b.rg = tile_rsrc(b.g, elems * (BF16 ? 2u : 4u));
     b.rmq = tile_rsrc(b.mq, elems >> 1);
     b.rvq = tile_rsrc(b.vq, elems >> 1);
-    b.rms = tile_rsrc(b.ms, uint32_t(n_rows) * uint32_t(a.nb) * 4u);
     b.rr = tile_rsrc(b.r, uint32_t(n_rows) * 4u);
     b.rr_new = tile_rsrc(b.r_new, uint32_t(n_rows) * 4u);
     return b;
@@ -972,7 +971,7 @@ struct TileB {
     uint8_t* vq;
     float* ms;
     float* vs;
-    Rsrc rp, rg, rmq, rvq, rms, rvs;      // bounds-checked views of the tile, for the loads
+    Rsrc rp, rg, rmq, rvq;                // bounds-checked views of the tile, for the loads and stores
 };
 
 template <bool BF16>
@@ -989,8 +988,6 @@ __device__ __forceinline__ TileB tile_b128(const Tensor4& a, int64_t blk0, int n
     b.rg = tile_rsrc(reinterpret_cast<const char*>(a.g) + e * (BF16 ? 2 : 4), elems * (BF16 ? 2u : 4u));
     b.rmq = tile_rsrc(b.mq, elems >> 1);
     b.rvq = tile_rsrc(b.vq, elems >> 1);
-    b.rms = tile_rsrc(b.ms, uint32_t(n_blk) * 4u);
-    b.rvs = tile_rsrc(b.vs, uint32_t(n_blk) * 4u);
     return b;
 }
 
