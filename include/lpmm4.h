@@ -115,6 +115,24 @@ int lpmm_adamw4_step_bf16g(void* param, const void* grad, uint8_t* m_codes, floa
                            const int64_t shape[2], float lr, float beta1, float beta2, float eps,
                            float weight_decay, int64_t step, void* stream);
 
+/* The step of lpmm_adamw4_step / _step_bf16g for callers that cannot allocate device memory and do not want to
+ * size a workspace: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The
+ * row / column maxima of the updated second moment and the completion counters live in a device array that
+ * is part of the library itself (LPMM_NOALLOC_MAX_ROWS_PLUS_COLS + 128 floats + 8 KiB, held by every GPU the
+ * library is loaded on until the process ends) instead of the workspace given to lpmm_adamw4_init; init must
+ * still have run on the current device (it looks up the array's address there and uploads the tables), with
+ * any workspace.  Arguments, state layout, alignment and results as lpmm_adamw4_step; grad_dtype is
+ * LPMM_GRAD_F32 or LPMM_GRAD_BF16.  Limit: round_up(rows, 64) + round_up(cols, 64) <=
+ * LPMM_NOALLOC_MAX_ROWS_PLUS_COLS + 128, else LPMM_EWORKSPACE and nothing is enqueued.  Enqueues three kernels
+ * (one clears the part of the array this call uses), calls no allocating routine, no memset, no
+ * synchronization.  All calls on one GPU share the one array: calls that may overlap in time on one GPU
+ * (different streams) race; calls on one stream are safe. */
+#define LPMM_NOALLOC_MAX_ROWS_PLUS_COLS 131072
+int lpmm_adamw4_step_noalloc(void* param, const void* grad, int grad_dtype, uint8_t* m_codes,
+                             float* m_blockscale, uint8_t* v_codes, float* v_rowmax, float* v_colmax,
+                             const int64_t shape[2], float lr, float beta1, float beta2, float eps,
+                             float weight_decay, int64_t step, void* stream);
+
 /* ---- block-wise second moment: 1-dimensional and flattened tensors ---------------------------------
  * Rank-1 normalization needs a 2-dimensional shape; for a 1-dimensional tensor it degenerates and the
  * paper uses block-wise normalization with block size 128 for the second moment as well (Sec. 4.2,

@@ -71,6 +71,7 @@ def lib() -> ctypes.CDLL:
         step_args = [_VP] * 7 + [_VP] + [_F] * 5 + [_I64, _VP]
         L.lpmm_adamw4_step.argtypes = step_args
         L.lpmm_adamw4_step_bf16g.argtypes = step_args
+        L.lpmm_adamw4_step_noalloc.argtypes = [_VP, _VP, ctypes.c_int] + [_VP] * 5 + [_VP] + [_F] * 5 + [_I64, _VP]
         L.lpmm_adamw32_step.argtypes = [_VP] * 4 + [_I64, ctypes.c_int] + [_F] * 5 + [_I64, _VP]
         L.lpmm_adamw4_b128_state_sizes.argtypes = [_I64, _VP]
         L.lpmm_adamw4_b128_state_zero.argtypes = [_VP] * 4 + [_I64, _VP]
@@ -249,6 +250,15 @@ def lpmm_adamw4_step(param, grad, st: State4, lr, beta1, beta2, eps, weight_deca
 def lpmm_adamw4_step_bf16g(param, grad, st: State4, lr, beta1, beta2, eps, weight_decay, step,
                            stream=None):
     _step("lpmm_adamw4_step_bf16g", param, grad, st, lr, beta1, beta2, eps, weight_decay, step, stream)
+
+
+def lpmm_adamw4_step_noalloc(param, grad, grad_dtype: int, st: State4, lr, beta1, beta2, eps, weight_decay, step,
+                             stream=None):
+    shape = _shape(st.rows, st.cols)
+    _check(lib().lpmm_adamw4_step_noalloc(_ptr(param), _ptr(grad), int(grad_dtype), _ptr(st.m_codes),
+                                          _ptr(st.m_blockscale), _ptr(st.v_codes), _ptr(st.v_rowmax),
+                                          _ptr(st.v_colmax), ctypes.addressof(shape), lr, beta1, beta2, eps,
+                                          weight_decay, int(step), _stream(stream)), "lpmm_adamw4_step_noalloc")
 
 
 # ---- block-wise second moment (1-D / flattened tensors) ------------------------------------------------

@@ -29,7 +29,15 @@ struct DeviceCtx {
     int64_t cap_floats = 0;
     unsigned int* counter = nullptr;
     int n_cu = 256;
+    unsigned char* scratch = nullptr;   // this device's copy of `scratch` below (its address on this device)
 };
+
+// Device memory of the library's own for lpmm_adamw4_step_noalloc: the ticket counters of pass 2, then the row
+// and column maxima of the updated second moment.  Every GPU that loads the library holds one copy until the
+// process ends.  In host code this name is only a handle for hipGetSymbolAddress; the address of a device's
+// copy is DeviceCtx::scratch, looked up once per device by lpmm_adamw4_init.
+constexpr int64_t kScratchFloats = LPMM_NOALLOC_MAX_ROWS_PLUS_COLS + 128;     // rows and cols each padded to 64
+static __device__ __align__(256) unsigned char scratch[kCounterBytes + kScratchFloats * 4];
 
 DeviceCtx g_ctx[kMaxDevices];
 std::mutex g_mu;
@@ -254,9 +262,13 @@ int launch_step(const Tensor4& t, const Hyper& h, bool fast, hipStream_t s) {
     return LPMM_OK;
 }
 
+int fill(void* dst, int64_t n, uint8_t value, int64_t last_index, uint8_t last, hipStream_t s);
+
+// use_scratch: the maxima and counters live in the library's own device array instead of the workspace given
+// to lpmm_adamw4_init (lpmm_adamw4_step_noalloc)
 int step_impl(bool bf16, void* param, const void* grad, uint8_t* m_codes, float* m_blockscale,
               uint8_t* v_codes, float* v_rowmax, float* v_colmax, const int64_t* shape, float lr,
-              float beta1, float beta2, float eps, float wd, int64_t step, void* stream) {
+              float beta1, float beta2, float eps, float wd, int64_t step, void* stream, bool use_scratch = false) {
     int64_t rows, cols;
     int rc = check_shape(shape, &rows, &cols);
     if (rc) return rc;
@@ -272,7 +284,22 @@ int step_impl(bool bf16, void* param, const void* grad, uint8_t* m_codes, float*
     rc = current_ctx(&ctx);
     if (rc) return rc;
     const int64_t rows_pad = round_up(rows, 64), cols_pad = round_up(cols, 64);
-    if (rows_pad + cols_pad > ctx->cap_floats) return LPMM_EWORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    float* ws = ctx->ws;
+    unsigned int* counter = ctx->counter;
+    if (use_scratch) {
+        if (!ctx->scratch) return LPMM_ENOTINIT;
+        if (rows_pad + cols_pad > kScratchFloats) return LPMM_EWORKSPACE;
+        // The array keeps what the last call on this device left.  A completed step leaves zeros, a step that
+        // was cut short may not have: clear the part this call uses (counters, then the two runs of maxima)
+        // with a kernel, so that the call stays capturable.
+        rc = fill(ctx->scratch, int64_t(kCounterBytes) + (rows_pad + cols_pad) * int64_t(sizeof(float)), 0, -1, 0, s);
+        if (rc) return rc;
+        counter = reinterpret_cast<unsigned int*>(ctx->scratch);
+        ws = reinterpret_cast<float*>(ctx->scratch + kCounterBytes);
+    } else if (rows_pad + cols_pad > ctx->cap_floats) {
+        return LPMM_EWORKSPACE;
+    }
 
     Tensor4 t{};
     t.p = static_cast<float*>(param);
@@ -282,9 +309,9 @@ int step_impl(bool bf16, void* param, const void* grad, uint8_t* m_codes, float*
     t.vq = reinterpret_cast<uint32_t*>(v_codes);
     t.r = v_rowmax;
     t.c = v_colmax;
-    t.r_new = ctx->ws;
-    t.c_new = ctx->ws + rows_pad;
-    t.counter = ctx->counter;
+    t.r_new = ws;
+    t.c_new = ws + rows_pad;
+    t.counter = counter;
     t.rows = rows;
     t.cols = cols;
     t.P = rows * cols;
@@ -292,7 +319,6 @@ int step_impl(bool bf16, void* param, const void* grad, uint8_t* m_codes, float*
     t.kind = fast ? kQuantFast : kQuantGeneral;
     if (fast) fast_geometry(&t, ctx->n_cu, 0, 0, bf16 ? 2 : 4);
     else general_geometry(&t, ctx->n_cu);
-    hipStream_t s = static_cast<hipStream_t>(stream);
     return bf16 ? launch_step<true>(t, h, fast, s) : launch_step<false>(t, h, fast, s);
 }
 
@@ -722,9 +748,13 @@ int lpmm_adamw4_init(int device, void* workspace, size_t workspace_bytes, void* 
     if (e == hipSuccess) e = hipMemsetAsync(workspace, 0, workspace_bytes, s);
     int n_cu = 256;
     if (e == hipSuccess) e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, device);
+    // where this device keeps its copy of the library's own scratch array (`device` is current here)
+    unsigned char* scratch_ptr = nullptr;
+    if (e == hipSuccess) e = hipGetSymbolAddress(reinterpret_cast<void**>(&scratch_ptr), HIP_SYMBOL(scratch));
     (void)hipSetDevice(prev);
     if (e != hipSuccess) return hip_fail(e);
     DeviceCtx& c = g_ctx[device];
+    c.scratch = scratch_ptr;
     c.ws = static_cast<float*>(workspace);
     c.cap_floats = int64_t((workspace_bytes - kCounterBytes) / sizeof(float)) / 64 * 64;
     c.counter = reinterpret_cast<unsigned int*>(static_cast<char*>(workspace) + size_t(c.cap_floats) * sizeof(float));
@@ -778,6 +808,15 @@ int lpmm_adamw4_step_bf16g(void* param, const void* grad, uint8_t* m_codes, floa
                            int64_t step, void* stream) {
     return step_impl(true, param, grad, m_codes, m_blockscale, v_codes, v_rowmax, v_colmax, shape, lr,
                      beta1, beta2, eps, weight_decay, step, stream);
+}
+
+int lpmm_adamw4_step_noalloc(void* param, const void* grad, int grad_dtype, uint8_t* m_codes, float* m_blockscale,
+                             uint8_t* v_codes, float* v_rowmax, float* v_colmax, const int64_t shape[2],
+                             float lr, float beta1, float beta2, float eps, float weight_decay, int64_t step,
+                             void* stream) {
+    if (grad_dtype != LPMM_GRAD_F32 && grad_dtype != LPMM_GRAD_BF16) return LPMM_EINVAL;
+    return step_impl(grad_dtype == LPMM_GRAD_BF16, param, grad, m_codes, m_blockscale, v_codes, v_rowmax, v_colmax,
+                     shape, lr, beta1, beta2, eps, weight_decay, step, stream, true);
 }
 
 int lpmm_adamw4_b128_state_sizes(int64_t numel, size_t sizes[4]) {
