@@ -24,3 +24,23 @@ def golden(name):
             key, *vals = line.split()
             out[key] = vals
     return out
+
+
+_CONFIG = None
+
+
+def pytest_sessionstart(session):
+    global _CONFIG
+    _CONFIG = session.config
+
+
+def progress(msg: str) -> None:
+    """One line to the real stdout, past pytest's capture: long GPU tests report each stage, so that a run that
+    is merely busy can be told from one that hangs."""
+    line = "[gpu-test] " + msg
+    capman = _CONFIG.pluginmanager.getplugin("capturemanager") if _CONFIG is not None else None
+    if capman is None:
+        print(line, flush=True)
+        return
+    with capman.global_and_fixture_disabled():
+        print(line, flush=True)
