@@ -48,48 +48,26 @@ def bytes_per_param_factor(bf16: bool):
     return 8.0 + g + 1.0 + 8.0 / 128.0, g
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", default="c5_llama_7b")
-    ap.add_argument("--seed", type=int, default=1)
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--grad-dtype", choices=["config", "bf16", "f32"], default="config",
-                    help="override the gradient type of the configuration (experiments)")
-    ap.add_argument("--second-moment", choices=["rank1", "b128", "factor"], default="rank1",
-                    help="rank1: rank-1/Linear second moment of 2-D tensors (two passes, the headline "
-                         "configuration); b128: every tensor flat with a block-wise second moment (one pass); "
-                         "factor: row / column statistics instead of a per-element second moment (two passes)")
-    ap.add_argument("--optimizer", choices=["adamw", "sgdm"], default="adamw",
-                    help="adamw: the 4-bit AdamW step (the headline metric); sgdm: SGD with momentum and 4-bit "
-                         "momentum (App. E Alg. 2), every tensor flat, one pass")
-    ap.add_argument("--launch", choices=["multi", "per-tensor"], default="multi",
-                    help="multi: one plan, pass 1 / pass 2 of neighbouring tensor groups share launches; "
-                         "per-tensor: two launches per quantized tensor")
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
-              "use --gpus 1", file=sys.stderr)
-        sys.exit(2)
 
+class Workload:
+    """One synthetic parameter set resident on the device, with the closure that runs one optimizer step over it."""
+    pass
+
+
+def build_workload(config, second_moment, optimizer, grad_dtype, launch, seed):
     import torch
     import paper_2309_01507_amd as lpmm
     import workloads
 
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    lpmm.lib()                                   # fail loudly if lpmm4.so is missing
     dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
-    specs = workloads.param_set(args.config)
-    bf16 = workloads.GRAD_BF16[args.config] if args.grad_dtype == "config" else args.grad_dtype == "bf16"
-    recipe = workloads.GRAD_RECIPE[args.config]
+    specs = workloads.param_set(config)
+    bf16 = workloads.GRAD_BF16[config] if grad_dtype == "config" else grad_dtype == "bf16"
+    recipe = workloads.GRAD_RECIPE[config]
     lr, b1, b2, eps, wd = 1e-3, 0.9, 0.999, 1e-8, 0.01
 
     # ---- synthetic workload, generated on the device ------------------------------------------------
     gen = torch.Generator(device=dev)
-    gen.manual_seed(args.seed)
+    gen.manual_seed(seed)
     n_grad_sets = 2                              # the timed steps alternate between two gradient sets
     tensors = []
     max_rc = 2
@@ -114,13 +92,13 @@ def main():
                 z[zero, :] = 0.0
             gs.append(z.reshape(-1).to(torch.bfloat16) if bf16 else z.reshape(-1).contiguous())
             del z
-        if args.optimizer == "sgdm":
+        if optimizer == "sgdm":
             tensors.append(("q", sp, p, gs, lpmm.new_state_sgdm(sp.numel, dev)) if sp.quantized else
                            ("f", sp, p, gs, torch.zeros(sp.numel, device=dev)))
-        elif sp.quantized and args.second_moment == "b128":
+        elif sp.quantized and second_moment == "b128":
             tensors.append(("q", sp, p, gs, lpmm.new_state_b128(sp.numel, dev)))
         elif sp.quantized:
-            st = (lpmm.new_state_factor if args.second_moment == "factor" else lpmm.new_state)(sp.rows, sp.cols, dev)
+            st = (lpmm.new_state_factor if second_moment == "factor" else lpmm.new_state)(sp.rows, sp.cols, dev)
             max_rc = max(max_rc, sp.rows + sp.cols)
             tensors.append(("q", sp, p, gs, st))
         else:
@@ -130,11 +108,9 @@ def main():
     lpmm.ensure_init(max_rc)
     torch.cuda.synchronize()
 
-    n_params = sum(sp.numel for sp in specs)
-    n_quant = sum(sp.numel for sp in specs if sp.quantized)
-    sgdm = args.optimizer == "sgdm"
-    b128 = args.second_moment == "b128" and not sgdm
-    factor = args.second_moment == "factor" and not sgdm
+    sgdm = optimizer == "sgdm"
+    b128 = second_moment == "b128" and not sgdm
+    factor = second_moment == "factor" and not sgdm
     momentum = 0.9
     if sgdm:
         step4 = lpmm.lpmm_sgdm4_step_bf16g if bf16 else lpmm.lpmm_sgdm4_step
@@ -147,7 +123,7 @@ def main():
 
     # one plan per gradient set (a plan refers to its buffers by address)
     plans = []
-    if args.launch == "multi":
+    if launch == "multi":
         for k in range(n_grad_sets):
             if sgdm:
                 descs = [lpmm.make_desc_sgdm(p, gs[k], st, sp.numel) for kind, sp, p, gs, st in tensors]
@@ -175,6 +151,113 @@ def main():
                 lpmm.lpmm_adamw32_step(p, gs[k], st[0], st[1], sp.numel, 1 if bf16 else 0, lr, b1, b2, eps,
                                        wd, t)
 
+    def release():
+        for pl in plans:
+            lpmm.lpmm_adamw4_plan_release(pl)
+
+    wl = Workload()
+    wl.specs, wl.tensors, wl.plans, wl.one_step, wl.release = specs, tensors, plans, one_step, release
+    wl.bf16, wl.recipe, wl.sgdm, wl.b128, wl.factor = bf16, recipe, sgdm, b128, factor
+    wl.n_params = sum(sp.numel for sp in specs)
+    wl.n_quant = sum(sp.numel for sp in specs if sp.quantized)
+    wl.hyper = (lr, b1, b2, eps, wd, momentum)
+    # bp1: the recorded (dominant) kernel, bp2: the other pass
+    wl.bp1, wl.bp2 = ((bytes_per_param_b128(bf16), 0.0) if b128 else bytes_per_param_factor(bf16) if factor
+                      else (bytes_per_param_factor(bf16)[0], 0.0) if sgdm    # param 8, grad, m codes 1, block scales 8/128
+                      else bytes_per_param(bf16))
+    n_small = wl.n_params - wl.n_quant
+    wl.small_bytes = ((16.0 if sgdm else 24.0) + (2.0 if bf16 else 4.0)) * n_small   # fp32 states: p, m (, v) read+write, g read
+    return wl
+
+
+def time_steps(wl, steps, warmup, t0=0):
+    """`warmup` untimed steps, then exactly `steps` steps between two device synchronizations; returns (seconds, t)."""
+    import torch
+    t = t0
+    for _ in range(warmup):
+        t += 1
+        wl.one_step(t)
+    torch.cuda.synchronize()
+    c0 = time.perf_counter()
+    for _ in range(steps):
+        t += 1
+        wl.one_step(t)
+    torch.cuda.synchronize()
+    return time.perf_counter() - c0, t
+
+
+# The other configurations and variants, timed after the headline leg (outside its timed region) and reported under
+# "secondary": (workload, second moment, optimizer).
+SECONDARY = [("c1_single_1024", "rank1", "adamw"), ("c2_bert_base", "rank1", "adamw"),
+             ("c3_outlier_32000x4096", "rank1", "adamw"), ("c4_gpt2_medium", "rank1", "adamw"),
+             ("c5_llama_7b", "b128", "adamw"), ("c5_llama_7b", "factor", "adamw"), ("c5_llama_7b", "b128", "sgdm")]
+
+
+def secondary_leg(config, second_moment, optimizer, seed):
+    import gc
+    import torch
+    wl = build_workload(config, second_moment, optimizer, "config", "multi", seed)
+    probe, t = time_steps(wl, 3, 3)                        # sizes the timed run: about 0.2 s, 20 to 2000 steps
+    steps = int(min(2000, max(20, 0.2 / max(probe / 3, 1e-6))))
+    elapsed, t = time_steps(wl, steps, 0, t)
+    per_step = elapsed / steps
+    step_bytes = (wl.bp1 + wl.bp2) * wl.n_quant + wl.small_bytes
+    out = {"workload": config,
+           "variant": ("sgdm, flattened, one pass" if wl.sgdm else "block-wise second moment, flattened, one pass" if wl.b128
+                       else "factorized second moment, two passes" if wl.factor else "rank-1/Linear, two passes"),
+           "grad_dtype": "bf16" if wl.bf16 else "f32", "params": wl.n_params, "steps": steps,
+           "ms_per_step": round(per_step * 1e3, 4), "params_per_s": round(wl.n_params / per_step, 1),
+           "bytes_per_param": wl.bp1 + wl.bp2, "hbm_gbps": round(step_bytes / per_step / 1e9, 1),
+           "hbm_frac": round(step_bytes / per_step / 1e9 / HBM_PEAK_GBPS, 4)}
+    wl.release()
+    del wl
+    gc.collect()
+    torch.cuda.empty_cache()
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="c5_llama_7b")
+    ap.add_argument("--seed", type=int, default=1)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-secondary", action="store_true",
+                    help="skip the other configurations and variants that are timed after the headline leg")
+    ap.add_argument("--grad-dtype", choices=["config", "bf16", "f32"], default="config",
+                    help="override the gradient type of the configuration (experiments)")
+    ap.add_argument("--second-moment", choices=["rank1", "b128", "factor"], default="rank1",
+                    help="rank1: rank-1/Linear second moment of 2-D tensors (two passes, the headline "
+                         "configuration); b128: every tensor flat with a block-wise second moment (one pass); "
+                         "factor: row / column statistics instead of a per-element second moment (two passes)")
+    ap.add_argument("--optimizer", choices=["adamw", "sgdm"], default="adamw",
+                    help="adamw: the 4-bit AdamW step (the headline metric); sgdm: SGD with momentum and 4-bit "
+                         "momentum (App. E Alg. 2), every tensor flat, one pass")
+    ap.add_argument("--launch", choices=["multi", "per-tensor"], default="multi",
+                    help="multi: one plan, pass 1 / pass 2 of neighbouring tensor groups share launches; "
+                         "per-tensor: two launches per quantized tensor")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2309_01507_amd as lpmm
+    import workloads
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    lpmm.lib()                                   # fail loudly if lpmm4.so is missing
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    wl = build_workload(args.config, args.second_moment, args.optimizer, args.grad_dtype, args.launch, args.seed)
+    specs, tensors, plans, one_step = wl.specs, wl.tensors, wl.plans, wl.one_step
+    bf16, recipe, sgdm, b128, factor = wl.bf16, wl.recipe, wl.sgdm, wl.b128, wl.factor
+    n_params, n_quant = wl.n_params, wl.n_quant
+    lr, b1, b2, eps, wd, momentum = wl.hyper
+
     # ---- warm-up, then the timed region ---------------------------------------------------------------
     t = 0
     for _ in range(args.warmup):
@@ -191,14 +274,10 @@ def main():
     value = n_params / (elapsed / args.steps)
 
     # ---- the same K steps again with HIP events around every launch of the step -------------------------
-    # bp1: the recorded (dominant) kernel, bp2: the other pass
-    bp1, bp2 = ((bytes_per_param_b128(bf16), 0.0) if b128 else bytes_per_param_factor(bf16) if factor
-                else (bytes_per_param_factor(bf16)[0], 0.0) if sgdm    # param 8, grad, m codes 1, block scales 8/128
-                else bytes_per_param(bf16))
+    bp1, bp2, small_bytes = wl.bp1, wl.bp2, wl.small_bytes
     one_pass = b128 or sgdm
-    n_small = n_params - n_quant
-    small_bytes = ((16.0 if sgdm else 24.0) + (2.0 if bf16 else 4.0)) * n_small   # fp32 states: p, m (, v) read+write, g read
     n_q_tensors = sum(1 for x in tensors if x[0] == "q")
+    n_tensors, has_plans = len(tensors), bool(plans)
     lpmm.lpmm_profile_begin(max(n_q_tensors, 64) * args.steps)
     for _ in range(args.steps):
         t += 1
@@ -298,6 +377,22 @@ def main():
     except RuntimeError:
         pass
 
+    # ---- the other configurations and variants, for the record (after and outside the headline's timed region) ----
+    secondary = None
+    if not args.no_secondary and args.config == "c5_llama_7b" and args.second_moment == "rank1" and not sgdm \
+            and args.launch == "multi" and args.grad_dtype == "config":
+        import gc
+        wl.release()
+        del wl, specs, tensors, plans, one_step
+        gc.collect()
+        torch.cuda.empty_cache()
+        secondary = []
+        for cfg, sm, opt in SECONDARY:
+            try:
+                secondary.append(secondary_leg(cfg, sm, opt, args.seed))
+            except Exception as e:            # a failing side leg must not take the headline line with it
+                secondary.append({"workload": cfg, "variant": sm + "/" + opt, "error": repr(e)[:200]})
+
     total_gbps = ((bp1 + bp2) * n_quant + small_bytes) / (elapsed / args.steps) / 1e9
     # the same roofline for all kernels of a step together (they overlap on two streams, so a single kernel's
     # duration includes the slow-down from its neighbour): algorithmic bytes of the step / wall time of the step
@@ -308,16 +403,16 @@ def main():
     # for the rank-1 form, one more float per 128 elements standing in for the row / column maxima
     floor_bpp = 8.0 + (2.0 if bf16 else 4.0) + (1.0 if factor or sgdm else 2.0) + (16.0 if b128 else 8.0) / 128.0
     floor_gbps = (floor_bpp * n_quant + small_bytes) / (elapsed / args.steps) / 1e9
-    if plans:
+    if has_plans:
         kernels_per_step = (n_calls // max(args.steps, 1)) * (1 if one_pass else 2)     # as many A as B launches
     else:
-        kernels_per_step = n_q_tensors * (1 if one_pass else 2) + (len(tensors) - n_q_tensors)
+        kernels_per_step = n_q_tensors * (1 if one_pass else 2) + (n_tensors - n_q_tensors)
     out = {
         "metric": "params updated/sec per 4-bit SGDM step" if sgdm else "params updated/sec per 4-bit AdamW step", "value": round(value, 1), "unit": "params/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": args.config, "tensors": len(specs), "params": n_params,
+        "config": {"workload": args.config, "tensors": n_tensors, "params": n_params,
                    "quantized_params": n_quant, "grad_dtype": "bf16" if bf16 else "f32",
                    "second_moment": "none (SGD with momentum, App. E Alg. 2), flattened tensors, one pass" if sgdm
                    else "block-wise B128/Linear on flattened tensors, one pass" if b128
@@ -329,13 +424,13 @@ def main():
                                "passes on the caller's stream" if factor else
                                "multi-tensor plan, %d pass-1 launches per step on the caller's stream, "
                                "pass 2 on a second stream") % (n_calls // max(args.steps, 1)))
-                   if plans else "per-tensor, %d kernel%s per quantized tensor" % ((1, "") if one_pass else (2, "s")),
+                   if has_plans else "per-tensor, %d kernel%s per quantized tensor" % ((1, "") if one_pass else (2, "s")),
                    "kernels_per_step": kernels_per_step,
                    "hbm_gbps_one_touch_floor": round(floor_gbps, 1),
                    ("hbm_gbps_one_pass_model" if one_pass else "hbm_gbps_two_pass_model"): round(total_gbps, 1),
                    ("hbm_frac_one_pass_model" if one_pass else "hbm_frac_two_pass_model"):
                        round(total_gbps / HBM_PEAK_GBPS, 4)},
-        "roofline": roofline, "cpu_baseline": cpu,
+        "roofline": roofline, "cpu_baseline": cpu, "secondary": secondary,
     }
     print(json.dumps(out), flush=True)
 
