@@ -286,6 +286,43 @@ int lpmm_dequant_state(int which, const uint8_t* codes, const float* scale_a, co
 int lpmm_quant_state(int which, const float* in, const int64_t shape[2], uint8_t* codes,
                      float* scale_a, float* scale_b, void* stream);
 
+/* ---- the quantizers the paper ablates for the second moment ---------------------------------------------
+ * Sec. 4.1 and Tab. 1 compare, for the second moment: block-wise normalization with block size 2048 (the
+ * 8-bit optimizer's) or 128, or rank-1 normalization; the 4-bit dynamic-exponent map of App. D.2 ("DE":
+ * unsigned variant, 16 points with a zero), the same map with its zero removed ("DE-0", 15 points, the
+ * smallest being 0.0033), or the Linear map; and rounding to the nearest entry or stochastic rounding
+ * (App. D.3: between the two entries that enclose n, the upper one with probability (n - T(q1)) / (T(q2) -
+ * T(q1))).  Tab. 1's first line also compresses the first moment with B2048 / signed DE.  These two calls
+ * compress and decompress one tensor with any of those quantizers; they are not on an optimizer step's path.
+ *   codes    uint8[(P+1)/2], packed like the states above; a code is the rank in the map (DE-0: 0..14)
+ *   scale_a  float[ceil(P/128)] or float[ceil(P/2048)] block scales (absmax, blocks of the row-major
+ *            flattening), or float[rows] row maxima for rank-1
+ *   scale_b  float[cols] column maxima for rank-1, else ignored (may be NULL)
+ * is_signed = 1 (signed input, scale = max |x|, signed DE map) exists for the block-wise normalizations with
+ * LPMM_MAP_DE only; rank-1, DE-0 and Linear take non-negative input.  A zero scale gives n = 0.
+ * Stochastic rounding draws the uniform number of element idx (its row-major index) from a counter-based
+ * generator, so that results do not depend on the launch: u = (top 24 bits of SplitMix64's output number
+ * idx + 1 for the initial state `seed`) * 2^-24; the upper entry is taken iff u < p, p evaluated in fp32
+ * (two subtractions and one correctly rounded division).  in, codes, scales 4-byte aligned. */
+#define LPMM_NORM_B128   0
+#define LPMM_NORM_B2048  1
+#define LPMM_NORM_RANK1  2
+#define LPMM_MAP_DE      0
+#define LPMM_MAP_DE0     1
+#define LPMM_MAP_LINEAR  2
+#define LPMM_ROUND_NEAREST    0
+#define LPMM_ROUND_STOCHASTIC 1
+
+/* The entries of one of these maps (host call, no GPU needed): out[0 .. n) increasing, the rest 0; returns n
+ * (16, or 15 for DE-0), or LPMM_EINVAL for a combination that does not exist. */
+int lpmm_ablation_table(int map, int is_signed, float out[16]);
+
+int lpmm_quant_ablation(int norm, int map, int is_signed, int rounding, uint64_t seed, const float* in,
+                        const int64_t shape[2], uint8_t* codes, float* scale_a, float* scale_b, void* stream);
+
+int lpmm_dequant_ablation(int norm, int map, int is_signed, const uint8_t* codes, const float* scale_a,
+                          const float* scale_b, const int64_t shape[2], float* out, void* stream);
+
 /* ---- many tensors in one call ---------------------------------------------------------------------
  * The same step for a whole parameter set (Alg. 1: "perform the optimizer steps separately for each
  * layer" -- here all layers are enqueued by one call).  A plan is built once for a list of tensors;

@@ -73,6 +73,19 @@ def lib() -> ctypes.CDLL:
         L.oracle_adamw4_factor_step.argtypes = [f32p, f32p, u8p, f32p, f32p, f32p, i64, i64,
                                                 cf, cf, cf, cf, cf, i64, f32p, f32p]
         L.oracle_state_zero_factor.argtypes = [u8p, f32p, f32p, f32p, i64, i64]
+        u64 = ctypes.c_uint64
+        L.oracle_ablation_table.argtypes = [ctypes.c_int, ctypes.c_int, f32p]
+        L.oracle_ablation_table.restype = ctypes.c_int
+        L.oracle_splitmix64_at.argtypes = [u64, u64]
+        L.oracle_splitmix64_at.restype = u64
+        L.oracle_uniform_at.argtypes = [u64, u64]
+        L.oracle_uniform_at.restype = cf
+        L.oracle_round_stochastic.argtypes = [f32p, ctypes.c_int, cf, cf]
+        L.oracle_round_stochastic.restype = ctypes.c_int
+        L.oracle_quant_ablation.argtypes = [ctypes.c_int] * 4 + [u64, f32p, i64, i64, u8p, f32p, f32p]
+        L.oracle_quant_ablation.restype = ctypes.c_int
+        L.oracle_dequant_ablation.argtypes = [ctypes.c_int] * 3 + [u8p, f32p, f32p, i64, i64, f32p]
+        L.oracle_dequant_ablation.restype = ctypes.c_int
         for name in ("oracle_table_linear", "oracle_table_de", "oracle_table_de_f64",
                      "oracle_step_table", "oracle_nearest_codes", "oracle_quant_m",
                      "oracle_dequant_m", "oracle_quant_v", "oracle_dequant_v",
@@ -417,3 +430,66 @@ def sgdm4_step(w: np.ndarray, g: np.ndarray, st: StateSgdm, lr: float, beta: flo
 
 def sgdm32_step(w: np.ndarray, g: np.ndarray, m: np.ndarray, lr: float, beta: float):
     lib().oracle_sgdm32_step(_f32(w), _f32(g), _f32(m), w.size, lr, beta)
+
+
+# ---- ablation quantizers of the second moment (Sec. 4.1, Tab. 1) and stochastic rounding (App. D.3) --------------
+
+NORMS = {"b128": 0, "b2048": 1, "rank1": 2}
+MAPS = {"de": 0, "de0": 1, "linear": 2}
+NORM_BLOCK = {"b128": 128, "b2048": 2048}
+
+
+def ablation_table(map_name: str, signed: bool = False) -> np.ndarray:
+    """Entries of a 4-bit map: de (16 points; the signed or the unsigned variant), de0 (unsigned DE without its
+    zero, 15 points), linear (16 points)."""
+    out = np.zeros(16, np.float32)
+    n = lib().oracle_ablation_table(MAPS[map_name], int(signed), _f32(out))
+    if n == 0:
+        raise ValueError(f"no such map: {map_name}, signed={signed}")
+    return out[:n].copy()
+
+
+def splitmix64_at(seed: int, idx: int) -> int:
+    return int(lib().oracle_splitmix64_at(seed, idx))
+
+
+def uniform_at(seed: int, idx: int) -> float:
+    return float(lib().oracle_uniform_at(seed, idx))
+
+
+def round_stochastic(table: np.ndarray, n: float, u: float) -> int:
+    table = np.ascontiguousarray(table, np.float32)
+    return int(lib().oracle_round_stochastic(_f32(table), table.size, float(n), float(u)))
+
+
+def _ablation_scale_sizes(norm: str, rows: int, cols: int):
+    if norm == "rank1":
+        return rows, cols
+    B = NORM_BLOCK[norm]
+    return (rows * cols + B - 1) // B, 1
+
+
+def quant_ablation(x: np.ndarray, norm: str, map_name: str, signed: bool = False, stochastic: bool = False,
+                   seed: int = 0):
+    """x: float32 (rows, cols).  Returns (codes, scale_a, scale_b): block scales or row maxima, column maxima
+    (rank-1 only, else one unused float)."""
+    x = np.ascontiguousarray(x, np.float32)
+    rows, cols = x.shape
+    na, nb = _ablation_scale_sizes(norm, rows, cols)
+    codes = np.zeros(codes_bytes(x.size), np.uint8)
+    sa, sb = np.zeros(na, np.float32), np.zeros(nb, np.float32)
+    rc = lib().oracle_quant_ablation(NORMS[norm], MAPS[map_name], int(signed), int(stochastic), seed, _f32(x),
+                                     rows, cols, _u8(codes), _f32(sa), _f32(sb))
+    if rc != 0:
+        raise ValueError(f"no such quantizer: {norm}/{map_name}, signed={signed}")
+    return codes, sa, sb
+
+
+def dequant_ablation(codes: np.ndarray, sa: np.ndarray, sb: np.ndarray, rows: int, cols: int, norm: str,
+                     map_name: str, signed: bool = False) -> np.ndarray:
+    out = np.empty((rows, cols), np.float32)
+    rc = lib().oracle_dequant_ablation(NORMS[norm], MAPS[map_name], int(signed), _u8(codes), _f32(sa), _f32(sb),
+                                       rows, cols, _f32(out))
+    if rc != 0:
+        raise ValueError(f"no such quantizer: {norm}/{map_name}, signed={signed}")
+    return out

@@ -27,6 +27,10 @@
 //     not stored per element but factorized the way the cited Adafactor method does it: one
 //     statistic per row and one per column, v_ij reconstructed as row_i * col_j / sum(row).  The
 //     first moment stays B128/DE.  Functions *_factor_*.
+//   * Sec. 4.1, Tab. 1 and App. D.3 (ablation quantizers, not on any optimizer step's path): block-wise
+//     normalization with block size 2048 ("B2048", the 8-bit optimizer's), the unsigned 4-bit DE map, the same
+//     map with its zero removed ("DE-0", 15 points, smallest 0.0033), and stochastic rounding between the two
+//     neighbouring table entries.  Functions *_ablation.
 //   * App. D.1: signed normalization n = sign(x) N(|x|).
 //   * App. D.2: the dynamic-exponent (DE) map: sign bit, E leading zeros, indicator bit,
 //     F fraction bits; value 10^-E * fraction[k]; two special bit patterns; sorted list.
@@ -47,6 +51,10 @@
 //   * A zero scale (all-zero block, untouched row/column, the zero initial state) gives n := 0.
 //   * Scales are fp32.  Two codes per byte: element 2k in bits 0..3, element 2k+1 in bits 4..7.
 //   * Blocks are [128k, 128k+127] of the row-major flattening; the last one may be short.
+//   * Stochastic rounding (App. D.3) needs one uniform number per element.  It is drawn from a counter-based
+//     generator so that both sides can produce it on their own: u = (top 24 bits of SplitMix64's output number
+//     idx+1 for the state `seed`) * 2^-24, idx the element's flat index; the upper candidate is taken iff
+//     u < p, with p = (n - T[q1]) / (T[q2] - T[q1]) evaluated in fp32 (two subtractions, one division).
 //   * 4-bit Factor: the paper gives no formulas, only the citation.  Reading: the optimizer stays the
 //     AdamW of Eq. 1 (same beta2, same bias correction, same eps; none of the cited method's own extras:
 //     no update clipping, no relative step size, no decay-rate schedule, no 1e-30 added to g^2);
@@ -327,9 +335,136 @@ void sgdm_rule(float* w, float* m, const float* g, int64_t P, float lr, float be
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Ablation quantizers of the second moment (Sec. 4.1, Tab. 1) and stochastic rounding (App. D.3).
+// norm: 0 = B128, 1 = B2048 (block-wise normalization, Sec. 2.2, with the two block sizes the paper
+// compares), 2 = rank-1 (Sec. 4.2).  map: 0 = 4-bit DE (unsigned variant for non-negative input, signed
+// variant for signed input), 1 = DE-0 (unsigned DE without its zero: 15 points), 2 = Linear.
+// Signed input (the first moment of Tab. 1's first line, "B2048/DE for both moments") takes block-wise
+// normalization and the signed DE map only.
+// ---------------------------------------------------------------------------------------------
+
+bool ablation_table(int map, bool is_signed, std::vector<float>& T) {
+    std::vector<double> t;
+    if (map == 0) {
+        table_de(kBits, is_signed, t);
+    } else if (map == 1 && !is_signed) {
+        table_de(kBits, false, t);
+        t.erase(std::remove(t.begin(), t.end(), 0.0), t.end());      // "simply remove zero" (Sec. 4.1)
+    } else if (map == 2 && !is_signed) {
+        table_linear(kBits, t);
+    } else {
+        return false;
+    }
+    T.resize(t.size());
+    for (size_t i = 0; i < t.size(); ++i) T[i] = float(t[i]);
+    return true;
+}
+
+// SplitMix64 (Steele, Lea, Flood 2014): output number idx+1 of the generator whose state starts at `seed`.
+uint64_t splitmix64_at(uint64_t seed, uint64_t idx) {
+    uint64_t z = seed + (idx + 1) * 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+float uniform_at(uint64_t seed, uint64_t idx) { return float(splitmix64_at(seed, idx) >> 40) * 0x1p-24f; }
+
+// App. D.3: the candidate set M(n) holds the nearest entry at or below n and the nearest entry at or
+// above n (one point when n is an entry or lies outside the table's range); between two candidates
+// q1 < q2 the upper one is chosen with probability (n - T(q1)) / (T(q2) - T(q1)).
+int round_stochastic(const float* T, int n_entries, float n, float u) {
+    int q1 = -1, q2 = -1;
+    for (int i = 0; i < n_entries; ++i) if (T[i] <= n) q1 = i;                // largest entry <= n
+    for (int i = n_entries - 1; i >= 0; --i) if (T[i] >= n) q2 = i;           // smallest entry >= n
+    if (q1 < 0 && q2 < 0) return 0;     // n is not a number
+    if (q1 < 0) return q2;
+    if (q2 < 0) return q1;
+    if (q1 == q2) return q1;
+    const float p = (n - T[q1]) / (T[q2] - T[q1]);
+    return u < p ? q2 : q1;
+}
+
+// per-element scale of the chosen normalization; sa / sb receive the statistics
+void ablation_scales(const float* x, int64_t rows, int64_t cols, int norm, float* sa, float* sb,
+                     std::vector<float>& scale) {
+    const int64_t P = rows * cols;
+    scale.assign(size_t(P), 0.0f);
+    if (norm == 2) {
+        for (int64_t i = 0; i < rows; ++i) sa[i] = 0.0f;
+        for (int64_t j = 0; j < cols; ++j) sb[j] = 0.0f;
+        for (int64_t i = 0; i < rows; ++i)
+            for (int64_t j = 0; j < cols; ++j) {
+                sa[i] = std::max(sa[i], x[i * cols + j]);
+                sb[j] = std::max(sb[j], x[i * cols + j]);
+            }
+        for (int64_t i = 0; i < rows; ++i)
+            for (int64_t j = 0; j < cols; ++j) scale[size_t(i * cols + j)] = std::min(sa[i], sb[j]);
+    } else {
+        const int64_t B = norm == 0 ? 128 : 2048;
+        const int64_t nblk = (P + B - 1) / B;
+        for (int64_t k = 0; k < nblk; ++k) {
+            const int64_t lo = k * B, hi = std::min(P, lo + B);
+            float s = 0.0f;
+            for (int64_t i = lo; i < hi; ++i) s = std::max(s, std::fabs(x[i]));
+            sa[k] = s;
+            for (int64_t i = lo; i < hi; ++i) scale[size_t(i)] = s;
+        }
+    }
+}
+
 }  // namespace
 
 extern "C" {
+
+// ---- ablation quantizers (Sec. 4.1, Tab. 1, App. D.3) ------------------------------------------
+// Number of entries of the map (16, or 15 for DE-0), 0 for an invalid combination; out (may be null)
+// receives the entries.
+int oracle_ablation_table(int map, int is_signed, float* out) {
+    std::vector<float> T;
+    if (!ablation_table(map, is_signed != 0, T)) return 0;
+    if (out) for (size_t i = 0; i < T.size(); ++i) out[i] = T[i];
+    return int(T.size());
+}
+uint64_t oracle_splitmix64_at(uint64_t seed, uint64_t idx) { return splitmix64_at(seed, idx); }
+float oracle_uniform_at(uint64_t seed, uint64_t idx) { return uniform_at(seed, idx); }
+int oracle_round_stochastic(const float* table, int n_entries, float n, float u) {
+    return round_stochastic(table, n_entries, n, u);
+}
+// Compress x (rows x cols, row-major; block-wise normalizations take it flat).  codes: (P+1)/2 bytes.
+// sa: block scales (ceil(P/128) or ceil(P/2048) floats) or row maxima (rows floats); sb: column maxima
+// (cols floats, rank-1 only).  rounding: 0 = nearest (Sec. 2.2), 1 = stochastic (App. D.3) with `seed`.
+// Returns 0, or -1 for a combination that does not exist.
+int oracle_quant_ablation(int norm, int map, int is_signed, int rounding, uint64_t seed, const float* x,
+                          int64_t rows, int64_t cols, uint8_t* codes, float* sa, float* sb) {
+    std::vector<float> T, scale;
+    if (!ablation_table(map, is_signed != 0, T) || norm < 0 || norm > 2 || (norm == 2 && is_signed)) return -1;
+    const int64_t P = rows * cols;
+    ablation_scales(x, rows, cols, norm, sa, sb, scale);
+    std::memset(codes, 0, size_t((P + 1) / 2));
+    for (int64_t e = 0; e < P; ++e) {
+        const float s = scale[size_t(e)];
+        const float n = (s == 0.0f) ? 0.0f : x[e] / s;
+        const int q = rounding ? round_stochastic(T.data(), int(T.size()), n, uniform_at(seed, uint64_t(e)))
+                               : nearest_code(T.data(), int(T.size()), n);
+        put_code(codes, e, q);
+    }
+    return 0;
+}
+int oracle_dequant_ablation(int norm, int map, int is_signed, const uint8_t* codes, const float* sa,
+                            const float* sb, int64_t rows, int64_t cols, float* out) {
+    std::vector<float> T;
+    if (!ablation_table(map, is_signed != 0, T) || norm < 0 || norm > 2 || (norm == 2 && is_signed)) return -1;
+    const int64_t B = norm == 0 ? 128 : 2048;
+    for (int64_t i = 0; i < rows; ++i)
+        for (int64_t j = 0; j < cols; ++j) {
+            const int64_t e = i * cols + j;
+            const float s = norm == 2 ? std::min(sa[i], sb[j]) : sa[e / B];
+            const int q = get_code(codes, e);
+            out[e] = (q < int(T.size()) ? T[size_t(q)] : 0.0f) * s;
+        }
+    return 0;
+}
 
 // ---- tables --------------------------------------------------------------------------------
 // out must hold 2^bits floats (table_de) / doubles (table_de_f64).

@@ -1,8 +1,8 @@
 """A synthetic quantization-error study of the second-moment quantizers that the paper ablates (Sec. 4.1, Tab. 1):
-normalization (per tensor, B2048, B128, rank-1) x mapping (DE with zero, DE-0, Linear) x rounding (nearest,
-stochastic as in App. D.3).  CPU only, numpy in fp64 on top of the oracle's tables; test infrastructure like the rest
-of this directory (there is no GPU counterpart: none of these variants is on a step's path except Rank-1/Linear and
-B128/Linear, which the oracle proper and the kernels implement).
+normalization (B2048, B128, rank-1) x mapping (DE with zero, DE-0, Linear) x rounding (nearest, stochastic as in
+App. D.3), on the CPU with the oracle's quantizers (oracle_quant_ablation / oracle_dequant_ablation).  Test
+infrastructure like the rest of this directory; the GPU library has the same quantizers behind
+lpmm_quant_ablation, and its own study script.
 
 What is measured, per quantizer, on a synthetic second moment: the share of entries that decompress to exactly 0,
 and the error of h(v) = 1 / (sqrt(v) + 1e-6), the factor by which Adam's update direction scales (Sec. 4.1 "zero-point
@@ -12,63 +12,13 @@ from __future__ import annotations
 
 import numpy as np
 
-from . import table_de, table_linear
+from . import dequant_ablation, quant_ablation
 
 
-def mapping(name: str) -> np.ndarray:
-    """de: unsigned 4-bit dynamic-exponent map (contains 0); de0: the same without its zero (15 points, Sec. 4.1);
-    linear: (i+1)/16."""
-    if name == "de":
-        return table_de(4, signed=False).astype(np.float64)
-    if name == "de0":
-        t = table_de(4, signed=False).astype(np.float64)
-        return t[t > 0]
-    if name == "linear":
-        return table_linear(4).astype(np.float64)
-    raise ValueError(name)
-
-
-def scales(x: np.ndarray, norm: str) -> np.ndarray:
-    """Per-element normalization scale of a non-negative matrix (Sec. 2.2 per-tensor and block-wise over the
-    row-major flattening, Sec. 4.2 rank-1)."""
-    if norm == "tensor":
-        return np.full(x.shape, x.max())
-    if norm.startswith("b"):
-        B = int(norm[1:])
-        flat = x.reshape(-1)
-        nb = -(-flat.size // B)
-        pad = np.zeros(nb * B)
-        pad[:flat.size] = flat
-        return np.repeat(pad.reshape(nb, B).max(axis=1), B)[:flat.size].reshape(x.shape)
-    if norm == "rank1":
-        return np.minimum(x.max(axis=1)[:, None], x.max(axis=0)[None, :])
-    raise ValueError(norm)
-
-
-def quantize(n: np.ndarray, T: np.ndarray, u: np.ndarray | None = None) -> np.ndarray:
-    """Codes of normalized values n in [0, 1].  u is None: nearest entry, ties to the lower index (Sec. 2.2).
-    u given (uniform numbers in [0, 1), one per element): stochastic rounding between the two neighbouring entries
-    (App. D.3): the upper one with probability (n - T[q1]) / (T[q2] - T[q1]); values outside the table's range
-    or on an entry have a single candidate."""
-    hi = np.clip(np.searchsorted(T, n, side="left"), 0, T.size - 1)       # first entry >= n
-    lo = np.clip(hi - 1, 0, T.size - 1)
-    lo = np.where(T[hi] == n, hi, lo)                                      # n is an entry: one candidate
-    lo = np.where(n < T[0], 0, lo)
-    hi = np.where(n < T[0], 0, hi)
-    hi = np.where(n > T[-1], T.size - 1, hi)
-    lo = np.where(n > T[-1], T.size - 1, lo)
-    if u is None:
-        return np.where(np.abs(n - T[lo]) <= np.abs(T[hi] - n), lo, hi)
-    gap = T[hi] - T[lo]
-    p_up = np.where(gap > 0, (n - T[lo]) / np.where(gap > 0, gap, 1.0), 0.0)
-    return np.where(u < p_up, hi, lo)
-
-
-def roundtrip(x: np.ndarray, norm: str, map_name: str, u: np.ndarray | None = None) -> np.ndarray:
-    T = mapping(map_name)
-    s = scales(x, norm)
-    n = np.divide(x, s, out=np.zeros_like(x), where=s > 0)
-    return T[quantize(n, T, u)] * s
+def roundtrip(x: np.ndarray, norm: str, map_name: str, stochastic: bool = False, seed: int = 0) -> np.ndarray:
+    x = np.ascontiguousarray(x, np.float32)
+    codes, sa, sb = quant_ablation(x, norm, map_name, False, stochastic, seed)
+    return dequant_ablation(codes, sa, sb, x.shape[0], x.shape[1], norm, map_name)
 
 
 def synthetic_second_moment(rows=512, cols=1024, seed=0) -> np.ndarray:
@@ -82,27 +32,26 @@ def synthetic_second_moment(rows=512, cols=1024, seed=0) -> np.ndarray:
     for _ in range(50):
         g = rng.standard_normal((rows, cols)) * sigma[None, :]
         v = 0.999 * v + 0.001 * g * g
-    return v
+    return v.astype(np.float32)
 
 
 def h(v):
-    return 1.0 / (np.sqrt(v) + 1e-6)
+    return 1.0 / (np.sqrt(v.astype(np.float64)) + 1e-6)
 
 
 def study(v: np.ndarray, seed=1):
-    rng = np.random.default_rng(seed)
-    u = rng.random(v.shape)
     rows = []
-    for norm in ("tensor", "b2048", "b128", "rank1"):
+    v64 = v.astype(np.float64)
+    for norm in ("b2048", "b128", "rank1"):
         for map_name in ("de", "de0", "linear"):
             for sr in (False, True):
-                d = roundtrip(v, norm, map_name, u if sr else None)
+                d = roundtrip(v, norm, map_name, sr, seed)
                 ratio = h(d) / h(v)
                 rows.append({"norm": norm, "map": map_name, "rounding": "stochastic" if sr else "nearest",
                              "zero_share": float((d == 0).mean()),
                              "median_h_factor": float(10 ** np.median(np.abs(np.log10(ratio)))),
                              "share_h_off_2x": float((np.abs(np.log10(ratio)) > np.log10(2.0)).mean()),
-                             "rel_err_v": float(np.sqrt(((d - v) ** 2).sum() / (v ** 2).sum()))})
+                             "rel_err_v": float(np.sqrt(((d.astype(np.float64) - v64) ** 2).sum() / (v64 ** 2).sum()))})
     return rows
 
 

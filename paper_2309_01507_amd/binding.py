@@ -101,6 +101,9 @@ def lib() -> ctypes.CDLL:
         L.lpmm_adamw4_factor_step_bf16g.argtypes = factor_args
         L.lpmm_dequant_state.argtypes = [ctypes.c_int, _VP, _VP, _VP, _VP, _VP, _VP]
         L.lpmm_quant_state.argtypes = [ctypes.c_int, _VP, _VP, _VP, _VP, _VP, _VP]
+        L.lpmm_ablation_table.argtypes = [ctypes.c_int, ctypes.c_int, _VP]
+        L.lpmm_quant_ablation.argtypes = [ctypes.c_int] * 4 + [ctypes.c_uint64, _VP, _VP, _VP, _VP, _VP, _VP]
+        L.lpmm_dequant_ablation.argtypes = [ctypes.c_int] * 3 + [_VP, _VP, _VP, _VP, _VP, _VP]
         L.lpmm_adamw4_plan_bytes.argtypes = [_VP, _I64]
         L.lpmm_adamw4_plan_bytes.restype = ctypes.c_size_t
         L.lpmm_adamw4_plan_build.argtypes = [_VP, _I64, ctypes.c_int, _VP, ctypes.c_size_t, _VP]
@@ -516,6 +519,43 @@ def lpmm_quant_state(which: int, x, rows, cols, codes, scale_a, scale_b, stream=
     _check(lib().lpmm_quant_state(int(which), _ptr(x), ctypes.addressof(shape), _ptr(codes),
                                   _ptr(scale_a), _ptr(scale_b), _stream(stream)),
            "lpmm_quant_state")
+
+
+# ---- the ablation quantizers of the second moment ---------------------------------------------------------
+
+NORM_B128, NORM_B2048, NORM_RANK1 = 0, 1, 2
+MAP_DE, MAP_DE0, MAP_LINEAR = 0, 1, 2
+ROUND_NEAREST, ROUND_STOCHASTIC = 0, 1
+
+
+def lpmm_ablation_table(map_: int, is_signed: bool = False):
+    import numpy as np
+    out = np.zeros(16, np.float32)
+    n = lib().lpmm_ablation_table(int(map_), int(is_signed), out.ctypes.data)
+    _check(min(n, 0), "lpmm_ablation_table")
+    return out[:n].copy()
+
+
+def ablation_scale_sizes(norm: int, rows: int, cols: int):
+    """Number of floats of scale_a and scale_b."""
+    if norm == NORM_RANK1:
+        return rows, cols
+    B = 128 if norm == NORM_B128 else 2048
+    return (rows * cols + B - 1) // B, 0
+
+
+def lpmm_quant_ablation(norm, map_, is_signed, rounding, seed, x, rows, cols, codes, scale_a, scale_b, stream=None):
+    shape = _shape(rows, cols)
+    _check(lib().lpmm_quant_ablation(int(norm), int(map_), int(is_signed), int(rounding), int(seed), _ptr(x),
+                                     ctypes.addressof(shape), _ptr(codes), _ptr(scale_a), _ptr(scale_b),
+                                     _stream(stream)), "lpmm_quant_ablation")
+
+
+def lpmm_dequant_ablation(norm, map_, is_signed, codes, scale_a, scale_b, rows, cols, out, stream=None):
+    shape = _shape(rows, cols)
+    _check(lib().lpmm_dequant_ablation(int(norm), int(map_), int(is_signed), _ptr(codes), _ptr(scale_a),
+                                       _ptr(scale_b), ctypes.addressof(shape), _ptr(out), _stream(stream)),
+           "lpmm_dequant_ablation")
 
 
 # ---- many tensors in one call ------------------------------------------------------------------------

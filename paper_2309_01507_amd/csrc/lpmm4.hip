@@ -14,6 +14,7 @@
 
 #include "../../include/lpmm4.h"
 #include "kernels.hpp"
+#include "ablation.hpp"
 
 namespace {
 
@@ -1071,6 +1072,108 @@ int lpmm_quant_state(int which, const float* in, const int64_t shape[2], uint8_t
         hipLaunchKernelGGL(quant_v_code_kernel, dim3(grid), dim3(kThreads), 0, s, q);
         LPMM_HIP(hipGetLastError());
     }
+    return LPMM_OK;
+}
+
+}  // extern "C"
+
+namespace {
+
+// the map of an ablation quantizer, with its decision thresholds; false for a combination that does not exist
+bool ablation_map(int map, int is_signed, AblMap* m) {
+    float T[kCodes];
+    int n = kCodes;
+    if (map == LPMM_MAP_DE) {
+        if (is_signed) build_de_signed(T); else build_de_unsigned(T);
+    } else if (map == LPMM_MAP_DE0 && !is_signed) {
+        float U[kCodes];
+        build_de_unsigned(U);                 // U[0] is the zero that DE-0 drops
+        n = kCodes - 1;
+        for (int i = 0; i < n; ++i) T[i] = U[i + 1];
+    } else if (map == LPMM_MAP_LINEAR && !is_signed) {
+        build_linear(T);
+    } else {
+        return false;
+    }
+    *m = AblMap{};
+    m->n = n;
+    for (int i = 0; i < n; ++i) m->T[i] = T[i];
+    build_thresholds_n(T, n, m->thr);
+    return true;
+}
+
+bool ablation_valid(int norm, int is_signed) {
+    return (norm == LPMM_NORM_B128 || norm == LPMM_NORM_B2048 || (norm == LPMM_NORM_RANK1 && !is_signed));
+}
+
+}  // namespace
+
+extern "C" {
+
+int lpmm_ablation_table(int map, int is_signed, float out[16]) {
+    AblMap m;
+    if (!out || !ablation_map(map, is_signed, &m)) return LPMM_EINVAL;
+    for (int i = 0; i < kCodes; ++i) out[i] = i < m.n ? m.T[i] : 0.0f;
+    return m.n;
+}
+
+int lpmm_quant_ablation(int norm, int map, int is_signed, int rounding, uint64_t seed, const float* in,
+                        const int64_t shape[2], uint8_t* codes, float* scale_a, float* scale_b, void* stream) {
+    int64_t rows, cols;
+    const int rc = check_shape(shape, &rows, &cols);
+    if (rc) return rc;
+    AblMap m;
+    if (!ablation_valid(norm, is_signed) || !ablation_map(map, is_signed, &m)) return LPMM_EINVAL;
+    if (rounding != LPMM_ROUND_NEAREST && rounding != LPMM_ROUND_STOCHASTIC) return LPMM_EINVAL;
+    if (!in || !codes || !scale_a || (norm == LPMM_NORM_RANK1 && !scale_b)) return LPMM_EINVAL;
+    if (!aligned(in, 4) || !aligned(codes, 4) || !aligned(scale_a, 4)) return LPMM_EINVAL;
+    AblArgs a{};
+    a.x_in = in;
+    a.q_out = reinterpret_cast<uint32_t*>(codes);
+    a.sa = scale_a;
+    a.sb = scale_b;
+    a.rows = rows; a.cols = cols; a.P = rows * cols;
+    a.stochastic = rounding == LPMM_ROUND_STOCHASTIC;
+    a.seed = seed;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int grid = grid_for(a.P, 8);
+    if (norm == LPMM_NORM_RANK1) {
+        int r = fill(scale_a, rows * int64_t(sizeof(float)), 0, -1, 0, s);
+        if (!r) r = fill(scale_b, cols * int64_t(sizeof(float)), 0, -1, 0, s);
+        if (r) return r;
+        QuantArgs q{};
+        q.x_in = in; q.sa = scale_a; q.sb = scale_b;
+        q.rows = rows; q.cols = cols; q.P = a.P;
+        hipLaunchKernelGGL(quant_v_max_kernel, dim3(grid), dim3(kThreads), 0, s, q);
+        LPMM_HIP(hipGetLastError());
+        hipLaunchKernelGGL(abl_quant_rank1_kernel, dim3(grid), dim3(kThreads), 0, s, a, m);
+    } else if (norm == LPMM_NORM_B128) {
+        hipLaunchKernelGGL(abl_quant_block_kernel<128>, dim3(grid), dim3(kThreads), 0, s, a, m);
+    } else {
+        hipLaunchKernelGGL(abl_quant_block_kernel<2048>, dim3(grid), dim3(kThreads), 0, s, a, m);
+    }
+    LPMM_HIP(hipGetLastError());
+    return LPMM_OK;
+}
+
+int lpmm_dequant_ablation(int norm, int map, int is_signed, const uint8_t* codes, const float* scale_a,
+                          const float* scale_b, const int64_t shape[2], float* out, void* stream) {
+    int64_t rows, cols;
+    const int rc = check_shape(shape, &rows, &cols);
+    if (rc) return rc;
+    AblMap m;
+    if (!ablation_valid(norm, is_signed) || !ablation_map(map, is_signed, &m)) return LPMM_EINVAL;
+    if (!codes || !scale_a || !out || (norm == LPMM_NORM_RANK1 && !scale_b)) return LPMM_EINVAL;
+    if (!aligned(codes, 4) || !aligned(out, 4) || !aligned(scale_a, 4)) return LPMM_EINVAL;
+    AblArgs a{};
+    a.q_in = reinterpret_cast<const uint32_t*>(codes);
+    a.x_out = out;
+    a.sa = const_cast<float*>(scale_a);
+    a.sb = const_cast<float*>(scale_b);
+    a.rows = rows; a.cols = cols; a.P = rows * cols;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipLaunchKernelGGL(abl_dequant_kernel, dim3(grid_for(a.P, 8)), dim3(kThreads), 0, s, a, m, norm);
+    LPMM_HIP(hipGetLastError());
     return LPMM_OK;
 }
 

@@ -67,6 +67,30 @@ inline void build_de_signed(float T[kCodes]) {
     T[15] = 1.0f;   // the -000 pattern
 }
 
+// Unsigned 4-bit dynamic-exponent map (App. D.2; used by the ablation quantizers of Sec. 4.1 / Tab. 1): no sign
+// bit, so one more bit for the fraction in every decade: 8 bins with E = 0, 4 with E = 1, 2 with E = 2; the single
+// bin of E = 3 is the bit pattern 0001, which the map assigns the value 1, and 0000 is 0.
+inline void build_de_unsigned(float T[kCodes]) {
+    int n = 0;
+    T[n++] = 0.0f;
+    for (int E = 2; E >= 0; --E) {
+        const int bins = 1 << (3 - E);
+        const double width = 0.9 / bins;
+        for (int k = 0; k < bins; ++k) T[n++] = float((0.1 + width * (k + 0.5)) * std::pow(10.0, -E));
+    }
+    T[n++] = 1.0f;      // n == 16; increasing by construction
+}
+
+// thr[k], k = 0..n-2, for any increasing table of n entries (see build_thresholds)
+inline void build_thresholds_n(const float* T, int n, float* thr) {
+    for (int k = 0; k + 1 < n; ++k) {
+        const double mid = (double(T[k]) + double(T[k + 1])) * 0.5;
+        float f = float(mid);
+        if (double(f) > mid) f = std::nextafterf(f, -std::numeric_limits<float>::infinity());
+        thr[k] = f;
+    }
+}
+
 inline void build_linear(float T[kCodes]) {
     for (int i = 0; i < kCodes; ++i) T[i] = float(i + 1) * 0.0625f;
 }
@@ -99,6 +123,13 @@ inline bool build_search(const float thr[kCodes - 1], SearchEntry tab[kBucketsPa
         if (!(std::fabs(thr[k]) <= 1.0f)) return false;
         const int b = search_bucket(thr[k]);
         if (owner[b] >= 0) return false;
+        // The step kernels look up the bucket of an approximate n' that may be a few units in the last place away
+        // from the exact n; their guard only compares n' with the threshold of its own bucket.  That is sound as
+        // long as no threshold lies so close to a bucket edge (k + 0.5) / 256 that n and n' could straddle the
+        // edge next to it: demand a distance of 2^-20 relative, thousands of times the guard's reach.
+        const double pos = double(thr[k]) * kBucketHalf + 0.5;
+        const double to_edge = std::fabs(pos - std::nearbyint(pos));
+        if (to_edge < std::ldexp(std::fabs(double(thr[k])) * kBucketHalf, -20)) return false;
         owner[b] = k;
     }
     uint32_t below = 0;

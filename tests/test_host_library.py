@@ -215,3 +215,17 @@ def test_plan_bytes_with_inner_dimension_tables():
     f = lpmm.TensorDesc(p, p, p, p, None, p, p, 8, 128, lpmm.KIND_4BIT_FACTOR, 0)
     d.inner = (4, 32)
     assert lpmm.lpmm_adamw4_plan_bytes([d, f]) == 0                    # rank-1 and factorized tensors do not mix
+
+
+def test_ablation_maps_equal_the_oracles():
+    """The maps of the ablation quantizers (Sec. 4.1, Tab. 1) as the library builds them (per-decade bin midpoints)
+    against the oracle's (bit-pattern decode and sort), entry for entry; combinations that do not exist are
+    refused."""
+    import ctypes
+    for name, code, signed in (("de", 0, False), ("de", 0, True), ("de0", 1, False), ("linear", 2, False)):
+        np.testing.assert_array_equal(lpmm.lpmm_ablation_table(code, signed), oracle.ablation_table(name, signed))
+    out = (ctypes.c_float * 16)()
+    L = lpmm.lib()
+    for code, signed in ((1, 1), (2, 1), (3, 0), (-1, 0)):
+        assert L.lpmm_ablation_table(code, signed, ctypes.addressof(out)) == -1
+    assert L.lpmm_ablation_table(0, 0, None) == -1
