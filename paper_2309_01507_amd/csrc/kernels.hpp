@@ -844,12 +844,16 @@ struct Row2 {                      // everything pass 2 reads for one row of one
     float r_old, r_new;            // the same value in every lane
 };
 
+// row_elems = il * cols, wave-uniform (scalar arithmetic); lane_g / lane_q: the lane's byte offsets inside a row
+// of the gradient / of the codes, fixed for the tile: two vector adds per row for the addresses
 template <bool BF16>
-__device__ __forceinline__ Row2<BF16> load_row2(const TileBase& b, const Tensor4& a, uint32_t col0, int il) {
+__device__ __forceinline__ Row2<BF16> load_row2(const TileBase& b, uint32_t row_elems, uint32_t lane_g, uint32_t lane_q,
+                                                int il) {
     Row2<BF16> r;
-    const uint32_t off4 = row_offset(il, a.cols, col0) * 4u;
-    r.g = load_grad_regs4<BF16, kPolicyNt>(b.rg, off4);    // last use of the gradient in this step
-    r.vq = buf_ld_u16(b.rvq, off4 >> 3);
+    const uint32_t off_g = row_elems * (BF16 ? 2u : 4u) + lane_g;
+    if constexpr (BF16) r.g.w = buf_ld_u2<kPolicyNt>(b.rg, off_g);      // last use of the gradient in this step
+    else r.g.a = buf_ld_f4<kPolicyNt>(b.rg, off_g);
+    r.vq = buf_ld_u16(b.rvq, (row_elems >> 1) + lane_q);
     r.r_old = buf_ld_f(b.rr, uint32_t(il) * 4u);
     r.r_new = buf_ld_f(b.rr_new, uint32_t(il) * 4u);
     return r;
@@ -859,17 +863,20 @@ __device__ __forceinline__ float wave_uniform(float v) {
     return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(v)));
 }
 
-// new codes of the lane's 4 elements of one row
+// New codes of the lane's 4 elements of one row.  The usual route multiplies by approximate reciprocals and keeps
+// track of how close it came to a decision boundary; if the row's scales are extreme, or some lane came too close,
+// the whole wave computes the row again from its inputs with exact arithmetic (same bits where both apply).  The
+// second route shares no value with the first, so that nothing has to be kept in registers for it.
 template <bool BF16>
 __device__ __forceinline__ uint32_t pass2_row(const Tensor4& a, const Hyper& h, uint32_t col0,
                                               const Row2<BF16>& row, const float cold16[4],
                                               const float inv_cnew[4], bool cols_tame) {
     const float r_old = wave_uniform(row.r_old), r_new = wave_uniform(row.r_new);
-    float g[4], vt[4];
+    float g[4];
     unpack_grad4<BF16>(row.g, g);
     // cols_tame is wave-uniform: the whole wave takes one route
     if (__builtin_expect(cols_tame && scale_is_tame(r_old) && scale_is_tame(r_new), 1)) {
-        float qf[4];
+        float qf[4], vt[4];
         codes_to_float4(row.vq, qf);
         const float r16 = r_old * 0.0625f;
 #pragma unroll
@@ -885,18 +892,16 @@ __device__ __forceinline__ uint32_t pass2_row(const Tensor4& a, const Hyper& h, 
         LPMM_V2(0) LPMM_V2(1)
 #undef LPMM_V2
         if (__builtin_expect(__ballot(closest < kMarginV) == 0, 1)) return lo | (hi << 4);
-    } else {
-        float cold[4];
-        load4(a.c + col0, cold);
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-            vt[e] = moment_v(h, dequant_v((uint32_t(row.vq) >> (4 * e)) & 15u, fminf(r_old, cold[e])), g[e]);
     }
-    float cnew[4];
+    float cold[4], cnew[4];
+    load4(a.c + col0, cold);
     load4(a.c_new + col0, cnew);
     uint32_t out = 0;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) out |= quant_v_code(vt[e], fminf(r_new, cnew[e])) << (4 * e);
+    for (int e = 0; e < 4; ++e) {
+        const float vt = moment_v(h, dequant_v((uint32_t(row.vq) >> (4 * e)) & 15u, fminf(r_old, cold[e])), g[e]);
+        out |= quant_v_code(vt, fminf(r_new, cnew[e])) << (4 * e);
+    }
     return out;
 }
 
@@ -925,28 +930,39 @@ __device__ __forceinline__ void pass2_fast_tile(const Tensor4& a, const Hyper& h
     const bool cols_tame = __ballot(!lane_tame) == 0;
     // the loads of two rows are in flight while a third is computed (three register sets take
     // turns, the loop is unrolled by three); rows past the tile read as zeros and are never used
-    const uint32_t row_bytes = uint32_t(a.cols) >> 1;               // bytes of codes per row
+    const uint32_t cols = uint32_t(a.cols);
+    const uint32_t lane_g = col0 * (BF16 ? 2u : 4u), lane_q = col0 >> 1;
+    auto fetch = [&](int il) { return load_row2<BF16>(tb, uint32_t(il) * cols, lane_g, lane_q, il); };   // il * cols < 2^29 + a few rows
     auto put = [&](int il, uint32_t codes) {
-        st<uint16_t>(tb.vq, __umul24(uint32_t(il), row_bytes) + (col0 >> 1), uint16_t(codes));
+        st<uint16_t>(tb.vq, ((uint32_t(il) * cols) >> 1) + lane_q, uint16_t(codes));
     };
     // rows of this wave in the order it takes them, as in pass 1: the four waves are 2^rs2 rows apart
     const int rs = a.rs2;
     const int row_w = wave << rs, hop = kWaves << rs, low = (1 << rs) - 1;
     auto row = [&](int k) { return row_w + (k & low) + (k >> rs) * hop; };
     int k = 0;
-    Row2<BF16> r0 = load_row2<BF16>(tb, a, col0, row(0));
-    Row2<BF16> r1 = load_row2<BF16>(tb, a, col0, row(1));
-    Row2<BF16> r2;
+    Row2<BF16> r0 = fetch(row(0));
+    Row2<BF16> r1 = fetch(row(1));
+    Row2<BF16> r2 = fetch(row(2));
     __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);     // loop start-up state: nothing outstanding (see pass 1)
-    while (row(k + 2) < n) {             // rounds of three rows, no exit in the middle (see pass 1)
-        r2 = load_row2<BF16>(tb, a, col0, row(k + 2));
+    // Rounds of three rows, no exit in the middle (see pass 1).  A register set is reloaded right after the row it
+    // held has been processed, two rows ahead of its next use; the loads are pinned there, after the last use of
+    // the values they replace.
+    if (row(k + 2) < n) do {
         put(row(k), pass2_row<BF16>(a, h, col0, r0, cold16, inv_cnew, cols_tame));
-        r0 = load_row2<BF16>(tb, a, col0, row(k + 3));
+        __builtin_amdgcn_sched_barrier(0);
+        r0 = fetch(row(k + 3));
+        __builtin_amdgcn_sched_barrier(0);
         put(row(k + 1), pass2_row<BF16>(a, h, col0, r1, cold16, inv_cnew, cols_tame));
-        r1 = load_row2<BF16>(tb, a, col0, row(k + 4));
+        __builtin_amdgcn_sched_barrier(0);
+        r1 = fetch(row(k + 4));
+        __builtin_amdgcn_sched_barrier(0);
         put(row(k + 2), pass2_row<BF16>(a, h, col0, r2, cold16, inv_cnew, cols_tame));
+        __builtin_amdgcn_sched_barrier(0);
+        r2 = fetch(row(k + 5));
+        __builtin_amdgcn_sched_barrier(0);
         k += 3;
-    }
+    } while (row(k + 2) < n);
     if (row(k) < n) {
         put(row(k), pass2_row<BF16>(a, h, col0, r0, cold16, inv_cnew, cols_tame));
         if (row(k + 1) < n) put(row(k + 1), pass2_row<BF16>(a, h, col0, r1, cold16, inv_cnew, cols_tame));
