@@ -1227,9 +1227,13 @@ int lpmm_adamw4_plan_build_nd(const lpmm_tensor_desc* descs, int64_t n, const in
     // mixes many cheap tiles with a few four times more expensive flat ones loses 20 % to imbalance between the
     // XCDs.  So: only in plans with several groups whose rank-1 parameters are at least 90 % in large tensors.
     constexpr int64_t kFlatMinElems = int64_t(1) << 23;
+    // parameters per group of consecutive tensors: large groups win (fewer kernel tails); cutting a set that fits
+    // one group into three so that its pass 2 has a pass 1 to run beside gave -3 % on the 108 M set, nothing on
+    // the 354 M set and +1.4 % on its factorized form, so it is not done
+    const int64_t group_params = int64_t(env_int("LPMM_PHASE_MPARAMS", 2048)) << 20;
     bool plan_flat = false;
     {
-        const int64_t gp = int64_t(env_int("LPMM_PHASE_MPARAMS", 2048)) << 20;
+        const int64_t gp = group_params;
         int64_t p_rank1 = 0, p_big = 0, acc = 0, in_group = 0, n_groups = 0;
         for (int64_t i = 0; i < n; ++i) {
             const int64_t P = descs[i].rows * descs[i].cols;
@@ -1244,6 +1248,25 @@ int lpmm_adamw4_plan_build_nd(const lpmm_tensor_desc* descs, int64_t n, const in
         }
         plan_flat = n_groups > 1 && p_rank1 > 0 && p_big * 10 >= p_rank1 * 9;
     }
+    // Tiling of one quantized tensor of the plan.  shrink = 0 gives the plan's default tiles (sized for sets that
+    // fill the chip many times over); each further level halves the rows (blocks) a workgroup takes, for groups of
+    // tensors that are too small to give every CU a couple of workgroups (see below).
+    const int gbytes = grad_dtype == LPMM_GRAD_BF16 ? 2 : 4;
+    auto set_geometry = [&](Tensor4& t, const lpmm_tensor_desc& d, int shrink) {
+        const int64_t rw_s = std::max<int64_t>((rw_hint < 0 ? 64 : rw_hint) >> shrink, 8);
+        const int64_t rw2_s = std::max<int64_t>(rw2_hint >> shrink, 4);
+        const int64_t rounds_s = std::max<int64_t>(int64_t(env_int("LPMM_MULTI_B128_ROUNDS", 8)) >> shrink, 1);
+        if (d.kind == LPMM_KIND_SGDM_4BIT) {
+            b128_geometry(&t, ctx->n_cu, rounds_s);
+            t.kind = kSgdmBlock;
+        } else if (d.kind == LPMM_KIND_4BIT_B128) {
+            b128_geometry(&t, ctx->n_cu, rounds_s);
+        } else if (d.kind == LPMM_KIND_4BIT_FACTOR) {
+            factor_geometry(&t, ctx->n_cu, shrink ? rw_s : rw_hint, rw2_s, gbytes, fast_eligible(d.cols, d.v_colmax), 1);
+        } else if (t.kind == kQuantFast) {
+            fast_geometry(&t, ctx->n_cu, shrink ? rw_s : rw_hint, rw2_s, gbytes, plan_flat && t.P >= kFlatMinElems);
+        }
+    };
     int64_t fofs = 0;
     for (int64_t i = 0; i < n; ++i) {
         const lpmm_tensor_desc& d = descs[i];
@@ -1271,8 +1294,7 @@ int lpmm_adamw4_plan_build_nd(const lpmm_tensor_desc* descs, int64_t n, const in
                 return LPMM_EINVAL;
             t.vq = nullptr;
             t.ms = d.m_blockscale;
-            b128_geometry(&t, ctx->n_cu, env_int("LPMM_MULTI_B128_ROUNDS", 8));
-            t.kind = kSgdmBlock;
+            set_geometry(t, d, 0);
             host->sgdm = true;
         } else if (d.kind == LPMM_KIND_4BIT_FACTOR) {
             if (!d.m_blockscale || !d.v_rowmax || !d.v_colmax) return LPMM_EINVAL;
@@ -1288,8 +1310,7 @@ int lpmm_adamw4_plan_build_nd(const lpmm_tensor_desc* descs, int64_t n, const in
             t.c_new = d_floats + fofs;
             fofs += round_up(d.cols, 64);
             t.counter = d_counters + i * kCounterWords;
-            factor_geometry(&t, ctx->n_cu, rw_hint, rw2_hint, grad_dtype == LPMM_GRAD_BF16 ? 2 : 4,
-                            fast_eligible(d.cols, d.v_colmax), 1);
+            set_geometry(t, d, 0);
             host->factor = true;
         } else if (d.kind == LPMM_KIND_FP32) {
             if (!aligned(d.param, 4) || !aligned(d.m_state, 4) || !aligned(d.v_state, 4) || !aligned(d.grad, galign))
@@ -1304,7 +1325,7 @@ int lpmm_adamw4_plan_build_nd(const lpmm_tensor_desc* descs, int64_t n, const in
             t.ms = d.m_blockscale;
             t.r = d.v_rowmax;                      // block scales of the second moment
             t.kind = kQuantBlockV;
-            b128_geometry(&t, ctx->n_cu, env_int("LPMM_MULTI_B128_ROUNDS", 8));
+            set_geometry(t, d, 0);
         } else {
             if (!d.m_blockscale || !d.v_rowmax || !d.v_colmax) return LPMM_EINVAL;
             if (!aligned(d.param, 16) || !aligned(d.grad, 16) || !aligned(d.m_state, 4) || !aligned(d.v_state, 4) ||
@@ -1331,8 +1352,7 @@ int lpmm_adamw4_plan_build_nd(const lpmm_tensor_desc* descs, int64_t n, const in
             t.counter = d_counters + i * kCounterWords;
             if (fast_eligible(d.cols, d.v_colmax)) {
                 t.kind = kQuantFast;
-                fast_geometry(&t, ctx->n_cu, rw_hint, rw2_hint, grad_dtype == LPMM_GRAD_BF16 ? 2 : 4,
-                              plan_flat && t.P >= kFlatMinElems);
+                set_geometry(t, d, 0);
                 if (t.flat) host->flat = true;
             } else {
                 t.kind = kQuantGeneral;
@@ -1344,13 +1364,29 @@ int lpmm_adamw4_plan_build_nd(const lpmm_tensor_desc* descs, int64_t n, const in
     }
 
     // groups of consecutive tensors; phase j = A work of group j + B work of group j-1
-    const int64_t group_params = int64_t(env_int("LPMM_PHASE_MPARAMS", 2048)) << 20;
     std::vector<std::pair<int64_t, int64_t>> groups;      // [first, last)
     for (int64_t i = 0; i < n;) {
         int64_t j = i, acc = 0;
         while (j < n && j - i < kMaxSeg && (j == i || acc + tens[j].P <= group_params)) acc += tens[j++].P;
         groups.emplace_back(i, j);
         i = j;
+    }
+    // A group whose tensors are small would put few, long workgroups on the chip (one 1024 x 1024 matrix: 128 for
+    // its first pass, 32 for its second, on 256 CUs): halve its tiles until each of its launches has two
+    // workgroups per CU (measured on that matrix: 23.5 -> 13.8 us per step).
+    for (const auto& gr : groups) {
+        for (int shrink = 1; shrink <= 3; ++shrink) {
+            int64_t n_a = 0, n_b = 0;
+            bool two_pass = false;
+            for (int64_t i = gr.first; i < gr.second; ++i) {
+                n_a += tens[i].n_wg;
+                const bool has_b = tens[i].kind == kQuantFast || tens[i].kind == kQuantGeneral ||
+                                   tens[i].kind == kFactorFast || tens[i].kind == kFactorGeneral;
+                if (has_b) { n_b += tens[i].n_wg2; two_pass = true; }
+            }
+            if (n_a >= 2 * int64_t(ctx->n_cu) && (!two_pass || n_b >= 2 * int64_t(ctx->n_cu))) break;
+            for (int64_t i = gr.first; i < gr.second; ++i) set_geometry(tens[i], descs[i], shrink);
+        }
     }
     for (size_t j = 0; j <= groups.size(); ++j) {
         PhaseLaunch pl{};
