@@ -20,7 +20,11 @@
  *   - All data pointers are DEVICE pointers unless the comment says "host".  The caller owns every
  *     buffer; the library allocates no device memory and never frees anything.
  *   - `shape` is a HOST pointer to {rows, cols}; tensors are row-major, P = rows*cols elements.
- *     A 1-D tensor is passed as {1, P}.
+ *     Calls that take a flat tensor (numel) accept any shape.  A 1-dimensional tensor belongs to
+ *     lpmm_adamw4_b128_step, not to the rank-1 step: Sec. 4.2 replaces rank-1 normalization by B128 there.
+ *     (The rank-1 calls accept rows == 1 or cols == 1 and then do what Sec. 4.2's formula says literally --
+ *     every element is its own column maximum, all codes are 15 and v_colmax is a plain fp32 copy of the
+ *     second moment -- which is correct but compresses nothing.)
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue work
  *     and return; they never synchronize.  Work of one call is ordered on `stream`.
  *   - Return value: LPMM_OK or a negative error code; nothing is printed, nothing aborts.
@@ -412,7 +416,12 @@ int lpmm_adamw4_step_multi_capturable(void* plan, const float* lr, const int64_t
                                       float eps, float weight_decay, void* stream);
 int lpmm_sgdm4_step_multi_capturable(void* plan, const float* lr, float momentum, void* stream);
 
-/* Forgets the host-side record of a plan (the device memory stays the caller's). */
+/* Forgets the host-side record of a plan (the device memory stays the caller's): lpmm_adamw4_plan_build keeps,
+ * per plan, a host copy of the launch tables and, for plans with more than one tensor group, up to two HIP streams
+ * (default priority, non-blocking) and a handful of events for the ordering between the two passes; they are
+ * created by plan_build and destroyed here (or when the last step that is still enqueueing on another host thread
+ * returns).  No device memory is allocated or freed by either call.  Work already enqueued is not waited for:
+ * synchronize first if the plan's device memory is going to be reused. */
 int lpmm_adamw4_plan_release(void* plan);
 
 /* Per-kernel timing for benchmarks, with HIP events recorded on each call's own stream.
@@ -425,7 +434,7 @@ int lpmm_adamw4_plan_release(void* plan);
  * *n_calls = recorded calls.  Multi-tensor steps: ms[0] = summed duration of the recorded launches
  * that carry pass 1 (their pass-2 companions run beside them on the plan's second stream), ms[1]
  * = 0, *n_calls = recorded launches.  (Do not mix the two kinds between one begin and end.)
- * ms, n_calls: host.  Not thread-safe. */
+ * ms, n_calls: host.  Not thread-safe: begin, end and every step between them must come from one host thread. */
 int lpmm_profile_begin(int64_t max_calls);
 int lpmm_profile_end(double ms[2], int64_t* n_calls);
 

@@ -612,7 +612,9 @@ struct PlanHost {
     }
 };
 
-std::unordered_map<void*, std::unique_ptr<PlanHost>> g_plans;
+// shared ownership: a step copies the pointer out under the lock and keeps the plan's host record (streams, events)
+// alive until it has enqueued its work, even if another thread releases the plan meanwhile
+std::unordered_map<void*, std::shared_ptr<PlanHost>> g_plans;
 
 struct PlanLayout {
     size_t off_tensors, off_dims, off_hyper, off_counters, off_floats, total;
@@ -1205,7 +1207,7 @@ int lpmm_adamw4_plan_build_nd(const lpmm_tensor_desc* descs, int64_t n, const in
     int dev = 0;
     LPMM_HIP(hipGetDevice(&dev));
 
-    auto host = std::make_unique<PlanHost>();
+    auto host = std::make_shared<PlanHost>();
     host->bf16 = grad_dtype == LPMM_GRAD_BF16;
     host->device = dev;
     host->staging.assign(L.off_counters, 0);
@@ -1472,12 +1474,12 @@ int adamw4_step_multi_impl(void* plan, float lr, const float* lr_dev, float beta
     const int rc = make_hyper(capturable ? 0.0f : lr, beta1, beta2, eps, weight_decay, capturable ? 1 : step, &h.h);
     if (rc) return rc;
     if (capturable && !step_dev) return LPMM_EINVAL;
-    const PlanHost* host = nullptr;
+    std::shared_ptr<const PlanHost> host;
     {
         std::lock_guard<std::mutex> lock(g_mu);
         auto it = g_plans.find(plan);
         if (it == g_plans.end()) return LPMM_EINVAL;
-        host = it->second.get();
+        host = it->second;
     }
     int dev = 0;
     LPMM_HIP(hipGetDevice(&dev));
@@ -1583,12 +1585,12 @@ int sgdm4_step_multi_impl(void* plan, float lr, const float* lr_dev, float momen
     HyperArg h{};
     const int rc = make_sgdm_hyper(lr_dev ? 0.0f : lr, momentum, &h.h);
     if (rc) return rc;
-    const PlanHost* host = nullptr;
+    std::shared_ptr<const PlanHost> host;
     {
         std::lock_guard<std::mutex> lock(g_mu);
         auto it = g_plans.find(plan);
         if (it == g_plans.end()) return LPMM_EINVAL;
-        host = it->second.get();
+        host = it->second;
     }
     int dev = 0;
     LPMM_HIP(hipGetDevice(&dev));

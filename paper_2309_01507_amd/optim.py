@@ -94,9 +94,11 @@ class _PlanOptimizer:
     def state_dict(self):
         """Step count and a copy of every state buffer (the buffers ARE the whole optimizer state).  States exist
         after the first step."""
+        # a capturable optimizer counts its steps on the device (graph replays do not run step())
+        t = int(self.step_dev.item()) if getattr(self, "capturable", False) else self.t
         if self._states is None:
-            return {"t": self.t, "states": None}
-        return {"t": self.t, "states": [{k: v.clone() for k, v in self._tensors_of(st).items()} for st in self._states]}
+            return {"t": t, "states": None}
+        return {"t": t, "states": [{k: v.clone() for k, v in self._tensors_of(st).items()} for st in self._states]}
 
     def load_state_dict(self, sd):
         """Into an optimizer over the same parameters (same shapes, same second-moment kind); the buffers keep

@@ -179,6 +179,23 @@ def test_capturable_optimizer_step_in_a_graph():
         for pa, pb in zip(a.parameters(), b.parameters()):
             torch.testing.assert_close(pa, pb, rtol=1e-6, atol=1e-9)
             pa.data.copy_(pb.data)
+    # the replays advanced the step count on the device only: a checkpoint must carry that count
+    assert oa.state_dict()["t"] == ob.state_dict()["t"] == 4
+    c = _model(7)
+    c.load_state_dict({k: v.clone() for k, v in a.state_dict().items()})
+    oc = lpmm.AdamW4bit(c.parameters(), lr=1e-3, weight_decay=0.05, capturable=True)
+    oc.load_state_dict(oa.state_dict())
+    oc.set_lr(2e-4)
+    ob.set_lr(2e-4)
+    for m, o in ((c, oc), (b, ob)):                      # step 5 in both: same bias corrections, same result
+        for p in m.parameters():
+            p.grad = None
+        _loss(m, 4).backward()
+        o.step()
+    torch.cuda.synchronize()
+    assert int(oc.step_dev.item()) == 5
+    for pc, pb in zip(c.parameters(), b.parameters()):
+        torch.testing.assert_close(pc, pb, rtol=1e-6, atol=1e-9)
 
 
 def test_state_dict_round_trip_resumes_bit_for_bit():
