@@ -54,7 +54,7 @@ class Workload:
     pass
 
 
-def build_workload(config, second_moment, optimizer, grad_dtype, launch, seed):
+def build_workload(config, second_moment, optimizer, grad_dtype, launch, seed, deterministic=False):
     import torch
     import paper_2309_01507_amd as lpmm
     import workloads
@@ -128,7 +128,8 @@ def build_workload(config, second_moment, optimizer, grad_dtype, launch, seed):
             if sgdm:
                 descs = [lpmm.make_desc_sgdm(p, gs[k], st, sp.numel) for kind, sp, p, gs, st in tensors]
             else:
-                descs = [lpmm.make_desc(p, gs[k], st, sp.rows, sp.cols) for kind, sp, p, gs, st in tensors]
+                det = lambda sp: deterministic and factor and sp.quantized and sp.cols % 128 == 0
+                descs = [lpmm.make_desc(p, gs[k], st, sp.rows, sp.cols, deterministic=det(sp)) for kind, sp, p, gs, st in tensors]
             plans.append(lpmm.new_plan(descs, 1 if bf16 else 0, dev))
 
     def one_step(t):
@@ -235,6 +236,8 @@ def main():
     ap.add_argument("--optimizer", choices=["adamw", "sgdm"], default="adamw",
                     help="adamw: the 4-bit AdamW step (the headline metric); sgdm: SGD with momentum and 4-bit "
                          "momentum (App. E Alg. 2), every tensor flat, one pass")
+    ap.add_argument("--deterministic", action="store_true",
+                    help="with --second-moment factor: row / column sums in a fixed order instead of float atomics")
     ap.add_argument("--launch", choices=["multi", "per-tensor"], default="multi",
                     help="multi: one plan, pass 1 / pass 2 of neighbouring tensor groups share launches; "
                          "per-tensor: two launches per quantized tensor")
@@ -252,7 +255,8 @@ def main():
     lpmm.lib()                                   # fail loudly if lpmm4.so is missing
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    wl = build_workload(args.config, args.second_moment, args.optimizer, args.grad_dtype, args.launch, args.seed)
+    wl = build_workload(args.config, args.second_moment, args.optimizer, args.grad_dtype, args.launch, args.seed,
+                        args.deterministic)
     specs, tensors, plans, one_step = wl.specs, wl.tensors, wl.plans, wl.one_step
     bf16, recipe, sgdm, b128, factor = wl.bf16, wl.recipe, wl.sgdm, wl.b128, wl.factor
     n_params, n_quant = wl.n_params, wl.n_quant

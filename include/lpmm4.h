@@ -182,7 +182,8 @@ int lpmm_adamw4_b128_step_bf16g(void* param, const void* grad, uint8_t* m_codes,
  *   v_row  float[rows]      R            v_col  float[cols]      C          zero state: all 0
  * (1-dimensional second moments are quantized instead: lpmm_adamw4_b128_step.)  Two kernels are
  * enqueued: one reads the gradient and accumulates the sums (fp32 atomics: R, C and the parameters
- * may differ in their last bits from run to run; the first moment does not), one updates.  Needs
+ * may differ in their last bits from run to run; the first moment does not; in a plan, LPMM_FLAG_DETERMINISTIC
+ * selects sums in a fixed order instead), one updates.  Needs
  * lpmm_adamw4_init on the current device with rows + cols within the workspace.  param, grad 16-byte
  * aligned, the rest 4-byte. */
 
@@ -355,6 +356,13 @@ int lpmm_dequant_ablation(int norm, int map, int is_signed, const uint8_t* codes
 #define LPMM_FLAG_NO_DECAY 1    /* this tensor takes no weight decay (biases and normalization weights are commonly
                                    excluded); lpmm_adamw4_step_multi then uses weight_decay = 0 for it */
 
+#define LPMM_FLAG_DETERMINISTIC 2  /* LPMM_KIND_4BIT_FACTOR tensors with cols % 128 == 0 only: the row and column sums of
+                                   g^2 (Sec. 4.3) are not accumulated with float atomics, whose order varies from run to
+                                   run, but written per tile and added in a fixed order by two small extra kernels per
+                                   tensor group: R, C and the parameters are then reproducible bit for bit.  Costs plan
+                                   memory (about 0.05 bytes per parameter for the partial sums); other tensors with this
+                                   flag make lpmm_adamw4_plan_build return LPMM_EINVAL */
+
 #define LPMM_KIND_4BIT_ND 6     /* quantized states of a tensor with more than two dimensions, as in lpmm_adamw4_nd_step:
                                    rows = d_1, cols = d_2 * ... * d_p, v_rowmax points at v_row, v_colmax at v_col
                                    (cols + d_2 + ... + d_p floats); the sizes d_2 .. d_p come from the side tables of
@@ -371,12 +379,12 @@ typedef struct lpmm_tensor_desc {
     float* v_colmax;        /* 4BIT only */
     int64_t rows, cols;
     int32_t kind;           /* LPMM_KIND_* */
-    int32_t flags;          /* LPMM_FLAG_* bits, 0 for none */
+    int32_t flags;          /* LPMM_FLAG_* bits, 0 for none (plan_bytes reads them too) */
 } lpmm_tensor_desc;
 
 /* Bytes of device memory a plan for these tensors needs (descriptor tables, per-tensor row/column
  * maxima of the updated second moment, ticket counters).  descs: host array of n entries; only
- * rows, cols and kind are read.  Returns 0 for invalid input. */
+ * rows, cols, kind and flags are read.  Returns 0 for invalid input. */
 size_t lpmm_adamw4_plan_bytes(const lpmm_tensor_desc* descs, int64_t n);
 
 /* Builds the plan into `plan` (device memory, 256-byte aligned, plan_bytes long, owned by the caller

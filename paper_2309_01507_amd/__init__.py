@@ -19,6 +19,6 @@ from .binding import (  # noqa: F401
     lpmm_adamw4_nd_step_bf16g,
     StateSgdm, new_state_sgdm, lpmm_sgdm4_state_sizes, lpmm_sgdm4_state_zero, lpmm_sgdm4_step, lpmm_sgdm4_step_bf16g,
     lpmm_sgdm32_step, lpmm_sgdm4_step_multi, make_desc_sgdm, lpmm_adamw4_step_multi_capturable,
-    lpmm_sgdm4_step_multi_capturable, KIND_SGDM_4BIT, KIND_SGDM_FP32, FLAG_NO_DECAY, KIND_4BIT_ND,
+    lpmm_sgdm4_step_multi_capturable, KIND_SGDM_4BIT, KIND_SGDM_FP32, FLAG_NO_DECAY, FLAG_DETERMINISTIC, KIND_4BIT_ND,
 )
 from .optim import AdamW4bit, SGDM4bit  # noqa: F401,E402

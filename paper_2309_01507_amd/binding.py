@@ -562,6 +562,7 @@ def lpmm_dequant_ablation(norm, map_, is_signed, codes, scale_a, scale_b, rows, 
 
 KIND_4BIT, KIND_FP32, KIND_4BIT_B128, KIND_4BIT_FACTOR, KIND_SGDM_4BIT, KIND_SGDM_FP32, KIND_4BIT_ND = 0, 1, 2, 3, 4, 5, 6
 FLAG_NO_DECAY = 1
+FLAG_DETERMINISTIC = 2
 
 
 class TensorDesc(ctypes.Structure):
@@ -571,11 +572,13 @@ class TensorDesc(ctypes.Structure):
                 ("kind", ctypes.c_int32), ("flags", ctypes.c_int32)]
 
 
-def make_desc(param, grad, state, rows=None, cols=None, no_decay=False) -> TensorDesc:
+def make_desc(param, grad, state, rows=None, cols=None, no_decay=False, deterministic=False) -> TensorDesc:
     """state: a State4 (4-bit, rank-1 second moment), a StateB128 (4-bit, block-wise second moment), a StateFactor
     (factorized second moment) or a (m, v) pair of fp32 tensors (then rows, cols must be given).
     no_decay: the plan's weight decay does not apply to this tensor."""
     flags = FLAG_NO_DECAY if no_decay else 0
+    if deterministic:
+        flags |= FLAG_DETERMINISTIC          # factorized tensors only: sums in a fixed order
     if isinstance(state, StateFactor):
         return TensorDesc(_ptr(param), _ptr(grad), _ptr(state.m_codes), _ptr(state.m_blockscale), None,
                           _ptr(state.v_row), _ptr(state.v_col), state.rows, state.cols, KIND_4BIT_FACTOR, flags)

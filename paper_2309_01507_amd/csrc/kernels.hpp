@@ -71,7 +71,9 @@ struct Tensor4 {
     int c_extra;            // floats behind c_new (and room behind c) that the publishing workgroup moves and clears
                             // along with the column maxima (tensors with more than two dimensions)
     int nd_index;           // plans: index into the plan's table of inner dimensions, -1 for matrices
-    int pad_;
+    int det;                // kFactorFast in a plan: the sums of g^2 are reduced in a fixed order (no float atomics);
+                            // vq then points at the partial sums: float[strips2][round_up(rows, 64)] per strip and row,
+                            // then float[tiles][round_up(cols, 64)] per row tile and column
 };
 
 // The tensor table of a plan lives in device memory.  A pointer read from memory is a generic
@@ -93,7 +95,7 @@ struct Tensor4Table {
     float LPMM_AS_GLOBAL* c_new;
     unsigned int LPMM_AS_GLOBAL* counter;
     int64_t rows, cols, P;
-    int nb, gx, gy, rw, strips, n_wg, kind, strips2, rw2, n_wg2, rs, rs2, tot_slots, flat, no_decay, c_extra, nd_index, pad_;
+    int nb, gx, gy, rw, strips, n_wg, kind, strips2, rw2, n_wg2, rs, rs2, tot_slots, flat, no_decay, c_extra, nd_index, det;
 };
 static_assert(sizeof(Tensor4Table) == sizeof(Tensor4), "the table twin must mirror Tensor4");
 __device__ __forceinline__ Tensor4 from_table(const Tensor4Table& t) {
@@ -111,7 +113,7 @@ __device__ __forceinline__ Tensor4 from_table(const Tensor4Table& t) {
     a.rows = t.rows; a.cols = t.cols; a.P = t.P;
     a.nb = t.nb; a.gx = t.gx; a.gy = t.gy; a.rw = t.rw; a.strips = t.strips; a.n_wg = t.n_wg; a.kind = t.kind;
     a.strips2 = t.strips2; a.rw2 = t.rw2; a.n_wg2 = t.n_wg2; a.rs = t.rs; a.rs2 = t.rs2;
-    a.tot_slots = t.tot_slots; a.flat = t.flat; a.no_decay = t.no_decay; a.c_extra = t.c_extra; a.nd_index = t.nd_index; a.pad_ = 0;
+    a.tot_slots = t.tot_slots; a.flat = t.flat; a.no_decay = t.no_decay; a.c_extra = t.c_extra; a.nd_index = t.nd_index; a.det = t.det;
     return a;
 }
 #else
@@ -1554,6 +1556,19 @@ __device__ __forceinline__ void factor_stats_tile(const Tensor4& a, int wg, Lds&
 #pragma unroll
     for (int e = 0; e < 4; ++e) s.col[wave * 256 + lane * 4 + e] = cacc[e];
     __syncthreads();
+    if (a.det) {
+        // fixed order of summation: this tile's sums go to slots of their own; factor_reduce_one adds the strips
+        // of a row and the tiles of a column in index order, factor_totals_one the rows
+        const int64_t rows_pad = (a.rows + 63) / 64 * 64, cols_pad = (a.cols + 63) / 64 * 64;
+        float* rowpart = reinterpret_cast<float*>(a.vq) + int64_t(strip) * rows_pad + row0;
+        float* colpart = reinterpret_cast<float*>(a.vq) + int64_t(a.strips2) * rows_pad + int64_t(tile) * cols_pad;
+        for (int t = threadIdx.x; t < n; t += kThreads) rowpart[t] = s.blk_scale[t];
+        const int t = threadIdx.x;
+        const float csum = (s.col[t] + s.col[256 + t]) + (s.col[512 + t] + s.col[768 + t]);
+        const int64_t col = int64_t(strip) * 256 + t;
+        if (col < a.cols) colpart[col] = csum;
+        return;
+    }
     for (int t = threadIdx.x; t < n; t += kThreads) atomic_add_f32(a.r_new + row0 + t, s.blk_scale[t]);
     {
         const int t = threadIdx.x;
@@ -1719,6 +1734,95 @@ __device__ __forceinline__ void factor_publish_if_last(const Tensor4& a, const H
     if (int(threadIdx.x) < a.tot_slots) {
         a.counter[tot_new_word(threadIdx.x)] = 0u;
         a.counter[tot_old_word(threadIdx.x)] = 0u;
+    }
+}
+
+// Deterministic sums (Tensor4::det): between the statistics pass and the update pass two small kernels turn the
+// per-tile partial sums into what the float atomics would have left in the workspace, in a fixed order.
+// Layout of the partial sums behind a.vq (rows_pad, cols_pad = rows, cols rounded up to 64):
+//   float[strips2][rows_pad]  a row's sum over the columns of one strip
+//   float[tiles][cols_pad]    a column's sum over the rows of one tile
+//   float[2 * row_wgs]        per 256 rows: the sum of their new row sums, and of their old row statistics
+__device__ __forceinline__ const float* det_rowpart(const Tensor4& a) { return reinterpret_cast<const float*>(a.vq); }
+__device__ __forceinline__ const float* det_colpart(const Tensor4& a) {
+    return det_rowpart(a) + int64_t(a.strips2) * ((a.rows + 63) / 64 * 64);
+}
+__device__ __forceinline__ float* det_totpart(const Tensor4& a) {
+    const int64_t tiles = (a.rows + a.rw2 - 1) / a.rw2;
+    return const_cast<float*>(det_colpart(a)) + tiles * ((a.cols + 63) / 64 * 64);
+}
+// sum over the workgroup, the same value in every thread, combined in a fixed order
+__device__ __forceinline__ float wg_sum_fixed(float v, float* s_part) {
+    v = wave_sum(v);
+    __syncthreads();                                   // s_part may still be read from a previous call
+    if ((threadIdx.x & 63) == 0) s_part[threadIdx.x >> 6] = v;
+    __syncthreads();
+    return (s_part[0] + s_part[1]) + (s_part[2] + s_part[3]);
+}
+
+// Workgroup `w` of a tensor's reduce step: 256 rows (w < ceil(rows / 256)) or 64 columns.
+__device__ __forceinline__ void factor_reduce_one(const Tensor4& a, int w, float* s_part) {
+    const int64_t rows_pad = (a.rows + 63) / 64 * 64, cols_pad = (a.cols + 63) / 64 * 64;
+    const int row_wgs = int((a.rows + kThreads - 1) / kThreads);
+    if (w < row_wgs) {                                 // uniform over the workgroup
+        const float* rowpart = det_rowpart(a);
+        const int64_t i = int64_t(w) * kThreads + threadIdx.x;
+        float acc = 0.0f, old = 0.0f;
+        if (i < a.rows) {
+            for (int s0 = 0; s0 < a.strips2; s0 += 8) {        // eight loads in flight, added in index order
+                float v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) v[u] = s0 + u < a.strips2 ? rowpart[int64_t(s0 + u) * rows_pad + i] : 0.0f;
+#pragma unroll
+                for (int u = 0; u < 8; ++u) acc += v[u];
+            }
+            a.r_new[i] = acc;
+            old = a.r[i];
+        }
+        const float t_new = wg_sum_fixed(acc, s_part), t_old = wg_sum_fixed(old, s_part);
+        if (threadIdx.x == 0) {
+            float* tp = det_totpart(a);
+            tp[2 * w] = t_new;
+            tp[2 * w + 1] = t_old;
+        }
+    } else {
+        // 64 columns per workgroup; a tall tensor has hundreds of row tiles, so four threads share a column: thread
+        // (q, c) adds tiles q, q + 4, ... in order, eight loads in flight, and the four sums are added in order of q
+        const float* colpart = det_colpart(a);
+        const int c = threadIdx.x & 63, q = threadIdx.x >> 6;
+        const int64_t j = int64_t(w - row_wgs) * 64 + c;
+        const int tiles = int((a.rows + a.rw2 - 1) / a.rw2);
+        float acc = 0.0f;
+        if (j < a.cols)
+            for (int t0 = q; t0 < tiles; t0 += 32) {
+                float v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) v[u] = t0 + 4 * u < tiles ? colpart[int64_t(t0 + 4 * u) * cols_pad + j] : 0.0f;
+#pragma unroll
+                for (int u = 0; u < 8; ++u) acc += v[u];
+            }
+        __shared__ float s_col[kThreads];
+        s_col[threadIdx.x] = acc;
+        __syncthreads();
+        if (q == 0 && j < a.cols) a.c_new[j] = (s_col[c] + s_col[64 + c]) + (s_col[128 + c] + s_col[192 + c]);
+    }
+}
+// One workgroup per tensor, after the reduce step: the two totals (sum of this step's row sums, sum of the old row
+// statistics) into slot 0, from the per-256-rows sums dealt to the threads in a fixed pattern.
+__device__ __forceinline__ void factor_totals_one(const Tensor4& a, float* s_part) {
+    const int row_wgs = int((a.rows + kThreads - 1) / kThreads);
+    const float* tp = det_totpart(a);
+    float t_new = 0.0f, t_old = 0.0f;
+    for (int k = threadIdx.x; k < row_wgs; k += kThreads) {
+        t_new += tp[2 * k];
+        t_old += tp[2 * k + 1];
+    }
+    t_new = wg_sum_fixed(t_new, s_part);
+    t_old = wg_sum_fixed(t_old, s_part);
+    if (threadIdx.x == 0) {
+        float* tot = reinterpret_cast<float*>(a.counter);
+        tot[tot_new_word(0)] = t_new;
+        tot[tot_old_word(0)] = t_old;
     }
 }
 
@@ -2210,6 +2314,27 @@ __global__ __launch_bounds__(kThreads) void nd_plan_expand(const NdPhase ph) {
     const Tensor4 a = from_table(ph.tensors[sg.tensor]);
     const InnerDims dm = ph.dims[a.nd_index];
     nd_expand_one(a.c_new + a.cols, a.c_new, a.cols, dm, int64_t(x - sg.wg_begin) * kThreads + threadIdx.x);
+}
+
+// The reduce and totals steps for all tensors with deterministic sums of one group of a plan.
+struct DetPhase {
+    const Tensor4Table* tensors;
+    int n_seg, n_r;                 // tensors; workgroups of the reduce kernel
+    Segment seg_r[kMaxSeg];         // per tensor: first workgroup of the reduce kernel
+};
+
+__global__ __launch_bounds__(kThreads) void factor_plan_reduce(const DetPhase ph) {
+    __shared__ float s_part[kThreads / 64];
+    const int x = blockIdx.x;
+    if (x >= ph.n_r) return;
+    const Segment sg = find_segment(ph.seg_r, ph.n_seg, x);
+    factor_reduce_one(from_table(ph.tensors[sg.tensor]), x - sg.wg_begin, s_part);
+}
+
+__global__ __launch_bounds__(kThreads) void factor_plan_totals(const DetPhase ph) {
+    __shared__ float s_part[kThreads / 64];
+    if (int(blockIdx.x) >= ph.n_seg) return;
+    factor_totals_one(from_table(ph.tensors[ph.seg_r[blockIdx.x].tensor]), s_part);
 }
 
 // The same for a plan whose 2-dimensional tensors keep a factorized second moment: "A" work is the

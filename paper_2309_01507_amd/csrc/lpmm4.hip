@@ -500,12 +500,28 @@ int nd_step_impl(bool bf16, void* param, const void* grad, uint8_t* m_codes, flo
 
 // Tiling of a tensor with a factorized second moment: the statistics pass is tiled like pass 2 and is the
 // step's first ("A") launch, the update pass is tiled like pass 1 and is the second ("B") one.
+// rows per tile of the statistics pass when its sums are reduced in a fixed order: fixed, because the size of the
+// partial-sum buffer (part of the plan's memory) follows from it
+constexpr int64_t kDetStatRows = 128;
+
+// floats of partial sums of a rows x cols tensor with deterministic sums
+int64_t det_partial_floats(int64_t rows, int64_t cols) {
+    const int64_t strips2 = (cols / LPMM_BLOCK + 1) / 2, tiles = (rows + kDetStatRows - 1) / kDetStatRows;
+    const int64_t row_wgs = (rows + kThreads - 1) / kThreads;
+    return strips2 * round_up(rows, 64) + tiles * round_up(cols, 64) + round_up(2 * row_wgs, 64);
+}
+
 void factor_geometry(Tensor4* a, int n_cu, int64_t rw_hint, int64_t rw2_hint, int grad_bytes, bool fast,
                      int tot_slots) {
     a->tot_slots = tot_slots;
     a->kind = fast ? kFactorFast : kFactorGeneral;
     if (fast) {
         fast_geometry(a, n_cu, rw_hint, rw2_hint, grad_bytes);
+        if (a->det) {
+            a->rw2 = int(std::min<int64_t>(kDetStatRows, a->rows));
+            a->n_wg2 = int(a->strips2 * ((a->rows + kDetStatRows - 1) / kDetStatRows));
+            a->rs2 = row_spacing_log2(a->cols * grad_bytes, a->rw2, kWaves, "LPMM_RS2");
+        }
         if (a->rw2 > kMaxRowSlots) {          // row sums of a statistics tile are staged in LDS
             a->rw2 = kMaxRowSlots;
             a->n_wg2 = int(a->strips2 * ((a->rows + a->rw2 - 1) / a->rw2));
@@ -584,6 +600,9 @@ struct PhaseLaunch {
     // tensors with more than two dimensions among the B tensors: two small kernels run before their pass 2
     NdPhase nd;
     bool has_nd;
+    // tensors with deterministic sums among the B tensors (factorized plans): two small kernels before their update pass
+    DetPhase det;
+    bool has_det;
 };
 
 struct PlanHost {
@@ -653,6 +672,8 @@ bool plan_layout(const lpmm_tensor_desc* descs, int64_t n, const int64_t* inner_
         if (!desc_shape_ok(descs[i])) return false;
         if (descs[i].kind == LPMM_KIND_4BIT || descs[i].kind == LPMM_KIND_4BIT_FACTOR)
             floats += round_up(descs[i].rows, 64) + round_up(descs[i].cols, 64);
+        if (descs[i].kind == LPMM_KIND_4BIT_FACTOR && (descs[i].flags & LPMM_FLAG_DETERMINISTIC))
+            floats += det_partial_floats(descs[i].rows, descs[i].cols);
         if (descs[i].kind == LPMM_KIND_4BIT_ND) {
             InnerDims dm;
             int64_t ext;
@@ -1275,7 +1296,9 @@ int lpmm_adamw4_plan_build_nd(const lpmm_tensor_desc* descs, int64_t n, const in
         const size_t galign = grad_dtype == LPMM_GRAD_F32 ? 4 : 2;
         Tensor4 t{};
         t.rows = d.rows; t.cols = d.cols; t.P = d.rows * d.cols;
-        if (d.flags & ~LPMM_FLAG_NO_DECAY) return LPMM_EINVAL;
+        if (d.flags & ~(LPMM_FLAG_NO_DECAY | LPMM_FLAG_DETERMINISTIC)) return LPMM_EINVAL;
+        if ((d.flags & LPMM_FLAG_DETERMINISTIC) &&
+            (d.kind != LPMM_KIND_4BIT_FACTOR || !fast_eligible(d.cols, d.v_colmax))) return LPMM_EINVAL;
         t.no_decay = (d.flags & LPMM_FLAG_NO_DECAY) ? 1 : 0;
         t.p = static_cast<float*>(d.param);
         t.g = d.grad;
@@ -1312,6 +1335,11 @@ int lpmm_adamw4_plan_build_nd(const lpmm_tensor_desc* descs, int64_t n, const in
             t.c_new = d_floats + fofs;
             fofs += round_up(d.cols, 64);
             t.counter = d_counters + i * kCounterWords;
+            if (d.flags & LPMM_FLAG_DETERMINISTIC) {
+                t.det = 1;
+                t.vq = reinterpret_cast<uint32_t*>(d_floats + fofs);      // the partial sums
+                fofs += det_partial_floats(d.rows, d.cols);
+            }
             set_geometry(t, d, 0);
             host->factor = true;
         } else if (d.kind == LPMM_KIND_FP32) {
@@ -1406,6 +1434,11 @@ int lpmm_adamw4_plan_build_nd(const lpmm_tensor_desc* descs, int64_t n, const in
                     continue;
                 pl.ph.seg_b[pl.ph.n_seg_b++] = Segment{pl.ph.n_b, int(i)};
                 pl.ph.n_b += tens[i].n_wg2;
+                if (tens[i].det) {
+                    pl.has_det = true;
+                    pl.det.seg_r[pl.det.n_seg++] = Segment{pl.det.n_r, int(i)};
+                    pl.det.n_r += int((tens[i].rows + kThreads - 1) / kThreads + (tens[i].cols + 63) / 64);
+                }
                 if (tens[i].nd_index >= 0 && (tens[i].kind == kQuantFast || tens[i].kind == kQuantGeneral)) {
                     pl.has_nd = true;
                     pl.nd.seg_r[pl.nd.n_seg] = Segment{pl.nd.n_r, int(i)};
@@ -1417,6 +1450,7 @@ int lpmm_adamw4_plan_build_nd(const lpmm_tensor_desc* descs, int64_t n, const in
             }
         pl.nd.tensors = pl.ph.tensors;
         pl.nd.dims = d_dims;
+        pl.det.tensors = pl.ph.tensors;
         if (pl.ph.n_a + pl.ph.n_b == 0) continue;
         if (int64_t(pl.ph.n_a) + pl.ph.n_b > (int64_t(1) << 30)) return LPMM_EINVAL;
         pl.grid = pad8(int64_t(pl.ph.n_a) + pl.ph.n_b);
@@ -1466,6 +1500,14 @@ int adamw4_step_multi_impl(void* plan, float lr, const float* lr_dev, float beta
         hipLaunchKernelGGL(nd_plan_reduce, dim3(pl.nd.n_r), dim3(kThreads), 0, on, pl.nd);
         LPMM_HIP(hipGetLastError());
         hipLaunchKernelGGL(nd_plan_expand, dim3(pl.nd.n_e), dim3(kThreads), 0, on, pl.nd);
+        LPMM_HIP(hipGetLastError());
+        return LPMM_OK;
+    };
+    // per-tile partial sums -> row / column sums and totals, for the group's tensors with deterministic sums
+    auto launch_det = [](const PhaseLaunch& pl, hipStream_t on) -> int {
+        hipLaunchKernelGGL(factor_plan_reduce, dim3(pl.det.n_r), dim3(kThreads), 0, on, pl.det);
+        LPMM_HIP(hipGetLastError());
+        hipLaunchKernelGGL(factor_plan_totals, dim3(pl.det.n_seg), dim3(kThreads), 0, on, pl.det);
         LPMM_HIP(hipGetLastError());
         return LPMM_OK;
     };
@@ -1531,6 +1573,7 @@ int adamw4_step_multi_impl(void* plan, float lr, const float* lr_dev, float beta
                 const int64_t call = g_prof.calls;
                 if (rec) LPMM_HIP(hipEventRecord(prof_event(call, 0), s2));
                 if (pl.has_nd) LPMM_CHECK(launch_nd(pl, s2));
+                if (pl.has_det) LPMM_CHECK(launch_det(pl, s2));
                 launch(2, pl.grid_b, s2, pl);
                 LPMM_HIP(hipGetLastError());
                 if (rec) {
@@ -1569,6 +1612,7 @@ int adamw4_step_multi_impl(void* plan, float lr, const float* lr_dev, float beta
         if (rec) LPMM_HIP(hipEventRecord(prof_event(call, 0), s));
         // a launch that holds only one kind of work takes that kind's (lighter) kernel
         if (pl.has_nd) LPMM_CHECK(launch_nd(pl, s));      // the A work of these tensors ran in the previous launch
+        if (pl.has_det) LPMM_CHECK(launch_det(pl, s));
         const int roles = pl.ph.n_b == 0 ? (pl.a_has_rank1 ? 1 : 3) : (pl.ph.n_a == 0 ? 2 : 0);
         launch(roles, pl.grid, s, pl);
         LPMM_HIP(hipGetLastError());

@@ -290,3 +290,70 @@ def test_plan_rejects_rank1_and_factorized_tensors_together():
     d2 = lpmm.make_desc(w, g, lpmm.new_state_factor(64, 128, DEV))
     assert lpmm.lpmm_adamw4_plan_bytes([d1, d2]) == 0
     assert lpmm.lpmm_adamw4_plan_bytes([d2]) > 0
+
+
+DET_STAT_RTOL = 2e-6      # fixed-order fp32 sums against fp64: about sqrt(levels) * 2^-24, observed below 1e-6
+
+
+@pytest.mark.parametrize("bf16", [False, True])
+def test_deterministic_sums_are_reproducible_and_match_the_oracle(bf16):
+    """LPMM_FLAG_DETERMINISTIC: the same plan step on the same inputs twice gives identical bits in R, C and the
+    parameters (float atomics do not), on all three launch routes, and stays within 2e-6 of the oracle's fp64
+    statistics over several free-running steps.  Shapes: several row tiles of 128 with a ragged last one, an odd
+    number of column blocks, a single row tile, 11008 columns."""
+    hp = oracle.Hyper()
+    shapes = [(300, 1024), (257, 384), (64, 128), (130, 11008), (1000, 4096)]
+    for streams, mparams in (("2", "1"), ("1", "1"), ("2", "2048")):
+        os.environ["LPMM_MULTI_STREAMS"], os.environ["LPMM_PHASE_MPARAMS"] = streams, mparams
+        try:
+            runs = []
+            for rep in range(2):
+                lpmm.ensure_init(4096)
+                keep, descs, refs = [], [], []
+                for tid, (rows, cols) in enumerate(shapes):
+                    w_ref = workloads.weights(61, tid, rows, cols).reshape(-1)
+                    w = to_dev(w_ref.copy())
+                    g = torch.empty(rows * cols, dtype=torch.bfloat16 if bf16 else torch.float32, device=DEV)
+                    st = lpmm.new_state_factor(rows, cols, DEV)
+                    descs.append(lpmm.make_desc(w, g, st, deterministic=True))
+                    keep.append((w, g, st))
+                    refs.append((w_ref, oracle.state_zero_factor(rows, cols)))
+                if rep == 0:
+                    refs0 = refs                     # the oracle runs once, beside the first repetition
+                plan = lpmm.new_plan(descs, 1 if bf16 else 0, DEV)
+                out = []
+                for t in range(1, 5):
+                    for tid, ((rows, cols), (w, g, st), (w_ref, st_ref)) in enumerate(zip(shapes, keep, refs)):
+                        gn = workloads.grads(61, tid, t, rows, cols, "col_lognormal", bf16).reshape(-1)
+                        g.copy_(to_dev(gn, bf16))
+                        if rep == 0:
+                            oracle.adamw4_factor_step(w_ref, gn, st_ref, hp, t)
+                    lpmm.lpmm_adamw4_step_multi(plan, hp.lr, hp.beta1, hp.beta2, hp.eps, hp.weight_decay, t)
+                    torch.cuda.synchronize()
+                    out.append([(w.clone(), st.v_row.clone(), st.v_col.clone(), st.m_codes.clone()) for w, g, st in keep])
+                lpmm.lpmm_adamw4_plan_release(plan)
+                runs.append(out)
+            for t, (a, b) in enumerate(zip(*runs), start=1):
+                for (shape, xa, xb) in zip(shapes, a, b):
+                    for name, ta, tb in zip(("parameters", "R", "C", "m codes"), xa, xb):
+                        assert torch.equal(ta, tb), f"{shape} step {t}: {name} differ between two identical runs"
+            # free-running against the oracle (the statistics' rounding compounds through beta2 only)
+            for (rows, cols), (w, R, C, mq), (w_ref, st_ref) in zip(shapes, runs[0][-1], refs0):
+                np.testing.assert_allclose(R.cpu().numpy(), st_ref.v_row, rtol=DET_STAT_RTOL, atol=0, err_msg=f"{rows}x{cols}: R")
+                np.testing.assert_allclose(C.cpu().numpy(), st_ref.v_col, rtol=DET_STAT_RTOL, atol=0, err_msg=f"{rows}x{cols}: C")
+                np.testing.assert_allclose(w.cpu().numpy(), w_ref, rtol=PARAM_RTOL, atol=PARAM_ATOL, err_msg=f"{rows}x{cols}: parameters")
+        finally:
+            os.environ.pop("LPMM_MULTI_STREAMS", None)
+            os.environ.pop("LPMM_PHASE_MPARAMS", None)
+
+
+def test_deterministic_flag_is_refused_where_it_does_not_apply():
+    lpmm.ensure_init(4096)
+    w = torch.zeros(64 * 100, device=DEV)
+    g = torch.zeros_like(w)
+    with pytest.raises(lpmm.LpmmError):          # general path (cols % 128 != 0)
+        lpmm.new_plan([lpmm.make_desc(w, g, lpmm.new_state_factor(64, 100, DEV), deterministic=True)], 0, DEV)
+    w = torch.zeros(64 * 128, device=DEV)
+    g = torch.zeros_like(w)
+    with pytest.raises(lpmm.LpmmError):          # rank-1 tensor
+        lpmm.new_plan([lpmm.make_desc(w, g, lpmm.new_state(64, 128, DEV), deterministic=True)], 0, DEV)
