@@ -119,6 +119,20 @@ int lpmm_adamw4_step_bf16g(void* param, const void* grad, uint8_t* m_codes, floa
                            const int64_t shape[2], float lr, float beta1, float beta2, float eps,
                            float weight_decay, int64_t step, void* stream);
 
+/* The step of lpmm_adamw4_step / _step_bf16g (Alg. 3, Sec. 4.2) with a workspace of the caller's in place of the
+ * one registered by lpmm_adamw4_init, so that steps on different tensors can run on different streams at the same
+ * time: give every stream (or every tensor) its own workspace.  workspace: device memory, 256-byte aligned, at
+ * least lpmm_adamw4_workspace_bytes(rows + cols) long, owned by the caller, zero-filled once before its first use
+ * (hipMemset, or any fill); every completed step leaves it zero-filled again, so it can be passed to the next step
+ * as it is.  Two calls that may overlap in time must not share a workspace.  lpmm_adamw4_init must have run on the
+ * current device (for the tables), with any workspace.  Other arguments, state layout, alignment and results as
+ * lpmm_adamw4_step; grad_dtype is LPMM_GRAD_F32 or LPMM_GRAD_BF16.  Errors: LPMM_EINVAL (null or misaligned
+ * workspace, fewer than 8 KiB + 1 KiB), LPMM_EWORKSPACE (too small for this shape); nothing is enqueued then. */
+int lpmm_adamw4_step_ws(void* param, const void* grad, int grad_dtype, uint8_t* m_codes, float* m_blockscale,
+                        uint8_t* v_codes, float* v_rowmax, float* v_colmax, const int64_t shape[2], float lr,
+                        float beta1, float beta2, float eps, float weight_decay, int64_t step, void* workspace,
+                        size_t workspace_bytes, void* stream);
+
 /* The step of lpmm_adamw4_step / _step_bf16g for callers that cannot allocate device memory and do not want to
  * size a workspace: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The
  * row / column maxima of the updated second moment and the completion counters live in a device array that

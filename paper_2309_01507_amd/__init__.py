@@ -6,7 +6,7 @@ from .binding import (  # noqa: F401
     LpmmError, State4, lib, lib_path, build_library, GRAD_F32, GRAD_BF16,
     lpmm_table, lpmm_host_nearest_codes, lpmm_adamw4_workspace_bytes, lpmm_adamw4_init,
     lpmm_adamw4_state_sizes, lpmm_adamw4_state_zero, lpmm_adamw4_step, lpmm_adamw4_step_bf16g,
-    lpmm_adamw4_step_noalloc, lpmm_ablation_table, lpmm_quant_ablation, lpmm_dequant_ablation,
+    lpmm_adamw4_step_noalloc, lpmm_adamw4_step_ws, lpmm_ablation_table, lpmm_quant_ablation, lpmm_dequant_ablation,
     ablation_scale_sizes, NORM_B128, NORM_B2048, NORM_RANK1, MAP_DE, MAP_DE0, MAP_LINEAR, ROUND_NEAREST, ROUND_STOCHASTIC,
     lpmm_adamw32_step, lpmm_dequant_state, lpmm_quant_state, ensure_init, new_state,
     lpmm_profile_begin, lpmm_profile_end, TensorDesc, make_desc, new_plan, KIND_4BIT, KIND_FP32,

@@ -72,6 +72,8 @@ def lib() -> ctypes.CDLL:
         L.lpmm_adamw4_step.argtypes = step_args
         L.lpmm_adamw4_step_bf16g.argtypes = step_args
         L.lpmm_adamw4_step_noalloc.argtypes = [_VP, _VP, ctypes.c_int] + [_VP] * 5 + [_VP] + [_F] * 5 + [_I64, _VP]
+        L.lpmm_adamw4_step_ws.argtypes = ([_VP, _VP, ctypes.c_int] + [_VP] * 5 + [_VP] + [_F] * 5 +
+                                          [_I64, _VP, ctypes.c_size_t, _VP])
         L.lpmm_adamw32_step.argtypes = [_VP] * 4 + [_I64, ctypes.c_int] + [_F] * 5 + [_I64, _VP]
         L.lpmm_adamw4_b128_state_sizes.argtypes = [_I64, _VP]
         L.lpmm_adamw4_b128_state_zero.argtypes = [_VP] * 4 + [_I64, _VP]
@@ -262,6 +264,19 @@ def lpmm_adamw4_step_noalloc(param, grad, grad_dtype: int, st: State4, lr, beta1
                                           _ptr(st.m_blockscale), _ptr(st.v_codes), _ptr(st.v_rowmax),
                                           _ptr(st.v_colmax), ctypes.addressof(shape), lr, beta1, beta2, eps,
                                           weight_decay, int(step), _stream(stream)), "lpmm_adamw4_step_noalloc")
+
+
+def lpmm_adamw4_step_ws(param, grad, grad_dtype: int, st: State4, lr, beta1, beta2, eps, weight_decay, step,
+                        workspace, stream=None):
+    """workspace: a zero-filled uint8 / float32 device tensor of at least lpmm_adamw4_workspace_bytes(rows + cols)
+    bytes that no other call in flight uses."""
+    shape = _shape(st.rows, st.cols)
+    _check(lib().lpmm_adamw4_step_ws(_ptr(param), _ptr(grad), int(grad_dtype), _ptr(st.m_codes),
+                                     _ptr(st.m_blockscale), _ptr(st.v_codes), _ptr(st.v_rowmax),
+                                     _ptr(st.v_colmax), ctypes.addressof(shape), lr, beta1, beta2, eps,
+                                     weight_decay, int(step), _ptr(workspace),
+                                     workspace.numel() * workspace.element_size(), _stream(stream)),
+           "lpmm_adamw4_step_ws")
 
 
 # ---- block-wise second moment (1-D / flattened tensors) ------------------------------------------------

@@ -265,11 +265,19 @@ int launch_step(const Tensor4& t, const Hyper& h, bool fast, hipStream_t s) {
 
 int fill(void* dst, int64_t n, uint8_t value, int64_t last_index, uint8_t last, hipStream_t s);
 
-// use_scratch: the maxima and counters live in the library's own device array instead of the workspace given
-// to lpmm_adamw4_init (lpmm_adamw4_step_noalloc)
+// Where a single-tensor step keeps its new maxima and ticket counters: the workspace given to lpmm_adamw4_init
+// (the default), the library's own device array (lpmm_adamw4_step_noalloc), or a workspace of the caller's
+// (lpmm_adamw4_step_ws).
+struct WorkspaceChoice {
+    bool use_scratch = false;
+    void* own = nullptr;
+    size_t own_bytes = 0;
+};
+
 int step_impl(bool bf16, void* param, const void* grad, uint8_t* m_codes, float* m_blockscale,
               uint8_t* v_codes, float* v_rowmax, float* v_colmax, const int64_t* shape, float lr,
-              float beta1, float beta2, float eps, float wd, int64_t step, void* stream, bool use_scratch = false) {
+              float beta1, float beta2, float eps, float wd, int64_t step, void* stream,
+              const WorkspaceChoice& wc = WorkspaceChoice()) {
     int64_t rows, cols;
     int rc = check_shape(shape, &rows, &cols);
     if (rc) return rc;
@@ -288,7 +296,14 @@ int step_impl(bool bf16, void* param, const void* grad, uint8_t* m_codes, float*
     hipStream_t s = static_cast<hipStream_t>(stream);
     float* ws = ctx->ws;
     unsigned int* counter = ctx->counter;
-    if (use_scratch) {
+    if (wc.own) {
+        // same layout as the workspace of lpmm_adamw4_init: the floats, then the counters in the last 8 KiB
+        if (!aligned(wc.own, 256) || wc.own_bytes < kCounterBytes + 256 * sizeof(float)) return LPMM_EINVAL;
+        const int64_t cap = int64_t((wc.own_bytes - kCounterBytes) / sizeof(float)) / 64 * 64;
+        if (rows_pad + cols_pad > cap) return LPMM_EWORKSPACE;
+        ws = static_cast<float*>(wc.own);
+        counter = reinterpret_cast<unsigned int*>(static_cast<char*>(wc.own) + size_t(cap) * sizeof(float));
+    } else if (wc.use_scratch) {
         if (!ctx->scratch) return LPMM_ENOTINIT;
         if (rows_pad + cols_pad > kScratchFloats) return LPMM_EWORKSPACE;
         // The array keeps what the last call on this device left.  A completed step leaves zeros, a step that
@@ -840,7 +855,18 @@ int lpmm_adamw4_step_noalloc(void* param, const void* grad, int grad_dtype, uint
                              void* stream) {
     if (grad_dtype != LPMM_GRAD_F32 && grad_dtype != LPMM_GRAD_BF16) return LPMM_EINVAL;
     return step_impl(grad_dtype == LPMM_GRAD_BF16, param, grad, m_codes, m_blockscale, v_codes, v_rowmax, v_colmax,
-                     shape, lr, beta1, beta2, eps, weight_decay, step, stream, true);
+                     shape, lr, beta1, beta2, eps, weight_decay, step, stream, WorkspaceChoice{true, nullptr, 0});
+}
+
+int lpmm_adamw4_step_ws(void* param, const void* grad, int grad_dtype, uint8_t* m_codes, float* m_blockscale,
+                        uint8_t* v_codes, float* v_rowmax, float* v_colmax, const int64_t shape[2], float lr,
+                        float beta1, float beta2, float eps, float weight_decay, int64_t step, void* workspace,
+                        size_t workspace_bytes, void* stream) {
+    if (grad_dtype != LPMM_GRAD_F32 && grad_dtype != LPMM_GRAD_BF16) return LPMM_EINVAL;
+    if (!workspace) return LPMM_EINVAL;
+    return step_impl(grad_dtype == LPMM_GRAD_BF16, param, grad, m_codes, m_blockscale, v_codes, v_rowmax, v_colmax,
+                     shape, lr, beta1, beta2, eps, weight_decay, step, stream,
+                     WorkspaceChoice{false, workspace, workspace_bytes});
 }
 
 int lpmm_adamw4_b128_state_sizes(int64_t numel, size_t sizes[4]) {
