@@ -87,7 +87,8 @@ size_t lpmm_adamw4_workspace_bytes(int64_t max_rows_plus_cols);
  * and kept alive until the process ends or init is called again) for device `device`, clears it
  * on `stream`, and uploads the quantization tables.  May be called again to replace the
  * workspace.  Steps on one device share this workspace: calls that may overlap in time on one
- * device (different streams) race; calls on one stream are safe. */
+ * device (different streams) race; calls on one stream are safe.  For steps that overlap, see
+ * lpmm_adamw4_step_ws (a workspace per call) and the plans (a workspace per plan). */
 int lpmm_adamw4_init(int device, void* workspace, size_t workspace_bytes, void* stream);
 
 /* Sizes in bytes of the five state buffers of a rows x cols tensor, in the order
