@@ -122,23 +122,27 @@ def build_workload(config, second_moment, optimizer, grad_dtype, launch, seed, d
         step4 = lpmm.lpmm_adamw4_step_bf16g if bf16 else lpmm.lpmm_adamw4_step
 
     # one plan per gradient set (a plan refers to its buffers by address)
-    plans = []
-    if launch == "multi":
+    def make_plans():
+        out = []
         for k in range(n_grad_sets):
             if sgdm:
                 descs = [lpmm.make_desc_sgdm(p, gs[k], st, sp.numel) for kind, sp, p, gs, st in tensors]
             else:
                 det = lambda sp: deterministic and factor and sp.quantized and sp.cols % 128 == 0
                 descs = [lpmm.make_desc(p, gs[k], st, sp.rows, sp.cols, deterministic=det(sp)) for kind, sp, p, gs, st in tensors]
-            plans.append(lpmm.new_plan(descs, 1 if bf16 else 0, dev))
+            out.append(lpmm.new_plan(descs, 1 if bf16 else 0, dev))
+        return out
 
-    def one_step(t):
+    plans = make_plans() if launch == "multi" else []
+
+    def one_step(t, use=None):
         k = t % n_grad_sets
         if plans:
+            pl = (use or plans)[k]
             if sgdm:
-                lpmm.lpmm_sgdm4_step_multi(plans[k], lr, momentum)
+                lpmm.lpmm_sgdm4_step_multi(pl, lr, momentum)
             else:
-                lpmm.lpmm_adamw4_step_multi(plans[k], lr, b1, b2, eps, wd, t)
+                lpmm.lpmm_adamw4_step_multi(pl, lr, b1, b2, eps, wd, t)
             return
         for kind, sp, p, gs, st in tensors:
             if sgdm:
@@ -158,6 +162,7 @@ def build_workload(config, second_moment, optimizer, grad_dtype, launch, seed, d
 
     wl = Workload()
     wl.specs, wl.tensors, wl.plans, wl.one_step, wl.release = specs, tensors, plans, one_step, release
+    wl.make_plans = make_plans
     wl.bf16, wl.recipe, wl.sgdm, wl.b128, wl.factor = bf16, recipe, sgdm, b128, factor
     wl.n_params = sum(sp.numel for sp in specs)
     wl.n_quant = sum(sp.numel for sp in specs if sp.quantized)
@@ -226,7 +231,8 @@ def main():
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-secondary", action="store_true",
-                    help="skip the other configurations and variants that are timed after the headline leg")
+                    help="skip what is timed after the headline leg: the other configurations and variants, and the serial "
+                         "leg behind roofline.alone")
     ap.add_argument("--grad-dtype", choices=["config", "bf16", "f32"], default="config",
                     help="override the gradient type of the configuration (experiments)")
     ap.add_argument("--second-moment", choices=["rank1", "b128", "factor"], default="rank1",
@@ -315,6 +321,35 @@ def main():
                      "pass 2 of the neighbouring tensor group (%.1f B/param) runs concurrently and shares "
                      "the bandwidth; whole-step figures are in config" % bp2),
         }
+        if not one_pass and not args.no_secondary:
+            # The same steps once more with every launch on the caller's stream, one after the other (plans built
+            # under LPMM_MULTI_STREAMS=0): the dominant kernel's rate when it has the chip to itself.  The step as a
+            # whole is slower that way, which is why the timed region above overlaps the passes.
+            os.environ["LPMM_MULTI_STREAMS"] = "0"
+            try:
+                serial = wl.make_plans()
+            finally:
+                del os.environ["LPMM_MULTI_STREAMS"]
+            for _ in range(2):
+                t += 1
+                one_step(t, serial)
+            torch.cuda.synchronize()
+            lpmm.lpmm_profile_begin(max(n_q_tensors, 64) * args.steps)
+            c0 = time.perf_counter()
+            for _ in range(args.steps):
+                t += 1
+                one_step(t, serial)
+            torch.cuda.synchronize()
+            serial_ms = (time.perf_counter() - c0) * 1e3 / args.steps
+            s1_ms, _, s_calls = lpmm.lpmm_profile_end()
+            for pl in serial:
+                lpmm.lpmm_adamw4_plan_release(pl)
+            if s_calls == n_calls and s1_ms > 0:
+                alone = bytes_per_launch / (s1_ms / s_calls * 1e-3) / 1e9
+                roofline["alone"] = {"achieved": round(alone, 1), "frac": round(alone / HBM_PEAK_GBPS, 4),
+                                     "avg_launch_ms": round(s1_ms / s_calls, 5), "ms_per_step": round(serial_ms, 4),
+                                     "note": "same kernels and tiles, every launch on the caller's stream one after "
+                                             "the other: this kernel with the chip to itself (events included in the step time)"}
         # HBM bytes per launch measured offline with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (see profiles/)
         tpath = os.path.join(ROOT, "profiles", "traffic_phase_kernel_%s%s.json" % (args.config, "_sgdm" if sgdm else "_b128" if b128 else "_factor" if factor else ""))
         if os.path.exists(tpath):

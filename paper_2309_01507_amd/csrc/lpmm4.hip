@@ -627,6 +627,7 @@ struct PlanHost {
     bool factor = false;                // the plan's 2-dimensional tensors keep a factorized second moment
     bool sgdm = false;                  // a plan of SGD-with-momentum tensors (lpmm_sgdm4_step_multi)
     bool flat = false;                  // large tensors, several groups: pass 1 uses the flat tiling
+    bool serial = false;                // LPMM_MULTI_STREAMS=0: every pass a launch of its own on the caller's stream
     int64_t params = 0;                 // parameters of all tensors of the plan
     Hyper* d_hyper = nullptr;           // device slot inside the plan for the hyper-parameters of a captured step
     int device = 0;
@@ -1485,6 +1486,7 @@ int lpmm_adamw4_plan_build_nd(const lpmm_tensor_desc* descs, int64_t n, const in
         host->phases.push_back(pl);
     }
     // a second stream pays only if some pass 2 has a pass 1 of another group to run beside
+    host->serial = env_int("LPMM_MULTI_STREAMS", 2) == 0 && !host->sgdm;
     if (env_int("LPMM_MULTI_STREAMS", 2) >= 2 && groups.size() > 1 && !host->sgdm) {
         LPMM_HIP(hipStreamCreateWithFlags(&host->side, hipStreamNonBlocking));
         LPMM_HIP(hipEventCreateWithFlags(&host->ev_fork, hipEventDisableTiming));
@@ -1583,17 +1585,21 @@ int adamw4_step_multi_impl(void* plan, float lr, const float* lr_dev, float beta
         }
 #undef LPMM_PHASE_CASE
     };
-    if (host->side) {
+    if (host->side || host->serial) {
         // A work of phase j on the caller's stream, B work (pass 2 of the tensors whose pass 1 ran
         // in phase j-1) on the side stream behind an event; the caller's stream rejoins at the end.
-        hipStream_t s2 = host->side;
-        LPMM_HIP(hipEventRecord(host->ev_fork, s));
-        LPMM_HIP(hipStreamWaitEvent(s2, host->ev_fork, 0));
-        if (host->side_a) LPMM_HIP(hipStreamWaitEvent(host->side_a, host->ev_fork, 0));
+        // Serial plans take the same launches one after the other on the caller's stream, without events.
+        const bool two = host->side != nullptr;
+        hipStream_t s2 = two ? host->side : s;
+        if (two) {
+            LPMM_HIP(hipEventRecord(host->ev_fork, s));
+            LPMM_HIP(hipStreamWaitEvent(s2, host->ev_fork, 0));
+            if (host->side_a) LPMM_HIP(hipStreamWaitEvent(host->side_a, host->ev_fork, 0));
+        }
         for (size_t j = 0; j < host->phases.size(); ++j) {
             const PhaseLaunch& pl = host->phases[j];
             if (pl.ph.n_b > 0) {
-                LPMM_HIP(hipStreamWaitEvent(s2, host->ev_a[j - 1], 0));
+                if (two) LPMM_HIP(hipStreamWaitEvent(s2, host->ev_a[j - 1], 0));
                 // a factorized plan's heavy kernel is its B work (the update pass): that one is timed
                 const bool rec = host->factor && g_prof.on && g_prof.calls < g_prof.max_calls;
                 const int64_t call = g_prof.calls;
@@ -1621,8 +1627,9 @@ int adamw4_step_multi_impl(void* plan, float lr, const float* lr_dev, float beta
                     g_prof.calls = call + 1;
                 }
             }
-            LPMM_HIP(hipEventRecord(host->ev_a[j], sa));
+            if (two) LPMM_HIP(hipEventRecord(host->ev_a[j], sa));
         }
+        if (!two) return LPMM_OK;
         LPMM_HIP(hipEventRecord(host->ev_join, s2));
         LPMM_HIP(hipStreamWaitEvent(s, host->ev_join, 0));
         if (host->side_a) {

@@ -173,8 +173,8 @@ def test_bad_arguments_are_rejected():
 
 
 @pytest.mark.parametrize("env", [{}, {"LPMM_PHASE_MPARAMS": "1"}, {"LPMM_PHASE_MPARAMS": "1", "LPMM_MULTI_STREAMS": "1"},
-                                 {"LPMM_PHASE_MPARAMS": "1", "LPMM_FLAT": "1"}],
-                         ids=["one-group", "two-streams", "fused-launches", "flat"])
+                                 {"LPMM_PHASE_MPARAMS": "1", "LPMM_FLAT": "1"}, {"LPMM_PHASE_MPARAMS": "1", "LPMM_MULTI_STREAMS": "0"}],
+                         ids=["one-group", "two-streams", "fused-launches", "flat", "serial-launches"])
 def test_plan_with_n_dimensional_tensors(env):
     """Convolution-shaped tensors, matrices and small fp32-state tensors in one plan."""
     seed = 64
