@@ -13,8 +13,9 @@
  *
  * Further sections below: the block-wise second moment for 1-dimensional / flattened tensors (Sec. 4.2),
  * the factorized second moment of "4-bit Factor" (Sec. 4.3), rank-1 normalization for more than two
- * dimensions (App. F Alg. 4), SGD with momentum (App. E Alg. 2), stand-alone compress / decompress,
- * plans (many tensors per call), and the plan steps with device-resident learning rate and step number.
+ * dimensions (App. F Alg. 4), SGD with momentum (App. E Alg. 2), stand-alone compress / decompress, the
+ * quantizers the paper ablates for the second moment (Sec. 4.1, Tab. 1, App. D.3), plans (many tensors per
+ * call), and the plan steps with device-resident learning rate and step number.
  *
  * Conventions for every call
  *   - All data pointers are DEVICE pointers unless the comment says "host".  The caller owns every
