@@ -80,11 +80,12 @@ def _mini_transformer():
 @pytest.mark.parametrize("env", [{}, {"LPMM_PHASE_MPARAMS": "1"}, {"LPMM_PHASE_MPARAMS": "1", "LPMM_MULTI_RW": "8"},
                                  {"LPMM_PHASE_MPARAMS": "1", "LPMM_FLAT": "1"}, {"LPMM_FLAT": "1", "LPMM_MULTI_RW": "24"},
                                  {"LPMM_PHASE_MPARAMS": "1", "LPMM_MULTI_STREAMS": "1"},
-                                 {"LPMM_PHASE_MPARAMS": "1", "LPMM_MULTI_STREAMS": "0"}])
+                                 {"LPMM_PHASE_MPARAMS": "1", "LPMM_MULTI_STREAMS": "0"},
+                                 {"LPMM_PHASE_MPARAMS": "1", "LPMM_MULTI_STREAMS": "3"}])
 def test_multi_matches_oracle_fp32_grads(env):
     """Default grouping (everything in one group), and tiny groups so that many phases overlap
-    pass 1 of one group with pass 2 of the previous one; the last two: both passes of a phase in one launch, and
-    every pass a launch of its own on the caller's stream."""
+    pass 1 of one group with pass 2 of the previous one; the last three: both passes of a phase in one launch,
+    every pass a launch of its own on the caller's stream, and pass 1 alternating between two streams."""
     _run_set(_mini_transformer(), "col_lognormal", False, steps=4, seed=11, env=env)
 
 
