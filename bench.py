@@ -300,8 +300,8 @@ def main():
     if plans:
         # the recorded launches are the pass-1 kernels (pass 1 of a tensor group plus the fp32-state
         # tensors); pass 2 of the previous group runs beside them on the plan's second stream
-        # (a factorized plan's recorded launches are its update passes, on the second stream; the fp32-state
-        # tensors ride with the statistics passes)
+        # (a factorized plan's recorded launches are its update passes; its launches run one after the other on the
+        # caller's stream, and the fp32-state tensors ride with the statistics passes)
         bytes_per_launch = (bp1 * n_quant + (0.0 if factor else small_bytes)) * args.steps / launches
         avg_ms = p1_ms / launches
         achieved = bytes_per_launch / (avg_ms * 1e-3) / 1e9
@@ -316,12 +316,12 @@ def main():
             "bytes_per_launch": round(bytes_per_launch),
             "traffic_source": None,
             "note": ("one pass: this kernel is the whole step" if one_pass else
-                     "the statistics pass of the next tensor group (%.1f B/param) runs concurrently and shares "
-                     "the bandwidth; whole-step figures are in config" % bp2 if factor else
+                     "the statistics pass (%.1f B/param) is a launch of its own before it on the same stream; "
+                     "whole-step figures are in config" % bp2 if factor else
                      "pass 2 of the neighbouring tensor group (%.1f B/param) runs concurrently and shares "
                      "the bandwidth; whole-step figures are in config" % bp2),
         }
-        if not one_pass and not args.no_secondary:
+        if not one_pass and not factor and not args.no_secondary:
             # The same steps once more with every launch on the caller's stream, one after the other (plans built
             # under LPMM_MULTI_STREAMS=0): the dominant kernel's rate when it has the chip to itself.  The step as a
             # whole is slower that way, which is why the timed region above overlaps the passes.
@@ -459,8 +459,8 @@ def main():
                    else "rank-1/Linear, two passes",
                    "grad_recipe": recipe,
                    "launch": (("multi-tensor plan, %d launches per step" if one_pass else
-                               "multi-tensor plan, %d update launches per step on a second stream, the statistics "
-                               "passes on the caller's stream" if factor else
+                               "multi-tensor plan, %d update launches per step, each behind its statistics launch "
+                               "on the caller's stream" if factor else
                                "multi-tensor plan, %d pass-1 launches per step on the caller's stream, "
                                "pass 2 on a second stream") % (n_calls // max(args.steps, 1)))
                    if has_plans else "per-tensor, %d kernel%s per quantized tensor" % ((1, "") if one_pass else (2, "s")),

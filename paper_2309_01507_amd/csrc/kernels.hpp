@@ -1533,26 +1533,30 @@ __device__ __forceinline__ void factor_stats_tile(const Tensor4& a, int wg, Lds&
         const float rsum = wave_sum((sq[0] + sq[1]) + (sq[2] + sq[3]));
         if (lane == 0) s.blk_scale[il] = rsum;
     };
-    // rows in the order of pass 2; loads of two rows in flight while a third is summed
+    // rows in the order of pass 2; three register sets take turns: a set is reloaded right after its row has been
+    // summed, so the loads of two rows are in flight while a third is summed (more sets in flight measured slower)
     const int rs = a.rs2;
     const int row_w = wave << rs, hop = kWaves << rs, low = (1 << rs) - 1;
     auto row = [&](int k) { return row_w + (k & low) + (k >> rs) * hop; };
     int k = 0;
-    GradRegs4<BF16> r0 = ld(row(0)), r1 = ld(row(1)), r2;
+    constexpr int kDepth = 3;
+    GradRegs4<BF16> r[kDepth];
+#pragma unroll
+    for (int u = 0; u < kDepth; ++u) r[u] = ld(row(u));
     __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
-    while (row(k + 2) < n) {
-        r2 = ld(row(k + 2));
-        one(r0, row(k));
-        r0 = ld(row(k + 3));
-        one(r1, row(k + 1));
-        r1 = ld(row(k + 4));
-        one(r2, row(k + 2));
-        k += 3;
-    }
-    if (row(k) < n) {
-        one(r0, row(k));
-        if (row(k + 1) < n) one(r1, row(k + 1));
-    }
+    if (row(k + kDepth - 1) < n) do {
+#pragma unroll
+        for (int u = 0; u < kDepth; ++u) {
+            one(r[u], row(k + u));
+            __builtin_amdgcn_sched_barrier(0);
+            r[u] = ld(row(k + kDepth + u));
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        k += kDepth;
+    } while (row(k + kDepth - 1) < n);
+#pragma unroll
+    for (int u = 0; u < kDepth - 1; ++u)
+        if (row(k + u) < n) one(r[u], row(k + u));
 #pragma unroll
     for (int e = 0; e < 4; ++e) s.col[wave * 256 + lane * 4 + e] = cacc[e];
     __syncthreads();

@@ -1485,13 +1485,17 @@ int lpmm_adamw4_plan_build_nd(const lpmm_tensor_desc* descs, int64_t n, const in
         pl.grid_b = pad8(pl.ph.n_b);
         host->phases.push_back(pl);
     }
-    // a second stream pays only if some pass 2 has a pass 1 of another group to run beside
-    host->serial = env_int("LPMM_MULTI_STREAMS", 2) == 0 && !host->sgdm;
-    if (env_int("LPMM_MULTI_STREAMS", 2) >= 2 && groups.size() > 1 && !host->sgdm) {
+    // A second stream pays only if some pass 2 has a pass 1 of another group to run beside.  Factorized plans take
+    // their launches one after the other on the caller's stream by default: the statistics pass (read-only) and the
+    // update pass each run at the memory system's rate alone, and side by side they only get in each other's way
+    // (7B-shaped set: 14.71 ms per step against 14.84, 354 M set 0.841 against 0.854).
+    const int stream_mode = env_int("LPMM_MULTI_STREAMS", host->factor ? 0 : 2);
+    host->serial = stream_mode == 0 && !host->sgdm;
+    if (stream_mode >= 2 && groups.size() > 1 && !host->sgdm) {
         LPMM_HIP(hipStreamCreateWithFlags(&host->side, hipStreamNonBlocking));
         LPMM_HIP(hipEventCreateWithFlags(&host->ev_fork, hipEventDisableTiming));
         LPMM_HIP(hipEventCreateWithFlags(&host->ev_join, hipEventDisableTiming));
-        if (env_int("LPMM_MULTI_STREAMS", 2) >= 3) {
+        if (stream_mode >= 3) {
             LPMM_HIP(hipStreamCreateWithFlags(&host->side_a, hipStreamNonBlocking));
             LPMM_HIP(hipEventCreateWithFlags(&host->ev_join_a, hipEventDisableTiming));
         }

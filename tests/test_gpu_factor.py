@@ -221,8 +221,8 @@ def test_bad_arguments_are_rejected():
     torch.cuda.synchronize()
 
 
-@pytest.mark.parametrize("env", [{}, {"LPMM_PHASE_MPARAMS": "1"}, {"LPMM_PHASE_MPARAMS": "1", "LPMM_MULTI_STREAMS": "1"},
-                                 {"LPMM_PHASE_MPARAMS": "1", "LPMM_MULTI_STREAMS": "0"}],
+@pytest.mark.parametrize("env", [{}, {"LPMM_PHASE_MPARAMS": "1", "LPMM_MULTI_STREAMS": "2"},
+                                 {"LPMM_PHASE_MPARAMS": "1", "LPMM_MULTI_STREAMS": "1"}, {"LPMM_PHASE_MPARAMS": "1"}],
                          ids=["one-group", "two-streams", "fused-launches", "serial-launches"])
 def test_plan_with_factorized_block_wise_and_fp32_tensors(env):
     """A "4-bit Factor" parameter set in one plan: matrices factorized, a large 1-dimensional tensor
