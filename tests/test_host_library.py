@@ -229,3 +229,13 @@ def test_ablation_maps_equal_the_oracles():
     for code, signed in ((1, 1), (2, 1), (3, 0), (-1, 0)):
         assert L.lpmm_ablation_table(code, signed, ctypes.addressof(out)) == -1
     assert L.lpmm_ablation_table(0, 0, None) == -1
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; asked for more it says so and exits before touching any device."""
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode == 2
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
