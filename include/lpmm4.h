@@ -350,8 +350,9 @@ int lpmm_dequant_ablation(int norm, int map, int is_signed, const uint8_t* codes
  * lpmm_adamw4_step_multi then enqueues a short sequence of launches: pass 1 of one group of tensors
  * runs on `stream` while pass 2 of the previous group runs beside it on a second stream that the
  * plan owns (same priority; `stream` waits for it before the call's work counts as complete, so the
- * usual stream ordering holds for the caller).  Results are identical to calling the single-tensor
- * entry points one tensor at a time. */
+ * usual stream ordering holds for the caller).  Plans with a single group, plans of factorized tensors and
+ * the one-pass kinds enqueue all their launches on `stream`.  Results are identical to calling the
+ * single-tensor entry points one tensor at a time. */
 
 #define LPMM_KIND_4BIT 0   /* quantized states as in lpmm_adamw4_step */
 #define LPMM_KIND_FP32 1   /* uncompressed fp32 states as in lpmm_adamw32_step */
@@ -456,8 +457,8 @@ int lpmm_adamw4_plan_release(void* plan);
  * lpmm_profile_end: waits for the recorded events and stops recording.  Single-tensor steps: ms[0]
  * = summed duration in milliseconds of the recorded pass-1 launches, ms[1] = of the pass-2 launches,
  * *n_calls = recorded calls.  Multi-tensor steps: ms[0] = summed duration of the recorded launches
- * that carry pass 1 (their pass-2 companions run beside them on the plan's second stream), ms[1]
- * = 0, *n_calls = recorded launches.  (Do not mix the two kinds between one begin and end.)
+ * that carry pass 1 (their pass-2 companions run beside them on the plan's second stream; in a plan of
+ * factorized tensors: of the update passes), ms[1] = 0, *n_calls = recorded launches.  (Do not mix the two kinds between one begin and end.)
  * ms, n_calls: host.  Not thread-safe: begin, end and every step between them must come from one host thread. */
 int lpmm_profile_begin(int64_t max_calls);
 int lpmm_profile_end(double ms[2], int64_t* n_calls);
