@@ -170,24 +170,13 @@ __device__ __forceinline__ float max_nonneg(float a, float b) {
 }
 
 // Streaming 128-bit access for the parameters: they are read and written exactly once per step.
-// The load carries the non-temporal hint; the store goes out as a buffer store with the nt and sc1
-// cache-policy bits (write through, do not keep the line).  Measured on the 7B-shaped set: about 9 %
-// less time per step than plain accesses for nt on both, and a further 2-3 % of pass 1 for sc1 on
-// the store.  `base` is wave-uniform and byte_off stays below 2^31 (tiles are sized for that).
+// The loads carry the non-temporal hint; the stores go out with the nt and sc1 cache-policy bits (write
+// through, do not keep the line).  Measured on the 7B-shaped set: about 9 % less time per step than plain
+// accesses for nt on both, and a further 2-3 % of pass 1 for sc1 on the store.
 typedef float v4f_t __attribute__((ext_vector_type(4)));
 typedef uint32_t v4u_t __attribute__((ext_vector_type(4)));
 constexpr int kPolicyNtSc1 = 2 | 16;            // gfx94x/gfx950 cache-policy bits: 1 = sc0, 2 = nt, 16 = sc1
 constexpr int kRawBufferWord3 = 0x00020000;     // untyped 32-bit data format, no swizzle, offsets in bytes
-__device__ __forceinline__ float4 ld_stream4(const void* base, uint32_t byte_off) {
-    const v4f_t v = __builtin_nontemporal_load(
-        reinterpret_cast<const v4f_t*>(reinterpret_cast<const char*>(base) + byte_off));
-    return make_float4(v.x, v.y, v.z, v.w);
-}
-__device__ __forceinline__ void st_stream4(void* base, uint32_t byte_off, float4 f) {
-    const v4f_t v = {f.x, f.y, f.z, f.w};
-    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(base, 0, 0x7FFFFFFF, kRawBufferWord3);
-    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(v4u_t, v), rsrc, int(byte_off), 0, kPolicyNtSc1);
-}
 
 // Bounds-checked loads of the fast path.  A tile's arrays are described by raw buffer resources
 // whose length is the tile's; a load beyond it returns zero and touches no memory.  The row
@@ -236,35 +225,6 @@ __device__ __forceinline__ void load8(const float* p, float out[8]) {
     const float4 b = *reinterpret_cast<const float4*>(p + 4);
     out[0] = a.x; out[1] = a.y; out[2] = a.z; out[3] = a.w;
     out[4] = b.x; out[5] = b.y; out[6] = b.z; out[7] = b.w;
-}
-
-template <bool BF16> struct GradRegs;
-template <> struct GradRegs<true> { uint4 w; };
-template <> struct GradRegs<false> { float4 a, b; };
-
-// gradient of a lane's 8 elements; off4 is the byte offset the elements have in an fp32 array
-template <bool BF16>
-__device__ __forceinline__ GradRegs<BF16> load_grad_regs(const void* g_tile, uint32_t off4) {
-    GradRegs<BF16> r;
-    if constexpr (BF16) {
-        r.w = ld<uint4>(g_tile, off4 >> 1);
-    } else {
-        r.a = ld<float4>(g_tile, off4);
-        r.b = ld<float4>(g_tile, off4 + 16);
-    }
-    return r;
-}
-template <bool BF16>
-__device__ __forceinline__ void unpack_grad(const GradRegs<BF16>& r, float out[8]) {
-    if constexpr (BF16) {
-        out[0] = bf16_lo(r.w.x); out[1] = bf16_hi(r.w.x);
-        out[2] = bf16_lo(r.w.y); out[3] = bf16_hi(r.w.y);
-        out[4] = bf16_lo(r.w.z); out[5] = bf16_hi(r.w.z);
-        out[6] = bf16_lo(r.w.w); out[7] = bf16_hi(r.w.w);
-    } else {
-        out[0] = r.a.x; out[1] = r.a.y; out[2] = r.a.z; out[3] = r.a.w;
-        out[4] = r.b.x; out[5] = r.b.y; out[6] = r.b.z; out[7] = r.b.w;
-    }
 }
 
 // =====================================================================================================

@@ -41,7 +41,6 @@ struct SearchEntry {
 };
 
 inline uint32_t f2u(float f) { uint32_t u; std::memcpy(&u, &f, 4); return u; }
-inline float u2f(uint32_t u) { float f; std::memcpy(&f, &u, 4); return f; }
 
 // ---- the two maps -------------------------------------------------------------------------------
 
