@@ -802,50 +802,59 @@ __device__ __forceinline__ void publish_if_last(const Tensor4& a, unsigned int m
 // gradient), the four waves of a workgroup take rows w, w+4, ... of the tile.  The row index, the two
 // row maxima and everything derived from them are wave-uniform and live in scalar registers.
 template <bool BF16>
-struct Row2 {                      // everything pass 2 reads for one row of one lane
+struct Row2 {                      // what pass 2 reads per element for one row of one lane
     GradRegs4<BF16> g;
     uint16_t vq;                   // the lane's 4 codes
-    float r_old, r_new;            // the same value in every lane
 };
 
-// row_elems = il * cols, wave-uniform (scalar arithmetic); lane_g / lane_q: the lane's byte offsets inside a row
-// of the gradient / of the codes, fixed for the tile: two vector adds per row for the addresses
+// row_elems = il * cols, wave-uniform: it travels as the scalar offset of the buffer instructions, so a row costs no
+// vector arithmetic for its addresses.  lane_g / lane_q: the lane's byte offsets inside a row of the gradient / of the
+// codes, fixed for the tile.  (Callers pass rows inside the tile only: the scalar offset may not take part in the
+// range check of the resource.)
 template <bool BF16>
-__device__ __forceinline__ Row2<BF16> load_row2(const TileBase& b, uint32_t row_elems, uint32_t lane_g, uint32_t lane_q,
-                                                int il) {
+__device__ __forceinline__ Row2<BF16> load_row2(const TileBase& b, uint32_t row_elems, uint32_t lane_g, uint32_t lane_q) {
     Row2<BF16> r;
-    const uint32_t off_g = row_elems * (BF16 ? 2u : 4u) + lane_g;
-    if constexpr (BF16) r.g.w = buf_ld_u2<kPolicyNt>(b.rg, off_g);      // last use of the gradient in this step
-    else r.g.a = buf_ld_f4<kPolicyNt>(b.rg, off_g);
-    r.vq = buf_ld_u16(b.rvq, (row_elems >> 1) + lane_q);
-    r.r_old = buf_ld_f(b.rr, uint32_t(il) * 4u);
-    r.r_new = buf_ld_f(b.rr_new, uint32_t(il) * 4u);
+    if constexpr (BF16) {                                       // last use of the gradient in this step
+        const v2u_t w = __builtin_amdgcn_raw_buffer_load_b64(b.rg, int(lane_g), int(row_elems * 2u), kPolicyNt);
+        r.g.w = make_uint2(w.x, w.y);
+    } else {
+        const v4f_t v = __builtin_bit_cast(v4f_t, __builtin_amdgcn_raw_buffer_load_b128(b.rg, int(lane_g), int(row_elems * 4u), kPolicyNt));
+        r.g.a = make_float4(v.x, v.y, v.z, v.w);
+    }
+    r.vq = uint16_t(__builtin_amdgcn_raw_buffer_load_b16(b.rvq, int(lane_q), int(row_elems >> 1), 0));
     return r;
 }
 
-__device__ __forceinline__ float wave_uniform(float v) {
-    return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(v)));
+__device__ __forceinline__ float lane_value(float v, int lane) {      // lane: wave-uniform
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
 }
 
-// New codes of the lane's 4 elements of one row.  The usual route multiplies by approximate reciprocals and keeps
-// track of how close it came to a decision boundary; if the row's scales are extreme, or some lane came too close,
-// the whole wave computes the row again from its inputs with exact arithmetic (same bits where both apply).  The
-// second route shares no value with the first, so that nothing has to be kept in registers for it.
+// The scalars of a wave's rows of one pass-2 tile, one row per lane (row k of the wave in lane k): the old and the new
+// row maximum, the old one / 16, the approximate reciprocal of the new one (0 for 0), and `wild`, the mask of the
+// rows that must take the exact route whatever their elements (a scale of the row or of the strip's columns outside
+// the range in which scale / 16 and the reciprocal keep all their bits).
+struct RowScalars {
+    float r_old, r_new, r16, inv;
+    uint64_t wild;
+};
+
+// New codes of the lane's 4 elements of row k of the wave.  The usual route multiplies by approximate reciprocals and
+// keeps track of how close it came to a decision boundary; if the row is marked wild, or some lane came too close, the
+// whole wave computes the row again from its inputs with exact arithmetic (same bits where both apply).  The second
+// route shares no value with the first, so that nothing has to be kept in registers for it.
 template <bool BF16>
-__device__ __forceinline__ uint32_t pass2_row(const Tensor4& a, const Hyper& h, uint32_t col0,
-                                              const Row2<BF16>& row, const float cold16[4],
-                                              const float inv_cnew[4], bool cols_tame) {
-    const float r_old = wave_uniform(row.r_old), r_new = wave_uniform(row.r_new);
+__device__ __forceinline__ uint32_t pass2_row(const Tensor4& a, const Hyper& h, uint32_t col0, const Row2<BF16>& row,
+                                              const RowScalars& rs, int k, const float cold16[4],
+                                              const float inv_cnew[4]) {
     float g[4];
     unpack_grad4<BF16>(row.g, g);
-    // cols_tame is wave-uniform: the whole wave takes one route
-    if (__builtin_expect(cols_tame && scale_is_tame(r_old) && scale_is_tame(r_new), 1)) {
+    // wave-uniform: the whole wave takes one route
+    if (__builtin_expect(((rs.wild >> k) & 1u) == 0u, 1)) {
         float qf[4], vt[4];
         codes_to_float4(row.vq, qf);
-        const float r16 = r_old * 0.0625f;
+        const float r16 = lane_value(rs.r16, k), inv_r = lane_value(rs.inv, k);
 #pragma unroll
         for (int e = 0; e < 4; ++e) vt[e] = moment_v(h, dequant_v16(qf[e], min_nonneg(r16, cold16[e])), g[e]);
-        const float inv_r = approx_inv(r_new);
         // even elements collect in the bytes of `lo`, odd ones in `hi`; word = lo | hi << 4
         uint32_t lo = 0, hi = 0;
         float closest = 0.5f, fa, fb;
@@ -857,6 +866,7 @@ __device__ __forceinline__ uint32_t pass2_row(const Tensor4& a, const Hyper& h, 
 #undef LPMM_V2
         if (__builtin_expect(__ballot(closest < kMarginV) == 0, 1)) return lo | (hi << 4);
     }
+    const float r_old = lane_value(rs.r_old, k), r_new = lane_value(rs.r_new, k);
     float cold[4], cnew[4];
     load4(a.c + col0, cold);
     load4(a.c_new + col0, cnew);
@@ -870,17 +880,40 @@ __device__ __forceinline__ uint32_t pass2_row(const Tensor4& a, const Hyper& h, 
 }
 
 constexpr int kWaves = kThreads / 64;
+constexpr int kMaxRw2 = 64 * kWaves;      // rows of a pass-2 tile: a wave keeps its rows' scalars one per lane
 
 template <bool BF16>
 __device__ __forceinline__ void pass2_fast_tile(const Tensor4& a, const Hyper& h, int wg) {
     const int strip = wg % a.strips2, tile = wg / a.strips2;
     const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x) >> 6);
-    const uint32_t col0 = uint32_t(strip) * 256u + (threadIdx.x & 63u) * 4u;
-    if (col0 >= uint32_t(a.cols)) return;        // odd number of column blocks: upper half of the last strip
+    const int lane = threadIdx.x & 63;
+    // With an odd number of column blocks the upper half-wave of the last strip has no columns.  Those lanes stay
+    // in the loop all the same, because every lane of the wave holds the scalars of one of its rows (below): they
+    // work on the lower half's columns a second time and only their stores are left out.
+    const uint32_t col_own = uint32_t(strip) * 256u + uint32_t(lane) * 4u;
+    const bool live = col_own < uint32_t(a.cols);
+    const uint32_t col0 = live ? col_own : col_own - 128u;
     const int64_t row0 = int64_t(tile) * a.rw2;
     const int64_t left = a.rows - row0;
     const int n = left < a.rw2 ? int(left) : a.rw2;
     const TileBase tb = tile_base<BF16>(a, row0, n);
+    // rows of this wave in the order it takes them, as in pass 1: the four waves are 2^rs2 rows apart
+    const int rs = a.rs2;
+    const int row_w = wave << rs, hop = kWaves << rs, low = (1 << rs) - 1;
+    auto row = [&](int k) { return row_w + (k & low) + (k >> rs) * hop; };
+    // The scalars of the wave's rows (at most 64 per tile), one row per lane; the row loop fetches what it needs
+    // with v_readlane instead of two loads, a reciprocal, a select and two range checks per row.  Rows past the
+    // tile read as zeros through the bounds-checked resources.
+    RowScalars sc;
+    {
+        const uint32_t il_l = uint32_t(row(lane));
+        sc.r_old = buf_ld_f(tb.rr, il_l * 4u);
+        sc.r_new = buf_ld_f(tb.rr_new, il_l * 4u);
+        sc.r16 = sc.r_old * 0.0625f;
+        sc.inv = approx_inv(sc.r_new);
+        const bool row_tame = bool(int(scale_is_tame(sc.r_old)) & int(scale_is_tame(sc.r_new)));
+        sc.wild = __ballot(!row_tame);
+    }
     float cold16[4], inv_cnew[4];
     load4(a.c + col0, cold16);
     load4(a.c_new + col0, inv_cnew);
@@ -891,19 +924,17 @@ __device__ __forceinline__ void pass2_fast_tile(const Tensor4& a, const Hyper& h
         cold16[e] *= 0.0625f;
         inv_cnew[e] = approx_inv(inv_cnew[e]);
     }
-    const bool cols_tame = __ballot(!lane_tame) == 0;
-    // the loads of two rows are in flight while a third is computed (three register sets take
-    // turns, the loop is unrolled by three); rows past the tile read as zeros and are never used
+    if (__ballot(!lane_tame) != 0) sc.wild = ~uint64_t(0);        // a wild column scale: every row takes the exact route
+    // the loads of two rows are in flight while a third is computed (three register sets take turns, the loop is
+    // unrolled by three); a prefetch past the tile takes the tile's last row again and is never used
     const uint32_t cols = uint32_t(a.cols);
     const uint32_t lane_g = col0 * (BF16 ? 2u : 4u), lane_q = col0 >> 1;
-    auto fetch = [&](int il) { return load_row2<BF16>(tb, uint32_t(il) * cols, lane_g, lane_q, il); };   // il * cols < 2^29 + a few rows
+    const int last = n - 1;
+    auto fetch = [&](int il) { return load_row2<BF16>(tb, uint32_t(il < last ? il : last) * cols, lane_g, lane_q); };   // il * cols < 2^29
     auto put = [&](int il, uint32_t codes) {
-        st<uint16_t>(tb.vq, ((uint32_t(il) * cols) >> 1) + lane_q, uint16_t(codes));
+        if (live) __builtin_amdgcn_raw_buffer_store_b16(short(codes), tb.rvq, int(lane_q), int((uint32_t(il) * cols) >> 1), 0);
     };
-    // rows of this wave in the order it takes them, as in pass 1: the four waves are 2^rs2 rows apart
-    const int rs = a.rs2;
-    const int row_w = wave << rs, hop = kWaves << rs, low = (1 << rs) - 1;
-    auto row = [&](int k) { return row_w + (k & low) + (k >> rs) * hop; };
+    auto codes_of = [&](const Row2<BF16>& r, int k) { return pass2_row<BF16>(a, h, col0, r, sc, k, cold16, inv_cnew); };
     int k = 0;
     Row2<BF16> r0 = fetch(row(0));
     Row2<BF16> r1 = fetch(row(1));
@@ -913,23 +944,23 @@ __device__ __forceinline__ void pass2_fast_tile(const Tensor4& a, const Hyper& h
     // held has been processed, two rows ahead of its next use; the loads are pinned there, after the last use of
     // the values they replace.
     if (row(k + 2) < n) do {
-        put(row(k), pass2_row<BF16>(a, h, col0, r0, cold16, inv_cnew, cols_tame));
+        put(row(k), codes_of(r0, k));
         __builtin_amdgcn_sched_barrier(0);
         r0 = fetch(row(k + 3));
         __builtin_amdgcn_sched_barrier(0);
-        put(row(k + 1), pass2_row<BF16>(a, h, col0, r1, cold16, inv_cnew, cols_tame));
+        put(row(k + 1), codes_of(r1, k + 1));
         __builtin_amdgcn_sched_barrier(0);
         r1 = fetch(row(k + 4));
         __builtin_amdgcn_sched_barrier(0);
-        put(row(k + 2), pass2_row<BF16>(a, h, col0, r2, cold16, inv_cnew, cols_tame));
+        put(row(k + 2), codes_of(r2, k + 2));
         __builtin_amdgcn_sched_barrier(0);
         r2 = fetch(row(k + 5));
         __builtin_amdgcn_sched_barrier(0);
         k += 3;
     } while (row(k + 2) < n);
     if (row(k) < n) {
-        put(row(k), pass2_row<BF16>(a, h, col0, r0, cold16, inv_cnew, cols_tame));
-        if (row(k + 1) < n) put(row(k + 1), pass2_row<BF16>(a, h, col0, r1, cold16, inv_cnew, cols_tame));
+        put(row(k), codes_of(r0, k));
+        if (row(k + 1) < n) put(row(k + 1), codes_of(r1, k + 1));
     }
 }
 

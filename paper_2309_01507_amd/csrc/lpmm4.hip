@@ -197,6 +197,7 @@ void fast_geometry(Tensor4* a, int n_cu, int64_t rw_hint, int64_t rw2_hint, int 
         while (rw2 > kWaves && a->strips2 * ((a->rows + rw2 - 1) / rw2) < 2 * int64_t(n_cu)) rw2 >>= 1;
     }
     if (rw2 > cap) rw2 = cap;
+    if (rw2 > kMaxRw2) rw2 = kMaxRw2;                       // a wave of pass 2 keeps its rows' scalars one per lane
     if (rw2 > a->rows) rw2 = a->rows;
     if (rw2 < 1) rw2 = 1;
     a->rw2 = int(rw2);

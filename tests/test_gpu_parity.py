@@ -202,6 +202,25 @@ def test_launch_geometry_does_not_change_results():
         np.testing.assert_array_equal(w, ref_w)
 
 
+@pytest.mark.parametrize("env", [{"LPMM_RW2": "256"}, {"LPMM_RW2": "512", "LPMM_RS2": "0"}, {"LPMM_RW2": "200", "LPMM_RS2": "2"},
+                                 {"LPMM_RW2": "256", "LPMM_RS2": "3"}])
+def test_pass2_tall_tiles_and_a_half_empty_last_strip(env):
+    """A wave of pass 2 keeps the scalars of its rows one per lane, up to 64 rows (tiles of 256 rows; taller ones are
+    cut down to that).  With an odd number of column blocks the upper half of the last strip's lanes has no columns
+    but still holds rows 32 to 63: tall tiles on such shapes, against the oracle, with outlier rows (so that rows
+    differ), bf16 and fp32 gradients."""
+    for k in ALL_KNOBS:
+        os.environ.pop(k, None)
+    os.environ.update(env)
+    try:
+        assert run_parity(300, 640, steps=3, recipe="outlier_sparse", seed=31) == 0
+        assert run_parity(777, 128, steps=3, recipe="col_lognormal", bf16=True, seed=32) == 0
+        assert run_parity(520, 1152, steps=2, recipe="col_lognormal", bf16=True, seed=33) == 0
+    finally:
+        for k in env:
+            os.environ.pop(k, None)
+
+
 def test_resume_from_copied_state():
     """The five buffers are the whole optimizer state: 6 steps == 3 steps + copy out/in + 3 steps."""
     rows, cols = 128, 256
