@@ -2142,7 +2142,10 @@ struct Segment {        // a run of workgroups that work on one tensor
     int tensor;         // index into the tensor table
 };
 
-constexpr int kMaxSeg = 128;  // tensors per kind in one phase; the tables travel as kernel arguments (2 KiB)
+// Tensors per kind in one phase; the tables travel as kernel arguments (3 KiB of the 4 KiB a launch may carry).
+// As many as fit: sets of a few hundred small tensors run fastest as a single group (the 108 M-parameter set of 197
+// tensors: 0.361 ms per step as one group against 0.397 as two with their passes overlapped).
+constexpr int kMaxSeg = 192;
 
 struct Phase {
     const Tensor4Table* tensors;
@@ -2151,6 +2154,8 @@ struct Phase {
     Segment seg_a[kMaxSeg];
     Segment seg_b[kMaxSeg];
 };
+
+static_assert(sizeof(Phase) + sizeof(HyperArg) <= 4000, "kernel arguments of a phase launch");
 
 // the hyper-parameters as they apply to one tensor of a plan
 __device__ __forceinline__ Hyper for_tensor(const Hyper& h, const Tensor4& a) {
@@ -2291,6 +2296,8 @@ struct NdPhase {
     Segment seg_r[kMaxSeg];         // per tensor: first workgroup of the reduce kernel (one per statistic)
     Segment seg_e[kMaxSeg];         // per tensor: first workgroup of the expand kernel (one per 256 columns)
 };
+
+static_assert(sizeof(NdPhase) <= 4000, "kernel arguments of the reduce / expand launches");
 
 __global__ __launch_bounds__(kThreads) void nd_plan_reduce(const NdPhase ph) {
     __shared__ float s_part[kThreads / 64];
