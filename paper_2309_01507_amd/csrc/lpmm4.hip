@@ -1596,15 +1596,27 @@ int adamw4_step_multi_impl(void* plan, float lr, const float* lr_dev, float beta
         // Serial plans take the same launches one after the other on the caller's stream, without events.
         const bool two = host->side != nullptr;
         hipStream_t s2 = two ? host->side : s;
-        if (two) {
+        // The side stream's first work waits for the event behind the first A launch, which also puts it behind
+        // everything that was on the caller's stream before this call (and into a capture of that stream): no fork
+        // event is needed for it.  A second stream for pass 1 starts with work of its own and does need one.
+        if (host->side_a) {
             LPMM_HIP(hipEventRecord(host->ev_fork, s));
-            LPMM_HIP(hipStreamWaitEvent(s2, host->ev_fork, 0));
-            if (host->side_a) LPMM_HIP(hipStreamWaitEvent(host->side_a, host->ev_fork, 0));
+            LPMM_HIP(hipStreamWaitEvent(host->side_a, host->ev_fork, 0));
         }
-        for (size_t j = 0; j < host->phases.size(); ++j) {
+        // The last phase holds B work only, with no pass 1 left to run beside: it goes on the caller's stream,
+        // straight behind the A work it depends on, and spares the step one hand-over between the streams (a
+        // dependent launch on another stream starts 10-15 us later than one on the same stream).
+        const size_t n_ph = host->phases.size();
+        const bool tail_on_s = two && !host->side_a && n_ph >= 2 && host->phases[n_ph - 1].ph.n_a == 0;
+        for (size_t j = 0; j < n_ph; ++j) {
             const PhaseLaunch& pl = host->phases[j];
+            const bool tail = tail_on_s && j + 1 == n_ph;
+            if (tail) {
+                LPMM_HIP(hipEventRecord(host->ev_join, s2));      // everything the side stream was given
+                s2 = s;
+            }
             if (pl.ph.n_b > 0) {
-                if (two) LPMM_HIP(hipStreamWaitEvent(s2, host->ev_a[j - 1], 0));
+                if (two && !tail) LPMM_HIP(hipStreamWaitEvent(s2, host->ev_a[j - 1], 0));
                 // a factorized plan's heavy kernel is its B work (the update pass): that one is timed
                 const bool rec = host->factor && g_prof.on && g_prof.calls < g_prof.max_calls;
                 const int64_t call = g_prof.calls;
@@ -1632,10 +1644,11 @@ int adamw4_step_multi_impl(void* plan, float lr, const float* lr_dev, float beta
                     g_prof.calls = call + 1;
                 }
             }
-            if (two) LPMM_HIP(hipEventRecord(host->ev_a[j], sa));
+            // nobody waits for the A work of the last group when its B work follows it on the same stream
+            if (two && !(tail_on_s && j + 2 >= n_ph)) LPMM_HIP(hipEventRecord(host->ev_a[j], sa));
         }
         if (!two) return LPMM_OK;
-        LPMM_HIP(hipEventRecord(host->ev_join, s2));
+        if (!tail_on_s) LPMM_HIP(hipEventRecord(host->ev_join, s2));
         LPMM_HIP(hipStreamWaitEvent(s, host->ev_join, 0));
         if (host->side_a) {
             LPMM_HIP(hipEventRecord(host->ev_join_a, host->side_a));
