@@ -160,3 +160,18 @@ def test_per_tensor_no_decay_flag(second):
     bad.flags = 6
     with pytest.raises(lpmm.LpmmError):
         lpmm.new_plan([bad], 0, DEV)
+
+
+def test_plan_with_more_tensors_than_one_group_holds():
+    """450 small tensors: more than the segment tables of one group hold, so the plan is cut by parameters into three
+    groups of unequal tensor counts (the large tensors sit at the front); quantized and fp32-state tensors mixed."""
+    T = workloads.TensorSpec
+    rng = np.random.default_rng(77)
+    specs = [T("big0", 300, 512), T("big1", 256, 640)]
+    for k in range(448):
+        if k % 3 == 2:
+            specs.append(T(f"v{k}", 1, int(rng.integers(1, 9)) * 128, 1))
+        else:
+            specs.append(T(f"w{k}", int(rng.integers(33, 90)), 128 * int(rng.integers(1, 4))))
+    _run_set(specs, "col_lognormal", True, steps=3, seed=77)
+    _run_set(specs, "col_lognormal", False, steps=2, seed=78, env={"LPMM_MULTI_STREAMS": "0"})
