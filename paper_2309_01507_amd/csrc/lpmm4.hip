@@ -1502,7 +1502,9 @@ int lpmm_adamw4_plan_build_nd(const lpmm_tensor_desc* descs, int64_t n, const in
     // (7B-shaped set: 14.71 ms per step against 14.84, 354 M set 0.841 against 0.854).
     const int stream_mode = env_int("LPMM_MULTI_STREAMS", host->factor ? 0 : 2);
     host->serial = stream_mode == 0 && !host->sgdm;
-    if (stream_mode >= 2 && groups.size() > 1 && !host->sgdm) {
+    bool any_b = false;
+    for (const PhaseLaunch& pl : host->phases) any_b = any_b || pl.ph.n_b > 0;
+    if (stream_mode >= 2 && groups.size() > 1 && !host->sgdm && any_b) {
         LPMM_HIP(hipStreamCreateWithFlags(&host->side, hipStreamNonBlocking));
         LPMM_HIP(hipEventCreateWithFlags(&host->ev_fork, hipEventDisableTiming));
         LPMM_HIP(hipEventCreateWithFlags(&host->ev_join, hipEventDisableTiming));
@@ -1654,8 +1656,10 @@ int adamw4_step_multi_impl(void* plan, float lr, const float* lr_dev, float beta
                     g_prof.calls = call + 1;
                 }
             }
-            // nobody waits for the A work of the last group when its B work follows it on the same stream
-            if (two && !(tail_on_s && j + 2 >= n_ph)) LPMM_HIP(hipEventRecord(host->ev_a[j], sa));
+            // an event only where the next phase has B work that waits for it on the side stream (nobody waits
+            // for the A work of the last group when its B work follows it on the same stream)
+            const bool waited_for = j + 1 < n_ph && host->phases[j + 1].ph.n_b > 0 && !(tail_on_s && j + 2 >= n_ph);
+            if (two && waited_for) LPMM_HIP(hipEventRecord(host->ev_a[j], sa));
         }
         if (!two) return LPMM_OK;
         if (!tail_on_s) LPMM_HIP(hipEventRecord(host->ev_join, s2));
